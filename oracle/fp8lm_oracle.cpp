@@ -1,0 +1,537 @@
+// CPU oracle for the FP8 gradient cast + FP8 Adam step of FP8-LM (arXiv 2310.18313).
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, scalar, obviously-correct statement of what
+// the GPU path must compute.  Only the test-suite, the smoke check and the benchmark's
+// cpu_baseline leg may load it.  It shares no code, header, table or constant generator with the
+// HIP library: every struct below is declared here on its own, and the layout merely has to agree
+// with the library's because both describe the same device-resident metadata.
+//
+// Build: g++ -O2 -std=c++17 -ffp-contract=off -fPIC -shared   (no -ffast-math; one rounding per
+// written operation; std::fmaf only where a fused multiply-add is written).
+//
+// What the paper fixes and where:
+//   * the two FP8 encodings, their largest values 448 / 57344 and which of them has inf
+//     (Appendix A.1 and its range table);
+//   * "scaling tensor" semantics: stored payload = value * scale, value = payload / scale
+//     (Sec. 2.1, the paragraph before Eq. 4; Appendix A.2);
+//   * just-in-time scaling = scale from the amax of the tensor being cast (Appendix A.2);
+//   * the auto-scaling factor mu with its 0.001 % saturation threshold, the drop to 1/2 and the
+//     ramp to 2 over 1000 steps (Sec. 2.1, Eq. 3 and the paragraph after it);
+//   * the optimizer's storage types: FP8 gradient, FP8 first moment, FP16 second moment, FP16
+//     master weight with tensor scaling (Sec. 2.2, Eq. 8), AdamW with beta1 .9, beta2 .95,
+//     weight decay .1 (Sec. 3.1.2).
+// What the paper leaves open (rounding mode, scale formula, eps placement, how each scale is
+// refreshed) follows the readings stated at each function below; each says
+// which reading it takes.
+//
+// Parity pins (tests marked "not gpu"): decode tables against the paper's printed range table and
+// numpy's IEEE half; encoders against a brute-force nearest-value search and a library FP8 cast;
+// FP16 conversion against numpy; amax against a float loop; the Adam recurrences against float64
+// closed forms.  PARITY UNPINNED: the mu state machine and the v / master-weight / weight-copy
+// scale refresh rules have no printed example or closed form; they are held only by invariants.
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+
+namespace {
+
+inline uint32_t f32_bits(float x) { uint32_t u; std::memcpy(&u, &x, 4); return u; }
+inline float bits_f32(uint32_t u) { float x; std::memcpy(&x, &u, 4); return x; }
+
+// Description of a small binary floating-point format with IEEE-style subnormals.
+struct SmallFmt {
+  int mbits;        // explicit mantissa bits
+  int bias;         // exponent bias
+  uint32_t maxcode; // magnitude code of the largest finite value
+  float fmax;       // that value
+  uint32_t nancode; // canonical NaN magnitude code
+};
+
+// Appendix A.1: E4M3 = 1/4/3 bits, largest value 448, NaN but no infinity.
+constexpr SmallFmt kE4M3{3, 7, 0x7E, 448.0f, 0x7F};
+// Appendix A.1: E5M2 = 1/5/2 bits, largest value 57344, has +-inf and NaN.
+constexpr SmallFmt kE5M2{2, 15, 0x7B, 57344.0f, 0x7F};
+// IEEE half: 1/5/10, largest finite 65504 (range table, FP16 row).
+constexpr SmallFmt kF16{10, 15, 0x7BFF, 65504.0f, 0x7E00};
+
+// Round a non-negative finite fp32 below fmt.fmax (given by its bit pattern) to the nearest
+// magnitude code of `fmt`, ties to the even code.
+uint32_t round_mag_rne(uint32_t abits, const SmallFmt& fmt) {
+  const int e32 = int(abits >> 23);
+  if (e32 == 0) return 0;                       // fp32 zero/subnormal: far below every format's half-ulp
+  const int E = e32 - 127;                      // value = sig * 2^(E-23), sig in [2^23, 2^24)
+  const uint32_t sig = (abits & 0x7FFFFFu) | 0x800000u;
+  const int emin = 1 - fmt.bias;                // exponent of the smallest normal
+  int shift = 23 - fmt.mbits;                   // bits dropped for a normal result
+  if (E < emin) shift += emin - E;              // subnormal result: drop more
+  if (shift > 25) return 0;                     // below half of the smallest subnormal
+  uint32_t q = sig >> shift;
+  const uint32_t rem = sig & ((1u << shift) - 1u);
+  const uint32_t half = 1u << (shift - 1);
+  if (rem > half || (rem == half && (q & 1u))) q += 1;
+  if (E < emin) return q;                       // q == 2^mbits lands exactly on the smallest normal
+  // normal: q in [2^mbits, 2^(mbits+1)]; a mantissa carry walks into the exponent field
+  return (uint32_t(E + fmt.bias) << fmt.mbits) + (q - (1u << fmt.mbits));
+}
+
+// Saturating round-to-nearest-even encoder: NaN -> canonical NaN code (sign dropped),
+// |x| >= fmax (incl. inf) -> sign | maxcode, else nearest code, -0 keeps its sign.
+uint32_t encode_sat(float x, const SmallFmt& fmt, int total_bits) {
+  const uint32_t b = f32_bits(x);
+  const uint32_t abits = b & 0x7FFFFFFFu;
+  if (abits > 0x7F800000u) return fmt.nancode;
+  const uint32_t sign = (b >> 31) << (total_bits - 1);
+  if (bits_f32(abits) >= fmt.fmax) return sign | fmt.maxcode;
+  return sign | round_mag_rne(abits, fmt);       // a < fmax never rounds past the top code
+}
+
+float decode_small(uint32_t code, int ebits, int mbits, int bias, bool has_inf, int total_bits) {
+  const uint32_t s = (code >> (total_bits - 1)) & 1u;
+  const uint32_t e = (code >> mbits) & ((1u << ebits) - 1u);
+  const uint32_t f = code & ((1u << mbits) - 1u);
+  const uint32_t emax = (1u << ebits) - 1u;
+  float mag;
+  if (has_inf && e == emax) {
+    mag = f == 0 ? std::numeric_limits<float>::infinity() : std::numeric_limits<float>::quiet_NaN();
+  } else if (!has_inf && e == emax && f == (1u << mbits) - 1u) {
+    mag = std::numeric_limits<float>::quiet_NaN();
+  } else if (e == 0) {
+    mag = std::ldexp(float(f), 1 - bias - mbits);
+  } else {
+    mag = std::ldexp(float((1u << mbits) + f), int(e) - bias - mbits);
+  }
+  return s ? -mag : mag;
+}
+
+inline float dec_e4m3(uint8_t c) { return decode_small(c, 4, 3, 7, false, 8); }
+inline float dec_e5m2(uint8_t c) { return decode_small(c, 5, 2, 15, true, 8); }
+inline float dec_f16(uint16_t c) { return decode_small(c, 5, 10, 15, true, 16); }
+inline float dec_bf16(uint16_t c) { return bits_f32(uint32_t(c) << 16); }
+inline uint8_t enc_e4m3(float x) { return uint8_t(encode_sat(x, kE4M3, 8)); }
+inline uint8_t enc_e5m2(float x) { return uint8_t(encode_sat(x, kE5M2, 8)); }
+inline uint16_t enc_f16_sat(float x) { return uint16_t(encode_sat(x, kF16, 16)); }
+
+// fp32 -> bf16, round to nearest even, IEEE overflow to inf, NaN -> 0x7FC0.
+uint16_t enc_bf16(float x) {
+  const uint32_t b = f32_bits(x);
+  if ((b & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;
+  return uint16_t((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+}
+
+inline float dec_fp8(int fmt, uint8_t c) { return fmt == 0 ? dec_e4m3(c) : dec_e5m2(c); }
+inline uint8_t enc_fp8(int fmt, float x) { return fmt == 0 ? enc_e4m3(x) : enc_e5m2(x); }
+inline uint32_t maxcode_fp8(int fmt) { return fmt == 0 ? kE4M3.maxcode : kE5M2.maxcode; }
+inline float fmax_fp8(int fmt) { return fmt == 0 ? kE4M3.fmax : kE5M2.fmax; }
+
+// The power-of-two scale rule: for A > 0 finite, the unique integer k with
+//   2^k * A <= fmax < 2^(k+1) * A.
+// Written with frexp in double so that fp32 subnormal A needs no special case.
+int pow2_exp(float fmax, float A) {
+  int ea, ef;
+  const double ma = std::frexp(double(A), &ea);     // A    = ma * 2^ea, ma in [0.5, 1)
+  const double mf = std::frexp(double(fmax), &ef);  // fmax = mf * 2^ef
+  return ma <= mf ? ef - ea : ef - ea - 1;
+}
+
+inline int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+}  // namespace
+
+extern "C" {
+
+// ---- metadata, declared independently of the library's header (same byte layout) -------------
+enum { ORACLE_HIST = 16 };
+enum { ORACLE_FLAG_NONFINITE = 1u, ORACLE_FLAG_AMAX_ZERO = 2u, ORACLE_FLAG_SCALE_CLAMPED = 4u,
+       ORACLE_FLAG_SATURATED = 8u };
+
+typedef struct { int64_t offset; int64_t numel; } oracle_tensor;
+
+typedef struct {
+  float scale;       // power of two; stored payload = value * scale
+  float inv_scale;   // exact reciprocal
+  float amax;        // max |value| before quantisation (+inf when a non-finite value was seen)
+  float amax_deq;    // max |stored payload| / scale over the non-NaN stored codes
+  float amax_hist[ORACLE_HIST];
+  int32_t hist_pos;
+  int32_t mu_exp;      // log2 of the auto-scaling factor: -1, 0, +1
+  int32_t clean_steps; // consecutive steps without overflow, capped at ramp_steps
+  uint32_t flags;
+  uint64_t n_sat;
+  uint64_t n_underflow;
+} oracle_meta;
+
+typedef struct { int32_t sat_num, sat_den, ramp_steps, hist_window, margin; } oracle_autoscale_cfg;
+
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay;
+  int64_t step;        // >= 1
+  int32_t v_scaled;    // 1: second moment stored as scaled FP16; 0: plain FP16 (scale 1)
+  int32_t wcopy;       // 0: E4M3 weight copy with its own scale; 1: bf16 weight copy
+} oracle_adam_hparams;
+
+// ---- scalar format functions exported for the pins -------------------------------------------
+float oracle_decode_e4m3(uint8_t c) { return dec_e4m3(c); }
+float oracle_decode_e5m2(uint8_t c) { return dec_e5m2(c); }
+float oracle_decode_f16(uint16_t c) { return dec_f16(c); }
+float oracle_decode_bf16(uint16_t c) { return dec_bf16(c); }
+uint8_t oracle_encode_e4m3(float x) { return enc_e4m3(x); }
+uint8_t oracle_encode_e5m2(float x) { return enc_e5m2(x); }
+uint16_t oracle_encode_f16_sat(float x) { return enc_f16_sat(x); }
+uint16_t oracle_encode_bf16(float x) { return enc_bf16(x); }
+int oracle_pow2_exp(float fmax, float A) { return pow2_exp(fmax, A); }
+
+// Second, independent FP8 encoder: nearest of the finite non-negative code values by exhaustive
+// search in double precision, ties to the even code.  Used only to pin the bit-level encoder.
+uint8_t oracle_encode_fp8_nearest(int fmt, float x) {
+  if (x != x) return 0x7F;
+  const uint32_t sign = f32_bits(x) >> 31 << 7;
+  const double a = std::fabs(double(x));
+  const uint32_t top = maxcode_fp8(fmt);
+  if (a >= double(fmax_fp8(fmt))) return uint8_t(sign | top);
+  uint32_t best = 0;
+  double best_d = a;  // distance to code 0 (value 0)
+  for (uint32_t c = 1; c <= top; ++c) {
+    const double d = std::fabs(a - double(dec_fp8(fmt, uint8_t(c))));
+    if (d < best_d || (d == best_d && (c & 1u) == 0)) { best = c; best_d = d; }
+  }
+  return uint8_t(sign | best);
+}
+
+void oracle_encode_fp8_array(int fmt, const float* x, uint8_t* out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = enc_fp8(fmt, x[i]);
+}
+void oracle_encode_fp8_nearest_array(int fmt, const float* x, uint8_t* out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = oracle_encode_fp8_nearest(fmt, x[i]);
+}
+void oracle_encode_f16_sat_array(const float* x, uint16_t* out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = enc_f16_sat(x[i]);
+}
+void oracle_encode_bf16_array(const float* x, uint16_t* out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = enc_bf16(x[i]);
+}
+
+// ---- metadata initial state ---------------------------------------------------------------------
+// scale 1, empty history, mu = 1: the clean-step counter starts halfway up the ramp.
+void oracle_meta_init(oracle_meta* meta, int32_t n, const oracle_autoscale_cfg* cfg) {
+  for (int32_t t = 0; t < n; ++t) {
+    oracle_meta& M = meta[t];
+    std::memset(&M, 0, sizeof(M));
+    M.scale = 1.0f;
+    M.inv_scale = 1.0f;
+    M.clean_steps = cfg->ramp_steps / 2;
+    M.mu_exp = 0;
+  }
+}
+
+// ---- step a1 + a2: per-tensor amax of the bf16 gradient and the scale update ------------------
+// amax is just-in-time (Appendix A.2): it is taken over the tensor that is about to be cast.
+// The scale is the largest power of two that keeps scale * amax_eff inside the target format,
+// times the auto-scaling factor mu = 2^mu_exp (Sec. 2.1, Eq. 3: g' = mu * g), divided by
+// 2^margin.  amax_eff is the largest of the hist_window most recent amax values (Appendix A.2,
+// delayed scaling keeps such a history; a window of 1 is pure just-in-time scaling).
+void oracle_amax_scale(const uint16_t* src_bf16, const oracle_tensor* tensors, int32_t n_tensors,
+                       int target_fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    const int64_t n = tensors[t].numel;
+    if (n == 0) continue;
+    const uint16_t* g = src_bf16 + tensors[t].offset;
+    oracle_meta& M = meta[t];
+    bool nonfinite = false;
+    float A = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+      const float a = std::fabs(dec_bf16(g[i]));
+      if (!(a <= std::numeric_limits<float>::max())) nonfinite = true;  // inf or NaN
+      else if (a > A) A = a;
+    }
+    uint32_t flags = 0;
+    if (nonfinite) {
+      M.amax = std::numeric_limits<float>::infinity();
+      M.flags = ORACLE_FLAG_NONFINITE;  // scale and history left as they were
+      continue;
+    }
+    M.amax = A;
+    const int H = clampi(cfg->hist_window, 1, ORACLE_HIST);
+    const int slot = M.hist_pos % H;
+    M.amax_hist[slot] = A;
+    M.hist_pos = (slot + 1) % H;
+    float Aeff = 0.0f;
+    for (int h = 0; h < H; ++h) Aeff = M.amax_hist[h] > Aeff ? M.amax_hist[h] : Aeff;
+    if (Aeff == 0.0f) {
+      flags |= ORACLE_FLAG_AMAX_ZERO;  // nothing to scale by: keep the previous scale
+    } else {
+      const int k = pow2_exp(fmax_fp8(target_fmt), Aeff) + M.mu_exp - cfg->margin;
+      const int e = clampi(k, -126, 126);
+      if (e != k) flags |= ORACLE_FLAG_SCALE_CLAMPED;
+      M.scale = std::ldexp(1.0f, e);
+      M.inv_scale = std::ldexp(1.0f, -e);
+    }
+    M.flags = flags;
+  }
+}
+
+// ---- step a3 + a4: the scaled saturating cast and the auto-scaling state machine --------------
+// payload = FP8(scale * g), round to nearest even, saturating (Sec. 2.1: the value is
+// payload / scale).  The statistic of Sec. 2.1 is the share of payloads whose magnitude is the
+// largest finite code; above sat_num/sat_den (0.001 %) the next step uses mu = 1/2, and after
+// that mu climbs back one doubling per ramp_steps/2 clean steps until it reaches 2.
+void oracle_cast_fp8(const uint16_t* src_bf16, const oracle_tensor* tensors, int32_t n_tensors,
+                     uint8_t* dst, int fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
+  const uint32_t top = maxcode_fp8(fmt);
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    const int64_t n = tensors[t].numel;
+    if (n == 0) continue;
+    const uint16_t* g = src_bf16 + tensors[t].offset;
+    uint8_t* q = dst + tensors[t].offset;
+    oracle_meta& M = meta[t];
+    uint64_t n_sat = 0, n_under = 0;
+    float stored_max = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+      const float y = dec_bf16(g[i]) * M.scale;
+      const uint8_t c = enc_fp8(fmt, y);
+      q[i] = c;
+      const uint32_t mag = c & 0x7Fu;
+      if (mag == top) ++n_sat;
+      if ((g[i] & 0x7FFFu) != 0 && mag == 0) ++n_under;
+      const float d = std::fabs(dec_fp8(fmt, c));
+      if (d == d && d > stored_max) stored_max = d;   // NaN codes carry no magnitude
+    }
+    M.n_sat = n_sat;
+    M.n_underflow = n_under;
+    M.amax_deq = stored_max * M.inv_scale;
+    if (n_sat > 0) M.flags |= ORACLE_FLAG_SATURATED; else M.flags &= ~uint32_t(ORACLE_FLAG_SATURATED);
+    // auto-scaling state machine; takes effect in the next amax/scale call
+    const int R = cfg->ramp_steps < 2 ? 2 : cfg->ramp_steps;
+    const bool overflow = int64_t(n_sat) * int64_t(cfg->sat_den) > n * int64_t(cfg->sat_num);
+    if (overflow) M.clean_steps = 0;
+    else M.clean_steps = M.clean_steps + 1 > R ? R : M.clean_steps + 1;
+    const int ramp = (2 * M.clean_steps) / R;
+    M.mu_exp = -1 + (ramp > 2 ? 2 : ramp);
+  }
+}
+
+// ---- master-weight initialisation ----------------------------------------------------------------
+// Sec. 2.2: master weights are FP16 with tensor scaling.  The scale leaves one binade of
+// headroom above the initial amax so that weights can grow between scale refreshes.
+void oracle_init_master(const uint16_t* w_bf16, const oracle_tensor* tensors, int32_t n_tensors,
+                        uint16_t* w_f16, oracle_meta* w_meta) {
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    const int64_t n = tensors[t].numel;
+    if (n == 0) continue;
+    const uint16_t* src = w_bf16 + tensors[t].offset;
+    uint16_t* dst = w_f16 + tensors[t].offset;
+    oracle_meta& M = w_meta[t];
+    bool nonfinite = false;
+    float A = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+      const float a = std::fabs(dec_bf16(src[i]));
+      if (!(a <= std::numeric_limits<float>::max())) nonfinite = true;
+      else if (a > A) A = a;
+    }
+    uint32_t flags = 0;
+    M.amax = nonfinite ? std::numeric_limits<float>::infinity() : A;
+    if (nonfinite) flags |= ORACLE_FLAG_NONFINITE;
+    else if (A == 0.0f) flags |= ORACLE_FLAG_AMAX_ZERO;
+    else {
+      const int k = pow2_exp(kF16.fmax, A) - 1;
+      const int e = clampi(k, -126, 126);
+      if (e != k) flags |= ORACLE_FLAG_SCALE_CLAMPED;
+      M.scale = std::ldexp(1.0f, e);
+      M.inv_scale = std::ldexp(1.0f, -e);
+    }
+    float stored_max = 0.0f;
+    uint64_t n_sat = 0, n_under = 0;
+    for (int64_t i = 0; i < n; ++i) {
+      const float x = dec_bf16(src[i]);
+      const uint16_t h = enc_f16_sat(x * M.scale);
+      dst[i] = h;
+      const float d = std::fabs(dec_f16(h));
+      if (d == d && d > stored_max) stored_max = d;
+      if ((h & 0x7FFFu) == kF16.maxcode) ++n_sat;
+      if ((src[i] & 0x7FFFu) != 0 && (h & 0x7FFFu) == 0) ++n_under;
+    }
+    M.amax_deq = stored_max * M.inv_scale;
+    M.n_sat = n_sat;
+    M.n_underflow = n_under;
+    if (n_sat > 0) flags |= ORACLE_FLAG_SATURATED;
+    M.flags = flags;
+  }
+}
+
+// ---- step a5 + a6: the FP8 Adam step ---------------------------------------------------------
+// Sec. 2.2 / Eq. 8: gradient FP8, first moment FP8 (E4M3 with a per-tensor scale), second moment
+// FP16, master weight FP16 with tensor scaling; AdamW (Sec. 3.1.2) with bias correction and the
+// usual sqrt(v_hat) + eps denominator.  All arithmetic in fp32; the update uses the fp32 moments
+// before they are quantised for storage.
+//
+// Scales of the values written back:
+//   first moment : just-in-time, from the exact amax of the new moment (Appendix A.2);
+//   second moment: from the bound B_v = fma(beta2, amax_deq(v), (1-beta2) * amax_deq(g)^2), which
+//                  by monotonicity of rounding is >= every new v, so the FP16 store never clips;
+//   master weight: from the amax of the stored weights before the step, minus one binade;
+//   weight copy  : E4M3 from the same amax without headroom (saturating), or plain bf16.
+static void derive_hparams(const oracle_adam_hparams* hp, float& b1, float& omb1, float& rbc1,
+                           float& b2, float& omb2, float& rbc2, float& decay) {
+  b1 = hp->beta1;
+  b2 = hp->beta2;
+  omb1 = float(1.0 - double(b1));
+  omb2 = float(1.0 - double(b2));
+  rbc1 = float(1.0 / (1.0 - std::pow(double(b1), double(hp->step))));
+  rbc2 = float(1.0 / (1.0 - std::pow(double(b2), double(hp->step))));
+  decay = float(1.0 - double(hp->lr) * double(hp->weight_decay));
+}
+
+// Picks the stored scale of one output buffer from a magnitude bound.  Keeps the old scale when the
+// bound is zero or not finite and reports why.
+static void refresh_scale(float fmax, float bound, int headroom, float old_scale, float old_inv,
+                          float& scale, float& inv, uint32_t& flags) {
+  scale = old_scale;
+  inv = old_inv;
+  if (!(bound <= std::numeric_limits<float>::max())) { flags |= ORACLE_FLAG_NONFINITE; return; }
+  if (bound == 0.0f) { flags |= ORACLE_FLAG_AMAX_ZERO; return; }
+  const int k = pow2_exp(fmax, bound) - headroom;
+  const int e = clampi(k, -126, 126);
+  if (e != k) flags |= ORACLE_FLAG_SCALE_CLAMPED;
+  scale = std::ldexp(1.0f, e);
+  inv = std::ldexp(1.0f, -e);
+}
+
+void oracle_adam_step_fp8(const oracle_tensor* tensors, int32_t n_tensors,
+                          const uint8_t* grad, int grad_fmt, const oracle_meta* grad_meta,
+                          uint8_t* m, oracle_meta* m_meta,
+                          uint16_t* v, oracle_meta* v_meta,
+                          uint16_t* w, oracle_meta* w_meta,
+                          void* wcopy, oracle_meta* wcopy_meta,
+                          const oracle_adam_hparams* hp) {
+  float b1, omb1, rbc1, b2, omb2, rbc2, decay;
+  derive_hparams(hp, b1, omb1, rbc1, b2, omb2, rbc2, decay);
+  const float lr = hp->lr, eps = hp->eps;
+  const float INF = std::numeric_limits<float>::infinity();
+
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    const int64_t n = tensors[t].numel;
+    if (n == 0) continue;
+    const int64_t off = tensors[t].offset;
+    const uint8_t* qg = grad + off;
+    uint8_t* qm = m + off;
+    uint16_t* hv = v + off;
+    uint16_t* hw = w + off;
+    const float inv_sg = grad_meta[t].inv_scale;
+    const float inv_sm = m_meta[t].inv_scale;
+    const float inv_sv = v_meta[t].inv_scale;
+    const float inv_sw = w_meta[t].inv_scale;
+
+    // phase A: exact amax of the new first moment
+    bool m_nonfinite = false;
+    float A_m = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+      const float g = dec_fp8(grad_fmt, qg[i]) * inv_sg;
+      const float m0 = dec_e4m3(qm[i]) * inv_sm;
+      const float m1 = std::fmaf(b1, m0, omb1 * g);
+      const float a = std::fabs(m1);
+      if (!(a <= std::numeric_limits<float>::max())) m_nonfinite = true;
+      else if (a > A_m) A_m = a;
+    }
+
+    // scales for the four writes
+    uint32_t fm = 0, fv = 0, fw = 0, fq = 0;
+    float sm, ism, sv, isv, sw, isw, sq, isq;
+    refresh_scale(kE4M3.fmax, m_nonfinite ? INF : A_m, 0, m_meta[t].scale, m_meta[t].inv_scale, sm, ism, fm);
+    if (hp->v_scaled) {
+      const float Ag = grad_meta[t].amax_deq;
+      const float Bv = std::fmaf(b2, v_meta[t].amax_deq, omb2 * (Ag * Ag));
+      refresh_scale(kF16.fmax, Bv, 0, v_meta[t].scale, v_meta[t].inv_scale, sv, isv, fv);
+    } else {
+      sv = 1.0f; isv = 1.0f;
+    }
+    refresh_scale(kF16.fmax, w_meta[t].amax_deq, 1, w_meta[t].scale, w_meta[t].inv_scale, sw, isw, fw);
+    if (hp->wcopy == 0) {
+      refresh_scale(kE4M3.fmax, w_meta[t].amax_deq, 0, wcopy_meta[t].scale, wcopy_meta[t].inv_scale, sq, isq, fq);
+    } else {
+      sq = 1.0f; isq = 1.0f;
+    }
+
+    // phase B: the update
+    bool v_nonfinite = false, w_nonfinite = false;
+    float A_v = 0.0f, A_w = 0.0f;
+    float st_m = 0.0f, st_v = 0.0f, st_w = 0.0f, st_q = 0.0f;       // max |stored payload|
+    uint64_t sat_m = 0, sat_v = 0, sat_w = 0, sat_q = 0;
+    uint64_t und_m = 0, und_v = 0, und_w = 0, und_q = 0;
+    for (int64_t i = 0; i < n; ++i) {
+      const float g = dec_fp8(grad_fmt, qg[i]) * inv_sg;
+      const float m0 = dec_e4m3(qm[i]) * inv_sm;
+      const float v0 = dec_f16(hv[i]) * inv_sv;
+      const float w0 = dec_f16(hw[i]) * inv_sw;
+      const float m1 = std::fmaf(b1, m0, omb1 * g);
+      const float v1 = std::fmaf(b2, v0, omb2 * (g * g));
+      const float den = std::sqrt(v1 * rbc2) + eps;
+      const float upd = (m1 * rbc1) / den;
+      const float w1 = std::fmaf(-lr, upd, w0 * decay);
+
+      const uint8_t cm = enc_e4m3(m1 * sm);
+      const uint16_t cv = enc_f16_sat(v1 * sv);
+      const uint16_t cw = enc_f16_sat(w1 * sw);
+      qm[i] = cm;
+      hv[i] = cv;
+      hw[i] = cw;
+
+      float d;
+      d = std::fabs(dec_e4m3(cm)); if (d == d && d > st_m) st_m = d;
+      d = std::fabs(dec_f16(cv));  if (d == d && d > st_v) st_v = d;
+      d = std::fabs(dec_f16(cw));  if (d == d && d > st_w) st_w = d;
+      if ((cm & 0x7Fu) == kE4M3.maxcode) ++sat_m;
+      if ((cv & 0x7FFFu) == kF16.maxcode) ++sat_v;
+      if ((cw & 0x7FFFu) == kF16.maxcode) ++sat_w;
+      if (m1 != 0.0f && (cm & 0x7Fu) == 0) ++und_m;
+      if (v1 != 0.0f && (cv & 0x7FFFu) == 0) ++und_v;
+      if (w1 != 0.0f && (cw & 0x7FFFu) == 0) ++und_w;
+
+      float a = std::fabs(v1);
+      if (!(a <= std::numeric_limits<float>::max())) v_nonfinite = true; else if (a > A_v) A_v = a;
+      a = std::fabs(w1);
+      if (!(a <= std::numeric_limits<float>::max())) w_nonfinite = true; else if (a > A_w) A_w = a;
+
+      if (hp->wcopy == 0) {
+        const uint8_t cq = enc_e4m3(w1 * sq);
+        static_cast<uint8_t*>(wcopy)[off + i] = cq;
+        d = std::fabs(dec_e4m3(cq)); if (d == d && d > st_q) st_q = d;
+        if ((cq & 0x7Fu) == kE4M3.maxcode) ++sat_q;
+        if (w1 != 0.0f && (cq & 0x7Fu) == 0) ++und_q;
+      } else {
+        const uint16_t cq = enc_bf16(w1);
+        static_cast<uint16_t*>(wcopy)[off + i] = cq;
+        d = std::fabs(dec_bf16(cq));
+        if (d <= std::numeric_limits<float>::max() && d > st_q) st_q = d;
+        if ((cq & 0x7FFFu) == 0x7F80u) ++sat_q;                 // rounded to infinity
+        if (w1 != 0.0f && (cq & 0x7FFFu) == 0) ++und_q;
+      }
+    }
+
+    auto finish = [&](oracle_meta& M, float scale, float inv, float amax, bool nonfinite,
+                      float stored, uint64_t n_sat, uint64_t n_und, uint32_t flags) {
+      M.scale = scale;
+      M.inv_scale = inv;
+      M.amax = nonfinite ? INF : amax;
+      M.amax_deq = stored * inv;
+      M.n_sat = n_sat;
+      M.n_underflow = n_und;
+      if (nonfinite) flags |= ORACLE_FLAG_NONFINITE;
+      if (n_sat > 0) flags |= ORACLE_FLAG_SATURATED;
+      M.flags = flags;
+    };
+    finish(m_meta[t], sm, ism, A_m, m_nonfinite, st_m, sat_m, und_m, fm);
+    finish(v_meta[t], sv, isv, A_v, v_nonfinite, st_v, sat_v, und_v, fv);
+    finish(w_meta[t], sw, isw, A_w, w_nonfinite, st_w, sat_w, und_w, fw);
+    finish(wcopy_meta[t], sq, isq, A_w, w_nonfinite, st_q, sat_q, und_q, fq);
+  }
+}
+
+// Derived host scalars, exported so a test can check them against float64 arithmetic.
+void oracle_derive_hparams(const oracle_adam_hparams* hp, float* out7) {
+  derive_hparams(hp, out7[0], out7[1], out7[2], out7[3], out7[4], out7[5], out7[6]);
+}
+
+uint32_t oracle_sizeof_meta(void) { return uint32_t(sizeof(oracle_meta)); }
+
+}  // extern "C"
