@@ -1,0 +1,215 @@
+/*
+ * fp8lm.h -- C ABI of the MI355X (gfx950) implementation of the optimizer-side hot path of
+ * FP8-LM (arXiv 2310.18313): per-tensor automatically scaled FP8 gradient quantisation
+ * (Sec. 2.1, Appendix A.2) and the FP8 Adam step (Sec. 2.2).
+ *
+ * General rules of this boundary
+ *   - Plain C.  Every pointer named "device" is a device (HBM) address on the context's GPU; every
+ *     pointer named "host" is ordinary host memory that is only read during the call.
+ *   - All tensors of a model live in flat buffers.  Tensor t occupies elements
+ *     [tensors[t].offset, tensors[t].offset + tensors[t].numel) of EVERY flat buffer passed to a call
+ *     (gradient source, FP8 gradient, moments, master weights, weight copy), whatever its element
+ *     size.  Offsets are multiples of 16 elements, buffers start on a 16-byte boundary, tensors do not
+ *     overlap.  Elements between tensors are padding: never read into a result, never written.
+ *   - Each scaled buffer carries one fp8lm_meta per tensor (device memory, caller-owned).  A stored
+ *     payload equals value * scale; the value is payload / scale (Sec. 2.1, text before Eq. 4).
+ *     Scales are powers of two, so scaling is exact.
+ *   - Calls enqueue work on the given HIP stream and return without synchronising.  They allocate
+ *     nothing; only fp8lm_create / fp8lm_destroy touch the allocator.  One context must not be used
+ *     from two streams at the same time (its reduction scratch is shared).
+ *   - Return value: FP8LM_OK or a negative fp8lm_status.  On an error nothing has been enqueued.
+ *     Data-dependent conditions (non-finite inputs, all-zero tensors, saturation) are reported in the
+ *     metadata flags and counters on the device, never in the return value.
+ *   - Tensors with numel == 0 are skipped: their metadata is left untouched.
+ */
+#ifndef FP8LM_H
+#define FP8LM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fp8lm_ctx fp8lm_ctx;
+
+typedef enum {
+  FP8LM_OK = 0,
+  FP8LM_ERR_INVALID_ARGUMENT = -1, /* null pointer, bad enum, bad hyper-parameter               */
+  FP8LM_ERR_MISALIGNED = -2,       /* offset not a multiple of 16 or buffer not 16-byte aligned  */
+  FP8LM_ERR_OVERLAP = -3,          /* two tensors share elements                                 */
+  FP8LM_ERR_HIP = -4,              /* a HIP runtime call failed (see fp8lm_last_hip_error)       */
+  FP8LM_ERR_TOO_LARGE = -5         /* more chunks / tensors than the 32-bit tables can index     */
+} fp8lm_status;
+
+/* Appendix A.1: E4M3 (max 448, NaN, no infinity) and E5M2 (max 57344, infinities and NaN).      */
+typedef enum { FP8LM_E4M3 = 0, FP8LM_E5M2 = 1 } fp8lm_fmt;
+/* Element type of the high-precision gradient handed to the cast.                               */
+typedef enum { FP8LM_SRC_BF16 = 0 } fp8lm_src;
+/* Format of the low-precision weight copy written by the optimizer.                             */
+typedef enum { FP8LM_WCOPY_E4M3 = 0, FP8LM_WCOPY_BF16 = 1 } fp8lm_wcopy;
+
+typedef struct {
+  int64_t offset; /* first element, multiple of 16 */
+  int64_t numel;  /* >= 0                          */
+} fp8lm_tensor;
+
+#define FP8LM_HIST 16
+
+#define FP8LM_FLAG_NONFINITE 1u     /* an inf/NaN was seen; scale (and amax history) left unchanged  */
+#define FP8LM_FLAG_AMAX_ZERO 2u     /* the magnitude bound was zero; scale left unchanged            */
+#define FP8LM_FLAG_SCALE_CLAMPED 4u /* the scale exponent was clamped to [-126, 126]                 */
+#define FP8LM_FLAG_SATURATED 8u     /* at least one stored payload sits on the largest finite code   */
+
+/* Per-tensor, per-buffer scaling metadata.  Device resident, plain data, 112 bytes.               */
+typedef struct {
+  float scale;       /* power of two; stored payload = value * scale                               */
+  float inv_scale;   /* exact reciprocal                                                           */
+  float amax;        /* max |value| before quantisation; +inf if a non-finite value was seen       */
+  float amax_deq;    /* max |stored payload| / scale over the stored codes that are not NaN        */
+  float amax_hist[FP8LM_HIST]; /* ring of recent amax values (Appendix A.2, delayed scaling)       */
+  int32_t hist_pos;    /* next ring slot                                                           */
+  int32_t mu_exp;      /* log2 of the auto-scaling factor mu of Sec. 2.1, Eq. 3: -1, 0 or +1       */
+  int32_t clean_steps; /* consecutive casts without overflow, capped at ramp_steps                 */
+  uint32_t flags;      /* FP8LM_FLAG_*                                                             */
+  uint64_t n_sat;       /* stored payloads whose magnitude is the largest finite code              */
+  uint64_t n_underflow; /* non-zero values stored as zero                                          */
+} fp8lm_meta;
+
+/* Auto-scaling configuration (Sec. 2.1, paragraph after Eq. 3).  Defaults in brackets.            */
+typedef struct {
+  int32_t sat_num;     /* overflow when n_sat * sat_den > numel * sat_num  [1]                     */
+  int32_t sat_den;     /*   ... i.e. more than 0.001 % of the payloads on the top code  [100000]   */
+  int32_t ramp_steps;  /* mu climbs from 1/2 to 2 over this many clean steps  [1000]               */
+  int32_t hist_window; /* amax values that bound the scale, 1..FP8LM_HIST; 1 = just-in-time  [1]   */
+  int32_t margin;      /* extra binades of headroom subtracted from the scale exponent  [0]        */
+} fp8lm_autoscale_cfg;
+
+/* Hyper-parameters of one AdamW step (Sec. 3.1.2: beta1 0.9, beta2 0.95, weight decay 0.1).
+ * Accepted ranges: 0 <= lr <= 1024, 0 <= beta1, beta2 < 1, 2^-36 <= eps < inf,
+ * 0 <= weight_decay <= 1024, step >= 1.                                                            */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay;
+  int64_t step;     /* 1 for the first update (bias correction)                                    */
+  int32_t v_scaled; /* 1: second moment stored as FP16 with a per-tensor scale; 0: plain FP16      */
+  int32_t wcopy;    /* fp8lm_wcopy                                                                 */
+  int32_t stats;    /* 1: count n_sat / n_underflow of the four outputs exactly (more ALU work);
+                       0: leave them 0; FLAG_SATURATED is still exact (derived from the amax)      */
+  int32_t exact;    /* 1: correctly rounded sqrt and divide in the weight update (results identical to
+                          the scalar definition);
+                       0: hardware v_sqrt_f32 / v_rcp_f32, 1 ulp each: m and v are unaffected, the
+                          update term is off by a few fp32 ulps, so a new weight is within one FP16
+                          ulp of max(|w|, lr * |update|) -- more than one ulp of the result itself
+                          where the two nearly cancel                                              */
+} fp8lm_adam_hparams;
+
+/*
+ * Creates a context for a fixed tensor list on GPU `device`.
+ *   tensors : host array of n entries, copied.  n >= 0.
+ * Allocates the device-side tensor/chunk tables and the reduction scratch, and synchronises once.
+ * Errors: INVALID_ARGUMENT (null, negative numel/offset), MISALIGNED, OVERLAP, TOO_LARGE, HIP.
+ */
+fp8lm_status fp8lm_create(fp8lm_ctx** out, const fp8lm_tensor* tensors /*host*/, int32_t n, int device);
+
+/* Frees everything fp8lm_create allocated.  The caller guarantees no enqueued work still uses it. */
+fp8lm_status fp8lm_destroy(fp8lm_ctx* ctx);
+
+/*
+ * Launch tuning (optional).  chunk_elems: elements per work unit, a multiple of 4096 in
+ * [4096, 1048576]; blocks_per_cu: resident 256-thread workgroups per compute unit the persistent
+ * grids aim for, 1..16; interleave: 0 = each workgroup walks one contiguous range of chunks,
+ * 1 = chunks are dealt round-robin.  Rebuilds the chunk table (synchronises).
+ */
+fp8lm_status fp8lm_set_tuning(fp8lm_ctx* ctx, int32_t chunk_elems, int32_t blocks_per_cu, int32_t interleave);
+
+/*
+ * Initial metadata: scale 1, empty amax history, mu = 1 (clean_steps = ramp_steps / 2), counters 0.
+ *   meta : device array of n entries (n = the context's tensor count), overwritten.
+ */
+fp8lm_status fp8lm_meta_init(fp8lm_ctx* ctx, fp8lm_meta* meta /*device*/, const fp8lm_autoscale_cfg* cfg /*host*/,
+                             void* stream);
+
+/*
+ * Step 1 of the gradient quantisation (Appendix A.2, just-in-time scaling; Sec. 2.1, Eq. 3).
+ * For every tensor: amax = max |src|; the amax is pushed into the history ring; the scale becomes
+ * 2^(k + mu_exp - margin) where k is the largest integer with 2^k * amax_eff <= max finite value of
+ * `target` and amax_eff is the largest of the last hist_window amax values.  An all-zero history
+ * keeps the old scale (FLAG_AMAX_ZERO); a non-finite input keeps scale and history, sets amax = +inf
+ * (FLAG_NONFINITE).  Writes meta[t].{scale, inv_scale, amax, amax_hist, hist_pos, flags}.
+ *   src  : device, flat bf16 gradient buffer (read only).
+ *   meta : device array [n_tensors], read and written.
+ */
+fp8lm_status fp8lm_amax_scale(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_src src_type, fp8lm_fmt target,
+                              fp8lm_meta* meta /*device*/, const fp8lm_autoscale_cfg* cfg /*host*/, void* stream);
+
+/*
+ * Step 2 of the gradient quantisation (Sec. 2.1: the scaling tensor (g', s'); Appendix A.1).
+ * dst[i] = FP8(meta[t].scale * src[i]), round to nearest even, saturating to the largest finite
+ * code (inf included); NaN becomes 0x7F.  Also writes meta[t].{n_sat, n_underflow, amax_deq,
+ * FLAG_SATURATED} and advances the auto-scaling state of Sec. 2.1: if more than sat_num/sat_den of
+ * the payloads sit on the top code the next scale uses mu = 1/2 (clean_steps = 0); otherwise
+ * clean_steps grows and mu = 1/2, 1, 2 as it passes 0, ramp_steps/2, ramp_steps.
+ *   src : device, flat bf16 (read only).   dst : device, flat uint8 (written inside tensors only).
+ */
+fp8lm_status fp8lm_cast_fp8(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_src src_type, uint8_t* dst /*device*/,
+                            fp8lm_fmt fmt, fp8lm_meta* meta /*device*/, const fp8lm_autoscale_cfg* cfg /*host*/,
+                            void* stream);
+
+/*
+ * Master-weight initialisation (Sec. 2.2: FP16 master weights with tensor scaling).
+ * For every tensor: scale = 2^(k - 1) with k the largest integer such that 2^k * max|w| <= 65504,
+ * w_f16[i] = FP16(scale * w_bf16[i]) (round to nearest even, saturating).  Fills w_meta[t].
+ */
+fp8lm_status fp8lm_init_master(fp8lm_ctx* ctx, const void* w_bf16 /*device*/, uint16_t* w_f16 /*device*/,
+                               fp8lm_meta* w_meta /*device*/, void* stream);
+
+/*
+ * One FP8 AdamW step (Sec. 2.2, Eq. 8: FP8 gradient, FP8 first moment, FP16 second moment, scaled FP16
+ * master weight; Sec. 3.1.2 for the optimizer).  With g, m, v, w the dequantised inputs, in fp32:
+ *     m' = fma(beta1, m, (1-beta1) * g)          v' = fma(beta2, v, (1-beta2) * g*g)
+ *     w' = fma(-lr, (m' / (1-beta1^step)) / (sqrt(v' / (1-beta2^step)) + eps), w * (1 - lr*weight_decay))
+ * and m', v', w' are stored back in place with refreshed per-tensor scales:
+ *     m : E4M3, scale from the exact amax of m' (an extra read-only pass over grad and m);
+ *     v : FP16, scale from the bound fma(beta2, v_meta.amax_deq, (1-beta2) * grad_meta.amax_deq^2), which
+ *         no v' exceeds (v_scaled = 0: scale 1);
+ *     w : FP16, scale from w_meta.amax_deq before the step, minus one binade;
+ *     wcopy : E4M3 with the scale from w_meta.amax_deq before the step (saturating), or bf16 (scale 1).
+ * Each meta receives scale, inv_scale, amax, amax_deq and flags; n_sat / n_underflow are counted
+ * when hp->stats is set.  grad_meta is read only; its amax_deq and flags must describe `grad` (as left by
+ * fp8lm_cast_fp8).  The state buffers must hold what this library (or an equivalent encoder) wrote:
+ * non-finite payloads in v or w are only handled when the corresponding meta carries FLAG_NONFINITE.
+ * Errors: INVALID_ARGUMENT for hyper-parameters outside the ranges given at fp8lm_adam_hparams.
+ */
+fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* ctx,
+                                 const uint8_t* grad /*device*/, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta /*device*/,
+                                 uint8_t* m /*device, in place*/, fp8lm_meta* m_meta /*device*/,
+                                 uint16_t* v /*device, in place*/, fp8lm_meta* v_meta /*device*/,
+                                 uint16_t* w /*device, in place*/, fp8lm_meta* w_meta /*device*/,
+                                 void* wcopy /*device, write only*/, fp8lm_meta* wcopy_meta /*device*/,
+                                 const fp8lm_adam_hparams* hp /*host*/, void* stream);
+
+/* A plain 128-bit copy kernel over `bytes` bytes (multiple of 16): the measured bandwidth ceiling
+ * the streaming kernels are compared with.                                                        */
+fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* ctx, const void* src /*device*/, void* dst /*device*/, int64_t bytes,
+                              void* stream);
+
+/* Times the most recent launch of each kernel with HIP events recorded on the launch stream.
+ * fp8lm_set_timing(ctx, 1) starts recording event pairs around every kernel launch;
+ * fp8lm_get_timing synchronises and returns, per kernel id, the number of launches and the summed
+ * duration in milliseconds since timing was enabled, then resets the sums.                       */
+enum { FP8LM_K_AMAX = 0, FP8LM_K_CAST = 1, FP8LM_K_ADAM_AMAX = 2, FP8LM_K_ADAM_UPDATE = 3,
+       FP8LM_K_INIT_MASTER = 4, FP8LM_K_COPY = 5, FP8LM_K_COUNT = 6 };
+fp8lm_status fp8lm_set_timing(fp8lm_ctx* ctx, int32_t enable);
+fp8lm_status fp8lm_get_timing(fp8lm_ctx* ctx, int32_t* launches /*host[FP8LM_K_COUNT]*/,
+                              double* total_ms /*host[FP8LM_K_COUNT]*/);
+
+const char* fp8lm_status_string(fp8lm_status s);
+/* Text of the last HIP error seen by this thread's calls ("" if none).                            */
+const char* fp8lm_last_hip_error(void);
+/* Size of fp8lm_meta as compiled into the library (layout check for bindings).                    */
+uint32_t fp8lm_sizeof_meta(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FP8LM_H */

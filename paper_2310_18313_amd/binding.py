@@ -1,0 +1,240 @@
+"""Thin ctypes binding of libfp8lm.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in include/fp8lm.h; this
+module turns torch tensors into raw device pointers and the current torch stream into a HIP stream
+handle.  There is no CPU fallback: if the library is missing or fails to load, importing the
+functions raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Sequence, Tuple
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libfp8lm.so")
+
+HIST = 16
+E4M3, E5M2 = 0, 1
+SRC_BF16 = 0
+WCOPY_E4M3, WCOPY_BF16 = 0, 1
+FLAG_NONFINITE, FLAG_AMAX_ZERO, FLAG_SCALE_CLAMPED, FLAG_SATURATED = 1, 2, 4, 8
+K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_COUNT = range(7)
+KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy"]
+
+EXPORTS = [
+    "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_meta_init", "fp8lm_amax_scale",
+    "fp8lm_cast_fp8", "fp8lm_init_master", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
+    "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
+]
+
+
+class Tensor(C.Structure):
+    _fields_ = [("offset", C.c_int64), ("numel", C.c_int64)]
+
+
+class Meta(C.Structure):
+    _fields_ = [
+        ("scale", C.c_float), ("inv_scale", C.c_float), ("amax", C.c_float), ("amax_deq", C.c_float),
+        ("amax_hist", C.c_float * HIST), ("hist_pos", C.c_int32), ("mu_exp", C.c_int32),
+        ("clean_steps", C.c_int32), ("flags", C.c_uint32), ("n_sat", C.c_uint64),
+        ("n_underflow", C.c_uint64),
+    ]
+
+
+META_DTYPE = np.dtype([
+    ("scale", "<f4"), ("inv_scale", "<f4"), ("amax", "<f4"), ("amax_deq", "<f4"),
+    ("amax_hist", "<f4", (HIST,)), ("hist_pos", "<i4"), ("mu_exp", "<i4"), ("clean_steps", "<i4"),
+    ("flags", "<u4"), ("n_sat", "<u8"), ("n_underflow", "<u8"),
+])
+
+
+class AutoscaleCfg(C.Structure):
+    _fields_ = [("sat_num", C.c_int32), ("sat_den", C.c_int32), ("ramp_steps", C.c_int32),
+                ("hist_window", C.c_int32), ("margin", C.c_int32)]
+
+
+class AdamHparams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("step", C.c_int64), ("v_scaled", C.c_int32),
+                ("wcopy", C.c_int32), ("stats", C.c_int32), ("exact", C.c_int32)]
+
+
+def autoscale_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=100000) -> AutoscaleCfg:
+    return AutoscaleCfg(sat_num, sat_den, ramp_steps, hist_window, margin)
+
+
+def adam_hparams(lr, step, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, v_scaled=1,
+                 wcopy=WCOPY_E4M3, stats=0, exact=1) -> AdamHparams:
+    return AdamHparams(lr, beta1, beta2, eps, weight_decay, step, v_scaled, wcopy, stats, exact)
+
+
+class Fp8lmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        L = lib()
+        msg = L.fp8lm_status_string(status).decode()
+        hip = L.fp8lm_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} ({status})" + (f" [{hip}]" if hip and status == -4 else ""))
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libfp8lm.so (built in-tree by paper_2310_18313_amd.build); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2310_18313_amd.build` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        L.fp8lm_create.argtypes = [C.POINTER(vp), vp, i32, C.c_int]
+        L.fp8lm_destroy.argtypes = [vp]
+        L.fp8lm_set_tuning.argtypes = [vp, i32, i32, i32]
+        L.fp8lm_meta_init.argtypes = [vp, vp, vp, vp]
+        L.fp8lm_amax_scale.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, vp]
+        L.fp8lm_cast_fp8.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
+        L.fp8lm_init_master.argtypes = [vp, vp, vp, vp, vp]
+        L.fp8lm_adam_step_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.fp8lm_copy_bytes.argtypes = [vp, vp, vp, i64, vp]
+        L.fp8lm_set_timing.argtypes = [vp, i32]
+        L.fp8lm_get_timing.argtypes = [vp, vp, vp]
+        for name in EXPORTS:
+            getattr(L, name).restype = C.c_int
+        L.fp8lm_status_string.restype = C.c_char_p
+        L.fp8lm_status_string.argtypes = [C.c_int]
+        L.fp8lm_last_hip_error.restype = C.c_char_p
+        L.fp8lm_last_hip_error.argtypes = []
+        L.fp8lm_sizeof_meta.restype = C.c_uint32
+        L.fp8lm_sizeof_meta.argtypes = []
+        if L.fp8lm_sizeof_meta() != C.sizeof(Meta) or C.sizeof(Meta) != META_DTYPE.itemsize:
+            raise ImportError("fp8lm_meta layout mismatch between the library and the binding")
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise Fp8lmError(status, where)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t) -> int:
+    if t is None:
+        return 0
+    assert t.is_cuda and t.is_contiguous()
+    return t.data_ptr()
+
+
+class Context:
+    """Owns one fp8lm_ctx: a fixed list of (offset, numel) tensors inside flat device buffers."""
+
+    def __init__(self, tensors: Sequence[Tuple[int, int]], device: int = 0):
+        self.n_tensors = len(tensors)
+        arr = (Tensor * max(1, self.n_tensors))()
+        for i, (off, n) in enumerate(tensors):
+            arr[i].offset, arr[i].numel = int(off), int(n)
+        h = C.c_void_p()
+        _check(lib().fp8lm_create(C.byref(h), C.cast(arr, C.c_void_p), self.n_tensors, device), "fp8lm_create")
+        self._h = h
+        self.device = device
+        # the C ABI takes bare pointers: the extent every flat buffer must cover is checked here
+        self.required_elems = max([int(o) + int(n) for o, n in tensors if n > 0], default=0)
+
+    def _fits(self, *bufs):
+        for t in bufs:
+            if t.numel() < self.required_elems:
+                raise ValueError(f"flat buffer of {t.numel()} elements is shorter than the tensor list needs "
+                                 f"({self.required_elems})")
+            if t.device.index != self.device:
+                raise ValueError("buffer is on another device than the context")
+
+    def _fits_meta(self, *metas):
+        for t in metas:
+            if t.numel() * t.element_size() < self.n_tensors * C.sizeof(Meta):
+                raise ValueError("meta array is shorter than the tensor list")
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().fp8lm_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:  # interpreter shutdown
+            pass
+
+    def set_tuning(self, chunk_elems=16384, blocks_per_cu=8, interleave=0):
+        _check(lib().fp8lm_set_tuning(self._h, chunk_elems, blocks_per_cu, interleave), "fp8lm_set_tuning")
+
+    def new_meta(self, cfg: AutoscaleCfg, stream=None) -> torch.Tensor:
+        """Device array of fp8lm_meta (as raw bytes, [n_tensors, 112]) in its initial state."""
+        meta = torch.empty((max(1, self.n_tensors), C.sizeof(Meta)), dtype=torch.uint8, device=f"cuda:{self.device}")
+        _check(lib().fp8lm_meta_init(self._h, _ptr(meta), C.addressof(cfg), _stream(stream)), "fp8lm_meta_init")
+        return meta
+
+    def amax_scale(self, src, target_fmt, meta, cfg, stream=None):
+        assert src.element_size() == 2
+        self._fits(src)
+        self._fits_meta(meta)
+        _check(lib().fp8lm_amax_scale(self._h, _ptr(src), SRC_BF16, target_fmt, _ptr(meta), C.addressof(cfg),
+                                      _stream(stream)), "fp8lm_amax_scale")
+
+    def cast_fp8(self, src, dst, fmt, meta, cfg, stream=None):
+        assert src.element_size() == 2 and dst.element_size() == 1
+        self._fits(src, dst)
+        self._fits_meta(meta)
+        _check(lib().fp8lm_cast_fp8(self._h, _ptr(src), SRC_BF16, _ptr(dst), fmt, _ptr(meta), C.addressof(cfg),
+                                    _stream(stream)), "fp8lm_cast_fp8")
+
+    def init_master(self, w_bf16, w_f16, w_meta, stream=None):
+        assert w_bf16.element_size() == 2 and w_f16.element_size() == 2
+        self._fits(w_bf16, w_f16)
+        self._fits_meta(w_meta)
+        _check(lib().fp8lm_init_master(self._h, _ptr(w_bf16), _ptr(w_f16), _ptr(w_meta), _stream(stream)),
+               "fp8lm_init_master")
+
+    def adam_step_fp8(self, grad, grad_fmt, grad_meta, m, m_meta, v, v_meta, w, w_meta, wcopy, wcopy_meta,
+                      hp: AdamHparams, stream=None):
+        assert grad.element_size() == 1 and m.element_size() == 1 and v.element_size() == 2 and w.element_size() == 2
+        assert wcopy.element_size() == (1 if hp.wcopy == WCOPY_E4M3 else 2)
+        self._fits(grad, m, v, w, wcopy)
+        self._fits_meta(grad_meta, m_meta, v_meta, w_meta, wcopy_meta)
+        _check(lib().fp8lm_adam_step_fp8(self._h, _ptr(grad), grad_fmt, _ptr(grad_meta), _ptr(m), _ptr(m_meta),
+                                         _ptr(v), _ptr(v_meta), _ptr(w), _ptr(w_meta), _ptr(wcopy),
+                                         _ptr(wcopy_meta), C.addressof(hp), _stream(stream)), "fp8lm_adam_step_fp8")
+
+    def copy_bytes(self, src, dst, nbytes, stream=None):
+        assert src.numel() * src.element_size() >= nbytes and dst.numel() * dst.element_size() >= nbytes
+        _check(lib().fp8lm_copy_bytes(self._h, _ptr(src), _ptr(dst), nbytes, _stream(stream)), "fp8lm_copy_bytes")
+
+    def set_timing(self, enable: bool):
+        _check(lib().fp8lm_set_timing(self._h, 1 if enable else 0), "fp8lm_set_timing")
+
+    def get_timing(self):
+        """{kernel name: (launches, total ms)} since timing was enabled or last read (synchronises)."""
+        n = (C.c_int32 * K_COUNT)()
+        ms = (C.c_double * K_COUNT)()
+        _check(lib().fp8lm_get_timing(self._h, C.cast(n, C.c_void_p), C.cast(ms, C.c_void_p)), "fp8lm_get_timing")
+        return {KERNEL_NAMES[k]: (int(n[k]), float(ms[k])) for k in range(K_COUNT)}
+
+
+def meta_to_numpy(meta: torch.Tensor, n: int) -> np.ndarray:
+    """Host copy of a device meta array as a numpy structured array."""
+    return meta.detach().cpu().numpy().reshape(-1).view(META_DTYPE)[:n].copy()
+
+
+def meta_from_numpy(arr: np.ndarray, device) -> torch.Tensor:
+    raw = np.ascontiguousarray(arr).view(np.uint8).reshape(len(arr), META_DTYPE.itemsize)
+    return torch.from_numpy(raw.copy()).to(device)

@@ -1,0 +1,1240 @@
+// libfp8lm: FP8 gradient quantisation and FP8 Adam step of FP8-LM (arXiv 2310.18313, Sec. 2.1, 2.2,
+// Appendix A) for MI355X / gfx950.  See include/fp8lm.h for the boundary.
+//
+// Shape of every hot kernel
+//   * The tensor list is cut into chunks of `chunk_elems` elements that never straddle a tensor.  A
+//     persistent grid of 256-thread workgroups (a few per compute unit) walks the chunk table, so a
+//     5 K-element bias and a 250 M-element matrix are served by the same launch.
+//   * A thread handles 16 consecutive elements per iteration: one 128-bit access for 8-bit buffers,
+//     two adjacent 128-bit accesses for 16-bit buffers; a wavefront covers 1 KiB / 2 KiB contiguous.
+//   * Per-tensor statistics (amax, counters) are kept in registers while a workgroup stays inside one
+//     tensor, then reduced wavefront -> LDS -> one atomic per workgroup into a per-tensor scratch slot.
+//     A ticket counter of finished chunks tells the last workgroup of a tensor to run the scalar
+//     epilogue (scale update, auto-scaling state, metadata) and to clear the scratch: a single pass,
+//     no second launch.
+//   * These kernels are HBM-bandwidth bound (2..12 bytes per element against ~40 ALU operations); no
+//     matrix cores are involved.
+#include <hip/hip_runtime.h>
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "fp8lm.h"
+#include "formats.hpp"
+
+namespace fp8lm {
+
+constexpr int kThreads = 256;
+constexpr int kGroup = 16;                 // elements per thread per iteration
+constexpr int kTile = kThreads * kGroup;   // elements per workgroup per iteration
+constexpr int kWaves = kThreads / 64;
+
+struct TensorDesc {
+  int64_t offset;
+  int64_t numel;
+  int32_t first_chunk;
+  int32_t n_chunks;
+};
+
+// Per-tensor reduction scratch.  All-zero between launches except the `pend` block, which carries
+// the scales chosen by the first Adam pass to the second.
+struct Scratch {
+  uint32_t max_a, max_b, max_c;   // running maxima (bit patterns of non-negative values)
+  uint32_t ticket;                // chunks finished
+  uint32_t nf;                    // careful path: bit (2*k) NaN seen, bit (2*k+1) inf seen, k = 0 m, 1 v, 2 w
+  uint32_t pad;
+  unsigned long long cnt[8];      // counters: n_sat / n_underflow
+  struct Pending {
+    float sm, ism, sv, isv, sw, isw, sq, isq;
+    uint32_t fm, fv, fw, fq;      // flags gathered while choosing the scales
+    float amax_m;
+    uint32_t careful;
+  } pend;
+};
+
+struct Tables {
+  const TensorDesc* desc;
+  const int32_t* chunk_tensor;
+  Scratch* scratch;
+  int32_t n_chunks;
+  int32_t chunk_elems;
+  int32_t interleave;
+};
+
+// ---- reductions ----------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o, 64));
+  return v;
+}
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_or_u32(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v |= (uint32_t)__shfl_xor((int)v, o, 64);
+  return v;
+}
+
+// Workgroup-wide combine of up to NV maxima, NC counters and one OR-mask; result valid in thread 0.
+template <int NV, int NC>
+struct BlockStats {
+  uint32_t mx[NV > 0 ? NV : 1];
+  unsigned long long ct[NC > 0 ? NC : 1];
+  uint32_t orv;
+};
+
+template <int NV, int NC>
+__device__ __forceinline__ void block_combine(BlockStats<NV, NC>& s) {
+  __shared__ uint32_t l_mx[kWaves][NV > 0 ? NV : 1];
+  __shared__ unsigned long long l_ct[kWaves][NC > 0 ? NC : 1];
+  __shared__ uint32_t l_or[kWaves];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) s.mx[i] = wave_max_u32(s.mx[i]);
+#pragma unroll
+  for (int i = 0; i < NC; ++i) s.ct[i] = wave_sum_u64(s.ct[i]);
+  s.orv = wave_or_u32(s.orv);
+  __syncthreads();   // the previous use of the LDS arrays is over
+  if (lane == 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) l_mx[wave][i] = s.mx[i];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) l_ct[wave][i] = s.ct[i];
+    l_or[wave] = s.orv;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) s.mx[i] = max(s.mx[i], l_mx[w][i]);
+#pragma unroll
+      for (int i = 0; i < NC; ++i) s.ct[i] += l_ct[w][i];
+      s.orv |= l_or[w];
+    }
+  }
+}
+
+// Publishes a workgroup's partial results for tensor t and returns true in thread 0 of the workgroup
+// that completes the tensor.  Ordering: partials are written with agent-scope atomics, then the
+// ticket is bumped with release/acquire semantics; the completing workgroup therefore observes
+// every other workgroup's partials.
+__device__ __forceinline__ bool publish_ticket(Scratch* sc, int chunks_done, int chunks_total) {
+  const uint32_t old = __hip_atomic_fetch_add(&sc->ticket, (uint32_t)chunks_done, __ATOMIC_ACQ_REL,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+  return old + (uint32_t)chunks_done == (uint32_t)chunks_total;
+}
+__device__ __forceinline__ void atomic_max_u32(uint32_t* p, uint32_t v) {
+  if (v) __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void atomic_add_u64(unsigned long long* p, unsigned long long v) {
+  if (v) __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void atomic_or_u32(uint32_t* p, uint32_t v) {
+  if (v) __hip_atomic_fetch_or(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t take_u32(uint32_t* p) {   // read and clear
+  return __hip_atomic_exchange(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long take_u64(unsigned long long* p) {
+  return __hip_atomic_exchange(p, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---- the chunk walk shared by all kernels -------------------------------------------------------
+// Op must provide: begin(t, desc), group(pos, valid) with `pos` the element index into the flat
+// buffers and 1 <= valid <= 16, and flush(t, desc, chunks_done) (called by all threads).
+template <class Op>
+__device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
+  const long long G = gridDim.x, b = blockIdx.x;
+  long long c, c_end, step;
+  if (tb.interleave) { c = b; c_end = tb.n_chunks; step = G; }
+  else { c = b * tb.n_chunks / G; c_end = (b + 1) * tb.n_chunks / G; step = 1; }
+  int cur = -1, done = 0;
+  TensorDesc d{};
+  for (; c < c_end; c += step) {
+    const int t = tb.chunk_tensor[c];
+    if (t != cur) {
+      if (cur >= 0) op.flush(cur, d, done);
+      cur = t;
+      done = 0;
+      d = tb.desc[t];
+      op.begin(t, d);
+    }
+    const long long e0 = (long long)((int)c - d.first_chunk) * tb.chunk_elems;
+    const long long rest = d.numel - e0;
+    const int len = rest < tb.chunk_elems ? (int)rest : tb.chunk_elems;
+    const long long base = d.offset + e0;
+    for (int i = threadIdx.x * kGroup; i < len; i += kTile) {
+      const int valid = len - i < kGroup ? len - i : kGroup;
+      op.group(base + i, valid);
+    }
+    ++done;
+  }
+  if (cur >= 0) op.flush(cur, d, done);
+}
+
+__device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void st16(void* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
+
+// ================================================================================================
+// Kernel 1: per-tensor amax of a bf16 buffer, then the scale update (Appendix A.2; Sec. 2.1 Eq. 3)
+// ================================================================================================
+// |x| of a bf16 is monotone in (bits & 0x7FFF), so the maximum is taken on packed 16-bit integers:
+// exact, order independent, and inf/NaN show up as a result >= 0x7F80.
+enum : int { kAmaxForGradient = 0, kAmaxForMaster = 1 };
+
+struct AmaxParams {
+  const uint16_t* src;
+  fp8lm_meta* meta;
+  uint32_t fmax_bits;     // gradient mode: largest finite value of the target format
+  int32_t hist_window;
+  int32_t margin;
+};
+
+template <int MODE>
+struct AmaxOp {
+  const AmaxParams& p;
+  const Tables& tb;
+  uint32_t acc;   // two 16-bit running maxima
+  __device__ AmaxOp(const AmaxParams& p_, const Tables& tb_) : p(p_), tb(tb_), acc(0) {}
+  __device__ __forceinline__ void begin(int, const TensorDesc&) { acc = 0; }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    if (valid == kGroup) {
+      const uint4 a = ld16(p.src + pos), b = ld16(p.src + pos + 8);
+      const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const ushort2_t x = __builtin_bit_cast(ushort2_t, w[j] & 0x7FFF7FFFu);
+        acc = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, acc), x));
+      }
+    } else {
+      uint32_t m = acc & 0xFFFFu;
+      for (int j = 0; j < valid; ++j) m = max(m, (uint32_t)(p.src[pos + j] & 0x7FFFu));
+      acc = (acc & 0xFFFF0000u) | m;
+    }
+  }
+  __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
+    BlockStats<1, 0> s;
+    s.mx[0] = max(acc & 0xFFFFu, acc >> 16);
+    s.orv = 0;
+    block_combine(s);
+    if (threadIdx.x == 0) {
+      Scratch* sc = tb.scratch + t;
+      atomic_max_u32(&sc->max_a, s.mx[0]);
+      if (publish_ticket(sc, done, d.n_chunks)) {
+        const uint32_t abits = take_u32(&sc->max_a);
+        take_u32(&sc->ticket);
+        finish(t, abits);
+      }
+    }
+  }
+  // scalar epilogue, one thread per tensor
+  __device__ void finish(int t, uint32_t abits) {
+    fp8lm_meta& M = p.meta[t];
+    if (abits >= 0x7F80u) {
+      M.amax = __builtin_inff();
+      M.flags = FP8LM_FLAG_NONFINITE;
+      return;
+    }
+    const float A = u2f(abits << 16);
+    M.amax = A;
+    uint32_t flags = 0;
+    if constexpr (MODE == kAmaxForGradient) {
+      int H = p.hist_window < 1 ? 1 : (p.hist_window > FP8LM_HIST ? FP8LM_HIST : p.hist_window);
+      const int slot = M.hist_pos % H;
+      M.amax_hist[slot] = A;
+      M.hist_pos = (slot + 1) % H;
+      float Aeff = 0.0f;
+      for (int h = 0; h < H; ++h) Aeff = M.amax_hist[h] > Aeff ? M.amax_hist[h] : Aeff;
+      if (Aeff == 0.0f) {
+        flags |= FP8LM_FLAG_AMAX_ZERO;
+      } else {
+        const int k = pow2_exp(p.fmax_bits, Aeff) + M.mu_exp - p.margin;
+        const int e = k < -126 ? -126 : (k > 126 ? 126 : k);
+        if (e != k) flags |= FP8LM_FLAG_SCALE_CLAMPED;
+        M.scale = pow2f(e);
+        M.inv_scale = pow2f(-e);
+      }
+      M.flags = flags;
+    } else {
+      // master weights: one binade of headroom; flags and the rest are completed by the cast pass
+      if (A == 0.0f) {
+        flags |= FP8LM_FLAG_AMAX_ZERO;
+      } else {
+        const int k = pow2_exp(kBitsF16Max, A) - 1;
+        const int e = k < -126 ? -126 : (k > 126 ? 126 : k);
+        if (e != k) flags |= FP8LM_FLAG_SCALE_CLAMPED;
+        M.scale = pow2f(e);
+        M.inv_scale = pow2f(-e);
+      }
+      M.flags = flags;
+    }
+  }
+};
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void amax_kernel(Tables tb, AmaxParams p) {
+  AmaxOp<MODE> op(p, tb);
+  walk_chunks(tb, op);
+}
+
+// ================================================================================================
+// Kernel 2: scaled saturating FP8 cast + auto-scaling state (Sec. 2.1; Appendix A.1)
+// ================================================================================================
+struct CastParams {
+  const uint16_t* src;
+  uint8_t* dst;
+  fp8lm_meta* meta;
+  int32_t sat_num, sat_den, ramp_steps;
+};
+
+// number of zero bytes among the four 7-bit fields of x (each byte of x must be <= 0x7F)
+__device__ __forceinline__ uint32_t nonzero_bytes7(uint32_t x) { return __popc((x + 0x7F7F7F7Fu) & 0x80808080u); }
+
+template <int FMT>
+struct CastOp {
+  const CastParams& p;
+  const Tables& tb;
+  float scale;
+  bool careful;
+  float vmax;             // max |clamped scaled value|
+  uint32_t n_elems;       // elements seen (full groups * 16 + tails) since the last flush
+  uint32_t nz_top;        // codes whose magnitude differs from the top code
+  uint32_t nz_code;       // codes with non-zero magnitude
+  uint32_t z_in;          // inputs that are +-0
+  __device__ CastOp(const CastParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
+  __device__ __forceinline__ void reset() { vmax = 0.0f; n_elems = nz_top = nz_code = z_in = 0; }
+  __device__ __forceinline__ void begin(int t, const TensorDesc&) {
+    scale = p.meta[t].scale;
+    careful = (p.meta[t].flags & FP8LM_FLAG_NONFINITE) != 0;
+    reset();
+  }
+  __device__ __forceinline__ uint32_t quad(uint32_t w0, uint32_t w1) {
+    const float f0 = bf16lo_to_f32(w0), f1 = bf16hi_to_f32(w0), f2 = bf16lo_to_f32(w1), f3 = bf16hi_to_f32(w1);
+    const float y0 = clamp_fp8<FMT>(f0 * scale), y1 = clamp_fp8<FMT>(f1 * scale);
+    const float y2 = clamp_fp8<FMT>(f2 * scale), y3 = clamp_fp8<FMT>(f3 * scale);
+    vmax = fmaxf(fmaxf(vmax, fmaxf(fabsf(y0), fabsf(y1))), fmaxf(fabsf(y2), fabsf(y3)));
+    z_in += (f0 == 0.0f) + (f1 == 0.0f) + (f2 == 0.0f) + (f3 == 0.0f);
+    uint32_t c = f32x2_to_fp8<FMT, false>(y0, y1, 0u);
+    c = f32x2_to_fp8<FMT, true>(y2, y3, c);
+    const uint32_t mag = c & 0x7F7F7F7Fu;
+    nz_code += nonzero_bytes7(mag);
+    nz_top += nonzero_bytes7(mag ^ Fp8Traits<FMT>::kTopX4);
+    return c;
+  }
+  __device__ __forceinline__ uint32_t one(uint32_t bits) {
+    const float f = u2f(bits << 16);
+    const float y = f * scale;
+    uint32_t c;
+    if (y != y) {
+      c = 0x7Fu;
+    } else {
+      const float yc = clamp_fp8<FMT>(y);
+      vmax = fmaxf(vmax, fabsf(yc));
+      c = f32x2_to_fp8<FMT, false>(yc, 0.0f, 0u) & 0xFFu;
+    }
+    z_in += (f == 0.0f);
+    nz_code += (c & 0x7Fu) != 0;
+    nz_top += (c & 0x7Fu) != Fp8Traits<FMT>::kTop;
+    return c;
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    if (valid == kGroup && !careful) {
+      const uint4 a = ld16(p.src + pos), b = ld16(p.src + pos + 8);
+      uint4 o;
+      o.x = quad(a.x, a.y);
+      o.y = quad(a.z, a.w);
+      o.z = quad(b.x, b.y);
+      o.w = quad(b.z, b.w);
+      st16(p.dst + pos, o);
+    } else {
+      for (int j = 0; j < valid; ++j) p.dst[pos + j] = (uint8_t)one(p.src[pos + j]);
+    }
+    n_elems += valid;
+  }
+  __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
+    BlockStats<1, 2> s;
+    s.mx[0] = f2u(vmax);
+    s.ct[0] = n_elems - nz_top;                 // codes on the top magnitude
+    s.ct[1] = (n_elems - nz_code) - z_in;       // zero codes that did not come from zero inputs
+    s.orv = 0;
+    block_combine(s);
+    if (threadIdx.x == 0) {
+      Scratch* sc = tb.scratch + t;
+      atomic_max_u32(&sc->max_a, s.mx[0]);
+      atomic_add_u64(&sc->cnt[0], s.ct[0]);
+      atomic_add_u64(&sc->cnt[1], s.ct[1]);
+      if (publish_ticket(sc, done, d.n_chunks)) {
+        const float vm = u2f(take_u32(&sc->max_a));
+        const unsigned long long n_sat = take_u64(&sc->cnt[0]), n_und = take_u64(&sc->cnt[1]);
+        take_u32(&sc->ticket);
+        finish(t, d, vm, n_sat, n_und);
+      }
+    }
+  }
+  __device__ void finish(int t, const TensorDesc& d, float vm, unsigned long long n_sat, unsigned long long n_und) {
+    fp8lm_meta& M = p.meta[t];
+    M.n_sat = n_sat;
+    M.n_underflow = n_und;
+    M.amax_deq = fp8_to_f32<FMT>(encode1_fp8<FMT>(vm)) * M.inv_scale;
+    M.flags = n_sat ? (M.flags | FP8LM_FLAG_SATURATED) : (M.flags & ~FP8LM_FLAG_SATURATED);
+    // auto-scaling state machine (Sec. 2.1, paragraph after Eq. 3)
+    const int R = p.ramp_steps < 2 ? 2 : p.ramp_steps;
+    const bool overflow = (long long)n_sat * (long long)p.sat_den > d.numel * (long long)p.sat_num;
+    int clean = overflow ? 0 : (M.clean_steps + 1 > R ? R : M.clean_steps + 1);
+    M.clean_steps = clean;
+    const int ramp = (2 * clean) / R;
+    M.mu_exp = -1 + (ramp > 2 ? 2 : ramp);
+  }
+};
+
+template <int FMT>
+__global__ __launch_bounds__(kThreads) void cast_kernel(Tables tb, CastParams p) {
+  CastOp<FMT> op(p, tb);
+  walk_chunks(tb, op);
+}
+
+// ================================================================================================
+// Master-weight initialisation: bf16 -> scaled FP16 (Sec. 2.2)
+// ================================================================================================
+struct InitParams {
+  const uint16_t* src;
+  uint16_t* dst;
+  fp8lm_meta* meta;
+};
+
+struct InitCastOp {
+  const InitParams& p;
+  const Tables& tb;
+  float scale;
+  float vmax;
+  uint32_t n_sat, n_und;
+  __device__ InitCastOp(const InitParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
+  __device__ __forceinline__ void begin(int t, const TensorDesc&) {
+    scale = p.meta[t].scale;
+    vmax = 0.0f;
+    n_sat = n_und = 0;
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    for (int j = 0; j < valid; ++j) {
+      const uint32_t bits = p.src[pos + j];
+      const float y = u2f(bits << 16) * scale;
+      const uint32_t h = encode1_f16_careful(y);
+      if (y == y) vmax = fmaxf(vmax, fabsf(clamp_f16(y)));
+      n_sat += (h & 0x7FFFu) == 0x7BFFu;
+      n_und += ((bits & 0x7FFFu) != 0) && ((h & 0x7FFFu) == 0);
+      p.dst[pos + j] = (uint16_t)h;
+    }
+  }
+  __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
+    BlockStats<1, 2> s;
+    s.mx[0] = f2u(vmax);
+    s.ct[0] = n_sat;
+    s.ct[1] = n_und;
+    s.orv = 0;
+    block_combine(s);
+    if (threadIdx.x == 0) {
+      Scratch* sc = tb.scratch + t;
+      atomic_max_u32(&sc->max_a, s.mx[0]);
+      atomic_add_u64(&sc->cnt[0], s.ct[0]);
+      atomic_add_u64(&sc->cnt[1], s.ct[1]);
+      if (publish_ticket(sc, done, d.n_chunks)) {
+        const float vm = u2f(take_u32(&sc->max_a));
+        fp8lm_meta& M = p.meta[t];
+        M.n_sat = take_u64(&sc->cnt[0]);
+        M.n_underflow = take_u64(&sc->cnt[1]);
+        take_u32(&sc->ticket);
+        M.amax_deq = f16_to_f32(encode1_f16(vm)) * M.inv_scale;
+        if (M.n_sat) M.flags |= FP8LM_FLAG_SATURATED;
+      }
+    }
+  }
+};
+
+__global__ __launch_bounds__(kThreads) void init_master_cast_kernel(Tables tb, InitParams p) {
+  InitCastOp op(p, tb);
+  walk_chunks(tb, op);
+}
+
+// ================================================================================================
+// Kernels 3 + 4: the FP8 Adam step (Sec. 2.2, Eq. 8; Sec. 3.1.2)
+// ================================================================================================
+struct AdamParams {
+  const uint8_t* grad;
+  const fp8lm_meta* grad_meta;
+  uint8_t* m;
+  fp8lm_meta* m_meta;
+  uint16_t* v;
+  fp8lm_meta* v_meta;
+  uint16_t* w;
+  fp8lm_meta* w_meta;
+  void* wcopy;
+  fp8lm_meta* wcopy_meta;
+  float b1, omb1, rbc1, b2, omb2, rbc2, lr, eps, decay;
+  int32_t v_scaled;
+};
+
+// Chooses a stored scale from a magnitude bound; keeps the old one when the bound is 0 or not finite.
+__device__ __forceinline__ void refresh_scale(uint32_t fmax_bits, float bound, int headroom, float old_scale,
+                                              float old_inv, float& scale, float& inv, uint32_t& flags) {
+  scale = old_scale;
+  inv = old_inv;
+  if (!(bound <= 3.4028234663852886e38f)) { flags |= FP8LM_FLAG_NONFINITE; return; }
+  if (bound == 0.0f) { flags |= FP8LM_FLAG_AMAX_ZERO; return; }
+  const int k = pow2_exp(fmax_bits, bound) - headroom;
+  const int e = k < -126 ? -126 : (k > 126 ? 126 : k);
+  if (e != k) flags |= FP8LM_FLAG_SCALE_CLAMPED;
+  scale = pow2f(e);
+  inv = pow2f(-e);
+}
+
+// ---- pass A: exact amax of the new first moment, then all four scales ---------------------------
+template <int GFMT, int WCOPY>
+struct AdamAmaxOp {
+  const AdamParams& p;
+  const Tables& tb;
+  float inv_sg, inv_sm;
+  uint32_t acc;
+  __device__ AdamAmaxOp(const AdamParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
+  __device__ __forceinline__ void begin(int t, const TensorDesc&) {
+    inv_sg = p.grad_meta[t].inv_scale;
+    inv_sm = p.m_meta[t].inv_scale;
+    acc = 0;
+  }
+  __device__ __forceinline__ void elem(float dg, float dm) {
+    const float g = dg * inv_sg, m0 = dm * inv_sm;
+    const float m1 = __builtin_fmaf(p.b1, m0, p.omb1 * g);
+    acc = max(acc, f2u(m1) & 0x7FFFFFFFu);
+  }
+  __device__ __forceinline__ void word(uint32_t gw, uint32_t mw) {
+    const float2_t g01 = fp8x2_to_f32<GFMT, false>(gw), g23 = fp8x2_to_f32<GFMT, true>(gw);
+    const float2_t m01 = fp8x2_to_f32<kE4M3, false>(mw), m23 = fp8x2_to_f32<kE4M3, true>(mw);
+    elem(g01.x, m01.x);
+    elem(g01.y, m01.y);
+    elem(g23.x, m23.x);
+    elem(g23.y, m23.y);
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    if (valid == kGroup) {
+      const uint4 g = ld16(p.grad + pos), m = ld16(p.m + pos);
+      word(g.x, m.x);
+      word(g.y, m.y);
+      word(g.z, m.z);
+      word(g.w, m.w);
+    } else {
+      for (int j = 0; j < valid; ++j) elem(fp8_to_f32<GFMT>(p.grad[pos + j]), fp8_to_f32<kE4M3>(p.m[pos + j]));
+    }
+  }
+  __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
+    BlockStats<1, 0> s;
+    s.mx[0] = acc;
+    s.orv = 0;
+    block_combine(s);
+    if (threadIdx.x == 0) {
+      Scratch* sc = tb.scratch + t;
+      atomic_max_u32(&sc->max_a, s.mx[0]);
+      if (publish_ticket(sc, done, d.n_chunks)) {
+        const uint32_t abits = take_u32(&sc->max_a);
+        take_u32(&sc->ticket);
+        finish(t, abits);
+      }
+    }
+  }
+  __device__ void finish(int t, uint32_t abits) {
+    Scratch::Pending& P = tb.scratch[t].pend;
+    const fp8lm_meta& G = p.grad_meta[t];
+    const fp8lm_meta& Mm = p.m_meta[t];
+    const fp8lm_meta& Mv = p.v_meta[t];
+    const fp8lm_meta& Mw = p.w_meta[t];
+    const fp8lm_meta& Mq = p.wcopy_meta[t];
+    const bool m_nonfinite = abits >= 0x7F800000u;
+    const float A_m = m_nonfinite ? __builtin_inff() : u2f(abits);
+    uint32_t fm = 0, fv = 0, fw = 0, fq = 0;
+    refresh_scale(kBitsE4M3Max, A_m, 0, Mm.scale, Mm.inv_scale, P.sm, P.ism, fm);
+    float Bv = 0.0f;
+    if (p.v_scaled) {
+      const float Ag = G.amax_deq;
+      Bv = __builtin_fmaf(p.b2, Mv.amax_deq, p.omb2 * (Ag * Ag));
+      refresh_scale(kBitsF16Max, Bv, 0, Mv.scale, Mv.inv_scale, P.sv, P.isv, fv);
+    } else {
+      P.sv = 1.0f;
+      P.isv = 1.0f;
+    }
+    refresh_scale(kBitsF16Max, Mw.amax_deq, 1, Mw.scale, Mw.inv_scale, P.sw, P.isw, fw);
+    if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
+      refresh_scale(kBitsE4M3Max, Mw.amax_deq, 0, Mq.scale, Mq.inv_scale, P.sq, P.isq, fq);
+    } else {
+      P.sq = 1.0f;
+      P.isq = 1.0f;
+    }
+    P.fm = fm; P.fv = fv; P.fw = fw; P.fq = fq;
+    P.amax_m = A_m;
+    // The fast update path assumes that no NaN and no fp32 overflow can occur.  That holds when every
+    // input magnitude is moderate; anything else takes the careful path, which checks every element.
+    const float kBig = 1.0995116e12f;     // 2^40
+    const float kHuge = 1.2089258e24f;    // 2^80
+    const uint32_t anyflag = (G.flags | Mm.flags | Mv.flags | Mw.flags) & FP8LM_FLAG_NONFINITE;
+    const bool calm = !anyflag && !m_nonfinite && (A_m < kBig) && (G.amax_deq < kBig) &&
+                      (Mv.amax_deq < kHuge) && (Mw.amax_deq < kHuge);
+    P.careful = calm ? 0u : 1u;
+  }
+};
+
+template <int GFMT, int WCOPY>
+__global__ __launch_bounds__(kThreads) void adam_amax_kernel(Tables tb, AdamParams p) {
+  AdamAmaxOp<GFMT, WCOPY> op(p, tb);
+  walk_chunks(tb, op);
+}
+
+// ---- pass B: the update ----------------------------------------------------------------------------
+// FAST: v_sqrt_f32 / v_rcp_f32 (1 ulp each) instead of correctly rounded sqrt and divide in the weight
+// update; m and v are unaffected (multiply/fma only).  STATS: count n_sat / n_underflow per output.
+template <bool FAST> __device__ __forceinline__ float adam_update(float m1, float v1, float w0, const AdamParams& p) {
+  if constexpr (FAST) {
+    const float den = __builtin_amdgcn_sqrtf(v1 * p.rbc2) + p.eps;
+    const float upd = (m1 * p.rbc1) * __builtin_amdgcn_rcpf(den);
+    return __builtin_fmaf(-p.lr, upd, w0 * p.decay);
+  } else {
+    const float den = __builtin_sqrtf(v1 * p.rbc2) + p.eps;
+    const float upd = ((m1 * p.rbc1) / den);
+    return __builtin_fmaf(-p.lr, upd, w0 * p.decay);
+  }
+}
+
+template <int GFMT, int WCOPY, bool FAST, bool STATS>
+struct AdamUpdateOp {
+  const AdamParams& p;
+  const Tables& tb;
+  float inv_sg, inv_sm, inv_sv, inv_sw;   // scales of the inputs
+  float sm, sv, sw, sq;                   // scales of the outputs
+  bool careful;
+  float vmax, wmax, mmax;                 // running maxima of v', |w'| (and |m'| on the careful path)
+  uint32_t nf;
+  uint32_t cnt[8];                        // sat m,v,w,q ; underflow m,v,w,q
+  __device__ AdamUpdateOp(const AdamParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
+  __device__ __forceinline__ void begin(int t, const TensorDesc&) {
+    const Scratch::Pending& P = tb.scratch[t].pend;
+    inv_sg = p.grad_meta[t].inv_scale;
+    inv_sm = p.m_meta[t].inv_scale;
+    inv_sv = p.v_meta[t].inv_scale;
+    inv_sw = p.w_meta[t].inv_scale;
+    sm = P.sm; sv = P.sv; sw = P.sw; sq = P.sq;
+    careful = P.careful != 0;
+    vmax = wmax = mmax = 0.0f;
+    nf = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cnt[i] = 0;
+  }
+
+  // exact counters, from the scaled values before clamping
+  __device__ __forceinline__ void stats(float m1, float v1, float w1, float tm, float tv, float tw, float tq) {
+    if constexpr (STATS) {
+      cnt[0] += fabsf(tm) >= 432.0f;                       // rounds to (or beyond) the top E4M3 code
+      cnt[1] += fabsf(tv) > 65488.0f;                      // rounds to the top FP16 code
+      cnt[2] += fabsf(tw) > 65488.0f;
+      cnt[4] += (fabsf(tm) <= 0x1p-10f) && (m1 != 0.0f);   // rounds to zero
+      cnt[5] += (fabsf(tv) <= 0x1p-25f) && (v1 != 0.0f);
+      cnt[6] += (fabsf(tw) <= 0x1p-25f) && (w1 != 0.0f);
+      if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
+        cnt[3] += fabsf(tq) >= 432.0f;
+        cnt[7] += (fabsf(tq) <= 0x1p-10f) && (w1 != 0.0f);
+      } else {
+        const uint32_t ab = f2u(w1) & 0x7FFFFFFFu;
+        cnt[3] += (ab >= 0x7F7F8000u) && (ab <= 0x7F800000u);   // rounds to infinity
+        cnt[7] += (ab <= 0x00008000u) && (ab != 0u);
+      }
+    }
+  }
+
+  struct Quad { uint32_t m, v01, v23, w01, w23, q, q2; };
+
+  // four elements: one word of gradient codes, one of moment codes, two words each of v and w
+  __device__ __forceinline__ Quad quad(uint32_t gw, uint32_t mw, uint32_t v01, uint32_t v23, uint32_t w01, uint32_t w23) {
+    const float2_t dg01 = fp8x2_to_f32<GFMT, false>(gw), dg23 = fp8x2_to_f32<GFMT, true>(gw);
+    const float2_t dm01 = fp8x2_to_f32<kE4M3, false>(mw), dm23 = fp8x2_to_f32<kE4M3, true>(mw);
+    const float2_t dv01 = f16x2_to_f32(v01), dv23 = f16x2_to_f32(v23);
+    const float2_t dw01 = f16x2_to_f32(w01), dw23 = f16x2_to_f32(w23);
+    const float dg[4] = {dg01.x, dg01.y, dg23.x, dg23.y};
+    const float dm[4] = {dm01.x, dm01.y, dm23.x, dm23.y};
+    const float dv[4] = {dv01.x, dv01.y, dv23.x, dv23.y};
+    const float dw[4] = {dw01.x, dw01.y, dw23.x, dw23.y};
+    float tm[4], tv[4], tw[4], tq[4], w1s[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float g = dg[j] * inv_sg, m0 = dm[j] * inv_sm, v0 = dv[j] * inv_sv, w0 = dw[j] * inv_sw;
+      const float m1 = __builtin_fmaf(p.b1, m0, p.omb1 * g);
+      const float v1 = __builtin_fmaf(p.b2, v0, p.omb2 * (g * g));
+      const float w1 = adam_update<FAST>(m1, v1, w0, p);
+      vmax = fmaxf(vmax, v1);
+      wmax = fmaxf(wmax, fabsf(w1));
+      tm[j] = m1 * sm;
+      tv[j] = v1 * sv;
+      tw[j] = w1 * sw;
+      tq[j] = w1 * sq;
+      w1s[j] = w1;
+      stats(m1, v1, w1, tm[j], tv[j], tw[j], tq[j]);
+    }
+    Quad o;
+    o.m = encode4_fp8<kE4M3>(tm[0], tm[1], tm[2], tm[3]);
+    o.v01 = encode2_f16(tv[0], tv[1]);
+    o.v23 = encode2_f16(tv[2], tv[3]);
+    o.w01 = encode2_f16(tw[0], tw[1]);
+    o.w23 = encode2_f16(tw[2], tw[3]);
+    if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
+      o.q = encode4_fp8<kE4M3>(tq[0], tq[1], tq[2], tq[3]);
+      o.q2 = 0;
+    } else {
+      o.q = encode1_bf16(w1s[0]) | (encode1_bf16(w1s[1]) << 16);
+      o.q2 = encode1_bf16(w1s[2]) | (encode1_bf16(w1s[3]) << 16);
+    }
+    return o;
+  }
+
+  // one element with every special case handled (NaN codes, infinities, fp32 overflow)
+  __device__ __forceinline__ void one_careful(long long i) {
+    const float g = fp8_to_f32<GFMT>(p.grad[i]) * inv_sg;
+    const float m0 = fp8_to_f32<kE4M3>(p.m[i]) * inv_sm;
+    const float v0 = f16_to_f32(p.v[i]) * inv_sv;
+    const float w0 = f16_to_f32(p.w[i]) * inv_sw;
+    const float m1 = __builtin_fmaf(p.b1, m0, p.omb1 * g);
+    const float v1 = __builtin_fmaf(p.b2, v0, p.omb2 * (g * g));
+    const float den = __builtin_sqrtf(v1 * p.rbc2) + p.eps;
+    const float upd = ((m1 * p.rbc1) / den);
+    const float w1 = __builtin_fmaf(-p.lr, upd, w0 * p.decay);
+    const float tm = m1 * sm, tv = v1 * sv, tw = w1 * sw, tq = w1 * sq;
+    p.m[i] = (uint8_t)encode1_fp8_careful<kE4M3>(tm);
+    p.v[i] = (uint16_t)encode1_f16_careful(tv);
+    p.w[i] = (uint16_t)encode1_f16_careful(tw);
+    if constexpr (WCOPY == FP8LM_WCOPY_E4M3) static_cast<uint8_t*>(p.wcopy)[i] = (uint8_t)encode1_fp8_careful<kE4M3>(tq);
+    else static_cast<uint16_t*>(p.wcopy)[i] = (uint16_t)encode1_bf16(w1);
+    const float kMaxF = 3.4028234663852886e38f;
+    const float am = fabsf(m1), av = fabsf(v1), aw = fabsf(w1);
+    if (am <= kMaxF) mmax = fmaxf(mmax, am); else nf |= (m1 != m1) ? 1u : 2u;
+    if (av <= kMaxF) vmax = fmaxf(vmax, av); else nf |= (v1 != v1) ? 4u : 8u;
+    if (aw <= kMaxF) wmax = fmaxf(wmax, aw); else nf |= (w1 != w1) ? 16u : 32u;
+    stats(m1, v1, w1, tm, tv, tw, tq);
+  }
+
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    if (valid == kGroup && !careful) {
+      const uint4 g = ld16(p.grad + pos), m = ld16(p.m + pos);
+      const uint4 va = ld16(p.v + pos), vb = ld16(p.v + pos + 8);
+      const uint4 wa = ld16(p.w + pos), wb = ld16(p.w + pos + 8);
+      const Quad q0 = quad(g.x, m.x, va.x, va.y, wa.x, wa.y);
+      const Quad q1 = quad(g.y, m.y, va.z, va.w, wa.z, wa.w);
+      const Quad q2 = quad(g.z, m.z, vb.x, vb.y, wb.x, wb.y);
+      const Quad q3 = quad(g.w, m.w, vb.z, vb.w, wb.z, wb.w);
+      st16(p.m + pos, make_uint4(q0.m, q1.m, q2.m, q3.m));
+      st16(p.v + pos, make_uint4(q0.v01, q0.v23, q1.v01, q1.v23));
+      st16(p.v + pos + 8, make_uint4(q2.v01, q2.v23, q3.v01, q3.v23));
+      st16(p.w + pos, make_uint4(q0.w01, q0.w23, q1.w01, q1.w23));
+      st16(p.w + pos + 8, make_uint4(q2.w01, q2.w23, q3.w01, q3.w23));
+      if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
+        st16(static_cast<uint8_t*>(p.wcopy) + pos, make_uint4(q0.q, q1.q, q2.q, q3.q));
+      } else {
+        uint16_t* q = static_cast<uint16_t*>(p.wcopy);
+        st16(q + pos, make_uint4(q0.q, q0.q2, q1.q, q1.q2));
+        st16(q + pos + 8, make_uint4(q2.q, q2.q2, q3.q, q3.q2));
+      }
+    } else if (!careful) {
+      // ragged tail of a tensor: same arithmetic, element by element
+      for (int j = 0; j < valid; ++j) {
+        const long long i = pos + j;
+        const Quad o = quad(p.grad[i], p.m[i], p.v[i], 0u, p.w[i], 0u);
+        p.m[i] = (uint8_t)o.m;
+        p.v[i] = (uint16_t)o.v01;
+        p.w[i] = (uint16_t)o.w01;
+        if constexpr (WCOPY == FP8LM_WCOPY_E4M3) static_cast<uint8_t*>(p.wcopy)[i] = (uint8_t)o.q;
+        else static_cast<uint16_t*>(p.wcopy)[i] = (uint16_t)o.q;
+      }
+    } else {
+      for (int j = 0; j < valid; ++j) one_careful(pos + j);
+    }
+  }
+
+  __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
+    BlockStats<3, 8> s;
+    s.mx[0] = f2u(vmax);
+    s.mx[1] = f2u(wmax);
+    s.mx[2] = f2u(mmax);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s.ct[i] = cnt[i];
+    s.orv = nf;
+    block_combine(s);
+    if (threadIdx.x == 0) {
+      Scratch* sc = tb.scratch + t;
+      atomic_max_u32(&sc->max_a, s.mx[0]);
+      atomic_max_u32(&sc->max_b, s.mx[1]);
+      atomic_max_u32(&sc->max_c, s.mx[2]);
+      atomic_or_u32(&sc->nf, s.orv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) atomic_add_u64(&sc->cnt[i], s.ct[i]);
+      if (publish_ticket(sc, done, d.n_chunks)) {
+        const float A_v = u2f(take_u32(&sc->max_a));
+        const float A_w = u2f(take_u32(&sc->max_b));
+        const float A_mc = u2f(take_u32(&sc->max_c));
+        const uint32_t nfb = take_u32(&sc->nf);
+        unsigned long long c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c[i] = take_u64(&sc->cnt[i]);
+        take_u32(&sc->ticket);
+        finish(t, A_v, A_w, A_mc, nfb, c);
+      }
+    }
+  }
+
+  // Fills one output meta.  amax_deq is the stored value of the largest element: rounding is monotone,
+  // so quantising the maximum gives the maximum of the quantised values.  An infinity is stored as the
+  // top code of a saturating format, so it pins amax_deq to fmax / scale.
+  template <class Enc, class Dec>
+  __device__ __forceinline__ void fill(fp8lm_meta& M, float scale, float inv, float amax, uint32_t nan_inf_bits,
+                                       uint32_t flags, float fmax, bool saturating, unsigned long long n_sat,
+                                       unsigned long long n_und, Enc enc, Dec dec, uint32_t magmask, uint32_t topcode) {
+    const bool nonfinite = nan_inf_bits != 0;
+    const bool inf_seen = saturating && (nan_inf_bits & 2u) != 0;
+    M.scale = scale;
+    M.inv_scale = inv;
+    M.amax = nonfinite ? __builtin_inff() : amax;
+    const uint32_t code = enc(amax * scale);
+    const float stored = inf_seen ? fmax : dec(code);
+    M.amax_deq = stored * inv;
+    if (nonfinite) flags |= FP8LM_FLAG_NONFINITE;
+    bool sat = inf_seen || (code & magmask) == topcode;
+    if constexpr (STATS) sat = n_sat != 0;
+    if (sat) flags |= FP8LM_FLAG_SATURATED;
+    M.flags = flags;
+    M.n_sat = STATS ? n_sat : 0;
+    M.n_underflow = STATS ? n_und : 0;
+  }
+
+  __device__ void finish(int t, float A_v, float A_w, float A_mc, uint32_t nfb, const unsigned long long* c) {
+    const Scratch::Pending& P = tb.scratch[t].pend;
+    // first moment: on the fast path its amax is the one pass A measured
+    const bool m_bad = (P.fm & FP8LM_FLAG_NONFINITE) != 0;
+    const float A_m = m_bad ? A_mc : P.amax_m;
+    uint32_t m_nf = nfb & 3u;
+    auto enc8 = [](float x) { return encode1_fp8<kE4M3>(x); };
+    auto dec8 = [](uint32_t cc) { return fp8_to_f32<kE4M3>(cc); };
+    auto enc16 = [](float x) { return encode1_f16(x); };
+    auto dec16 = [](uint32_t cc) { return f16_to_f32(cc); };
+    fill(p.m_meta[t], P.sm, P.ism, A_m, m_nf, P.fm, 448.0f, true, c[0], c[4], enc8, dec8, 0x7Fu, 0x7Eu);
+    fill(p.v_meta[t], P.sv, P.isv, A_v, (nfb >> 2) & 3u, P.fv, 65504.0f, true, c[1], c[5], enc16, dec16, 0x7FFFu, 0x7BFFu);
+    fill(p.w_meta[t], P.sw, P.isw, A_w, (nfb >> 4) & 3u, P.fw, 65504.0f, true, c[2], c[6], enc16, dec16, 0x7FFFu, 0x7BFFu);
+    if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
+      fill(p.wcopy_meta[t], P.sq, P.isq, A_w, (nfb >> 4) & 3u, P.fq, 448.0f, true, c[3], c[7], enc8, dec8, 0x7Fu, 0x7Eu);
+    } else {
+      // bf16 is not saturating: an overflow is stored as infinity, which carries no magnitude
+      auto encb = [](float x) { return encode1_bf16(x); };
+      auto decb = [](uint32_t cc) { return u2f(cc << 16); };
+      fill(p.wcopy_meta[t], 1.0f, 1.0f, A_w, (nfb >> 4) & 3u, 0u, 0.0f, false, c[3], c[7], encb, decb, 0x7FFFu, 0x7F80u);
+    }
+  }
+};
+
+template <int GFMT, int WCOPY, bool FAST, bool STATS>
+__global__ __launch_bounds__(kThreads) void adam_update_kernel(Tables tb, AdamParams p) {
+  AdamUpdateOp<GFMT, WCOPY, FAST, STATS> op(p, tb);
+  walk_chunks(tb, op);
+}
+
+// ---- small kernels ---------------------------------------------------------------------------------
+__global__ void meta_init_kernel(fp8lm_meta* meta, int n, int clean0) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n) return;
+  fp8lm_meta M;
+  M.scale = 1.0f; M.inv_scale = 1.0f; M.amax = 0.0f; M.amax_deq = 0.0f;
+  for (int h = 0; h < FP8LM_HIST; ++h) M.amax_hist[h] = 0.0f;
+  M.hist_pos = 0; M.mu_exp = 0; M.clean_steps = clean0; M.flags = 0; M.n_sat = 0; M.n_underflow = 0;
+  meta[t] = M;
+}
+
+__global__ __launch_bounds__(kThreads) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long long n16) {
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+}  // namespace fp8lm
+
+// ====================================================================================================
+// Host side: context, validation, launches
+// ====================================================================================================
+using namespace fp8lm;
+
+static thread_local std::string g_hip_error;
+
+struct fp8lm_ctx {
+  int device = 0;
+  int n_tensors = 0;
+  int num_cus = 0;
+  std::vector<fp8lm_tensor> tensors;
+  int32_t chunk_elems = 16384;
+  int32_t blocks_per_cu = 8;
+  int32_t interleave = 0;
+  int32_t n_chunks = 0;
+  TensorDesc* d_desc = nullptr;
+  int32_t* d_chunk_tensor = nullptr;
+  Scratch* d_scratch = nullptr;
+  // timing
+  bool timing = false;
+  struct Stamp { int kernel; hipEvent_t a, b; };
+  std::vector<Stamp> stamps;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> free_events;
+};
+
+#define HIP_TRY(expr)                                                      \
+  do {                                                                     \
+    hipError_t e_ = (expr);                                                \
+    if (e_ != hipSuccess) {                                                \
+      g_hip_error = std::string(#expr) + ": " + hipGetErrorString(e_);     \
+      return FP8LM_ERR_HIP;                                                \
+    }                                                                      \
+  } while (0)
+
+namespace {
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = true;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+    if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+    if (prev == dev) prev = -1;
+  }
+  ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+fp8lm_status build_tables(fp8lm_ctx* c) {
+  std::vector<TensorDesc> desc(c->n_tensors);
+  std::vector<int32_t> chunk_tensor;
+  long long total_chunks = 0;
+  for (int t = 0; t < c->n_tensors; ++t) {
+    const long long n = c->tensors[t].numel;
+    const long long nc = (n + c->chunk_elems - 1) / c->chunk_elems;
+    if (total_chunks + nc > 0x7FFFFFF0LL) return FP8LM_ERR_TOO_LARGE;
+    desc[t] = TensorDesc{c->tensors[t].offset, n, (int32_t)total_chunks, (int32_t)nc};
+    total_chunks += nc;
+  }
+  chunk_tensor.resize((size_t)total_chunks);
+  for (int t = 0; t < c->n_tensors; ++t)
+    std::fill(chunk_tensor.begin() + desc[t].first_chunk, chunk_tensor.begin() + desc[t].first_chunk + desc[t].n_chunks, t);
+  if (c->d_desc) HIP_TRY(hipFree(c->d_desc));
+  if (c->d_chunk_tensor) HIP_TRY(hipFree(c->d_chunk_tensor));
+  c->d_desc = nullptr;
+  c->d_chunk_tensor = nullptr;
+  c->n_chunks = (int32_t)total_chunks;
+  HIP_TRY(hipMalloc((void**)&c->d_desc, std::max<size_t>(1, desc.size()) * sizeof(TensorDesc)));
+  HIP_TRY(hipMalloc((void**)&c->d_chunk_tensor, std::max<size_t>(1, chunk_tensor.size()) * sizeof(int32_t)));
+  if (!desc.empty()) HIP_TRY(hipMemcpy(c->d_desc, desc.data(), desc.size() * sizeof(TensorDesc), hipMemcpyHostToDevice));
+  if (!chunk_tensor.empty())
+    HIP_TRY(hipMemcpy(c->d_chunk_tensor, chunk_tensor.data(), chunk_tensor.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+  return FP8LM_OK;
+}
+
+Tables tables_of(const fp8lm_ctx* c) {
+  return Tables{c->d_desc, c->d_chunk_tensor, c->d_scratch, c->n_chunks, c->chunk_elems, c->interleave};
+}
+
+int grid_of(const fp8lm_ctx* c) {
+  const long long want = (long long)c->num_cus * c->blocks_per_cu;
+  return (int)std::max<long long>(1, std::min<long long>(want, c->n_chunks));
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Timed {
+  fp8lm_ctx* c;
+  hipStream_t s;
+  int kernel;
+  hipEvent_t a = nullptr, b = nullptr;
+  Timed(fp8lm_ctx* c_, hipStream_t s_, int k) : c(c_), s(s_), kernel(k) {
+    if (!c->timing || c->free_events.empty()) return;
+    a = c->free_events.back().first;
+    b = c->free_events.back().second;
+    c->free_events.pop_back();
+    (void)hipEventRecord(a, s);
+  }
+  ~Timed() {
+    if (!a) return;
+    (void)hipEventRecord(b, s);
+    c->stamps.push_back({kernel, a, b});
+  }
+};
+
+fp8lm_status after_launch() {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    g_hip_error = std::string("kernel launch: ") + hipGetErrorString(e);
+    return FP8LM_ERR_HIP;
+  }
+  return FP8LM_OK;
+}
+
+// Selects the adam_update_kernel instantiation.
+template <int GFMT, int WCOPY>
+void launch_update(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, bool fast, bool stats) {
+  const dim3 g(grid_of(c)), b(kThreads);
+  const Tables tb = tables_of(c);
+  if (fast) {
+    if (stats) hipLaunchKernelGGL((adam_update_kernel<GFMT, WCOPY, true, true>), g, b, 0, s, tb, p);
+    else hipLaunchKernelGGL((adam_update_kernel<GFMT, WCOPY, true, false>), g, b, 0, s, tb, p);
+  } else {
+    if (stats) hipLaunchKernelGGL((adam_update_kernel<GFMT, WCOPY, false, true>), g, b, 0, s, tb, p);
+    else hipLaunchKernelGGL((adam_update_kernel<GFMT, WCOPY, false, false>), g, b, 0, s, tb, p);
+  }
+}
+
+bool cfg_ok(const fp8lm_autoscale_cfg* cfg) {
+  return cfg && cfg->sat_num >= 0 && cfg->sat_den > 0 && cfg->ramp_steps >= 2 && cfg->hist_window >= 1 &&
+         cfg->hist_window <= FP8LM_HIST && cfg->margin >= -64 && cfg->margin <= 64;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fp8lm_status_string(fp8lm_status s) {
+  switch (s) {
+    case FP8LM_OK: return "ok";
+    case FP8LM_ERR_INVALID_ARGUMENT: return "invalid argument";
+    case FP8LM_ERR_MISALIGNED: return "misaligned offset or buffer";
+    case FP8LM_ERR_OVERLAP: return "tensors overlap";
+    case FP8LM_ERR_HIP: return "HIP runtime error";
+    case FP8LM_ERR_TOO_LARGE: return "too many chunks or tensors";
+  }
+  return "unknown status";
+}
+
+const char* fp8lm_last_hip_error(void) { return g_hip_error.c_str(); }
+uint32_t fp8lm_sizeof_meta(void) { return (uint32_t)sizeof(fp8lm_meta); }
+
+fp8lm_status fp8lm_create(fp8lm_ctx** out, const fp8lm_tensor* tensors, int32_t n, int device) {
+  if (!out || n < 0 || (n > 0 && !tensors)) return FP8LM_ERR_INVALID_ARGUMENT;
+  *out = nullptr;
+  for (int t = 0; t < n; ++t) {
+    if (tensors[t].numel < 0 || tensors[t].offset < 0) return FP8LM_ERR_INVALID_ARGUMENT;
+    if (tensors[t].offset % 16 != 0) return FP8LM_ERR_MISALIGNED;
+  }
+  {
+    std::vector<std::pair<long long, long long>> spans;
+    for (int t = 0; t < n; ++t)
+      if (tensors[t].numel > 0) spans.emplace_back(tensors[t].offset, tensors[t].offset + tensors[t].numel);
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+      if (spans[i].first < spans[i - 1].second) return FP8LM_ERR_OVERLAP;
+  }
+  int count = 0;
+  HIP_TRY(hipGetDeviceCount(&count));
+  if (device < 0 || device >= count) return FP8LM_ERR_INVALID_ARGUMENT;
+  DeviceGuard guard(device);
+  if (!guard.ok) { g_hip_error = "hipSetDevice failed"; return FP8LM_ERR_HIP; }
+  hipDeviceProp_t prop;
+  HIP_TRY(hipGetDeviceProperties(&prop, device));
+  fp8lm_ctx* c = new fp8lm_ctx();
+  c->device = device;
+  c->n_tensors = n;
+  c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  c->tensors.assign(tensors, tensors + n);
+  fp8lm_status st = build_tables(c);
+  if (st == FP8LM_OK) {
+    const size_t bytes = std::max<size_t>(1, (size_t)n) * sizeof(Scratch);
+    hipError_t e = hipMalloc((void**)&c->d_scratch, bytes);
+    if (e == hipSuccess) e = hipMemset(c->d_scratch, 0, bytes);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) { g_hip_error = hipGetErrorString(e); st = FP8LM_ERR_HIP; }
+  }
+  if (st != FP8LM_OK) { fp8lm_destroy(c); return st; }
+  *out = c;
+  return FP8LM_OK;
+}
+
+fp8lm_status fp8lm_destroy(fp8lm_ctx* c) {
+  if (!c) return FP8LM_OK;
+  DeviceGuard guard(c->device);
+  if (c->d_desc) (void)hipFree(c->d_desc);
+  if (c->d_chunk_tensor) (void)hipFree(c->d_chunk_tensor);
+  if (c->d_scratch) (void)hipFree(c->d_scratch);
+  for (auto& s : c->stamps) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
+  for (auto& e : c->free_events) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
+  delete c;
+  return FP8LM_OK;
+}
+
+fp8lm_status fp8lm_set_tuning(fp8lm_ctx* c, int32_t chunk_elems, int32_t blocks_per_cu, int32_t interleave) {
+  if (!c || chunk_elems < kTile || chunk_elems > (1 << 20) || chunk_elems % kTile != 0 || blocks_per_cu < 1 ||
+      blocks_per_cu > 16 || (interleave != 0 && interleave != 1))
+    return FP8LM_ERR_INVALID_ARGUMENT;
+  DeviceGuard guard(c->device);
+  HIP_TRY(hipDeviceSynchronize());
+  c->chunk_elems = chunk_elems;
+  c->blocks_per_cu = blocks_per_cu;
+  c->interleave = interleave;
+  return build_tables(c);
+}
+
+fp8lm_status fp8lm_meta_init(fp8lm_ctx* c, fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {
+  if (!c || !cfg_ok(cfg) || (c->n_tensors > 0 && !meta)) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_tensors == 0) return FP8LM_OK;
+  DeviceGuard guard(c->device);
+  const int blocks = (c->n_tensors + 255) / 256;
+  hipLaunchKernelGGL(meta_init_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, meta, c->n_tensors,
+                     cfg->ramp_steps / 2);
+  return after_launch();
+}
+
+fp8lm_status fp8lm_amax_scale(fp8lm_ctx* c, const void* src, fp8lm_src src_type, fp8lm_fmt target, fp8lm_meta* meta,
+                              const fp8lm_autoscale_cfg* cfg, void* stream) {
+  if (!c || !cfg_ok(cfg) || src_type != FP8LM_SRC_BF16 || (target != FP8LM_E4M3 && target != FP8LM_E5M2))
+    return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_chunks == 0) return FP8LM_OK;
+  if (!src || !meta) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!aligned16(src)) return FP8LM_ERR_MISALIGNED;
+  DeviceGuard guard(c->device);
+  AmaxParams p{static_cast<const uint16_t*>(src), meta, target == FP8LM_E4M3 ? kBitsE4M3Max : kBitsE5M2Max,
+               cfg->hist_window, cfg->margin};
+  Timed tm(c, (hipStream_t)stream, FP8LM_K_AMAX);
+  hipLaunchKernelGGL(amax_kernel<kAmaxForGradient>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream,
+                     tables_of(c), p);
+  return after_launch();
+}
+
+fp8lm_status fp8lm_cast_fp8(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
+                            fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {
+  if (!c || !cfg_ok(cfg) || src_type != FP8LM_SRC_BF16 || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2))
+    return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_chunks == 0) return FP8LM_OK;
+  if (!src || !dst || !meta) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!aligned16(src) || !aligned16(dst)) return FP8LM_ERR_MISALIGNED;
+  DeviceGuard guard(c->device);
+  CastParams p{static_cast<const uint16_t*>(src), dst, meta, cfg->sat_num, cfg->sat_den, cfg->ramp_steps};
+  Timed tm(c, (hipStream_t)stream, FP8LM_K_CAST);
+  if (fmt == FP8LM_E4M3)
+    hipLaunchKernelGGL(cast_kernel<kE4M3>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
+  else
+    hipLaunchKernelGGL(cast_kernel<kE5M2>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
+  return after_launch();
+}
+
+fp8lm_status fp8lm_init_master(fp8lm_ctx* c, const void* w_bf16, uint16_t* w_f16, fp8lm_meta* w_meta, void* stream) {
+  if (!c) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_chunks == 0) return FP8LM_OK;
+  if (!w_bf16 || !w_f16 || !w_meta) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!aligned16(w_bf16) || !aligned16(w_f16)) return FP8LM_ERR_MISALIGNED;
+  DeviceGuard guard(c->device);
+  Timed tm(c, (hipStream_t)stream, FP8LM_K_INIT_MASTER);
+  AmaxParams pa{static_cast<const uint16_t*>(w_bf16), w_meta, kBitsF16Max, 1, 0};
+  hipLaunchKernelGGL(amax_kernel<kAmaxForMaster>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream,
+                     tables_of(c), pa);
+  fp8lm_status st = after_launch();
+  if (st != FP8LM_OK) return st;
+  InitParams pi{static_cast<const uint16_t*>(w_bf16), w_f16, w_meta};
+  hipLaunchKernelGGL(init_master_cast_kernel, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), pi);
+  return after_launch();
+}
+
+fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta,
+                                 uint8_t* m, fp8lm_meta* m_meta, uint16_t* v, fp8lm_meta* v_meta, uint16_t* w,
+                                 fp8lm_meta* w_meta, void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp,
+                                 void* stream) {
+  if (!c || !hp || (grad_fmt != FP8LM_E4M3 && grad_fmt != FP8LM_E5M2)) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (hp->wcopy != FP8LM_WCOPY_E4M3 && hp->wcopy != FP8LM_WCOPY_BF16) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!(hp->lr >= 0.0f && hp->lr <= 1024.0f) || !(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) ||
+      !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f) || !(hp->eps >= 0x1p-36f && hp->eps < INFINITY) ||
+      !(hp->weight_decay >= 0.0f && hp->weight_decay <= 1024.0f) || hp->step < 1)
+    return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_chunks == 0) return FP8LM_OK;
+  if (!grad || !grad_meta || !m || !m_meta || !v || !v_meta || !w || !w_meta || !wcopy || !wcopy_meta)
+    return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!aligned16(grad) || !aligned16(m) || !aligned16(v) || !aligned16(w) || !aligned16(wcopy)) return FP8LM_ERR_MISALIGNED;
+  DeviceGuard guard(c->device);
+
+  AdamParams p{};
+  p.grad = grad; p.grad_meta = grad_meta; p.m = m; p.m_meta = m_meta; p.v = v; p.v_meta = v_meta;
+  p.w = w; p.w_meta = w_meta; p.wcopy = wcopy; p.wcopy_meta = wcopy_meta;
+  // scalars derived once on the host, in double, then rounded to fp32
+  p.b1 = hp->beta1;
+  p.b2 = hp->beta2;
+  p.omb1 = (float)(1.0 - (double)p.b1);
+  p.omb2 = (float)(1.0 - (double)p.b2);
+  p.rbc1 = (float)(1.0 / (1.0 - std::pow((double)p.b1, (double)hp->step)));
+  p.rbc2 = (float)(1.0 / (1.0 - std::pow((double)p.b2, (double)hp->step)));
+  p.lr = hp->lr;
+  p.eps = hp->eps;
+  p.decay = (float)(1.0 - (double)hp->lr * (double)hp->weight_decay);
+  p.v_scaled = hp->v_scaled ? 1 : 0;
+
+  const bool stats = hp->stats != 0, fast = hp->exact == 0;
+  hipStream_t s = (hipStream_t)stream;
+  const dim3 g(grid_of(c)), b(kThreads);
+  const Tables tb = tables_of(c);
+  const bool e5 = grad_fmt == FP8LM_E5M2, q8 = hp->wcopy == FP8LM_WCOPY_E4M3;
+  {
+    Timed tm(c, s, FP8LM_K_ADAM_AMAX);
+    if (e5 && q8) hipLaunchKernelGGL((adam_amax_kernel<kE5M2, FP8LM_WCOPY_E4M3>), g, b, 0, s, tb, p);
+    else if (e5) hipLaunchKernelGGL((adam_amax_kernel<kE5M2, FP8LM_WCOPY_BF16>), g, b, 0, s, tb, p);
+    else if (q8) hipLaunchKernelGGL((adam_amax_kernel<kE4M3, FP8LM_WCOPY_E4M3>), g, b, 0, s, tb, p);
+    else hipLaunchKernelGGL((adam_amax_kernel<kE4M3, FP8LM_WCOPY_BF16>), g, b, 0, s, tb, p);
+  }
+  fp8lm_status st = after_launch();
+  if (st != FP8LM_OK) return st;
+  {
+    Timed tm(c, s, FP8LM_K_ADAM_UPDATE);
+    if (e5 && q8) launch_update<kE5M2, FP8LM_WCOPY_E4M3>(c, s, p, fast, stats);
+    else if (e5) launch_update<kE5M2, FP8LM_WCOPY_BF16>(c, s, p, fast, stats);
+    else if (q8) launch_update<kE4M3, FP8LM_WCOPY_E4M3>(c, s, p, fast, stats);
+    else launch_update<kE4M3, FP8LM_WCOPY_BF16>(c, s, p, fast, stats);
+  }
+  return after_launch();
+}
+
+fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* c, const void* src, void* dst, int64_t bytes, void* stream) {
+  if (!c || !src || !dst || bytes < 0 || bytes % 16 != 0) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!aligned16(src) || !aligned16(dst)) return FP8LM_ERR_MISALIGNED;
+  if (bytes == 0) return FP8LM_OK;
+  DeviceGuard guard(c->device);
+  const long long n16 = bytes / 16;
+  const long long want = (long long)c->num_cus * c->blocks_per_cu;
+  const int grid = (int)std::max<long long>(1, std::min<long long>(want, (n16 + kThreads - 1) / kThreads));
+  Timed tm(c, (hipStream_t)stream, FP8LM_K_COPY);
+  hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, static_cast<const uint4*>(src),
+                     static_cast<uint4*>(dst), n16);
+  return after_launch();
+}
+
+fp8lm_status fp8lm_set_timing(fp8lm_ctx* c, int32_t enable) {
+  if (!c) return FP8LM_ERR_INVALID_ARGUMENT;
+  DeviceGuard guard(c->device);
+  if (enable && c->free_events.empty() && c->stamps.empty()) {
+    for (int i = 0; i < 4096; ++i) {
+      hipEvent_t a, b;
+      HIP_TRY(hipEventCreate(&a));
+      HIP_TRY(hipEventCreate(&b));
+      c->free_events.emplace_back(a, b);
+    }
+  }
+  c->timing = enable != 0;
+  return FP8LM_OK;
+}
+
+fp8lm_status fp8lm_get_timing(fp8lm_ctx* c, int32_t* launches, double* total_ms) {
+  if (!c || !launches || !total_ms) return FP8LM_ERR_INVALID_ARGUMENT;
+  DeviceGuard guard(c->device);
+  for (int k = 0; k < FP8LM_K_COUNT; ++k) { launches[k] = 0; total_ms[k] = 0.0; }
+  for (auto& s : c->stamps) {
+    HIP_TRY(hipEventSynchronize(s.b));
+    float ms = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&ms, s.a, s.b));
+    launches[s.kernel] += 1;
+    total_ms[s.kernel] += ms;
+    c->free_events.emplace_back(s.a, s.b);
+  }
+  c->stamps.clear();
+  return FP8LM_OK;
+}
+
+}  // extern "C"

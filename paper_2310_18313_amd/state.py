@@ -1,0 +1,54 @@
+"""Flat device buffers of one model's optimizer state and the three calls of one training step.
+
+Memory per parameter (Sec. 2.2, Eq. 8 of the paper): FP8 gradient 1 B, FP8 first moment 1 B, FP16
+second moment 2 B, FP16 master weight 2 B -- 6 B -- plus the 1 B (E4M3) or 2 B (bf16) weight copy
+handed back to the model.  The bf16 gradient source belongs to the caller.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class OptimizerState:
+    def __init__(self, tensors, total_elems: int, cfg: B.AutoscaleCfg, device: int = 0,
+                 grad_fmt: int = B.E5M2, wcopy: int = B.WCOPY_E4M3):
+        dev = torch.device(f"cuda:{device}")
+        self.tensors = list(tensors)
+        self.total = int(total_elems)
+        self.cfg = cfg
+        self.grad_fmt = grad_fmt
+        self.wcopy_kind = wcopy
+        self.ctx = B.Context(self.tensors, device)
+        n = max(self.total, 16)
+        self.g8 = torch.zeros(n, dtype=torch.uint8, device=dev)
+        self.m = torch.zeros(n, dtype=torch.uint8, device=dev)       # E4M3 code 0 = +0
+        self.v = torch.zeros(n, dtype=torch.float16, device=dev)
+        self.w = torch.zeros(n, dtype=torch.float16, device=dev)
+        self.wq = torch.zeros(n, dtype=torch.uint8 if wcopy == B.WCOPY_E4M3 else torch.bfloat16, device=dev)
+        self.g_meta = self.ctx.new_meta(cfg)
+        self.m_meta = self.ctx.new_meta(cfg)
+        self.v_meta = self.ctx.new_meta(cfg)
+        self.w_meta = self.ctx.new_meta(cfg)
+        self.q_meta = self.ctx.new_meta(cfg)
+
+    @property
+    def state_bytes_per_param(self) -> int:
+        return self.g8.element_size() + self.m.element_size() + self.v.element_size() + self.w.element_size()
+
+    def init_master(self, w_bf16: torch.Tensor) -> None:
+        self.ctx.init_master(w_bf16, self.w, self.w_meta)
+
+    def quantize_grad(self, grad_bf16: torch.Tensor) -> None:
+        self.ctx.amax_scale(grad_bf16, self.grad_fmt, self.g_meta, self.cfg)
+        self.ctx.cast_fp8(grad_bf16, self.g8, self.grad_fmt, self.g_meta, self.cfg)
+
+    def adam(self, hp: B.AdamHparams) -> None:
+        self.ctx.adam_step_fp8(self.g8, self.grad_fmt, self.g_meta, self.m, self.m_meta, self.v, self.v_meta,
+                               self.w, self.w_meta, self.wq, self.q_meta, hp)
+
+    def step(self, grad_bf16: torch.Tensor, hp: B.AdamHparams) -> None:
+        """One pass of the whole hot path: amax + scale, FP8 cast, FP8 Adam."""
+        self.quantize_grad(grad_bf16)
+        self.adam(hp)

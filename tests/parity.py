@@ -1,0 +1,200 @@
+"""Lock-step comparison of the HIP path with the CPU oracle (helpers for the GPU tests).
+
+Before a step the inputs of the sampled tensors are copied from the GPU to the host; the GPU step
+runs through the C ABI; the oracle runs the same step on the host copies; the outputs are compared
+element by element.  Bars: FP8 gradient codes, amax, scales, counters and auto-scaling state are
+bit-exact; the second moment is bit-exact; the first moment may differ by one E4M3 code on at most
+1e-4 of the elements (it is bit-exact in practice); master weights within one FP16 ulp and the FP8
+weight copy within one code on at most 1e-4 of the elements when the hardware sqrt/reciprocal are
+used, bit-exact with correctly rounded sqrt and divide.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle as O
+from paper_2310_18313_amd import binding as B
+from paper_2310_18313_amd import synth
+
+ALIGN = 16
+
+
+def _host_bits(t: torch.Tensor, off: int, n: int) -> np.ndarray:
+    sl = t[off:off + n]
+    if sl.element_size() == 1:
+        return sl.view(torch.uint8).cpu().numpy().copy()
+    return sl.view(torch.int16).cpu().numpy().view(np.uint16).copy()
+
+
+def _pad(a: np.ndarray) -> np.ndarray:
+    n = max(ALIGN, (a.size + ALIGN - 1) // ALIGN * ALIGN)
+    out = np.zeros(n, dtype=a.dtype)
+    out[:a.size] = a
+    return out
+
+
+def ordered16(bits: np.ndarray) -> np.ndarray:
+    """Sign-magnitude 16-bit float patterns -> integers ordered like the values."""
+    mag = (bits & 0x7FFF).astype(np.int32)
+    return np.where(bits & 0x8000, -mag, mag)
+
+
+def ordered8(bits: np.ndarray) -> np.ndarray:
+    mag = (bits & 0x7F).astype(np.int32)
+    return np.where(bits & 0x80, -mag, mag)
+
+
+def oracle_cfg(cfg: B.AutoscaleCfg) -> O.AutoscaleCfg:
+    return O.AutoscaleCfg(cfg.sat_num, cfg.sat_den, cfg.ramp_steps, cfg.hist_window, cfg.margin)
+
+
+def oracle_hp(hp: B.AdamHparams) -> O.AdamHparams:
+    return O.AdamHparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.step, hp.v_scaled, hp.wcopy)
+
+
+class Snapshot:
+    """Host copy of everything one tensor's step reads."""
+
+    def __init__(self, st, grad_bf16: torch.Tensor, t: int):
+        off, n = st.tensors[t]
+        self.t, self.off, self.n = t, off, n
+        self.src = _pad(_host_bits(grad_bf16, off, n))
+        self.m = _pad(_host_bits(st.m, off, n))
+        self.v = _pad(_host_bits(st.v, off, n))
+        self.w = _pad(_host_bits(st.w, off, n))
+        self.metas = {k: B.meta_to_numpy(getattr(st, k), len(st.tensors))[t:t + 1].copy()
+                      for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta")}
+
+
+def meta_equal(a, b, fields):
+    return [f for f in fields if not np.array_equal(a[f], b[f], equal_nan=True)]
+
+
+ALL_FIELDS = ["scale", "inv_scale", "amax", "amax_deq", "amax_hist", "hist_pos", "mu_exp", "clean_steps",
+              "flags", "n_sat", "n_underflow"]
+
+
+def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool = False) -> dict:
+    """Runs the oracle on the snapshots and compares with the GPU state after the step."""
+    cfg = oracle_cfg(st.cfg)
+    ohp = oracle_hp(hp) if hp is not None else None
+    n_tensors = len(st.tensors)
+    post_meta = {k: B.meta_to_numpy(getattr(st, k), n_tensors)
+                 for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta")}
+    out = dict(elements=0, m_diff=0, w_diff=0, q_diff=0, w_amax_ulp=0)
+    for s in snaps:
+        tag = f"{what} tensor {s.t} (n={s.n})"
+        tens = O.tensors_array([(0, s.n)])
+        g_meta = s.metas["g_meta"].copy()
+        g8 = np.zeros(s.src.size, dtype=np.uint8)
+        O.amax_scale(s.src, tens, st.grad_fmt, g_meta, cfg)
+        O.cast_fp8(s.src, tens, g8, st.grad_fmt, g_meta, cfg)
+        gpu_g8 = _host_bits(st.g8, s.off, s.n)
+        assert np.array_equal(gpu_g8, g8[:s.n]), f"{tag}: FP8 gradient codes differ"
+        if s.n:
+            bad = meta_equal(post_meta["g_meta"][s.t], g_meta[0], ALL_FIELDS)
+            assert not bad, f"{tag}: gradient meta differs in {bad}: gpu {post_meta['g_meta'][s.t]} oracle {g_meta[0]}"
+        out["elements"] += s.n
+        if quantize_only:
+            continue
+        m, v, w = s.m.copy(), s.v.copy(), s.w.copy()
+        wq = np.zeros(s.src.size, dtype=np.uint8 if hp.wcopy == B.WCOPY_E4M3 else np.uint16)
+        mm, vm, wm, qm = (s.metas[k].copy() for k in ("m_meta", "v_meta", "w_meta", "q_meta"))
+        O.adam_step_fp8(tens, g8, st.grad_fmt, g_meta, m, mm, v, vm, w, wm, wq, qm, ohp)
+        gm, gv, gw, gq = (_host_bits(getattr(st, k), s.off, s.n) for k in ("m", "v", "w", "wq"))
+        n = max(s.n, 1)
+        # second moment: multiply/fma only -> bit-exact
+        assert np.array_equal(gv, v[:s.n]), f"{tag}: second moment differs"
+        # first moment: bit-exact expected; bar is one code on <= 1e-4 of the elements
+        dm = np.abs(ordered8(gm) - ordered8(m[:s.n]))
+        nan_m = (m[:s.n] & 0x7F) == 0x7F
+        assert np.array_equal(gm[nan_m], m[:s.n][nan_m]), f"{tag}: NaN codes of m differ"
+        assert dm[~nan_m].max(initial=0) <= 1 and np.count_nonzero(dm) <= 1e-4 * n, f"{tag}: first moment differs"
+        out["m_diff"] += int(np.count_nonzero(dm))
+        # master weights
+        nan_w = (w[:s.n] & 0x7FFF) > 0x7C00
+        assert np.array_equal(gw[nan_w], w[:s.n][nan_w]), f"{tag}: NaN codes of w differ"
+        dw = np.abs(ordered16(gw) - ordered16(w[:s.n]))[~nan_w]
+        if hp.exact:
+            assert dw.max(initial=0) == 0, f"{tag}: master weights differ with exact sqrt/divide"
+        else:
+            # hardware sqrt/reciprocal: the update term carries a few fp32 ulps of error, so the new
+            # weight is within one FP16 ulp at the magnitude of the larger of old weight and update
+            # (payload units: the old payload, or lr * scale when the update dominates)
+            old = np.abs(s.w[:s.n].view(np.float16).astype(np.float64))[~nan_w]
+            new = np.abs(w[:s.n].view(np.float16).astype(np.float64))[~nan_w]
+            big = np.maximum(np.maximum(old, new), float(hp.lr) * float(wm[0]["scale"]) * 16)
+            err = np.abs(gw.view(np.float16).astype(np.float64) - w[:s.n].view(np.float16).astype(np.float64))[~nan_w]
+            assert np.all(err <= np.maximum(big * 2.0 ** -10, 2.0 ** -24)), f"{tag}: master weight off by more than one FP16 ulp of its operands"
+            assert np.count_nonzero(dw > 1) <= 1e-3 * n, f"{tag}: too many master weights off by more than one ulp"
+        out["w_diff"] += int(np.count_nonzero(dw))
+        # weight copy
+        if hp.wcopy == B.WCOPY_E4M3:
+            nan_q = (wq[:s.n] & 0x7F) == 0x7F
+            dq = np.abs(ordered8(gq) - ordered8(wq[:s.n]))[~nan_q]
+        else:
+            nan_q = (wq[:s.n] & 0x7FFF) > 0x7F80
+            dq = np.abs(ordered16(gq) - ordered16(wq[:s.n]))[~nan_q]
+        assert np.array_equal(gq[nan_q], wq[:s.n][nan_q]), f"{tag}: NaN codes of the weight copy differ"
+        if hp.exact:
+            assert dq.max(initial=0) == 0, f"{tag}: weight copy differs with exact sqrt/divide"
+        else:
+            assert np.count_nonzero(dq > 1) <= 1e-4 * n and np.count_nonzero(dq) <= max(1e-3 * n, 2), \
+                f"{tag}: weight copy differs ({np.count_nonzero(dq)} of {s.n})"
+        out["q_diff"] += int(np.count_nonzero(dq))
+        if s.n == 0:
+            continue
+        # metadata
+        stat_fields = ["n_sat", "n_underflow"] if hp.stats else []
+        exact_fields = ["scale", "inv_scale", "amax", "amax_deq", "flags"] + stat_fields
+        for key, ref in (("m_meta", mm), ("v_meta", vm)):
+            bad = meta_equal(post_meta[key][s.t], ref[0], exact_fields)
+            assert not bad, f"{tag}: {key} differs in {bad}: gpu {post_meta[key][s.t]} oracle {ref[0]}"
+        for key, ref in (("w_meta", wm), ("q_meta", qm)):
+            fields = exact_fields if hp.exact else ["scale", "inv_scale"]
+            bad = meta_equal(post_meta[key][s.t], ref[0], fields)
+            assert not bad, f"{tag}: {key} differs in {bad}: gpu {post_meta[key][s.t]} oracle {ref[0]}"
+            if not hp.exact:
+                a, b = post_meta[key][s.t]["amax"], ref[0]["amax"]
+                if np.isfinite(b):
+                    ulps = abs(int(np.float32(a).view(np.int32)) - int(np.float32(b).view(np.int32)))
+                    assert ulps <= 8, f"{tag}: {key}.amax {a} vs {b}"
+                    out["w_amax_ulp"] = max(out["w_amax_ulp"], ulps)
+                    da, db = post_meta[key][s.t]["amax_deq"], ref[0]["amax_deq"]
+                    assert abs(float(da) - float(db)) <= 2.0 ** -3 * abs(float(db)) * (1 if key == "q_meta" else 2.0 ** -7) + 1e-45, \
+                        f"{tag}: {key}.amax_deq {da} vs {db}"
+                else:
+                    assert not np.isfinite(a)
+                if hp.stats:
+                    # counters may move by the few elements whose rounding moved
+                    for f in stat_fields:
+                        assert abs(int(post_meta[key][s.t][f]) - int(ref[0][f])) <= max(2, int(1e-4 * n)), f"{tag}: {key}.{f}"
+    return out
+
+
+def make_state(wl: synth.Workload, seed: int, grad_fmt=B.E5M2, wcopy=B.WCOPY_E4M3, hist_window=None,
+               ramp_steps=None, device=0):
+    """State on the GPU with master weights initialised from the seeded bf16 weights."""
+    from paper_2310_18313_amd.state import OptimizerState
+    cfg = B.autoscale_cfg(ramp_steps=ramp_steps or wl.ramp_steps, hist_window=hist_window or wl.hist_window)
+    st = OptimizerState(wl.layout.tensors(), wl.layout.total, cfg, device, grad_fmt, wcopy)
+    w0 = torch.zeros(max(wl.layout.total, 16), dtype=torch.bfloat16, device=f"cuda:{device}")
+    synth.fill_weights(w0, wl.layout, seed)
+    st.init_master(w0)
+    return st, w0
+
+
+def check_init_master(st, w0: torch.Tensor, ids) -> None:
+    n_tensors = len(st.tensors)
+    gpu_meta = B.meta_to_numpy(st.w_meta, n_tensors)
+    for t in ids:
+        off, n = st.tensors[t]
+        src = _pad(_host_bits(w0, off, n))
+        ref = np.zeros(src.size, dtype=np.uint16)
+        meta = O.new_meta(1, oracle_cfg(st.cfg))
+        O.init_master(src, O.tensors_array([(0, n)]), ref, meta)
+        assert np.array_equal(_host_bits(st.w, off, n), ref[:n]), f"init_master: tensor {t} payload differs"
+        if n:
+            bad = meta_equal(gpu_meta[t], meta[0], ALL_FIELDS)
+            assert not bad, f"init_master: tensor {t} meta differs in {bad}: {gpu_meta[t]} vs {meta[0]}"

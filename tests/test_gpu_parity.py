@@ -1,0 +1,260 @@
+"""GPU parity tests: the HIP path behind the C ABI against the CPU oracle, element by element."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import parity as P
+from paper_2310_18313_amd import binding as B
+from paper_2310_18313_amd import synth
+from paper_2310_18313_amd.state import OptimizerState
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def bf16_tensor_from_bits(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(bits.view(np.int16).copy()).to(DEV).view(torch.bfloat16)
+
+
+# ---- hardware convert semantics: every bf16 pattern times many power-of-two scales --------------------
+@pytest.mark.parametrize("fmt", [B.E5M2, B.E4M3])
+def test_cast_every_bf16_pattern_under_many_scales(fmt):
+    pats = np.arange(65536, dtype=np.uint16)
+    finite = pats[(pats & 0x7F80) != 0x7F80]                  # 65280 patterns, no inf/NaN: fast path
+    exps = list(range(-126, 127, 6)) + [-20, -17, -16, -15, -10, -9, -8, -1, 0, 1, 7, 8, 15, 16]
+    n_fast = len(exps)
+    numels = [finite.size] * n_fast + [pats.size] * 3          # three tensors with inf/NaN: careful path
+    lay = synth.Layout([f"t{i}" for i in range(len(numels))], numels)
+    src = np.zeros(lay.total, dtype=np.uint16)
+    for i, (off, n) in enumerate(lay.tensors()):
+        src[off:off + n] = finite if i < n_fast else pats
+    cfg = B.autoscale_cfg()
+    ctx = B.Context(lay.tensors())
+    meta = B.meta_to_numpy(ctx.new_meta(cfg), lay.n_tensors)
+    scales = exps + [0, -12, 9]
+    for i, e in enumerate(scales):
+        meta["scale"][i] = 2.0 ** e
+        meta["inv_scale"][i] = 2.0 ** -e
+        if i >= n_fast:
+            meta["flags"][i] = B.FLAG_NONFINITE              # as the amax pass would have left it
+    ref_meta = meta.copy()
+    d_meta = B.meta_from_numpy(meta, DEV)
+    d_src = bf16_tensor_from_bits(src)
+    d_dst = torch.zeros(lay.total, dtype=torch.uint8, device=DEV)
+    say(f"cast sweep fmt={fmt} tensors={lay.n_tensors}")
+    ctx.cast_fp8(d_src, d_dst, fmt, d_meta, cfg)
+    torch.cuda.synchronize()
+    ref = np.zeros(lay.total, dtype=np.uint8)
+    O.cast_fp8(src, O.tensors_array(lay.tensors()), ref, fmt, ref_meta, P.oracle_cfg(cfg))
+    got = d_dst.cpu().numpy()
+    bad = np.flatnonzero(got != ref)
+    assert bad.size == 0, f"{bad.size} codes differ, first at {bad[:5]}: gpu {got[bad[:5]]} oracle {ref[bad[:5]]} src {src[bad[:5]]}"
+    got_meta = B.meta_to_numpy(d_meta, lay.n_tensors)
+    for t in range(lay.n_tensors):
+        diff = P.meta_equal(got_meta[t], ref_meta[t], P.ALL_FIELDS)
+        assert not diff, (t, diff, got_meta[t], ref_meta[t])
+
+
+@pytest.mark.parametrize("gfmt", [B.E5M2, B.E4M3])
+@pytest.mark.parametrize("finite_only", [True, False])
+def test_fp8_decode_of_every_code_matches_the_oracle_through_adam(gfmt, finite_only):
+    """Every gradient code x every moment code goes through the Adam kernels (all 256 x 256 codes on the
+    careful path, the finite ones on the fast path); the results must equal the oracle's, which pins
+    the hardware decoders."""
+    g_codes = np.repeat(np.arange(256, dtype=np.uint8), 256)
+    m_codes = np.tile(np.arange(256, dtype=np.uint8), 256)
+    if finite_only:
+        g_fin = np.isfinite(O.decode_table(gfmt))[g_codes]
+        m_fin = np.isfinite(O.decode_table(O.E4M3))[m_codes]
+        g_codes, m_codes = g_codes[g_fin & m_fin], m_codes[g_fin & m_fin]
+    n = g_codes.size
+    lay = synth.flat_layout(n)
+    cfg = B.autoscale_cfg()
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, gfmt, B.WCOPY_E4M3)
+    st.g8[:n] = torch.from_numpy(g_codes).to(DEV)
+    st.m[:n] = torch.from_numpy(m_codes).to(DEV)
+    gm = B.meta_to_numpy(st.g_meta, 1)
+    gm["scale"][0], gm["inv_scale"][0], gm["amax_deq"][0] = 4.0, 0.25, (57344.0 if gfmt == B.E5M2 else 448.0) / 4
+    st.g_meta = B.meta_from_numpy(gm, DEV)
+    hp = B.adam_hparams(1e-3, 3, stats=1, exact=1)
+    pad = lay.total
+    pre_m = np.zeros(pad, np.uint8)
+    pre_m[:n] = m_codes
+    g_pad = np.zeros(pad, np.uint8)
+    g_pad[:n] = g_codes
+    pre_v, pre_w, wq = np.zeros(pad, np.uint16), np.zeros(pad, np.uint16), np.zeros(pad, np.uint8)
+    metas = {k: B.meta_to_numpy(getattr(st, k), 1) for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta")}
+    say(f"decode sweep gfmt={gfmt} finite_only={finite_only} n={n}")
+    st.adam(hp)
+    torch.cuda.synchronize()
+    O.adam_step_fp8(O.tensors_array(lay.tensors()), g_pad, gfmt, metas["g_meta"], pre_m, metas["m_meta"],
+                    pre_v, metas["v_meta"], pre_w, metas["w_meta"], wq, metas["q_meta"], P.oracle_hp(hp))
+    assert np.array_equal(st.m[:n].cpu().numpy(), pre_m[:n])
+    assert np.array_equal(synth.bits16(st.v[:n]), pre_v[:n])
+    assert np.array_equal(synth.bits16(st.w[:n]), pre_w[:n])
+    assert np.array_equal(st.wq[:n].cpu().numpy(), wq[:n])
+    for k in ("m_meta", "v_meta", "w_meta", "q_meta"):
+        got = B.meta_to_numpy(getattr(st, k), 1)[0]
+        diff = P.meta_equal(got, metas[k][0], ["scale", "inv_scale", "amax", "amax_deq", "flags", "n_sat", "n_underflow"])
+        assert not diff, (k, diff, got, metas[k][0])
+
+
+# ---- whole-path lock-step parity ------------------------------------------------------------------------
+def run_lockstep(wl, seed, steps, ids=None, grad_fmt=B.E5M2, wcopy=B.WCOPY_E4M3, v_scaled=1, stats=0, exact=1,
+                 check_steps=None, tuning=None, lr=None):
+    st, w0 = P.make_state(wl, seed, grad_fmt, wcopy)
+    if tuning:
+        st.ctx.set_tuning(*tuning)
+    ids = list(range(wl.layout.n_tensors)) if ids is None else ids
+    P.check_init_master(st, w0, ids)
+    del w0
+    grad = torch.zeros(max(wl.layout.total, 16), dtype=torch.bfloat16, device=DEV)
+    tot = dict(elements=0, m_diff=0, w_diff=0, q_diff=0, w_amax_ulp=0)
+    for step in range(1, steps + 1):
+        synth.fill_gradients(grad, wl, seed, step)
+        hp = B.adam_hparams(lr or wl.lr, step, v_scaled=v_scaled, wcopy=wcopy, stats=stats, exact=exact)
+        checked = check_steps is None or step in check_steps
+        snaps = [P.Snapshot(st, grad, t) for t in ids] if checked else []
+        say(f"{wl.name} seed={seed} step={step} fmt={grad_fmt} wcopy={wcopy} v_scaled={v_scaled} stats={stats} exact={exact} checked={checked}")
+        st.step(grad, hp)
+        torch.cuda.synchronize()
+        if checked:
+            r = P.check_step(st, snaps, hp, what=f"{wl.name} step {step}")
+            for k in tot:
+                tot[k] = max(tot[k], r[k]) if k == "w_amax_ulp" else tot[k] + r[k]
+    say(f"  -> {tot}")
+    return st, tot
+
+
+@pytest.mark.parametrize("grad_fmt", [B.E5M2, B.E4M3])
+@pytest.mark.parametrize("wcopy", [B.WCOPY_E4M3, B.WCOPY_BF16])
+@pytest.mark.parametrize("exact", [0, 1])
+def test_ragged_tensors_every_variant(grad_fmt, wcopy, exact):
+    wl = synth.workload("tiny")
+    for v_scaled, stats in ((1, 1), (0, 0)):
+        _, tot = run_lockstep(wl, seed=3, steps=3, grad_fmt=grad_fmt, wcopy=wcopy, v_scaled=v_scaled, stats=stats, exact=exact)
+        assert tot["m_diff"] == 0
+        if exact:
+            assert tot["w_diff"] == 0 and tot["q_diff"] == 0
+
+
+def test_config1_flat_1m():
+    wl = synth.workload("flat1m")
+    for exact in (1, 0):
+        _, tot = run_lockstep(wl, seed=0, steps=1, exact=exact, stats=1)
+        assert tot["m_diff"] == 0
+        assert tot["w_diff"] <= 0.01 * tot["elements"]
+
+
+def test_config2_gpt125m_ten_steps():
+    wl = synth.workload("gpt125m")
+    _, tot = run_lockstep(wl, seed=1, steps=10, check_steps={1, 2, 5, 10})
+    assert tot["m_diff"] == 0
+    assert tot["w_diff"] <= 0.01 * tot["elements"]
+
+
+@pytest.mark.parametrize("tuning", [(4096, 1, 0), (4096, 16, 1), (65536, 4, 1), (1048576, 2, 0)])
+def test_launch_shapes_give_identical_results(tuning):
+    wl = synth.workload("tiny")
+    run_lockstep(wl, seed=5, steps=2, exact=1, stats=1, tuning=tuning)
+    wl2 = synth.Workload("mid", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-3, sigma=None)
+    run_lockstep(wl2, seed=5, steps=2, exact=1, tuning=tuning)
+
+
+# ---- special values and degenerate tensors ------------------------------------------------------------
+def test_nonfinite_zero_and_extreme_gradients():
+    lay = synth.Layout(["nan", "inf", "zero", "huge", "tiny", "ok", "one"], [5000, 4099, 777, 20000, 20000, 33333, 1])
+    wl = synth.Workload("special", lay, lr=1e-3, sigma=1e-3)
+    st, w0 = P.make_state(wl, 4)
+    rng = np.random.default_rng(0)
+    ids = list(range(lay.n_tensors))
+    for step in range(1, 4):
+        bits = np.zeros(lay.total, dtype=np.uint16)
+        for i, (off, n) in enumerate(lay.tensors()):
+            x = rng.standard_normal(n).astype(np.float32) * 1e-3
+            if lay.names[i] == "huge":
+                x *= 1e35 if step != 2 else 1e20
+            if lay.names[i] == "tiny":
+                x *= 1e-34
+            b = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+            if lay.names[i] == "zero":
+                b[:] = 0
+                b[5] = 0x8000
+            if lay.names[i] == "nan" and step == 1:
+                b[17] = 0x7FC0
+                b[4000] = 0xFFFF
+            if lay.names[i] == "inf" and step <= 2:
+                b[0] = 0x7F80
+                b[4098] = 0xFF80
+            bits[off:off + n] = b
+        grad = bf16_tensor_from_bits(bits)
+        hp = B.adam_hparams(1e-3, step, stats=1, exact=1)
+        snaps = [P.Snapshot(st, grad, t) for t in ids]
+        say(f"special step {step}")
+        st.step(grad, hp)
+        torch.cuda.synchronize()
+        P.check_step(st, snaps, hp, what=f"special step {step}")
+    gm = B.meta_to_numpy(st.g_meta, lay.n_tensors)
+    assert gm["flags"][2] & B.FLAG_AMAX_ZERO
+    mm = B.meta_to_numpy(st.m_meta, lay.n_tensors)
+    assert mm["flags"][0] & B.FLAG_NONFINITE          # the NaN of step 1 lives on in the moment
+
+
+def test_empty_layouts_and_empty_tensors():
+    cfg = B.autoscale_cfg()
+    ctx = B.Context([])
+    z = torch.zeros(16, dtype=torch.bfloat16, device=DEV)
+    meta = ctx.new_meta(cfg)
+    ctx.amax_scale(z, B.E5M2, meta, cfg)
+    ctx.cast_fp8(z, torch.zeros(16, dtype=torch.uint8, device=DEV), B.E5M2, meta, cfg)
+    ctx2 = B.Context([(0, 0), (16, 0)])
+    meta2 = ctx2.new_meta(cfg)
+    before = meta2.clone()
+    ctx2.amax_scale(z, B.E5M2, meta2, cfg)
+    torch.cuda.synchronize()
+    assert torch.equal(before, meta2)
+
+
+def test_argument_errors_are_reported_not_launched():
+    lay = synth.flat_layout(1024)
+    cfg = B.autoscale_cfg()
+    st = OptimizerState(lay.tensors(), lay.total, cfg)
+    grad = torch.zeros(lay.total + 16, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(B.Fp8lmError) as e:
+        st.ctx.amax_scale(grad[1:], B.E5M2, st.g_meta, cfg)          # 2-byte offset: misaligned
+    assert e.value.status == -2
+    for bad in (dict(eps=0.0), dict(beta1=1.0), dict(lr=-1.0), dict(step=0), dict(weight_decay=float("nan"))):
+        kw = dict(lr=1e-3, step=1)
+        kw.update(bad)
+        with pytest.raises(B.Fp8lmError) as e:
+            st.adam(B.adam_hparams(**kw))
+        assert e.value.status == -1
+    with pytest.raises(B.Fp8lmError):
+        st.ctx.set_tuning(1000, 8, 0)
+    bad_cfg = B.autoscale_cfg(hist_window=17)
+    with pytest.raises(B.Fp8lmError):
+        st.ctx.amax_scale(grad, B.E5M2, st.g_meta, bad_cfg)
+
+
+# ---- auto-scaling over many steps with heavy tails ----------------------------------------------------
+def test_heavy_tailed_gradients_drive_the_mu_state_machine():
+    """A scaled-down transformer layer with Student-t gradients and rare huge outliers, short ramp:
+    overflow -> mu = 1/2 -> ramp -> saturation at mu = 2, metadata bit-exact along the way."""
+    wl = synth.Workload("layer_small", synth.gpt_layout(384, 1, 1536, 0), lr=3e-5, grad_kind="student_t",
+                        sigma=1e-4, steps=60, ramp_steps=20)
+    st, tot = run_lockstep(wl, seed=7, steps=60, check_steps={1, 2, 3, 10, 11, 20, 21, 22, 23, 24, 40, 59, 60})
+    gm = B.meta_to_numpy(st.g_meta, wl.layout.n_tensors)
+    assert tot["m_diff"] == 0
+    assert set(np.unique(gm["mu_exp"])) <= {-1, 0, 1}
+
+
+def test_amax_history_window_carries_across_steps():
+    wl = synth.Workload("hist", synth.gpt_layout(128, 2, 512, 500), lr=3e-4, sigma=None, hist_window=4)
+    run_lockstep(wl, seed=9, steps=6)
