@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the FP8 gradient cast + FP8 Adam step on one MI355X.
+
+A "step" is one pass of the whole hot path over one model's flat tensors, all inputs resident in HBM:
+    fp8lm_amax_scale  (read 2 B/param)
+    fp8lm_cast_fp8    (read 2, write 1)
+    fp8lm_adam_step_fp8: amax pass (read 2) + update pass (read 6, write 6)
+= 19 algorithmic bytes per parameter.  Prints one JSON line: parameters updated per second, the
+achieved HBM bandwidth of the dominant kernel (the Adam update pass, 12 B/param) against the 8 TB/s
+peak, and the CPU oracle timed on the host cores for a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BYTES_PER_PARAM = {"amax": 2, "cast": 3, "adam_amax": 2, "adam_update": 12}
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(wl, seed: int, budget_s: float = 20.0) -> dict:
+    """The CPU oracle, as it stands, on a prefix of the workload sized for about `budget_s` seconds."""
+    import numpy as np
+    import torch
+    import oracle as O
+    from paper_2310_18313_amd import synth
+
+    cores = max(1, min(os.cpu_count() or 1, 16))
+
+    def sample_of(target_total: int):
+        """Leading tensors of the workload, each cut to its first target/cores elements, until the
+        target is reached: every thread then has a similar share whatever the tensor sizes are."""
+        cap = max(1, target_total // cores)
+        names, numels, acc = [], [], 0
+        for nm, n in zip(wl.layout.names, wl.layout.numels):
+            if n == 0:
+                continue
+            names.append(nm)
+            numels.append(min(n, cap))
+            acc += numels[-1]
+            if acc >= target_total:
+                break
+        return synth.Workload("sample", synth.Layout(names, numels), wl.lr, wl.grad_kind, wl.sigma,
+                              ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
+
+    def run(sample_wl):
+        lay = sample_wl.layout
+        # deal tensors to threads, largest first, so every thread gets a similar share
+        order = sorted(range(lay.n_tensors), key=lambda t: -lay.numels[t])
+        shares = [[] for _ in range(cores)]
+        loads = [0] * cores
+        for t in order:
+            k = loads.index(min(loads))
+            shares[k].append(t)
+            loads[k] += lay.numels[t]
+        shares = [s for s in shares if s]
+        grad = torch.zeros(lay.total, dtype=torch.bfloat16)
+        w0 = torch.zeros(lay.total, dtype=torch.bfloat16)
+        synth.fill_gradients(grad, sample_wl, seed, 1)
+        synth.fill_weights(w0, lay, seed)
+        gbits, wbits = synth.bits16(grad), synth.bits16(w0)
+        cfg = O.default_cfg(ramp_steps=sample_wl.ramp_steps, hist_window=sample_wl.hist_window)
+        # the threads share the flat buffers and write disjoint tensors of them
+        bufs = dict(g8=np.zeros(lay.total, np.uint8), m=np.zeros(lay.total, np.uint8),
+                    v=np.zeros(lay.total, np.uint16), w=np.zeros(lay.total, np.uint16),
+                    wq=np.zeros(lay.total, np.uint8))
+        jobs = []
+        for ids in shares:
+            tens = O.tensors_array([lay.tensors()[t] for t in ids])
+            job = dict(bufs, tens=tens, metas=[O.new_meta(len(ids), cfg) for _ in range(5)])
+            O.init_master(wbits, tens, job["w"], job["metas"][3])
+            jobs.append(job)
+        hp = O.AdamHparams(sample_wl.lr, 0.9, 0.95, 1e-8, 0.1, 1, 1, O.WCOPY_E4M3)
+
+        def one(job):
+            g, m, v, w, q = job["metas"]
+            O.amax_scale(gbits, job["tens"], O.E5M2, g, cfg)
+            O.cast_fp8(gbits, job["tens"], job["g8"], O.E5M2, g, cfg)
+            O.adam_step_fp8(job["tens"], job["g8"], O.E5M2, g, job["m"], m, job["v"], v, job["w"], w, job["wq"], q, hp)
+
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(len(jobs)) as ex:
+            list(ex.map(one, jobs))
+        return time.perf_counter() - t0, lay.n_params, len(jobs)
+
+    dt, n, _ = run(sample_of(1_000_000 * cores))        # calibration
+    sample = sample_of(int(min(max(n / dt * budget_s, 1_000_000), 2e9)))
+    dt, n, used = run(sample)
+    lay = sample.layout
+    return {"value": n / dt, "unit": "params/s", "cores": used, "kind": "oracle",
+            "sample": f"first {lay.n_tensors} tensors of {wl.name}, each cut to at most {max(lay.numels)} elements "
+                      f"({n} params), one step in {dt:.1f} s"}
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE, scaled by a copy kernel of known size); None when no measurement is recorded."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            parts = line.split("#")[0].split()
+            if len(parts) == 2 and parts[0] == "adam_update":
+                return float(parts[1])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gpt13b")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--blocks-per-cu", type=int, default=0)
+    ap.add_argument("--interleave", type=int, default=-1)
+    ap.add_argument("--exact", type=int, default=1)
+    ap.add_argument("--stats", type=int, default=0)
+    ap.add_argument("--copy-ceiling", action="store_true", help="also time a plain 128-bit copy kernel")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2310_18313_amd import binding as B
+    from paper_2310_18313_amd import synth
+    from paper_2310_18313_amd.state import OptimizerState
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.lib()  # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    wl = synth.workload(args.workload)
+    lay = wl.layout
+    P = lay.n_params
+    cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
+    if args.chunk or args.blocks_per_cu or args.interleave >= 0:
+        st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 8, max(args.interleave, 0))
+    grad = torch.zeros(lay.total, dtype=torch.bfloat16, device=dev)
+    synth.fill_weights(grad, lay, args.seed)          # reuse the buffer for the initial weights
+    st.init_master(grad)
+    torch.cuda.synchronize()
+    grad.zero_()
+    synth.fill_gradients(grad, wl, args.seed, 1)
+    torch.cuda.synchronize()
+
+    def hp(step):
+        return B.adam_hparams(wl.lr, step, exact=args.exact, stats=args.stats)
+
+    for s in range(1, args.warmup + 1):
+        st.step(grad, hp(s))
+    torch.cuda.synchronize()
+    st.ctx.set_timing(True)
+    st.ctx.get_timing()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.warmup + 1, args.warmup + args.steps + 1):
+        st.step(grad, hp(s))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    timing = st.ctx.get_timing()
+    st.ctx.set_timing(False)
+
+    ms_per_step = dt / args.steps * 1e3
+    kernels = {}
+    for name, bpp in BYTES_PER_PARAM.items():
+        n, ms = timing[name]
+        if n:
+            avg = ms / n
+            kernels[name] = {"avg_ms": round(avg, 4), "launches": n, "bytes_per_param": bpp,
+                             "GBps": round(bpp * P / (avg * 1e-3) / 1e9, 1)}
+    dom = "adam_update"
+    achieved = kernels[dom]["GBps"]
+    out = {
+        "metric": "params updated/sec + achieved HBM GB/s (% of peak), FP8 cast+Adam step",
+        "value": P / (dt / args.steps),
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "tensors": lay.n_tensors, "params": P, "grad_fmt": "e5m2",
+                   "m_fmt": "e4m3", "v": "fp16 scaled", "master": "fp16 scaled", "wcopy": "e4m3",
+                   "exact_div_sqrt": bool(args.exact), "bytes_per_param_step": 19},
+        "step_GBps": round(19 * P / (dt / args.steps) / 1e9, 1),
+        "step_frac_of_peak": round(19 * P / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+        "kernels": kernels,
+        "roofline": {"kernel": "adam_update_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(wl.name)},
+    }
+    if args.copy_ceiling:
+        nbytes = min(lay.total, 1 << 32)
+        st.ctx.set_timing(True)
+        st.ctx.get_timing()
+        for _ in range(5):
+            st.ctx.copy_bytes(st.m, st.g8, nbytes)
+        n, ms = st.ctx.get_timing()["copy"]
+        st.ctx.set_timing(False)
+        out["copy_kernel_GBps"] = round(2 * nbytes / (ms / n * 1e-3) / 1e9, 1)
+    del st, grad
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.seed)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
