@@ -128,6 +128,7 @@ def main() -> int:
     ap.add_argument("--exact", type=int, default=1)
     ap.add_argument("--stats", type=int, default=0)
     ap.add_argument("--copy-ceiling", action="store_true", help="also time a plain 128-bit copy kernel")
+    ap.add_argument("--no-spread", action="store_true", help="allocate the buffers plainly, one after the other")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -147,10 +148,15 @@ def main() -> int:
     lay = wl.layout
     P = lay.n_params
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
-    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=not args.no_spread,
+                        grad_buffer=True)
     if args.chunk or args.blocks_per_cu or args.interleave >= 0:
         st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 8, max(args.interleave, 0))
-    grad = torch.zeros(lay.total, dtype=torch.bfloat16, device=dev)
+    grad = st.grad
+    placement = {"spread_over_hbm_regions": st.spread}
+    if st.spread:
+        from paper_2310_18313_amd.placement import verify_spread
+        placement["check_v_vs_w"] = verify_spread(st.ctx, st.v, st.w)
     synth.fill_weights(grad, lay, args.seed)          # reuse the buffer for the initial weights
     st.init_master(grad)
     torch.cuda.synchronize()
@@ -200,7 +206,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": wl.name, "tensors": lay.n_tensors, "params": P, "grad_fmt": "e5m2",
                    "m_fmt": "e4m3", "v": "fp16 scaled", "master": "fp16 scaled", "wcopy": "e4m3",
-                   "exact_div_sqrt": bool(args.exact), "bytes_per_param_step": 19},
+                   "exact_div_sqrt": bool(args.exact), "bytes_per_param_step": 19, "placement": placement},
         "step_GBps": round(19 * P / (dt / args.steps) / 1e9, 1),
         "step_frac_of_peak": round(19 * P / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
         "kernels": kernels,

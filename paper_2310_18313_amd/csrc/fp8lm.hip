@@ -147,9 +147,12 @@ __device__ __forceinline__ unsigned long long take_u64(unsigned long long* p) {
 }
 
 // ---- the chunk walk shared by all kernels -------------------------------------------------------
-// Op must provide: begin(t, desc), group(pos, valid) with `pos` the element index into the flat
-// buffers and 1 <= valid <= 16, and flush(t, desc, chunks_done) (called by all threads).
-template <class Op>
+// Op must provide: begin(t, desc); fast() (uniform: may the vector path be used for this tensor);
+// tiles<UN>(pos): UN complete 4096-element tiles starting at element `pos` of the flat buffers, handled
+// by the whole workgroup (all loads issued before the first use; the op chooses which 16 elements of
+// a tile a thread takes); group(pos, valid) with 1 <= valid <= 16 for everything else, element by
+// element; flush(t, desc, chunks_done) (called by all threads).
+template <int UN, class Op>
 __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
   const long long G = gridDim.x, b = blockIdx.x;
   long long c, c_end, step;
@@ -170,7 +173,14 @@ __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
     const long long rest = d.numel - e0;
     const int len = rest < tb.chunk_elems ? (int)rest : tb.chunk_elems;
     const long long base = d.offset + e0;
-    for (int i = threadIdx.x * kGroup; i < len; i += kTile) {
+    const int ntiles = len / kTile;
+    int tile = 0;
+    if (op.fast()) {
+      if constexpr (UN > 1)
+        for (; tile + UN <= ntiles; tile += UN) op.template tiles<UN>(base + (long long)tile * kTile);
+      for (; tile < ntiles; ++tile) op.template tiles<1>(base + (long long)tile * kTile);
+    }
+    for (int i = tile * kTile + threadIdx.x * kGroup; i < len; i += kTile) {
       const int valid = len - i < kGroup ? len - i : kGroup;
       op.group(base + i, valid);
     }
@@ -179,8 +189,46 @@ __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
   if (cur >= 0) op.flush(cur, d, done);
 }
 
-__device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
-__device__ __forceinline__ void st16(void* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
+// Build-time tuning knobs (defaults are the measured best on MI355X).
+#ifndef FP8LM_NT_MASK
+#define FP8LM_NT_MASK 3   // bit0 non-temporal loads of read-only streams, bit1 non-temporal stores of write-only
+                          // streams, bit2 / bit3 the same for the in-place (read-modify-write) streams
+#endif
+#ifndef FP8LM_UN_READ
+#define FP8LM_UN_READ 4   // 16-element groups a thread keeps in flight in the read-only kernels
+#endif
+#ifndef FP8LM_UN_CAST
+#define FP8LM_UN_CAST 2
+#endif
+#ifndef FP8LM_UN_UPDATE
+#define FP8LM_UN_UPDATE 1
+#endif
+#ifndef FP8LM_CAST_ROWS
+#define FP8LM_CAST_ROWS 0
+#endif
+#ifndef FP8LM_NT16
+#define FP8LM_NT16 0      // non-temporal loads of the 16-bit in-place streams when a thread reads 32 contiguous bytes
+#endif
+constexpr bool kNtLoadRO = (FP8LM_NT_MASK & 1) != 0, kNtStoreWO = (FP8LM_NT_MASK & 2) != 0;
+constexpr bool kNtLoadRW = (FP8LM_NT_MASK & 4) != 0, kNtStoreRW = (FP8LM_NT_MASK & 8) != 0;
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <bool NT = false> __device__ __forceinline__ uint4 ld16(const void* p) {
+  if constexpr (NT) {
+    const u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(r.x, r.y, r.z, r.w);
+  } else {
+    return *reinterpret_cast<const uint4*>(p);
+  }
+}
+template <bool NT = false> __device__ __forceinline__ void st16(void* p, uint4 v) {
+  if constexpr (NT) {
+    const u32x4_t r = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(r, reinterpret_cast<u32x4_t*>(p));
+  } else {
+    *reinterpret_cast<uint4*>(p) = v;
+  }
+}
 
 // ================================================================================================
 // Kernel 1: per-tensor amax of a bf16 buffer, then the scale update (Appendix A.2; Sec. 2.1 Eq. 3)
@@ -204,20 +252,30 @@ struct AmaxOp {
   uint32_t acc;   // two 16-bit running maxima
   __device__ AmaxOp(const AmaxParams& p_, const Tables& tb_) : p(p_), tb(tb_), acc(0) {}
   __device__ __forceinline__ void begin(int, const TensorDesc&) { acc = 0; }
-  __device__ __forceinline__ void group(long long pos, int valid) {
-    if (valid == kGroup) {
-      const uint4 a = ld16(p.src + pos), b = ld16(p.src + pos + 8);
-      const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+  __device__ __forceinline__ bool fast() const { return true; }
+  template <int UN> __device__ __forceinline__ void tiles(long long pos) {
+    // a pure reduction: each load instruction of a wavefront covers 1 KiB contiguous
+    uint4 a[UN], b[UN];
+    const uint16_t* q = p.src + pos + threadIdx.x * 8;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      a[u] = ld16<kNtLoadRO>(q + u * kTile);
+      b[u] = ld16<kNtLoadRO>(q + u * kTile + kTile / 2);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const uint32_t w[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const ushort2_t x = __builtin_bit_cast(ushort2_t, w[j] & 0x7FFF7FFFu);
         acc = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, acc), x));
       }
-    } else {
-      uint32_t m = acc & 0xFFFFu;
-      for (int j = 0; j < valid; ++j) m = max(m, (uint32_t)(p.src[pos + j] & 0x7FFFu));
-      acc = (acc & 0xFFFF0000u) | m;
     }
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    uint32_t m = acc & 0xFFFFu;
+    for (int j = 0; j < valid; ++j) m = max(m, (uint32_t)(p.src[pos + j] & 0x7FFFu));
+    acc = (acc & 0xFFFF0000u) | m;
   }
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
     BlockStats<1, 0> s;
@@ -281,7 +339,7 @@ struct AmaxOp {
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void amax_kernel(Tables tb, AmaxParams p) {
   AmaxOp<MODE> op(p, tb);
-  walk_chunks(tb, op);
+  walk_chunks<FP8LM_UN_READ>(tb, op);
 }
 
 // ================================================================================================
@@ -344,18 +402,49 @@ struct CastOp {
     nz_top += (c & 0x7Fu) != Fp8Traits<FMT>::kTop;
     return c;
   }
-  __device__ __forceinline__ void group(long long pos, int valid) {
-    if (valid == kGroup && !careful) {
-      const uint4 a = ld16(p.src + pos), b = ld16(p.src + pos + 8);
-      uint4 o;
-      o.x = quad(a.x, a.y);
-      o.y = quad(a.z, a.w);
-      o.z = quad(b.x, b.y);
-      o.w = quad(b.z, b.w);
-      st16(p.dst + pos, o);
-    } else {
-      for (int j = 0; j < valid; ++j) p.dst[pos + j] = (uint8_t)one(p.src[pos + j]);
+  __device__ __forceinline__ bool fast() const { return !careful; }
+  template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
+    uint4 a[UN], b[UN];
+#if FP8LM_CAST_ROWS
+    // each load instruction of a wavefront covers 1 KiB contiguous; a thread takes elements
+    // [8t, 8t+8) and [2048+8t, 2048+8t+8) of the tile and writes two 8-byte pieces
+    const long long pos = pos0 + threadIdx.x * 8;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      a[u] = ld16<kNtLoadRO>(p.src + pos + u * kTile);
+      b[u] = ld16<kNtLoadRO>(p.src + pos + u * kTile + kTile / 2);
     }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      uint2 lo, hi;
+      lo.x = quad(a[u].x, a[u].y);
+      lo.y = quad(a[u].z, a[u].w);
+      hi.x = quad(b[u].x, b[u].y);
+      hi.y = quad(b[u].z, b[u].w);
+      *reinterpret_cast<uint2*>(p.dst + pos + u * kTile) = lo;
+      *reinterpret_cast<uint2*>(p.dst + pos + u * kTile + kTile / 2) = hi;
+    }
+#else
+    const long long pos = pos0 + threadIdx.x * kGroup;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      a[u] = ld16<kNtLoadRO>(p.src + pos + u * kTile);
+      b[u] = ld16<kNtLoadRO>(p.src + pos + u * kTile + 8);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      uint4 o;
+      o.x = quad(a[u].x, a[u].y);
+      o.y = quad(a[u].z, a[u].w);
+      o.z = quad(b[u].x, b[u].y);
+      o.w = quad(b[u].z, b[u].w);
+      st16<kNtStoreWO>(p.dst + pos + u * kTile, o);
+    }
+#endif
+    n_elems += UN * kGroup;
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    for (int j = 0; j < valid; ++j) p.dst[pos + j] = (uint8_t)one(p.src[pos + j]);
     n_elems += valid;
   }
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
@@ -397,7 +486,7 @@ struct CastOp {
 template <int FMT>
 __global__ __launch_bounds__(kThreads) void cast_kernel(Tables tb, CastParams p) {
   CastOp<FMT> op(p, tb);
-  walk_chunks(tb, op);
+  walk_chunks<FP8LM_UN_CAST>(tb, op);
 }
 
 // ================================================================================================
@@ -421,6 +510,8 @@ struct InitCastOp {
     vmax = 0.0f;
     n_sat = n_und = 0;
   }
+  __device__ __forceinline__ bool fast() const { return false; }
+  template <int UN> __device__ __forceinline__ void tiles(long long) {}
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) {
       const uint32_t bits = p.src[pos + j];
@@ -459,7 +550,7 @@ struct InitCastOp {
 
 __global__ __launch_bounds__(kThreads) void init_master_cast_kernel(Tables tb, InitParams p) {
   InitCastOp op(p, tb);
-  walk_chunks(tb, op);
+  walk_chunks<1>(tb, op);
 }
 
 // ================================================================================================
@@ -520,16 +611,25 @@ struct AdamAmaxOp {
     elem(g23.x, m23.x);
     elem(g23.y, m23.y);
   }
-  __device__ __forceinline__ void group(long long pos, int valid) {
-    if (valid == kGroup) {
-      const uint4 g = ld16(p.grad + pos), m = ld16(p.m + pos);
-      word(g.x, m.x);
-      word(g.y, m.y);
-      word(g.z, m.z);
-      word(g.w, m.w);
-    } else {
-      for (int j = 0; j < valid; ++j) elem(fp8_to_f32<GFMT>(p.grad[pos + j]), fp8_to_f32<kE4M3>(p.m[pos + j]));
+  __device__ __forceinline__ bool fast() const { return true; }
+  template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
+    uint4 g[UN], m[UN];
+    const long long pos = pos0 + threadIdx.x * kGroup;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      g[u] = ld16<kNtLoadRO>(p.grad + pos + u * kTile);
+      m[u] = ld16<kNtLoadRO>(p.m + pos + u * kTile);
     }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      word(g[u].x, m[u].x);
+      word(g[u].y, m[u].y);
+      word(g[u].z, m[u].z);
+      word(g[u].w, m[u].w);
+    }
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    for (int j = 0; j < valid; ++j) elem(fp8_to_f32<GFMT>(p.grad[pos + j]), fp8_to_f32<kE4M3>(p.m[pos + j]));
   }
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
     BlockStats<1, 0> s;
@@ -589,7 +689,7 @@ struct AdamAmaxOp {
 template <int GFMT, int WCOPY>
 __global__ __launch_bounds__(kThreads) void adam_amax_kernel(Tables tb, AdamParams p) {
   AdamAmaxOp<GFMT, WCOPY> op(p, tb);
-  walk_chunks(tb, op);
+  walk_chunks<FP8LM_UN_READ>(tb, op);
 }
 
 // ---- pass B: the update ----------------------------------------------------------------------------
@@ -721,28 +821,43 @@ struct AdamUpdateOp {
     stats(m1, v1, w1, tm, tv, tw, tq);
   }
 
-  __device__ __forceinline__ void group(long long pos, int valid) {
-    if (valid == kGroup && !careful) {
-      const uint4 g = ld16(p.grad + pos), m = ld16(p.m + pos);
-      const uint4 va = ld16(p.v + pos), vb = ld16(p.v + pos + 8);
-      const uint4 wa = ld16(p.w + pos), wb = ld16(p.w + pos + 8);
-      const Quad q0 = quad(g.x, m.x, va.x, va.y, wa.x, wa.y);
-      const Quad q1 = quad(g.y, m.y, va.z, va.w, wa.z, wa.w);
-      const Quad q2 = quad(g.z, m.z, vb.x, vb.y, wb.x, wb.y);
-      const Quad q3 = quad(g.w, m.w, vb.z, vb.w, wb.z, wb.w);
-      st16(p.m + pos, make_uint4(q0.m, q1.m, q2.m, q3.m));
-      st16(p.v + pos, make_uint4(q0.v01, q0.v23, q1.v01, q1.v23));
-      st16(p.v + pos + 8, make_uint4(q2.v01, q2.v23, q3.v01, q3.v23));
-      st16(p.w + pos, make_uint4(q0.w01, q0.w23, q1.w01, q1.w23));
-      st16(p.w + pos + 8, make_uint4(q2.w01, q2.w23, q3.w01, q3.w23));
+  __device__ __forceinline__ bool fast() const { return !careful; }
+  template <int UN> __device__ __forceinline__ void tiles(long long tile0) {
+    uint4 g[UN], m[UN], va[UN], vb[UN], wa[UN], wb[UN];
+    const long long pos0 = tile0 + threadIdx.x * kGroup;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const long long pos = pos0 + u * kTile;
+      g[u] = ld16<kNtLoadRO>(p.grad + pos);
+      m[u] = ld16<kNtLoadRW>(p.m + pos);
+      va[u] = ld16<kNtLoadRW>(p.v + pos);
+      vb[u] = ld16<kNtLoadRW>(p.v + pos + 8);
+      wa[u] = ld16<kNtLoadRW>(p.w + pos);
+      wb[u] = ld16<kNtLoadRW>(p.w + pos + 8);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const long long pos = pos0 + u * kTile;
+      const Quad q0 = quad(g[u].x, m[u].x, va[u].x, va[u].y, wa[u].x, wa[u].y);
+      const Quad q1 = quad(g[u].y, m[u].y, va[u].z, va[u].w, wa[u].z, wa[u].w);
+      const Quad q2 = quad(g[u].z, m[u].z, vb[u].x, vb[u].y, wb[u].x, wb[u].y);
+      const Quad q3 = quad(g[u].w, m[u].w, vb[u].z, vb[u].w, wb[u].z, wb[u].w);
+      st16<kNtStoreRW>(p.m + pos, make_uint4(q0.m, q1.m, q2.m, q3.m));
+      st16<kNtStoreRW>(p.v + pos, make_uint4(q0.v01, q0.v23, q1.v01, q1.v23));
+      st16<kNtStoreRW>(p.v + pos + 8, make_uint4(q2.v01, q2.v23, q3.v01, q3.v23));
+      st16<kNtStoreRW>(p.w + pos, make_uint4(q0.w01, q0.w23, q1.w01, q1.w23));
+      st16<kNtStoreRW>(p.w + pos + 8, make_uint4(q2.w01, q2.w23, q3.w01, q3.w23));
       if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
-        st16(static_cast<uint8_t*>(p.wcopy) + pos, make_uint4(q0.q, q1.q, q2.q, q3.q));
+        st16<kNtStoreWO>(static_cast<uint8_t*>(p.wcopy) + pos, make_uint4(q0.q, q1.q, q2.q, q3.q));
       } else {
         uint16_t* q = static_cast<uint16_t*>(p.wcopy);
-        st16(q + pos, make_uint4(q0.q, q0.q2, q1.q, q1.q2));
-        st16(q + pos + 8, make_uint4(q2.q, q2.q2, q3.q, q3.q2));
+        st16<kNtStoreWO>(q + pos, make_uint4(q0.q, q0.q2, q1.q, q1.q2));
+        st16<kNtStoreWO>(q + pos + 8, make_uint4(q2.q, q2.q2, q3.q, q3.q2));
       }
-    } else if (!careful) {
+    }
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    if (!careful) {
       // ragged tail of a tensor: same arithmetic, element by element
       for (int j = 0; j < valid; ++j) {
         const long long i = pos + j;
@@ -837,10 +952,18 @@ struct AdamUpdateOp {
   }
 };
 
+#ifndef FP8LM_UPDATE_WAVES
+#define FP8LM_UPDATE_WAVES 0
+#endif
+#if FP8LM_UPDATE_WAVES > 0
+#define FP8LM_UPDATE_ATTR __attribute__((amdgpu_waves_per_eu(FP8LM_UPDATE_WAVES)))
+#else
+#define FP8LM_UPDATE_ATTR
+#endif
 template <int GFMT, int WCOPY, bool FAST, bool STATS>
-__global__ __launch_bounds__(kThreads) void adam_update_kernel(Tables tb, AdamParams p) {
+__global__ __launch_bounds__(kThreads) FP8LM_UPDATE_ATTR void adam_update_kernel(Tables tb, AdamParams p) {
   AdamUpdateOp<GFMT, WCOPY, FAST, STATS> op(p, tb);
-  walk_chunks(tb, op);
+  walk_chunks<FP8LM_UN_UPDATE>(tb, op);
 }
 
 // ---- small kernels ---------------------------------------------------------------------------------

@@ -9,11 +9,13 @@ from __future__ import annotations
 import torch
 
 from . import binding as B
+from .placement import SpreadAllocator
 
 
 class OptimizerState:
     def __init__(self, tensors, total_elems: int, cfg: B.AutoscaleCfg, device: int = 0,
-                 grad_fmt: int = B.E5M2, wcopy: int = B.WCOPY_E4M3):
+                 grad_fmt: int = B.E5M2, wcopy: int = B.WCOPY_E4M3, spread: bool = False,
+                 grad_buffer: bool = False):
         dev = torch.device(f"cuda:{device}")
         self.tensors = list(tensors)
         self.total = int(total_elems)
@@ -22,11 +24,21 @@ class OptimizerState:
         self.wcopy_kind = wcopy
         self.ctx = B.Context(self.tensors, device)
         n = max(self.total, 16)
-        self.g8 = torch.zeros(n, dtype=torch.uint8, device=dev)
-        self.m = torch.zeros(n, dtype=torch.uint8, device=dev)       # E4M3 code 0 = +0
-        self.v = torch.zeros(n, dtype=torch.float16, device=dev)
-        self.w = torch.zeros(n, dtype=torch.float16, device=dev)
-        self.wq = torch.zeros(n, dtype=torch.uint8 if wcopy == B.WCOPY_E4M3 else torch.bfloat16, device=dev)
+        qdt = torch.uint8 if wcopy == B.WCOPY_E4M3 else torch.bfloat16
+        # Streams that the update kernel walks together go to different thirds of HBM when `spread` is
+        # set (see placement.py): v (+ the bf16 gradient source) | w | m, FP8 gradient, weight copy.
+        plan = [[("v", n, torch.float16)] + ([("grad", n, torch.bfloat16)] if grad_buffer else []),
+                [("w", n, torch.float16)],
+                [("m", n, torch.uint8), ("g8", n, torch.uint8), ("wq", n, qdt)]]
+        if spread:
+            alloc = SpreadAllocator(device)
+            bufs = alloc.allocate(plan)
+            self.spread = alloc.spread
+        else:
+            bufs = {name: torch.zeros(k, dtype=dt, device=dev) for reg in plan for name, k, dt in reg}
+            self.spread = False
+        self.g8, self.m, self.v, self.w, self.wq = bufs["g8"], bufs["m"], bufs["v"], bufs["w"], bufs["wq"]
+        self.grad = bufs.get("grad")       # bf16 gradient source, only if asked for
         self.g_meta = self.ctx.new_meta(cfg)
         self.m_meta = self.ctx.new_meta(cfg)
         self.v_meta = self.ctx.new_meta(cfg)
