@@ -83,7 +83,9 @@ def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool
     post_meta = {k: B.meta_to_numpy(getattr(st, k), n_tensors)
                  for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta")}
     out = dict(elements=0, m_diff=0, w_diff=0, q_diff=0, w_amax_ulp=0)
-    for s in snaps:
+
+    def check_one(s):
+        out = dict(elements=0, m_diff=0, w_diff=0, q_diff=0, w_amax_ulp=0)
         tag = f"{what} tensor {s.t} (n={s.n})"
         tens = O.tensors_array([(0, s.n)])
         g_meta = s.metas["g_meta"].copy()
@@ -97,7 +99,7 @@ def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool
             assert not bad, f"{tag}: gradient meta differs in {bad}: gpu {post_meta['g_meta'][s.t]} oracle {g_meta[0]}"
         out["elements"] += s.n
         if quantize_only:
-            continue
+            return out
         m, v, w = s.m.copy(), s.v.copy(), s.w.copy()
         wq = np.zeros(s.src.size, dtype=np.uint8 if hp.wcopy == B.WCOPY_E4M3 else np.uint16)
         mm, vm, wm, qm = (s.metas[k].copy() for k in ("m_meta", "v_meta", "w_meta", "q_meta"))
@@ -144,7 +146,7 @@ def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool
                 f"{tag}: weight copy differs ({np.count_nonzero(dq)} of {s.n})"
         out["q_diff"] += int(np.count_nonzero(dq))
         if s.n == 0:
-            continue
+            return out
         # metadata
         stat_fields = ["n_sat", "n_underflow"] if hp.stats else []
         exact_fields = ["scale", "inv_scale", "amax", "amax_deq", "flags"] + stat_fields
@@ -170,6 +172,15 @@ def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool
                     # counters may move by the few elements whose rounding moved
                     for f in stat_fields:
                         assert abs(int(post_meta[key][s.t][f]) - int(ref[0][f])) <= max(2, int(1e-4 * n)), f"{tag}: {key}.{f}"
+        return out
+
+    # the oracle is single-threaded; tensors are independent, so they are checked side by side
+    # (ctypes releases the GIL during the oracle calls)
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=min(12, max(1, len(snaps)))) as ex:
+        for r in ex.map(check_one, sorted(snaps, key=lambda x: -x.n)):
+            for k in out:
+                out[k] = max(out[k], r[k]) if k == "w_amax_ulp" else out[k] + r[k]
     return out
 
 

@@ -1,0 +1,105 @@
+"""GPU parity at the full sizes of the benchmark configurations, on sampled tensors.
+
+The whole model steps on the GPU in the launch configuration bench.py times (default tuning, buffers
+spread over the HBM regions); before a checked step the inputs of the sampled tensors are copied to
+the host and the oracle recomputes those tensors completely.  Every small tensor (LayerNorm weights,
+biases) is sampled, plus one tensor of every distinct large shape.
+"""
+import numpy as np
+import pytest
+import torch
+
+import parity as P
+from paper_2310_18313_amd import binding as B
+from paper_2310_18313_amd import synth
+from paper_2310_18313_amd.state import OptimizerState
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+SMALL = 1 << 20
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def sample_ids(layout):
+    small = [t for t, n in enumerate(layout.numels) if 0 < n <= SMALL]
+    seen, big = set(), []
+    # one tensor per distinct large shape, taken from the middle of the model
+    order = sorted(range(layout.n_tensors), key=lambda t: abs(t - layout.n_tensors // 2))
+    for t in order:
+        n = layout.numels[t]
+        kind = layout.names[t].split(".", 1)[-1]
+        if n > SMALL and (kind, n) not in seen:
+            seen.add((kind, n))
+            big.append(t)
+    return small, sorted(big)
+
+
+def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False):
+    lay = wl.layout
+    cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=True, grad_buffer=True)
+    say(f"{wl.name}: {lay.n_tensors} tensors, {lay.n_params} params, spread={st.spread}")
+    grad = st.grad
+    synth.fill_weights(grad, lay, seed)
+    st.init_master(grad)
+    torch.cuda.synchronize()
+    small, big = sample_ids(lay)
+    if big_ids is not None:
+        big = big_ids
+    P.check_init_master(st, grad, small + big[:2])
+    grad.zero_()
+    tot = dict(elements=0, m_diff=0, w_diff=0, q_diff=0, w_amax_ulp=0)
+    mus = []
+    for step in range(1, steps + 1):
+        synth.fill_gradients(grad, wl, seed, step)
+        hp = B.adam_hparams(wl.lr, step)
+        ids = (small if step in small_steps else []) + (big if step in big_steps else [])
+        snaps = [P.Snapshot(st, grad, t) for t in ids]
+        st.step(grad, hp)
+        torch.cuda.synchronize()
+        if ids:
+            say(f"{wl.name} step {step}: checking {len(ids)} tensors, {sum(lay.numels[t] for t in ids)} elements")
+            r = P.check_step(st, snaps, hp, what=f"{wl.name} step {step}")
+            for k in tot:
+                tot[k] = max(tot[k], r[k]) if k == "w_amax_ulp" else tot[k] + r[k]
+        if track_mu:
+            mus.append(B.meta_to_numpy(st.g_meta, lay.n_tensors)["mu_exp"].copy())
+    say(f"{wl.name}: {tot}")
+    # exact arithmetic is the default: nothing may differ
+    assert tot["m_diff"] == 0 and tot["w_diff"] == 0 and tot["q_diff"] == 0
+    return st, tot, mus
+
+
+def test_gpt13b_in_the_benchmark_configuration():
+    wl = synth.workload("gpt13b")
+    st, tot, _ = run(wl, seed=0, steps=2, small_steps={1, 2}, big_steps={1})
+    assert st.state_bytes_per_param == 6          # Sec. 2.2, Eq. 8
+    assert tot["elements"] > 5e8
+
+
+def test_gpt7b_five_steps_with_amax_history():
+    wl = synth.workload("gpt7b")
+    assert wl.hist_window == 4
+    run(wl, seed=2, steps=5, small_steps={1, 2, 3, 4, 5}, big_steps={1, 5})
+
+
+def test_gpt175b_layer_heavy_tails_hundred_steps():
+    wl = synth.workload("gpt175b_layer")
+    lay = wl.layout
+    proj = lay.names.index("l0.proj.w")
+    checked = {1, 2, 3, 10, 11, 20, 21, 22, 23, 24, 50, 99, 100}
+    st, tot, mus = run(wl, seed=5, steps=100, small_steps=checked, big_steps={1, 24, 100}, big_ids=[proj],
+                       track_mu=True)
+    mus = np.array(mus)                            # [step, tensor]
+    # Large matrices: the amax is set by a rare outlier, so even mu = 2 clips far fewer than 0.001 % of
+    # the elements and mu climbs to 2 and stays.  Small tensors (< 100 000 elements) overflow whenever
+    # their largest element lands on the top code, so they keep cycling 1/2 -> 1 -> 2.
+    big = [t for t, n in enumerate(lay.numels) if n > SMALL]
+    small = [t for t, n in enumerate(lay.numels) if 0 < n <= SMALL]
+    assert (mus[-1, big] == 1).all() and (mus[0, big] == 0).all()
+    assert (mus[:, small] == -1).any() and (mus[:, small] == 0).any() and (mus[:, small] == 1).any()
+    gm = B.meta_to_numpy(st.g_meta, lay.n_tensors)
+    assert gm["n_sat"].sum() > 0
