@@ -95,6 +95,11 @@ typedef struct {
   int32_t wcopy;    /* fp8lm_wcopy                                                                 */
   int32_t stats;    /* 1: count n_sat / n_underflow of the four outputs exactly (more ALU work);
                        0: leave them 0; FLAG_SATURATED is still exact (derived from the amax)      */
+  int32_t m_predict; /* 0: the first-moment scale comes from the exact amax of the new moment (an extra
+                          read-only pass over grad and m);
+                       1: it comes from the bound fma(beta1, m_meta.amax_deq, (1-beta1) * grad_meta.amax_deq),
+                          which no new |m| exceeds: one pass less, the scale can be a binade or more
+                          looser; v, w and the update itself are unaffected                       */
   int32_t exact;    /* 1: correctly rounded sqrt and divide in the weight update (results identical to
                           the scalar definition);
                        0: hardware v_sqrt_f32 / v_rcp_f32, 1 ulp each: m and v are unaffected, the
@@ -156,6 +161,20 @@ fp8lm_status fp8lm_cast_fp8(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_sr
                             void* stream);
 
 /*
+ * Single-pass gradient quantisation with delayed scaling (Appendix A.2: the scale is chosen from the
+ * amax values of preceding iterations).  The scale of every tensor is first set from its history ring
+ * as it stands (same rule as fp8lm_amax_scale; an all-zero history keeps the scale in the metadata,
+ * FLAG_AMAX_ZERO), then one pass casts src with that scale exactly as fp8lm_cast_fp8 does
+ * (saturating: a gradient that outgrew its history clips and is counted in n_sat) and at the same
+ * time measures this step's amax, which is stored in meta[t].amax and pushed into the ring for the
+ * following steps (a non-finite amax is flagged and not pushed).  The first step of a run should use
+ * fp8lm_amax_scale + fp8lm_cast_fp8, which also seeds the history.
+ */
+fp8lm_status fp8lm_cast_fp8_delayed(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_src src_type,
+                                    uint8_t* dst /*device*/, fp8lm_fmt fmt, fp8lm_meta* meta /*device*/,
+                                    const fp8lm_autoscale_cfg* cfg /*host*/, void* stream);
+
+/*
  * Master-weight initialisation (Sec. 2.2: FP16 master weights with tensor scaling).
  * For every tensor: scale = 2^(k - 1) with k the largest integer such that 2^k * max|w| <= 65504,
  * w_f16[i] = FP16(scale * w_bf16[i]) (round to nearest even, saturating).  Fills w_meta[t].
@@ -169,7 +188,8 @@ fp8lm_status fp8lm_init_master(fp8lm_ctx* ctx, const void* w_bf16 /*device*/, ui
  *     m' = fma(beta1, m, (1-beta1) * g)          v' = fma(beta2, v, (1-beta2) * g*g)
  *     w' = fma(-lr, (m' / (1-beta1^step)) / (sqrt(v' / (1-beta2^step)) + eps), w * (1 - lr*weight_decay))
  * and m', v', w' are stored back in place with refreshed per-tensor scales:
- *     m : E4M3, scale from the exact amax of m' (an extra read-only pass over grad and m);
+ *     m : E4M3, scale from the exact amax of m' (an extra read-only pass over grad and m), or from a
+ *         predicted bound when hp->m_predict is set;
  *     v : FP16, scale from the bound fma(beta2, v_meta.amax_deq, (1-beta2) * grad_meta.amax_deq^2), which
  *         no v' exceeds (v_scaled = 0: scale 1);
  *     w : FP16, scale from w_meta.amax_deq before the step, minus one binade;
@@ -198,7 +218,8 @@ fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* ctx, const void* src /*device*/, void* 
  * fp8lm_get_timing synchronises and returns, per kernel id, the number of launches and the summed
  * duration in milliseconds since timing was enabled, then resets the sums.                       */
 enum { FP8LM_K_AMAX = 0, FP8LM_K_CAST = 1, FP8LM_K_ADAM_AMAX = 2, FP8LM_K_ADAM_UPDATE = 3,
-       FP8LM_K_INIT_MASTER = 4, FP8LM_K_COPY = 5, FP8LM_K_COUNT = 6 };
+       FP8LM_K_INIT_MASTER = 4, FP8LM_K_COPY = 5, FP8LM_K_SCALARS = 6 /* per-tensor scalar kernels */,
+       FP8LM_K_COUNT = 7 };
 fp8lm_status fp8lm_set_timing(fp8lm_ctx* ctx, int32_t enable);
 fp8lm_status fp8lm_get_timing(fp8lm_ctx* ctx, int32_t* launches /*host[FP8LM_K_COUNT]*/,
                               double* total_ms /*host[FP8LM_K_COUNT]*/);

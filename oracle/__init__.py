@@ -50,7 +50,7 @@ class AutoscaleCfg(C.Structure):
 class AdamHparams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float), ("step", C.c_int64), ("v_scaled", C.c_int32),
-                ("wcopy", C.c_int32)]
+                ("wcopy", C.c_int32), ("m_predict", C.c_int32)]
 
 
 def default_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=100000):
@@ -108,6 +108,8 @@ def lib():
         L.oracle_cast_fp8.restype = None
         L.oracle_cast_fp8.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int,
                                       C.c_void_p, C.c_void_p]
+        L.oracle_cast_fp8_delayed.restype = None
+        L.oracle_cast_fp8_delayed.argtypes = L.oracle_cast_fp8.argtypes
         L.oracle_init_master.restype = None
         L.oracle_init_master.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.oracle_adam_step_fp8.restype = None
@@ -146,6 +148,12 @@ def cast_fp8(src_bf16: np.ndarray, tensors: np.ndarray, dst: np.ndarray, fmt: in
              cfg: AutoscaleCfg) -> None:
     assert src_bf16.dtype == np.uint16 and dst.dtype == np.uint8
     lib().oracle_cast_fp8(_p(src_bf16), _p(tensors), len(tensors), _p(dst), fmt, _p(meta), C.byref(cfg))
+
+
+def cast_fp8_delayed(src_bf16: np.ndarray, tensors: np.ndarray, dst: np.ndarray, fmt: int, meta: np.ndarray,
+                     cfg: AutoscaleCfg) -> None:
+    assert src_bf16.dtype == np.uint16 and dst.dtype == np.uint8
+    lib().oracle_cast_fp8_delayed(_p(src_bf16), _p(tensors), len(tensors), _p(dst), fmt, _p(meta), C.byref(cfg))
 
 
 def init_master(w_bf16: np.ndarray, tensors: np.ndarray, w_f16: np.ndarray, w_meta: np.ndarray) -> None:

@@ -169,6 +169,8 @@ typedef struct {
   int64_t step;        // >= 1
   int32_t v_scaled;    // 1: second moment stored as scaled FP16; 0: plain FP16 (scale 1)
   int32_t wcopy;       // 0: E4M3 weight copy with its own scale; 1: bf16 weight copy
+  int32_t m_predict;   // 0: first-moment scale from the exact amax of the new moment (just-in-time);
+                       // 1: from the bound fma(beta1, amax_deq(m), (1-beta1) * amax_deq(g)), no extra pass
 } oracle_adam_hparams;
 
 // ---- scalar format functions exported for the pins -------------------------------------------
@@ -311,6 +313,56 @@ void oracle_cast_fp8(const uint16_t* src_bf16, const oracle_tensor* tensors, int
   }
 }
 
+// ---- delayed scaling for the gradient cast (Appendix A.2) --------------------------------------
+// The scale comes from the amax values of preceding steps only (the history ring as it stands
+// before this call), so amax and cast need a single pass over the data: the tensor is cast with
+// that scale (saturating: a gradient that grew past the history clips and is counted in n_sat),
+// and this step's amax is pushed into the ring for the steps to come.  An all-zero history (first
+// step) keeps the scale that is already in the metadata.
+void oracle_cast_fp8_delayed(const uint16_t* src_bf16, const oracle_tensor* tensors, int32_t n_tensors,
+                             uint8_t* dst, int fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
+  const int H = clampi(cfg->hist_window, 1, ORACLE_HIST);
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    const int64_t n = tensors[t].numel;
+    if (n == 0) continue;
+    oracle_meta& M = meta[t];
+    // 1. scale from the history before this step
+    uint32_t flags = 0;
+    float Aeff = 0.0f;
+    for (int h = 0; h < H; ++h) Aeff = M.amax_hist[h] > Aeff ? M.amax_hist[h] : Aeff;
+    if (Aeff == 0.0f) {
+      flags |= ORACLE_FLAG_AMAX_ZERO;
+    } else {
+      const int k = pow2_exp(fmax_fp8(fmt), Aeff) + M.mu_exp - cfg->margin;
+      const int e = clampi(k, -126, 126);
+      if (e != k) flags |= ORACLE_FLAG_SCALE_CLAMPED;
+      M.scale = std::ldexp(1.0f, e);
+      M.inv_scale = std::ldexp(1.0f, -e);
+    }
+    // 2. this step's amax, for the history
+    const uint16_t* g = src_bf16 + tensors[t].offset;
+    bool nonfinite = false;
+    float A = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+      const float a = std::fabs(dec_bf16(g[i]));
+      if (!(a <= std::numeric_limits<float>::max())) nonfinite = true;
+      else if (a > A) A = a;
+    }
+    if (nonfinite) {
+      M.amax = std::numeric_limits<float>::infinity();
+      flags |= ORACLE_FLAG_NONFINITE;
+    } else {
+      M.amax = A;
+      const int slot = M.hist_pos % H;
+      M.amax_hist[slot] = A;
+      M.hist_pos = (slot + 1) % H;
+    }
+    M.flags = flags;
+  }
+  // 3. the cast itself, counters and the auto-scaling state: identical to the two-pass path
+  oracle_cast_fp8(src_bf16, tensors, n_tensors, dst, fmt, meta, cfg);
+}
+
 // ---- master-weight initialisation ----------------------------------------------------------------
 // Sec. 2.2: master weights are FP16 with tensor scaling.  The scale leaves one binade of
 // headroom above the initial amax so that weights can grow between scale refreshes.
@@ -437,7 +489,15 @@ void oracle_adam_step_fp8(const oracle_tensor* tensors, int32_t n_tensors,
     // scales for the four writes
     uint32_t fm = 0, fv = 0, fw = 0, fq = 0;
     float sm, ism, sv, isv, sw, isw, sq, isq;
-    refresh_scale(kE4M3.fmax, m_nonfinite ? INF : A_m, 0, m_meta[t].scale, m_meta[t].inv_scale, sm, ism, fm);
+    if (hp->m_predict) {
+      // Single-pass variant (Appendix A.2 names the extra passes as the cost of just-in-time scaling):
+      // |m'| <= beta1 * max|m| + (1-beta1) * max|g|, and with monotone rounding the fp32 value of
+      // that bound is >= every fp32 m', so the E4M3 store cannot clip.
+      const float Bm = std::fmaf(b1, m_meta[t].amax_deq, omb1 * grad_meta[t].amax_deq);
+      refresh_scale(kE4M3.fmax, Bm, 0, m_meta[t].scale, m_meta[t].inv_scale, sm, ism, fm);
+    } else {
+      refresh_scale(kE4M3.fmax, m_nonfinite ? INF : A_m, 0, m_meta[t].scale, m_meta[t].inv_scale, sm, ism, fm);
+    }
     if (hp->v_scaled) {
       const float Ag = grad_meta[t].amax_deq;
       const float Bv = std::fmaf(b2, v_meta[t].amax_deq, omb2 * (Ag * Ag));

@@ -22,12 +22,12 @@ E4M3, E5M2 = 0, 1
 SRC_BF16 = 0
 WCOPY_E4M3, WCOPY_BF16 = 0, 1
 FLAG_NONFINITE, FLAG_AMAX_ZERO, FLAG_SCALE_CLAMPED, FLAG_SATURATED = 1, 2, 4, 8
-K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_COUNT = range(7)
-KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy"]
+K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_COUNT = range(8)
+KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars"]
 
 EXPORTS = [
     "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_meta_init", "fp8lm_amax_scale",
-    "fp8lm_cast_fp8", "fp8lm_init_master", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
+    "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_init_master", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
 
@@ -60,7 +60,7 @@ class AutoscaleCfg(C.Structure):
 class AdamHparams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float), ("step", C.c_int64), ("v_scaled", C.c_int32),
-                ("wcopy", C.c_int32), ("stats", C.c_int32), ("exact", C.c_int32)]
+                ("wcopy", C.c_int32), ("stats", C.c_int32), ("m_predict", C.c_int32), ("exact", C.c_int32)]
 
 
 def autoscale_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=100000) -> AutoscaleCfg:
@@ -68,8 +68,8 @@ def autoscale_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=1
 
 
 def adam_hparams(lr, step, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, v_scaled=1,
-                 wcopy=WCOPY_E4M3, stats=0, exact=1) -> AdamHparams:
-    return AdamHparams(lr, beta1, beta2, eps, weight_decay, step, v_scaled, wcopy, stats, exact)
+                 wcopy=WCOPY_E4M3, stats=0, exact=1, m_predict=0) -> AdamHparams:
+    return AdamHparams(lr, beta1, beta2, eps, weight_decay, step, v_scaled, wcopy, stats, m_predict, exact)
 
 
 class Fp8lmError(RuntimeError):
@@ -99,6 +99,7 @@ def lib() -> C.CDLL:
         L.fp8lm_meta_init.argtypes = [vp, vp, vp, vp]
         L.fp8lm_amax_scale.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, vp]
         L.fp8lm_cast_fp8.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
+        L.fp8lm_cast_fp8_delayed.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
         L.fp8lm_init_master.argtypes = [vp, vp, vp, vp, vp]
         L.fp8lm_adam_step_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fp8lm_copy_bytes.argtypes = [vp, vp, vp, i64, vp]
@@ -197,6 +198,13 @@ class Context:
         self._fits_meta(meta)
         _check(lib().fp8lm_cast_fp8(self._h, _ptr(src), SRC_BF16, _ptr(dst), fmt, _ptr(meta), C.addressof(cfg),
                                     _stream(stream)), "fp8lm_cast_fp8")
+
+    def cast_fp8_delayed(self, src, dst, fmt, meta, cfg, stream=None):
+        assert src.element_size() == 2 and dst.element_size() == 1
+        self._fits(src, dst)
+        self._fits_meta(meta)
+        _check(lib().fp8lm_cast_fp8_delayed(self._h, _ptr(src), SRC_BF16, _ptr(dst), fmt, _ptr(meta),
+                                            C.addressof(cfg), _stream(stream)), "fp8lm_cast_fp8_delayed")
 
     def init_master(self, w_bf16, w_f16, w_meta, stream=None):
         assert w_bf16.element_size() == 2 and w_f16.element_size() == 2

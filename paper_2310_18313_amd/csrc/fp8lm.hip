@@ -50,8 +50,8 @@ struct Scratch {
   struct Pending {
     float sm, ism, sv, isv, sw, isw, sq, isq;
     uint32_t fm, fv, fw, fq;      // flags gathered while choosing the scales
-    float amax_m;
     uint32_t careful;
+    uint32_t pad;
   } pend;
 };
 
@@ -203,12 +203,6 @@ __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
 #ifndef FP8LM_UN_UPDATE
 #define FP8LM_UN_UPDATE 1
 #endif
-#ifndef FP8LM_CAST_ROWS
-#define FP8LM_CAST_ROWS 0
-#endif
-#ifndef FP8LM_NT16
-#define FP8LM_NT16 0      // non-temporal loads of the 16-bit in-place streams when a thread reads 32 contiguous bytes
-#endif
 constexpr bool kNtLoadRO = (FP8LM_NT_MASK & 1) != 0, kNtStoreWO = (FP8LM_NT_MASK & 2) != 0;
 constexpr bool kNtLoadRW = (FP8LM_NT_MASK & 4) != 0, kNtStoreRW = (FP8LM_NT_MASK & 8) != 0;
 
@@ -244,6 +238,29 @@ struct AmaxParams {
   int32_t hist_window;
   int32_t margin;
 };
+
+// Scale of a gradient tensor from the amax history as it stands: the largest of the last H entries,
+// times 2^(mu_exp - margin).  Returns the flags (amax zero / clamped) and leaves the scale alone
+// when the history is all zero.
+__device__ __forceinline__ uint32_t scale_from_history(fp8lm_meta& M, uint32_t fmax_bits, int hist_window, int margin) {
+  const int H = hist_window < 1 ? 1 : (hist_window > FP8LM_HIST ? FP8LM_HIST : hist_window);
+  float Aeff = 0.0f;
+  for (int h = 0; h < H; ++h) Aeff = M.amax_hist[h] > Aeff ? M.amax_hist[h] : Aeff;
+  if (Aeff == 0.0f) return FP8LM_FLAG_AMAX_ZERO;
+  uint32_t flags = 0;
+  const int k = pow2_exp(fmax_bits, Aeff) + M.mu_exp - margin;
+  const int e = k < -126 ? -126 : (k > 126 ? 126 : k);
+  if (e != k) flags |= FP8LM_FLAG_SCALE_CLAMPED;
+  M.scale = pow2f(e);
+  M.inv_scale = pow2f(-e);
+  return flags;
+}
+__device__ __forceinline__ void push_history(fp8lm_meta& M, float A, int hist_window) {
+  const int H = hist_window < 1 ? 1 : (hist_window > FP8LM_HIST ? FP8LM_HIST : hist_window);
+  const int slot = M.hist_pos % H;
+  M.amax_hist[slot] = A;
+  M.hist_pos = (slot + 1) % H;
+}
 
 template <int MODE>
 struct AmaxOp {
@@ -304,22 +321,8 @@ struct AmaxOp {
     M.amax = A;
     uint32_t flags = 0;
     if constexpr (MODE == kAmaxForGradient) {
-      int H = p.hist_window < 1 ? 1 : (p.hist_window > FP8LM_HIST ? FP8LM_HIST : p.hist_window);
-      const int slot = M.hist_pos % H;
-      M.amax_hist[slot] = A;
-      M.hist_pos = (slot + 1) % H;
-      float Aeff = 0.0f;
-      for (int h = 0; h < H; ++h) Aeff = M.amax_hist[h] > Aeff ? M.amax_hist[h] : Aeff;
-      if (Aeff == 0.0f) {
-        flags |= FP8LM_FLAG_AMAX_ZERO;
-      } else {
-        const int k = pow2_exp(p.fmax_bits, Aeff) + M.mu_exp - p.margin;
-        const int e = k < -126 ? -126 : (k > 126 ? 126 : k);
-        if (e != k) flags |= FP8LM_FLAG_SCALE_CLAMPED;
-        M.scale = pow2f(e);
-        M.inv_scale = pow2f(-e);
-      }
-      M.flags = flags;
+      push_history(M, A, p.hist_window);
+      M.flags = scale_from_history(M, p.fmax_bits, p.hist_window, p.margin);
     } else {
       // master weights: one binade of headroom; flags and the rest are completed by the cast pass
       if (A == 0.0f) {
@@ -350,28 +353,42 @@ struct CastParams {
   uint8_t* dst;
   fp8lm_meta* meta;
   int32_t sat_num, sat_den, ramp_steps;
+  int32_t hist_window;   // delayed scaling only
 };
 
 // number of zero bytes among the four 7-bit fields of x (each byte of x must be <= 0x7F)
 __device__ __forceinline__ uint32_t nonzero_bytes7(uint32_t x) { return __popc((x + 0x7F7F7F7Fu) & 0x80808080u); }
 
-template <int FMT>
+// DELAYED: the scale was fixed from the amax history before the launch (Appendix A.2, delayed
+// scaling); this pass also measures the amax of the source for the history, and since no amax pass
+// has looked for inf/NaN it checks every 16-element group itself.
+template <int FMT, bool DELAYED>
 struct CastOp {
   const CastParams& p;
   const Tables& tb;
   float scale;
   bool careful;
+  uint32_t amax16;        // DELAYED: two 16-bit running maxima of (bits & 0x7FFF)
   float vmax;             // max |clamped scaled value|
   uint32_t n_elems;       // elements seen (full groups * 16 + tails) since the last flush
   uint32_t nz_top;        // codes whose magnitude differs from the top code
   uint32_t nz_code;       // codes with non-zero magnitude
   uint32_t z_in;          // inputs that are +-0
   __device__ CastOp(const CastParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
-  __device__ __forceinline__ void reset() { vmax = 0.0f; n_elems = nz_top = nz_code = z_in = 0; }
+  __device__ __forceinline__ void reset() { vmax = 0.0f; n_elems = nz_top = nz_code = z_in = 0; amax16 = 0; }
   __device__ __forceinline__ void begin(int t, const TensorDesc&) {
     scale = p.meta[t].scale;
-    careful = (p.meta[t].flags & FP8LM_FLAG_NONFINITE) != 0;
+    careful = !DELAYED && (p.meta[t].flags & FP8LM_FLAG_NONFINITE) != 0;
     reset();
+  }
+  // DELAYED: folds one group's source bits into the running amax; true if the group holds inf or NaN
+  __device__ __forceinline__ bool note_source(const uint4& a, const uint4& b) {
+    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    ushort2_t gm = __builtin_bit_cast(ushort2_t, w[0] & 0x7FFF7FFFu);
+#pragma unroll
+    for (int j = 1; j < 8; ++j) gm = __builtin_elementwise_max(gm, __builtin_bit_cast(ushort2_t, w[j] & 0x7FFF7FFFu));
+    amax16 = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, amax16), gm));
+    return (gm.x > gm.y ? gm.x : gm.y) >= 0x7F80u;
   }
   __device__ __forceinline__ uint32_t quad(uint32_t w0, uint32_t w1) {
     const float f0 = bf16lo_to_f32(w0), f1 = bf16hi_to_f32(w0), f2 = bf16lo_to_f32(w1), f3 = bf16hi_to_f32(w1);
@@ -400,31 +417,12 @@ struct CastOp {
     z_in += (f == 0.0f);
     nz_code += (c & 0x7Fu) != 0;
     nz_top += (c & 0x7Fu) != Fp8Traits<FMT>::kTop;
+    if constexpr (DELAYED) amax16 = max(amax16 & 0xFFFFu, bits & 0x7FFFu) | (amax16 & 0xFFFF0000u);
     return c;
   }
   __device__ __forceinline__ bool fast() const { return !careful; }
   template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
     uint4 a[UN], b[UN];
-#if FP8LM_CAST_ROWS
-    // each load instruction of a wavefront covers 1 KiB contiguous; a thread takes elements
-    // [8t, 8t+8) and [2048+8t, 2048+8t+8) of the tile and writes two 8-byte pieces
-    const long long pos = pos0 + threadIdx.x * 8;
-#pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      a[u] = ld16<kNtLoadRO>(p.src + pos + u * kTile);
-      b[u] = ld16<kNtLoadRO>(p.src + pos + u * kTile + kTile / 2);
-    }
-#pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      uint2 lo, hi;
-      lo.x = quad(a[u].x, a[u].y);
-      lo.y = quad(a[u].z, a[u].w);
-      hi.x = quad(b[u].x, b[u].y);
-      hi.y = quad(b[u].z, b[u].w);
-      *reinterpret_cast<uint2*>(p.dst + pos + u * kTile) = lo;
-      *reinterpret_cast<uint2*>(p.dst + pos + u * kTile + kTile / 2) = hi;
-    }
-#else
     const long long pos = pos0 + threadIdx.x * kGroup;
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
@@ -433,6 +431,19 @@ struct CastOp {
     }
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
+      if constexpr (DELAYED) {
+        if (note_source(a[u], b[u])) {   // rare: this group holds inf/NaN, encode it element by element
+          const uint32_t w[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
+          const uint32_t keep = amax16;
+          uint4 o = make_uint4(0, 0, 0, 0);
+          uint32_t* ow = &o.x;
+#pragma unroll
+          for (int j = 0; j < 16; ++j) ow[j >> 2] |= one((w[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu) << ((j & 3) * 8);
+          amax16 = keep;
+          st16<kNtStoreWO>(p.dst + pos + u * kTile, o);
+          continue;
+        }
+      }
       uint4 o;
       o.x = quad(a[u].x, a[u].y);
       o.y = quad(a[u].z, a[u].w);
@@ -440,7 +451,6 @@ struct CastOp {
       o.w = quad(b[u].z, b[u].w);
       st16<kNtStoreWO>(p.dst + pos + u * kTile, o);
     }
-#endif
     n_elems += UN * kGroup;
   }
   __device__ __forceinline__ void group(long long pos, int valid) {
@@ -448,8 +458,9 @@ struct CastOp {
     n_elems += valid;
   }
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<1, 2> s;
+    BlockStats<2, 2> s;
     s.mx[0] = f2u(vmax);
+    s.mx[1] = max(amax16 & 0xFFFFu, amax16 >> 16);
     s.ct[0] = n_elems - nz_top;                 // codes on the top magnitude
     s.ct[1] = (n_elems - nz_code) - z_in;       // zero codes that did not come from zero inputs
     s.orv = 0;
@@ -457,12 +468,24 @@ struct CastOp {
     if (threadIdx.x == 0) {
       Scratch* sc = tb.scratch + t;
       atomic_max_u32(&sc->max_a, s.mx[0]);
+      atomic_max_u32(&sc->max_b, s.mx[1]);
       atomic_add_u64(&sc->cnt[0], s.ct[0]);
       atomic_add_u64(&sc->cnt[1], s.ct[1]);
       if (publish_ticket(sc, done, d.n_chunks)) {
         const float vm = u2f(take_u32(&sc->max_a));
+        const uint32_t abits = take_u32(&sc->max_b);
         const unsigned long long n_sat = take_u64(&sc->cnt[0]), n_und = take_u64(&sc->cnt[1]);
         take_u32(&sc->ticket);
+        if constexpr (DELAYED) {
+          fp8lm_meta& M = p.meta[t];
+          if (abits >= 0x7F80u) {
+            M.amax = __builtin_inff();
+            M.flags |= FP8LM_FLAG_NONFINITE;
+          } else {
+            M.amax = u2f(abits << 16);
+            push_history(M, M.amax, p.hist_window);
+          }
+        }
         finish(t, d, vm, n_sat, n_und);
       }
     }
@@ -483,10 +506,18 @@ struct CastOp {
   }
 };
 
-template <int FMT>
+template <int FMT, bool DELAYED>
 __global__ __launch_bounds__(kThreads) void cast_kernel(Tables tb, CastParams p) {
-  CastOp<FMT> op(p, tb);
+  CastOp<FMT, DELAYED> op(p, tb);
   walk_chunks<FP8LM_UN_CAST>(tb, op);
+}
+
+// Delayed scaling, step 1: one thread per tensor fixes the scale from the history before the cast.
+__global__ void delayed_scale_kernel(const TensorDesc* desc, fp8lm_meta* meta, int n, uint32_t fmax_bits,
+                                     int hist_window, int margin) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n || desc[t].numel == 0) return;
+  meta[t].flags = scale_from_history(meta[t], fmax_bits, hist_window, margin);
 }
 
 // ================================================================================================
@@ -585,6 +616,55 @@ __device__ __forceinline__ void refresh_scale(uint32_t fmax_bits, float bound, i
   inv = pow2f(-e);
 }
 
+// Chooses the scales of the four buffers the update pass writes, from a bound on the new first moment
+// (its exact amax, or the predicted bound) and the metadata of the inputs; decides whether the tensor
+// may take the fast update path.
+template <int WCOPY>
+__device__ void adam_choose_scales(const AdamParams& p, Scratch::Pending& P, int t, float bound_m) {
+  const fp8lm_meta& G = p.grad_meta[t];
+  const fp8lm_meta& Mm = p.m_meta[t];
+  const fp8lm_meta& Mv = p.v_meta[t];
+  const fp8lm_meta& Mw = p.w_meta[t];
+  const fp8lm_meta& Mq = p.wcopy_meta[t];
+  uint32_t fm = 0, fv = 0, fw = 0, fq = 0;
+  refresh_scale(kBitsE4M3Max, bound_m, 0, Mm.scale, Mm.inv_scale, P.sm, P.ism, fm);
+  if (p.v_scaled) {
+    const float Ag = G.amax_deq;
+    const float Bv = __builtin_fmaf(p.b2, Mv.amax_deq, p.omb2 * (Ag * Ag));
+    refresh_scale(kBitsF16Max, Bv, 0, Mv.scale, Mv.inv_scale, P.sv, P.isv, fv);
+  } else {
+    P.sv = 1.0f;
+    P.isv = 1.0f;
+  }
+  refresh_scale(kBitsF16Max, Mw.amax_deq, 1, Mw.scale, Mw.inv_scale, P.sw, P.isw, fw);
+  if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
+    refresh_scale(kBitsE4M3Max, Mw.amax_deq, 0, Mq.scale, Mq.inv_scale, P.sq, P.isq, fq);
+  } else {
+    P.sq = 1.0f;
+    P.isq = 1.0f;
+  }
+  P.fm = fm; P.fv = fv; P.fw = fw; P.fq = fq;
+  // The fast update path assumes that no NaN and no fp32 overflow can occur.  That holds when every
+  // input magnitude is moderate; anything else takes the careful path, which checks every element.
+  const float kBig = 1.0995116e12f;     // 2^40
+  const float kHuge = 1.2089258e24f;    // 2^80
+  const uint32_t anyflag = (G.flags | Mm.flags | Mv.flags | Mw.flags) & FP8LM_FLAG_NONFINITE;
+  const bool calm = !anyflag && (bound_m < kBig) && (G.amax_deq < kBig) && (Mm.amax_deq < kBig) &&
+                    (Mv.amax_deq < kHuge) && (Mw.amax_deq < kHuge);
+  P.careful = calm ? 0u : 1u;
+}
+
+// Single-pass variant: the first-moment scale comes from the bound
+// fma(beta1, amax_deq(m), (1-beta1) * amax_deq(g)) >= every new |m| (monotone rounding), so no pass
+// over the data is needed before the update.  One thread per tensor.
+template <int WCOPY>
+__global__ void adam_predict_scales_kernel(Tables tb, AdamParams p, int n) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n || tb.desc[t].numel == 0) return;
+  const float Bm = __builtin_fmaf(p.b1, p.m_meta[t].amax_deq, p.omb1 * p.grad_meta[t].amax_deq);
+  adam_choose_scales<WCOPY>(p, tb.scratch[t].pend, t, Bm);
+}
+
 // ---- pass A: exact amax of the new first moment, then all four scales ---------------------------
 template <int GFMT, int WCOPY>
 struct AdamAmaxOp {
@@ -647,42 +727,8 @@ struct AdamAmaxOp {
     }
   }
   __device__ void finish(int t, uint32_t abits) {
-    Scratch::Pending& P = tb.scratch[t].pend;
-    const fp8lm_meta& G = p.grad_meta[t];
-    const fp8lm_meta& Mm = p.m_meta[t];
-    const fp8lm_meta& Mv = p.v_meta[t];
-    const fp8lm_meta& Mw = p.w_meta[t];
-    const fp8lm_meta& Mq = p.wcopy_meta[t];
     const bool m_nonfinite = abits >= 0x7F800000u;
-    const float A_m = m_nonfinite ? __builtin_inff() : u2f(abits);
-    uint32_t fm = 0, fv = 0, fw = 0, fq = 0;
-    refresh_scale(kBitsE4M3Max, A_m, 0, Mm.scale, Mm.inv_scale, P.sm, P.ism, fm);
-    float Bv = 0.0f;
-    if (p.v_scaled) {
-      const float Ag = G.amax_deq;
-      Bv = __builtin_fmaf(p.b2, Mv.amax_deq, p.omb2 * (Ag * Ag));
-      refresh_scale(kBitsF16Max, Bv, 0, Mv.scale, Mv.inv_scale, P.sv, P.isv, fv);
-    } else {
-      P.sv = 1.0f;
-      P.isv = 1.0f;
-    }
-    refresh_scale(kBitsF16Max, Mw.amax_deq, 1, Mw.scale, Mw.inv_scale, P.sw, P.isw, fw);
-    if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
-      refresh_scale(kBitsE4M3Max, Mw.amax_deq, 0, Mq.scale, Mq.inv_scale, P.sq, P.isq, fq);
-    } else {
-      P.sq = 1.0f;
-      P.isq = 1.0f;
-    }
-    P.fm = fm; P.fv = fv; P.fw = fw; P.fq = fq;
-    P.amax_m = A_m;
-    // The fast update path assumes that no NaN and no fp32 overflow can occur.  That holds when every
-    // input magnitude is moderate; anything else takes the careful path, which checks every element.
-    const float kBig = 1.0995116e12f;     // 2^40
-    const float kHuge = 1.2089258e24f;    // 2^80
-    const uint32_t anyflag = (G.flags | Mm.flags | Mv.flags | Mw.flags) & FP8LM_FLAG_NONFINITE;
-    const bool calm = !anyflag && !m_nonfinite && (A_m < kBig) && (G.amax_deq < kBig) &&
-                      (Mv.amax_deq < kHuge) && (Mw.amax_deq < kHuge);
-    P.careful = calm ? 0u : 1u;
+    adam_choose_scales<WCOPY>(p, tb.scratch[t].pend, t, m_nonfinite ? __builtin_inff() : u2f(abits));
   }
 };
 
@@ -773,6 +819,7 @@ struct AdamUpdateOp {
       const float w1 = adam_update<FAST>(m1, v1, w0, p);
       vmax = fmaxf(vmax, v1);
       wmax = fmaxf(wmax, fabsf(w1));
+      mmax = fmaxf(mmax, fabsf(m1));
       tm[j] = m1 * sm;
       tv[j] = v1 * sv;
       tw[j] = w1 * sw;
@@ -930,9 +977,7 @@ struct AdamUpdateOp {
 
   __device__ void finish(int t, float A_v, float A_w, float A_mc, uint32_t nfb, const unsigned long long* c) {
     const Scratch::Pending& P = tb.scratch[t].pend;
-    // first moment: on the fast path its amax is the one pass A measured
-    const bool m_bad = (P.fm & FP8LM_FLAG_NONFINITE) != 0;
-    const float A_m = m_bad ? A_mc : P.amax_m;
+    const float A_m = A_mc;    // measured by this pass on both paths (equals what pass A saw)
     uint32_t m_nf = nfb & 3u;
     auto enc8 = [](float x) { return encode1_fp8<kE4M3>(x); };
     auto dec8 = [](uint32_t cc) { return fp8_to_f32<kE4M3>(cc); };
@@ -1234,12 +1279,41 @@ fp8lm_status fp8lm_cast_fp8(fp8lm_ctx* c, const void* src, fp8lm_src src_type, u
   if (!src || !dst || !meta) return FP8LM_ERR_INVALID_ARGUMENT;
   if (!aligned16(src) || !aligned16(dst)) return FP8LM_ERR_MISALIGNED;
   DeviceGuard guard(c->device);
-  CastParams p{static_cast<const uint16_t*>(src), dst, meta, cfg->sat_num, cfg->sat_den, cfg->ramp_steps};
+  CastParams p{static_cast<const uint16_t*>(src), dst, meta, cfg->sat_num, cfg->sat_den, cfg->ramp_steps,
+               cfg->hist_window};
   Timed tm(c, (hipStream_t)stream, FP8LM_K_CAST);
   if (fmt == FP8LM_E4M3)
-    hipLaunchKernelGGL(cast_kernel<kE4M3>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
+    hipLaunchKernelGGL((cast_kernel<kE4M3, false>), dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream,
+                       tables_of(c), p);
   else
-    hipLaunchKernelGGL(cast_kernel<kE5M2>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
+    hipLaunchKernelGGL((cast_kernel<kE5M2, false>), dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream,
+                       tables_of(c), p);
+  return after_launch();
+}
+
+fp8lm_status fp8lm_cast_fp8_delayed(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
+                                    fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {
+  if (!c || !cfg_ok(cfg) || src_type != FP8LM_SRC_BF16 || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2))
+    return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_chunks == 0) return FP8LM_OK;
+  if (!src || !dst || !meta) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!aligned16(src) || !aligned16(dst)) return FP8LM_ERR_MISALIGNED;
+  DeviceGuard guard(c->device);
+  hipStream_t s = (hipStream_t)stream;
+  {
+    Timed tm(c, s, FP8LM_K_SCALARS);
+    hipLaunchKernelGGL(delayed_scale_kernel, dim3((c->n_tensors + 255) / 256), dim3(256), 0, s, c->d_desc, meta,
+                       c->n_tensors, fmt == FP8LM_E4M3 ? kBitsE4M3Max : kBitsE5M2Max, cfg->hist_window, cfg->margin);
+  }
+  fp8lm_status st = after_launch();
+  if (st != FP8LM_OK) return st;
+  CastParams p{static_cast<const uint16_t*>(src), dst, meta, cfg->sat_num, cfg->sat_den, cfg->ramp_steps,
+               cfg->hist_window};
+  Timed tm(c, s, FP8LM_K_CAST);
+  if (fmt == FP8LM_E4M3)
+    hipLaunchKernelGGL((cast_kernel<kE4M3, true>), dim3(grid_of(c)), dim3(kThreads), 0, s, tables_of(c), p);
+  else
+    hipLaunchKernelGGL((cast_kernel<kE5M2, true>), dim3(grid_of(c)), dim3(kThreads), 0, s, tables_of(c), p);
   return after_launch();
 }
 
@@ -1296,7 +1370,12 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
   const dim3 g(grid_of(c)), b(kThreads);
   const Tables tb = tables_of(c);
   const bool e5 = grad_fmt == FP8LM_E5M2, q8 = hp->wcopy == FP8LM_WCOPY_E4M3;
-  {
+  if (hp->m_predict) {
+    Timed tm(c, s, FP8LM_K_SCALARS);
+    const dim3 gs((c->n_tensors + 255) / 256), bs(256);
+    if (q8) hipLaunchKernelGGL((adam_predict_scales_kernel<FP8LM_WCOPY_E4M3>), gs, bs, 0, s, tb, p, c->n_tensors);
+    else hipLaunchKernelGGL((adam_predict_scales_kernel<FP8LM_WCOPY_BF16>), gs, bs, 0, s, tb, p, c->n_tensors);
+  } else {
     Timed tm(c, s, FP8LM_K_ADAM_AMAX);
     if (e5 && q8) hipLaunchKernelGGL((adam_amax_kernel<kE5M2, FP8LM_WCOPY_E4M3>), g, b, 0, s, tb, p);
     else if (e5) hipLaunchKernelGGL((adam_amax_kernel<kE5M2, FP8LM_WCOPY_BF16>), g, b, 0, s, tb, p);

@@ -56,11 +56,19 @@ class OptimizerState:
         self.ctx.amax_scale(grad_bf16, self.grad_fmt, self.g_meta, self.cfg)
         self.ctx.cast_fp8(grad_bf16, self.g8, self.grad_fmt, self.g_meta, self.cfg)
 
+    def quantize_grad_delayed(self, grad_bf16: torch.Tensor) -> None:
+        """Single pass: scale from the amax history, cast, and record this step's amax."""
+        self.ctx.cast_fp8_delayed(grad_bf16, self.g8, self.grad_fmt, self.g_meta, self.cfg)
+
     def adam(self, hp: B.AdamHparams) -> None:
         self.ctx.adam_step_fp8(self.g8, self.grad_fmt, self.g_meta, self.m, self.m_meta, self.v, self.v_meta,
                                self.w, self.w_meta, self.wq, self.q_meta, hp)
 
-    def step(self, grad_bf16: torch.Tensor, hp: B.AdamHparams) -> None:
-        """One pass of the whole hot path: amax + scale, FP8 cast, FP8 Adam."""
-        self.quantize_grad(grad_bf16)
+    def step(self, grad_bf16: torch.Tensor, hp: B.AdamHparams, delayed: bool = False) -> None:
+        """One pass of the whole hot path: amax + scale, FP8 cast, FP8 Adam.  With `delayed` the
+        gradient is quantised in a single pass with the scale of the preceding steps."""
+        if delayed:
+            self.quantize_grad_delayed(grad_bf16)
+        else:
+            self.quantize_grad(grad_bf16)
         self.adam(hp)

@@ -50,7 +50,8 @@ def oracle_cfg(cfg: B.AutoscaleCfg) -> O.AutoscaleCfg:
 
 
 def oracle_hp(hp: B.AdamHparams) -> O.AdamHparams:
-    return O.AdamHparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.step, hp.v_scaled, hp.wcopy)
+    return O.AdamHparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.step, hp.v_scaled, hp.wcopy,
+                         hp.m_predict)
 
 
 class Snapshot:
@@ -75,7 +76,8 @@ ALL_FIELDS = ["scale", "inv_scale", "amax", "amax_deq", "amax_hist", "hist_pos",
               "flags", "n_sat", "n_underflow"]
 
 
-def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool = False) -> dict:
+def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool = False,
+               delayed: bool = False) -> dict:
     """Runs the oracle on the snapshots and compares with the GPU state after the step."""
     cfg = oracle_cfg(st.cfg)
     ohp = oracle_hp(hp) if hp is not None else None
@@ -90,8 +92,11 @@ def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool
         tens = O.tensors_array([(0, s.n)])
         g_meta = s.metas["g_meta"].copy()
         g8 = np.zeros(s.src.size, dtype=np.uint8)
-        O.amax_scale(s.src, tens, st.grad_fmt, g_meta, cfg)
-        O.cast_fp8(s.src, tens, g8, st.grad_fmt, g_meta, cfg)
+        if delayed:
+            O.cast_fp8_delayed(s.src, tens, g8, st.grad_fmt, g_meta, cfg)
+        else:
+            O.amax_scale(s.src, tens, st.grad_fmt, g_meta, cfg)
+            O.cast_fp8(s.src, tens, g8, st.grad_fmt, g_meta, cfg)
         gpu_g8 = _host_bits(st.g8, s.off, s.n)
         assert np.array_equal(gpu_g8, g8[:s.n]), f"{tag}: FP8 gradient codes differ"
         if s.n:

@@ -258,3 +258,34 @@ def test_heavy_tailed_gradients_drive_the_mu_state_machine():
 def test_amax_history_window_carries_across_steps():
     wl = synth.Workload("hist", synth.gpt_layout(128, 2, 512, 500), lr=3e-4, sigma=None, hist_window=4)
     run_lockstep(wl, seed=9, steps=6)
+
+
+# ---- single-pass variants: delayed gradient scaling and predicted first-moment scale ------------------
+@pytest.mark.parametrize("grad_fmt", [B.E5M2, B.E4M3])
+@pytest.mark.parametrize("m_predict", [0, 1])
+def test_delayed_scaling_and_predicted_moment_scale(grad_fmt, m_predict):
+    for wl in (synth.workload("tiny"), synth.Workload("mid", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-3, sigma=None,
+                                                      hist_window=2, ramp_steps=6)):
+        st, w0 = P.make_state(wl, 11, grad_fmt)
+        ids = list(range(wl.layout.n_tensors))
+        grad = torch.zeros(max(wl.layout.total, 16), dtype=torch.bfloat16, device=DEV)
+        for step in range(1, 8):
+            synth.fill_gradients(grad, wl, 11, step)
+            if step == 4:
+                grad *= 4                                    # outgrows the history: the delayed cast clips
+            if step == 6:
+                bits = synth.bits16(grad).copy()
+                off0, n0 = wl.layout.tensors()[0]
+                bits[off0 + 5] = 0x7FC0                      # a NaN and an infinity nobody announced
+                bits[off0 + n0 - 1] = 0xFF80
+                grad = bf16_tensor_from_bits(bits)
+            delayed = step > 1                               # the first step seeds the history just in time
+            hp = B.adam_hparams(wl.lr, step, stats=1, m_predict=m_predict)
+            snaps = [P.Snapshot(st, grad, t) for t in ids]
+            say(f"{wl.name} fmt={grad_fmt} m_predict={m_predict} step={step} delayed={delayed}")
+            st.step(grad, hp, delayed=delayed)
+            torch.cuda.synchronize()
+            r = P.check_step(st, snaps, hp, what=f"{wl.name} variants step {step}", delayed=delayed)
+            assert r["m_diff"] == 0 and r["w_diff"] == 0 and r["q_diff"] == 0
+            if step == 4:
+                assert B.meta_to_numpy(st.g_meta, len(ids))["n_sat"].sum() > 0

@@ -1,0 +1,136 @@
+"""Pins for the single-pass variants of the oracle (CPU only): delayed scaling of the gradient cast
+(Appendix A.2) and the predicted scale of the first moment.  Checked against brute-force encoders,
+the two-pass path, float64 AdamW and the invariants that define the variants."""
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2310_18313_amd import synth
+from test_oracle_steps import State, _adamw64_step, bf16_bits, bf16_vals, dec8, ragged_case
+
+
+def _grad(lay, rng, sig):
+    bits = np.zeros(lay.total, dtype=np.uint16)
+    for (off, n), s in zip(lay.tensors(), sig):
+        bits[off:off + n] = bf16_bits(rng.standard_normal(n) * s)
+    return bits
+
+
+@pytest.mark.parametrize("fmt,fmax,mid", [(O.E5M2, 57344.0, 53248.0), (O.E4M3, 448.0, 432.0)])
+def test_delayed_cast_uses_the_previous_amax_and_saturates(fmt, fmax, mid):
+    lay, tens, g1 = ragged_case(seed=1)
+    cfg = O.default_cfg()
+    meta = O.new_meta(lay.n_tensors, cfg)
+    q = np.zeros(lay.total, dtype=np.uint8)
+    # empty history: the scale in the metadata is kept
+    O.cast_fp8_delayed(g1, tens, q, fmt, meta, cfg)
+    live = np.array(lay.numels) > 0
+    assert np.all(meta["scale"][live] == 1.0) and np.all(meta["flags"][live] & O.FLAG_AMAX_ZERO)
+    a1 = np.array([np.abs(bf16_vals(g1[o:o + n])).max() if n else 0 for o, n in lay.tensors()], dtype=np.float32)
+    assert np.array_equal(meta["amax"][live], a1[live]) and np.array_equal(meta["amax_hist"][live, 0], a1[live])
+    # second step: four times larger gradients are cast with the scale that fitted the first ones
+    g2 = bf16_bits(bf16_vals(g1) * np.float32(4.0))
+    O.cast_fp8_delayed(g2, tens, q, fmt, meta, cfg)
+    for t, (off, n) in enumerate(lay.tensors()):
+        if n == 0:
+            continue
+        s = float(meta[t]["scale"])
+        assert s * a1[t] <= fmax < 2 * s * a1[t]                       # the just-in-time scale of step 1
+        y = bf16_vals(g2[off:off + n]) * np.float32(s)
+        assert np.array_equal(q[off:off + n], O.encode_fp8_nearest(fmt, y))  # nearest code, clipped at the top
+        top = (np.abs(y) >= mid) if fmt == O.E4M3 else (np.abs(y) > mid)
+        assert meta[t]["n_sat"] == np.count_nonzero(top) and meta[t]["n_sat"] >= 1
+        assert meta[t]["amax"] == 4 * a1[t] and meta[t]["amax_hist"][0] == 4 * a1[t]
+        assert meta[t]["amax_deq"] == np.float32(fmax / s)
+    # third step with the same data: now the history covers it and nothing clips
+    before = meta["scale"].copy()
+    O.cast_fp8_delayed(g2, tens, q, fmt, meta, cfg)
+    for t, (off, n) in enumerate(lay.tensors()):
+        if n == 0:
+            continue
+        # the amax grew fourfold, so the scale drops by 4, times the auto-scaling factor chosen after the clipping
+        mu = 2.0 ** float(np.log2(meta[t]["scale"]) - np.log2(before[t]) + 2)
+        assert mu in (0.5, 1.0)
+        y = bf16_vals(g2[off:off + n]) * meta[t]["scale"]
+        assert np.abs(y).max() <= fmax
+
+
+def test_delayed_cast_history_window_and_nonfinite():
+    lay = synth.flat_layout(500)
+    tens = O.tensors_array(lay.tensors())
+    cfg = O.default_cfg(hist_window=3)
+    meta = O.new_meta(1, cfg)
+    q = np.zeros(lay.total, dtype=np.uint8)
+    scales = []
+    for a in [1.0, 0.01, 0.01, 0.01, 0.01]:
+        src = np.zeros(lay.total, dtype=np.uint16)
+        src[:500] = bf16_bits(np.full(500, a))
+        O.cast_fp8_delayed(src, tens, q, O.E4M3, meta, cfg)
+        scales.append(float(meta["scale"][0]))
+    # call k sees the amax values of calls < k: [], [1], [1,.01], [1,.01,.01], [.01,.01,.01]
+    assert scales[0] == 1.0 and scales[1] in (256.0, 128.0) and scales[2] == scales[1] == scales[3]
+    assert scales[4] >= 2.0 ** 14
+    src[7] = 0x7F80
+    hist = meta["amax_hist"].copy()
+    O.cast_fp8_delayed(src, tens, q, O.E4M3, meta, cfg)
+    assert meta["flags"][0] & O.FLAG_NONFINITE and np.isinf(meta["amax"][0])
+    assert np.array_equal(meta["amax_hist"], hist) and q[7] == 0x7E
+
+
+def test_predicted_first_moment_scale_never_clips_and_leaves_v_w_untouched():
+    wl = synth.workload("tiny")
+    lay = wl.layout
+    rng = np.random.default_rng(3)
+    wbits = _grad(lay, rng, [0.02] * 6)
+    jit, pre = State(lay, wbits), State(lay, wbits)
+    sig = [1e-3, 1e-2, 3e-5, 1.0, 1.0, 2e-4]
+    b1, b2 = float(np.float32(0.9)), float(np.float32(0.95))
+    lr, eps, wd = float(np.float32(1e-3)), float(np.float32(1e-8)), float(np.float32(0.1))
+    looser = 0
+    for t in range(1, 9):
+        g = _grad(lay, rng, sig)
+        before = [pre.values(k) if n else None for k, (o, n) in enumerate(lay.tensors())]
+        jit.step(g, O.AdamHparams(lr, b1, b2, eps, wd, t, 1, O.WCOPY_E4M3, 0))
+        pre.step(g, O.AdamHparams(lr, b1, b2, eps, wd, t, 1, O.WCOPY_E4M3, 1))
+        # the update uses the fp32 moment, so the first moment's storage scale cannot touch v or w ...
+        assert np.array_equal(jit.v, pre.v)
+        if t == 1:
+            assert np.array_equal(jit.w, pre.w) and np.array_equal(jit.wq, pre.wq)
+        for k, (off, n) in enumerate(lay.tensors()):
+            if n == 0:
+                continue
+            after = pre.values(k)
+            m1, _, _ = _adamw64_step(after["g"], before[k]["m"], before[k]["v"], before[k]["w"], lr, b1, b2, eps, wd, t)
+            sm = float(pre.m_meta[k]["scale"])
+            assert np.abs(m1).max() * sm <= 448.0 * (1 + 1e-6)                    # the bound holds: no clipping
+            tol = np.maximum(np.abs(m1) * 2.0 ** -4, 2.0 ** -10 / sm) * (1 + 1e-5)
+            assert np.all(np.abs(after["m"] - m1) <= tol)                         # nearest code under the used scale
+            assert float(pre.m_meta[k]["amax_deq"]) == np.float32(np.abs(after["m"]).max())
+            assert float(pre.m_meta[k]["amax"]) == np.float32(np.abs(m1).max()) or \
+                abs(float(pre.m_meta[k]["amax"]) - np.abs(m1).max()) <= 1e-6 * np.abs(m1).max()
+            # never tighter than needed, and looser than just-in-time by whole binades only
+            ratio = np.log2(float(jit.m_meta[k]["scale"]) / sm) if t == 1 else None
+            if ratio is not None:
+                assert ratio >= 0 and ratio == int(ratio)
+                looser += int(ratio > 0)
+    # ... but from step 2 on the stored moments differ, so the two trajectories drift apart slowly
+    assert not np.array_equal(jit.m, pre.m) or looser == 0
+
+
+def test_predicted_scale_equals_just_in_time_when_the_bound_is_attained():
+    """One element holds both the largest old moment and the largest gradient with equal signs: the
+    bound is the new amax itself (same fp32 operations), so both modes choose the same scale."""
+    n = 300
+    lay = synth.flat_layout(n)
+    rng = np.random.default_rng(4)
+    wbits = np.zeros(lay.total, dtype=np.uint16)
+    sts = [State(lay, wbits), State(lay, wbits)]
+    for t in range(1, 5):
+        x = rng.uniform(-0.25, 0.25, n)
+        x[11] = 1.0                                        # always the largest, always positive
+        g = np.zeros(lay.total, dtype=np.uint16)
+        g[:n] = bf16_bits(x * 1e-3)
+        for mode, st in enumerate(sts):
+            st.step(g, O.AdamHparams(1e-3, 0.9, 0.95, 1e-8, 0.0, t, 1, O.WCOPY_E4M3, mode))
+        assert sts[0].m_meta[0]["scale"] == sts[1].m_meta[0]["scale"]
+        assert np.array_equal(sts[0].m, sts[1].m)
