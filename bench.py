@@ -131,6 +131,8 @@ def main() -> int:
     ap.add_argument("--path", choices=["jit", "single"], default="jit",
                     help="jit: amax pass + cast + two-pass Adam (19 B/param, the headline path); single: delayed "
                          "gradient scaling + predicted first-moment scale (one pass each, 15 B/param)")
+    ap.add_argument("--allreduce-steps", type=int, default=0, metavar="N",
+                    help="also time the shared-scale re-quantise kernel and the N-rank FP8 sum (Eq. 4-6) on this layout")
     ap.add_argument("--no-spread", action="store_true", help="allocate the buffers plainly, one after the other")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -229,8 +231,31 @@ def main() -> int:
         n, ms = st.ctx.get_timing()["copy"]
         st.ctx.set_timing(False)
         out["copy_kernel_GBps"] = round(2 * nbytes / (ms / n * 1e-3) / 1e9, 1)
+    if args.allreduce_steps:
+        N = args.allreduce_steps
+        ranks = [st.g8] + [st.g8.clone() for _ in range(N - 1)]
+        metas = [st.g_meta] * N
+        shared = st.ctx.shared_scale(metas)
+        summed = torch.zeros_like(st.g8)
+        out_meta = st.ctx.new_meta(cfg)
+        st.ctx.set_timing(True)
+        st.ctx.get_timing()
+        for _ in range(5):
+            st.ctx.requantize_fp8(ranks[0], B.E5M2, st.g_meta, shared, summed, out_meta)
+            st.ctx.sum_fp8(ranks, B.E5M2, shared, summed, out_meta, cfg)
+        tm = st.ctx.get_timing()
+        st.ctx.set_timing(False)
+        rq, sm = tm["requantize"][1] / tm["requantize"][0], tm["sum"][1] / tm["sum"][0]
+        extra = {"ranks": N,
+                 "requantize": {"avg_ms": round(rq, 4), "bytes_per_param": 2, "GBps": round(2 * P / (rq * 1e-3) / 1e9, 1)},
+                 "sum": {"avg_ms": round(sm, 4), "bytes_per_param": N + 1, "GBps": round((N + 1) * P / (sm * 1e-3) / 1e9, 1)}}
+        del ranks, summed
+    else:
+        extra = None
     del st, grad
     torch.cuda.empty_cache()
+    if extra:
+        out["allreduce_steps"] = extra
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.seed)
     print(json.dumps(out), flush=True)

@@ -175,6 +175,38 @@ fp8lm_status fp8lm_cast_fp8_delayed(fp8lm_ctx* ctx, const void* src /*device*/, 
                                     const fp8lm_autoscale_cfg* cfg /*host*/, void* stream);
 
 /*
+ * The three steps around the FP8 gradient all-reduce of Sec. 2.1 (Eq. 4-6), as one GPU can run them;
+ * the collectives themselves are not part of this library.  n_ranks <= 8.
+ *
+ * Eq. 4: shared[t] = min over r of metas[r][t].scale.
+ *   metas  : host array of n_ranks device pointers, each to a meta array [n_tensors];
+ *   shared : device array [n_tensors], written.
+ */
+fp8lm_status fp8lm_shared_scale(fp8lm_ctx* ctx, const fp8lm_meta* const* metas /*host -> device*/, int32_t n_ranks,
+                                float* shared /*device*/, void* stream);
+/*
+ * Eq. 5: dst[i] = FP8(shared[t] * (src[i] / src_meta[t].scale)), round to nearest even.  Both scales are
+ * powers of two and shared <= scale, so this is an exponent shift: nothing saturates, values that
+ * fall below the format's range lose bits or become zero (n_underflow).  dst may be src (in place);
+ * dst_meta must not be src_meta.  Writes dst_meta[t].{scale = shared, inv_scale, amax, amax_deq, n_sat,
+ * n_underflow, flags}; the auto-scaling fields are left alone.
+ */
+fp8lm_status fp8lm_requantize_fp8(fp8lm_ctx* ctx, const uint8_t* src /*device*/, fp8lm_fmt fmt,
+                                  const fp8lm_meta* src_meta /*device*/, const float* shared /*device*/,
+                                  uint8_t* dst /*device*/, fp8lm_meta* dst_meta /*device*/, void* stream);
+/*
+ * Eq. 6 as a sum all-reduce would leave it on every rank: dst[i] = FP8(payloads[0][i] + ... +
+ * payloads[N-1][i]), added in rank order in fp32 and rounded once (nearest even, saturating).  All
+ * payloads carry the shared scale; dst_meta[t].scale = N * shared[t], so dst / scale is the mean
+ * gradient.  Also writes amax (of the sum, in value units), amax_deq, n_sat, n_underflow, flags, and
+ * advances the auto-scaling state of dst_meta with n_sat as fp8lm_cast_fp8 does.
+ *   payloads : host array of n_ranks device pointers to flat FP8 buffers (read only).
+ */
+fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* ctx, const uint8_t* const* payloads /*host -> device*/, int32_t n_ranks,
+                           fp8lm_fmt fmt, const float* shared /*device*/, uint8_t* dst /*device*/,
+                           fp8lm_meta* dst_meta /*device*/, const fp8lm_autoscale_cfg* cfg /*host*/, void* stream);
+
+/*
  * Master-weight initialisation (Sec. 2.2: FP16 master weights with tensor scaling).
  * For every tensor: scale = 2^(k - 1) with k the largest integer such that 2^k * max|w| <= 65504,
  * w_f16[i] = FP16(scale * w_bf16[i]) (round to nearest even, saturating).  Fills w_meta[t].
@@ -219,7 +251,7 @@ fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* ctx, const void* src /*device*/, void* 
  * duration in milliseconds since timing was enabled, then resets the sums.                       */
 enum { FP8LM_K_AMAX = 0, FP8LM_K_CAST = 1, FP8LM_K_ADAM_AMAX = 2, FP8LM_K_ADAM_UPDATE = 3,
        FP8LM_K_INIT_MASTER = 4, FP8LM_K_COPY = 5, FP8LM_K_SCALARS = 6 /* per-tensor scalar kernels */,
-       FP8LM_K_COUNT = 7 };
+       FP8LM_K_REQUANT = 7, FP8LM_K_SUM = 8, FP8LM_K_COUNT = 9 };
 fp8lm_status fp8lm_set_timing(fp8lm_ctx* ctx, int32_t enable);
 fp8lm_status fp8lm_get_timing(fp8lm_ctx* ctx, int32_t* launches /*host[FP8LM_K_COUNT]*/,
                               double* total_ms /*host[FP8LM_K_COUNT]*/);

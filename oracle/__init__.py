@@ -110,6 +110,14 @@ def lib():
                                       C.c_void_p, C.c_void_p]
         L.oracle_cast_fp8_delayed.restype = None
         L.oracle_cast_fp8_delayed.argtypes = L.oracle_cast_fp8.argtypes
+        L.oracle_shared_scale.restype = None
+        L.oracle_shared_scale.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+        L.oracle_requantize_fp8.restype = None
+        L.oracle_requantize_fp8.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                            C.c_void_p, C.c_void_p]
+        L.oracle_sum_fp8.restype = None
+        L.oracle_sum_fp8.argtypes = [C.c_void_p, C.c_int32, C.c_int, C.c_void_p, C.c_void_p, C.c_int32,
+                                     C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_init_master.restype = None
         L.oracle_init_master.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.oracle_adam_step_fp8.restype = None
@@ -154,6 +162,29 @@ def cast_fp8_delayed(src_bf16: np.ndarray, tensors: np.ndarray, dst: np.ndarray,
                      cfg: AutoscaleCfg) -> None:
     assert src_bf16.dtype == np.uint16 and dst.dtype == np.uint8
     lib().oracle_cast_fp8_delayed(_p(src_bf16), _p(tensors), len(tensors), _p(dst), fmt, _p(meta), C.byref(cfg))
+
+
+def _ptr_array(arrays):
+    arr = (C.c_void_p * len(arrays))(*[a.ctypes.data for a in arrays])
+    return arr
+
+
+def shared_scale(metas, n_tensors: int) -> np.ndarray:
+    """Eq. 4: per tensor, the smallest scale among the ranks' meta arrays."""
+    out = np.zeros(n_tensors, dtype=np.float32)
+    lib().oracle_shared_scale(_ptr_array(metas), len(metas), n_tensors, _p(out))
+    return out
+
+
+def requantize_fp8(src, fmt, src_meta, shared, tensors, dst, dst_meta) -> None:
+    assert src.dtype == np.uint8 and dst.dtype == np.uint8 and shared.dtype == np.float32
+    lib().oracle_requantize_fp8(_p(src), fmt, _p(src_meta), _p(shared), _p(tensors), len(tensors), _p(dst), _p(dst_meta))
+
+
+def sum_fp8(payloads, fmt, shared, tensors, dst, dst_meta, cfg) -> None:
+    assert all(a.dtype == np.uint8 for a in payloads) and dst.dtype == np.uint8
+    lib().oracle_sum_fp8(_ptr_array(payloads), len(payloads), fmt, _p(shared), _p(tensors), len(tensors), _p(dst),
+                         _p(dst_meta), C.byref(cfg))
 
 
 def init_master(w_bf16: np.ndarray, tensors: np.ndarray, w_f16: np.ndarray, w_meta: np.ndarray) -> None:

@@ -363,6 +363,95 @@ void oracle_cast_fp8_delayed(const uint16_t* src_bf16, const oracle_tensor* tens
   oracle_cast_fp8(src_bf16, tensors, n_tensors, dst, fmt, meta, cfg);
 }
 
+// ---- shared-scale re-quantisation and the FP8 gradient sum (Sec. 2.1, Eq. 4-6) -------------------
+// Eq. 4: the shared scale of a tensor is the smallest of the ranks' scales.
+void oracle_shared_scale(const oracle_meta* const* metas, int32_t n_ranks, int32_t n_tensors, float* shared) {
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    float s = metas[0][t].scale;
+    for (int32_t r = 1; r < n_ranks; ++r) s = metas[r][t].scale < s ? metas[r][t].scale : s;
+    shared[t] = s;
+  }
+}
+
+// Eq. 5: g'' = FP8(s_g * (g' / s')).  Scales are powers of two and s_g <= s', so the value only moves
+// down in exponent: nothing can saturate, small values may fall into the subnormals or to zero.
+void oracle_requantize_fp8(const uint8_t* src, int fmt, const oracle_meta* src_meta, const float* shared,
+                           const oracle_tensor* tensors, int32_t n_tensors, uint8_t* dst, oracle_meta* dst_meta) {
+  const uint32_t top = maxcode_fp8(fmt);
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    const int64_t n = tensors[t].numel;
+    if (n == 0) continue;
+    const int64_t off = tensors[t].offset;
+    const float sg = shared[t];
+    oracle_meta& M = dst_meta[t];
+    uint64_t n_sat = 0, n_under = 0;
+    float stored = 0.0f;
+    bool nonfinite = false;
+    for (int64_t i = 0; i < n; ++i) {
+      const float value = dec_fp8(fmt, src[off + i]) * src_meta[t].inv_scale;   // g' / s'
+      const uint8_t c = enc_fp8(fmt, value * sg);
+      dst[off + i] = c;
+      const float d = std::fabs(dec_fp8(fmt, c));
+      if (d == d && d > stored) stored = d;
+      if (!(std::fabs(value) <= std::numeric_limits<float>::max())) nonfinite = true;
+      if ((c & 0x7Fu) == top) ++n_sat;
+      if (value != 0.0f && (c & 0x7Fu) == 0) ++n_under;
+    }
+    const float inv = 1.0f / sg;           // exact: sg is a power of two
+    M.scale = sg;
+    M.inv_scale = inv;
+    M.amax = nonfinite ? std::numeric_limits<float>::infinity() : src_meta[t].amax;
+    M.amax_deq = stored * inv;
+    M.n_sat = n_sat;
+    M.n_underflow = n_under;
+    M.flags = (nonfinite ? ORACLE_FLAG_NONFINITE : 0u) | (n_sat ? ORACLE_FLAG_SATURATED : 0u);
+  }
+}
+
+// Eq. 6: g = g''_1 + ... + g''_N with scale N * s_g.  The payloads are added in rank order in an fp32
+// accumulator and rounded once to FP8 (nearest even, saturating): sums that leave the FP8 range clip,
+// which is what the auto-scaling statistic of Sec. 2.1 watches.
+void oracle_sum_fp8(const uint8_t* const* payloads, int32_t n_ranks, int fmt, const float* shared,
+                    const oracle_tensor* tensors, int32_t n_tensors, uint8_t* dst, oracle_meta* dst_meta,
+                    const oracle_autoscale_cfg* cfg) {
+  const uint32_t top = maxcode_fp8(fmt);
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    const int64_t n = tensors[t].numel;
+    if (n == 0) continue;
+    const int64_t off = tensors[t].offset;
+    oracle_meta& M = dst_meta[t];
+    uint64_t n_sat = 0, n_under = 0;
+    float stored = 0.0f, amax = 0.0f;
+    bool nonfinite = false;
+    for (int64_t i = 0; i < n; ++i) {
+      float acc = 0.0f;
+      for (int32_t r = 0; r < n_ranks; ++r) acc = acc + dec_fp8(fmt, payloads[r][off + i]);
+      const uint8_t c = enc_fp8(fmt, acc);
+      dst[off + i] = c;
+      const float d = std::fabs(dec_fp8(fmt, c));
+      if (d == d && d > stored) stored = d;
+      const float a = std::fabs(acc);
+      if (!(a <= std::numeric_limits<float>::max())) nonfinite = true; else if (a > amax) amax = a;
+      if ((c & 0x7Fu) == top) ++n_sat;
+      if (acc != 0.0f && (c & 0x7Fu) == 0) ++n_under;
+    }
+    const float s = float(n_ranks) * shared[t];
+    M.scale = s;
+    M.inv_scale = 1.0f / s;
+    M.amax = nonfinite ? std::numeric_limits<float>::infinity() : amax * M.inv_scale;
+    M.amax_deq = stored * M.inv_scale;
+    M.n_sat = n_sat;
+    M.n_underflow = n_under;
+    M.flags = (nonfinite ? ORACLE_FLAG_NONFINITE : 0u) | (n_sat ? ORACLE_FLAG_SATURATED : 0u);
+    const int R = cfg->ramp_steps < 2 ? 2 : cfg->ramp_steps;
+    const bool overflow = int64_t(n_sat) * int64_t(cfg->sat_den) > n * int64_t(cfg->sat_num);
+    if (overflow) M.clean_steps = 0;
+    else M.clean_steps = M.clean_steps + 1 > R ? R : M.clean_steps + 1;
+    const int ramp = (2 * M.clean_steps) / R;
+    M.mu_exp = -1 + (ramp > 2 ? 2 : ramp);
+  }
+}
+
 // ---- master-weight initialisation ----------------------------------------------------------------
 // Sec. 2.2: master weights are FP16 with tensor scaling.  The scale leaves one binade of
 // headroom above the initial amax so that weights can grow between scale refreshes.

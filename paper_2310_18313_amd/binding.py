@@ -22,12 +22,13 @@ E4M3, E5M2 = 0, 1
 SRC_BF16 = 0
 WCOPY_E4M3, WCOPY_BF16 = 0, 1
 FLAG_NONFINITE, FLAG_AMAX_ZERO, FLAG_SCALE_CLAMPED, FLAG_SATURATED = 1, 2, 4, 8
-K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_COUNT = range(8)
-KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars"]
+K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_REQUANT, K_SUM, K_COUNT = range(10)
+KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars", "requantize", "sum"]
 
 EXPORTS = [
     "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_meta_init", "fp8lm_amax_scale",
-    "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_init_master", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
+    "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
+    "fp8lm_init_master", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
 
@@ -101,6 +102,9 @@ def lib() -> C.CDLL:
         L.fp8lm_cast_fp8.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
         L.fp8lm_cast_fp8_delayed.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
         L.fp8lm_init_master.argtypes = [vp, vp, vp, vp, vp]
+        L.fp8lm_shared_scale.argtypes = [vp, vp, i32, vp, vp]
+        L.fp8lm_requantize_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp]
+        L.fp8lm_sum_fp8.argtypes = [vp, vp, i32, C.c_int, vp, vp, vp, vp, vp]
         L.fp8lm_adam_step_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fp8lm_copy_bytes.argtypes = [vp, vp, vp, i64, vp]
         L.fp8lm_set_timing.argtypes = [vp, i32]
@@ -205,6 +209,32 @@ class Context:
         self._fits_meta(meta)
         _check(lib().fp8lm_cast_fp8_delayed(self._h, _ptr(src), SRC_BF16, _ptr(dst), fmt, _ptr(meta),
                                             C.addressof(cfg), _stream(stream)), "fp8lm_cast_fp8_delayed")
+
+    def shared_scale(self, metas, stream=None) -> torch.Tensor:
+        """Eq. 4: per-tensor minimum of the ranks' scales; returns a device fp32 array [n_tensors]."""
+        self._fits_meta(*metas)
+        out = torch.empty(max(1, self.n_tensors), dtype=torch.float32, device=f"cuda:{self.device}")
+        ptrs = (C.c_void_p * len(metas))(*[_ptr(m) for m in metas])
+        _check(lib().fp8lm_shared_scale(self._h, C.cast(ptrs, C.c_void_p), len(metas), _ptr(out), _stream(stream)),
+               "fp8lm_shared_scale")
+        return out
+
+    def requantize_fp8(self, src, fmt, src_meta, shared, dst, dst_meta, stream=None):
+        assert src.element_size() == 1 and dst.element_size() == 1 and shared.dtype == torch.float32
+        self._fits(src, dst)
+        self._fits_meta(src_meta, dst_meta)
+        assert shared.numel() >= self.n_tensors
+        _check(lib().fp8lm_requantize_fp8(self._h, _ptr(src), fmt, _ptr(src_meta), _ptr(shared), _ptr(dst),
+                                          _ptr(dst_meta), _stream(stream)), "fp8lm_requantize_fp8")
+
+    def sum_fp8(self, payloads, fmt, shared, dst, dst_meta, cfg, stream=None):
+        assert all(p.element_size() == 1 for p in payloads) and dst.element_size() == 1
+        self._fits(dst, *payloads)
+        self._fits_meta(dst_meta)
+        assert shared.dtype == torch.float32 and shared.numel() >= self.n_tensors
+        ptrs = (C.c_void_p * len(payloads))(*[_ptr(p) for p in payloads])
+        _check(lib().fp8lm_sum_fp8(self._h, C.cast(ptrs, C.c_void_p), len(payloads), fmt, _ptr(shared), _ptr(dst),
+                                   _ptr(dst_meta), C.addressof(cfg), _stream(stream)), "fp8lm_sum_fp8")
 
     def init_master(self, w_bf16, w_f16, w_meta, stream=None):
         assert w_bf16.element_size() == 2 and w_f16.element_size() == 2

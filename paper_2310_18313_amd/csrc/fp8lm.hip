@@ -348,6 +348,17 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(Tables tb, AmaxParams p)
 // ================================================================================================
 // Kernel 2: scaled saturating FP8 cast + auto-scaling state (Sec. 2.1; Appendix A.1)
 // ================================================================================================
+// The auto-scaling state machine of Sec. 2.1 (text after Eq. 3), shared by the cast and the sum.
+__device__ __forceinline__ void autoscale_update(fp8lm_meta& M, unsigned long long n_sat, long long numel, int sat_num,
+                                                 int sat_den, int ramp_steps) {
+  const int R = ramp_steps < 2 ? 2 : ramp_steps;
+  const bool overflow = (long long)n_sat * (long long)sat_den > numel * (long long)sat_num;
+  const int clean = overflow ? 0 : (M.clean_steps + 1 > R ? R : M.clean_steps + 1);
+  M.clean_steps = clean;
+  const int ramp = (2 * clean) / R;
+  M.mu_exp = -1 + (ramp > 2 ? 2 : ramp);
+}
+
 struct CastParams {
   const uint16_t* src;
   uint8_t* dst;
@@ -496,13 +507,7 @@ struct CastOp {
     M.n_underflow = n_und;
     M.amax_deq = fp8_to_f32<FMT>(encode1_fp8<FMT>(vm)) * M.inv_scale;
     M.flags = n_sat ? (M.flags | FP8LM_FLAG_SATURATED) : (M.flags & ~FP8LM_FLAG_SATURATED);
-    // auto-scaling state machine (Sec. 2.1, paragraph after Eq. 3)
-    const int R = p.ramp_steps < 2 ? 2 : p.ramp_steps;
-    const bool overflow = (long long)n_sat * (long long)p.sat_den > d.numel * (long long)p.sat_num;
-    int clean = overflow ? 0 : (M.clean_steps + 1 > R ? R : M.clean_steps + 1);
-    M.clean_steps = clean;
-    const int ramp = (2 * clean) / R;
-    M.mu_exp = -1 + (ramp > 2 ? 2 : ramp);
+    autoscale_update(M, n_sat, d.numel, p.sat_num, p.sat_den, p.ramp_steps);
   }
 };
 
@@ -518,6 +523,222 @@ __global__ void delayed_scale_kernel(const TensorDesc* desc, fp8lm_meta* meta, i
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= n || desc[t].numel == 0) return;
   meta[t].flags = scale_from_history(meta[t], fmax_bits, hist_window, margin);
+}
+
+// ================================================================================================
+// Shared-scale re-quantisation and the FP8 gradient sum (Sec. 2.1, Eq. 4-6)
+// ================================================================================================
+constexpr int kMaxRanks = 8;
+struct RankMetas { const fp8lm_meta* m[kMaxRanks]; int32_t n_ranks; };
+struct RankPayloads { const uint8_t* p[kMaxRanks]; int32_t n_ranks; };
+
+// Eq. 4: one thread per tensor takes the smallest scale among the ranks.
+__global__ void shared_scale_kernel(RankMetas rm, int n, float* shared) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n) return;
+  float s = rm.m[0][t].scale;
+  for (int r = 1; r < rm.n_ranks; ++r) s = rm.m[r][t].scale < s ? rm.m[r][t].scale : s;
+  shared[t] = s;
+}
+
+struct RequantParams {
+  const uint8_t* src;
+  const fp8lm_meta* src_meta;
+  const float* shared;
+  uint8_t* dst;
+  fp8lm_meta* dst_meta;
+};
+
+// Eq. 5: dst = FP8(s_g * (src / s')).  Both scales are powers of two with s_g <= s': an exponent shift
+// that can only lose bits at the bottom of the range.
+template <int FMT>
+struct RequantOp {
+  const RequantParams& p;
+  const Tables& tb;
+  float inv_src, sg;
+  bool careful;
+  float vmax;
+  uint32_t n_elems, nz_top, nz_code, nz_in, nonfinite;
+  __device__ RequantOp(const RequantParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
+  __device__ __forceinline__ void begin(int t, const TensorDesc&) {
+    inv_src = p.src_meta[t].inv_scale;
+    sg = p.shared[t];
+    careful = (p.src_meta[t].flags & FP8LM_FLAG_NONFINITE) != 0;
+    vmax = 0.0f;
+    n_elems = nz_top = nz_code = nz_in = nonfinite = 0;
+  }
+  __device__ __forceinline__ bool fast() const { return !careful; }
+  __device__ __forceinline__ uint32_t word(uint32_t w) {
+    const float2_t a = fp8x2_to_f32<FMT, false>(w), b = fp8x2_to_f32<FMT, true>(w);
+    const float y0 = (a.x * inv_src) * sg, y1 = (a.y * inv_src) * sg, y2 = (b.x * inv_src) * sg, y3 = (b.y * inv_src) * sg;
+    vmax = fmaxf(fmaxf(vmax, fmaxf(fabsf(y0), fabsf(y1))), fmaxf(fabsf(y2), fabsf(y3)));
+    const uint32_t c = encode4_fp8<FMT>(y0, y1, y2, y3);
+    const uint32_t mag = c & 0x7F7F7F7Fu;
+    nz_in += nonzero_bytes7(w & 0x7F7F7F7Fu);
+    nz_code += nonzero_bytes7(mag);
+    nz_top += nonzero_bytes7(mag ^ Fp8Traits<FMT>::kTopX4);
+    return c;
+  }
+  template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
+    uint4 a[UN];
+    const long long pos = pos0 + threadIdx.x * kGroup;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) a[u] = ld16<false>(p.src + pos + u * kTile);   // may be in place: cached loads
+#pragma unroll
+    for (int u = 0; u < UN; ++u) st16<false>(p.dst + pos + u * kTile, make_uint4(word(a[u].x), word(a[u].y), word(a[u].z), word(a[u].w)));
+    n_elems += UN * kGroup;
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    for (int j = 0; j < valid; ++j) {
+      const uint32_t in = p.src[pos + j];
+      const float y = (fp8_to_f32<FMT>(in) * inv_src) * sg;
+      const uint32_t c = encode1_fp8_careful<FMT>(y);
+      if (y == y) vmax = fmaxf(vmax, fabsf(clamp_fp8<FMT>(y)));
+      nonfinite |= !(fabsf(y) <= 3.4028234663852886e38f);
+      nz_in += (in & 0x7Fu) != 0;
+      nz_code += (c & 0x7Fu) != 0;
+      nz_top += (c & 0x7Fu) != Fp8Traits<FMT>::kTop;
+      p.dst[pos + j] = (uint8_t)c;
+    }
+    n_elems += valid;
+  }
+  __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
+    BlockStats<1, 2> s;
+    s.mx[0] = f2u(vmax);
+    s.ct[0] = n_elems - nz_top;
+    s.ct[1] = nz_in - nz_code;                 // non-zero codes in, zero codes out (a NaN code is non-zero on both sides)
+    s.orv = nonfinite;
+    block_combine(s);
+    if (threadIdx.x == 0) {
+      Scratch* sc = tb.scratch + t;
+      atomic_max_u32(&sc->max_a, s.mx[0]);
+      atomic_add_u64(&sc->cnt[0], s.ct[0]);
+      atomic_add_u64(&sc->cnt[1], s.ct[1]);
+      atomic_or_u32(&sc->nf, s.orv);
+      if (publish_ticket(sc, done, d.n_chunks)) {
+        const float vm = u2f(take_u32(&sc->max_a));
+        const unsigned long long n_sat = take_u64(&sc->cnt[0]), n_und = take_u64(&sc->cnt[1]);
+        const uint32_t nf = take_u32(&sc->nf);
+        take_u32(&sc->ticket);
+        fp8lm_meta& M = p.dst_meta[t];
+        const float src_amax = p.src_meta[t].amax;
+        const float inv = 1.0f / sg;
+        M.scale = sg;
+        M.inv_scale = inv;
+        M.amax = nf ? __builtin_inff() : src_amax;
+        M.amax_deq = fp8_to_f32<FMT>(encode1_fp8<FMT>(vm)) * inv;
+        M.n_sat = n_sat;
+        M.n_underflow = n_und;
+        M.flags = (nf ? FP8LM_FLAG_NONFINITE : 0u) | (n_sat ? FP8LM_FLAG_SATURATED : 0u);
+      }
+    }
+  }
+};
+
+template <int FMT>
+__global__ __launch_bounds__(kThreads) void requantize_kernel(Tables tb, RequantParams p) {
+  RequantOp<FMT> op(p, tb);
+  walk_chunks<2>(tb, op);
+}
+
+struct SumParams {
+  RankPayloads in;
+  const float* shared;
+  uint8_t* dst;
+  fp8lm_meta* dst_meta;
+  int32_t sat_num, sat_den, ramp_steps;
+};
+
+// Eq. 6 on one GPU: the payloads of all ranks (same shared scale) are added in rank order in fp32 and
+// rounded once to FP8, saturating; the result carries the scale N * s_g.
+template <int FMT>
+struct SumOp {
+  const SumParams& p;
+  const Tables& tb;
+  float vmax;
+  uint32_t amax_bits, n_elems, n_top, n_und;
+  __device__ SumOp(const SumParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
+  __device__ __forceinline__ void begin(int, const TensorDesc&) { vmax = 0.0f; amax_bits = n_elems = n_top = n_und = 0; }
+  __device__ __forceinline__ bool fast() const { return true; }
+  __device__ __forceinline__ uint32_t finish_one(float acc) {
+    const uint32_t c = encode1_fp8_careful<FMT>(acc);
+    amax_bits = max(amax_bits, f2u(acc) & 0x7FFFFFFFu);
+    if (acc == acc) vmax = fmaxf(vmax, fabsf(clamp_fp8<FMT>(acc)));
+    n_top += (c & 0x7Fu) == Fp8Traits<FMT>::kTop;
+    n_und += (acc != 0.0f) && ((c & 0x7Fu) == 0);
+    return c;
+  }
+  template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
+    static_assert(UN == 1, "one group at a time");
+    const long long pos = pos0 + threadIdx.x * kGroup;
+    float acc[kGroup];
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j) acc[j] = 0.0f;
+    for (int r = 0; r < p.in.n_ranks; ++r) {
+      const uint4 a = ld16<kNtLoadRO>(p.in.p[r] + pos);
+      const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float2_t lo = fp8x2_to_f32<FMT, false>(w[k]), hi = fp8x2_to_f32<FMT, true>(w[k]);
+        acc[4 * k + 0] = acc[4 * k + 0] + lo.x;
+        acc[4 * k + 1] = acc[4 * k + 1] + lo.y;
+        acc[4 * k + 2] = acc[4 * k + 2] + hi.x;
+        acc[4 * k + 3] = acc[4 * k + 3] + hi.y;
+      }
+    }
+    uint32_t o[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j) o[j >> 2] |= finish_one(acc[j]) << ((j & 3) * 8);
+    st16<kNtStoreWO>(p.dst + pos, make_uint4(o[0], o[1], o[2], o[3]));
+    n_elems += kGroup;
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    for (int j = 0; j < valid; ++j) {
+      float acc = 0.0f;
+      for (int r = 0; r < p.in.n_ranks; ++r) acc = acc + fp8_to_f32<FMT>(p.in.p[r][pos + j]);
+      p.dst[pos + j] = (uint8_t)finish_one(acc);
+    }
+    n_elems += valid;
+  }
+  __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
+    BlockStats<2, 2> s;
+    s.mx[0] = f2u(vmax);
+    s.mx[1] = amax_bits;
+    s.ct[0] = n_top;
+    s.ct[1] = n_und;
+    s.orv = 0;
+    block_combine(s);
+    if (threadIdx.x == 0) {
+      Scratch* sc = tb.scratch + t;
+      atomic_max_u32(&sc->max_a, s.mx[0]);
+      atomic_max_u32(&sc->max_b, s.mx[1]);
+      atomic_add_u64(&sc->cnt[0], s.ct[0]);
+      atomic_add_u64(&sc->cnt[1], s.ct[1]);
+      if (publish_ticket(sc, done, d.n_chunks)) {
+        const float vm = u2f(take_u32(&sc->max_a));
+        const uint32_t ab = take_u32(&sc->max_b);
+        const unsigned long long n_sat = take_u64(&sc->cnt[0]), n_under = take_u64(&sc->cnt[1]);
+        take_u32(&sc->ticket);
+        fp8lm_meta& M = p.dst_meta[t];
+        const float sc_out = (float)p.in.n_ranks * p.shared[t];
+        const bool nf = ab >= 0x7F800000u;
+        M.scale = sc_out;
+        M.inv_scale = 1.0f / sc_out;
+        M.amax = nf ? __builtin_inff() : u2f(ab) * M.inv_scale;
+        M.amax_deq = fp8_to_f32<FMT>(encode1_fp8<FMT>(vm)) * M.inv_scale;
+        M.n_sat = n_sat;
+        M.n_underflow = n_under;
+        M.flags = (nf ? FP8LM_FLAG_NONFINITE : 0u) | (n_sat ? FP8LM_FLAG_SATURATED : 0u);
+        autoscale_update(M, n_sat, d.numel, p.sat_num, p.sat_den, p.ramp_steps);
+      }
+    }
+  }
+};
+
+template <int FMT>
+__global__ __launch_bounds__(kThreads) void sum_fp8_kernel(Tables tb, SumParams p) {
+  SumOp<FMT> op(p, tb);
+  walk_chunks<1>(tb, op);
 }
 
 // ================================================================================================
@@ -1314,6 +1535,66 @@ fp8lm_status fp8lm_cast_fp8_delayed(fp8lm_ctx* c, const void* src, fp8lm_src src
     hipLaunchKernelGGL((cast_kernel<kE4M3, true>), dim3(grid_of(c)), dim3(kThreads), 0, s, tables_of(c), p);
   else
     hipLaunchKernelGGL((cast_kernel<kE5M2, true>), dim3(grid_of(c)), dim3(kThreads), 0, s, tables_of(c), p);
+  return after_launch();
+}
+
+fp8lm_status fp8lm_shared_scale(fp8lm_ctx* c, const fp8lm_meta* const* metas, int32_t n_ranks, float* shared,
+                                void* stream) {
+  if (!c || !metas || n_ranks < 1 || n_ranks > kMaxRanks) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_tensors == 0) return FP8LM_OK;
+  if (!shared) return FP8LM_ERR_INVALID_ARGUMENT;
+  RankMetas rm{};
+  rm.n_ranks = n_ranks;
+  for (int r = 0; r < n_ranks; ++r) {
+    if (!metas[r]) return FP8LM_ERR_INVALID_ARGUMENT;
+    rm.m[r] = metas[r];
+  }
+  DeviceGuard guard(c->device);
+  Timed tm(c, (hipStream_t)stream, FP8LM_K_SCALARS);
+  hipLaunchKernelGGL(shared_scale_kernel, dim3((c->n_tensors + 255) / 256), dim3(256), 0, (hipStream_t)stream, rm,
+                     c->n_tensors, shared);
+  return after_launch();
+}
+
+fp8lm_status fp8lm_requantize_fp8(fp8lm_ctx* c, const uint8_t* src, fp8lm_fmt fmt, const fp8lm_meta* src_meta,
+                                  const float* shared, uint8_t* dst, fp8lm_meta* dst_meta, void* stream) {
+  if (!c || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2)) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_chunks == 0) return FP8LM_OK;
+  if (!src || !src_meta || !shared || !dst || !dst_meta || src_meta == dst_meta) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!aligned16(src) || !aligned16(dst)) return FP8LM_ERR_MISALIGNED;
+  DeviceGuard guard(c->device);
+  RequantParams p{src, src_meta, shared, dst, dst_meta};
+  Timed tm(c, (hipStream_t)stream, FP8LM_K_REQUANT);
+  if (fmt == FP8LM_E4M3)
+    hipLaunchKernelGGL(requantize_kernel<kE4M3>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
+  else
+    hipLaunchKernelGGL(requantize_kernel<kE5M2>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
+  return after_launch();
+}
+
+fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* c, const uint8_t* const* payloads, int32_t n_ranks, fp8lm_fmt fmt,
+                           const float* shared, uint8_t* dst, fp8lm_meta* dst_meta, const fp8lm_autoscale_cfg* cfg,
+                           void* stream) {
+  if (!c || !cfg_ok(cfg) || !payloads || n_ranks < 1 || n_ranks > kMaxRanks || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2))
+    return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_chunks == 0) return FP8LM_OK;
+  if (!shared || !dst || !dst_meta) return FP8LM_ERR_INVALID_ARGUMENT;
+  SumParams p{};
+  p.in.n_ranks = n_ranks;
+  for (int r = 0; r < n_ranks; ++r) {
+    if (!payloads[r]) return FP8LM_ERR_INVALID_ARGUMENT;
+    if (!aligned16(payloads[r])) return FP8LM_ERR_MISALIGNED;
+    p.in.p[r] = payloads[r];
+  }
+  if (!aligned16(dst)) return FP8LM_ERR_MISALIGNED;
+  p.shared = shared; p.dst = dst; p.dst_meta = dst_meta;
+  p.sat_num = cfg->sat_num; p.sat_den = cfg->sat_den; p.ramp_steps = cfg->ramp_steps;
+  DeviceGuard guard(c->device);
+  Timed tm(c, (hipStream_t)stream, FP8LM_K_SUM);
+  if (fmt == FP8LM_E4M3)
+    hipLaunchKernelGGL(sum_fp8_kernel<kE4M3>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
+  else
+    hipLaunchKernelGGL(sum_fp8_kernel<kE5M2>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
   return after_launch();
 }
 

@@ -289,3 +289,70 @@ def test_delayed_scaling_and_predicted_moment_scale(grad_fmt, m_predict):
             assert r["m_diff"] == 0 and r["w_diff"] == 0 and r["q_diff"] == 0
             if step == 4:
                 assert B.meta_to_numpy(st.g_meta, len(ids))["n_sat"].sum() > 0
+
+
+# ---- shared-scale re-quantisation and the FP8 sum (Sec. 2.1, Eq. 4-6) on one GPU -------------------------
+@pytest.mark.parametrize("fmt", [B.E5M2, B.E4M3])
+def test_shared_scale_requantize_and_sum(fmt):
+    n_ranks = 4
+    wl = synth.Workload("ranks", synth.Layout(["a", "b", "c", "d", "e", "f", "g"], [70001, 1, 4096, 333, 0, 16385, 300000]),
+                        lr=1e-3, sigma=None)
+    lay = wl.layout
+    cfg = B.autoscale_cfg(ramp_steps=20)
+    ocfg = P.oracle_cfg(cfg)
+    ctx = B.Context(lay.tensors())
+    tens = O.tensors_array(lay.tensors())
+    nt = lay.n_tensors
+    d_q, d_meta, h_q, h_meta = [], [], [], []
+    for r in range(n_ranks):
+        grad = torch.zeros(lay.total, dtype=torch.bfloat16, device=DEV)
+        synth.fill_gradients(grad, wl, 20 + r, 1)
+        grad *= [1.0, 0.25, 8.0, 0.01][r]
+        if r == 2:
+            bits = synth.bits16(grad).copy()
+            bits[lay.offsets[0] + 9] = 0x7FC0            # rank 2 contributes a NaN in tensor 0
+            grad = bf16_tensor_from_bits(bits)
+        meta = ctx.new_meta(cfg)
+        q = torch.zeros(lay.total, dtype=torch.uint8, device=DEV)
+        ctx.amax_scale(grad, fmt, meta, cfg)
+        ctx.cast_fp8(grad, q, fmt, meta, cfg)
+        d_q.append(q); d_meta.append(meta)
+    torch.cuda.synchronize()
+    h_q = [q.cpu().numpy() for q in d_q]
+    h_meta = [B.meta_to_numpy(m, nt) for m in d_meta]
+    say(f"requantize/sum fmt={fmt}")
+    shared = ctx.shared_scale(d_meta)
+    ref_shared = O.shared_scale(h_meta, nt)
+    assert np.array_equal(shared.cpu().numpy()[:nt], ref_shared)
+    d_rq, h_rq = [], []
+    for r in range(n_ranks):
+        out_meta = ctx.new_meta(cfg)
+        before = B.meta_to_numpy(out_meta, nt)
+        dst = d_q[r].clone() if r % 2 else torch.zeros_like(d_q[r])
+        ctx.requantize_fp8(dst if r % 2 else d_q[r], fmt, d_meta[r], shared, dst, out_meta)     # odd ranks: in place
+        torch.cuda.synchronize()
+        ref = np.zeros(lay.total, dtype=np.uint8)
+        ref_meta = before.copy()
+        O.requantize_fp8(h_q[r], fmt, h_meta[r], ref_shared, tens, ref, ref_meta)
+        got = dst.cpu().numpy()
+        for t, (off, n) in enumerate(lay.tensors()):
+            assert np.array_equal(got[off:off + n], ref[off:off + n]), (r, t)
+            diff = P.meta_equal(B.meta_to_numpy(out_meta, nt)[t], ref_meta[t], P.ALL_FIELDS)
+            assert not diff, (r, t, diff, B.meta_to_numpy(out_meta, nt)[t], ref_meta[t])
+        d_rq.append(dst); h_rq.append(ref)
+    for ranks in (n_ranks, 1, 3):
+        out = torch.zeros(lay.total, dtype=torch.uint8, device=DEV)
+        out_meta = ctx.new_meta(cfg)
+        ref_meta = B.meta_to_numpy(out_meta, nt)
+        ctx.sum_fp8(d_rq[:ranks], fmt, shared, out, out_meta, cfg)
+        torch.cuda.synchronize()
+        ref = np.zeros(lay.total, dtype=np.uint8)
+        O.sum_fp8(h_rq[:ranks], fmt, ref_shared, tens, ref, ref_meta, ocfg)
+        got = out.cpu().numpy()
+        gm = B.meta_to_numpy(out_meta, nt)
+        for t, (off, n) in enumerate(lay.tensors()):
+            assert np.array_equal(got[off:off + n], ref[off:off + n]), (ranks, t)
+            diff = P.meta_equal(gm[t], ref_meta[t], P.ALL_FIELDS)
+            assert not diff, (ranks, t, diff, gm[t], ref_meta[t])
+        if ranks >= 3:
+            assert gm["flags"][0] & B.FLAG_NONFINITE

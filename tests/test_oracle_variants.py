@@ -134,3 +134,88 @@ def test_predicted_scale_equals_just_in_time_when_the_bound_is_attained():
             st.step(g, O.AdamHparams(1e-3, 0.9, 0.95, 1e-8, 0.0, t, 1, O.WCOPY_E4M3, mode))
         assert sts[0].m_meta[0]["scale"] == sts[1].m_meta[0]["scale"]
         assert np.array_equal(sts[0].m, sts[1].m)
+
+
+# ---- shared-scale re-quantisation and the FP8 sum (Sec. 2.1, Eq. 4-6) -------------------------------
+def _ranks(n_ranks, fmt, seed=0, spread=(1.0, 0.3, 5.0, 0.02)):
+    """Every rank casts its own gradient of the same layout just in time."""
+    lay, tens, _ = ragged_case(seed=seed)
+    cfg = O.default_cfg()
+    rng = np.random.default_rng(seed)
+    srcs, metas, q = [], [], []
+    for r in range(n_ranks):
+        bits = np.zeros(lay.total, dtype=np.uint16)
+        for (off, n), s in zip(lay.tensors(), (1e-3, 3e-6, 40.0, 1e-4, 1.0, 2e-2)):
+            bits[off:off + n] = bf16_bits(rng.standard_normal(n) * s * spread[r % len(spread)])
+        meta = O.new_meta(lay.n_tensors, cfg)
+        codes = np.zeros(lay.total, dtype=np.uint8)
+        O.amax_scale(bits, tens, fmt, meta, cfg)
+        O.cast_fp8(bits, tens, codes, fmt, meta, cfg)
+        srcs.append(bits); metas.append(meta); q.append(codes)
+    return lay, tens, cfg, srcs, metas, q
+
+
+@pytest.mark.parametrize("fmt", [O.E5M2, O.E4M3])
+def test_shared_scale_requantize_and_sum(fmt):
+    n_ranks = 4
+    lay, tens, cfg, srcs, metas, q = _ranks(n_ranks, fmt, seed=2)
+    shared = O.shared_scale(metas, lay.n_tensors)
+    assert np.array_equal(shared, np.min(np.stack([m["scale"] for m in metas]), axis=0))   # Eq. 4
+    rq, rmetas = [], []
+    live = [(t, off, n) for t, (off, n) in enumerate(lay.tensors()) if n]
+    for r in range(n_ranks):
+        dst = np.zeros(lay.total, dtype=np.uint8)
+        dmeta = O.new_meta(lay.n_tensors, cfg)
+        O.requantize_fp8(q[r], fmt, metas[r], shared, tens, dst, dmeta)
+        for t, off, n in live:
+            value = dec8(fmt, q[r][off:off + n]).astype(np.float64) / float(metas[r][t]["scale"])
+            want = O.encode_fp8_nearest(fmt, (value * float(shared[t])).astype(np.float32))         # Eq. 5, brute force
+            assert np.array_equal(dst[off:off + n], want)
+            ratio = float(shared[t]) / float(metas[r][t]["scale"])
+            assert ratio <= 1 and np.log2(ratio) == int(np.log2(ratio))
+            if ratio == 1:
+                assert np.array_equal(dst[off:off + n], q[r][off:off + n])                          # nothing to do
+            assert dmeta[t]["scale"] == shared[t] and dmeta[t]["n_sat"] <= metas[r][t]["n_sat"]
+            back = dec8(fmt, dst[off:off + n]).astype(np.float64) / float(shared[t])
+            assert dmeta[t]["amax_deq"] == np.float32(np.abs(back).max())
+            # an exponent shift loses nothing until the value reaches the subnormals
+            keep = np.abs(value * float(shared[t])) >= (2.0 ** -6 if fmt == O.E4M3 else 2.0 ** -14)
+            assert np.array_equal(back[keep], value[keep])
+            assert dmeta[t]["n_underflow"] == np.count_nonzero((value != 0) & (back == 0))
+        rq.append(dst); rmetas.append(dmeta)
+    # Eq. 6: the sum of the re-quantised payloads carries the scale N * s_g, i.e. it is the mean gradient
+    out = np.zeros(lay.total, dtype=np.uint8)
+    smeta = O.new_meta(lay.n_tensors, cfg)
+    O.sum_fp8(rq, fmt, shared, tens, out, smeta, cfg)
+    fmax = 448.0 if fmt == O.E4M3 else 57344.0
+    for t, off, n in live:
+        exact = sum(dec8(fmt, rq[r][off:off + n]).astype(np.float64) for r in range(n_ranks))   # exact in float64
+        want = O.encode_fp8_nearest(fmt, exact.astype(np.float32))
+        diff = np.count_nonzero(out[off:off + n] != want)
+        assert diff <= max(1, n // 10000)             # one rounding; fp32 accumulation differs only on rare double roundings
+        assert smeta[t]["scale"] == n_ranks * shared[t]
+        mean_true = sum(bf16_vals(srcs[r][off:off + n]).astype(np.float64) for r in range(n_ranks)) / n_ranks
+        got = dec8(fmt, out[off:off + n]).astype(np.float64) / float(smeta[t]["scale"])
+        clipped = np.abs(exact) >= fmax
+        assert smeta[t]["n_sat"] >= np.count_nonzero(clipped)
+        # away from clipping the result is the mean gradient up to a few FP8 roundings of its terms
+        gap = 2.0 ** (-3 if fmt == O.E4M3 else -2)
+        bound = (n_ranks + 1) * gap * np.max([np.abs(bf16_vals(srcs[r][off:off + n])) for r in range(n_ranks)], axis=0) / n_ranks \
+            + 4 * (2.0 ** -9 if fmt == O.E4M3 else 2.0 ** -16) / float(smeta[t]["scale"])
+        assert np.all(np.abs(got - mean_true)[~clipped] <= bound[~clipped])
+
+
+def test_sum_of_one_rank_is_the_identity_and_equal_ranks_double():
+    lay, tens, cfg, srcs, metas, q = _ranks(1, O.E5M2, seed=5)
+    shared = O.shared_scale(metas, lay.n_tensors)
+    out = np.zeros(lay.total, dtype=np.uint8)
+    smeta = O.new_meta(lay.n_tensors, cfg)
+    O.sum_fp8(q, O.E5M2, shared, tens, out, smeta, cfg)
+    used = np.zeros(lay.total, dtype=bool)
+    for off, n in lay.tensors():
+        used[off:off + n] = True
+    assert np.array_equal(out[used], q[0][used])
+    O.sum_fp8([q[0], q[0]], O.E5M2, shared, tens, out, smeta, cfg)
+    twice = O.encode_fp8(O.E5M2, 2 * dec8(O.E5M2, q[0]))
+    assert np.array_equal(out[used], twice[used])
+    assert smeta["n_sat"].sum() > 0                   # the top binade doubles past the largest code and clips
