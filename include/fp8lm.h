@@ -240,6 +240,16 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* ctx,
                                  void* wcopy /*device, write only*/, fp8lm_meta* wcopy_meta /*device*/,
                                  const fp8lm_adam_hparams* hp /*host*/, void* stream);
 
+/*
+ * Host-only helper: the whole-tensor greedy distribution of Sec. 2.3, Alg. 1 (how this path would be
+ * sharded over GPUs: a tensor and its scale always stay together).  Tensors are taken in descending
+ * order of sizes[i] (equal sizes in index order); each goes to the GPU with the least memory in use
+ * (the lowest-numbered among equals).
+ *   sizes : host[n], >= 0.   owner : host[n], written: GPU of tensor i.   usage : host[n_gpus], written.
+ */
+fp8lm_status fp8lm_greedy_partition(const int64_t* sizes /*host*/, int32_t n, int32_t n_gpus,
+                                    int32_t* owner /*host*/, int64_t* usage /*host*/);
+
 /* A plain 128-bit copy kernel over `bytes` bytes (multiple of 16): the measured bandwidth ceiling
  * the streaming kernels are compared with.                                                        */
 fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* ctx, const void* src /*device*/, void* dst /*device*/, int64_t bytes,

@@ -118,6 +118,8 @@ def lib():
         L.oracle_sum_fp8.restype = None
         L.oracle_sum_fp8.argtypes = [C.c_void_p, C.c_int32, C.c_int, C.c_void_p, C.c_void_p, C.c_int32,
                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oracle_greedy_partition.restype = None
+        L.oracle_greedy_partition.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.oracle_init_master.restype = None
         L.oracle_init_master.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.oracle_adam_step_fp8.restype = None
@@ -185,6 +187,15 @@ def sum_fp8(payloads, fmt, shared, tensors, dst, dst_meta, cfg) -> None:
     assert all(a.dtype == np.uint8 for a in payloads) and dst.dtype == np.uint8
     lib().oracle_sum_fp8(_ptr_array(payloads), len(payloads), fmt, _p(shared), _p(tensors), len(tensors), _p(dst),
                          _p(dst_meta), C.byref(cfg))
+
+
+def greedy_partition(sizes, n_gpus: int):
+    """Alg. 1: (owner[n], usage[n_gpus])."""
+    sizes = np.ascontiguousarray(sizes, dtype=np.int64)
+    owner = np.zeros(len(sizes), dtype=np.int32)
+    usage = np.zeros(n_gpus, dtype=np.int64)
+    lib().oracle_greedy_partition(_p(sizes), len(sizes), n_gpus, _p(owner), _p(usage))
+    return owner, usage
 
 
 def init_master(w_bf16: np.ndarray, tensors: np.ndarray, w_f16: np.ndarray, w_meta: np.ndarray) -> None:

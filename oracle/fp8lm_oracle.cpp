@@ -676,6 +676,24 @@ void oracle_adam_step_fp8(const oracle_tensor* tensors, int32_t n_tensors,
   }
 }
 
+// ---- whole-tensor greedy distribution (Sec. 2.3, Alg. 1) -----------------------------------------
+// Tensors are visited in descending order of size (equal sizes in their original order); each goes
+// to the GPU with the least memory in use so far (the lowest-numbered one among equals).
+void oracle_greedy_partition(const int64_t* sizes, int32_t n, int32_t n_gpus, int32_t* owner, int64_t* usage) {
+  for (int32_t j = 0; j < n_gpus; ++j) usage[j] = 0;
+  for (int32_t i = 0; i < n; ++i) owner[i] = -1;
+  for (int32_t round = 0; round < n; ++round) {
+    int32_t pick = -1;                       // the largest tensor not yet placed
+    for (int32_t i = 0; i < n; ++i)
+      if (owner[i] < 0 && (pick < 0 || sizes[i] > sizes[pick])) pick = i;
+    int32_t j = 0;
+    for (int32_t k = 1; k < n_gpus; ++k)
+      if (usage[k] < usage[j]) j = k;
+    owner[pick] = j;
+    usage[j] += sizes[pick];
+  }
+}
+
 // Derived host scalars, exported so a test can check them against float64 arithmetic.
 void oracle_derive_hparams(const oracle_adam_hparams* hp, float* out7) {
   derive_hparams(hp, out7[0], out7[1], out7[2], out7[3], out7[4], out7[5], out7[6]);

@@ -28,7 +28,7 @@ KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy
 EXPORTS = [
     "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_meta_init", "fp8lm_amax_scale",
     "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
-    "fp8lm_init_master", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
+    "fp8lm_init_master", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
 
@@ -107,6 +107,7 @@ def lib() -> C.CDLL:
         L.fp8lm_sum_fp8.argtypes = [vp, vp, i32, C.c_int, vp, vp, vp, vp, vp]
         L.fp8lm_adam_step_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fp8lm_copy_bytes.argtypes = [vp, vp, vp, i64, vp]
+        L.fp8lm_greedy_partition.argtypes = [vp, i32, i32, vp, vp]
         L.fp8lm_set_timing.argtypes = [vp, i32]
         L.fp8lm_get_timing.argtypes = [vp, vp, vp]
         for name in EXPORTS:
@@ -266,6 +267,16 @@ class Context:
         ms = (C.c_double * K_COUNT)()
         _check(lib().fp8lm_get_timing(self._h, C.cast(n, C.c_void_p), C.cast(ms, C.c_void_p)), "fp8lm_get_timing")
         return {KERNEL_NAMES[k]: (int(n[k]), float(ms[k])) for k in range(K_COUNT)}
+
+
+def greedy_partition(sizes, n_gpus: int):
+    """Alg. 1 of the paper on the host: returns (owner[n], usage[n_gpus]) as numpy arrays."""
+    sizes = np.ascontiguousarray(sizes, dtype=np.int64)
+    owner = np.zeros(max(1, len(sizes)), dtype=np.int32)
+    usage = np.zeros(n_gpus, dtype=np.int64)
+    _check(lib().fp8lm_greedy_partition(sizes.ctypes.data, len(sizes), n_gpus, owner.ctypes.data, usage.ctypes.data),
+           "fp8lm_greedy_partition")
+    return owner[:len(sizes)], usage
 
 
 def meta_to_numpy(meta: torch.Tensor, n: int) -> np.ndarray:

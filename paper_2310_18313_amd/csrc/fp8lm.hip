@@ -19,6 +19,8 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <numeric>
+#include <queue>
 #include <string>
 #include <vector>
 
@@ -1673,6 +1675,29 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
     else launch_update<kE4M3, FP8LM_WCOPY_BF16>(c, s, p, fast, stats);
   }
   return after_launch();
+}
+
+// Host only.  Whole-tensor greedy distribution of Sec. 2.3, Alg. 1, with a heap over the GPUs.
+fp8lm_status fp8lm_greedy_partition(const int64_t* sizes, int32_t n, int32_t n_gpus, int32_t* owner, int64_t* usage) {
+  if (n < 0 || n_gpus < 1 || (n > 0 && (!sizes || !owner)) || !usage) return FP8LM_ERR_INVALID_ARGUMENT;
+  for (int32_t i = 0; i < n; ++i)
+    if (sizes[i] < 0) return FP8LM_ERR_INVALID_ARGUMENT;
+  std::vector<int32_t> order(n);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return sizes[a] > sizes[b]; });
+  typedef std::pair<int64_t, int32_t> Load;   // (memory in use, gpu): the smallest pair is the next receiver
+  std::priority_queue<Load, std::vector<Load>, std::greater<Load>> heap;
+  for (int32_t j = 0; j < n_gpus; ++j) heap.emplace(0, j);
+  for (int32_t i : order) {
+    Load top = heap.top();
+    heap.pop();
+    owner[i] = top.second;
+    top.first += sizes[i];
+    heap.push(top);
+  }
+  for (int32_t j = 0; j < n_gpus; ++j) usage[j] = 0;
+  for (int32_t i = 0; i < n; ++i) usage[owner[i]] += sizes[i];
+  return FP8LM_OK;
 }
 
 fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* c, const void* src, void* dst, int64_t bytes, void* stream) {
