@@ -158,7 +158,7 @@ def main() -> int:
     if args.chunk or args.blocks_per_cu or args.interleave >= 0:
         st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 8, max(args.interleave, 0))
     grad = st.grad
-    placement = {"spread_over_hbm_regions": st.spread}
+    placement = {"spread_over_hbm_regions": st.spread, **{k: v for k, v in st.placement.items() if k != "where"}}
     if st.spread:
         from paper_2310_18313_amd.placement import verify_spread
         placement["check_v_vs_w"] = verify_spread(st.ctx, st.v, st.w)

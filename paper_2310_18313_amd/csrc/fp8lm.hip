@@ -1245,9 +1245,20 @@ __global__ void meta_init_kernel(fp8lm_meta* meta, int n, int clean0) {
   meta[t] = M;
 }
 
+// Plain streaming copy: every workgroup owns one contiguous range, four 128-bit loads in flight per
+// thread, non-temporal on both sides.
 __global__ __launch_bounds__(kThreads) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long long n16) {
-  const long long stride = (long long)gridDim.x * blockDim.x;
-  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+  const long long b0 = n16 * blockIdx.x / gridDim.x, b1 = n16 * (blockIdx.x + 1) / gridDim.x;
+  long long i = b0 + threadIdx.x;
+  for (; i + 3 * kThreads < b1; i += 4 * kThreads) {
+    const uint4 a = ld16<true>(src + i), b = ld16<true>(src + i + kThreads), c = ld16<true>(src + i + 2 * kThreads),
+                d = ld16<true>(src + i + 3 * kThreads);
+    st16<true>(dst + i, a);
+    st16<true>(dst + i + kThreads, b);
+    st16<true>(dst + i + 2 * kThreads, c);
+    st16<true>(dst + i + 3 * kThreads, d);
+  }
+  for (; i < b1; i += kThreads) st16<true>(dst + i, ld16<true>(src + i));
 }
 
 }  // namespace fp8lm

@@ -1,11 +1,14 @@
 """Placement of the large flat buffers in HBM on MI355X.
 
-Measured on MI355X (see `python -m paper_2310_18313_amd.placement --probe`): the 288 GiB of HBM3E behave
-as three regions of 96 GiB each.  Streams that a kernel walks at the same time run faster when they
-live in different regions (a copy between regions reaches about 5 % more bandwidth than a copy inside
-one region; the eight-stream Adam update kernel about 18 % more).  A fresh process receives physical
-memory in allocation order, so the regions can be targeted by allocating the buffers in a chosen
-order with temporary ballast in between; the ballast is freed again once everything is placed.
+Measured on MI355X (`python -m paper_2310_18313_amd.placement --probe`): the 288 GiB of HBM3E behave
+as three regions of 96 GiB.  Streams that a kernel walks at the same time run faster when they live
+in different regions: a copy between regions reaches about 5 % more bandwidth than a copy inside one
+region, the eight-stream Adam update kernel about 18 % more.
+
+`SpreadAllocator` therefore puts the buffers of an optimizer state into chosen regions without
+assuming anything about the allocator: it takes all free device memory in slabs, finds out which
+slabs share a region by timing copies between them, then frees exactly the slabs a buffer should
+occupy and allocates the buffer into that hole.  The remaining slabs are released at the end.
 
 Nothing here computes anything of the method: it only decides where `torch.zeros` buffers land.
 """
@@ -17,54 +20,11 @@ from typing import Dict, List, Sequence, Tuple
 import torch
 
 GiB = 1 << 30
-N_REGIONS = 3
 _ROUND = 2 << 20          # torch hands large blocks to hipMalloc in multiples of 2 MiB
 
 
 def _round_up(n: int, m: int = _ROUND) -> int:
     return (n + m - 1) // m * m
-
-
-class SpreadAllocator:
-    """Allocates named buffers region by region.
-
-    `plan` lists, per region, the buffers to put there as (name, numel, dtype).  Must be used before the
-    process has made other large device allocations (the physical position is inferred from the amount
-    of memory in use).  If the plan does not fit, or the device does not look like a 3 x 96 GiB
-    MI355X, everything is allocated plainly and `spread` is False.
-    """
-
-    def __init__(self, device: int = 0):
-        self.device = torch.device(f"cuda:{device}")
-        free, total = torch.cuda.mem_get_info(self.device)
-        self.total = total
-        self.used0 = total - free
-        self.region = total // N_REGIONS
-        self.spread = False
-        self.where: Dict[str, int] = {}
-
-    def allocate(self, plan: Sequence[Sequence[Tuple[str, int, torch.dtype]]]) -> Dict[str, torch.Tensor]:
-        sizes = [[_round_up(n * torch.empty((), dtype=dt).element_size()) for _, n, dt in reg] for reg in plan]
-        want = sum(sum(s) for s in sizes)
-        fits = (len(plan) <= N_REGIONS and abs(self.total - 288 * GiB) < 8 * GiB and want >= 2 * GiB and
-                all(sum(s) <= self.region - (self.used0 if r == 0 else 0) - 64 * (1 << 20) for r, s in enumerate(sizes)))
-        bufs: Dict[str, torch.Tensor] = {}
-        ballast: List[torch.Tensor] = []
-        pos = self.used0
-        for r, reg in enumerate(plan):
-            for (name, n, dt), nbytes in zip(reg, sizes[r]):
-                bufs[name] = torch.zeros(n, dtype=dt, device=self.device)
-                self.where[name] = r if fits else 0
-                pos += nbytes
-            end = (r + 1) * self.region
-            if fits and r + 1 < len(plan) and pos < end:
-                ballast.append(torch.empty(end - pos, dtype=torch.uint8, device=self.device))
-                pos = end
-        del ballast
-        if fits:
-            torch.cuda.empty_cache()
-        self.spread = fits
-        return bufs
 
 
 def copy_rate(ctx, src: torch.Tensor, dst: torch.Tensor, nbytes: int, reps: int = 3) -> float:
@@ -90,8 +50,103 @@ def verify_spread(ctx, a: torch.Tensor, b: torch.Tensor) -> dict:
     return {"inside_GBps": round(inside, 1), "across_GBps": round(across, 1), "distinct": across > 1.025 * inside}
 
 
+class SpreadAllocator:
+    """Allocates named buffers region by region (see the module docstring).
+
+    `plan` lists, per region, the buffers to put there as (name, numel, dtype).  Works whatever the
+    process allocated before, as long as most of the device memory is still free.  If the regions
+    cannot be told apart, or the plan does not fit, everything is allocated plainly and `spread` is
+    False.
+    """
+
+    def __init__(self, ctx, device: int = 0, slab_gib: int = 4, threshold: float = 1.025):
+        self.ctx = ctx
+        self.device = torch.device(f"cuda:{device}")
+        self.slab_bytes = slab_gib * GiB
+        self.threshold = threshold
+        self.spread = False
+        self.regions: List[List[int]] = []      # slab indices per discovered region
+        self.where: Dict[str, int] = {}
+        self.log: Dict[str, object] = {}
+
+    # -- discovery ---------------------------------------------------------------------------------
+    def _discover(self) -> List[torch.Tensor]:
+        slabs: List[torch.Tensor] = []
+        while torch.cuda.mem_get_info(self.device)[0] > self.slab_bytes + 3 * GiB:
+            slabs.append(torch.empty(self.slab_bytes, dtype=torch.uint8, device=self.device))
+        probe = min(2 * GiB, self.slab_bytes)
+        unassigned = list(range(len(slabs)))
+        regions: List[List[int]] = []
+        scratch_ok = len(slabs) >= 6
+        while scratch_ok and unassigned and len(regions) < 8:
+            ref = unassigned[0]
+            rest = unassigned[1:]
+            if len(rest) < 2:
+                regions.append([ref] + rest)
+                break
+            rates = sorted((copy_rate(self.ctx, slabs[ref], slabs[k], probe, reps=2), k) for k in rest)
+            # Copies inside the reference's region are the slow ones.  Split the sorted rates in two
+            # where the means of the two sides are furthest apart; accept the split only if the fast
+            # side is clearly faster.
+            vals = [r for r, _ in rates]
+            best, cut = 1.0, None
+            for i in range(1, len(vals)):
+                lo, hi = sum(vals[:i]) / i, sum(vals[i:]) / (len(vals) - i)
+                score = (hi - lo) * min(i, len(vals) - i) ** 0.25
+                if cut is None or score > best:
+                    best, cut = score, i
+            lo, hi = sum(vals[:cut]) / cut, sum(vals[cut:]) / (len(vals) - cut)
+            if hi >= self.threshold * lo:
+                same = [ref] + [k for _, k in rates[:cut]]
+            else:
+                same = [ref] + rest              # no structure left: one region
+            regions.append(sorted(same))
+            unassigned = [k for k in unassigned if k not in same]
+        self.regions = regions
+        self.log["slabs"] = len(slabs)
+        self.log["slab_GiB"] = self.slab_bytes // GiB
+        self.log["region_slabs"] = [len(r) for r in regions]
+        return slabs
+
+    # -- allocation --------------------------------------------------------------------------------
+    def allocate(self, plan: Sequence[Sequence[Tuple[str, int, torch.dtype]]]) -> Dict[str, torch.Tensor]:
+        sizes = [[_round_up(n * torch.empty((), dtype=dt).element_size()) for _, n, dt in reg] for reg in plan]
+        want = sum(sum(s) for s in sizes)
+        free = torch.cuda.mem_get_info(self.device)[0]
+        bufs: Dict[str, torch.Tensor] = {}
+        slabs: List[torch.Tensor] = []
+        ok = want >= 2 * GiB and free > want + 16 * GiB and free > 64 * GiB
+        if ok:
+            slabs = self._discover()
+            big = sorted((r for r in self.regions if len(r) >= 2), key=len, reverse=True)
+            need = [-(-sum(s) // self.slab_bytes) for s in sizes]          # slabs per plan region
+            ok = len(big) >= len(plan) and all(len(big[i]) >= need[i] for i in range(len(plan)))
+        if not ok:
+            del slabs
+            torch.cuda.empty_cache()
+            for reg in plan:
+                for name, n, dt in reg:
+                    bufs[name] = torch.zeros(n, dtype=dt, device=self.device)
+                    self.where[name] = 0
+            return bufs
+        # heaviest plan region into the largest discovered region, and so on
+        order = sorted(range(len(plan)), key=lambda i: -sum(sizes[i]))
+        for rank, i in enumerate(order):
+            take = big[rank][:need[i]]
+            for k in take:
+                slabs[k] = None                  # free exactly these slabs ...
+            torch.cuda.empty_cache()
+            for name, n, dt in plan[i]:          # ... and let the buffers fall into the hole
+                bufs[name] = torch.zeros(n, dtype=dt, device=self.device)
+                self.where[name] = rank
+        del slabs
+        torch.cuda.empty_cache()
+        self.spread = True
+        return bufs
+
+
 def probe(piece_gib: int = 4) -> None:
-    """Prints the copy rate from the first piece of device memory to every other piece."""
+    """Prints the copy rate from three reference pieces of device memory to every other piece."""
     from . import binding as B
     ctx = B.Context([(0, 16)])
     pieces = []
@@ -101,7 +156,7 @@ def probe(piece_gib: int = 4) -> None:
         pieces.append(torch.zeros(piece_gib * GiB, dtype=torch.uint8, device="cuda:0"))
     nb = min(piece_gib, 1) * GiB
     for ref in (0, len(pieces) // 2, len(pieces) - 1):
-        print(f"copy of 1 GiB from piece {ref} (starts at about {ref * piece_gib} GiB) to piece k, GB/s:")
+        print(f"copy of 1 GiB from piece {ref} (allocated {ref * piece_gib} GiB into the run) to piece k, GB/s:")
         row = []
         for k, p in enumerate(pieces):
             row.append("  ref" if k == ref else f"{copy_rate(ctx, pieces[ref], p, nb):5.0f}")

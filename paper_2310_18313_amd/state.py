@@ -30,10 +30,12 @@ class OptimizerState:
         plan = [[("v", n, torch.float16)] + ([("grad", n, torch.bfloat16)] if grad_buffer else []),
                 [("w", n, torch.float16)],
                 [("m", n, torch.uint8), ("g8", n, torch.uint8), ("wq", n, qdt)]]
+        self.placement = {}
         if spread:
-            alloc = SpreadAllocator(device)
+            alloc = SpreadAllocator(self.ctx, device)
             bufs = alloc.allocate(plan)
             self.spread = alloc.spread
+            self.placement = dict(alloc.log, where=alloc.where)
         else:
             bufs = {name: torch.zeros(k, dtype=dt, device=dev) for reg in plan for name, k, dt in reg}
             self.spread = False
