@@ -22,7 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-BYTES_PER_PARAM = {"amax": 2, "cast": 3, "adam_amax": 2, "adam_update": 12}
+BYTES_PER_PARAM = {"amax": 2, "cast": 3, "adam_amax": 2, "adam_update": 12}   # "cast" is 4 on the fused path
 HBM_PEAK_GBS = 8000.0
 
 
@@ -128,9 +128,10 @@ def main() -> int:
     ap.add_argument("--exact", type=int, default=1)
     ap.add_argument("--stats", type=int, default=0)
     ap.add_argument("--copy-ceiling", action="store_true", help="also time a plain 128-bit copy kernel")
-    ap.add_argument("--path", choices=["jit", "single"], default="jit",
-                    help="jit: amax pass + cast + two-pass Adam (19 B/param, the headline path); single: delayed "
-                         "gradient scaling + predicted first-moment scale (one pass each, 15 B/param)")
+    ap.add_argument("--path", choices=["jit", "fused", "single"], default="jit",
+                    help="jit: amax pass + cast + two-pass Adam (19 B/param, the three entry points as they are); "
+                         "fused: same results, the cast also does the Adam step's first pass (18 B/param, one GPU "
+                         "only); single: delayed gradient scaling + predicted first-moment scale (15 B/param)")
     ap.add_argument("--allreduce-steps", type=int, default=0, metavar="N",
                     help="also time the shared-scale re-quantise kernel and the N-rank FP8 sum (Eq. 4-6) on this layout")
     ap.add_argument("--no-spread", action="store_true", help="allocate the buffers plainly, one after the other")
@@ -170,10 +171,10 @@ def main() -> int:
     torch.cuda.synchronize()
 
     single = args.path == "single"
-    bytes_per_param = 15 if single else 19
+    bytes_per_param = {"jit": 19, "fused": 18, "single": 15}[args.path]
 
     def hp(step):
-        return B.adam_hparams(wl.lr, step, exact=args.exact, stats=args.stats, m_predict=1 if single else 0)
+        return B.adam_hparams(wl.lr, step, exact=args.exact, stats=args.stats, m_scale_mode=B.MSCALE_PREDICTED if single else (B.MSCALE_FROM_CAST if args.path == 'fused' else B.MSCALE_EXACT_PASS))
 
     for s in range(1, args.warmup + 1):
         st.step(grad, hp(s), delayed=single and s > 1)    # the first step seeds the amax history
@@ -192,6 +193,8 @@ def main() -> int:
     ms_per_step = dt / args.steps * 1e3
     kernels = {}
     for name, bpp in BYTES_PER_PARAM.items():
+        if name == "cast" and args.path == "fused":
+            bpp = 4
         n, ms = timing[name]
         if n:
             avg = ms / n

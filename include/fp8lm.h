@@ -49,6 +49,17 @@ typedef enum { FP8LM_SRC_BF16 = 0 } fp8lm_src;
 /* Format of the low-precision weight copy written by the optimizer.                             */
 typedef enum { FP8LM_WCOPY_E4M3 = 0, FP8LM_WCOPY_BF16 = 1 } fp8lm_wcopy;
 
+/* How fp8lm_adam_step_fp8 chooses the scale of the first moment it stores.
+ *   EXACT_PASS : from the exact amax of the new moment, measured by an extra read-only pass over grad
+ *                and m inside fp8lm_adam_step_fp8 (just-in-time scaling, Appendix A.2);
+ *   PREDICTED  : from the bound fma(beta1, m_meta.amax_deq, (1-beta1) * grad_meta.amax_deq), which no new
+ *                |m| exceeds: one pass less, the scale can be a binade or more looser; v, w and the
+ *                update itself are unaffected;
+ *   FROM_CAST  : the same exact amax as EXACT_PASS, but measured by the immediately preceding
+ *                fp8lm_cast_fp8_for_adam call on the same grad, m, m_meta and beta1 (checked; otherwise
+ *                INVALID_ARGUMENT).  Only valid when nothing changes grad between the two calls.   */
+typedef enum { FP8LM_MSCALE_EXACT_PASS = 0, FP8LM_MSCALE_PREDICTED = 1, FP8LM_MSCALE_FROM_CAST = 2 } fp8lm_mscale;
+
 typedef struct {
   int64_t offset; /* first element, multiple of 16 */
   int64_t numel;  /* >= 0                          */
@@ -95,11 +106,7 @@ typedef struct {
   int32_t wcopy;    /* fp8lm_wcopy                                                                 */
   int32_t stats;    /* 1: count n_sat / n_underflow of the four outputs exactly (more ALU work);
                        0: leave them 0; FLAG_SATURATED is still exact (derived from the amax)      */
-  int32_t m_predict; /* 0: the first-moment scale comes from the exact amax of the new moment (an extra
-                          read-only pass over grad and m);
-                       1: it comes from the bound fma(beta1, m_meta.amax_deq, (1-beta1) * grad_meta.amax_deq),
-                          which no new |m| exceeds: one pass less, the scale can be a binade or more
-                          looser; v, w and the update itself are unaffected                       */
+  int32_t m_scale_mode; /* fp8lm_mscale: where the scale of the stored first moment comes from             */
   int32_t exact;    /* 1: correctly rounded sqrt and divide in the weight update (results identical to
                           the scalar definition);
                        0: hardware v_sqrt_f32 / v_rcp_f32, 1 ulp each: m and v are unaffected, the
@@ -175,6 +182,21 @@ fp8lm_status fp8lm_cast_fp8_delayed(fp8lm_ctx* ctx, const void* src /*device*/, 
                                     const fp8lm_autoscale_cfg* cfg /*host*/, void* stream);
 
 /*
+ * fp8lm_cast_fp8 (delayed = 0) or fp8lm_cast_fp8_delayed (delayed = 1) that also measures, in the same
+ * pass, the amax of the first moment the following Adam step will produce: max |fma(beta1, m / s_m,
+ * (1-beta1) * dst / s_g)| over each tensor, with dst the FP8 gradient just written.  On one GPU, where
+ * nothing touches the gradient between quantisation and optimizer, this replaces the Adam step's own
+ * read-only pass (19 -> 18 bytes per parameter and step) with identical results: call
+ * fp8lm_adam_step_fp8 next with m_scale_mode = FP8LM_MSCALE_FROM_CAST.
+ *   m, m_meta : device, the E4M3 first moment and its metadata as they stand (read only).
+ */
+fp8lm_status fp8lm_cast_fp8_for_adam(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_src src_type,
+                                     uint8_t* dst /*device*/, fp8lm_fmt fmt, fp8lm_meta* meta /*device*/,
+                                     const fp8lm_autoscale_cfg* cfg /*host*/, int32_t delayed,
+                                     const uint8_t* m /*device*/, const fp8lm_meta* m_meta /*device*/, float beta1,
+                                     void* stream);
+
+/*
  * The three steps around the FP8 gradient all-reduce of Sec. 2.1 (Eq. 4-6), as one GPU can run them;
  * the collectives themselves are not part of this library.  n_ranks <= 8.
  *
@@ -220,8 +242,8 @@ fp8lm_status fp8lm_init_master(fp8lm_ctx* ctx, const void* w_bf16 /*device*/, ui
  *     m' = fma(beta1, m, (1-beta1) * g)          v' = fma(beta2, v, (1-beta2) * g*g)
  *     w' = fma(-lr, (m' / (1-beta1^step)) / (sqrt(v' / (1-beta2^step)) + eps), w * (1 - lr*weight_decay))
  * and m', v', w' are stored back in place with refreshed per-tensor scales:
- *     m : E4M3, scale from the exact amax of m' (an extra read-only pass over grad and m), or from a
- *         predicted bound when hp->m_predict is set;
+ *     m : E4M3, scale chosen as hp->m_scale_mode says (default: exact amax of m', measured by an extra
+ *         read-only pass over grad and m);
  *     v : FP16, scale from the bound fma(beta2, v_meta.amax_deq, (1-beta2) * grad_meta.amax_deq^2), which
  *         no v' exceeds (v_scaled = 0: scale 1);
  *     w : FP16, scale from w_meta.amax_deq before the step, minus one binade;

@@ -21,13 +21,14 @@ HIST = 16
 E4M3, E5M2 = 0, 1
 SRC_BF16 = 0
 WCOPY_E4M3, WCOPY_BF16 = 0, 1
+MSCALE_EXACT_PASS, MSCALE_PREDICTED, MSCALE_FROM_CAST = 0, 1, 2
 FLAG_NONFINITE, FLAG_AMAX_ZERO, FLAG_SCALE_CLAMPED, FLAG_SATURATED = 1, 2, 4, 8
 K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_REQUANT, K_SUM, K_COUNT = range(10)
 KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars", "requantize", "sum"]
 
 EXPORTS = [
     "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_meta_init", "fp8lm_amax_scale",
-    "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
+    "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_cast_fp8_for_adam", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
     "fp8lm_init_master", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
@@ -61,7 +62,7 @@ class AutoscaleCfg(C.Structure):
 class AdamHparams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float), ("step", C.c_int64), ("v_scaled", C.c_int32),
-                ("wcopy", C.c_int32), ("stats", C.c_int32), ("m_predict", C.c_int32), ("exact", C.c_int32)]
+                ("wcopy", C.c_int32), ("stats", C.c_int32), ("m_scale_mode", C.c_int32), ("exact", C.c_int32)]
 
 
 def autoscale_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=100000) -> AutoscaleCfg:
@@ -69,8 +70,8 @@ def autoscale_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=1
 
 
 def adam_hparams(lr, step, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, v_scaled=1,
-                 wcopy=WCOPY_E4M3, stats=0, exact=1, m_predict=0) -> AdamHparams:
-    return AdamHparams(lr, beta1, beta2, eps, weight_decay, step, v_scaled, wcopy, stats, m_predict, exact)
+                 wcopy=WCOPY_E4M3, stats=0, exact=1, m_scale_mode=MSCALE_EXACT_PASS) -> AdamHparams:
+    return AdamHparams(lr, beta1, beta2, eps, weight_decay, step, v_scaled, wcopy, stats, m_scale_mode, exact)
 
 
 class Fp8lmError(RuntimeError):
@@ -101,6 +102,7 @@ def lib() -> C.CDLL:
         L.fp8lm_amax_scale.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, vp]
         L.fp8lm_cast_fp8.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
         L.fp8lm_cast_fp8_delayed.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
+        L.fp8lm_cast_fp8_for_adam.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, i32, vp, vp, C.c_float, vp]
         L.fp8lm_init_master.argtypes = [vp, vp, vp, vp, vp]
         L.fp8lm_shared_scale.argtypes = [vp, vp, i32, vp, vp]
         L.fp8lm_requantize_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp]
@@ -210,6 +212,14 @@ class Context:
         self._fits_meta(meta)
         _check(lib().fp8lm_cast_fp8_delayed(self._h, _ptr(src), SRC_BF16, _ptr(dst), fmt, _ptr(meta),
                                             C.addressof(cfg), _stream(stream)), "fp8lm_cast_fp8_delayed")
+
+    def cast_fp8_for_adam(self, src, dst, fmt, meta, cfg, m, m_meta, beta1, delayed=False, stream=None):
+        assert src.element_size() == 2 and dst.element_size() == 1 and m.element_size() == 1
+        self._fits(src, dst, m)
+        self._fits_meta(meta, m_meta)
+        _check(lib().fp8lm_cast_fp8_for_adam(self._h, _ptr(src), SRC_BF16, _ptr(dst), fmt, _ptr(meta), C.addressof(cfg),
+                                             1 if delayed else 0, _ptr(m), _ptr(m_meta), beta1, _stream(stream)),
+               "fp8lm_cast_fp8_for_adam")
 
     def shared_scale(self, metas, stream=None) -> torch.Tensor:
         """Eq. 4: per-tensor minimum of the ranks' scales; returns a device fp32 array [n_tensors]."""

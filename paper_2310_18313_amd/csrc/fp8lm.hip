@@ -53,7 +53,7 @@ struct Scratch {
     float sm, ism, sv, isv, sw, isw, sq, isq;
     uint32_t fm, fv, fw, fq;      // flags gathered while choosing the scales
     uint32_t careful;
-    uint32_t pad;
+    uint32_t amax_m_bits;   // written by a fused cast: bit pattern of max |m'|
   } pend;
 };
 
@@ -367,6 +367,10 @@ struct CastParams {
   fp8lm_meta* meta;
   int32_t sat_num, sat_den, ramp_steps;
   int32_t hist_window;   // delayed scaling only
+  // fused first pass of the Adam step (FUSE): the first moment as it stands and beta1
+  const uint8_t* m;
+  const fp8lm_meta* m_meta;
+  float b1, omb1;
 };
 
 // number of zero bytes among the four 7-bit fields of x (each byte of x must be <= 0x7F)
@@ -375,12 +379,16 @@ __device__ __forceinline__ uint32_t nonzero_bytes7(uint32_t x) { return __popc((
 // DELAYED: the scale was fixed from the amax history before the launch (Appendix A.2, delayed
 // scaling); this pass also measures the amax of the source for the history, and since no amax pass
 // has looked for inf/NaN it checks every 16-element group itself.
-template <int FMT, bool DELAYED>
+// FUSE: on one GPU the Adam step follows the cast directly, so this pass also measures what the Adam
+// step's first pass would: max |fma(beta1, m, (1-beta1) * g)| with g the value just stored in FP8.
+template <int FMT, bool DELAYED, bool FUSE>
 struct CastOp {
   const CastParams& p;
   const Tables& tb;
   float scale;
   bool careful;
+  float inv_sg, inv_sm;   // FUSE
+  uint32_t macc;          // FUSE: running max of the |m'| bit patterns
   uint32_t amax16;        // DELAYED: two 16-bit running maxima of (bits & 0x7FFF)
   float vmax;             // max |clamped scaled value|
   uint32_t n_elems;       // elements seen (full groups * 16 + tails) since the last flush
@@ -388,11 +396,29 @@ struct CastOp {
   uint32_t nz_code;       // codes with non-zero magnitude
   uint32_t z_in;          // inputs that are +-0
   __device__ CastOp(const CastParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
-  __device__ __forceinline__ void reset() { vmax = 0.0f; n_elems = nz_top = nz_code = z_in = 0; amax16 = 0; }
+  __device__ __forceinline__ void reset() { vmax = 0.0f; n_elems = nz_top = nz_code = z_in = 0; amax16 = 0; macc = 0; }
   __device__ __forceinline__ void begin(int t, const TensorDesc&) {
     scale = p.meta[t].scale;
     careful = !DELAYED && (p.meta[t].flags & FP8LM_FLAG_NONFINITE) != 0;
+    if constexpr (FUSE) {
+      inv_sg = p.meta[t].inv_scale;
+      inv_sm = p.m_meta[t].inv_scale;
+    }
     reset();
+  }
+  // FUSE: the new first moment of one element, from the decoded FP8 gradient and moment codes
+  __device__ __forceinline__ void moment(float dg, float dm) {
+    const float g = dg * inv_sg, m0 = dm * inv_sm;
+    const float m1 = __builtin_fmaf(p.b1, m0, p.omb1 * g);
+    macc = max(macc, f2u(m1) & 0x7FFFFFFFu);
+  }
+  __device__ __forceinline__ void moment_word(uint32_t gw, uint32_t mw) {
+    const float2_t g01 = fp8x2_to_f32<FMT, false>(gw), g23 = fp8x2_to_f32<FMT, true>(gw);
+    const float2_t m01 = fp8x2_to_f32<kE4M3, false>(mw), m23 = fp8x2_to_f32<kE4M3, true>(mw);
+    moment(g01.x, m01.x);
+    moment(g01.y, m01.y);
+    moment(g23.x, m23.x);
+    moment(g23.y, m23.y);
   }
   // DELAYED: folds one group's source bits into the running amax; true if the group holds inf or NaN
   __device__ __forceinline__ bool note_source(const uint4& a, const uint4& b) {
@@ -416,7 +442,7 @@ struct CastOp {
     nz_top += nonzero_bytes7(mag ^ Fp8Traits<FMT>::kTopX4);
     return c;
   }
-  __device__ __forceinline__ uint32_t one(uint32_t bits) {
+  __device__ __forceinline__ uint32_t one(uint32_t bits, uint32_t mcode) {
     const float f = u2f(bits << 16);
     const float y = f * scale;
     uint32_t c;
@@ -431,27 +457,32 @@ struct CastOp {
     nz_code += (c & 0x7Fu) != 0;
     nz_top += (c & 0x7Fu) != Fp8Traits<FMT>::kTop;
     if constexpr (DELAYED) amax16 = max(amax16 & 0xFFFFu, bits & 0x7FFFu) | (amax16 & 0xFFFF0000u);
+    if constexpr (FUSE) moment(fp8_to_f32<FMT>(c), fp8_to_f32<kE4M3>(mcode));
     return c;
   }
   __device__ __forceinline__ bool fast() const { return !careful; }
   template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
-    uint4 a[UN], b[UN];
+    uint4 a[UN], b[UN], mm[UN];
     const long long pos = pos0 + threadIdx.x * kGroup;
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       a[u] = ld16<kNtLoadRO>(p.src + pos + u * kTile);
       b[u] = ld16<kNtLoadRO>(p.src + pos + u * kTile + 8);
+      if constexpr (FUSE) mm[u] = ld16<kNtLoadRO>(p.m + pos + u * kTile);
     }
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       if constexpr (DELAYED) {
         if (note_source(a[u], b[u])) {   // rare: this group holds inf/NaN, encode it element by element
           const uint32_t w[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
+          const uint32_t mw[4] = {mm[u].x, mm[u].y, mm[u].z, mm[u].w};
           const uint32_t keep = amax16;
           uint4 o = make_uint4(0, 0, 0, 0);
           uint32_t* ow = &o.x;
 #pragma unroll
-          for (int j = 0; j < 16; ++j) ow[j >> 2] |= one((w[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu) << ((j & 3) * 8);
+          for (int j = 0; j < 16; ++j)
+            ow[j >> 2] |= one((w[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu, FUSE ? (mw[j >> 2] >> ((j & 3) * 8)) & 0xFFu : 0u)
+                          << ((j & 3) * 8);
           amax16 = keep;
           st16<kNtStoreWO>(p.dst + pos + u * kTile, o);
           continue;
@@ -462,18 +493,25 @@ struct CastOp {
       o.y = quad(a[u].z, a[u].w);
       o.z = quad(b[u].x, b[u].y);
       o.w = quad(b[u].z, b[u].w);
+      if constexpr (FUSE) {
+        moment_word(o.x, mm[u].x);
+        moment_word(o.y, mm[u].y);
+        moment_word(o.z, mm[u].z);
+        moment_word(o.w, mm[u].w);
+      }
       st16<kNtStoreWO>(p.dst + pos + u * kTile, o);
     }
     n_elems += UN * kGroup;
   }
   __device__ __forceinline__ void group(long long pos, int valid) {
-    for (int j = 0; j < valid; ++j) p.dst[pos + j] = (uint8_t)one(p.src[pos + j]);
+    for (int j = 0; j < valid; ++j) p.dst[pos + j] = (uint8_t)one(p.src[pos + j], FUSE ? p.m[pos + j] : 0u);
     n_elems += valid;
   }
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<2, 2> s;
+    BlockStats<3, 2> s;
     s.mx[0] = f2u(vmax);
     s.mx[1] = max(amax16 & 0xFFFFu, amax16 >> 16);
+    s.mx[2] = macc;
     s.ct[0] = n_elems - nz_top;                 // codes on the top magnitude
     s.ct[1] = (n_elems - nz_code) - z_in;       // zero codes that did not come from zero inputs
     s.orv = 0;
@@ -482,11 +520,13 @@ struct CastOp {
       Scratch* sc = tb.scratch + t;
       atomic_max_u32(&sc->max_a, s.mx[0]);
       atomic_max_u32(&sc->max_b, s.mx[1]);
+      if constexpr (FUSE) atomic_max_u32(&sc->max_c, s.mx[2]);
       atomic_add_u64(&sc->cnt[0], s.ct[0]);
       atomic_add_u64(&sc->cnt[1], s.ct[1]);
       if (publish_ticket(sc, done, d.n_chunks)) {
         const float vm = u2f(take_u32(&sc->max_a));
         const uint32_t abits = take_u32(&sc->max_b);
+        if constexpr (FUSE) sc->pend.amax_m_bits = take_u32(&sc->max_c);
         const unsigned long long n_sat = take_u64(&sc->cnt[0]), n_und = take_u64(&sc->cnt[1]);
         take_u32(&sc->ticket);
         if constexpr (DELAYED) {
@@ -513,9 +553,9 @@ struct CastOp {
   }
 };
 
-template <int FMT, bool DELAYED>
+template <int FMT, bool DELAYED, bool FUSE>
 __global__ __launch_bounds__(kThreads) void cast_kernel(Tables tb, CastParams p) {
-  CastOp<FMT, DELAYED> op(p, tb);
+  CastOp<FMT, DELAYED, FUSE> op(p, tb);
   walk_chunks<FP8LM_UN_CAST>(tb, op);
 }
 
@@ -886,6 +926,15 @@ __global__ void adam_predict_scales_kernel(Tables tb, AdamParams p, int n) {
   if (t >= n || tb.desc[t].numel == 0) return;
   const float Bm = __builtin_fmaf(p.b1, p.m_meta[t].amax_deq, p.omb1 * p.grad_meta[t].amax_deq);
   adam_choose_scales<WCOPY>(p, tb.scratch[t].pend, t, Bm);
+}
+
+// The first pass was done by a fused cast: its result sits in the scratch.  One thread per tensor.
+template <int WCOPY>
+__global__ void adam_scales_from_cast_kernel(Tables tb, AdamParams p, int n) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n || tb.desc[t].numel == 0) return;
+  const uint32_t bits = tb.scratch[t].pend.amax_m_bits;
+  adam_choose_scales<WCOPY>(p, tb.scratch[t].pend, t, bits >= 0x7F800000u ? __builtin_inff() : u2f(bits));
 }
 
 // ---- pass A: exact amax of the new first moment, then all four scales ---------------------------
@@ -1276,12 +1325,15 @@ struct fp8lm_ctx {
   int num_cus = 0;
   std::vector<fp8lm_tensor> tensors;
   int32_t chunk_elems = 16384;
-  int32_t blocks_per_cu = 8;
+  int32_t blocks_per_cu = 16;
   int32_t interleave = 0;
   int32_t n_chunks = 0;
   TensorDesc* d_desc = nullptr;
   int32_t* d_chunk_tensor = nullptr;
   Scratch* d_scratch = nullptr;
+  // what the last fused cast measured for (checked by the Adam step that wants to use it)
+  struct Fused { bool valid; const uint8_t* grad; const uint8_t* m; const fp8lm_meta* m_meta; float b1; int fmt; };
+  Fused fused{false, nullptr, nullptr, nullptr, 0.0f, 0};
   // timing
   bool timing = false;
   struct Stamp { int kernel; hipEvent_t a, b; };
@@ -1505,50 +1557,69 @@ fp8lm_status fp8lm_amax_scale(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
   return after_launch();
 }
 
-fp8lm_status fp8lm_cast_fp8(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
-                            fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {
+// Common body of the three cast entry points.
+static fp8lm_status cast_impl(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
+                              fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, bool delayed, bool fuse,
+                              const uint8_t* m, const fp8lm_meta* m_meta, float beta1, void* stream) {
   if (!c || !cfg_ok(cfg) || src_type != FP8LM_SRC_BF16 || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2))
     return FP8LM_ERR_INVALID_ARGUMENT;
+  c->fused.valid = false;
+  if (fuse && !(beta1 >= 0.0f && beta1 < 1.0f)) return FP8LM_ERR_INVALID_ARGUMENT;
   if (c->n_chunks == 0) return FP8LM_OK;
-  if (!src || !dst || !meta) return FP8LM_ERR_INVALID_ARGUMENT;
-  if (!aligned16(src) || !aligned16(dst)) return FP8LM_ERR_MISALIGNED;
+  if (!src || !dst || !meta || (fuse && (!m || !m_meta))) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!aligned16(src) || !aligned16(dst) || (fuse && !aligned16(m))) return FP8LM_ERR_MISALIGNED;
   DeviceGuard guard(c->device);
-  CastParams p{static_cast<const uint16_t*>(src), dst, meta, cfg->sat_num, cfg->sat_den, cfg->ramp_steps,
-               cfg->hist_window};
-  Timed tm(c, (hipStream_t)stream, FP8LM_K_CAST);
-  if (fmt == FP8LM_E4M3)
-    hipLaunchKernelGGL((cast_kernel<kE4M3, false>), dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream,
-                       tables_of(c), p);
-  else
-    hipLaunchKernelGGL((cast_kernel<kE5M2, false>), dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream,
-                       tables_of(c), p);
-  return after_launch();
+  hipStream_t s = (hipStream_t)stream;
+  if (delayed) {
+    Timed tm(c, s, FP8LM_K_SCALARS);
+    hipLaunchKernelGGL(delayed_scale_kernel, dim3((c->n_tensors + 255) / 256), dim3(256), 0, s, c->d_desc, meta,
+                       c->n_tensors, fmt == FP8LM_E4M3 ? kBitsE4M3Max : kBitsE5M2Max, cfg->hist_window, cfg->margin);
+    fp8lm_status st = after_launch();
+    if (st != FP8LM_OK) return st;
+  }
+  CastParams p{};
+  p.src = static_cast<const uint16_t*>(src);
+  p.dst = dst;
+  p.meta = meta;
+  p.sat_num = cfg->sat_num; p.sat_den = cfg->sat_den; p.ramp_steps = cfg->ramp_steps; p.hist_window = cfg->hist_window;
+  p.m = m;
+  p.m_meta = m_meta;
+  p.b1 = beta1;
+  p.omb1 = (float)(1.0 - (double)beta1);
+  const dim3 g(grid_of(c)), b(kThreads);
+  const Tables tb = tables_of(c);
+  {
+    Timed tm(c, s, FP8LM_K_CAST);
+#define FP8LM_CAST_LAUNCH(F)                                                                              \
+    do {                                                                                                    \
+      if (delayed && fuse) hipLaunchKernelGGL((cast_kernel<F, true, true>), g, b, 0, s, tb, p);             \
+      else if (delayed) hipLaunchKernelGGL((cast_kernel<F, true, false>), g, b, 0, s, tb, p);               \
+      else if (fuse) hipLaunchKernelGGL((cast_kernel<F, false, true>), g, b, 0, s, tb, p);                  \
+      else hipLaunchKernelGGL((cast_kernel<F, false, false>), g, b, 0, s, tb, p);                           \
+    } while (0)
+    if (fmt == FP8LM_E4M3) FP8LM_CAST_LAUNCH(kE4M3);
+    else FP8LM_CAST_LAUNCH(kE5M2);
+#undef FP8LM_CAST_LAUNCH
+  }
+  fp8lm_status st = after_launch();
+  if (st == FP8LM_OK && fuse) c->fused = {true, dst, m, m_meta, p.b1, fmt};
+  return st;
+}
+
+fp8lm_status fp8lm_cast_fp8(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
+                            fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {
+  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, false, false, nullptr, nullptr, 0.0f, stream);
 }
 
 fp8lm_status fp8lm_cast_fp8_delayed(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
                                     fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {
-  if (!c || !cfg_ok(cfg) || src_type != FP8LM_SRC_BF16 || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2))
-    return FP8LM_ERR_INVALID_ARGUMENT;
-  if (c->n_chunks == 0) return FP8LM_OK;
-  if (!src || !dst || !meta) return FP8LM_ERR_INVALID_ARGUMENT;
-  if (!aligned16(src) || !aligned16(dst)) return FP8LM_ERR_MISALIGNED;
-  DeviceGuard guard(c->device);
-  hipStream_t s = (hipStream_t)stream;
-  {
-    Timed tm(c, s, FP8LM_K_SCALARS);
-    hipLaunchKernelGGL(delayed_scale_kernel, dim3((c->n_tensors + 255) / 256), dim3(256), 0, s, c->d_desc, meta,
-                       c->n_tensors, fmt == FP8LM_E4M3 ? kBitsE4M3Max : kBitsE5M2Max, cfg->hist_window, cfg->margin);
-  }
-  fp8lm_status st = after_launch();
-  if (st != FP8LM_OK) return st;
-  CastParams p{static_cast<const uint16_t*>(src), dst, meta, cfg->sat_num, cfg->sat_den, cfg->ramp_steps,
-               cfg->hist_window};
-  Timed tm(c, s, FP8LM_K_CAST);
-  if (fmt == FP8LM_E4M3)
-    hipLaunchKernelGGL((cast_kernel<kE4M3, true>), dim3(grid_of(c)), dim3(kThreads), 0, s, tables_of(c), p);
-  else
-    hipLaunchKernelGGL((cast_kernel<kE5M2, true>), dim3(grid_of(c)), dim3(kThreads), 0, s, tables_of(c), p);
-  return after_launch();
+  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, true, false, nullptr, nullptr, 0.0f, stream);
+}
+
+fp8lm_status fp8lm_cast_fp8_for_adam(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
+                                     fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, int32_t delayed,
+                                     const uint8_t* m, const fp8lm_meta* m_meta, float beta1, void* stream) {
+  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, delayed != 0, true, m, m_meta, beta1, stream);
 }
 
 fp8lm_status fp8lm_shared_scale(fp8lm_ctx* c, const fp8lm_meta* const* metas, int32_t n_ranks, float* shared,
@@ -1634,6 +1705,7 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
                                  void* stream) {
   if (!c || !hp || (grad_fmt != FP8LM_E4M3 && grad_fmt != FP8LM_E5M2)) return FP8LM_ERR_INVALID_ARGUMENT;
   if (hp->wcopy != FP8LM_WCOPY_E4M3 && hp->wcopy != FP8LM_WCOPY_BF16) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (hp->m_scale_mode < 0 || hp->m_scale_mode > 2) return FP8LM_ERR_INVALID_ARGUMENT;
   if (!(hp->lr >= 0.0f && hp->lr <= 1024.0f) || !(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) ||
       !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f) || !(hp->eps >= 0x1p-36f && hp->eps < INFINITY) ||
       !(hp->weight_decay >= 0.0f && hp->weight_decay <= 1024.0f) || hp->step < 1)
@@ -1664,7 +1736,16 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
   const dim3 g(grid_of(c)), b(kThreads);
   const Tables tb = tables_of(c);
   const bool e5 = grad_fmt == FP8LM_E5M2, q8 = hp->wcopy == FP8LM_WCOPY_E4M3;
-  if (hp->m_predict) {
+  if (hp->m_scale_mode == FP8LM_MSCALE_FROM_CAST) {
+    const fp8lm_ctx::Fused f = c->fused;
+    c->fused.valid = false;
+    if (!f.valid || f.grad != grad || f.m != m || f.m_meta != m_meta || f.b1 != p.b1 || f.fmt != (int)grad_fmt)
+      return FP8LM_ERR_INVALID_ARGUMENT;
+    Timed tm(c, s, FP8LM_K_SCALARS);
+    const dim3 gs((c->n_tensors + 255) / 256), bs(256);
+    if (q8) hipLaunchKernelGGL((adam_scales_from_cast_kernel<FP8LM_WCOPY_E4M3>), gs, bs, 0, s, tb, p, c->n_tensors);
+    else hipLaunchKernelGGL((adam_scales_from_cast_kernel<FP8LM_WCOPY_BF16>), gs, bs, 0, s, tb, p, c->n_tensors);
+  } else if (hp->m_scale_mode == FP8LM_MSCALE_PREDICTED) {
     Timed tm(c, s, FP8LM_K_SCALARS);
     const dim3 gs((c->n_tensors + 255) / 256), bs(256);
     if (q8) hipLaunchKernelGGL((adam_predict_scales_kernel<FP8LM_WCOPY_E4M3>), gs, bs, 0, s, tb, p, c->n_tensors);

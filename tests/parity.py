@@ -51,7 +51,7 @@ def oracle_cfg(cfg: B.AutoscaleCfg) -> O.AutoscaleCfg:
 
 def oracle_hp(hp: B.AdamHparams) -> O.AdamHparams:
     return O.AdamHparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.step, hp.v_scaled, hp.wcopy,
-                         hp.m_predict)
+                         1 if hp.m_scale_mode == B.MSCALE_PREDICTED else 0)
 
 
 class Snapshot:

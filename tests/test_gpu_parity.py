@@ -236,6 +236,12 @@ def test_argument_errors_are_reported_not_launched():
         with pytest.raises(B.Fp8lmError) as e:
             st.adam(B.adam_hparams(**kw))
         assert e.value.status == -1
+    with pytest.raises(B.Fp8lmError) as e:      # no fused cast came before
+        st.adam(B.adam_hparams(1e-3, 1, m_scale_mode=B.MSCALE_FROM_CAST))
+    assert e.value.status == -1
+    st.ctx.cast_fp8_for_adam(grad, st.g8, B.E5M2, st.g_meta, cfg, st.m, st.m_meta, 0.9)
+    with pytest.raises(B.Fp8lmError):           # another beta1 than the cast measured for
+        st.adam(B.adam_hparams(1e-3, 1, beta1=0.8, m_scale_mode=B.MSCALE_FROM_CAST))
     with pytest.raises(B.Fp8lmError):
         st.ctx.set_tuning(1000, 8, 0)
     bad_cfg = B.autoscale_cfg(hist_window=17)
@@ -262,8 +268,8 @@ def test_amax_history_window_carries_across_steps():
 
 # ---- single-pass variants: delayed gradient scaling and predicted first-moment scale ------------------
 @pytest.mark.parametrize("grad_fmt", [B.E5M2, B.E4M3])
-@pytest.mark.parametrize("m_predict", [0, 1])
-def test_delayed_scaling_and_predicted_moment_scale(grad_fmt, m_predict):
+@pytest.mark.parametrize("m_scale_mode", [B.MSCALE_EXACT_PASS, B.MSCALE_PREDICTED, B.MSCALE_FROM_CAST])
+def test_delayed_scaling_and_moment_scale_modes(grad_fmt, m_scale_mode):
     for wl in (synth.workload("tiny"), synth.Workload("mid", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-3, sigma=None,
                                                       hist_window=2, ramp_steps=6)):
         st, w0 = P.make_state(wl, 11, grad_fmt)
@@ -280,9 +286,9 @@ def test_delayed_scaling_and_predicted_moment_scale(grad_fmt, m_predict):
                 bits[off0 + n0 - 1] = 0xFF80
                 grad = bf16_tensor_from_bits(bits)
             delayed = step > 1                               # the first step seeds the history just in time
-            hp = B.adam_hparams(wl.lr, step, stats=1, m_predict=m_predict)
+            hp = B.adam_hparams(wl.lr, step, stats=1, m_scale_mode=m_scale_mode)
             snaps = [P.Snapshot(st, grad, t) for t in ids]
-            say(f"{wl.name} fmt={grad_fmt} m_predict={m_predict} step={step} delayed={delayed}")
+            say(f"{wl.name} fmt={grad_fmt} m_scale_mode={m_scale_mode} step={step} delayed={delayed}")
             st.step(grad, hp, delayed=delayed)
             torch.cuda.synchronize()
             r = P.check_step(st, snaps, hp, what=f"{wl.name} variants step {step}", delayed=delayed)

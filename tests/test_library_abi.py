@@ -20,7 +20,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     names = declared_functions()
-    assert len(names) >= 18
+    assert len(names) >= 20
     for name in names:
         assert hasattr(L, name), name
     assert sorted(B.EXPORTS) == names
