@@ -134,6 +134,7 @@ def main() -> int:
                          "only); single: delayed gradient scaling + predicted first-moment scale (15 B/param)")
     ap.add_argument("--allreduce-steps", type=int, default=0, metavar="N",
                     help="also time the shared-scale re-quantise kernel and the N-rank FP8 sum (Eq. 4-6) on this layout")
+    ap.add_argument("--only-path", action="store_true", help="do not also time the other two paths")
     ap.add_argument("--no-spread", action="store_true", help="allocate the buffers plainly, one after the other")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -170,25 +171,42 @@ def main() -> int:
     synth.fill_gradients(grad, wl, args.seed, 1)
     torch.cuda.synchronize()
 
-    single = args.path == "single"
-    bytes_per_param = {"jit": 19, "fused": 18, "single": 15}[args.path]
+    bytes_of = {"jit": 19, "fused": 18, "single": 15}
+    mode_of = {"jit": B.MSCALE_EXACT_PASS, "fused": B.MSCALE_FROM_CAST, "single": B.MSCALE_PREDICTED}
+    step_no = [0]
 
-    def hp(step):
-        return B.adam_hparams(wl.lr, step, exact=args.exact, stats=args.stats, m_scale_mode=B.MSCALE_PREDICTED if single else (B.MSCALE_FROM_CAST if args.path == 'fused' else B.MSCALE_EXACT_PASS))
+    def run_steps(path, n):
+        """n steps of one path; the very first step of the run is always just in time (it seeds the history)."""
+        for _ in range(n):
+            step_no[0] += 1
+            hp = B.adam_hparams(wl.lr, step_no[0], exact=args.exact, stats=args.stats, m_scale_mode=mode_of[path])
+            st.step(grad, hp, delayed=(path == "single" and step_no[0] > 1))
 
-    for s in range(1, args.warmup + 1):
-        st.step(grad, hp(s), delayed=single and s > 1)    # the first step seeds the amax history
-    torch.cuda.synchronize()
-    st.ctx.set_timing(True)
-    st.ctx.get_timing()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.warmup + 1, args.warmup + args.steps + 1):
-        st.step(grad, hp(s), delayed=single and s > 1)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    timing = st.ctx.get_timing()
-    st.ctx.set_timing(False)
+    def timed(path, n):
+        torch.cuda.synchronize()
+        st.ctx.set_timing(True)
+        st.ctx.get_timing()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(path, n)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        tm = st.ctx.get_timing()
+        st.ctx.set_timing(False)
+        return dt, tm
+
+    bytes_per_param = bytes_of[args.path]
+    run_steps(args.path, args.warmup)
+    dt, timing = timed(args.path, args.steps)
+    other_paths = {}
+    if not args.only_path:
+        for path in ("jit", "fused", "single"):
+            if path != args.path:
+                run_steps(path, 2)
+                odt, _ = timed(path, min(args.steps, 10))
+                n = min(args.steps, 10)
+                other_paths[path] = {"ms_per_step": round(odt / n * 1e3, 3), "params_per_s": P / (odt / n),
+                                     "bytes_per_param_step": bytes_of[path]}
 
     ms_per_step = dt / args.steps * 1e3
     kernels = {}
@@ -222,6 +240,7 @@ def main() -> int:
         "step_GBps": round(bytes_per_param * P / (dt / args.steps) / 1e9, 1),
         "step_frac_of_peak": round(bytes_per_param * P / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
         "kernels": kernels,
+        "other_paths": other_paths,
         "roofline": {"kernel": "adam_update_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(wl.name)},
     }

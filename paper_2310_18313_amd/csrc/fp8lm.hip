@@ -798,14 +798,29 @@ struct InitCastOp {
   float scale;
   float vmax;
   uint32_t n_sat, n_und;
+  bool careful;
   __device__ InitCastOp(const InitParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
   __device__ __forceinline__ void begin(int t, const TensorDesc&) {
     scale = p.meta[t].scale;
+    careful = (p.meta[t].flags & FP8LM_FLAG_NONFINITE) != 0;   // set by the amax pass just before
     vmax = 0.0f;
     n_sat = n_und = 0;
   }
-  __device__ __forceinline__ bool fast() const { return false; }
-  template <int UN> __device__ __forceinline__ void tiles(long long) {}
+  __device__ __forceinline__ bool fast() const { return !careful; }
+  __device__ __forceinline__ uint32_t pair(uint32_t w) {
+    const float y0 = bf16lo_to_f32(w) * scale, y1 = bf16hi_to_f32(w) * scale;
+    vmax = fmaxf(vmax, fmaxf(fabsf(clamp_f16(y0)), fabsf(clamp_f16(y1))));
+    n_sat += (fabsf(y0) > 65488.0f) + (fabsf(y1) > 65488.0f);                 // rounds to the top FP16 code
+    n_und += ((fabsf(y0) <= 0x1p-25f) && (w & 0x7FFFu)) + ((fabsf(y1) <= 0x1p-25f) && (w & 0x7FFF0000u));
+    return encode2_f16(y0, y1);
+  }
+  template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
+    static_assert(UN == 1, "one group at a time");
+    const long long pos = pos0 + threadIdx.x * kGroup;
+    const uint4 a = ld16<kNtLoadRO>(p.src + pos), b = ld16<kNtLoadRO>(p.src + pos + 8);
+    st16<kNtStoreWO>(p.dst + pos, make_uint4(pair(a.x), pair(a.y), pair(a.z), pair(a.w)));
+    st16<kNtStoreWO>(p.dst + pos + 8, make_uint4(pair(b.x), pair(b.y), pair(b.z), pair(b.w)));
+  }
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) {
       const uint32_t bits = p.src[pos + j];
