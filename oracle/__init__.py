@@ -19,6 +19,7 @@ _LIB = os.path.join(_HERE, "_build", "libfp8lm_oracle.so")
 HIST = 16
 E4M3, E5M2 = 0, 1
 WCOPY_E4M3, WCOPY_BF16 = 0, 1
+ST_F16, ST_BF16, ST_E4M3, ST_F32 = 0, 1, 2, 3
 FLAG_NONFINITE, FLAG_AMAX_ZERO, FLAG_SCALE_CLAMPED, FLAG_SATURATED = 1, 2, 4, 8
 
 
@@ -50,7 +51,7 @@ class AutoscaleCfg(C.Structure):
 class AdamHparams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float), ("step", C.c_int64), ("v_scaled", C.c_int32),
-                ("wcopy", C.c_int32), ("m_predict", C.c_int32)]
+                ("wcopy", C.c_int32), ("m_predict", C.c_int32), ("master_fmt", C.c_int32), ("v_fmt", C.c_int32)]
 
 
 def default_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=100000):
@@ -122,6 +123,8 @@ def lib():
         L.oracle_greedy_partition.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.oracle_init_master.restype = None
         L.oracle_init_master.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.oracle_init_master_as.restype = None
+        L.oracle_init_master_as.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int]
         L.oracle_adam_step_fp8.restype = None
         L.oracle_adam_step_fp8.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int, C.c_void_p] + \
             [C.c_void_p] * 8 + [C.c_void_p]
@@ -203,10 +206,18 @@ def init_master(w_bf16: np.ndarray, tensors: np.ndarray, w_f16: np.ndarray, w_me
     lib().oracle_init_master(_p(w_bf16), _p(tensors), len(tensors), _p(w_f16), _p(w_meta))
 
 
+STATE_DTYPE = {ST_F16: np.uint16, ST_BF16: np.uint16, ST_E4M3: np.uint8, ST_F32: np.uint32}
+
+
+def init_master_as(w_bf16: np.ndarray, tensors: np.ndarray, w_out: np.ndarray, w_meta: np.ndarray, master_fmt: int) -> None:
+    assert w_bf16.dtype == np.uint16 and w_out.dtype == STATE_DTYPE[master_fmt]
+    lib().oracle_init_master_as(_p(w_bf16), _p(tensors), len(tensors), _p(w_out), _p(w_meta), master_fmt)
+
+
 def adam_step_fp8(tensors, grad, grad_fmt, grad_meta, m, m_meta, v, v_meta, w, w_meta, wcopy,
                   wcopy_meta, hp: AdamHparams) -> None:
     assert grad.dtype == np.uint8 and m.dtype == np.uint8
-    assert v.dtype == np.uint16 and w.dtype == np.uint16
+    assert v.dtype == STATE_DTYPE[hp.v_fmt] and w.dtype == STATE_DTYPE[hp.master_fmt]
     assert wcopy.dtype == (np.uint8 if hp.wcopy == WCOPY_E4M3 else np.uint16)
     lib().oracle_adam_step_fp8(_p(tensors), len(tensors), _p(grad), grad_fmt, _p(grad_meta),
                                _p(m), _p(m_meta), _p(v), _p(v_meta), _p(w), _p(w_meta),

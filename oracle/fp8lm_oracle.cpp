@@ -171,6 +171,10 @@ typedef struct {
   int32_t wcopy;       // 0: E4M3 weight copy with its own scale; 1: bf16 weight copy
   int32_t m_predict;   // 0: first-moment scale from the exact amax of the new moment (just-in-time);
                        // 1: from the bound fma(beta1, amax_deq(m), (1-beta1) * amax_deq(g)), no extra pass
+  // Storage formats of the precision-decoupling study (Sec. 3.3, the table of optimizer settings):
+  int32_t master_fmt;  // 0 FP16 with tensor scaling (setting 2a, the default), 1 BF16 (2b), 2 E4M3 with
+                       // tensor scaling (3), 3 FP32 (the alternative named in Sec. 2.2)
+  int32_t v_fmt;       // 0 FP16 (scaled or plain as v_scaled says), 2 E4M3 with tensor scaling (setting 4)
 } oracle_adam_hparams;
 
 // ---- scalar format functions exported for the pins -------------------------------------------
@@ -452,16 +456,69 @@ void oracle_sum_fp8(const uint8_t* const* payloads, int32_t n_ranks, int fmt, co
   }
 }
 
+// ---- storage formats of the optimizer state (precision decoupling, Sec. 2.2 and 3.3) ------------
+enum { ST_F16 = 0, ST_BF16 = 1, ST_E4M3 = 2, ST_F32 = 3 };
+static float st_decode(int kind, uint32_t code) {
+  switch (kind) {
+    case ST_F16: return dec_f16(uint16_t(code));
+    case ST_BF16: return dec_bf16(uint16_t(code));
+    case ST_E4M3: return dec_e4m3(uint8_t(code));
+    default: return bits_f32(code);
+  }
+}
+static uint32_t st_load(int kind, const void* buf, int64_t i) {
+  switch (kind) {
+    case ST_F16: case ST_BF16: return static_cast<const uint16_t*>(buf)[i];
+    case ST_E4M3: return static_cast<const uint8_t*>(buf)[i];
+    default: return static_cast<const uint32_t*>(buf)[i];
+  }
+}
+static void st_store(int kind, void* buf, int64_t i, uint32_t code) {
+  switch (kind) {
+    case ST_F16: case ST_BF16: static_cast<uint16_t*>(buf)[i] = uint16_t(code); break;
+    case ST_E4M3: static_cast<uint8_t*>(buf)[i] = uint8_t(code); break;
+    default: static_cast<uint32_t*>(buf)[i] = code;
+  }
+}
+// FP16 and E4M3 saturate; BF16 and FP32 follow IEEE (overflow to infinity), NaN is canonical
+static uint32_t st_encode(int kind, float x) {
+  switch (kind) {
+    case ST_F16: return enc_f16_sat(x);
+    case ST_BF16: return enc_bf16(x);
+    case ST_E4M3: return enc_e4m3(x);
+    default: return x != x ? 0x7FC00000u : f32_bits(x);
+  }
+}
+static uint32_t st_mag(int kind, uint32_t code) {
+  switch (kind) {
+    case ST_F16: case ST_BF16: return code & 0x7FFFu;
+    case ST_E4M3: return code & 0x7Fu;
+    default: return code & 0x7FFFFFFFu;
+  }
+}
+// the code counted by n_sat: the largest finite code of a saturating format, infinity otherwise
+static uint32_t st_topcode(int kind) {
+  switch (kind) {
+    case ST_F16: return 0x7BFFu;
+    case ST_BF16: return 0x7F80u;
+    case ST_E4M3: return 0x7Eu;
+    default: return 0x7F800000u;
+  }
+}
+static bool st_scaled(int kind) { return kind == ST_F16 || kind == ST_E4M3; }
+static float st_fmax(int kind) { return kind == ST_E4M3 ? kE4M3.fmax : kF16.fmax; }
+
 // ---- master-weight initialisation ----------------------------------------------------------------
 // Sec. 2.2: master weights are FP16 with tensor scaling.  The scale leaves one binade of
 // headroom above the initial amax so that weights can grow between scale refreshes.
-void oracle_init_master(const uint16_t* w_bf16, const oracle_tensor* tensors, int32_t n_tensors,
-                        uint16_t* w_f16, oracle_meta* w_meta) {
+void oracle_init_master_as(const uint16_t* w_bf16, const oracle_tensor* tensors, int32_t n_tensors,
+                           void* w_out, oracle_meta* w_meta, int master_fmt) {
+  const int wk = master_fmt;
   for (int32_t t = 0; t < n_tensors; ++t) {
     const int64_t n = tensors[t].numel;
     if (n == 0) continue;
-    const uint16_t* src = w_bf16 + tensors[t].offset;
-    uint16_t* dst = w_f16 + tensors[t].offset;
+    const int64_t off = tensors[t].offset;
+    const uint16_t* src = w_bf16 + off;
     oracle_meta& M = w_meta[t];
     bool nonfinite = false;
     float A = 0.0f;
@@ -474,23 +531,24 @@ void oracle_init_master(const uint16_t* w_bf16, const oracle_tensor* tensors, in
     M.amax = nonfinite ? std::numeric_limits<float>::infinity() : A;
     if (nonfinite) flags |= ORACLE_FLAG_NONFINITE;
     else if (A == 0.0f) flags |= ORACLE_FLAG_AMAX_ZERO;
-    else {
-      const int k = pow2_exp(kF16.fmax, A) - 1;
+    else if (st_scaled(wk)) {
+      const int k = pow2_exp(st_fmax(wk), A) - 1;
       const int e = clampi(k, -126, 126);
       if (e != k) flags |= ORACLE_FLAG_SCALE_CLAMPED;
       M.scale = std::ldexp(1.0f, e);
       M.inv_scale = std::ldexp(1.0f, -e);
     }
+    if (!st_scaled(wk)) { M.scale = 1.0f; M.inv_scale = 1.0f; }
     float stored_max = 0.0f;
     uint64_t n_sat = 0, n_under = 0;
     for (int64_t i = 0; i < n; ++i) {
       const float x = dec_bf16(src[i]);
-      const uint16_t h = enc_f16_sat(x * M.scale);
-      dst[i] = h;
-      const float d = std::fabs(dec_f16(h));
-      if (d == d && d > stored_max) stored_max = d;
-      if ((h & 0x7FFFu) == kF16.maxcode) ++n_sat;
-      if ((src[i] & 0x7FFFu) != 0 && (h & 0x7FFFu) == 0) ++n_under;
+      const uint32_t c = st_encode(wk, x * M.scale);
+      st_store(wk, w_out, off + i, c);
+      const float d = std::fabs(st_decode(wk, c));
+      if (d <= std::numeric_limits<float>::max() && d > stored_max) stored_max = d;
+      if (st_mag(wk, c) == st_topcode(wk)) ++n_sat;
+      if ((src[i] & 0x7FFFu) != 0 && st_mag(wk, c) == 0) ++n_under;
     }
     M.amax_deq = stored_max * M.inv_scale;
     M.n_sat = n_sat;
@@ -498,6 +556,11 @@ void oracle_init_master(const uint16_t* w_bf16, const oracle_tensor* tensors, in
     if (n_sat > 0) flags |= ORACLE_FLAG_SATURATED;
     M.flags = flags;
   }
+}
+
+void oracle_init_master(const uint16_t* w_bf16, const oracle_tensor* tensors, int32_t n_tensors,
+                        uint16_t* w_f16, oracle_meta* w_meta) {
+  oracle_init_master_as(w_bf16, tensors, n_tensors, w_f16, w_meta, ST_F16);
 }
 
 // ---- step a5 + a6: the FP8 Adam step ---------------------------------------------------------
@@ -541,14 +604,15 @@ static void refresh_scale(float fmax, float bound, int headroom, float old_scale
 void oracle_adam_step_fp8(const oracle_tensor* tensors, int32_t n_tensors,
                           const uint8_t* grad, int grad_fmt, const oracle_meta* grad_meta,
                           uint8_t* m, oracle_meta* m_meta,
-                          uint16_t* v, oracle_meta* v_meta,
-                          uint16_t* w, oracle_meta* w_meta,
+                          void* v, oracle_meta* v_meta,
+                          void* w, oracle_meta* w_meta,
                           void* wcopy, oracle_meta* wcopy_meta,
                           const oracle_adam_hparams* hp) {
   float b1, omb1, rbc1, b2, omb2, rbc2, decay;
   derive_hparams(hp, b1, omb1, rbc1, b2, omb2, rbc2, decay);
   const float lr = hp->lr, eps = hp->eps;
   const float INF = std::numeric_limits<float>::infinity();
+  const int wk = hp->master_fmt, vk = hp->v_fmt;
 
   for (int32_t t = 0; t < n_tensors; ++t) {
     const int64_t n = tensors[t].numel;
@@ -556,8 +620,6 @@ void oracle_adam_step_fp8(const oracle_tensor* tensors, int32_t n_tensors,
     const int64_t off = tensors[t].offset;
     const uint8_t* qg = grad + off;
     uint8_t* qm = m + off;
-    uint16_t* hv = v + off;
-    uint16_t* hw = w + off;
     const float inv_sg = grad_meta[t].inv_scale;
     const float inv_sm = m_meta[t].inv_scale;
     const float inv_sv = v_meta[t].inv_scale;
@@ -587,14 +649,18 @@ void oracle_adam_step_fp8(const oracle_tensor* tensors, int32_t n_tensors,
     } else {
       refresh_scale(kE4M3.fmax, m_nonfinite ? INF : A_m, 0, m_meta[t].scale, m_meta[t].inv_scale, sm, ism, fm);
     }
-    if (hp->v_scaled) {
+    if (hp->v_scaled || vk == ST_E4M3) {
       const float Ag = grad_meta[t].amax_deq;
       const float Bv = std::fmaf(b2, v_meta[t].amax_deq, omb2 * (Ag * Ag));
-      refresh_scale(kF16.fmax, Bv, 0, v_meta[t].scale, v_meta[t].inv_scale, sv, isv, fv);
+      refresh_scale(st_fmax(vk), Bv, 0, v_meta[t].scale, v_meta[t].inv_scale, sv, isv, fv);
     } else {
       sv = 1.0f; isv = 1.0f;
     }
-    refresh_scale(kF16.fmax, w_meta[t].amax_deq, 1, w_meta[t].scale, w_meta[t].inv_scale, sw, isw, fw);
+    if (st_scaled(wk)) {
+      refresh_scale(st_fmax(wk), w_meta[t].amax_deq, 1, w_meta[t].scale, w_meta[t].inv_scale, sw, isw, fw);
+    } else {
+      sw = 1.0f; isw = 1.0f;       // BF16 and FP32 master weights carry no scale
+    }
     if (hp->wcopy == 0) {
       refresh_scale(kE4M3.fmax, w_meta[t].amax_deq, 0, wcopy_meta[t].scale, wcopy_meta[t].inv_scale, sq, isq, fq);
     } else {
@@ -610,8 +676,8 @@ void oracle_adam_step_fp8(const oracle_tensor* tensors, int32_t n_tensors,
     for (int64_t i = 0; i < n; ++i) {
       const float g = dec_fp8(grad_fmt, qg[i]) * inv_sg;
       const float m0 = dec_e4m3(qm[i]) * inv_sm;
-      const float v0 = dec_f16(hv[i]) * inv_sv;
-      const float w0 = dec_f16(hw[i]) * inv_sw;
+      const float v0 = st_decode(vk, st_load(vk, v, off + i)) * inv_sv;
+      const float w0 = st_decode(wk, st_load(wk, w, off + i)) * inv_sw;
       const float m1 = std::fmaf(b1, m0, omb1 * g);
       const float v1 = std::fmaf(b2, v0, omb2 * (g * g));
       const float den = std::sqrt(v1 * rbc2) + eps;
@@ -619,22 +685,22 @@ void oracle_adam_step_fp8(const oracle_tensor* tensors, int32_t n_tensors,
       const float w1 = std::fmaf(-lr, upd, w0 * decay);
 
       const uint8_t cm = enc_e4m3(m1 * sm);
-      const uint16_t cv = enc_f16_sat(v1 * sv);
-      const uint16_t cw = enc_f16_sat(w1 * sw);
+      const uint32_t cv = st_encode(vk, v1 * sv);
+      const uint32_t cw = st_encode(wk, w1 * sw);
       qm[i] = cm;
-      hv[i] = cv;
-      hw[i] = cw;
+      st_store(vk, v, off + i, cv);
+      st_store(wk, w, off + i, cw);
 
       float d;
       d = std::fabs(dec_e4m3(cm)); if (d == d && d > st_m) st_m = d;
-      d = std::fabs(dec_f16(cv));  if (d == d && d > st_v) st_v = d;
-      d = std::fabs(dec_f16(cw));  if (d == d && d > st_w) st_w = d;
+      d = std::fabs(st_decode(vk, cv)); if (d <= std::numeric_limits<float>::max() && d > st_v) st_v = d;
+      d = std::fabs(st_decode(wk, cw)); if (d <= std::numeric_limits<float>::max() && d > st_w) st_w = d;
       if ((cm & 0x7Fu) == kE4M3.maxcode) ++sat_m;
-      if ((cv & 0x7FFFu) == kF16.maxcode) ++sat_v;
-      if ((cw & 0x7FFFu) == kF16.maxcode) ++sat_w;
+      if (st_mag(vk, cv) == st_topcode(vk)) ++sat_v;
+      if (st_mag(wk, cw) == st_topcode(wk)) ++sat_w;
       if (m1 != 0.0f && (cm & 0x7Fu) == 0) ++und_m;
-      if (v1 != 0.0f && (cv & 0x7FFFu) == 0) ++und_v;
-      if (w1 != 0.0f && (cw & 0x7FFFu) == 0) ++und_w;
+      if (v1 != 0.0f && st_mag(vk, cv) == 0) ++und_v;
+      if (w1 != 0.0f && st_mag(wk, cw) == 0) ++und_w;
 
       float a = std::fabs(v1);
       if (!(a <= std::numeric_limits<float>::max())) v_nonfinite = true; else if (a > A_v) A_v = a;

@@ -219,3 +219,141 @@ def test_sum_of_one_rank_is_the_identity_and_equal_ranks_double():
     twice = O.encode_fp8(O.E5M2, 2 * dec8(O.E5M2, q[0]))
     assert np.array_equal(out[used], twice[used])
     assert smeta["n_sat"].sum() > 0                   # the top binade doubles past the largest code and clips
+
+
+# ---- storage formats of the precision-decoupling study (Sec. 2.2; Sec. 3.3, table of optimizer settings) ---
+class VState:
+    """Optimizer state on the host with selectable master-weight and second-moment formats."""
+
+    def __init__(self, lay, w_init_bits, master_fmt, v_fmt):
+        self.lay, self.master_fmt, self.v_fmt = lay, master_fmt, v_fmt
+        self.tens = O.tensors_array(lay.tensors())
+        self.cfg = O.default_cfg()
+        n = lay.n_tensors
+        self.metas = {k: O.new_meta(n, self.cfg) for k in "gmvwq"}
+        self.g8 = np.zeros(lay.total, np.uint8)
+        self.m = np.zeros(lay.total, np.uint8)
+        self.v = np.zeros(lay.total, O.STATE_DTYPE[v_fmt])
+        self.w = np.zeros(lay.total, O.STATE_DTYPE[master_fmt])
+        self.wq = np.zeros(lay.total, np.uint8)
+        O.init_master_as(w_init_bits, self.tens, self.w, self.metas["w"], master_fmt)
+
+    def step(self, gbits, lr, t, v_scaled=1, eps=1e-8, wd=0.1):
+        O.amax_scale(gbits, self.tens, O.E5M2, self.metas["g"], self.cfg)
+        O.cast_fp8(gbits, self.tens, self.g8, O.E5M2, self.metas["g"], self.cfg)
+        hp = O.AdamHparams(lr, 0.9, 0.95, eps, wd, t, v_scaled, O.WCOPY_E4M3, 0, self.master_fmt, self.v_fmt)
+        O.adam_step_fp8(self.tens, self.g8, O.E5M2, self.metas["g"], self.m, self.metas["m"], self.v, self.metas["v"],
+                        self.w, self.metas["w"], self.wq, self.metas["q"], hp)
+
+    @staticmethod
+    def decode(fmt, bits):
+        if fmt == O.ST_F16:
+            return bits.view(np.float16).astype(np.float64)
+        if fmt == O.ST_BF16:
+            return bf16_vals(bits).astype(np.float64)
+        if fmt == O.ST_E4M3:
+            return dec8(O.E4M3, bits).astype(np.float64)
+        return bits.view(np.float32).astype(np.float64)
+
+    def values(self, k):
+        off, n = self.lay.tensors()[k]
+        sl = slice(off, off + n)
+        return dict(g=dec8(O.E5M2, self.g8[sl]).astype(np.float64) * float(self.metas["g"][k]["inv_scale"]),
+                    m=dec8(O.E4M3, self.m[sl]).astype(np.float64) * float(self.metas["m"][k]["inv_scale"]),
+                    v=self.decode(self.v_fmt, self.v[sl]) * float(self.metas["v"][k]["inv_scale"]),
+                    w=self.decode(self.master_fmt, self.w[sl]) * float(self.metas["w"][k]["inv_scale"]))
+
+
+# half the gap between neighbours: (relative for normal values, absolute payload for subnormal ones)
+HALF_GAP = {O.ST_F16: (2.0 ** -11, 2.0 ** -25), O.ST_BF16: (2.0 ** -8, 0.0), O.ST_E4M3: (2.0 ** -4, 2.0 ** -10),
+            O.ST_F32: (2.0 ** -24, 0.0)}
+
+
+@pytest.mark.parametrize("master_fmt", [O.ST_F16, O.ST_BF16, O.ST_E4M3, O.ST_F32])
+@pytest.mark.parametrize("v_fmt", [O.ST_F16, O.ST_E4M3])
+def test_state_formats_single_step_equals_float64_adamw_then_storage_rounding(master_fmt, v_fmt):
+    wl = synth.workload("tiny")
+    lay = wl.layout
+    rng = np.random.default_rng(7)
+    st = VState(lay, _grad(lay, rng, [0.02] * 6), master_fmt, v_fmt)
+    sig = [1e-3, 1e-2, 3e-5, 1.0, 1.0, 2e-4]
+    lr, eps, wd = (float(np.float32(x)) for x in (1e-3, 1e-8, 0.1))
+    b1, b2 = float(np.float32(0.9)), float(np.float32(0.95))
+    for k, (off, n) in enumerate(lay.tensors()):
+        if n:   # the initial master weights are the bf16 weights rounded to the storage format
+            w0 = bf16_vals(_grad(lay, np.random.default_rng(7), [0.02] * 6)[off:off + n]).astype(np.float64)
+            rel, sub = HALF_GAP[master_fmt]
+            sw = float(st.metas["w"][k]["scale"])
+            assert np.all(np.abs(st.values(k)["w"] - w0) <= np.maximum(np.abs(w0) * rel, sub / sw) * (1 + 1e-6))
+            if master_fmt in (O.ST_BF16, O.ST_F32):
+                assert sw == 1.0 and np.array_equal(st.values(k)["w"], w0)
+    for t in range(1, 6):
+        g = _grad(lay, rng, sig)
+        before = [st.values(k) if n else None for k, (o, n) in enumerate(lay.tensors())]
+        st.step(g, lr, t)
+        for k, (off, n) in enumerate(lay.tensors()):
+            if n == 0:
+                continue
+            after = st.values(k)
+            m1, v1, w1 = _adamw64_step(after["g"], before[k]["m"], before[k]["v"], before[k]["w"], lr, b1, b2, eps, wd, t)
+            for key, ref, fmt in (("v", v1, v_fmt), ("w", w1, master_fmt)):
+                rel, sub = HALF_GAP[fmt]
+                s = float(st.metas[key][k]["scale"])
+                tol = np.maximum(np.abs(ref) * rel, sub / s) * (1 + 1e-3) + np.abs(ref) * 1e-6 + (lr * 1e-5 if key == "w" else 0)
+                assert np.all(np.abs(after[key] - ref) <= tol), (key, fmt, t, k)
+                assert st.metas[key][k]["n_sat"] == 0
+                assert float(st.metas[key][k]["amax_deq"]) == np.float32(np.abs(after[key]).max())
+            if master_fmt in (O.ST_F16, O.ST_E4M3):
+                a = np.abs(before[k]["w"]).max()
+                fmax = 65504.0 if master_fmt == O.ST_F16 else 448.0
+                sw = float(st.metas["w"][k]["scale"])
+                assert 2 * sw * a <= fmax < 4 * sw * a
+            else:
+                assert st.metas["w"][k]["scale"] == 1.0
+            if v_fmt == O.ST_E4M3:
+                assert np.abs(v1).max() * float(st.metas["v"][k]["scale"]) <= 448.0 * (1 + 1e-6)
+
+
+def test_fp8_master_weights_swallow_small_updates_and_fp16_does_not():
+    """Sec. 3.3 on the optimizer settings: the master weight is the precision-sensitive variable.  With
+    lr = 1e-4 an update is about 0.5 % of a typical weight: far below half an E4M3 gap (6 %), well
+    above half an FP16 gap (0.05 %)."""
+    n = 20000
+    lay = synth.flat_layout(n)
+    rng = np.random.default_rng(1)
+    wbits = np.zeros(lay.total, np.uint16)
+    wbits[:n] = bf16_bits(rng.standard_normal(n) * 0.02)
+    gbits = np.zeros(lay.total, np.uint16)
+    gbits[:n] = bf16_bits(rng.standard_normal(n) * 1e-4)
+    moved = {}
+    for fmt in (O.ST_F16, O.ST_BF16, O.ST_E4M3, O.ST_F32):
+        st = VState(lay, wbits, fmt, O.ST_F16)
+        w0 = st.values(0)["w"].copy()
+        st.step(gbits, 1e-4, 1, wd=0.0)
+        moved[fmt] = np.mean(st.values(0)["w"] != w0)
+    assert moved[O.ST_F32] > 0.999 and moved[O.ST_F16] > 0.9
+    assert moved[O.ST_E4M3] < 0.15
+    assert moved[O.ST_E4M3] < moved[O.ST_BF16] < moved[O.ST_F16]
+
+
+def test_fp8_second_moment_flushes_small_entries_to_zero():
+    """Sec. 2.2 / 3.3: squaring small gradients underflows in a narrow format.  E4M3 spans 448 / 2^-9 =
+    2^17.8, so every v below amax * 2^-18.8 is stored as zero; FP16 with the same kind of scale keeps them."""
+    n = 50000
+    lay = synth.flat_layout(n)
+    rng = np.random.default_rng(2)
+    wbits = np.zeros(lay.total, np.uint16)
+    gbits = np.zeros(lay.total, np.uint16)
+    gbits[:n] = bf16_bits(rng.standard_normal(n) * 1e-4)
+    zeros = {}
+    for vf in (O.ST_F16, O.ST_E4M3):
+        st = VState(lay, wbits, O.ST_F16, vf)
+        st.step(gbits, 1e-4, 1)
+        v = st.values(0)["v"]
+        g = st.values(0)["g"]
+        zeros[vf] = np.mean((v == 0) & (g != 0))
+        if vf == O.ST_E4M3:
+            vmax = v.max()
+            exact = 0.05 * g ** 2
+            assert np.all(v[exact < vmax * 2.0 ** -19.9] == 0)
+    assert zeros[O.ST_F16] == 0 and zeros[O.ST_E4M3] > 0.001
