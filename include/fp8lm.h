@@ -60,6 +60,13 @@ typedef enum { FP8LM_WCOPY_E4M3 = 0, FP8LM_WCOPY_BF16 = 1 } fp8lm_wcopy;
  *                INVALID_ARGUMENT).  Only valid when nothing changes grad between the two calls.   */
 typedef enum { FP8LM_MSCALE_EXACT_PASS = 0, FP8LM_MSCALE_PREDICTED = 1, FP8LM_MSCALE_FROM_CAST = 2 } fp8lm_mscale;
 
+/* Storage formats of the optimizer state, the precision-decoupling settings of Sec. 3.3 (table of
+ * optimizer settings) and Sec. 2.2.  F16 and E4M3 are stored with a per-tensor power-of-two scale and
+ * saturate; BF16 and F32 carry no scale (scale 1) and overflow to infinity as IEEE does.
+ *   master weight: F16 (setting 2a, the default), BF16 (2b), E4M3 (3), F32 (the alternative of Sec. 2.2);
+ *   second moment: F16 (default) or E4M3 (setting 4).                                                  */
+typedef enum { FP8LM_STATE_F16 = 0, FP8LM_STATE_BF16 = 1, FP8LM_STATE_E4M3 = 2, FP8LM_STATE_F32 = 3 } fp8lm_state_fmt;
+
 typedef struct {
   int64_t offset; /* first element, multiple of 16 */
   int64_t numel;  /* >= 0                          */
@@ -107,6 +114,9 @@ typedef struct {
   int32_t stats;    /* 1: count n_sat / n_underflow of the four outputs exactly (more ALU work);
                        0: leave them 0; FLAG_SATURATED is still exact (derived from the amax)      */
   int32_t m_scale_mode; /* fp8lm_mscale: where the scale of the stored first moment comes from             */
+  int32_t master_fmt; /* fp8lm_state_fmt of w (default F16 with tensor scaling)                            */
+  int32_t v_fmt;      /* fp8lm_state_fmt of v: F16 (default) or E4M3.  Any non-default pair requires
+                         wcopy = E4M3 and stats = 0, and always uses correctly rounded arithmetic          */
   int32_t exact;    /* 1: correctly rounded sqrt and divide in the weight update (results identical to
                           the scalar definition);
                        0: hardware v_sqrt_f32 / v_rcp_f32, 1 ulp each: m and v are unaffected, the
@@ -235,6 +245,10 @@ fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* ctx, const uint8_t* const* payloads /*host
  */
 fp8lm_status fp8lm_init_master(fp8lm_ctx* ctx, const void* w_bf16 /*device*/, uint16_t* w_f16 /*device*/,
                                fp8lm_meta* w_meta /*device*/, void* stream);
+/* The same for any master-weight format: F16 / E4M3 with scale 2^(k - 1), k from their largest finite
+ * value; BF16 / F32 with scale 1.  w_out holds 2, 2, 1 or 4 bytes per element.                        */
+fp8lm_status fp8lm_init_master_as(fp8lm_ctx* ctx, const void* w_bf16 /*device*/, void* w_out /*device*/,
+                                  fp8lm_meta* w_meta /*device*/, fp8lm_state_fmt master_fmt, void* stream);
 
 /*
  * One FP8 AdamW step (Sec. 2.2, Eq. 8: FP8 gradient, FP8 first moment, FP16 second moment, scaled FP16
@@ -257,8 +271,8 @@ fp8lm_status fp8lm_init_master(fp8lm_ctx* ctx, const void* w_bf16 /*device*/, ui
 fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* ctx,
                                  const uint8_t* grad /*device*/, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta /*device*/,
                                  uint8_t* m /*device, in place*/, fp8lm_meta* m_meta /*device*/,
-                                 uint16_t* v /*device, in place*/, fp8lm_meta* v_meta /*device*/,
-                                 uint16_t* w /*device, in place*/, fp8lm_meta* w_meta /*device*/,
+                                 void* v /*device, in place; element type per hp->v_fmt*/, fp8lm_meta* v_meta /*device*/,
+                                 void* w /*device, in place; element type per hp->master_fmt*/, fp8lm_meta* w_meta /*device*/,
                                  void* wcopy /*device, write only*/, fp8lm_meta* wcopy_meta /*device*/,
                                  const fp8lm_adam_hparams* hp /*host*/, void* stream);
 

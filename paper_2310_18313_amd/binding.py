@@ -22,6 +22,8 @@ E4M3, E5M2 = 0, 1
 SRC_BF16 = 0
 WCOPY_E4M3, WCOPY_BF16 = 0, 1
 MSCALE_EXACT_PASS, MSCALE_PREDICTED, MSCALE_FROM_CAST = 0, 1, 2
+STATE_F16, STATE_BF16, STATE_E4M3, STATE_F32 = 0, 1, 2, 3
+STATE_BYTES = {STATE_F16: 2, STATE_BF16: 2, STATE_E4M3: 1, STATE_F32: 4}
 FLAG_NONFINITE, FLAG_AMAX_ZERO, FLAG_SCALE_CLAMPED, FLAG_SATURATED = 1, 2, 4, 8
 K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_REQUANT, K_SUM, K_COUNT = range(10)
 KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars", "requantize", "sum"]
@@ -29,7 +31,7 @@ KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy
 EXPORTS = [
     "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_meta_init", "fp8lm_amax_scale",
     "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_cast_fp8_for_adam", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
-    "fp8lm_init_master", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
+    "fp8lm_init_master", "fp8lm_init_master_as", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
 
@@ -62,7 +64,8 @@ class AutoscaleCfg(C.Structure):
 class AdamHparams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float), ("step", C.c_int64), ("v_scaled", C.c_int32),
-                ("wcopy", C.c_int32), ("stats", C.c_int32), ("m_scale_mode", C.c_int32), ("exact", C.c_int32)]
+                ("wcopy", C.c_int32), ("stats", C.c_int32), ("m_scale_mode", C.c_int32), ("master_fmt", C.c_int32),
+                ("v_fmt", C.c_int32), ("exact", C.c_int32)]
 
 
 def autoscale_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=100000) -> AutoscaleCfg:
@@ -70,8 +73,10 @@ def autoscale_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=1
 
 
 def adam_hparams(lr, step, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, v_scaled=1,
-                 wcopy=WCOPY_E4M3, stats=0, exact=1, m_scale_mode=MSCALE_EXACT_PASS) -> AdamHparams:
-    return AdamHparams(lr, beta1, beta2, eps, weight_decay, step, v_scaled, wcopy, stats, m_scale_mode, exact)
+                 wcopy=WCOPY_E4M3, stats=0, exact=1, m_scale_mode=MSCALE_EXACT_PASS, master_fmt=STATE_F16,
+                 v_fmt=STATE_F16) -> AdamHparams:
+    return AdamHparams(lr, beta1, beta2, eps, weight_decay, step, v_scaled, wcopy, stats, m_scale_mode, master_fmt,
+                       v_fmt, exact)
 
 
 class Fp8lmError(RuntimeError):
@@ -104,6 +109,7 @@ def lib() -> C.CDLL:
         L.fp8lm_cast_fp8_delayed.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
         L.fp8lm_cast_fp8_for_adam.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, i32, vp, vp, C.c_float, vp]
         L.fp8lm_init_master.argtypes = [vp, vp, vp, vp, vp]
+        L.fp8lm_init_master_as.argtypes = [vp, vp, vp, vp, C.c_int, vp]
         L.fp8lm_shared_scale.argtypes = [vp, vp, i32, vp, vp]
         L.fp8lm_requantize_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp]
         L.fp8lm_sum_fp8.argtypes = [vp, vp, i32, C.c_int, vp, vp, vp, vp, vp]
@@ -247,16 +253,17 @@ class Context:
         _check(lib().fp8lm_sum_fp8(self._h, C.cast(ptrs, C.c_void_p), len(payloads), fmt, _ptr(shared), _ptr(dst),
                                    _ptr(dst_meta), C.addressof(cfg), _stream(stream)), "fp8lm_sum_fp8")
 
-    def init_master(self, w_bf16, w_f16, w_meta, stream=None):
-        assert w_bf16.element_size() == 2 and w_f16.element_size() == 2
-        self._fits(w_bf16, w_f16)
+    def init_master(self, w_bf16, w_out, w_meta, master_fmt=STATE_F16, stream=None):
+        assert w_bf16.element_size() == 2 and w_out.element_size() == STATE_BYTES[master_fmt]
+        self._fits(w_bf16, w_out)
         self._fits_meta(w_meta)
-        _check(lib().fp8lm_init_master(self._h, _ptr(w_bf16), _ptr(w_f16), _ptr(w_meta), _stream(stream)),
-               "fp8lm_init_master")
+        _check(lib().fp8lm_init_master_as(self._h, _ptr(w_bf16), _ptr(w_out), _ptr(w_meta), master_fmt,
+                                          _stream(stream)), "fp8lm_init_master_as")
 
     def adam_step_fp8(self, grad, grad_fmt, grad_meta, m, m_meta, v, v_meta, w, w_meta, wcopy, wcopy_meta,
                       hp: AdamHparams, stream=None):
-        assert grad.element_size() == 1 and m.element_size() == 1 and v.element_size() == 2 and w.element_size() == 2
+        assert grad.element_size() == 1 and m.element_size() == 1
+        assert v.element_size() == STATE_BYTES[hp.v_fmt] and w.element_size() == STATE_BYTES[hp.master_fmt]
         assert wcopy.element_size() == (1 if hp.wcopy == WCOPY_E4M3 else 2)
         self._fits(grad, m, v, w, wcopy)
         self._fits_meta(grad_meta, m_meta, v_meta, w_meta, wcopy_meta)

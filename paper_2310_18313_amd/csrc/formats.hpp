@@ -99,6 +99,105 @@ __device__ __forceinline__ uint32_t encode1_bf16(float x) {
   return ((b & 0x7FFFFFFFu) > 0x7F800000u) ? 0x7FC0u : r;
 }
 
+// ---- storage formats of the optimizer state (precision-decoupling settings of the paper, Sec. 3.3) ----
+enum : int { kStF16 = 0, kStBF16 = 1, kStE4M3 = 2, kStF32 = 3 };
+
+template <int K> struct StTraits;
+template <> struct StTraits<kStF16> {
+  typedef uint16_t elem_t;
+  static constexpr bool kScaled = true, kSaturating = true;
+  static constexpr float kMax = 65504.0f;
+  static constexpr uint32_t kMaxBits = 0x477FE000u, kMagMask = 0x7FFFu, kTopCode = 0x7BFFu;
+  static __device__ __forceinline__ float dec(uint32_t c) { return f16_to_f32(c); }
+  static __device__ __forceinline__ uint32_t enc(float x) { return encode1_f16(x); }
+  static __device__ __forceinline__ uint32_t enc_careful(float x) { return encode1_f16_careful(x); }
+};
+template <> struct StTraits<kStBF16> {
+  typedef uint16_t elem_t;
+  static constexpr bool kScaled = false, kSaturating = false;
+  static constexpr float kMax = 0.0f;
+  static constexpr uint32_t kMaxBits = 0u, kMagMask = 0x7FFFu, kTopCode = 0x7F80u;   // "top" = rounded to infinity
+  static __device__ __forceinline__ float dec(uint32_t c) { return u2f(c << 16); }
+  static __device__ __forceinline__ uint32_t enc(float x) { return encode1_bf16(x); }
+  static __device__ __forceinline__ uint32_t enc_careful(float x) { return encode1_bf16(x); }
+};
+template <> struct StTraits<kStE4M3> {
+  typedef uint8_t elem_t;
+  static constexpr bool kScaled = true, kSaturating = true;
+  static constexpr float kMax = 448.0f;
+  static constexpr uint32_t kMaxBits = 0x43E00000u, kMagMask = 0x7Fu, kTopCode = 0x7Eu;
+  static __device__ __forceinline__ float dec(uint32_t c) { return fp8_to_f32<kE4M3>(c); }
+  static __device__ __forceinline__ uint32_t enc(float x) { return encode1_fp8<kE4M3>(x); }
+  static __device__ __forceinline__ uint32_t enc_careful(float x) { return encode1_fp8_careful<kE4M3>(x); }
+};
+template <> struct StTraits<kStF32> {
+  typedef uint32_t elem_t;
+  static constexpr bool kScaled = false, kSaturating = false;
+  static constexpr float kMax = 0.0f;
+  static constexpr uint32_t kMaxBits = 0u, kMagMask = 0x7FFFFFFFu, kTopCode = 0x7F800000u;
+  static __device__ __forceinline__ float dec(uint32_t c) { return u2f(c); }
+  static __device__ __forceinline__ uint32_t enc(float x) { return f2u(x); }
+  static __device__ __forceinline__ uint32_t enc_careful(float x) { return x != x ? 0x7FC00000u : f2u(x); }
+};
+
+// 16 consecutive elements: 128-bit accesses, decoded to / encoded from fp32 payloads
+template <int K> __device__ __forceinline__ void st_load16(const void* buf, long long pos, float* out) {
+  const typename StTraits<K>::elem_t* q = static_cast<const typename StTraits<K>::elem_t*>(buf) + pos;
+  if constexpr (K == kStE4M3) {
+    const uint4 a = *reinterpret_cast<const uint4*>(q);
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float2_t lo = fp8x2_to_f32<kE4M3, false>(w[k]), hi = fp8x2_to_f32<kE4M3, true>(w[k]);
+      out[4 * k] = lo.x; out[4 * k + 1] = lo.y; out[4 * k + 2] = hi.x; out[4 * k + 3] = hi.y;
+    }
+  } else if constexpr (K == kStF32) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint4 a = *reinterpret_cast<const uint4*>(q + 4 * k);
+      out[4 * k] = u2f(a.x); out[4 * k + 1] = u2f(a.y); out[4 * k + 2] = u2f(a.z); out[4 * k + 3] = u2f(a.w);
+    }
+  } else {
+    const uint4 a = *reinterpret_cast<const uint4*>(q), b = *reinterpret_cast<const uint4*>(q + 8);
+    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if constexpr (K == kStF16) {
+        const float2_t f = f16x2_to_f32(w[k]);
+        out[2 * k] = f.x; out[2 * k + 1] = f.y;
+      } else {
+        out[2 * k] = bf16lo_to_f32(w[k]); out[2 * k + 1] = bf16hi_to_f32(w[k]);
+      }
+    }
+  }
+}
+template <int K> __device__ __forceinline__ void st_store16(void* buf, long long pos, const float* x) {
+  typename StTraits<K>::elem_t* q = static_cast<typename StTraits<K>::elem_t*>(buf) + pos;
+  if constexpr (K == kStE4M3) {
+    *reinterpret_cast<uint4*>(q) = make_uint4(encode4_fp8<kE4M3>(x[0], x[1], x[2], x[3]), encode4_fp8<kE4M3>(x[4], x[5], x[6], x[7]),
+                                              encode4_fp8<kE4M3>(x[8], x[9], x[10], x[11]), encode4_fp8<kE4M3>(x[12], x[13], x[14], x[15]));
+  } else if constexpr (K == kStF32) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      *reinterpret_cast<uint4*>(q + 4 * k) = make_uint4(f2u(x[4 * k]), f2u(x[4 * k + 1]), f2u(x[4 * k + 2]), f2u(x[4 * k + 3]));
+  } else {
+    uint32_t w[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if constexpr (K == kStF16) w[k] = encode2_f16(x[2 * k], x[2 * k + 1]);
+      else w[k] = encode1_bf16(x[2 * k]) | (encode1_bf16(x[2 * k + 1]) << 16);
+    }
+    *reinterpret_cast<uint4*>(q) = make_uint4(w[0], w[1], w[2], w[3]);
+    *reinterpret_cast<uint4*>(q + 8) = make_uint4(w[4], w[5], w[6], w[7]);
+  }
+}
+template <int K> __device__ __forceinline__ float st_load1(const void* buf, long long i) {
+  return StTraits<K>::dec(static_cast<const typename StTraits<K>::elem_t*>(buf)[i]);
+}
+template <int K> __device__ __forceinline__ void st_store1(void* buf, long long i, uint32_t code) {
+  static_cast<typename StTraits<K>::elem_t*>(buf)[i] = (typename StTraits<K>::elem_t)code;
+}
+
 // ---- the power-of-two scale rule ------------------------------------------------------------------
 // For A > 0 finite returns the integer k with 2^k * A <= fmax < 2^(k+1) * A, using only integer
 // compares on the bit patterns.  fmax_bits is the fp32 pattern of a normal number.

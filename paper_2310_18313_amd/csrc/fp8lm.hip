@@ -329,8 +329,11 @@ struct AmaxOp {
       // master weights: one binade of headroom; flags and the rest are completed by the cast pass
       if (A == 0.0f) {
         flags |= FP8LM_FLAG_AMAX_ZERO;
+      } else if (p.fmax_bits == 0u) {      // BF16 / FP32 master weights carry no scale
+        M.scale = 1.0f;
+        M.inv_scale = 1.0f;
       } else {
-        const int k = pow2_exp(kBitsF16Max, A) - 1;
+        const int k = pow2_exp(p.fmax_bits, A) - 1;
         const int e = k < -126 ? -126 : (k > 126 ? 126 : k);
         if (e != k) flags |= FP8LM_FLAG_SCALE_CLAMPED;
         M.scale = pow2f(e);
@@ -788,11 +791,13 @@ __global__ __launch_bounds__(kThreads) void sum_fp8_kernel(Tables tb, SumParams 
 // ================================================================================================
 struct InitParams {
   const uint16_t* src;
-  uint16_t* dst;
+  void* dst;
   fp8lm_meta* meta;
 };
 
+template <int MASTER>
 struct InitCastOp {
+  typedef StTraits<MASTER> WT;
   const InitParams& p;
   const Tables& tb;
   float scale;
@@ -807,29 +812,39 @@ struct InitCastOp {
     n_sat = n_und = 0;
   }
   __device__ __forceinline__ bool fast() const { return !careful; }
-  __device__ __forceinline__ uint32_t pair(uint32_t w) {
-    const float y0 = bf16lo_to_f32(w) * scale, y1 = bf16hi_to_f32(w) * scale;
-    vmax = fmaxf(vmax, fmaxf(fabsf(clamp_f16(y0)), fabsf(clamp_f16(y1))));
-    n_sat += (fabsf(y0) > 65488.0f) + (fabsf(y1) > 65488.0f);                 // rounds to the top FP16 code
-    n_und += ((fabsf(y0) <= 0x1p-25f) && (w & 0x7FFFu)) + ((fabsf(y1) <= 0x1p-25f) && (w & 0x7FFF0000u));
-    return encode2_f16(y0, y1);
+  // what the stored code of a (NaN-free) scaled value will be, for the counters
+  __device__ __forceinline__ void note(float y, bool nonzero_in) {
+    const uint32_t c = WT::enc(y);
+    if constexpr (WT::kSaturating) vmax = fmaxf(vmax, fabsf(WT::dec(c)));
+    else if (fabsf(WT::dec(c)) <= 3.4028234663852886e38f) vmax = fmaxf(vmax, fabsf(WT::dec(c)));
+    n_sat += (c & WT::kMagMask) == WT::kTopCode;
+    n_und += nonzero_in && ((c & WT::kMagMask) == 0);
   }
   template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
     static_assert(UN == 1, "one group at a time");
     const long long pos = pos0 + threadIdx.x * kGroup;
     const uint4 a = ld16<kNtLoadRO>(p.src + pos), b = ld16<kNtLoadRO>(p.src + pos + 8);
-    st16<kNtStoreWO>(p.dst + pos, make_uint4(pair(a.x), pair(a.y), pair(a.z), pair(a.w)));
-    st16<kNtStoreWO>(p.dst + pos + 8, make_uint4(pair(b.x), pair(b.y), pair(b.z), pair(b.w)));
+    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    float y[kGroup];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      y[2 * k] = bf16lo_to_f32(w[k]) * scale;
+      y[2 * k + 1] = bf16hi_to_f32(w[k]) * scale;
+      note(y[2 * k], (w[k] & 0x7FFFu) != 0);
+      note(y[2 * k + 1], (w[k] & 0x7FFF0000u) != 0);
+    }
+    st_store16<MASTER>(p.dst, pos, y);
   }
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) {
       const uint32_t bits = p.src[pos + j];
       const float y = u2f(bits << 16) * scale;
-      const uint32_t h = encode1_f16_careful(y);
-      if (y == y) vmax = fmaxf(vmax, fabsf(clamp_f16(y)));
-      n_sat += (h & 0x7FFFu) == 0x7BFFu;
-      n_und += ((bits & 0x7FFFu) != 0) && ((h & 0x7FFFu) == 0);
-      p.dst[pos + j] = (uint16_t)h;
+      const uint32_t h = WT::enc_careful(y);
+      const float d = fabsf(WT::dec(h));
+      if (d <= 3.4028234663852886e38f) vmax = fmaxf(vmax, d);
+      n_sat += (h & WT::kMagMask) == WT::kTopCode;
+      n_und += ((bits & 0x7FFFu) != 0) && ((h & WT::kMagMask) == 0);
+      st_store1<MASTER>(p.dst, pos + j, h);
     }
   }
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
@@ -850,15 +865,16 @@ struct InitCastOp {
         M.n_sat = take_u64(&sc->cnt[0]);
         M.n_underflow = take_u64(&sc->cnt[1]);
         take_u32(&sc->ticket);
-        M.amax_deq = f16_to_f32(encode1_f16(vm)) * M.inv_scale;
+        M.amax_deq = vm * M.inv_scale;        // vm is already a stored value
         if (M.n_sat) M.flags |= FP8LM_FLAG_SATURATED;
       }
     }
   }
 };
 
+template <int MASTER>
 __global__ __launch_bounds__(kThreads) void init_master_cast_kernel(Tables tb, InitParams p) {
-  InitCastOp op(p, tb);
+  InitCastOp<MASTER> op(p, tb);
   walk_chunks<1>(tb, op);
 }
 
@@ -870,14 +886,16 @@ struct AdamParams {
   const fp8lm_meta* grad_meta;
   uint8_t* m;
   fp8lm_meta* m_meta;
-  uint16_t* v;
+  void* v;                 // FP16 (default) or E4M3
   fp8lm_meta* v_meta;
-  uint16_t* w;
+  void* w;                 // FP16 (default), BF16, E4M3 or FP32
   fp8lm_meta* w_meta;
   void* wcopy;
   fp8lm_meta* wcopy_meta;
   float b1, omb1, rbc1, b2, omb2, rbc2, lr, eps, decay;
   int32_t v_scaled;
+  uint32_t v_fmax_bits;    // largest finite value of the second moment's storage format
+  uint32_t w_fmax_bits;    // ... of the master weight's, 0 if that format carries no scale (BF16, FP32)
 };
 
 // Chooses a stored scale from a magnitude bound; keeps the old one when the bound is 0 or not finite.
@@ -909,12 +927,17 @@ __device__ void adam_choose_scales(const AdamParams& p, Scratch::Pending& P, int
   if (p.v_scaled) {
     const float Ag = G.amax_deq;
     const float Bv = __builtin_fmaf(p.b2, Mv.amax_deq, p.omb2 * (Ag * Ag));
-    refresh_scale(kBitsF16Max, Bv, 0, Mv.scale, Mv.inv_scale, P.sv, P.isv, fv);
+    refresh_scale(p.v_fmax_bits, Bv, 0, Mv.scale, Mv.inv_scale, P.sv, P.isv, fv);
   } else {
     P.sv = 1.0f;
     P.isv = 1.0f;
   }
-  refresh_scale(kBitsF16Max, Mw.amax_deq, 1, Mw.scale, Mw.inv_scale, P.sw, P.isw, fw);
+  if (p.w_fmax_bits) {
+    refresh_scale(p.w_fmax_bits, Mw.amax_deq, 1, Mw.scale, Mw.inv_scale, P.sw, P.isw, fw);
+  } else {
+    P.sw = 1.0f;
+    P.isw = 1.0f;
+  }
   if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
     refresh_scale(kBitsE4M3Max, Mw.amax_deq, 0, Mq.scale, Mq.inv_scale, P.sq, P.isq, fq);
   } else {
@@ -1134,8 +1157,10 @@ struct AdamUpdateOp {
   __device__ __forceinline__ void one_careful(long long i) {
     const float g = fp8_to_f32<GFMT>(p.grad[i]) * inv_sg;
     const float m0 = fp8_to_f32<kE4M3>(p.m[i]) * inv_sm;
-    const float v0 = f16_to_f32(p.v[i]) * inv_sv;
-    const float w0 = f16_to_f32(p.w[i]) * inv_sw;
+    uint16_t* pv = static_cast<uint16_t*>(p.v);
+    uint16_t* pw = static_cast<uint16_t*>(p.w);
+    const float v0 = f16_to_f32(pv[i]) * inv_sv;
+    const float w0 = f16_to_f32(pw[i]) * inv_sw;
     const float m1 = __builtin_fmaf(p.b1, m0, p.omb1 * g);
     const float v1 = __builtin_fmaf(p.b2, v0, p.omb2 * (g * g));
     const float den = __builtin_sqrtf(v1 * p.rbc2) + p.eps;
@@ -1143,8 +1168,8 @@ struct AdamUpdateOp {
     const float w1 = __builtin_fmaf(-p.lr, upd, w0 * p.decay);
     const float tm = m1 * sm, tv = v1 * sv, tw = w1 * sw, tq = w1 * sq;
     p.m[i] = (uint8_t)encode1_fp8_careful<kE4M3>(tm);
-    p.v[i] = (uint16_t)encode1_f16_careful(tv);
-    p.w[i] = (uint16_t)encode1_f16_careful(tw);
+    pv[i] = (uint16_t)encode1_f16_careful(tv);
+    pw[i] = (uint16_t)encode1_f16_careful(tw);
     if constexpr (WCOPY == FP8LM_WCOPY_E4M3) static_cast<uint8_t*>(p.wcopy)[i] = (uint8_t)encode1_fp8_careful<kE4M3>(tq);
     else static_cast<uint16_t*>(p.wcopy)[i] = (uint16_t)encode1_bf16(w1);
     const float kMaxF = 3.4028234663852886e38f;
@@ -1159,15 +1184,17 @@ struct AdamUpdateOp {
   template <int UN> __device__ __forceinline__ void tiles(long long tile0) {
     uint4 g[UN], m[UN], va[UN], vb[UN], wa[UN], wb[UN];
     const long long pos0 = tile0 + threadIdx.x * kGroup;
+    uint16_t* pv = static_cast<uint16_t*>(p.v);
+    uint16_t* pw = static_cast<uint16_t*>(p.w);
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       const long long pos = pos0 + u * kTile;
       g[u] = ld16<kNtLoadRO>(p.grad + pos);
       m[u] = ld16<kNtLoadRW>(p.m + pos);
-      va[u] = ld16<kNtLoadRW>(p.v + pos);
-      vb[u] = ld16<kNtLoadRW>(p.v + pos + 8);
-      wa[u] = ld16<kNtLoadRW>(p.w + pos);
-      wb[u] = ld16<kNtLoadRW>(p.w + pos + 8);
+      va[u] = ld16<kNtLoadRW>(pv + pos);
+      vb[u] = ld16<kNtLoadRW>(pv + pos + 8);
+      wa[u] = ld16<kNtLoadRW>(pw + pos);
+      wb[u] = ld16<kNtLoadRW>(pw + pos + 8);
     }
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
@@ -1177,10 +1204,10 @@ struct AdamUpdateOp {
       const Quad q2 = quad(g[u].z, m[u].z, vb[u].x, vb[u].y, wb[u].x, wb[u].y);
       const Quad q3 = quad(g[u].w, m[u].w, vb[u].z, vb[u].w, wb[u].z, wb[u].w);
       st16<kNtStoreRW>(p.m + pos, make_uint4(q0.m, q1.m, q2.m, q3.m));
-      st16<kNtStoreRW>(p.v + pos, make_uint4(q0.v01, q0.v23, q1.v01, q1.v23));
-      st16<kNtStoreRW>(p.v + pos + 8, make_uint4(q2.v01, q2.v23, q3.v01, q3.v23));
-      st16<kNtStoreRW>(p.w + pos, make_uint4(q0.w01, q0.w23, q1.w01, q1.w23));
-      st16<kNtStoreRW>(p.w + pos + 8, make_uint4(q2.w01, q2.w23, q3.w01, q3.w23));
+      st16<kNtStoreRW>(pv + pos, make_uint4(q0.v01, q0.v23, q1.v01, q1.v23));
+      st16<kNtStoreRW>(pv + pos + 8, make_uint4(q2.v01, q2.v23, q3.v01, q3.v23));
+      st16<kNtStoreRW>(pw + pos, make_uint4(q0.w01, q0.w23, q1.w01, q1.w23));
+      st16<kNtStoreRW>(pw + pos + 8, make_uint4(q2.w01, q2.w23, q3.w01, q3.w23));
       if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
         st16<kNtStoreWO>(static_cast<uint8_t*>(p.wcopy) + pos, make_uint4(q0.q, q1.q, q2.q, q3.q));
       } else {
@@ -1193,12 +1220,14 @@ struct AdamUpdateOp {
   __device__ __forceinline__ void group(long long pos, int valid) {
     if (!careful) {
       // ragged tail of a tensor: same arithmetic, element by element
+      uint16_t* pv = static_cast<uint16_t*>(p.v);
+      uint16_t* pw = static_cast<uint16_t*>(p.w);
       for (int j = 0; j < valid; ++j) {
         const long long i = pos + j;
-        const Quad o = quad(p.grad[i], p.m[i], p.v[i], 0u, p.w[i], 0u);
+        const Quad o = quad(p.grad[i], p.m[i], pv[i], 0u, pw[i], 0u);
         p.m[i] = (uint8_t)o.m;
-        p.v[i] = (uint16_t)o.v01;
-        p.w[i] = (uint16_t)o.w01;
+        pv[i] = (uint16_t)o.v01;
+        pw[i] = (uint16_t)o.w01;
         if constexpr (WCOPY == FP8LM_WCOPY_E4M3) static_cast<uint8_t*>(p.wcopy)[i] = (uint8_t)o.q;
         else static_cast<uint16_t*>(p.wcopy)[i] = (uint16_t)o.q;
       }
@@ -1246,7 +1275,8 @@ struct AdamUpdateOp {
                                        uint32_t flags, float fmax, bool saturating, unsigned long long n_sat,
                                        unsigned long long n_und, Enc enc, Dec dec, uint32_t magmask, uint32_t topcode) {
     const bool nonfinite = nan_inf_bits != 0;
-    const bool inf_seen = saturating && (nan_inf_bits & 2u) != 0;
+    const bool inf_stored = (nan_inf_bits & 2u) != 0;          // as the top code, or as infinity in bf16
+    const bool inf_seen = saturating && inf_stored;
     M.scale = scale;
     M.inv_scale = inv;
     M.amax = nonfinite ? __builtin_inff() : amax;
@@ -1254,7 +1284,7 @@ struct AdamUpdateOp {
     const float stored = inf_seen ? fmax : dec(code);
     M.amax_deq = stored * inv;
     if (nonfinite) flags |= FP8LM_FLAG_NONFINITE;
-    bool sat = inf_seen || (code & magmask) == topcode;
+    bool sat = inf_stored || (code & magmask) == topcode;
     if constexpr (STATS) sat = n_sat != 0;
     if (sat) flags |= FP8LM_FLAG_SATURATED;
     M.flags = flags;
@@ -1296,6 +1326,138 @@ template <int GFMT, int WCOPY, bool FAST, bool STATS>
 __global__ __launch_bounds__(kThreads) FP8LM_UPDATE_ATTR void adam_update_kernel(Tables tb, AdamParams p) {
   AdamUpdateOp<GFMT, WCOPY, FAST, STATS> op(p, tb);
   walk_chunks<FP8LM_UN_UPDATE>(tb, op);
+}
+
+// ---- pass B for the other storage formats of the precision-decoupling study ----------------------
+// Master weight FP16-scaled / BF16 / E4M3-scaled / FP32 and second moment FP16 / E4M3-scaled (Sec. 2.2;
+// Sec. 3.3, table of optimizer settings).  Same arithmetic as above, correctly rounded sqrt and divide,
+// E4M3 weight copy, no counters; one 16-element group per thread and iteration.
+template <int GFMT, int MASTER, int VFMT>
+struct AdamUpdateVarOp {
+  typedef StTraits<MASTER> WT;
+  typedef StTraits<VFMT> VT;
+  const AdamParams& p;
+  const Tables& tb;
+  float inv_sg, inv_sm, inv_sv, inv_sw, sm, sv, sw, sq;
+  bool careful;
+  float vmax, wmax, mmax;
+  uint32_t nf;
+  __device__ AdamUpdateVarOp(const AdamParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
+  __device__ __forceinline__ void begin(int t, const TensorDesc&) {
+    const Scratch::Pending& P = tb.scratch[t].pend;
+    inv_sg = p.grad_meta[t].inv_scale;
+    inv_sm = p.m_meta[t].inv_scale;
+    inv_sv = p.v_meta[t].inv_scale;
+    inv_sw = p.w_meta[t].inv_scale;
+    sm = P.sm; sv = P.sv; sw = P.sw; sq = P.sq;
+    careful = P.careful != 0;
+    vmax = wmax = mmax = 0.0f;
+    nf = 0;
+  }
+  __device__ __forceinline__ bool fast() const { return !careful; }
+  __device__ __forceinline__ void update(float dg, float dm, float dv, float dw, float& m1, float& v1, float& w1) {
+    const float g = dg * inv_sg, m0 = dm * inv_sm, v0 = dv * inv_sv, w0 = dw * inv_sw;
+    m1 = __builtin_fmaf(p.b1, m0, p.omb1 * g);
+    v1 = __builtin_fmaf(p.b2, v0, p.omb2 * (g * g));
+    const float den = __builtin_sqrtf(v1 * p.rbc2) + p.eps;
+    const float upd = (m1 * p.rbc1) / den;
+    w1 = __builtin_fmaf(-p.lr, upd, w0 * p.decay);
+  }
+  template <int UN> __device__ __forceinline__ void tiles(long long tile0) {
+    static_assert(UN == 1, "one group at a time");
+    const long long pos = tile0 + threadIdx.x * kGroup;
+    const uint4 gq = ld16<kNtLoadRO>(p.grad + pos), mq = ld16<false>(p.m + pos);
+    float dv[kGroup], dw[kGroup], dg[kGroup], dm[kGroup];
+    st_load16<VFMT>(p.v, pos, dv);
+    st_load16<MASTER>(p.w, pos, dw);
+    const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w}, mw[4] = {mq.x, mq.y, mq.z, mq.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float2_t g01 = fp8x2_to_f32<GFMT, false>(gw[k]), g23 = fp8x2_to_f32<GFMT, true>(gw[k]);
+      const float2_t m01 = fp8x2_to_f32<kE4M3, false>(mw[k]), m23 = fp8x2_to_f32<kE4M3, true>(mw[k]);
+      dg[4 * k] = g01.x; dg[4 * k + 1] = g01.y; dg[4 * k + 2] = g23.x; dg[4 * k + 3] = g23.y;
+      dm[4 * k] = m01.x; dm[4 * k + 1] = m01.y; dm[4 * k + 2] = m23.x; dm[4 * k + 3] = m23.y;
+    }
+    float tm[kGroup], tq[kGroup];
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j) {
+      float m1, v1, w1;
+      update(dg[j], dm[j], dv[j], dw[j], m1, v1, w1);
+      vmax = fmaxf(vmax, v1);
+      wmax = fmaxf(wmax, fabsf(w1));
+      mmax = fmaxf(mmax, fabsf(m1));
+      tm[j] = m1 * sm;
+      dv[j] = v1 * sv;
+      dw[j] = w1 * sw;
+      tq[j] = w1 * sq;
+    }
+    st_store16<kStE4M3>(p.m, pos, tm);
+    st_store16<VFMT>(p.v, pos, dv);
+    st_store16<MASTER>(p.w, pos, dw);
+    st_store16<kStE4M3>(p.wcopy, pos, tq);
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    for (int j = 0; j < valid; ++j) {
+      const long long i = pos + j;
+      float m1, v1, w1;
+      update(fp8_to_f32<GFMT>(p.grad[i]), fp8_to_f32<kE4M3>(p.m[i]), st_load1<VFMT>(p.v, i), st_load1<MASTER>(p.w, i), m1, v1, w1);
+      p.m[i] = (uint8_t)encode1_fp8_careful<kE4M3>(m1 * sm);
+      st_store1<VFMT>(p.v, i, VT::enc_careful(v1 * sv));
+      st_store1<MASTER>(p.w, i, WT::enc_careful(w1 * sw));
+      static_cast<uint8_t*>(p.wcopy)[i] = (uint8_t)encode1_fp8_careful<kE4M3>(w1 * sq);
+      const float kMaxF = 3.4028234663852886e38f;
+      const float am = fabsf(m1), av = fabsf(v1), aw = fabsf(w1);
+      if (am <= kMaxF) mmax = fmaxf(mmax, am); else nf |= (m1 != m1) ? 1u : 2u;
+      if (av <= kMaxF) vmax = fmaxf(vmax, av); else nf |= (v1 != v1) ? 4u : 8u;
+      if (aw <= kMaxF) wmax = fmaxf(wmax, aw); else nf |= (w1 != w1) ? 16u : 32u;
+    }
+  }
+  template <class T>
+  __device__ __forceinline__ void fill(fp8lm_meta& M, float scale, float inv, float amax, uint32_t nan_inf_bits, uint32_t flags) {
+    const bool nonfinite = nan_inf_bits != 0;
+    const bool inf_stored = (nan_inf_bits & 2u) != 0;          // as the top code, or as infinity where the format has one
+    M.scale = scale;
+    M.inv_scale = inv;
+    M.amax = nonfinite ? __builtin_inff() : amax;
+    const uint32_t code = T::enc(amax * scale);
+    M.amax_deq = ((T::kSaturating && inf_stored) ? T::kMax : T::dec(code)) * inv;
+    if (nonfinite) flags |= FP8LM_FLAG_NONFINITE;
+    if (inf_stored || (code & T::kMagMask) == T::kTopCode) flags |= FP8LM_FLAG_SATURATED;
+    M.flags = flags;
+    M.n_sat = 0;
+    M.n_underflow = 0;
+  }
+  __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
+    BlockStats<3, 0> s;
+    s.mx[0] = f2u(vmax);
+    s.mx[1] = f2u(wmax);
+    s.mx[2] = f2u(mmax);
+    s.orv = nf;
+    block_combine(s);
+    if (threadIdx.x == 0) {
+      Scratch* sc = tb.scratch + t;
+      atomic_max_u32(&sc->max_a, s.mx[0]);
+      atomic_max_u32(&sc->max_b, s.mx[1]);
+      atomic_max_u32(&sc->max_c, s.mx[2]);
+      atomic_or_u32(&sc->nf, s.orv);
+      if (publish_ticket(sc, done, d.n_chunks)) {
+        const float A_v = u2f(take_u32(&sc->max_a)), A_w = u2f(take_u32(&sc->max_b)), A_m = u2f(take_u32(&sc->max_c));
+        const uint32_t nfb = take_u32(&sc->nf);
+        take_u32(&sc->ticket);
+        const Scratch::Pending& P = sc->pend;
+        fill<StTraits<kStE4M3>>(p.m_meta[t], P.sm, P.ism, A_m, nfb & 3u, P.fm);
+        fill<VT>(p.v_meta[t], P.sv, P.isv, A_v, (nfb >> 2) & 3u, P.fv);
+        fill<WT>(p.w_meta[t], P.sw, P.isw, A_w, (nfb >> 4) & 3u, P.fw);
+        fill<StTraits<kStE4M3>>(p.wcopy_meta[t], P.sq, P.isq, A_w, (nfb >> 4) & 3u, P.fq);
+      }
+    }
+  }
+};
+
+template <int GFMT, int MASTER, int VFMT>
+__global__ __launch_bounds__(kThreads) void adam_update_var_kernel(Tables tb, AdamParams p) {
+  AdamUpdateVarOp<GFMT, MASTER, VFMT> op(p, tb);
+  walk_chunks<1>(tb, op);
 }
 
 // ---- small kernels ---------------------------------------------------------------------------------
@@ -1456,6 +1618,29 @@ void launch_update(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, bool fast, 
     if (stats) hipLaunchKernelGGL((adam_update_kernel<GFMT, WCOPY, false, true>), g, b, 0, s, tb, p);
     else hipLaunchKernelGGL((adam_update_kernel<GFMT, WCOPY, false, false>), g, b, 0, s, tb, p);
   }
+}
+
+// Selects the adam_update_var_kernel instantiation (every master / second-moment format pair except the default).
+template <int GFMT>
+void launch_update_variant_g(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, int master, int vfmt) {
+  const dim3 g(grid_of(c)), b(kThreads);
+  const Tables tb = tables_of(c);
+#define FP8LM_VAR(M, V) hipLaunchKernelGGL((adam_update_var_kernel<GFMT, M, V>), g, b, 0, s, tb, p)
+  if (vfmt == kStF16) {
+    if (master == kStBF16) FP8LM_VAR(kStBF16, kStF16);
+    else if (master == kStE4M3) FP8LM_VAR(kStE4M3, kStF16);
+    else FP8LM_VAR(kStF32, kStF16);
+  } else {
+    if (master == kStF16) FP8LM_VAR(kStF16, kStE4M3);
+    else if (master == kStBF16) FP8LM_VAR(kStBF16, kStE4M3);
+    else if (master == kStE4M3) FP8LM_VAR(kStE4M3, kStE4M3);
+    else FP8LM_VAR(kStF32, kStE4M3);
+  }
+#undef FP8LM_VAR
+}
+void launch_update_variant(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, bool e5, int master, int vfmt) {
+  if (e5) launch_update_variant_g<kE5M2>(c, s, p, master, vfmt);
+  else launch_update_variant_g<kE4M3>(c, s, p, master, vfmt);
 }
 
 bool cfg_ok(const fp8lm_autoscale_cfg* cfg) {
@@ -1697,30 +1882,46 @@ fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* c, const uint8_t* const* payloads, int32_t
   return after_launch();
 }
 
-fp8lm_status fp8lm_init_master(fp8lm_ctx* c, const void* w_bf16, uint16_t* w_f16, fp8lm_meta* w_meta, void* stream) {
-  if (!c) return FP8LM_ERR_INVALID_ARGUMENT;
+fp8lm_status fp8lm_init_master_as(fp8lm_ctx* c, const void* w_bf16, void* w_out, fp8lm_meta* w_meta,
+                                  fp8lm_state_fmt master_fmt, void* stream) {
+  if (!c || (int)master_fmt < 0 || (int)master_fmt > 3) return FP8LM_ERR_INVALID_ARGUMENT;
   if (c->n_chunks == 0) return FP8LM_OK;
-  if (!w_bf16 || !w_f16 || !w_meta) return FP8LM_ERR_INVALID_ARGUMENT;
-  if (!aligned16(w_bf16) || !aligned16(w_f16)) return FP8LM_ERR_MISALIGNED;
+  if (!w_bf16 || !w_out || !w_meta) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!aligned16(w_bf16) || !aligned16(w_out)) return FP8LM_ERR_MISALIGNED;
   DeviceGuard guard(c->device);
-  Timed tm(c, (hipStream_t)stream, FP8LM_K_INIT_MASTER);
-  AmaxParams pa{static_cast<const uint16_t*>(w_bf16), w_meta, kBitsF16Max, 1, 0};
-  hipLaunchKernelGGL(amax_kernel<kAmaxForMaster>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream,
-                     tables_of(c), pa);
+  hipStream_t s = (hipStream_t)stream;
+  Timed tm(c, s, FP8LM_K_INIT_MASTER);
+  const uint32_t fmax_bits = master_fmt == FP8LM_STATE_F16 ? kBitsF16Max : (master_fmt == FP8LM_STATE_E4M3 ? kBitsE4M3Max : 0u);
+  AmaxParams pa{static_cast<const uint16_t*>(w_bf16), w_meta, fmax_bits, 1, 0};
+  hipLaunchKernelGGL(amax_kernel<kAmaxForMaster>, dim3(grid_of(c)), dim3(kThreads), 0, s, tables_of(c), pa);
   fp8lm_status st = after_launch();
   if (st != FP8LM_OK) return st;
-  InitParams pi{static_cast<const uint16_t*>(w_bf16), w_f16, w_meta};
-  hipLaunchKernelGGL(init_master_cast_kernel, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), pi);
+  InitParams pi{static_cast<const uint16_t*>(w_bf16), w_out, w_meta};
+  const dim3 g(grid_of(c)), b(kThreads);
+  switch (master_fmt) {
+    case FP8LM_STATE_F16: hipLaunchKernelGGL(init_master_cast_kernel<kStF16>, g, b, 0, s, tables_of(c), pi); break;
+    case FP8LM_STATE_BF16: hipLaunchKernelGGL(init_master_cast_kernel<kStBF16>, g, b, 0, s, tables_of(c), pi); break;
+    case FP8LM_STATE_E4M3: hipLaunchKernelGGL(init_master_cast_kernel<kStE4M3>, g, b, 0, s, tables_of(c), pi); break;
+    default: hipLaunchKernelGGL(init_master_cast_kernel<kStF32>, g, b, 0, s, tables_of(c), pi); break;
+  }
   return after_launch();
 }
 
+fp8lm_status fp8lm_init_master(fp8lm_ctx* c, const void* w_bf16, uint16_t* w_f16, fp8lm_meta* w_meta, void* stream) {
+  return fp8lm_init_master_as(c, w_bf16, w_f16, w_meta, FP8LM_STATE_F16, stream);
+}
+
 fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta,
-                                 uint8_t* m, fp8lm_meta* m_meta, uint16_t* v, fp8lm_meta* v_meta, uint16_t* w,
+                                 uint8_t* m, fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta, void* w,
                                  fp8lm_meta* w_meta, void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp,
                                  void* stream) {
   if (!c || !hp || (grad_fmt != FP8LM_E4M3 && grad_fmt != FP8LM_E5M2)) return FP8LM_ERR_INVALID_ARGUMENT;
   if (hp->wcopy != FP8LM_WCOPY_E4M3 && hp->wcopy != FP8LM_WCOPY_BF16) return FP8LM_ERR_INVALID_ARGUMENT;
   if (hp->m_scale_mode < 0 || hp->m_scale_mode > 2) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (hp->master_fmt < 0 || hp->master_fmt > 3 || (hp->v_fmt != FP8LM_STATE_F16 && hp->v_fmt != FP8LM_STATE_E4M3))
+    return FP8LM_ERR_INVALID_ARGUMENT;
+  const bool variant = hp->master_fmt != FP8LM_STATE_F16 || hp->v_fmt != FP8LM_STATE_F16;
+  if (variant && (hp->wcopy != FP8LM_WCOPY_E4M3 || hp->stats)) return FP8LM_ERR_INVALID_ARGUMENT;
   if (!(hp->lr >= 0.0f && hp->lr <= 1024.0f) || !(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) ||
       !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f) || !(hp->eps >= 0x1p-36f && hp->eps < INFINITY) ||
       !(hp->weight_decay >= 0.0f && hp->weight_decay <= 1024.0f) || hp->step < 1)
@@ -1744,7 +1945,9 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
   p.lr = hp->lr;
   p.eps = hp->eps;
   p.decay = (float)(1.0 - (double)hp->lr * (double)hp->weight_decay);
-  p.v_scaled = hp->v_scaled ? 1 : 0;
+  p.v_scaled = (hp->v_scaled || hp->v_fmt == FP8LM_STATE_E4M3) ? 1 : 0;
+  p.v_fmax_bits = hp->v_fmt == FP8LM_STATE_E4M3 ? kBitsE4M3Max : kBitsF16Max;
+  p.w_fmax_bits = hp->master_fmt == FP8LM_STATE_F16 ? kBitsF16Max : (hp->master_fmt == FP8LM_STATE_E4M3 ? kBitsE4M3Max : 0u);
 
   const bool stats = hp->stats != 0, fast = hp->exact == 0;
   hipStream_t s = (hipStream_t)stream;
@@ -1774,7 +1977,10 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
   }
   fp8lm_status st = after_launch();
   if (st != FP8LM_OK) return st;
-  {
+  if (variant) {
+    Timed tm(c, s, FP8LM_K_ADAM_UPDATE);
+    launch_update_variant(c, s, p, e5, hp->master_fmt, hp->v_fmt);
+  } else {
     Timed tm(c, s, FP8LM_K_ADAM_UPDATE);
     if (e5 && q8) launch_update<kE5M2, FP8LM_WCOPY_E4M3>(c, s, p, fast, stats);
     else if (e5) launch_update<kE5M2, FP8LM_WCOPY_BF16>(c, s, p, fast, stats);

@@ -15,20 +15,23 @@ from .placement import SpreadAllocator
 class OptimizerState:
     def __init__(self, tensors, total_elems: int, cfg: B.AutoscaleCfg, device: int = 0,
                  grad_fmt: int = B.E5M2, wcopy: int = B.WCOPY_E4M3, spread: bool = False,
-                 grad_buffer: bool = False):
+                 grad_buffer: bool = False, master_fmt: int = B.STATE_F16, v_fmt: int = B.STATE_F16):
         dev = torch.device(f"cuda:{device}")
         self.tensors = list(tensors)
         self.total = int(total_elems)
         self.cfg = cfg
         self.grad_fmt = grad_fmt
         self.wcopy_kind = wcopy
+        self.master_fmt, self.v_fmt = master_fmt, v_fmt
+        state_dtype = {B.STATE_F16: torch.float16, B.STATE_BF16: torch.bfloat16, B.STATE_E4M3: torch.uint8,
+                       B.STATE_F32: torch.float32}
         self.ctx = B.Context(self.tensors, device)
         n = max(self.total, 16)
         qdt = torch.uint8 if wcopy == B.WCOPY_E4M3 else torch.bfloat16
         # Streams that the update kernel walks together go to different thirds of HBM when `spread` is
         # set (see placement.py): v (+ the bf16 gradient source) | w | m, FP8 gradient, weight copy.
-        plan = [[("v", n, torch.float16)] + ([("grad", n, torch.bfloat16)] if grad_buffer else []),
-                [("w", n, torch.float16)],
+        plan = [[("v", n, state_dtype[v_fmt])] + ([("grad", n, torch.bfloat16)] if grad_buffer else []),
+                [("w", n, state_dtype[master_fmt])],
                 [("m", n, torch.uint8), ("g8", n, torch.uint8), ("wq", n, qdt)]]
         self.placement = {}
         if spread:
@@ -52,7 +55,7 @@ class OptimizerState:
         return self.g8.element_size() + self.m.element_size() + self.v.element_size() + self.w.element_size()
 
     def init_master(self, w_bf16: torch.Tensor) -> None:
-        self.ctx.init_master(w_bf16, self.w, self.w_meta)
+        self.ctx.init_master(w_bf16, self.w, self.w_meta, self.master_fmt)
 
     def quantize_grad(self, grad_bf16: torch.Tensor) -> None:
         self.ctx.amax_scale(grad_bf16, self.grad_fmt, self.g_meta, self.cfg)

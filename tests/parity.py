@@ -24,6 +24,8 @@ def _host_bits(t: torch.Tensor, off: int, n: int) -> np.ndarray:
     sl = t[off:off + n]
     if sl.element_size() == 1:
         return sl.view(torch.uint8).cpu().numpy().copy()
+    if sl.element_size() == 4:
+        return sl.view(torch.int32).cpu().numpy().view(np.uint32).copy()
     return sl.view(torch.int16).cpu().numpy().view(np.uint16).copy()
 
 
@@ -51,7 +53,7 @@ def oracle_cfg(cfg: B.AutoscaleCfg) -> O.AutoscaleCfg:
 
 def oracle_hp(hp: B.AdamHparams) -> O.AdamHparams:
     return O.AdamHparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.step, hp.v_scaled, hp.wcopy,
-                         1 if hp.m_scale_mode == B.MSCALE_PREDICTED else 0)
+                         1 if hp.m_scale_mode == B.MSCALE_PREDICTED else 0, hp.master_fmt, hp.v_fmt)
 
 
 class Snapshot:
@@ -111,6 +113,15 @@ def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool
         O.adam_step_fp8(tens, g8, st.grad_fmt, g_meta, m, mm, v, vm, w, wm, wq, qm, ohp)
         gm, gv, gw, gq = (_host_bits(getattr(st, k), s.off, s.n) for k in ("m", "v", "w", "wq"))
         n = max(s.n, 1)
+        if hp.master_fmt != B.STATE_F16 or hp.v_fmt != B.STATE_F16:
+            # other storage formats always use correctly rounded arithmetic: everything is bit-exact
+            for name, a, b in (("m", gm, m), ("v", gv, v), ("w", gw, w), ("wcopy", gq, wq)):
+                assert np.array_equal(a, b[:s.n]), f"{tag}: {name} differs (master_fmt {hp.master_fmt}, v_fmt {hp.v_fmt})"
+            if s.n:
+                for key, ref in (("m_meta", mm), ("v_meta", vm), ("w_meta", wm), ("q_meta", qm)):
+                    bad = meta_equal(post_meta[key][s.t], ref[0], ["scale", "inv_scale", "amax", "amax_deq", "flags"])
+                    assert not bad, f"{tag}: {key} differs in {bad}: gpu {post_meta[key][s.t]} oracle {ref[0]}"
+            return out
         # second moment: multiply/fma only -> bit-exact
         assert np.array_equal(gv, v[:s.n]), f"{tag}: second moment differs"
         # first moment: bit-exact expected; bar is one code on <= 1e-4 of the elements
@@ -190,11 +201,12 @@ def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool
 
 
 def make_state(wl: synth.Workload, seed: int, grad_fmt=B.E5M2, wcopy=B.WCOPY_E4M3, hist_window=None,
-               ramp_steps=None, device=0):
+               ramp_steps=None, device=0, master_fmt=B.STATE_F16, v_fmt=B.STATE_F16):
     """State on the GPU with master weights initialised from the seeded bf16 weights."""
     from paper_2310_18313_amd.state import OptimizerState
     cfg = B.autoscale_cfg(ramp_steps=ramp_steps or wl.ramp_steps, hist_window=hist_window or wl.hist_window)
-    st = OptimizerState(wl.layout.tensors(), wl.layout.total, cfg, device, grad_fmt, wcopy)
+    st = OptimizerState(wl.layout.tensors(), wl.layout.total, cfg, device, grad_fmt, wcopy, master_fmt=master_fmt,
+                        v_fmt=v_fmt)
     w0 = torch.zeros(max(wl.layout.total, 16), dtype=torch.bfloat16, device=f"cuda:{device}")
     synth.fill_weights(w0, wl.layout, seed)
     st.init_master(w0)
@@ -207,9 +219,9 @@ def check_init_master(st, w0: torch.Tensor, ids) -> None:
     for t in ids:
         off, n = st.tensors[t]
         src = _pad(_host_bits(w0, off, n))
-        ref = np.zeros(src.size, dtype=np.uint16)
+        ref = np.zeros(src.size, dtype=O.STATE_DTYPE[st.master_fmt])
         meta = O.new_meta(1, oracle_cfg(st.cfg))
-        O.init_master(src, O.tensors_array([(0, n)]), ref, meta)
+        O.init_master_as(src, O.tensors_array([(0, n)]), ref, meta, st.master_fmt)
         assert np.array_equal(_host_bits(st.w, off, n), ref[:n]), f"init_master: tensor {t} payload differs"
         if n:
             bad = meta_equal(gpu_meta[t], meta[0], ALL_FIELDS)

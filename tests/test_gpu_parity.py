@@ -362,3 +362,34 @@ def test_shared_scale_requantize_and_sum(fmt):
             assert not diff, (ranks, t, diff, gm[t], ref_meta[t])
         if ranks >= 3:
             assert gm["flags"][0] & B.FLAG_NONFINITE
+
+
+# ---- storage formats of the precision-decoupling study (Sec. 2.2; Sec. 3.3) ----------------------------
+@pytest.mark.parametrize("master_fmt", [B.STATE_F16, B.STATE_BF16, B.STATE_E4M3, B.STATE_F32])
+@pytest.mark.parametrize("v_fmt", [B.STATE_F16, B.STATE_E4M3])
+def test_master_weight_and_second_moment_formats(master_fmt, v_fmt):
+    if master_fmt == B.STATE_F16 and v_fmt == B.STATE_F16:
+        pytest.skip("the default pair is covered everywhere else")
+    for wl, grad_fmt in ((synth.workload("tiny"), B.E5M2),
+                         (synth.Workload("mid", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-3, sigma=None), B.E4M3)):
+        st, w0 = P.make_state(wl, 13, grad_fmt, master_fmt=master_fmt, v_fmt=v_fmt)
+        ids = list(range(wl.layout.n_tensors))
+        P.check_init_master(st, w0, ids)
+        grad = torch.zeros(max(wl.layout.total, 16), dtype=torch.bfloat16, device=DEV)
+        for step in range(1, 5):
+            synth.fill_gradients(grad, wl, 13, step)
+            if step == 3:                                    # a NaN and an infinity: the careful path of every format
+                bits = synth.bits16(grad).copy()
+                off0, n0 = wl.layout.tensors()[0]
+                bits[off0 + 3] = 0x7FC0
+                bits[off0 + n0 - 2] = 0x7F80
+                grad = bf16_tensor_from_bits(bits)
+            mode = [B.MSCALE_EXACT_PASS, B.MSCALE_PREDICTED, B.MSCALE_FROM_CAST][step % 3]
+            hp = B.adam_hparams(wl.lr, step, master_fmt=master_fmt, v_fmt=v_fmt, m_scale_mode=mode)
+            snaps = [P.Snapshot(st, grad, t) for t in ids]
+            say(f"{wl.name} master_fmt={master_fmt} v_fmt={v_fmt} step={step} mode={mode}")
+            st.step(grad, hp)
+            torch.cuda.synchronize()
+            P.check_step(st, snaps, hp, what=f"{wl.name} formats step {step}")
+    with pytest.raises(B.Fp8lmError):                        # counters are not available for these formats
+        st.adam(B.adam_hparams(1e-3, 9, master_fmt=master_fmt, v_fmt=v_fmt, stats=1))
