@@ -111,6 +111,10 @@ def lib():
                                       C.c_void_p, C.c_void_p]
         L.oracle_cast_fp8_delayed.restype = None
         L.oracle_cast_fp8_delayed.argtypes = L.oracle_cast_fp8.argtypes
+        for name in ("oracle_amax_scale_src", "oracle_cast_fp8_src", "oracle_cast_fp8_delayed_src"):
+            base = getattr(L, name[:-4])
+            getattr(L, name).restype = None
+            getattr(L, name).argtypes = [C.c_void_p, C.c_int] + list(base.argtypes[1:])
         L.oracle_shared_scale.restype = None
         L.oracle_shared_scale.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.oracle_requantize_fp8.restype = None
@@ -151,22 +155,31 @@ def new_meta(n: int, cfg: AutoscaleCfg) -> np.ndarray:
     return meta
 
 
-def amax_scale(src_bf16: np.ndarray, tensors: np.ndarray, target_fmt: int, meta: np.ndarray,
-               cfg: AutoscaleCfg) -> None:
-    assert src_bf16.dtype == np.uint16
-    lib().oracle_amax_scale(_p(src_bf16), _p(tensors), len(tensors), target_fmt, _p(meta), C.byref(cfg))
+# source types of a cast: bf16 and IEEE half arrive as their uint16 bit patterns, fp32 as float32
+SRC_BF16, SRC_F16, SRC_F32 = 0, 1, 2
 
 
-def cast_fp8(src_bf16: np.ndarray, tensors: np.ndarray, dst: np.ndarray, fmt: int, meta: np.ndarray,
-             cfg: AutoscaleCfg) -> None:
-    assert src_bf16.dtype == np.uint16 and dst.dtype == np.uint8
-    lib().oracle_cast_fp8(_p(src_bf16), _p(tensors), len(tensors), _p(dst), fmt, _p(meta), C.byref(cfg))
+def _src_ok(src: np.ndarray, src_type: int) -> bool:
+    return src.dtype == (np.float32 if src_type == SRC_F32 else np.uint16)
 
 
-def cast_fp8_delayed(src_bf16: np.ndarray, tensors: np.ndarray, dst: np.ndarray, fmt: int, meta: np.ndarray,
-                     cfg: AutoscaleCfg) -> None:
-    assert src_bf16.dtype == np.uint16 and dst.dtype == np.uint8
-    lib().oracle_cast_fp8_delayed(_p(src_bf16), _p(tensors), len(tensors), _p(dst), fmt, _p(meta), C.byref(cfg))
+def amax_scale(src: np.ndarray, tensors: np.ndarray, target_fmt: int, meta: np.ndarray,
+               cfg: AutoscaleCfg, src_type: int = SRC_BF16) -> None:
+    assert _src_ok(src, src_type)
+    lib().oracle_amax_scale_src(_p(src), src_type, _p(tensors), len(tensors), target_fmt, _p(meta), C.byref(cfg))
+
+
+def cast_fp8(src: np.ndarray, tensors: np.ndarray, dst: np.ndarray, fmt: int, meta: np.ndarray,
+             cfg: AutoscaleCfg, src_type: int = SRC_BF16) -> None:
+    assert _src_ok(src, src_type) and dst.dtype == np.uint8
+    lib().oracle_cast_fp8_src(_p(src), src_type, _p(tensors), len(tensors), _p(dst), fmt, _p(meta), C.byref(cfg))
+
+
+def cast_fp8_delayed(src: np.ndarray, tensors: np.ndarray, dst: np.ndarray, fmt: int, meta: np.ndarray,
+                     cfg: AutoscaleCfg, src_type: int = SRC_BF16) -> None:
+    assert _src_ok(src, src_type) and dst.dtype == np.uint8
+    lib().oracle_cast_fp8_delayed_src(_p(src), src_type, _p(tensors), len(tensors), _p(dst), fmt, _p(meta),
+                                      C.byref(cfg))
 
 
 def _ptr_array(arrays):

@@ -231,23 +231,34 @@ void oracle_meta_init(oracle_meta* meta, int32_t n, const oracle_autoscale_cfg* 
   }
 }
 
-// ---- step a1 + a2: per-tensor amax of the bf16 gradient and the scale update ------------------
+// ---- the high-precision source of a cast ------------------------------------------------------
+// Gradients reach the cast as bf16, IEEE half or fp32 (Sec. 2.1 casts "high-precision" gradients;
+// the mixed-precision baselines of Sec. 3.1 keep them in 16 or 32 bits).  Every one of them is
+// widened to fp32 exactly before anything else happens.
+enum { ORACLE_SRC_BF16 = 0, ORACLE_SRC_F16 = 1, ORACLE_SRC_F32 = 2 };
+static float src_value(const void* src, int src_type, int64_t i) {
+  if (src_type == ORACLE_SRC_F32) return static_cast<const float*>(src)[i];
+  const uint16_t b = static_cast<const uint16_t*>(src)[i];
+  return src_type == ORACLE_SRC_F16 ? dec_f16(b) : dec_bf16(b);
+}
+
+// ---- step a1 + a2: per-tensor amax of the gradient and the scale update -----------------------
 // amax is just-in-time (Appendix A.2): it is taken over the tensor that is about to be cast.
 // The scale is the largest power of two that keeps scale * amax_eff inside the target format,
 // times the auto-scaling factor mu = 2^mu_exp (Sec. 2.1, Eq. 3: g' = mu * g), divided by
 // 2^margin.  amax_eff is the largest of the hist_window most recent amax values (Appendix A.2,
 // delayed scaling keeps such a history; a window of 1 is pure just-in-time scaling).
-void oracle_amax_scale(const uint16_t* src_bf16, const oracle_tensor* tensors, int32_t n_tensors,
-                       int target_fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
+void oracle_amax_scale_src(const void* src, int src_type, const oracle_tensor* tensors, int32_t n_tensors,
+                           int target_fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
   for (int32_t t = 0; t < n_tensors; ++t) {
     const int64_t n = tensors[t].numel;
     if (n == 0) continue;
-    const uint16_t* g = src_bf16 + tensors[t].offset;
+    const int64_t off = tensors[t].offset;
     oracle_meta& M = meta[t];
     bool nonfinite = false;
     float A = 0.0f;
     for (int64_t i = 0; i < n; ++i) {
-      const float a = std::fabs(dec_bf16(g[i]));
+      const float a = std::fabs(src_value(src, src_type, off + i));
       if (!(a <= std::numeric_limits<float>::max())) nonfinite = true;  // inf or NaN
       else if (a > A) A = a;
     }
@@ -276,30 +287,35 @@ void oracle_amax_scale(const uint16_t* src_bf16, const oracle_tensor* tensors, i
     M.flags = flags;
   }
 }
+void oracle_amax_scale(const uint16_t* src_bf16, const oracle_tensor* tensors, int32_t n_tensors,
+                       int target_fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
+  oracle_amax_scale_src(src_bf16, ORACLE_SRC_BF16, tensors, n_tensors, target_fmt, meta, cfg);
+}
 
 // ---- step a3 + a4: the scaled saturating cast and the auto-scaling state machine --------------
 // payload = FP8(scale * g), round to nearest even, saturating (Sec. 2.1: the value is
 // payload / scale).  The statistic of Sec. 2.1 is the share of payloads whose magnitude is the
 // largest finite code; above sat_num/sat_den (0.001 %) the next step uses mu = 1/2, and after
 // that mu climbs back one doubling per ramp_steps/2 clean steps until it reaches 2.
-void oracle_cast_fp8(const uint16_t* src_bf16, const oracle_tensor* tensors, int32_t n_tensors,
-                     uint8_t* dst, int fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
+void oracle_cast_fp8_src(const void* src, int src_type, const oracle_tensor* tensors, int32_t n_tensors,
+                         uint8_t* dst, int fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
   const uint32_t top = maxcode_fp8(fmt);
   for (int32_t t = 0; t < n_tensors; ++t) {
     const int64_t n = tensors[t].numel;
     if (n == 0) continue;
-    const uint16_t* g = src_bf16 + tensors[t].offset;
+    const int64_t off = tensors[t].offset;
     uint8_t* q = dst + tensors[t].offset;
     oracle_meta& M = meta[t];
     uint64_t n_sat = 0, n_under = 0;
     float stored_max = 0.0f;
     for (int64_t i = 0; i < n; ++i) {
-      const float y = dec_bf16(g[i]) * M.scale;
+      const float x = src_value(src, src_type, off + i);
+      const float y = x * M.scale;
       const uint8_t c = enc_fp8(fmt, y);
       q[i] = c;
       const uint32_t mag = c & 0x7Fu;
       if (mag == top) ++n_sat;
-      if ((g[i] & 0x7FFFu) != 0 && mag == 0) ++n_under;
+      if (x != 0.0f && mag == 0) ++n_under;   // a non-zero input (NaN included) stored as +-0
       const float d = std::fabs(dec_fp8(fmt, c));
       if (d == d && d > stored_max) stored_max = d;   // NaN codes carry no magnitude
     }
@@ -316,6 +332,10 @@ void oracle_cast_fp8(const uint16_t* src_bf16, const oracle_tensor* tensors, int
     M.mu_exp = -1 + (ramp > 2 ? 2 : ramp);
   }
 }
+void oracle_cast_fp8(const uint16_t* src_bf16, const oracle_tensor* tensors, int32_t n_tensors,
+                     uint8_t* dst, int fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
+  oracle_cast_fp8_src(src_bf16, ORACLE_SRC_BF16, tensors, n_tensors, dst, fmt, meta, cfg);
+}
 
 // ---- delayed scaling for the gradient cast (Appendix A.2) --------------------------------------
 // The scale comes from the amax values of preceding steps only (the history ring as it stands
@@ -323,8 +343,8 @@ void oracle_cast_fp8(const uint16_t* src_bf16, const oracle_tensor* tensors, int
 // that scale (saturating: a gradient that grew past the history clips and is counted in n_sat),
 // and this step's amax is pushed into the ring for the steps to come.  An all-zero history (first
 // step) keeps the scale that is already in the metadata.
-void oracle_cast_fp8_delayed(const uint16_t* src_bf16, const oracle_tensor* tensors, int32_t n_tensors,
-                             uint8_t* dst, int fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
+void oracle_cast_fp8_delayed_src(const void* src, int src_type, const oracle_tensor* tensors, int32_t n_tensors,
+                                 uint8_t* dst, int fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
   const int H = clampi(cfg->hist_window, 1, ORACLE_HIST);
   for (int32_t t = 0; t < n_tensors; ++t) {
     const int64_t n = tensors[t].numel;
@@ -344,11 +364,11 @@ void oracle_cast_fp8_delayed(const uint16_t* src_bf16, const oracle_tensor* tens
       M.inv_scale = std::ldexp(1.0f, -e);
     }
     // 2. this step's amax, for the history
-    const uint16_t* g = src_bf16 + tensors[t].offset;
+    const int64_t off = tensors[t].offset;
     bool nonfinite = false;
     float A = 0.0f;
     for (int64_t i = 0; i < n; ++i) {
-      const float a = std::fabs(dec_bf16(g[i]));
+      const float a = std::fabs(src_value(src, src_type, off + i));
       if (!(a <= std::numeric_limits<float>::max())) nonfinite = true;
       else if (a > A) A = a;
     }
@@ -364,7 +384,11 @@ void oracle_cast_fp8_delayed(const uint16_t* src_bf16, const oracle_tensor* tens
     M.flags = flags;
   }
   // 3. the cast itself, counters and the auto-scaling state: identical to the two-pass path
-  oracle_cast_fp8(src_bf16, tensors, n_tensors, dst, fmt, meta, cfg);
+  oracle_cast_fp8_src(src, src_type, tensors, n_tensors, dst, fmt, meta, cfg);
+}
+void oracle_cast_fp8_delayed(const uint16_t* src_bf16, const oracle_tensor* tensors, int32_t n_tensors,
+                             uint8_t* dst, int fmt, oracle_meta* meta, const oracle_autoscale_cfg* cfg) {
+  oracle_cast_fp8_delayed_src(src_bf16, ORACLE_SRC_BF16, tensors, n_tensors, dst, fmt, meta, cfg);
 }
 
 // ---- shared-scale re-quantisation and the FP8 gradient sum (Sec. 2.1, Eq. 4-6) -------------------
@@ -408,7 +432,7 @@ void oracle_requantize_fp8(const uint8_t* src, int fmt, const oracle_meta* src_m
     M.amax_deq = stored * inv;
     M.n_sat = n_sat;
     M.n_underflow = n_under;
-    M.flags = (nonfinite ? ORACLE_FLAG_NONFINITE : 0u) | (n_sat ? ORACLE_FLAG_SATURATED : 0u);
+    M.flags = (nonfinite ? uint32_t(ORACLE_FLAG_NONFINITE) : 0u) | (n_sat ? uint32_t(ORACLE_FLAG_SATURATED) : 0u);
   }
 }
 
@@ -446,7 +470,7 @@ void oracle_sum_fp8(const uint8_t* const* payloads, int32_t n_ranks, int fmt, co
     M.amax_deq = stored * M.inv_scale;
     M.n_sat = n_sat;
     M.n_underflow = n_under;
-    M.flags = (nonfinite ? ORACLE_FLAG_NONFINITE : 0u) | (n_sat ? ORACLE_FLAG_SATURATED : 0u);
+    M.flags = (nonfinite ? uint32_t(ORACLE_FLAG_NONFINITE) : 0u) | (n_sat ? uint32_t(ORACLE_FLAG_SATURATED) : 0u);
     const int R = cfg->ramp_steps < 2 ? 2 : cfg->ramp_steps;
     const bool overflow = int64_t(n_sat) * int64_t(cfg->sat_den) > n * int64_t(cfg->sat_num);
     if (overflow) M.clean_steps = 0;

@@ -357,3 +357,105 @@ def test_fp8_second_moment_flushes_small_entries_to_zero():
             exact = 0.05 * g ** 2
             assert np.all(v[exact < vmax * 2.0 ** -19.9] == 0)
     assert zeros[O.ST_F16] == 0 and zeros[O.ST_E4M3] > 0.001
+
+
+# ---- fp16 and fp32 gradient sources ----------------------------------------------------------------
+def _meta_same(a, b):
+    return all(np.array_equal(a[k], b[k], equal_nan=True) if a[k].dtype.kind == "f" else np.array_equal(a[k], b[k])
+               for k in a.dtype.names)
+
+
+@pytest.mark.parametrize("fmt", [O.E5M2, O.E4M3])
+@pytest.mark.parametrize("delayed", [False, True])
+def test_widening_a_bf16_source_changes_nothing(fmt, delayed):
+    """Every bf16 value is an fp32 value, and those inside the half-precision range are IEEE halves too: the
+    same numbers handed over in a wider type must give the same codes and metadata."""
+    lay, tens, g = ragged_case(seed=4, sigmas=(1e-3, 3e-2, 40.0, 1e-4, 1.0, 2e-2))
+    vals = bf16_vals(g)
+    vals[np.abs(vals) < 2.0 ** -14] = 0                      # keep to what a half holds exactly
+    vals = np.clip(vals, -60000, 60000).astype(np.float32)
+    g = bf16_bits(vals)
+    vals = bf16_vals(g)
+    half = vals.astype(np.float16)
+    assert np.array_equal(half.astype(np.float32), vals)
+    cfg = O.default_cfg(hist_window=3)
+    out = []
+    for src, kind in ((g, O.SRC_BF16), (half.view(np.uint16), O.SRC_F16), (vals, O.SRC_F32)):
+        meta = O.new_meta(lay.n_tensors, cfg)
+        q = np.zeros(lay.total, dtype=np.uint8)
+        for _ in range(3):
+            if delayed:
+                O.cast_fp8_delayed(src, tens, q, fmt, meta, cfg, src_type=kind)
+            else:
+                O.amax_scale(src, tens, fmt, meta, cfg, src_type=kind)
+                O.cast_fp8(src, tens, q, fmt, meta, cfg, src_type=kind)
+        out.append((q, meta))
+    for q, meta in out[1:]:
+        assert np.array_equal(q, out[0][0]) and _meta_same(meta, out[0][1])
+
+
+@pytest.mark.parametrize("fmt,fmax", [(O.E5M2, 57344.0), (O.E4M3, 448.0)])
+@pytest.mark.parametrize("kind", [O.SRC_F16, O.SRC_F32])
+def test_wide_sources_round_once_from_the_full_mantissa(fmt, fmax, kind):
+    """fp32 and fp16 inputs carry more mantissa bits than bf16: the cast is still the nearest FP8 value of
+    scale * x (brute force over the code table), the amax the plain float maximum, the counters plain counts."""
+    rng = np.random.default_rng(11)
+    lay = synth.flat_layout(20011)
+    tens = O.tensors_array(lay.tensors())
+    x = (rng.standard_normal(lay.total) * 3e-3).astype(np.float32)
+    x[::97] = 0
+    x[5] = np.float32(1e-12)                                   # far below the FP8 range at this scale
+    x[20011:] = 0                                              # padding behind the tensor is never touched
+    if kind == O.SRC_F16:
+        h = x.astype(np.float16)
+        src, x = h.view(np.uint16), h.astype(np.float32)       # numpy's IEEE half is the reference decoder
+    else:
+        src = x
+    cfg = O.default_cfg()
+    meta = O.new_meta(1, cfg)
+    q = np.zeros(lay.total, dtype=np.uint8)
+    O.amax_scale(src, tens, fmt, meta, cfg, src_type=kind)
+    A = np.abs(x).max()
+    s = float(meta[0]["scale"])
+    assert meta[0]["amax"] == A and s * A <= fmax < 2 * s * A and np.log2(s) == round(np.log2(s))
+    O.cast_fp8(src, tens, q, fmt, meta, cfg, src_type=kind)
+    y = x * np.float32(s)
+    assert np.array_equal(q, O.encode_fp8_nearest(fmt, y))
+    d = dec8(fmt, q)
+    assert np.all(np.abs(d - y) <= np.abs(dec8(fmt, q ^ 1) - y))          # no neighbouring code is nearer
+    assert meta[0]["n_underflow"] == np.count_nonzero((x != 0) & ((q & 0x7F) == 0)) >= (1 if kind == O.SRC_F32 else 0)
+    assert meta[0]["n_sat"] == np.count_nonzero((q & 0x7F) == (0x7B if fmt == O.E5M2 else 0x7E))
+    assert meta[0]["amax_deq"] == np.abs(d).max() / np.float32(s)
+    # an fp32 input that no 16-bit type holds: halfway cases are decided on the full mantissa
+    if kind == O.SRC_F32:
+        lo, hi = (1.0, 1.25) if fmt == O.E5M2 else (1.0, 1.125)
+        mid = np.float32((lo + hi) / 2)
+        probe = np.array([mid, np.nextafter(mid, np.float32(2)), np.nextafter(mid, np.float32(0)), 8.0] + [0.0] * 12,
+                         dtype=np.float32)                     # 8.0 fixes the scale
+        t1 = O.tensors_array([(0, 16)])
+        m1 = O.new_meta(1, cfg)
+        q1 = np.zeros(16, dtype=np.uint8)
+        O.amax_scale(probe, t1, fmt, m1, cfg, src_type=kind)
+        O.cast_fp8(probe, t1, q1, fmt, m1, cfg, src_type=kind)
+        back = dec8(fmt, q1[:3]) / m1[0]["scale"]
+        assert back[0] == lo and back[1] == hi and back[2] == lo          # tie to even, then strictly above / below
+
+
+@pytest.mark.parametrize("kind,bad", [(O.SRC_F16, 0x7C00), (O.SRC_F16, 0x7E01), (O.SRC_F32, np.inf), (O.SRC_F32, np.nan)])
+def test_wide_sources_flag_nonfinite_values(kind, bad):
+    lay = synth.flat_layout(100)
+    tens = O.tensors_array(lay.tensors())
+    if kind == O.SRC_F16:
+        src = np.full(lay.total, 0x3C00, dtype=np.uint16)
+        src[7] = bad
+    else:
+        src = np.ones(lay.total, dtype=np.float32)
+        src[7] = bad
+    cfg = O.default_cfg()
+    meta = O.new_meta(1, cfg)
+    q = np.zeros(lay.total, dtype=np.uint8)
+    O.amax_scale(src, tens, O.E5M2, meta, cfg, src_type=kind)
+    assert meta[0]["flags"] & O.FLAG_NONFINITE and np.isinf(meta[0]["amax"]) and meta[0]["scale"] == 1.0
+    O.cast_fp8(src, tens, q, O.E5M2, meta, cfg, src_type=kind)
+    is_nan = (kind == O.SRC_F16 and bad == 0x7E01) or (kind == O.SRC_F32 and bad != bad)
+    assert q[7] == (0x7F if is_nan else 0x7B) and q[8] == 0x3C
