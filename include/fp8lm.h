@@ -44,8 +44,10 @@ typedef enum {
 
 /* Appendix A.1: E4M3 (max 448, NaN, no infinity) and E5M2 (max 57344, infinities and NaN).      */
 typedef enum { FP8LM_E4M3 = 0, FP8LM_E5M2 = 1 } fp8lm_fmt;
-/* Element type of the high-precision gradient handed to the cast.                               */
-typedef enum { FP8LM_SRC_BF16 = 0 } fp8lm_src;
+/* Element type of the high-precision gradient handed to the cast (Sec. 2.1 quantises "high-
+ * precision" gradients): bf16 or IEEE half as 2-byte elements, fp32 as 4-byte elements.  Every
+ * source is widened to fp32 exactly before it is scaled.                                        */
+typedef enum { FP8LM_SRC_BF16 = 0, FP8LM_SRC_F16 = 1, FP8LM_SRC_F32 = 2 } fp8lm_src;
 /* Format of the low-precision weight copy written by the optimizer.                             */
 typedef enum { FP8LM_WCOPY_E4M3 = 0, FP8LM_WCOPY_BF16 = 1 } fp8lm_wcopy;
 
@@ -158,7 +160,7 @@ fp8lm_status fp8lm_meta_init(fp8lm_ctx* ctx, fp8lm_meta* meta /*device*/, const 
  * `target` and amax_eff is the largest of the last hist_window amax values.  An all-zero history
  * keeps the old scale (FLAG_AMAX_ZERO); a non-finite input keeps scale and history, sets amax = +inf
  * (FLAG_NONFINITE).  Writes meta[t].{scale, inv_scale, amax, amax_hist, hist_pos, flags}.
- *   src  : device, flat bf16 gradient buffer (read only).
+ *   src  : device, flat gradient buffer of element type src_type (read only, 16-byte aligned).
  *   meta : device array [n_tensors], read and written.
  */
 fp8lm_status fp8lm_amax_scale(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_src src_type, fp8lm_fmt target,
@@ -171,7 +173,8 @@ fp8lm_status fp8lm_amax_scale(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_
  * FLAG_SATURATED} and advances the auto-scaling state of Sec. 2.1: if more than sat_num/sat_den of
  * the payloads sit on the top code the next scale uses mu = 1/2 (clean_steps = 0); otherwise
  * clean_steps grows and mu = 1/2, 1, 2 as it passes 0, ramp_steps/2, ramp_steps.
- *   src : device, flat bf16 (read only).   dst : device, flat uint8 (written inside tensors only).
+ *   src : device, flat buffer of element type src_type (read only).
+ *   dst : device, flat uint8 (written inside tensors only).
  */
 fp8lm_status fp8lm_cast_fp8(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_src src_type, uint8_t* dst /*device*/,
                             fp8lm_fmt fmt, fp8lm_meta* meta /*device*/, const fp8lm_autoscale_cfg* cfg /*host*/,

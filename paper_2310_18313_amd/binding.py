@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(HERE, "libfp8lm.so")
 
 HIST = 16
 E4M3, E5M2 = 0, 1
-SRC_BF16 = 0
+SRC_BF16, SRC_F16, SRC_F32 = 0, 1, 2
 WCOPY_E4M3, WCOPY_BF16 = 0, 1
 MSCALE_EXACT_PASS, MSCALE_PREDICTED, MSCALE_FROM_CAST = 0, 1, 2
 STATE_F16, STATE_BF16, STATE_E4M3, STATE_F32 = 0, 1, 2, 3
@@ -150,6 +150,15 @@ def _ptr(t) -> int:
     return t.data_ptr()
 
 
+def src_type_of(t: torch.Tensor) -> int:
+    """The library's source type for a gradient tensor; 16-bit integer tensors count as bf16 bit patterns."""
+    kinds = {torch.bfloat16: SRC_BF16, torch.int16: SRC_BF16, torch.uint16: SRC_BF16, torch.float16: SRC_F16,
+             torch.float32: SRC_F32}
+    if t.dtype not in kinds:
+        raise TypeError(f"no FP8 cast from {t.dtype}: the gradient must be bf16, fp16 or fp32")
+    return kinds[t.dtype]
+
+
 class Context:
     """Owns one fp8lm_ctx: a fixed list of (offset, numel) tensors inside flat device buffers."""
 
@@ -199,31 +208,30 @@ class Context:
         return meta
 
     def amax_scale(self, src, target_fmt, meta, cfg, stream=None):
-        assert src.element_size() == 2
         self._fits(src)
         self._fits_meta(meta)
-        _check(lib().fp8lm_amax_scale(self._h, _ptr(src), SRC_BF16, target_fmt, _ptr(meta), C.addressof(cfg),
+        _check(lib().fp8lm_amax_scale(self._h, _ptr(src), src_type_of(src), target_fmt, _ptr(meta), C.addressof(cfg),
                                       _stream(stream)), "fp8lm_amax_scale")
 
     def cast_fp8(self, src, dst, fmt, meta, cfg, stream=None):
-        assert src.element_size() == 2 and dst.element_size() == 1
+        assert dst.element_size() == 1
         self._fits(src, dst)
         self._fits_meta(meta)
-        _check(lib().fp8lm_cast_fp8(self._h, _ptr(src), SRC_BF16, _ptr(dst), fmt, _ptr(meta), C.addressof(cfg),
+        _check(lib().fp8lm_cast_fp8(self._h, _ptr(src), src_type_of(src), _ptr(dst), fmt, _ptr(meta), C.addressof(cfg),
                                     _stream(stream)), "fp8lm_cast_fp8")
 
     def cast_fp8_delayed(self, src, dst, fmt, meta, cfg, stream=None):
-        assert src.element_size() == 2 and dst.element_size() == 1
+        assert dst.element_size() == 1
         self._fits(src, dst)
         self._fits_meta(meta)
-        _check(lib().fp8lm_cast_fp8_delayed(self._h, _ptr(src), SRC_BF16, _ptr(dst), fmt, _ptr(meta),
+        _check(lib().fp8lm_cast_fp8_delayed(self._h, _ptr(src), src_type_of(src), _ptr(dst), fmt, _ptr(meta),
                                             C.addressof(cfg), _stream(stream)), "fp8lm_cast_fp8_delayed")
 
     def cast_fp8_for_adam(self, src, dst, fmt, meta, cfg, m, m_meta, beta1, delayed=False, stream=None):
-        assert src.element_size() == 2 and dst.element_size() == 1 and m.element_size() == 1
+        assert dst.element_size() == 1 and m.element_size() == 1
         self._fits(src, dst, m)
         self._fits_meta(meta, m_meta)
-        _check(lib().fp8lm_cast_fp8_for_adam(self._h, _ptr(src), SRC_BF16, _ptr(dst), fmt, _ptr(meta), C.addressof(cfg),
+        _check(lib().fp8lm_cast_fp8_for_adam(self._h, _ptr(src), src_type_of(src), _ptr(dst), fmt, _ptr(meta), C.addressof(cfg),
                                              1 if delayed else 0, _ptr(m), _ptr(m_meta), beta1, _stream(stream)),
                "fp8lm_cast_fp8_for_adam")
 

@@ -233,8 +233,48 @@ template <bool NT = false> __device__ __forceinline__ void st16(void* p, uint4 v
 // exact, order independent, and inf/NaN show up as a result >= 0x7F80.
 enum : int { kAmaxForGradient = 0, kAmaxForMaster = 1 };
 
+// The high-precision source of a cast: bf16, IEEE half or fp32 (Sec. 2.1 casts "high-precision"
+// gradients).  |x| is monotone in the magnitude bits of all three, so the amax is an integer maximum;
+// for the 16-bit types two maxima are kept packed in one register.
+enum : int { kSrcBF16 = 0, kSrcF16 = 1, kSrcF32 = 2 };
+template <int SRC> struct SrcTraits;
+template <> struct SrcTraits<kSrcBF16> {
+  using elem_t = uint16_t;
+  static constexpr uint32_t kNonfinite = 0x7F80u;
+  static __device__ __forceinline__ float dec(uint32_t bits) { return u2f(bits << 16); }
+};
+template <> struct SrcTraits<kSrcF16> {
+  using elem_t = uint16_t;
+  static constexpr uint32_t kNonfinite = 0x7C00u;
+  static __device__ __forceinline__ float dec(uint32_t bits) { return f16_to_f32(bits); }
+};
+template <> struct SrcTraits<kSrcF32> {
+  using elem_t = uint32_t;
+  static constexpr uint32_t kNonfinite = 0x7F800000u;
+  static __device__ __forceinline__ float dec(uint32_t bits) { return u2f(bits); }
+};
+template <int SRC> constexpr bool kSrc16 = sizeof(typename SrcTraits<SRC>::elem_t) == 2;
+template <int SRC> constexpr int kSrcWords = kSrc16<SRC> ? 8 : 16;     // 32-bit words of a 16-element group
+// folds one 32-bit word of the source (two 16-bit elements or one fp32) into a running maximum
+template <int SRC> __device__ __forceinline__ void src_fold(uint32_t& acc, uint32_t word) {
+  if constexpr (kSrc16<SRC>)
+    acc = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, acc),
+                                                                 __builtin_bit_cast(ushort2_t, word & 0x7FFF7FFFu)));
+  else
+    acc = max(acc, word & 0x7FFFFFFFu);
+}
+// the same for a single element given by its bit pattern
+template <int SRC> __device__ __forceinline__ void src_fold1(uint32_t& acc, uint32_t bits) {
+  if constexpr (kSrc16<SRC>) acc = (acc & 0xFFFF0000u) | max(acc & 0xFFFFu, bits & 0x7FFFu);
+  else acc = max(acc, bits & 0x7FFFFFFFu);
+}
+template <int SRC> __device__ __forceinline__ uint32_t src_final(uint32_t acc) {
+  if constexpr (kSrc16<SRC>) return max(acc & 0xFFFFu, acc >> 16);
+  else return acc;
+}
+
 struct AmaxParams {
-  const uint16_t* src;
+  const void* src;
   fp8lm_meta* meta;
   uint32_t fmax_bits;     // gradient mode: largest finite value of the target format
   int32_t hist_window;
@@ -264,41 +304,42 @@ __device__ __forceinline__ void push_history(fp8lm_meta& M, float A, int hist_wi
   M.hist_pos = (slot + 1) % H;
 }
 
-template <int MODE>
+template <int MODE, int SRC>
 struct AmaxOp {
+  using elem_t = typename SrcTraits<SRC>::elem_t;
+  static constexpr int kPer = 16 / (int)sizeof(elem_t);   // elements per 128-bit load
+  static constexpr int kLoads = kGroup / kPer;            // loads per thread and tile
   const AmaxParams& p;
   const Tables& tb;
-  uint32_t acc;   // two 16-bit running maxima
+  uint32_t acc;   // running maximum of the magnitude bits (two packed maxima for 16-bit sources)
   __device__ AmaxOp(const AmaxParams& p_, const Tables& tb_) : p(p_), tb(tb_), acc(0) {}
   __device__ __forceinline__ void begin(int, const TensorDesc&) { acc = 0; }
   __device__ __forceinline__ bool fast() const { return true; }
   template <int UN> __device__ __forceinline__ void tiles(long long pos) {
     // a pure reduction: each load instruction of a wavefront covers 1 KiB contiguous
-    uint4 a[UN], b[UN];
-    const uint16_t* q = p.src + pos + threadIdx.x * 8;
+    uint4 r[UN][kLoads];
+    const elem_t* q = static_cast<const elem_t*>(p.src) + pos + threadIdx.x * kPer;
 #pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      a[u] = ld16<kNtLoadRO>(q + u * kTile);
-      b[u] = ld16<kNtLoadRO>(q + u * kTile + kTile / 2);
-    }
+    for (int u = 0; u < UN; ++u)
 #pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      const uint32_t w[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
+      for (int k = 0; k < kLoads; ++k) r[u][k] = ld16<kNtLoadRO>(q + u * kTile + k * (kThreads * kPer));
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const ushort2_t x = __builtin_bit_cast(ushort2_t, w[j] & 0x7FFF7FFFu);
-        acc = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, acc), x));
+    for (int u = 0; u < UN; ++u)
+#pragma unroll
+      for (int k = 0; k < kLoads; ++k) {
+        src_fold<SRC>(acc, r[u][k].x);
+        src_fold<SRC>(acc, r[u][k].y);
+        src_fold<SRC>(acc, r[u][k].z);
+        src_fold<SRC>(acc, r[u][k].w);
       }
-    }
   }
   __device__ __forceinline__ void group(long long pos, int valid) {
-    uint32_t m = acc & 0xFFFFu;
-    for (int j = 0; j < valid; ++j) m = max(m, (uint32_t)(p.src[pos + j] & 0x7FFFu));
-    acc = (acc & 0xFFFF0000u) | m;
+    const elem_t* q = static_cast<const elem_t*>(p.src) + pos;
+    for (int j = 0; j < valid; ++j) src_fold1<SRC>(acc, q[j]);
   }
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
     BlockStats<1, 0> s;
-    s.mx[0] = max(acc & 0xFFFFu, acc >> 16);
+    s.mx[0] = src_final<SRC>(acc);
     s.orv = 0;
     block_combine(s);
     if (threadIdx.x == 0) {
@@ -314,12 +355,12 @@ struct AmaxOp {
   // scalar epilogue, one thread per tensor
   __device__ void finish(int t, uint32_t abits) {
     fp8lm_meta& M = p.meta[t];
-    if (abits >= 0x7F80u) {
+    if (abits >= SrcTraits<SRC>::kNonfinite) {
       M.amax = __builtin_inff();
       M.flags = FP8LM_FLAG_NONFINITE;
       return;
     }
-    const float A = u2f(abits << 16);
+    const float A = SrcTraits<SRC>::dec(abits);
     M.amax = A;
     uint32_t flags = 0;
     if constexpr (MODE == kAmaxForGradient) {
@@ -344,9 +385,9 @@ struct AmaxOp {
   }
 };
 
-template <int MODE>
+template <int MODE, int SRC>
 __global__ __launch_bounds__(kThreads) void amax_kernel(Tables tb, AmaxParams p) {
-  AmaxOp<MODE> op(p, tb);
+  AmaxOp<MODE, SRC> op(p, tb);
   walk_chunks<FP8LM_UN_READ>(tb, op);
 }
 
@@ -365,7 +406,7 @@ __device__ __forceinline__ void autoscale_update(fp8lm_meta& M, unsigned long lo
 }
 
 struct CastParams {
-  const uint16_t* src;
+  const void* src;
   uint8_t* dst;
   fp8lm_meta* meta;
   int32_t sat_num, sat_den, ramp_steps;
@@ -384,15 +425,19 @@ __device__ __forceinline__ uint32_t nonzero_bytes7(uint32_t x) { return __popc((
 // has looked for inf/NaN it checks every 16-element group itself.
 // FUSE: on one GPU the Adam step follows the cast directly, so this pass also measures what the Adam
 // step's first pass would: max |fma(beta1, m, (1-beta1) * g)| with g the value just stored in FP8.
-template <int FMT, bool DELAYED, bool FUSE>
+template <int FMT, bool DELAYED, bool FUSE, int SRC>
 struct CastOp {
+  using elem_t = typename SrcTraits<SRC>::elem_t;
+  static constexpr int kPer = 16 / (int)sizeof(elem_t);   // elements per 128-bit load
+  static constexpr int kLoads = kGroup / kPer;            // loads per 16-element group
+  static constexpr int kW = kSrcWords<SRC>;
   const CastParams& p;
   const Tables& tb;
   float scale;
   bool careful;
   float inv_sg, inv_sm;   // FUSE
   uint32_t macc;          // FUSE: running max of the |m'| bit patterns
-  uint32_t amax16;        // DELAYED: two 16-bit running maxima of (bits & 0x7FFF)
+  uint32_t amax16;        // DELAYED: running maximum of the source's magnitude bits (packed pair for 16-bit types)
   float vmax;             // max |clamped scaled value|
   uint32_t n_elems;       // elements seen (full groups * 16 + tails) since the last flush
   uint32_t nz_top;        // codes whose magnitude differs from the top code
@@ -424,16 +469,29 @@ struct CastOp {
     moment(g23.y, m23.y);
   }
   // DELAYED: folds one group's source bits into the running amax; true if the group holds inf or NaN
-  __device__ __forceinline__ bool note_source(const uint4& a, const uint4& b) {
-    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    ushort2_t gm = __builtin_bit_cast(ushort2_t, w[0] & 0x7FFF7FFFu);
+  __device__ __forceinline__ bool note_source(const uint32_t (&w)[kW]) {
+    uint32_t gm = 0;
 #pragma unroll
-    for (int j = 1; j < 8; ++j) gm = __builtin_elementwise_max(gm, __builtin_bit_cast(ushort2_t, w[j] & 0x7FFF7FFFu));
-    amax16 = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, amax16), gm));
-    return (gm.x > gm.y ? gm.x : gm.y) >= 0x7F80u;
+    for (int j = 0; j < kW; ++j) src_fold<SRC>(gm, w[j]);
+    if constexpr (kSrc16<SRC>)
+      amax16 = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, amax16),
+                                                                      __builtin_bit_cast(ushort2_t, gm)));
+    else
+      amax16 = max(amax16, gm);
+    return src_final<SRC>(gm) >= SrcTraits<SRC>::kNonfinite;
   }
-  __device__ __forceinline__ uint32_t quad(uint32_t w0, uint32_t w1) {
-    const float f0 = bf16lo_to_f32(w0), f1 = bf16hi_to_f32(w0), f2 = bf16lo_to_f32(w1), f3 = bf16hi_to_f32(w1);
+  // four consecutive elements of a group (quad q = 0..3) widened to fp32
+  __device__ __forceinline__ uint32_t quad(const uint32_t (&w)[kW], int q) {
+    float f0, f1, f2, f3;
+    if constexpr (SRC == kSrcBF16) {
+      f0 = bf16lo_to_f32(w[2 * q]); f1 = bf16hi_to_f32(w[2 * q]);
+      f2 = bf16lo_to_f32(w[2 * q + 1]); f3 = bf16hi_to_f32(w[2 * q + 1]);
+    } else if constexpr (SRC == kSrcF16) {
+      const float2_t lo = f16x2_to_f32(w[2 * q]), hi = f16x2_to_f32(w[2 * q + 1]);
+      f0 = lo.x; f1 = lo.y; f2 = hi.x; f3 = hi.y;
+    } else {
+      f0 = u2f(w[4 * q]); f1 = u2f(w[4 * q + 1]); f2 = u2f(w[4 * q + 2]); f3 = u2f(w[4 * q + 3]);
+    }
     const float y0 = clamp_fp8<FMT>(f0 * scale), y1 = clamp_fp8<FMT>(f1 * scale);
     const float y2 = clamp_fp8<FMT>(f2 * scale), y3 = clamp_fp8<FMT>(f3 * scale);
     vmax = fmaxf(fmaxf(vmax, fmaxf(fabsf(y0), fabsf(y1))), fmaxf(fabsf(y2), fabsf(y3)));
@@ -446,7 +504,7 @@ struct CastOp {
     return c;
   }
   __device__ __forceinline__ uint32_t one(uint32_t bits, uint32_t mcode) {
-    const float f = u2f(bits << 16);
+    const float f = SrcTraits<SRC>::dec(bits);
     const float y = f * scale;
     uint32_t c;
     if (y != y) {
@@ -459,43 +517,49 @@ struct CastOp {
     z_in += (f == 0.0f);
     nz_code += (c & 0x7Fu) != 0;
     nz_top += (c & 0x7Fu) != Fp8Traits<FMT>::kTop;
-    if constexpr (DELAYED) amax16 = max(amax16 & 0xFFFFu, bits & 0x7FFFu) | (amax16 & 0xFFFF0000u);
+    if constexpr (DELAYED) src_fold1<SRC>(amax16, bits);
     if constexpr (FUSE) moment(fp8_to_f32<FMT>(c), fp8_to_f32<kE4M3>(mcode));
     return c;
   }
   __device__ __forceinline__ bool fast() const { return !careful; }
   template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
-    uint4 a[UN], b[UN], mm[UN];
+    uint4 r[UN][kLoads], mm[UN];
     const long long pos = pos0 + threadIdx.x * kGroup;
+    const elem_t* q = static_cast<const elem_t*>(p.src) + pos;
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      a[u] = ld16<kNtLoadRO>(p.src + pos + u * kTile);
-      b[u] = ld16<kNtLoadRO>(p.src + pos + u * kTile + 8);
+#pragma unroll
+      for (int k = 0; k < kLoads; ++k) r[u][k] = ld16<kNtLoadRO>(q + u * kTile + k * kPer);
       if constexpr (FUSE) mm[u] = ld16<kNtLoadRO>(p.m + pos + u * kTile);
     }
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
+      uint32_t w[kW];
+#pragma unroll
+      for (int k = 0; k < kLoads; ++k) {
+        w[4 * k] = r[u][k].x; w[4 * k + 1] = r[u][k].y; w[4 * k + 2] = r[u][k].z; w[4 * k + 3] = r[u][k].w;
+      }
       if constexpr (DELAYED) {
-        if (note_source(a[u], b[u])) {   // rare: this group holds inf/NaN, encode it element by element
-          const uint32_t w[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
+        if (note_source(w)) {   // rare: this group holds inf/NaN, encode it element by element
           const uint32_t mw[4] = {mm[u].x, mm[u].y, mm[u].z, mm[u].w};
           const uint32_t keep = amax16;
           uint4 o = make_uint4(0, 0, 0, 0);
           uint32_t* ow = &o.x;
 #pragma unroll
-          for (int j = 0; j < 16; ++j)
-            ow[j >> 2] |= one((w[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu, FUSE ? (mw[j >> 2] >> ((j & 3) * 8)) & 0xFFu : 0u)
-                          << ((j & 3) * 8);
+          for (int j = 0; j < 16; ++j) {
+            const uint32_t bits = kSrc16<SRC> ? (w[(j >> 1) % kW] >> ((j & 1) * 16)) & 0xFFFFu : w[j % kW];
+            ow[j >> 2] |= one(bits, FUSE ? (mw[j >> 2] >> ((j & 3) * 8)) & 0xFFu : 0u) << ((j & 3) * 8);
+          }
           amax16 = keep;
           st16<kNtStoreWO>(p.dst + pos + u * kTile, o);
           continue;
         }
       }
       uint4 o;
-      o.x = quad(a[u].x, a[u].y);
-      o.y = quad(a[u].z, a[u].w);
-      o.z = quad(b[u].x, b[u].y);
-      o.w = quad(b[u].z, b[u].w);
+      o.x = quad(w, 0);
+      o.y = quad(w, 1);
+      o.z = quad(w, 2);
+      o.w = quad(w, 3);
       if constexpr (FUSE) {
         moment_word(o.x, mm[u].x);
         moment_word(o.y, mm[u].y);
@@ -507,13 +571,14 @@ struct CastOp {
     n_elems += UN * kGroup;
   }
   __device__ __forceinline__ void group(long long pos, int valid) {
-    for (int j = 0; j < valid; ++j) p.dst[pos + j] = (uint8_t)one(p.src[pos + j], FUSE ? p.m[pos + j] : 0u);
+    const elem_t* q = static_cast<const elem_t*>(p.src) + pos;
+    for (int j = 0; j < valid; ++j) p.dst[pos + j] = (uint8_t)one(q[j], FUSE ? p.m[pos + j] : 0u);
     n_elems += valid;
   }
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
     BlockStats<3, 2> s;
     s.mx[0] = f2u(vmax);
-    s.mx[1] = max(amax16 & 0xFFFFu, amax16 >> 16);
+    s.mx[1] = src_final<SRC>(amax16);
     s.mx[2] = macc;
     s.ct[0] = n_elems - nz_top;                 // codes on the top magnitude
     s.ct[1] = (n_elems - nz_code) - z_in;       // zero codes that did not come from zero inputs
@@ -534,11 +599,11 @@ struct CastOp {
         take_u32(&sc->ticket);
         if constexpr (DELAYED) {
           fp8lm_meta& M = p.meta[t];
-          if (abits >= 0x7F80u) {
+          if (abits >= SrcTraits<SRC>::kNonfinite) {
             M.amax = __builtin_inff();
             M.flags |= FP8LM_FLAG_NONFINITE;
           } else {
-            M.amax = u2f(abits << 16);
+            M.amax = SrcTraits<SRC>::dec(abits);
             push_history(M, M.amax, p.hist_window);
           }
         }
@@ -556,9 +621,9 @@ struct CastOp {
   }
 };
 
-template <int FMT, bool DELAYED, bool FUSE>
+template <int FMT, bool DELAYED, bool FUSE, int SRC>
 __global__ __launch_bounds__(kThreads) void cast_kernel(Tables tb, CastParams p) {
-  CastOp<FMT, DELAYED, FUSE> op(p, tb);
+  CastOp<FMT, DELAYED, FUSE, SRC> op(p, tb);
   walk_chunks<FP8LM_UN_CAST>(tb, op);
 }
 
@@ -1643,6 +1708,7 @@ void launch_update_variant(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, boo
   else launch_update_variant_g<kE4M3>(c, s, p, master, vfmt);
 }
 
+bool src_ok(fp8lm_src t) { return t == FP8LM_SRC_BF16 || t == FP8LM_SRC_F16 || t == FP8LM_SRC_F32; }
 bool cfg_ok(const fp8lm_autoscale_cfg* cfg) {
   return cfg && cfg->sat_num >= 0 && cfg->sat_den > 0 && cfg->ramp_steps >= 2 && cfg->hist_window >= 1 &&
          cfg->hist_window <= FP8LM_HIST && cfg->margin >= -64 && cfg->margin <= 64;
@@ -1743,17 +1809,20 @@ fp8lm_status fp8lm_meta_init(fp8lm_ctx* c, fp8lm_meta* meta, const fp8lm_autosca
 
 fp8lm_status fp8lm_amax_scale(fp8lm_ctx* c, const void* src, fp8lm_src src_type, fp8lm_fmt target, fp8lm_meta* meta,
                               const fp8lm_autoscale_cfg* cfg, void* stream) {
-  if (!c || !cfg_ok(cfg) || src_type != FP8LM_SRC_BF16 || (target != FP8LM_E4M3 && target != FP8LM_E5M2))
+  if (!c || !cfg_ok(cfg) || !src_ok(src_type) || (target != FP8LM_E4M3 && target != FP8LM_E5M2))
     return FP8LM_ERR_INVALID_ARGUMENT;
   if (c->n_chunks == 0) return FP8LM_OK;
   if (!src || !meta) return FP8LM_ERR_INVALID_ARGUMENT;
   if (!aligned16(src)) return FP8LM_ERR_MISALIGNED;
   DeviceGuard guard(c->device);
-  AmaxParams p{static_cast<const uint16_t*>(src), meta, target == FP8LM_E4M3 ? kBitsE4M3Max : kBitsE5M2Max,
-               cfg->hist_window, cfg->margin};
-  Timed tm(c, (hipStream_t)stream, FP8LM_K_AMAX);
-  hipLaunchKernelGGL(amax_kernel<kAmaxForGradient>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream,
-                     tables_of(c), p);
+  AmaxParams p{src, meta, target == FP8LM_E4M3 ? kBitsE4M3Max : kBitsE5M2Max, cfg->hist_window, cfg->margin};
+  const dim3 g(grid_of(c)), b(kThreads);
+  hipStream_t s = (hipStream_t)stream;
+  const Tables tb = tables_of(c);
+  Timed tm(c, s, FP8LM_K_AMAX);
+  if (src_type == FP8LM_SRC_F32) hipLaunchKernelGGL((amax_kernel<kAmaxForGradient, kSrcF32>), g, b, 0, s, tb, p);
+  else if (src_type == FP8LM_SRC_F16) hipLaunchKernelGGL((amax_kernel<kAmaxForGradient, kSrcF16>), g, b, 0, s, tb, p);
+  else hipLaunchKernelGGL((amax_kernel<kAmaxForGradient, kSrcBF16>), g, b, 0, s, tb, p);
   return after_launch();
 }
 
@@ -1761,7 +1830,7 @@ fp8lm_status fp8lm_amax_scale(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
 static fp8lm_status cast_impl(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
                               fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, bool delayed, bool fuse,
                               const uint8_t* m, const fp8lm_meta* m_meta, float beta1, void* stream) {
-  if (!c || !cfg_ok(cfg) || src_type != FP8LM_SRC_BF16 || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2))
+  if (!c || !cfg_ok(cfg) || !src_ok(src_type) || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2))
     return FP8LM_ERR_INVALID_ARGUMENT;
   c->fused.valid = false;
   if (fuse && !(beta1 >= 0.0f && beta1 < 1.0f)) return FP8LM_ERR_INVALID_ARGUMENT;
@@ -1778,7 +1847,7 @@ static fp8lm_status cast_impl(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
     if (st != FP8LM_OK) return st;
   }
   CastParams p{};
-  p.src = static_cast<const uint16_t*>(src);
+  p.src = src;
   p.dst = dst;
   p.meta = meta;
   p.sat_num = cfg->sat_num; p.sat_den = cfg->sat_den; p.ramp_steps = cfg->ramp_steps; p.hist_window = cfg->hist_window;
@@ -1790,15 +1859,22 @@ static fp8lm_status cast_impl(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
   const Tables tb = tables_of(c);
   {
     Timed tm(c, s, FP8LM_K_CAST);
-#define FP8LM_CAST_LAUNCH(F)                                                                              \
+#define FP8LM_CAST_LAUNCH(F, S)                                                                           \
     do {                                                                                                    \
-      if (delayed && fuse) hipLaunchKernelGGL((cast_kernel<F, true, true>), g, b, 0, s, tb, p);             \
-      else if (delayed) hipLaunchKernelGGL((cast_kernel<F, true, false>), g, b, 0, s, tb, p);               \
-      else if (fuse) hipLaunchKernelGGL((cast_kernel<F, false, true>), g, b, 0, s, tb, p);                  \
-      else hipLaunchKernelGGL((cast_kernel<F, false, false>), g, b, 0, s, tb, p);                           \
+      if (delayed && fuse) hipLaunchKernelGGL((cast_kernel<F, true, true, S>), g, b, 0, s, tb, p);          \
+      else if (delayed) hipLaunchKernelGGL((cast_kernel<F, true, false, S>), g, b, 0, s, tb, p);            \
+      else if (fuse) hipLaunchKernelGGL((cast_kernel<F, false, true, S>), g, b, 0, s, tb, p);               \
+      else hipLaunchKernelGGL((cast_kernel<F, false, false, S>), g, b, 0, s, tb, p);                        \
     } while (0)
-    if (fmt == FP8LM_E4M3) FP8LM_CAST_LAUNCH(kE4M3);
-    else FP8LM_CAST_LAUNCH(kE5M2);
+#define FP8LM_CAST_SRC(S)                                                                                   \
+    do {                                                                                                    \
+      if (fmt == FP8LM_E4M3) FP8LM_CAST_LAUNCH(kE4M3, S);                                                   \
+      else FP8LM_CAST_LAUNCH(kE5M2, S);                                                                     \
+    } while (0)
+    if (src_type == FP8LM_SRC_F32) FP8LM_CAST_SRC(kSrcF32);
+    else if (src_type == FP8LM_SRC_F16) FP8LM_CAST_SRC(kSrcF16);
+    else FP8LM_CAST_SRC(kSrcBF16);
+#undef FP8LM_CAST_SRC
 #undef FP8LM_CAST_LAUNCH
   }
   fp8lm_status st = after_launch();
@@ -1893,7 +1969,7 @@ fp8lm_status fp8lm_init_master_as(fp8lm_ctx* c, const void* w_bf16, void* w_out,
   Timed tm(c, s, FP8LM_K_INIT_MASTER);
   const uint32_t fmax_bits = master_fmt == FP8LM_STATE_F16 ? kBitsF16Max : (master_fmt == FP8LM_STATE_E4M3 ? kBitsE4M3Max : 0u);
   AmaxParams pa{static_cast<const uint16_t*>(w_bf16), w_meta, fmax_bits, 1, 0};
-  hipLaunchKernelGGL(amax_kernel<kAmaxForMaster>, dim3(grid_of(c)), dim3(kThreads), 0, s, tables_of(c), pa);
+  hipLaunchKernelGGL((amax_kernel<kAmaxForMaster, kSrcBF16>), dim3(grid_of(c)), dim3(kThreads), 0, s, tables_of(c), pa);
   fp8lm_status st = after_launch();
   if (st != FP8LM_OK) return st;
   InitParams pi{static_cast<const uint16_t*>(w_bf16), w_out, w_meta};

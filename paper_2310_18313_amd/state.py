@@ -69,18 +69,19 @@ class OptimizerState:
         self.ctx.adam_step_fp8(self.g8, self.grad_fmt, self.g_meta, self.m, self.m_meta, self.v, self.v_meta,
                                self.w, self.w_meta, self.wq, self.q_meta, hp)
 
-    def step(self, grad_bf16: torch.Tensor, hp: B.AdamHparams, delayed: bool = False) -> None:
-        """One pass of the whole hot path: amax + scale, FP8 cast, FP8 Adam.  With `delayed` the
+    def step(self, grad: torch.Tensor, hp: B.AdamHparams, delayed: bool = False) -> None:
+        """One pass of the whole hot path: amax + scale, FP8 cast, FP8 Adam, from a bf16, fp16 or fp32
+        gradient buffer.  With `delayed` the
         gradient is quantised in a single pass with the scale of the preceding steps.  With
         hp.m_scale_mode == MSCALE_FROM_CAST the cast also does the Adam step's first pass."""
         fused = hp.m_scale_mode == B.MSCALE_FROM_CAST
         if not delayed:
-            self.ctx.amax_scale(grad_bf16, self.grad_fmt, self.g_meta, self.cfg)
+            self.ctx.amax_scale(grad, self.grad_fmt, self.g_meta, self.cfg)
         if fused:
-            self.ctx.cast_fp8_for_adam(grad_bf16, self.g8, self.grad_fmt, self.g_meta, self.cfg, self.m, self.m_meta,
+            self.ctx.cast_fp8_for_adam(grad, self.g8, self.grad_fmt, self.g_meta, self.cfg, self.m, self.m_meta,
                                        hp.beta1, delayed=delayed)
         elif delayed:
-            self.ctx.cast_fp8_delayed(grad_bf16, self.g8, self.grad_fmt, self.g_meta, self.cfg)
+            self.ctx.cast_fp8_delayed(grad, self.g8, self.grad_fmt, self.g_meta, self.cfg)
         else:
-            self.ctx.cast_fp8(grad_bf16, self.g8, self.grad_fmt, self.g_meta, self.cfg)
+            self.ctx.cast_fp8(grad, self.g8, self.grad_fmt, self.g_meta, self.cfg)
         self.adam(hp)

@@ -136,8 +136,8 @@ _PIECE = 1 << 26  # generate large tensors piecewise to bound the fp32 temporari
 
 
 def fill_gradients(dst: torch.Tensor, wl: Workload, seed: int, step: int) -> None:
-    """Fill the flat bf16 buffer `dst` with this step's gradients (padding stays zero)."""
-    assert dst.dtype == torch.bfloat16 and dst.numel() >= wl.layout.total
+    """Fill the flat buffer `dst` (bf16, fp16 or fp32) with this step's gradients (padding stays zero)."""
+    assert dst.dtype in (torch.bfloat16, torch.float16, torch.float32) and dst.numel() >= wl.layout.total
     sig = per_tensor_sigma(wl, seed)
     dev = dst.device
     for i, (off, n) in enumerate(wl.layout.tensors()):
@@ -155,7 +155,7 @@ def fill_gradients(dst: torch.Tensor, wl: Workload, seed: int, step: int) -> Non
                 out = torch.rand(pn, generator=g, device=dev, dtype=torch.float32) < 1e-4
                 x = torch.where(out, x * 1e3, x)
             x = x * float(sig[i])
-            dst[off + p0: off + p0 + pn] = x.to(torch.bfloat16)
+            dst[off + p0: off + p0 + pn] = x.to(dst.dtype)
 
 
 def fill_weights(dst: torch.Tensor, layout: Layout, seed: int) -> None:

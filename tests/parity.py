@@ -63,6 +63,9 @@ class Snapshot:
         off, n = st.tensors[t]
         self.t, self.off, self.n = t, off, n
         self.src = _pad(_host_bits(grad_bf16, off, n))
+        self.src_type = B.src_type_of(grad_bf16)             # same numbering in the library and the oracle
+        if self.src_type == B.SRC_F32:
+            self.src = self.src.view(np.float32)
         self.m = _pad(_host_bits(st.m, off, n))
         self.v = _pad(_host_bits(st.v, off, n))
         self.w = _pad(_host_bits(st.w, off, n))
@@ -95,10 +98,10 @@ def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool
         g_meta = s.metas["g_meta"].copy()
         g8 = np.zeros(s.src.size, dtype=np.uint8)
         if delayed:
-            O.cast_fp8_delayed(s.src, tens, g8, st.grad_fmt, g_meta, cfg)
+            O.cast_fp8_delayed(s.src, tens, g8, st.grad_fmt, g_meta, cfg, src_type=s.src_type)
         else:
-            O.amax_scale(s.src, tens, st.grad_fmt, g_meta, cfg)
-            O.cast_fp8(s.src, tens, g8, st.grad_fmt, g_meta, cfg)
+            O.amax_scale(s.src, tens, st.grad_fmt, g_meta, cfg, src_type=s.src_type)
+            O.cast_fp8(s.src, tens, g8, st.grad_fmt, g_meta, cfg, src_type=s.src_type)
         gpu_g8 = _host_bits(st.g8, s.off, s.n)
         assert np.array_equal(gpu_g8, g8[:s.n]), f"{tag}: FP8 gradient codes differ"
         if s.n:

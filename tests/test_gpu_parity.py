@@ -393,3 +393,114 @@ def test_master_weight_and_second_moment_formats(master_fmt, v_fmt):
             P.check_step(st, snaps, hp, what=f"{wl.name} formats step {step}")
     with pytest.raises(B.Fp8lmError):                        # counters are not available for these formats
         st.adam(B.adam_hparams(1e-3, 9, master_fmt=master_fmt, v_fmt=v_fmt, stats=1))
+
+
+# ---- fp16 and fp32 gradient sources ---------------------------------------------------------------------
+def _interesting_f32(fmt):
+    """fp32 values that decide roundings: every FP8 value, every midpoint between neighbours, each one fp32
+    step up and down, the same around the saturation point, zeros, subnormals and the largest floats."""
+    table = O.decode_table(fmt)
+    vals = np.unique(np.abs(table[np.isfinite(table)])).astype(np.float32)
+    mids = ((vals[:-1].astype(np.float64) + vals[1:].astype(np.float64)) / 2).astype(np.float32)
+    top = vals[-1]
+    base = np.concatenate([vals, mids, [top * 1.03125, top * 1.0625, top * 2, 3.0e38, 1e-45, 1e-40, 1.17549435e-38]])
+    base = base.astype(np.float32)
+    up = np.nextafter(base, np.float32(np.inf))
+    down = np.nextafter(base, np.float32(0))
+    mag = np.concatenate([base, up, down])
+    return np.concatenate([mag, -mag]).astype(np.float32)
+
+
+@pytest.mark.parametrize("fmt", [B.E5M2, B.E4M3])
+@pytest.mark.parametrize("kind", [B.SRC_F16, B.SRC_F32])
+def test_cast_wide_sources_under_many_scales(fmt, kind):
+    rng = np.random.default_rng(5)
+    if kind == B.SRC_F16:
+        pats = np.arange(65536, dtype=np.uint16)
+        finite = pats[(pats & 0x7C00) != 0x7C00]
+        everything = pats
+        exps = [-126, -60, -24, -15, -14, -9, -8, -3, -1, 0, 1, 2, 7, 8, 9, 15, 16, 17, 24, 25, 40, 126]
+        np_dtype, t_dtype = np.uint16, torch.float16
+    else:
+        special = _interesting_f32(fmt)
+        rnd = rng.integers(0, 1 << 32, size=200000, dtype=np.uint64).astype(np.uint32)
+        everything = np.concatenate([special.view(np.uint32), rnd, np.array([0x7F800000, 0xFF800000, 0x7FC00000, 0xFFFFFFFF], np.uint32)])
+        finite = everything[(everything & 0x7F800000) != 0x7F800000]
+        exps = [-126, -100, -30, -9, -8, -1, 0, 1, 3, 8, 15, 16, 30, 100, 126]
+        np_dtype, t_dtype = np.uint32, torch.float32
+    n_fast = len(exps)
+    numels = [finite.size] * n_fast + [everything.size] * 3
+    lay = synth.Layout([f"t{i}" for i in range(len(numels))], numels)
+    src = np.zeros(lay.total, dtype=np_dtype)
+    for i, (off, n) in enumerate(lay.tensors()):
+        src[off:off + n] = finite if i < n_fast else everything
+    cfg = B.autoscale_cfg()
+    ctx = B.Context(lay.tensors())
+    meta = B.meta_to_numpy(ctx.new_meta(cfg), lay.n_tensors)
+    for i, e in enumerate(exps + [0, -12, 9]):
+        meta["scale"][i] = 2.0 ** e
+        meta["inv_scale"][i] = 2.0 ** -e
+        if i >= n_fast:
+            meta["flags"][i] = B.FLAG_NONFINITE
+    d_src = torch.from_numpy(src.view(np.int16 if kind == B.SRC_F16 else np.int32).copy()).to(DEV).view(t_dtype)
+    o_src = src.view(np.float32) if kind == B.SRC_F32 else src
+    tens = O.tensors_array(lay.tensors())
+    # 1. the cast alone with the scales planted above (fast path and careful path)
+    ref_meta = meta.copy()
+    d_meta = B.meta_from_numpy(meta, DEV)
+    d_dst = torch.zeros(lay.total, dtype=torch.uint8, device=DEV)
+    say(f"wide-source cast sweep fmt={fmt} kind={kind} tensors={lay.n_tensors} elements={lay.total}")
+    ctx.cast_fp8(d_src, d_dst, fmt, d_meta, cfg)
+    torch.cuda.synchronize()
+    ref = np.zeros(lay.total, dtype=np.uint8)
+    O.cast_fp8(o_src, tens, ref, fmt, ref_meta, P.oracle_cfg(cfg), src_type=kind)
+    got = d_dst.cpu().numpy()
+    bad = np.flatnonzero(got != ref)
+    assert bad.size == 0, f"{bad.size} codes differ, first at {bad[:5]}: gpu {got[bad[:5]]} oracle {ref[bad[:5]]} src {src[bad[:5]]}"
+    got_meta = B.meta_to_numpy(d_meta, lay.n_tensors)
+    for t in range(lay.n_tensors):
+        diff = P.meta_equal(got_meta[t], ref_meta[t], P.ALL_FIELDS)
+        assert not diff, (t, diff, got_meta[t], ref_meta[t])
+    # 2. amax + scale + cast, and the delayed single pass, from fresh metadata
+    for delayed in (False, True):
+        ref_meta = B.meta_to_numpy(ctx.new_meta(cfg), lay.n_tensors)
+        d_meta = B.meta_from_numpy(ref_meta, DEV)
+        for rep in range(2):
+            say(f"  delayed={delayed} rep={rep}")
+            if delayed:
+                ctx.cast_fp8_delayed(d_src, d_dst, fmt, d_meta, cfg)
+                O.cast_fp8_delayed(o_src, tens, ref, fmt, ref_meta, P.oracle_cfg(cfg), src_type=kind)
+            else:
+                ctx.amax_scale(d_src, fmt, d_meta, cfg)
+                ctx.cast_fp8(d_src, d_dst, fmt, d_meta, cfg)
+                O.amax_scale(o_src, tens, fmt, ref_meta, P.oracle_cfg(cfg), src_type=kind)
+                O.cast_fp8(o_src, tens, ref, fmt, ref_meta, P.oracle_cfg(cfg), src_type=kind)
+            torch.cuda.synchronize()
+            assert np.array_equal(d_dst.cpu().numpy(), ref)
+            got_meta = B.meta_to_numpy(d_meta, lay.n_tensors)
+            for t in range(lay.n_tensors):
+                diff = P.meta_equal(got_meta[t], ref_meta[t], P.ALL_FIELDS)
+                assert not diff, (delayed, rep, t, diff, got_meta[t], ref_meta[t])
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("grad_fmt", [B.E5M2, B.E4M3])
+def test_whole_path_from_fp16_and_fp32_gradients(dtype, grad_fmt):
+    for wl in (synth.workload("tiny"), synth.Workload("mid", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-3, sigma=None)):
+        st, w0 = P.make_state(wl, 21, grad_fmt, hist_window=2)
+        ids = list(range(wl.layout.n_tensors))
+        grad = torch.zeros(max(wl.layout.total, 16), dtype=dtype, device=DEV)
+        for step in range(1, 7):
+            synth.fill_gradients(grad, wl, 21, step)
+            if step == 4:                                        # inf and NaN in the first tensor
+                off0, n0 = wl.layout.tensors()[0]
+                grad[off0 + 1] = float("inf")
+                grad[off0 + n0 - 1] = float("nan")
+            delayed = step in (3, 4, 6)
+            mode = [B.MSCALE_EXACT_PASS, B.MSCALE_PREDICTED, B.MSCALE_FROM_CAST][step % 3]
+            hp = B.adam_hparams(wl.lr, step, m_scale_mode=mode)
+            snaps = [P.Snapshot(st, grad, t) for t in ids]
+            say(f"{wl.name} dtype={dtype} fmt={grad_fmt} step={step} delayed={delayed} mode={mode}")
+            st.step(grad, hp, delayed=delayed)
+            torch.cuda.synchronize()
+            P.check_step(st, snaps, hp, what=f"{wl.name} {dtype} step {step}", delayed=delayed)
