@@ -280,6 +280,29 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* ctx,
                                  const fp8lm_adam_hparams* hp /*host*/, void* stream);
 
 /*
+ * Quantisation error of an FP8 gradient against a high-precision reference: the three quantities of
+ * the communication ablation (Sec. 3.3, figure comparing pre-, post- and auto-scaling for the FP8
+ * gradient all-reduce).  With r the reference and x = payload / scale the value a scaling tensor
+ * stands for (Sec. 2.1), per tensor:
+ *   signal = sum r^2, noise = sum (r - x)^2 (float64; SNR = 10 log10(signal / noise) is left to the
+ *   caller), n_nonzero = #{r != 0}, n_underflow = #{r != 0, payload = +-0}, n_overflow = #{|payload|
+ *   is the largest finite code}.  Elements whose reference is inf/NaN or whose payload is a NaN/inf
+ *   code are counted in n_nonfinite and in nothing else.
+ * The sums are accumulated in an unspecified order (agree with a sequential sum to about
+ * numel * 2^-52 relative); the counts are exact.
+ *   ref  : device, flat buffer of element type ref_type (read only);
+ *   q    : device, flat uint8 payloads of format fmt;  q_meta : device [n_tensors], only scale is read;
+ *   out  : device [n_tensors], overwritten (entries of empty tensors are zeroed).
+ */
+typedef struct {
+  double signal, noise;
+  uint64_t n_nonzero, n_underflow, n_overflow, n_nonfinite;
+} fp8lm_quant_stats;
+fp8lm_status fp8lm_quant_error_stats(fp8lm_ctx* ctx, const void* ref /*device*/, fp8lm_src ref_type,
+                                     const uint8_t* q /*device*/, fp8lm_fmt fmt, const fp8lm_meta* q_meta /*device*/,
+                                     fp8lm_quant_stats* out /*device*/, void* stream);
+
+/*
  * Host-only helper: the whole-tensor greedy distribution of Sec. 2.3, Alg. 1 (how this path would be
  * sharded over GPUs: a tensor and its scale always stay together).  Tensors are taken in descending
  * order of sizes[i] (equal sizes in index order); each goes to the GPU with the least memory in use
@@ -300,7 +323,7 @@ fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* ctx, const void* src /*device*/, void* 
  * duration in milliseconds since timing was enabled, then resets the sums.                       */
 enum { FP8LM_K_AMAX = 0, FP8LM_K_CAST = 1, FP8LM_K_ADAM_AMAX = 2, FP8LM_K_ADAM_UPDATE = 3,
        FP8LM_K_INIT_MASTER = 4, FP8LM_K_COPY = 5, FP8LM_K_SCALARS = 6 /* per-tensor scalar kernels */,
-       FP8LM_K_REQUANT = 7, FP8LM_K_SUM = 8, FP8LM_K_COUNT = 9 };
+       FP8LM_K_REQUANT = 7, FP8LM_K_SUM = 8, FP8LM_K_STATS = 9, FP8LM_K_COUNT = 10 };
 fp8lm_status fp8lm_set_timing(fp8lm_ctx* ctx, int32_t enable);
 fp8lm_status fp8lm_get_timing(fp8lm_ctx* ctx, int32_t* launches /*host[FP8LM_K_COUNT]*/,
                               double* total_ms /*host[FP8LM_K_COUNT]*/);

@@ -115,6 +115,9 @@ def lib():
             base = getattr(L, name[:-4])
             getattr(L, name).restype = None
             getattr(L, name).argtypes = [C.c_void_p, C.c_int] + list(base.argtypes[1:])
+        L.oracle_quant_error_stats.restype = None
+        L.oracle_quant_error_stats.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
+                                               C.c_int32, C.c_void_p]
         L.oracle_shared_scale.restype = None
         L.oracle_shared_scale.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.oracle_requantize_fp8.restype = None
@@ -180,6 +183,19 @@ def cast_fp8_delayed(src: np.ndarray, tensors: np.ndarray, dst: np.ndarray, fmt:
     assert _src_ok(src, src_type) and dst.dtype == np.uint8
     lib().oracle_cast_fp8_delayed_src(_p(src), src_type, _p(tensors), len(tensors), _p(dst), fmt, _p(meta),
                                       C.byref(cfg))
+
+
+QUANT_STATS_DTYPE = np.dtype([("signal", np.float64), ("noise", np.float64), ("n_nonzero", np.uint64),
+                              ("n_underflow", np.uint64), ("n_overflow", np.uint64), ("n_nonfinite", np.uint64)])
+
+
+def quant_error_stats(ref: np.ndarray, q: np.ndarray, fmt: int, meta: np.ndarray, tensors: np.ndarray,
+                      ref_type: int = SRC_F32) -> np.ndarray:
+    """Per-tensor signal / noise energies and underflow / overflow counts of an FP8 gradient (Sec. 3.3)."""
+    assert _src_ok(ref, ref_type) and q.dtype == np.uint8
+    out = np.zeros(len(tensors), dtype=QUANT_STATS_DTYPE)
+    lib().oracle_quant_error_stats(_p(ref), ref_type, _p(q), fmt, _p(meta), _p(tensors), len(tensors), _p(out))
+    return out
 
 
 def _ptr_array(arrays):

@@ -766,6 +766,52 @@ void oracle_adam_step_fp8(const oracle_tensor* tensors, int32_t n_tensors,
   }
 }
 
+// ---- quantisation error of an FP8 gradient against a high-precision reference -----------------------
+// The quantities of the communication ablation (Sec. 3.3, the figure comparing pre-scaling,
+// post-scaling and auto-scaling): per tensor, the signal-to-noise ratio of the FP8 gradient, the share
+// of its entries that underflowed and the share that sits on the largest finite code.  The paper does
+// not define them; the reading taken is the textbook one.  With r_i the reference and
+// x_i = payload_i / scale the value the scaling tensor stands for (Sec. 2.1):
+//   signal = sum r_i^2,  noise = sum (r_i - x_i)^2   (SNR = 10 log10(signal / noise), left to the caller),
+//   n_nonzero = #{r_i != 0},  n_underflow = #{r_i != 0 and payload_i = +-0},
+//   n_overflow = #{|payload_i| is the largest finite code}.
+// Entries whose reference is inf/NaN or whose payload is a NaN/inf code are counted in n_nonfinite
+// and take part in nothing else.  Sums are float64; x_i = double(payload_i) * (1.0 / double(scale)).
+typedef struct {
+  double signal, noise;
+  uint64_t n_nonzero, n_underflow, n_overflow, n_nonfinite;
+} oracle_quant_stats;
+
+void oracle_quant_error_stats(const void* ref, int ref_type, const uint8_t* q, int fmt, const oracle_meta* meta,
+                              const oracle_tensor* tensors, int32_t n_tensors, oracle_quant_stats* out) {
+  const uint32_t top = maxcode_fp8(fmt);
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    oracle_quant_stats S{};
+    const int64_t off = tensors[t].offset;
+    const double rs = 1.0 / double(meta[t].scale);
+    for (int64_t i = 0; i < tensors[t].numel; ++i) {
+      const float r = src_value(ref, ref_type, off + i);
+      const uint8_t c = q[off + i];
+      const float p = dec_fp8(fmt, c);
+      if (!(std::fabs(r) <= std::numeric_limits<float>::max()) || !(std::fabs(p) <= std::numeric_limits<float>::max())) {
+        ++S.n_nonfinite;
+        continue;
+      }
+      const double x = double(p) * rs;
+      const double e = double(r) - x;
+      S.signal += double(r) * double(r);
+      S.noise += e * e;
+      const uint32_t mag = c & 0x7Fu;
+      if (r != 0.0f) {
+        ++S.n_nonzero;
+        if (mag == 0) ++S.n_underflow;
+      }
+      if (mag == top) ++S.n_overflow;
+    }
+    out[t] = S;
+  }
+}
+
 // ---- whole-tensor greedy distribution (Sec. 2.3, Alg. 1) -----------------------------------------
 // Tensors are visited in descending order of size (equal sizes in their original order); each goes
 // to the GPU with the least memory in use so far (the lowest-numbered one among equals).

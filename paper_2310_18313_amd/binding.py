@@ -25,15 +25,26 @@ MSCALE_EXACT_PASS, MSCALE_PREDICTED, MSCALE_FROM_CAST = 0, 1, 2
 STATE_F16, STATE_BF16, STATE_E4M3, STATE_F32 = 0, 1, 2, 3
 STATE_BYTES = {STATE_F16: 2, STATE_BF16: 2, STATE_E4M3: 1, STATE_F32: 4}
 FLAG_NONFINITE, FLAG_AMAX_ZERO, FLAG_SCALE_CLAMPED, FLAG_SATURATED = 1, 2, 4, 8
-K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_REQUANT, K_SUM, K_COUNT = range(10)
-KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars", "requantize", "sum"]
+K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_REQUANT, K_SUM, K_STATS, K_COUNT = range(11)
+KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars", "requantize", "sum", "quant_stats"]
 
 EXPORTS = [
     "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_meta_init", "fp8lm_amax_scale",
     "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_cast_fp8_for_adam", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
+    "fp8lm_quant_error_stats",
     "fp8lm_init_master", "fp8lm_init_master_as", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
+
+
+QUANT_STATS_DTYPE = np.dtype([("signal", "<f8"), ("noise", "<f8"), ("n_nonzero", "<u8"), ("n_underflow", "<u8"),
+                              ("n_overflow", "<u8"), ("n_nonfinite", "<u8")])
+
+
+def snr_db(stats: np.ndarray) -> np.ndarray:
+    """10 log10(signal / noise) per tensor; +inf where nothing was lost, NaN for an all-zero reference."""
+    with np.errstate(divide="ignore", invalid="ignore"):
+        return 10.0 * np.log10(stats["signal"] / stats["noise"])
 
 
 class Tensor(C.Structure):
@@ -113,6 +124,7 @@ def lib() -> C.CDLL:
         L.fp8lm_shared_scale.argtypes = [vp, vp, i32, vp, vp]
         L.fp8lm_requantize_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp]
         L.fp8lm_sum_fp8.argtypes = [vp, vp, i32, C.c_int, vp, vp, vp, vp, vp]
+        L.fp8lm_quant_error_stats.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
         L.fp8lm_adam_step_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fp8lm_copy_bytes.argtypes = [vp, vp, vp, i64, vp]
         L.fp8lm_greedy_partition.argtypes = [vp, i32, i32, vp, vp]
@@ -260,6 +272,19 @@ class Context:
         ptrs = (C.c_void_p * len(payloads))(*[_ptr(p) for p in payloads])
         _check(lib().fp8lm_sum_fp8(self._h, C.cast(ptrs, C.c_void_p), len(payloads), fmt, _ptr(shared), _ptr(dst),
                                    _ptr(dst_meta), C.addressof(cfg), _stream(stream)), "fp8lm_sum_fp8")
+
+    def quant_error_stats(self, ref, q, fmt, q_meta, stream=None) -> np.ndarray:
+        """Per-tensor signal and noise energies and underflow / overflow counts of the FP8 tensor `q` against the
+        high-precision reference `ref` (Sec. 3.3, communication ablation).  Synchronises and returns a host array
+        of QUANT_STATS_DTYPE; `snr_db(stats)` turns the energies into decibels."""
+        assert q.element_size() == 1
+        self._fits(ref, q)
+        self._fits_meta(q_meta)
+        out = torch.empty((max(1, self.n_tensors), QUANT_STATS_DTYPE.itemsize), dtype=torch.uint8,
+                          device=f"cuda:{self.device}")
+        _check(lib().fp8lm_quant_error_stats(self._h, _ptr(ref), src_type_of(ref), _ptr(q), fmt, _ptr(q_meta), _ptr(out),
+                                             _stream(stream)), "fp8lm_quant_error_stats")
+        return out.cpu().numpy().view(QUANT_STATS_DTYPE).reshape(-1)[:self.n_tensors].copy()
 
     def init_master(self, w_bf16, w_out, w_meta, master_fmt=STATE_F16, stream=None):
         assert w_bf16.element_size() == 2 and w_out.element_size() == STATE_BYTES[master_fmt]

@@ -459,3 +459,75 @@ def test_wide_sources_flag_nonfinite_values(kind, bad):
     O.cast_fp8(src, tens, q, O.E5M2, meta, cfg, src_type=kind)
     is_nan = (kind == O.SRC_F16 and bad == 0x7E01) or (kind == O.SRC_F32 and bad != bad)
     assert q[7] == (0x7F if is_nan else 0x7B) and q[8] == 0x3C
+
+
+# ---- quantisation-error statistics (Sec. 3.3, communication ablation) -------------------------------------
+def test_quant_error_stats_closed_forms():
+    """Inputs whose error is known exactly: values on the FP8 grid (no noise), values a fixed quarter step above
+    the grid (noise = n * (step/4)^2), tiny values (underflow), clipped values (overflow), a NaN."""
+    fmt, s = O.E4M3, 4.0
+    cfg = O.default_cfg()
+    n = 64
+    tens = O.tensors_array([(0, n), (64, n), (128, n), (192, n)])
+    meta = O.new_meta(4, cfg)
+    meta["scale"][:] = s
+    meta["inv_scale"][:] = 1 / s
+    ref = np.zeros(256, dtype=np.float32)
+    grid = (16 + 2 * (np.arange(n) % 4)) / s                # payloads 16, 18, 20, 22: E4M3 values (step 2 in [16, 32))
+    ref[0:64] = grid
+    ref[64:128] = grid + np.float32(0.5 / s)                # a quarter of the step (2) above the grid, scaled back
+    ref[128:192] = np.float32(2.0 ** -12)                   # payload 2^-10: half the smallest subnormal -> ties to zero
+    ref[128] = 0.0
+    ref[192:256] = 1000.0                                   # payload 4000 clips to 448
+    ref[200] = np.nan
+    q = np.zeros(256, dtype=np.uint8)
+    m2 = meta.copy()
+    O.cast_fp8(ref, tens, q, fmt, m2, cfg, src_type=O.SRC_F32)
+    st = O.quant_error_stats(ref, q, fmt, meta, tens)
+    assert st[0]["noise"] == 0 and st[0]["signal"] == np.sum(grid.astype(np.float64) ** 2)
+    assert st[0]["n_underflow"] == 0 and st[0]["n_overflow"] == 0 and st[0]["n_nonzero"] == n
+    assert st[1]["noise"] == n * (0.5 / s) ** 2                                   # exact in binary
+    assert st[1]["signal"] == np.sum((grid.astype(np.float64) + 0.5 / s) ** 2)
+    assert st[2]["n_underflow"] == n - 1 and st[2]["n_nonzero"] == n - 1 and st[2]["n_overflow"] == 0
+    assert st[2]["noise"] == st[2]["signal"] == (n - 1) * 2.0 ** -24               # everything was lost
+    assert st[3]["n_overflow"] == n - 1 and st[3]["n_nonfinite"] == 1
+    assert st[3]["noise"] == (n - 1) * (1000.0 - 448.0 / s) ** 2
+    snr_db = 10 * np.log10(st[1]["signal"] / st[1]["noise"])
+    assert 30 < snr_db < 40                                                        # about 2^-5.5 relative error
+
+
+@pytest.mark.parametrize("fmt", [O.E5M2, O.E4M3])
+@pytest.mark.parametrize("kind", [O.SRC_BF16, O.SRC_F32])
+def test_quant_error_stats_uniform_noise_model(fmt, kind):
+    """Textbook: rounding to a grid of step D leaves an error uniform in [-D/2, D/2], energy D^2/12 per element,
+    when the inputs are spread smoothly over many steps.  One binade, fp32 reference."""
+    rng = np.random.default_rng(3)
+    n = 200000
+    lay = synth.flat_layout(n)
+    tens = O.tensors_array(lay.tensors())
+    ref = np.zeros(lay.total, dtype=np.float32)
+    ref[:n] = rng.uniform(1.0, 2.0, n) * rng.choice([-1.0, 1.0], n)
+    ref[0] = 2.0                                             # fixes the amax, so the scale is known
+    if kind == O.SRC_BF16:
+        src = bf16_bits(ref)
+        ref = bf16_vals(src)
+    else:
+        src = ref
+    cfg = O.default_cfg()
+    meta = O.new_meta(1, cfg)
+    q = np.zeros(lay.total, dtype=np.uint8)
+    O.amax_scale(src, tens, fmt, meta, cfg, src_type=kind)
+    O.cast_fp8(src, tens, q, fmt, meta, cfg, src_type=kind)
+    st = O.quant_error_stats(src, q, fmt, meta, tens, ref_type=kind)[0]
+    step = 2.0 ** -(2 if fmt == O.E5M2 else 3)               # spacing of the format inside [1, 2)
+    if kind == O.SRC_F32:
+        assert abs(st["noise"] / (n - 1) / (step ** 2 / 12) - 1) < 0.02
+    else:
+        # bf16 inputs lie on a grid of 2^-7 themselves: the error is uniform over the multiples of 2^-7 in a step
+        k = int(step / 2.0 ** -7)
+        offs = (np.arange(k) - k // 2) * 2.0 ** -7           # -D/2 .. D/2 - 2^-7; the tie at -D/2 rounds either way
+        assert abs(st["noise"] / (n - 1) / np.mean(offs ** 2) - 1) < 0.03
+    assert st["signal"] == pytest.approx(np.sum(ref[:n].astype(np.float64) ** 2), rel=1e-10)   # summation order
+    assert st["n_underflow"] == 0 and st["n_nonzero"] == n and st["n_nonfinite"] == 0
+    d = dec8(fmt, q[:n]).astype(np.float64) / float(meta[0]["scale"])
+    assert st["noise"] == pytest.approx(np.sum((ref[:n].astype(np.float64) - d) ** 2), rel=1e-10)
