@@ -51,7 +51,7 @@ def cpu_baseline(wl, seed: int, budget_s: float = 20.0) -> dict:
         return synth.Workload("sample", synth.Layout(names, numels), wl.lr, wl.grad_kind, wl.sigma,
                               ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
 
-    def run(sample_wl):
+    def run(sample_wl, cores=cores):
         lay = sample_wl.layout
         # deal tensors to threads, largest first, so every thread gets a similar share
         order = sorted(range(lay.n_tensors), key=lambda t: -lay.numels[t])
@@ -95,9 +95,12 @@ def cpu_baseline(wl, seed: int, budget_s: float = 20.0) -> dict:
     sample = sample_of(int(min(max(n / dt * budget_s, 1_000_000), 2e9)))
     dt, n, used = run(sample)
     lay = sample.layout
+    one_wl = sample_of(int(min(max(n / dt / used * 4.0, 1_000_000), 2e8)))     # about 4 s on one thread
+    dt1, n1, _ = run(one_wl, cores=1)
     return {"value": n / dt, "unit": "params/s", "cores": used, "kind": "oracle",
             "sample": f"first {lay.n_tensors} tensors of {wl.name}, each cut to at most {max(lay.numels)} elements "
-                      f"({n} params), one step in {dt:.1f} s"}
+                      f"({n} params), one step in {dt:.1f} s",
+            "single_thread": {"value": n1 / dt1, "unit": "params/s", "sample": f"{n1} params in {dt1:.1f} s"}}
 
 
 def measured_traffic(workload: str):

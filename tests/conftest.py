@@ -8,8 +8,23 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+_capture = None
+
+
 def pytest_configure(config):
+    global _capture
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    _capture = config.pluginmanager.getplugin("capturemanager")
+
+
+def say(msg: str) -> None:
+    """Progress line of a GPU test, printed past pytest's capture: it names the case before every GPU step, so a
+    run that dies says where, and a long test is never silent."""
+    if _capture is not None:
+        with _capture.global_and_fixture_disabled():
+            print(msg, flush=True)
+    else:
+        print(msg, flush=True)
 
 
 def pytest_collection_modifyitems(config, items):

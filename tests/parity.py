@@ -229,3 +229,59 @@ def check_init_master(st, w0: torch.Tensor, ids) -> None:
         if n:
             bad = meta_equal(gpu_meta[t], meta[0], ALL_FIELDS)
             assert not bad, f"init_master: tensor {t} meta differs in {bad}: {gpu_meta[t]} vs {meta[0]}"
+
+
+class FreeRunningOracle:
+    """The oracle stepping a whole model on its own state: it sees the same seeded gradients and initial weights
+    as the GPU and nothing else, so after k steps any divergence of the two paths has had k steps to grow."""
+
+    def __init__(self, layout: synth.Layout, cfg: B.AutoscaleCfg, w0_bits: np.ndarray, grad_fmt=B.E5M2,
+                 wcopy=B.WCOPY_E4M3, threads: int = 8):
+        from concurrent.futures import ThreadPoolExecutor
+        self.layout, self.cfg, self.grad_fmt, self.wcopy = layout, oracle_cfg(cfg), grad_fmt, wcopy
+        total = max(layout.total, ALIGN)
+        self.g8, self.m = np.zeros(total, np.uint8), np.zeros(total, np.uint8)
+        self.v, self.w = np.zeros(total, np.uint16), np.zeros(total, np.uint16)
+        self.wq = np.zeros(total, np.uint8 if wcopy == B.WCOPY_E4M3 else np.uint16)
+        # tensors dealt to threads, largest first; every thread owns the metadata of its tensors
+        order = sorted(range(layout.n_tensors), key=lambda t: -layout.numels[t])
+        shares = [[] for _ in range(threads)]
+        loads = [0] * threads
+        for t in order:
+            k = loads.index(min(loads))
+            shares[k].append(t)
+            loads[k] += layout.numels[t]
+        self.jobs = []
+        for ids in (s for s in shares if s):
+            tens = O.tensors_array([layout.tensors()[t] for t in ids])
+            metas = {k: O.new_meta(len(ids), self.cfg) for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta")}
+            O.init_master(w0_bits, tens, self.w, metas["w_meta"])
+            self.jobs.append((ids, tens, metas))
+        self.pool = ThreadPoolExecutor(len(self.jobs))
+
+    def step(self, grad_bits: np.ndarray, hp: B.AdamHparams) -> None:
+        ohp = oracle_hp(hp)
+
+        def one(job):
+            _, tens, M = job
+            O.amax_scale(grad_bits, tens, self.grad_fmt, M["g_meta"], self.cfg)
+            O.cast_fp8(grad_bits, tens, self.g8, self.grad_fmt, M["g_meta"], self.cfg)
+            O.adam_step_fp8(tens, self.g8, self.grad_fmt, M["g_meta"], self.m, M["m_meta"], self.v, M["v_meta"],
+                            self.w, M["w_meta"], self.wq, M["q_meta"], ohp)
+
+        list(self.pool.map(one, self.jobs))
+
+    def assert_equal_to(self, st, what: str) -> None:
+        n_tensors = self.layout.n_tensors
+        gpu_meta = {k: B.meta_to_numpy(getattr(st, k), n_tensors) for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta")}
+        for ids, _, M in self.jobs:
+            for j, t in enumerate(ids):
+                off, n = self.layout.tensors()[t]
+                for name, ref in (("g8", self.g8), ("m", self.m), ("v", self.v), ("w", self.w), ("wq", self.wq)):
+                    got = _host_bits(getattr(st, name), off, n)
+                    assert np.array_equal(got, ref[off:off + n]), f"{what}: {name} of tensor {t} differs"
+                if n:
+                    for k in gpu_meta:
+                        fields = ALL_FIELDS if k == "g_meta" else ["scale", "inv_scale", "amax", "amax_deq", "flags"]
+                        bad = meta_equal(gpu_meta[k][t], M[k][j], fields)
+                        assert not bad, f"{what}: {k} of tensor {t} differs in {bad}"

@@ -10,6 +10,7 @@ import pytest
 import torch
 
 import parity as P
+from conftest import say
 from paper_2310_18313_amd import binding as B
 from paper_2310_18313_amd import synth
 from paper_2310_18313_amd.state import OptimizerState
@@ -17,10 +18,6 @@ from paper_2310_18313_amd.state import OptimizerState
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 SMALL = 1 << 20
-
-
-def say(msg):
-    print(msg, flush=True)
 
 
 def sample_ids(layout):
@@ -37,7 +34,7 @@ def sample_ids(layout):
     return small, sorted(big)
 
 
-def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False):
+def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False, paths=None):
     lay = wl.layout
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
     st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=True, grad_buffer=True)
@@ -55,14 +52,16 @@ def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False):
     mus = []
     for step in range(1, steps + 1):
         synth.fill_gradients(grad, wl, seed, step)
-        hp = B.adam_hparams(wl.lr, step)
+        mode, delayed = (paths or {}).get(step, (B.MSCALE_EXACT_PASS, False))
+        hp = B.adam_hparams(wl.lr, step, m_scale_mode=mode)
         ids = (small if step in small_steps else []) + (big if step in big_steps else [])
         snaps = [P.Snapshot(st, grad, t) for t in ids]
-        st.step(grad, hp)
+        st.step(grad, hp, delayed=delayed)
         torch.cuda.synchronize()
         if ids:
-            say(f"{wl.name} step {step}: checking {len(ids)} tensors, {sum(lay.numels[t] for t in ids)} elements")
-            r = P.check_step(st, snaps, hp, what=f"{wl.name} step {step}")
+            say(f"{wl.name} step {step} (moment-scale mode {mode}, delayed {delayed}): checking {len(ids)} tensors, "
+                f"{sum(lay.numels[t] for t in ids)} elements")
+            r = P.check_step(st, snaps, hp, what=f"{wl.name} step {step}", delayed=delayed)
             for k in tot:
                 tot[k] = max(tot[k], r[k]) if k == "w_amax_ulp" else tot[k] + r[k]
         if track_mu:
@@ -83,7 +82,10 @@ def test_gpt13b_in_the_benchmark_configuration():
 def test_gpt7b_five_steps_with_amax_history():
     wl = synth.workload("gpt7b")
     assert wl.hist_window == 4
-    run(wl, seed=2, steps=5, small_steps={1, 2, 3, 4, 5}, big_steps={1, 5})
+    # steps 1-2 on the two-pass path, then the one-GPU fused cast, then the single-pass path (delayed gradient
+    # scale + predicted moment scale): the three paths bench.py times, at full size and default tuning
+    paths = {3: (B.MSCALE_FROM_CAST, False), 4: (B.MSCALE_PREDICTED, True), 5: (B.MSCALE_FROM_CAST, True)}
+    run(wl, seed=2, steps=5, small_steps={1, 2, 3, 4, 5}, big_steps={1, 3, 4, 5}, paths=paths)
 
 
 def test_gpt175b_layer_heavy_tails_hundred_steps():

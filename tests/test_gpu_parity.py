@@ -7,16 +7,13 @@ import torch
 
 import oracle as O
 import parity as P
+from conftest import say
 from paper_2310_18313_amd import binding as B
 from paper_2310_18313_amd import synth
 from paper_2310_18313_amd.state import OptimizerState
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-
-
-def say(msg):
-    print(msg, flush=True)
 
 
 def bf16_tensor_from_bits(bits: np.ndarray) -> torch.Tensor:
@@ -158,6 +155,23 @@ def test_config2_gpt125m_ten_steps():
     _, tot = run_lockstep(wl, seed=1, steps=10, check_steps={1, 2, 5, 10})
     assert tot["m_diff"] == 0
     assert tot["w_diff"] <= 0.01 * tot["elements"]
+
+
+@pytest.mark.parametrize("name,steps", [("flat1m", 3), ("gpt125m", 10)])
+def test_free_running_oracle_and_gpu_end_in_the_same_state(name, steps):
+    """Both sides start from the same seeded weights, see the same seeded gradients and never exchange state."""
+    wl = synth.workload(name)
+    st, w0 = P.make_state(wl, seed=4)
+    fr = P.FreeRunningOracle(wl.layout, st.cfg, synth.bits16(w0), threads=16)
+    grad = torch.zeros(max(wl.layout.total, 16), dtype=torch.bfloat16, device=DEV)
+    for step in range(1, steps + 1):
+        synth.fill_gradients(grad, wl, 4, step)
+        hp = B.adam_hparams(wl.lr, step)
+        say(f"free-running {name} step {step}")
+        st.step(grad, hp)
+        fr.step(synth.bits16(grad), hp)
+    torch.cuda.synchronize()
+    fr.assert_equal_to(st, f"{name} after {steps} free-running steps")
 
 
 @pytest.mark.parametrize("tuning", [(4096, 1, 0), (4096, 16, 1), (65536, 4, 1), (1048576, 2, 0)])
