@@ -205,6 +205,13 @@ __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
 #ifndef FP8LM_UN_UPDATE
 #define FP8LM_UN_UPDATE 1
 #endif
+#ifndef FP8LM_CAST_SPLIT
+#define FP8LM_CAST_SPLIT 1     // cast kernel, 16-bit sources: the same split layout as the update kernel
+#endif
+#ifndef FP8LM_UPDATE_SPLIT
+#define FP8LM_UPDATE_SPLIT 1   // update kernel: a thread takes elements [8L, 8L+8) of both halves of a tile, so
+                               // that every access of the workgroup is contiguous (0: 16 consecutive elements)
+#endif
 constexpr bool kNtLoadRO = (FP8LM_NT_MASK & 1) != 0, kNtStoreWO = (FP8LM_NT_MASK & 2) != 0;
 constexpr bool kNtLoadRW = (FP8LM_NT_MASK & 4) != 0, kNtStoreRW = (FP8LM_NT_MASK & 8) != 0;
 
@@ -223,6 +230,24 @@ template <bool NT = false> __device__ __forceinline__ void st16(void* p, uint4 v
     __builtin_nontemporal_store(r, reinterpret_cast<u32x4_t*>(p));
   } else {
     *reinterpret_cast<uint4*>(p) = v;
+  }
+}
+
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+template <bool NT = false> __device__ __forceinline__ uint2 ld8(const void* p) {
+  if constexpr (NT) {
+    const u32x2_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+    return make_uint2(r.x, r.y);
+  } else {
+    return *reinterpret_cast<const uint2*>(p);
+  }
+}
+template <bool NT = false> __device__ __forceinline__ void st8(void* p, uint2 v) {
+  if constexpr (NT) {
+    const u32x2_t r = {v.x, v.y};
+    __builtin_nontemporal_store(r, reinterpret_cast<u32x2_t*>(p));
+  } else {
+    *reinterpret_cast<uint2*>(p) = v;
   }
 }
 
@@ -523,15 +548,33 @@ struct CastOp {
   }
   __device__ __forceinline__ bool fast() const { return !careful; }
   template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
+    // kSplit: the thread's 16 elements are [8L, 8L+8) of each half of the tile (every 128-bit load contiguous
+    // over the workgroup, 64-bit stores); otherwise 16 consecutive elements.
+    constexpr bool kSplit = FP8LM_CAST_SPLIT && kSrc16<SRC>;
     uint4 r[UN][kLoads], mm[UN];
-    const long long pos = pos0 + threadIdx.x * kGroup;
+    const long long pos = pos0 + threadIdx.x * (kSplit ? 8 : kGroup);
     const elem_t* q = static_cast<const elem_t*>(p.src) + pos;
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
 #pragma unroll
-      for (int k = 0; k < kLoads; ++k) r[u][k] = ld16<kNtLoadRO>(q + u * kTile + k * kPer);
-      if constexpr (FUSE) mm[u] = ld16<kNtLoadRO>(p.m + pos + u * kTile);
+      for (int k = 0; k < kLoads; ++k) r[u][k] = ld16<kNtLoadRO>(q + u * kTile + k * (kSplit ? kTile / 2 : kPer));
+      if constexpr (FUSE) {
+        if constexpr (kSplit) {
+          const uint2 lo = ld8<kNtLoadRO>(p.m + pos + u * kTile), hi = ld8<kNtLoadRO>(p.m + pos + u * kTile + kTile / 2);
+          mm[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        } else {
+          mm[u] = ld16<kNtLoadRO>(p.m + pos + u * kTile);
+        }
+      }
     }
+    auto store = [&](int u, const uint4& o) {
+      if constexpr (kSplit) {
+        st8<kNtStoreWO>(p.dst + pos + u * kTile, make_uint2(o.x, o.y));
+        st8<kNtStoreWO>(p.dst + pos + u * kTile + kTile / 2, make_uint2(o.z, o.w));
+      } else {
+        st16<kNtStoreWO>(p.dst + pos + u * kTile, o);
+      }
+    };
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       uint32_t w[kW];
@@ -551,7 +594,7 @@ struct CastOp {
             ow[j >> 2] |= one(bits, FUSE ? (mw[j >> 2] >> ((j & 3) * 8)) & 0xFFu : 0u) << ((j & 3) * 8);
           }
           amax16 = keep;
-          st16<kNtStoreWO>(p.dst + pos + u * kTile, o);
+          store(u, o);
           continue;
         }
       }
@@ -566,7 +609,7 @@ struct CastOp {
         moment_word(o.z, mm[u].z);
         moment_word(o.w, mm[u].w);
       }
-      st16<kNtStoreWO>(p.dst + pos + u * kTile, o);
+      store(u, o);
     }
     n_elems += UN * kGroup;
   }
@@ -1246,7 +1289,56 @@ struct AdamUpdateOp {
   }
 
   __device__ __forceinline__ bool fast() const { return !careful; }
+  // Split layout: the 16-bit streams are walked with 128-bit accesses that are contiguous over the whole
+  // workgroup (4 KiB per instruction) instead of pairs of adjacent ones; the 8-bit streams then take
+  // 64-bit accesses.  Measured 1.6 % faster in a memory-only skeleton of this kernel.
+  template <int UN> __device__ __forceinline__ void tiles_split(long long tile0) {
+    uint2 ga[UN], gb[UN], ma[UN], mb[UN];
+    uint4 va[UN], vb[UN], wa[UN], wb[UN];
+    const long long pos0 = tile0 + threadIdx.x * 8;
+    uint16_t* pv = static_cast<uint16_t*>(p.v);
+    uint16_t* pw = static_cast<uint16_t*>(p.w);
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const long long a = pos0 + u * kTile, b = a + kTile / 2;
+      ga[u] = ld8<kNtLoadRO>(p.grad + a);
+      gb[u] = ld8<kNtLoadRO>(p.grad + b);
+      ma[u] = ld8<kNtLoadRW>(p.m + a);
+      mb[u] = ld8<kNtLoadRW>(p.m + b);
+      va[u] = ld16<kNtLoadRW>(pv + a);
+      vb[u] = ld16<kNtLoadRW>(pv + b);
+      wa[u] = ld16<kNtLoadRW>(pw + a);
+      wb[u] = ld16<kNtLoadRW>(pw + b);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const long long a = pos0 + u * kTile, b = a + kTile / 2;
+      const Quad q0 = quad(ga[u].x, ma[u].x, va[u].x, va[u].y, wa[u].x, wa[u].y);
+      const Quad q1 = quad(ga[u].y, ma[u].y, va[u].z, va[u].w, wa[u].z, wa[u].w);
+      const Quad q2 = quad(gb[u].x, mb[u].x, vb[u].x, vb[u].y, wb[u].x, wb[u].y);
+      const Quad q3 = quad(gb[u].y, mb[u].y, vb[u].z, vb[u].w, wb[u].z, wb[u].w);
+      st8<kNtStoreRW>(p.m + a, make_uint2(q0.m, q1.m));
+      st8<kNtStoreRW>(p.m + b, make_uint2(q2.m, q3.m));
+      st16<kNtStoreRW>(pv + a, make_uint4(q0.v01, q0.v23, q1.v01, q1.v23));
+      st16<kNtStoreRW>(pv + b, make_uint4(q2.v01, q2.v23, q3.v01, q3.v23));
+      st16<kNtStoreRW>(pw + a, make_uint4(q0.w01, q0.w23, q1.w01, q1.w23));
+      st16<kNtStoreRW>(pw + b, make_uint4(q2.w01, q2.w23, q3.w01, q3.w23));
+      if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
+        uint8_t* q = static_cast<uint8_t*>(p.wcopy);
+        st8<kNtStoreWO>(q + a, make_uint2(q0.q, q1.q));
+        st8<kNtStoreWO>(q + b, make_uint2(q2.q, q3.q));
+      } else {
+        uint16_t* q = static_cast<uint16_t*>(p.wcopy);
+        st16<kNtStoreWO>(q + a, make_uint4(q0.q, q0.q2, q1.q, q1.q2));
+        st16<kNtStoreWO>(q + b, make_uint4(q2.q, q2.q2, q3.q, q3.q2));
+      }
+    }
+  }
   template <int UN> __device__ __forceinline__ void tiles(long long tile0) {
+    if constexpr (FP8LM_UPDATE_SPLIT) {
+      tiles_split<UN>(tile0);
+      return;
+    }
     uint4 g[UN], m[UN], va[UN], vb[UN], wa[UN], wb[UN];
     const long long pos0 = tile0 + threadIdx.x * kGroup;
     uint16_t* pv = static_cast<uint16_t*>(p.v);
