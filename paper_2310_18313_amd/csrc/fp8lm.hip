@@ -804,14 +804,18 @@ struct SumParams {
 
 // Eq. 6 on one GPU: the payloads of all ranks (same shared scale) are added in rank order in fp32 and
 // rounded once to FP8, saturating; the result carries the scale N * s_g.
-template <int FMT>
+template <int FMT, int NR>
 struct SumOp {
   const SumParams& p;
   const Tables& tb;
   float vmax;
-  uint32_t amax_bits, n_elems, n_top, n_und;
+  uint32_t amax_bits, n_elems, n_top, n_und;   // n_top / n_und: counted element by element (tails, NaN groups)
+  uint32_t n_fast, nz_top, nz_code, z_acc;     // whole groups: counted on the packed codes, as in the cast
   __device__ SumOp(const SumParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
-  __device__ __forceinline__ void begin(int, const TensorDesc&) { vmax = 0.0f; amax_bits = n_elems = n_top = n_und = 0; }
+  __device__ __forceinline__ void begin(int, const TensorDesc&) {
+    vmax = 0.0f;
+    amax_bits = n_elems = n_top = n_und = n_fast = nz_top = nz_code = z_acc = 0;
+  }
   __device__ __forceinline__ bool fast() const { return true; }
   __device__ __forceinline__ uint32_t finish_one(float acc) {
     const uint32_t c = encode1_fp8_careful<FMT>(acc);
@@ -821,34 +825,66 @@ struct SumOp {
     n_und += (acc != 0.0f) && ((c & 0x7Fu) == 0);
     return c;
   }
+  // four sums without a NaN among them: clamp, convert in pairs, count on the packed codes
+  __device__ __forceinline__ uint32_t finish_quad(const float* acc) {
+    const float y0 = clamp_fp8<FMT>(acc[0]), y1 = clamp_fp8<FMT>(acc[1]);
+    const float y2 = clamp_fp8<FMT>(acc[2]), y3 = clamp_fp8<FMT>(acc[3]);
+    vmax = fmaxf(fmaxf(vmax, fmaxf(fabsf(y0), fabsf(y1))), fmaxf(fabsf(y2), fabsf(y3)));
+    amax_bits = max(max(amax_bits, max(f2u(acc[0]) & 0x7FFFFFFFu, f2u(acc[1]) & 0x7FFFFFFFu)),
+                    max(f2u(acc[2]) & 0x7FFFFFFFu, f2u(acc[3]) & 0x7FFFFFFFu));
+    z_acc += (acc[0] == 0.0f) + (acc[1] == 0.0f) + (acc[2] == 0.0f) + (acc[3] == 0.0f);
+    uint32_t c = f32x2_to_fp8<FMT, false>(y0, y1, 0u);
+    c = f32x2_to_fp8<FMT, true>(y2, y3, c);
+    const uint32_t mag = c & 0x7F7F7F7Fu;
+    nz_code += nonzero_bytes7(mag);
+    nz_top += nonzero_bytes7(mag ^ Fp8Traits<FMT>::kTopX4);
+    return c;
+  }
   template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
-    static_assert(UN == 1, "one group at a time");
     const long long pos = pos0 + threadIdx.x * kGroup;
-    float acc[kGroup];
+    uint4 a[UN][NR];
 #pragma unroll
-    for (int j = 0; j < kGroup; ++j) acc[j] = 0.0f;
-    for (int r = 0; r < p.in.n_ranks; ++r) {
-      const uint4 a = ld16<kNtLoadRO>(p.in.p[r] + pos);
-      const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+    for (int u = 0; u < UN; ++u)
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const float2_t lo = fp8x2_to_f32<FMT, false>(w[k]), hi = fp8x2_to_f32<FMT, true>(w[k]);
-        acc[4 * k + 0] = acc[4 * k + 0] + lo.x;
-        acc[4 * k + 1] = acc[4 * k + 1] + lo.y;
-        acc[4 * k + 2] = acc[4 * k + 2] + hi.x;
-        acc[4 * k + 3] = acc[4 * k + 3] + hi.y;
+      for (int r = 0; r < NR; ++r) a[u][r] = ld16<kNtLoadRO>(p.in.p[r] + pos + u * kTile);
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      float acc[kGroup];
+#pragma unroll
+      for (int j = 0; j < kGroup; ++j) acc[j] = 0.0f;
+#pragma unroll
+      for (int r = 0; r < NR; ++r) {            // rank order, one fp32 addition per rank
+        const uint32_t w[4] = {a[u][r].x, a[u][r].y, a[u][r].z, a[u][r].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float2_t lo = fp8x2_to_f32<FMT, false>(w[k]), hi = fp8x2_to_f32<FMT, true>(w[k]);
+          acc[4 * k + 0] = acc[4 * k + 0] + lo.x;
+          acc[4 * k + 1] = acc[4 * k + 1] + lo.y;
+          acc[4 * k + 2] = acc[4 * k + 2] + hi.x;
+          acc[4 * k + 3] = acc[4 * k + 3] + hi.y;
+        }
       }
-    }
-    uint32_t o[4] = {0, 0, 0, 0};
+      bool any_nan = false;
 #pragma unroll
-    for (int j = 0; j < kGroup; ++j) o[j >> 2] |= finish_one(acc[j]) << ((j & 3) * 8);
-    st16<kNtStoreWO>(p.dst + pos, make_uint4(o[0], o[1], o[2], o[3]));
-    n_elems += kGroup;
+      for (int j = 0; j < kGroup; ++j) any_nan |= acc[j] != acc[j];
+      uint32_t o[4] = {0, 0, 0, 0};
+      if (!any_nan) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = finish_quad(acc + 4 * k);
+        n_fast += kGroup;
+      } else {
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) o[j >> 2] |= finish_one(acc[j]) << ((j & 3) * 8);
+      }
+      st16<kNtStoreWO>(p.dst + pos + u * kTile, make_uint4(o[0], o[1], o[2], o[3]));
+    }
+    n_elems += UN * kGroup;
   }
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) {
       float acc = 0.0f;
-      for (int r = 0; r < p.in.n_ranks; ++r) acc = acc + fp8_to_f32<FMT>(p.in.p[r][pos + j]);
+#pragma unroll
+      for (int r = 0; r < NR; ++r) acc = acc + fp8_to_f32<FMT>(p.in.p[r][pos + j]);
       p.dst[pos + j] = (uint8_t)finish_one(acc);
     }
     n_elems += valid;
@@ -857,8 +893,8 @@ struct SumOp {
     BlockStats<2, 2> s;
     s.mx[0] = f2u(vmax);
     s.mx[1] = amax_bits;
-    s.ct[0] = n_top;
-    s.ct[1] = n_und;
+    s.ct[0] = n_top + (n_fast - nz_top);              // codes on the top magnitude
+    s.ct[1] = n_und + ((n_fast - nz_code) - z_acc);   // zero codes that did not come from zero sums
     s.orv = 0;
     block_combine(s);
     if (threadIdx.x == 0) {
@@ -888,10 +924,10 @@ struct SumOp {
   }
 };
 
-template <int FMT>
+template <int FMT, int NR>
 __global__ __launch_bounds__(kThreads) void sum_fp8_kernel(Tables tb, SumParams p) {
-  SumOp<FMT> op(p, tb);
-  walk_chunks<1>(tb, op);
+  SumOp<FMT, NR> op(p, tb);
+  walk_chunks<(NR <= 2 ? 4 : NR <= 4 ? 2 : 1)>(tb, op);   // about eight 128-bit loads in flight per thread
 }
 
 // ================================================================================================
@@ -2163,10 +2199,21 @@ fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* c, const uint8_t* const* payloads, int32_t
   p.sat_num = cfg->sat_num; p.sat_den = cfg->sat_den; p.ramp_steps = cfg->ramp_steps;
   DeviceGuard guard(c->device);
   Timed tm(c, (hipStream_t)stream, FP8LM_K_SUM);
-  if (fmt == FP8LM_E4M3)
-    hipLaunchKernelGGL(sum_fp8_kernel<kE4M3>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
-  else
-    hipLaunchKernelGGL(sum_fp8_kernel<kE5M2>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
+  const dim3 g(grid_of(c)), b(kThreads);
+  hipStream_t s = (hipStream_t)stream;
+  const Tables tb = tables_of(c);
+#define FP8LM_SUM_N(N)                                                                          \
+  case N:                                                                                       \
+    if (fmt == FP8LM_E4M3) hipLaunchKernelGGL((sum_fp8_kernel<kE4M3, N>), g, b, 0, s, tb, p);   \
+    else hipLaunchKernelGGL((sum_fp8_kernel<kE5M2, N>), g, b, 0, s, tb, p);                     \
+    break
+  static_assert(kMaxRanks == 8, "one case per rank count");
+  switch (n_ranks) {
+    FP8LM_SUM_N(1); FP8LM_SUM_N(2); FP8LM_SUM_N(3); FP8LM_SUM_N(4);
+    FP8LM_SUM_N(5); FP8LM_SUM_N(6); FP8LM_SUM_N(7); FP8LM_SUM_N(8);
+    default: return FP8LM_ERR_INVALID_ARGUMENT;
+  }
+#undef FP8LM_SUM_N
   return after_launch();
 }
 
