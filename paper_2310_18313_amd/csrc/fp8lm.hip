@@ -162,8 +162,11 @@ __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
   else { c = b * tb.n_chunks / G; c_end = (b + 1) * tb.n_chunks / G; step = 1; }
   int cur = -1, done = 0;
   TensorDesc d{};
+  // the tensor id of the next chunk is fetched one iteration ahead, so its latency hides behind the body
+  int t_next = c < c_end ? tb.chunk_tensor[c] : -1;
   for (; c < c_end; c += step) {
-    const int t = tb.chunk_tensor[c];
+    const int t = t_next;
+    t_next = c + step < c_end ? tb.chunk_tensor[c + step] : -1;
     if (t != cur) {
       if (cur >= 0) op.flush(cur, d, done);
       cur = t;
