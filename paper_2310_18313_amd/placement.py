@@ -3,7 +3,8 @@
 Measured on MI355X (`python -m paper_2310_18313_amd.placement --probe`): the 288 GiB of HBM3E behave
 as three regions of 96 GiB.  Streams that a kernel walks at the same time run faster when they live
 in different regions: a copy between regions reaches about 5 % more bandwidth than a copy inside one
-region, the eight-stream Adam update kernel about 18 % more.
+region.  For the whole cast + Adam step the gain is between 1 % and 5 %, and the slow outliers of plain
+allocation (the first process on a freshly booted GPU) disappear.
 
 `SpreadAllocator` therefore puts the buffers of an optimizer state into chosen regions without
 assuming anything about the allocator: it takes all free device memory in slabs, finds out which
