@@ -127,7 +127,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--blocks-per-cu", type=int, default=0)
-    ap.add_argument("--interleave", type=int, default=-1)
+    ap.add_argument("--min-chunks", type=int, default=0, help="chunks per workgroup below which a launch shrinks")
     ap.add_argument("--exact", type=int, default=1)
     ap.add_argument("--stats", type=int, default=0)
     ap.add_argument("--copy-ceiling", action="store_true", help="also time a plain 128-bit copy kernel")
@@ -139,6 +139,9 @@ def main() -> int:
                     help="also time the shared-scale re-quantise kernel and the N-rank FP8 sum (Eq. 4-6) on this layout")
     ap.add_argument("--only-path", action="store_true", help="do not also time the other two paths")
     ap.add_argument("--no-spread", action="store_true", help="allocate the buffers plainly, one after the other")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record one step into a HIP graph and time its replays (small workloads are bound by "
+                         "launch latency; the hyper-parameters, step number included, are baked into the graph)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -160,8 +163,8 @@ def main() -> int:
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
     st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=not args.no_spread,
                         grad_buffer=True)
-    if args.chunk or args.blocks_per_cu or args.interleave >= 0:
-        st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 8, max(args.interleave, 0))
+    if args.chunk or args.blocks_per_cu or args.min_chunks:
+        st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 16, args.min_chunks or 8)
     grad = st.grad
     placement = {"spread_over_hbm_regions": st.spread, **{k: v for k, v in st.placement.items() if k != "where"}}
     if st.spread:
@@ -247,6 +250,22 @@ def main() -> int:
         "roofline": {"kernel": "adam_update_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(wl.name)},
     }
+    if args.graph:
+        hp = B.adam_hparams(wl.lr, step_no[0] + 1, exact=args.exact, m_scale_mode=mode_of[args.path])
+        delayed = args.path == "single"
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            st.step(grad, hp, delayed=delayed)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        out["graph_replay_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
     if args.copy_ceiling:
         nbytes = min(lay.total, 1 << 32)
         st.ctx.set_timing(True)

@@ -139,12 +139,15 @@ fp8lm_status fp8lm_create(fp8lm_ctx** out, const fp8lm_tensor* tensors /*host*/,
 fp8lm_status fp8lm_destroy(fp8lm_ctx* ctx);
 
 /*
- * Launch tuning (optional).  chunk_elems: elements per work unit, a multiple of 4096 in
- * [4096, 1048576]; blocks_per_cu: resident 256-thread workgroups per compute unit the persistent
- * grids aim for, 1..16; interleave: 0 = each workgroup walks one contiguous range of chunks,
- * 1 = chunks are dealt round-robin.  Rebuilds the chunk table (synchronises).
+ * Launch tuning (optional; defaults 16384, 16, 8).  chunk_elems: elements per work unit, a multiple of
+ * 4096 in [4096, 1048576]; a chunk never spans two tensors.  blocks_per_cu: 256-thread workgroups per
+ * compute unit that a launch uses at most, 1..16.  min_chunks_per_wg: 1..65536; a launch uses fewer
+ * workgroups than that when the input is small, so that each has at least this many chunks (but never
+ * fewer workgroups than compute units): every workgroup ends with an atomic on a shared counter, and those
+ * cost more than the data of a small input.  Each workgroup walks one contiguous range of chunks.
+ * Rebuilds the chunk table (synchronises).
  */
-fp8lm_status fp8lm_set_tuning(fp8lm_ctx* ctx, int32_t chunk_elems, int32_t blocks_per_cu, int32_t interleave);
+fp8lm_status fp8lm_set_tuning(fp8lm_ctx* ctx, int32_t chunk_elems, int32_t blocks_per_cu, int32_t min_chunks_per_wg);
 
 /*
  * Initial metadata: scale 1, empty amax history, mu = 1 (clean_steps = ramp_steps / 2), counters 0.

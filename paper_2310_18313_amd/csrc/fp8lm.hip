@@ -33,6 +33,7 @@ constexpr int kThreads = 256;
 constexpr int kGroup = 16;                 // elements per thread per iteration
 constexpr int kTile = kThreads * kGroup;   // elements per workgroup per iteration
 constexpr int kWaves = kThreads / 64;
+constexpr int kMaxBlocksPerCu = 16;        // upper limit of the launch tuning; sizes the record array
 
 struct TensorDesc {
   int64_t offset;
@@ -41,14 +42,11 @@ struct TensorDesc {
   int32_t n_chunks;
 };
 
-// Per-tensor reduction scratch.  All-zero between launches except the `pend` block, which carries
-// the scales chosen by the first Adam pass to the second.
+// Per-tensor scratch.  The ticket is zero between launches; the `pend` block carries the scales chosen
+// by the first Adam pass to the second.
 struct Scratch {
-  uint32_t max_a, max_b, max_c;   // running maxima (bit patterns of non-negative values)
   uint32_t ticket;                // chunks finished
-  uint32_t nf;                    // careful path: bit (2*k) NaN seen, bit (2*k+1) inf seen, k = 0 m, 1 v, 2 w
-  uint32_t pad;
-  unsigned long long cnt[8];      // counters: n_sat / n_underflow
+  uint32_t pad[3];
   struct Pending {
     float sm, ism, sv, isv, sw, isw, sq, isq;
     uint32_t fm, fv, fw, fq;      // flags gathered while choosing the scales
@@ -57,13 +55,21 @@ struct Scratch {
   } pend;
 };
 
+// What one workgroup found in its part of one tensor: maxima (bit patterns of non-negative values),
+// counters and an OR-mask.  One record per (workgroup, tensor) pair, each in a cache line of its own.
+struct alignas(128) Partial {
+  uint32_t mx[3];
+  uint32_t orv;
+  unsigned long long ct[8];
+};
+
 struct Tables {
   const TensorDesc* desc;
   const int32_t* chunk_tensor;
   Scratch* scratch;
+  Partial* partials;              // [grid + n_tensors]
   int32_t n_chunks;
   int32_t chunk_elems;
-  int32_t interleave;
 };
 
 // ---- reductions ----------------------------------------------------------------------------------
@@ -123,29 +129,66 @@ __device__ __forceinline__ void block_combine(BlockStats<NV, NC>& s) {
   }
 }
 
-// Publishes a workgroup's partial results for tensor t and returns true in thread 0 of the workgroup
-// that completes the tensor.  Ordering: partials are written with agent-scope atomics, then the
-// ticket is bumped with release/acquire semantics; the completing workgroup therefore observes
-// every other workgroup's partials.
-__device__ __forceinline__ bool publish_ticket(Scratch* sc, int chunks_done, int chunks_total) {
-  const uint32_t old = __hip_atomic_fetch_add(&sc->ticket, (uint32_t)chunks_done, __ATOMIC_ACQ_REL,
-                                              __HIP_MEMORY_SCOPE_AGENT);
-  return old + (uint32_t)chunks_done == (uint32_t)chunks_total;
+// Cross-workgroup reduction of a tensor's statistics, in one pass.
+//
+// Workgroup b walks the chunk range [b*C/G, (b+1)*C/G), so the workgroups that touch tensor t are
+// consecutive and a workgroup touches consecutive tensors: record b + t is unique to the pair (b, t) and
+// the records of one tensor are contiguous.  Every workgroup stores its partial result into its record
+// (plain stores, each record its own cache line) and adds its finished chunks to the tensor's ticket with
+// one atomic.  The workgroup whose addition completes the ticket reads the records of all the others,
+// combines them and runs the tensor's scalar epilogue.  The ticket is the only address all workgroups
+// share: atomics on one address complete one after the other (about 26 ns each on MI355X), so a launch
+// pays one of them per workgroup and tensor instead of one per statistic.
+//
+// Ordering: records are written and read with agent-scope atomic accesses (they bypass the caches that
+// are not coherent across the chip); the ticket is bumped with release/acquire semantics, so the
+// completing workgroup observes every record written before the other workgroups' bumps.
+//
+// Called by all threads, after block_combine(s).  Returns true in every thread of the completing
+// workgroup, with the tensor's totals in thread 0's `s`.
+template <int NV, int NC>
+__device__ __forceinline__ bool collect(const Tables& tb, int t, const TensorDesc& d, int done, BlockStats<NV, NC>& s) {
+  __shared__ int l_last;
+  if (threadIdx.x == 0) {
+    Partial* rec = tb.partials + ((long long)blockIdx.x + t);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) __hip_atomic_store(&rec->mx[i], s.mx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int i = 0; i < NC; ++i) __hip_atomic_store(&rec->ct[i], s.ct[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&rec->orv, s.orv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    Scratch* sc = tb.scratch + t;
+    const uint32_t old = __hip_atomic_fetch_add(&sc->ticket, (uint32_t)done, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = old + (uint32_t)done == (uint32_t)d.n_chunks;
+    if (last) __hip_atomic_store(&sc->ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    l_last = last;
+  }
+  __syncthreads();
+  const bool last = l_last != 0;
+  __syncthreads();                 // l_last may be rewritten by the next flush
+  if (!last) return false;
+  // the workgroups whose chunk ranges meet this tensor: owner(c) = the b with b*C/G <= c < (b+1)*C/G
+  const long long G = gridDim.x, C = tb.n_chunks;
+  const long long c0 = d.first_chunk, c1 = c0 + d.n_chunks - 1;
+  const long long b_lo = ((c0 + 1) * G - 1) / C, b_hi = ((c1 + 1) * G - 1) / C;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) s.mx[i] = 0;
+#pragma unroll
+  for (int i = 0; i < NC; ++i) s.ct[i] = 0;
+  s.orv = 0;
+  for (long long b = b_lo + threadIdx.x; b <= b_hi; b += kThreads) {
+    const Partial* rec = tb.partials + (b + t);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) s.mx[i] = max(s.mx[i], __hip_atomic_load(&rec->mx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+#pragma unroll
+    for (int i = 0; i < NC; ++i) s.ct[i] += __hip_atomic_load(&rec->ct[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s.orv |= __hip_atomic_load(&rec->orv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  block_combine(s);
+  return true;
 }
-__device__ __forceinline__ void atomic_max_u32(uint32_t* p, uint32_t v) {
-  if (v) __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+
 __device__ __forceinline__ void atomic_add_u64(unsigned long long* p, unsigned long long v) {
   if (v) __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void atomic_or_u32(uint32_t* p, uint32_t v) {
-  if (v) __hip_atomic_fetch_or(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint32_t take_u32(uint32_t* p) {   // read and clear
-  return __hip_atomic_exchange(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ unsigned long long take_u64(unsigned long long* p) {
-  return __hip_atomic_exchange(p, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- the chunk walk shared by all kernels -------------------------------------------------------
@@ -156,10 +199,10 @@ __device__ __forceinline__ unsigned long long take_u64(unsigned long long* p) {
 // element; flush(t, desc, chunks_done) (called by all threads).
 template <int UN, class Op>
 __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
+  // workgroup b walks the contiguous chunk range [b*C/G, (b+1)*C/G): `collect` relies on this mapping
   const long long G = gridDim.x, b = blockIdx.x;
-  long long c, c_end, step;
-  if (tb.interleave) { c = b; c_end = tb.n_chunks; step = G; }
-  else { c = b * tb.n_chunks / G; c_end = (b + 1) * tb.n_chunks / G; step = 1; }
+  long long c = b * tb.n_chunks / G;
+  const long long c_end = (b + 1) * tb.n_chunks / G, step = 1;
   int cur = -1, done = 0;
   TensorDesc d{};
   // the tensor id of the next chunk is fetched one iteration ahead, so its latency hides behind the body
@@ -207,6 +250,9 @@ __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
 #endif
 #ifndef FP8LM_UN_UPDATE
 #define FP8LM_UN_UPDATE 1
+#endif
+#ifndef FP8LM_MIN_CHUNKS_PER_WG
+#define FP8LM_MIN_CHUNKS_PER_WG 8   // launches of small inputs use fewer workgroups (see grid_of)
 #endif
 #ifndef FP8LM_CAST_SPLIT
 #define FP8LM_CAST_SPLIT 1     // cast kernel, 16-bit sources: the same split layout as the update kernel
@@ -370,15 +416,7 @@ struct AmaxOp {
     s.mx[0] = src_final<SRC>(acc);
     s.orv = 0;
     block_combine(s);
-    if (threadIdx.x == 0) {
-      Scratch* sc = tb.scratch + t;
-      atomic_max_u32(&sc->max_a, s.mx[0]);
-      if (publish_ticket(sc, done, d.n_chunks)) {
-        const uint32_t abits = take_u32(&sc->max_a);
-        take_u32(&sc->ticket);
-        finish(t, abits);
-      }
-    }
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finish(t, s.mx[0]);
   }
   // scalar epilogue, one thread per tensor
   __device__ void finish(int t, uint32_t abits) {
@@ -630,19 +668,12 @@ struct CastOp {
     s.ct[1] = (n_elems - nz_code) - z_in;       // zero codes that did not come from zero inputs
     s.orv = 0;
     block_combine(s);
-    if (threadIdx.x == 0) {
-      Scratch* sc = tb.scratch + t;
-      atomic_max_u32(&sc->max_a, s.mx[0]);
-      atomic_max_u32(&sc->max_b, s.mx[1]);
-      if constexpr (FUSE) atomic_max_u32(&sc->max_c, s.mx[2]);
-      atomic_add_u64(&sc->cnt[0], s.ct[0]);
-      atomic_add_u64(&sc->cnt[1], s.ct[1]);
-      if (publish_ticket(sc, done, d.n_chunks)) {
-        const float vm = u2f(take_u32(&sc->max_a));
-        const uint32_t abits = take_u32(&sc->max_b);
-        if constexpr (FUSE) sc->pend.amax_m_bits = take_u32(&sc->max_c);
-        const unsigned long long n_sat = take_u64(&sc->cnt[0]), n_und = take_u64(&sc->cnt[1]);
-        take_u32(&sc->ticket);
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+      {
+        const float vm = u2f(s.mx[0]);
+        const uint32_t abits = s.mx[1];
+        if constexpr (FUSE) tb.scratch[t].pend.amax_m_bits = s.mx[2];
+        const unsigned long long n_sat = s.ct[0], n_und = s.ct[1];
         if constexpr (DELAYED) {
           fp8lm_meta& M = p.meta[t];
           if (abits >= SrcTraits<SRC>::kNonfinite) {
@@ -765,17 +796,11 @@ struct RequantOp {
     s.ct[1] = nz_in - nz_code;                 // non-zero codes in, zero codes out (a NaN code is non-zero on both sides)
     s.orv = nonfinite;
     block_combine(s);
-    if (threadIdx.x == 0) {
-      Scratch* sc = tb.scratch + t;
-      atomic_max_u32(&sc->max_a, s.mx[0]);
-      atomic_add_u64(&sc->cnt[0], s.ct[0]);
-      atomic_add_u64(&sc->cnt[1], s.ct[1]);
-      atomic_or_u32(&sc->nf, s.orv);
-      if (publish_ticket(sc, done, d.n_chunks)) {
-        const float vm = u2f(take_u32(&sc->max_a));
-        const unsigned long long n_sat = take_u64(&sc->cnt[0]), n_und = take_u64(&sc->cnt[1]);
-        const uint32_t nf = take_u32(&sc->nf);
-        take_u32(&sc->ticket);
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+      {
+        const float vm = u2f(s.mx[0]);
+        const unsigned long long n_sat = s.ct[0], n_und = s.ct[1];
+        const uint32_t nf = s.orv;
         fp8lm_meta& M = p.dst_meta[t];
         const float src_amax = p.src_meta[t].amax;
         const float inv = 1.0f / sg;
@@ -900,17 +925,11 @@ struct SumOp {
     s.ct[1] = n_und + ((n_fast - nz_code) - z_acc);   // zero codes that did not come from zero sums
     s.orv = 0;
     block_combine(s);
-    if (threadIdx.x == 0) {
-      Scratch* sc = tb.scratch + t;
-      atomic_max_u32(&sc->max_a, s.mx[0]);
-      atomic_max_u32(&sc->max_b, s.mx[1]);
-      atomic_add_u64(&sc->cnt[0], s.ct[0]);
-      atomic_add_u64(&sc->cnt[1], s.ct[1]);
-      if (publish_ticket(sc, done, d.n_chunks)) {
-        const float vm = u2f(take_u32(&sc->max_a));
-        const uint32_t ab = take_u32(&sc->max_b);
-        const unsigned long long n_sat = take_u64(&sc->cnt[0]), n_under = take_u64(&sc->cnt[1]);
-        take_u32(&sc->ticket);
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+      {
+        const float vm = u2f(s.mx[0]);
+        const uint32_t ab = s.mx[1];
+        const unsigned long long n_sat = s.ct[0], n_under = s.ct[1];
         fp8lm_meta& M = p.dst_meta[t];
         const float sc_out = (float)p.in.n_ranks * p.shared[t];
         const bool nf = ab >= 0x7F800000u;
@@ -1001,17 +1020,12 @@ struct InitCastOp {
     s.ct[1] = n_und;
     s.orv = 0;
     block_combine(s);
-    if (threadIdx.x == 0) {
-      Scratch* sc = tb.scratch + t;
-      atomic_max_u32(&sc->max_a, s.mx[0]);
-      atomic_add_u64(&sc->cnt[0], s.ct[0]);
-      atomic_add_u64(&sc->cnt[1], s.ct[1]);
-      if (publish_ticket(sc, done, d.n_chunks)) {
-        const float vm = u2f(take_u32(&sc->max_a));
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+      {
+        const float vm = u2f(s.mx[0]);
         fp8lm_meta& M = p.meta[t];
-        M.n_sat = take_u64(&sc->cnt[0]);
-        M.n_underflow = take_u64(&sc->cnt[1]);
-        take_u32(&sc->ticket);
+        M.n_sat = s.ct[0];
+        M.n_underflow = s.ct[1];
         M.amax_deq = vm * M.inv_scale;        // vm is already a stored value
         if (M.n_sat) M.flags |= FP8LM_FLAG_SATURATED;
       }
@@ -1173,15 +1187,7 @@ struct AdamAmaxOp {
     s.mx[0] = acc;
     s.orv = 0;
     block_combine(s);
-    if (threadIdx.x == 0) {
-      Scratch* sc = tb.scratch + t;
-      atomic_max_u32(&sc->max_a, s.mx[0]);
-      if (publish_ticket(sc, done, d.n_chunks)) {
-        const uint32_t abits = take_u32(&sc->max_a);
-        take_u32(&sc->ticket);
-        finish(t, abits);
-      }
-    }
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finish(t, s.mx[0]);
   }
   __device__ void finish(int t, uint32_t abits) {
     const bool m_nonfinite = abits >= 0x7F800000u;
@@ -1433,33 +1439,23 @@ struct AdamUpdateOp {
   }
 
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<3, 8> s;
+    BlockStats<3, STATS ? 8 : 0> s;
     s.mx[0] = f2u(vmax);
     s.mx[1] = f2u(wmax);
     s.mx[2] = f2u(mmax);
+    if constexpr (STATS) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) s.ct[i] = cnt[i];
+      for (int i = 0; i < 8; ++i) s.ct[i] = cnt[i];
+    }
     s.orv = nf;
     block_combine(s);
-    if (threadIdx.x == 0) {
-      Scratch* sc = tb.scratch + t;
-      atomic_max_u32(&sc->max_a, s.mx[0]);
-      atomic_max_u32(&sc->max_b, s.mx[1]);
-      atomic_max_u32(&sc->max_c, s.mx[2]);
-      atomic_or_u32(&sc->nf, s.orv);
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+      unsigned long long c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      if constexpr (STATS) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) atomic_add_u64(&sc->cnt[i], s.ct[i]);
-      if (publish_ticket(sc, done, d.n_chunks)) {
-        const float A_v = u2f(take_u32(&sc->max_a));
-        const float A_w = u2f(take_u32(&sc->max_b));
-        const float A_mc = u2f(take_u32(&sc->max_c));
-        const uint32_t nfb = take_u32(&sc->nf);
-        unsigned long long c[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) c[i] = take_u64(&sc->cnt[i]);
-        take_u32(&sc->ticket);
-        finish(t, A_v, A_w, A_mc, nfb, c);
+        for (int i = 0; i < 8; ++i) c[i] = s.ct[i];
       }
+      finish(t, u2f(s.mx[0]), u2f(s.mx[1]), u2f(s.mx[2]), s.orv, c);
     }
   }
 
@@ -1630,17 +1626,11 @@ struct AdamUpdateVarOp {
     s.mx[2] = f2u(mmax);
     s.orv = nf;
     block_combine(s);
-    if (threadIdx.x == 0) {
-      Scratch* sc = tb.scratch + t;
-      atomic_max_u32(&sc->max_a, s.mx[0]);
-      atomic_max_u32(&sc->max_b, s.mx[1]);
-      atomic_max_u32(&sc->max_c, s.mx[2]);
-      atomic_or_u32(&sc->nf, s.orv);
-      if (publish_ticket(sc, done, d.n_chunks)) {
-        const float A_v = u2f(take_u32(&sc->max_a)), A_w = u2f(take_u32(&sc->max_b)), A_m = u2f(take_u32(&sc->max_c));
-        const uint32_t nfb = take_u32(&sc->nf);
-        take_u32(&sc->ticket);
-        const Scratch::Pending& P = sc->pend;
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+      {
+        const float A_v = u2f(s.mx[0]), A_w = u2f(s.mx[1]), A_m = u2f(s.mx[2]);
+        const uint32_t nfb = s.orv;
+        const Scratch::Pending& P = tb.scratch[t].pend;
         fill<StTraits<kStE4M3>>(p.m_meta[t], P.sm, P.ism, A_m, nfb & 3u, P.fm);
         fill<VT>(p.v_meta[t], P.sv, P.isv, A_v, (nfb >> 2) & 3u, P.fv);
         fill<WT>(p.w_meta[t], P.sw, P.isw, A_w, (nfb >> 4) & 3u, P.fw);
@@ -1818,12 +1808,13 @@ struct fp8lm_ctx {
   int num_cus = 0;
   std::vector<fp8lm_tensor> tensors;
   int32_t chunk_elems = 16384;
-  int32_t blocks_per_cu = 16;
-  int32_t interleave = 0;
+  int32_t blocks_per_cu = kMaxBlocksPerCu;
+  int32_t min_chunks_per_wg = FP8LM_MIN_CHUNKS_PER_WG;
   int32_t n_chunks = 0;
   TensorDesc* d_desc = nullptr;
   int32_t* d_chunk_tensor = nullptr;
   Scratch* d_scratch = nullptr;
+  Partial* d_partials = nullptr;    // [num_cus * kMaxBlocksPerCu + n_tensors]
   // what the last fused cast measured for (checked by the Adam step that wants to use it)
   struct Fused { bool valid; const uint8_t* grad; const uint8_t* m; const fp8lm_meta* m_meta; float b1; int fmt; };
   Fused fused{false, nullptr, nullptr, nullptr, 0.0f, 0};
@@ -1884,12 +1875,17 @@ fp8lm_status build_tables(fp8lm_ctx* c) {
 }
 
 Tables tables_of(const fp8lm_ctx* c) {
-  return Tables{c->d_desc, c->d_chunk_tensor, c->d_scratch, c->n_chunks, c->chunk_elems, c->interleave};
+  return Tables{c->d_desc, c->d_chunk_tensor, c->d_scratch, c->d_partials, c->n_chunks, c->chunk_elems};
 }
 
+// Workgroups per launch.  Every workgroup ends with one ticket atomic per tensor it touched, and atomics on
+// the small scratch array complete one after the other (about 26 ns each on MI355X): a launch with G
+// workgroups cannot finish faster than G x 26 ns.  Large inputs hide that behind their data; smaller ones
+// get fewer workgroups, each with at least min_chunks_per_wg chunks, but no fewer than one per CU.
 int grid_of(const fp8lm_ctx* c) {
-  const long long want = (long long)c->num_cus * c->blocks_per_cu;
-  return (int)std::max<long long>(1, std::min<long long>(want, c->n_chunks));
+  const long long full = (long long)c->num_cus * c->blocks_per_cu;
+  const long long by_work = std::max<long long>(c->num_cus, c->n_chunks / std::max(1, c->min_chunks_per_wg));
+  return (int)std::max<long long>(1, std::min<long long>(std::min(full, by_work), c->n_chunks));
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -2016,6 +2012,9 @@ fp8lm_status fp8lm_create(fp8lm_ctx** out, const fp8lm_tensor* tensors, int32_t 
     const size_t bytes = std::max<size_t>(1, (size_t)n) * sizeof(Scratch);
     hipError_t e = hipMalloc((void**)&c->d_scratch, bytes);
     if (e == hipSuccess) e = hipMemset(c->d_scratch, 0, bytes);
+    const size_t records = (size_t)c->num_cus * kMaxBlocksPerCu + (size_t)n + 1;
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_partials, records * sizeof(Partial));
+    if (e == hipSuccess) e = hipMemset(c->d_partials, 0, records * sizeof(Partial));
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) { g_hip_error = hipGetErrorString(e); st = FP8LM_ERR_HIP; }
   }
@@ -2030,21 +2029,22 @@ fp8lm_status fp8lm_destroy(fp8lm_ctx* c) {
   if (c->d_desc) (void)hipFree(c->d_desc);
   if (c->d_chunk_tensor) (void)hipFree(c->d_chunk_tensor);
   if (c->d_scratch) (void)hipFree(c->d_scratch);
+  if (c->d_partials) (void)hipFree(c->d_partials);
   for (auto& s : c->stamps) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
   for (auto& e : c->free_events) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
   delete c;
   return FP8LM_OK;
 }
 
-fp8lm_status fp8lm_set_tuning(fp8lm_ctx* c, int32_t chunk_elems, int32_t blocks_per_cu, int32_t interleave) {
+fp8lm_status fp8lm_set_tuning(fp8lm_ctx* c, int32_t chunk_elems, int32_t blocks_per_cu, int32_t min_chunks_per_wg) {
   if (!c || chunk_elems < kTile || chunk_elems > (1 << 20) || chunk_elems % kTile != 0 || blocks_per_cu < 1 ||
-      blocks_per_cu > 16 || (interleave != 0 && interleave != 1))
+      blocks_per_cu > kMaxBlocksPerCu || min_chunks_per_wg < 1 || min_chunks_per_wg > 65536)
     return FP8LM_ERR_INVALID_ARGUMENT;
   DeviceGuard guard(c->device);
   HIP_TRY(hipDeviceSynchronize());
   c->chunk_elems = chunk_elems;
   c->blocks_per_cu = blocks_per_cu;
-  c->interleave = interleave;
+  c->min_chunks_per_wg = min_chunks_per_wg;
   return build_tables(c);
 }
 

@@ -174,7 +174,7 @@ def test_free_running_oracle_and_gpu_end_in_the_same_state(name, steps):
     fr.assert_equal_to(st, f"{name} after {steps} free-running steps")
 
 
-@pytest.mark.parametrize("tuning", [(4096, 1, 0), (4096, 16, 1), (65536, 4, 1), (1048576, 2, 0)])
+@pytest.mark.parametrize("tuning", [(4096, 1, 1), (4096, 16, 1), (65536, 4, 2), (1048576, 2, 64), (16384, 16, 1)])
 def test_launch_shapes_give_identical_results(tuning):
     wl = synth.workload("tiny")
     run_lockstep(wl, seed=5, steps=2, exact=1, stats=1, tuning=tuning)
@@ -257,7 +257,7 @@ def test_argument_errors_are_reported_not_launched():
     with pytest.raises(B.Fp8lmError):           # another beta1 than the cast measured for
         st.adam(B.adam_hparams(1e-3, 1, beta1=0.8, m_scale_mode=B.MSCALE_FROM_CAST))
     with pytest.raises(B.Fp8lmError):
-        st.ctx.set_tuning(1000, 8, 0)
+        st.ctx.set_tuning(1000, 8, 8)
     bad_cfg = B.autoscale_cfg(hist_window=17)
     with pytest.raises(B.Fp8lmError):
         st.ctx.amax_scale(grad, B.E5M2, st.g_meta, bad_cfg)
@@ -627,3 +627,44 @@ def test_allreduce_strategies_match_the_oracle_and_order_as_the_ablation_says(fm
     assert final["pre"]["underflow_rate"] >= final["post"]["underflow_rate"]
     assert final["post"]["overflow_rate"] >= final["pre"]["overflow_rate"]
     assert final["pre"]["underflow_rate"] >= final["auto"]["underflow_rate"]
+
+
+# ---- the entry points can be recorded into a HIP graph ---------------------------------------------------------
+def test_a_step_replayed_from_a_hip_graph_equals_the_eager_step():
+    """None of the hot-path calls synchronises, allocates or clears memory with a memset, so a whole step can be
+    captured once and replayed; the hyper-parameters are baked in at capture, so every replay is the same step."""
+    wl = synth.Workload("mid", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-3, sigma=None)
+    st, _ = P.make_state(wl, 31)
+    grad = torch.zeros(max(wl.layout.total, 16), dtype=torch.bfloat16, device=DEV)
+    for step in (1, 2):                                          # some history first
+        synth.fill_gradients(grad, wl, 31, step)
+        st.step(grad, B.adam_hparams(wl.lr, step))
+    synth.fill_gradients(grad, wl, 31, 3)
+    hp = B.adam_hparams(wl.lr, 3)
+    names = ("g8", "m", "v", "w", "wq", "g_meta", "m_meta", "v_meta", "w_meta", "q_meta")
+    before = {k: getattr(st, k).clone() for k in names}
+    st.step(grad, hp)                                            # eager reference
+    torch.cuda.synchronize()
+    want = {k: getattr(st, k).clone() for k in names}
+
+    def restore():
+        for k in names:
+            getattr(st, k).copy_(before[k])
+
+    restore()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    say("capturing one step into a HIP graph")
+    with torch.cuda.graph(graph, stream=side):
+        st.step(grad, hp)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        restore()                                                # eager work between the replays
+        torch.cuda.synchronize()
+        say(f"graph replay {rep}")
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in names:
+            assert torch.equal(getattr(st, k), want[k]), f"replay {rep}: {k} differs from the eager step"
