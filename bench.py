@@ -127,7 +127,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--blocks-per-cu", type=int, default=0)
-    ap.add_argument("--min-chunks", type=int, default=0, help="chunks per workgroup below which a launch shrinks")
+    ap.add_argument("--single-pass-min-chunks", type=int, default=-1,
+                    help="chunks per workgroup below which tensors are finished by a second launch (0: never)")
     ap.add_argument("--exact", type=int, default=1)
     ap.add_argument("--stats", type=int, default=0)
     ap.add_argument("--copy-ceiling", action="store_true", help="also time a plain 128-bit copy kernel")
@@ -163,8 +164,9 @@ def main() -> int:
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
     st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=not args.no_spread,
                         grad_buffer=True)
-    if args.chunk or args.blocks_per_cu or args.min_chunks:
-        st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 16, args.min_chunks or 8)
+    if args.chunk or args.blocks_per_cu or args.single_pass_min_chunks >= 0:
+        st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 16,
+                          64 if args.single_pass_min_chunks < 0 else args.single_pass_min_chunks)
     grad = st.grad
     placement = {"spread_over_hbm_regions": st.spread, **{k: v for k, v in st.placement.items() if k != "where"}}
     if st.spread:

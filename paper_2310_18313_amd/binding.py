@@ -210,8 +210,8 @@ class Context:
         except Exception:  # interpreter shutdown
             pass
 
-    def set_tuning(self, chunk_elems=16384, blocks_per_cu=16, min_chunks_per_wg=8):
-        _check(lib().fp8lm_set_tuning(self._h, chunk_elems, blocks_per_cu, min_chunks_per_wg), "fp8lm_set_tuning")
+    def set_tuning(self, chunk_elems=16384, blocks_per_cu=16, single_pass_min_chunks=64):
+        _check(lib().fp8lm_set_tuning(self._h, chunk_elems, blocks_per_cu, single_pass_min_chunks), "fp8lm_set_tuning")
 
     def new_meta(self, cfg: AutoscaleCfg, stream=None) -> torch.Tensor:
         """Device array of fp8lm_meta (as raw bytes, [n_tensors, 112]) in its initial state."""

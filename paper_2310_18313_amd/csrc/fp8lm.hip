@@ -70,6 +70,7 @@ struct Tables {
   Partial* partials;              // [grid + n_tensors]
   int32_t n_chunks;
   int32_t chunk_elems;
+  int32_t deferred;               // 1: workgroups only leave their records; an epilogue launch finishes the tensors
 };
 
 // ---- reductions ----------------------------------------------------------------------------------
@@ -129,47 +130,46 @@ __device__ __forceinline__ void block_combine(BlockStats<NV, NC>& s) {
   }
 }
 
-// Cross-workgroup reduction of a tensor's statistics, in one pass.
+// Cross-workgroup reduction of a tensor's statistics.
 //
 // Workgroup b walks the chunk range [b*C/G, (b+1)*C/G), so the workgroups that touch tensor t are
 // consecutive and a workgroup touches consecutive tensors: record b + t is unique to the pair (b, t) and
 // the records of one tensor are contiguous.  Every workgroup stores its partial result into its record
-// (plain stores, each record its own cache line) and adds its finished chunks to the tensor's ticket with
-// one atomic.  The workgroup whose addition completes the ticket reads the records of all the others,
-// combines them and runs the tensor's scalar epilogue.  The ticket is the only address all workgroups
-// share: atomics on one address complete one after the other (about 26 ns each on MI355X), so a launch
-// pays one of them per workgroup and tensor instead of one per statistic.
+// (each record has a cache line of its own).  What happens next has two forms:
 //
-// Ordering: records are written and read with agent-scope atomic accesses (they bypass the caches that
-// are not coherent across the chip); the ticket is bumped with release/acquire semantics, so the
-// completing workgroup observes every record written before the other workgroups' bumps.
+//  * single pass: the workgroup adds its finished chunks to the tensor's ticket with one atomic; the
+//    workgroup whose addition completes the ticket reads the records of all the others, combines them
+//    and runs the tensor's scalar epilogue.  Measured on MI355X, a ticket costs every workgroup about
+//    20 ns that do not overlap with those of other workgroups (12 ns for an atomic on an address all
+//    workgroups share, 8 ns for the release that makes the record visible): 80 us for a launch of 4096
+//    workgroups, nothing beside the milliseconds of a 13B-parameter model, more than the data of a
+//    100M-parameter one.
+//  * deferred: no ticket; a second, tiny launch (one workgroup per tensor) combines the records after the
+//    first has ended and runs the epilogues.  Costs one launch (about 3 us), independent of the grid.
 //
-// Called by all threads, after block_combine(s).  Returns true in every thread of the completing
-// workgroup, with the tensor's totals in thread 0's `s`.
+// The host picks the form per launch from the chunks each workgroup has (fp8lm_set_tuning).
+//
+// Ordering in the single pass: records are written and read with agent-scope atomic accesses (they bypass
+// the caches that are not coherent across the chip); the ticket is bumped with release/acquire semantics,
+// so the completing workgroup observes every record written before the other workgroups' bumps.
 template <int NV, int NC>
-__device__ __forceinline__ bool collect(const Tables& tb, int t, const TensorDesc& d, int done, BlockStats<NV, NC>& s) {
-  __shared__ int l_last;
-  if (threadIdx.x == 0) {
-    Partial* rec = tb.partials + ((long long)blockIdx.x + t);
+__device__ __forceinline__ void store_record(const Tables& tb, int t, const BlockStats<NV, NC>& s) {
+  Partial* rec = tb.partials + ((long long)blockIdx.x + t);
 #pragma unroll
-    for (int i = 0; i < NV; ++i) __hip_atomic_store(&rec->mx[i], s.mx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int i = 0; i < NV; ++i) __hip_atomic_store(&rec->mx[i], s.mx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-    for (int i = 0; i < NC; ++i) __hip_atomic_store(&rec->ct[i], s.ct[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&rec->orv, s.orv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    Scratch* sc = tb.scratch + t;
-    const uint32_t old = __hip_atomic_fetch_add(&sc->ticket, (uint32_t)done, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    const bool last = old + (uint32_t)done == (uint32_t)d.n_chunks;
-    if (last) __hip_atomic_store(&sc->ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
-    l_last = last;
-  }
-  __syncthreads();
-  const bool last = l_last != 0;
-  __syncthreads();                 // l_last may be rewritten by the next flush
-  if (!last) return false;
-  // the workgroups whose chunk ranges meet this tensor: owner(c) = the b with b*C/G <= c < (b+1)*C/G
-  const long long G = gridDim.x, C = tb.n_chunks;
+  for (int i = 0; i < NC; ++i) __hip_atomic_store(&rec->ct[i], s.ct[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(&rec->orv, s.orv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Combines the records of all workgroups of a launch with `grid` workgroups that touched tensor t.  Called
+// by all threads; the totals end up in thread 0's `s`.
+template <int NV, int NC>
+__device__ __forceinline__ void gather_records(const Tables& tb, int t, const TensorDesc& d, long long grid, BlockStats<NV, NC>& s) {
+  // owner(c) = the b with b*C/G <= c < (b+1)*C/G
+  const long long C = tb.n_chunks;
   const long long c0 = d.first_chunk, c1 = c0 + d.n_chunks - 1;
-  const long long b_lo = ((c0 + 1) * G - 1) / C, b_hi = ((c1 + 1) * G - 1) / C;
+  const long long b_lo = ((c0 + 1) * grid - 1) / C, b_hi = ((c1 + 1) * grid - 1) / C;
 #pragma unroll
   for (int i = 0; i < NV; ++i) s.mx[i] = 0;
 #pragma unroll
@@ -184,7 +184,46 @@ __device__ __forceinline__ bool collect(const Tables& tb, int t, const TensorDes
     s.orv |= __hip_atomic_load(&rec->orv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   block_combine(s);
+}
+
+// Called by all threads at the end of a workgroup's part of tensor t, after block_combine(s).  Returns
+// true in every thread of the workgroup that has to run the tensor's epilogue, with the tensor's totals in
+// thread 0's `s`; always false in the deferred form.
+template <int NV, int NC>
+__device__ __forceinline__ bool collect(const Tables& tb, int t, const TensorDesc& d, int done, BlockStats<NV, NC>& s) {
+  if (tb.deferred) {
+    if (threadIdx.x == 0) store_record(tb, t, s);
+    return false;
+  }
+  __shared__ int l_last;
+  if (threadIdx.x == 0) {
+    store_record(tb, t, s);
+    Scratch* sc = tb.scratch + t;
+    const uint32_t old = __hip_atomic_fetch_add(&sc->ticket, (uint32_t)done, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = old + (uint32_t)done == (uint32_t)d.n_chunks;
+    if (last) __hip_atomic_store(&sc->ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    l_last = last;
+  }
+  __syncthreads();
+  const bool last = l_last != 0;
+  __syncthreads();                 // l_last may be rewritten by the next flush
+  if (!last) return false;
+  gather_records(tb, t, d, gridDim.x, s);
   return true;
+}
+
+// The second launch of the deferred form: workgroup t finishes tensor t.
+template <class Op, class Params>
+__global__ __launch_bounds__(kThreads) void epilogue_kernel(Tables tb, Params p, int main_grid, int n_tensors) {
+  Op op(p, tb);
+  for (int t = blockIdx.x; t < n_tensors; t += gridDim.x) {
+    const TensorDesc d = tb.desc[t];
+    if (d.n_chunks == 0) continue;
+    op.begin(t, d);
+    typename Op::Stats s;
+    gather_records(tb, t, d, main_grid, s);
+    if (threadIdx.x == 0) op.finalize(t, d, s);
+  }
 }
 
 __device__ __forceinline__ void atomic_add_u64(unsigned long long* p, unsigned long long v) {
@@ -251,8 +290,9 @@ __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
 #ifndef FP8LM_UN_UPDATE
 #define FP8LM_UN_UPDATE 1
 #endif
-#ifndef FP8LM_MIN_CHUNKS_PER_WG
-#define FP8LM_MIN_CHUNKS_PER_WG 8   // launches of small inputs use fewer workgroups (see grid_of)
+#ifndef FP8LM_SINGLE_PASS_MIN_CHUNKS
+#define FP8LM_SINGLE_PASS_MIN_CHUNKS 64   // launches with fewer chunks per workgroup finish their tensors in a
+                                          // second launch instead of through tickets (see collect)
 #endif
 #ifndef FP8LM_CAST_SPLIT
 #define FP8LM_CAST_SPLIT 1     // cast kernel, 16-bit sources: the same split layout as the update kernel
@@ -411,15 +451,17 @@ struct AmaxOp {
     const elem_t* q = static_cast<const elem_t*>(p.src) + pos;
     for (int j = 0; j < valid; ++j) src_fold1<SRC>(acc, q[j]);
   }
+  using Stats = BlockStats<1, 0>;
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<1, 0> s;
+    Stats s;
     s.mx[0] = src_final<SRC>(acc);
     s.orv = 0;
     block_combine(s);
-    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finish(t, s.mx[0]);
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
   }
   // scalar epilogue, one thread per tensor
-  __device__ void finish(int t, uint32_t abits) {
+  __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
+    const uint32_t abits = s.mx[0];
     fp8lm_meta& M = p.meta[t];
     if (abits >= SrcTraits<SRC>::kNonfinite) {
       M.amax = __builtin_inff();
@@ -659,8 +701,9 @@ struct CastOp {
     for (int j = 0; j < valid; ++j) p.dst[pos + j] = (uint8_t)one(q[j], FUSE ? p.m[pos + j] : 0u);
     n_elems += valid;
   }
+  using Stats = BlockStats<3, 2>;
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<3, 2> s;
+    Stats s;
     s.mx[0] = f2u(vmax);
     s.mx[1] = src_final<SRC>(amax16);
     s.mx[2] = macc;
@@ -668,7 +711,10 @@ struct CastOp {
     s.ct[1] = (n_elems - nz_code) - z_in;       // zero codes that did not come from zero inputs
     s.orv = 0;
     block_combine(s);
-    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
+  }
+  __device__ void finalize(int t, const TensorDesc& d, const Stats& s) {
+    {
       {
         const float vm = u2f(s.mx[0]);
         const uint32_t abits = s.mx[1];
@@ -789,14 +835,18 @@ struct RequantOp {
     }
     n_elems += valid;
   }
+  using Stats = BlockStats<1, 2>;
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<1, 2> s;
+    Stats s;
     s.mx[0] = f2u(vmax);
     s.ct[0] = n_elems - nz_top;
     s.ct[1] = nz_in - nz_code;                 // non-zero codes in, zero codes out (a NaN code is non-zero on both sides)
     s.orv = nonfinite;
     block_combine(s);
-    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
+  }
+  __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
+    {
       {
         const float vm = u2f(s.mx[0]);
         const unsigned long long n_sat = s.ct[0], n_und = s.ct[1];
@@ -917,15 +967,19 @@ struct SumOp {
     }
     n_elems += valid;
   }
+  using Stats = BlockStats<2, 2>;
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<2, 2> s;
+    Stats s;
     s.mx[0] = f2u(vmax);
     s.mx[1] = amax_bits;
     s.ct[0] = n_top + (n_fast - nz_top);              // codes on the top magnitude
     s.ct[1] = n_und + ((n_fast - nz_code) - z_acc);   // zero codes that did not come from zero sums
     s.orv = 0;
     block_combine(s);
-    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
+  }
+  __device__ void finalize(int t, const TensorDesc& d, const Stats& s) {
+    {
       {
         const float vm = u2f(s.mx[0]);
         const uint32_t ab = s.mx[1];
@@ -1013,14 +1067,18 @@ struct InitCastOp {
       st_store1<MASTER>(p.dst, pos + j, h);
     }
   }
+  using Stats = BlockStats<1, 2>;
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<1, 2> s;
+    Stats s;
     s.mx[0] = f2u(vmax);
     s.ct[0] = n_sat;
     s.ct[1] = n_und;
     s.orv = 0;
     block_combine(s);
-    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
+  }
+  __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
+    {
       {
         const float vm = u2f(s.mx[0]);
         fp8lm_meta& M = p.meta[t];
@@ -1182,14 +1240,16 @@ struct AdamAmaxOp {
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) elem(fp8_to_f32<GFMT>(p.grad[pos + j]), fp8_to_f32<kE4M3>(p.m[pos + j]));
   }
+  using Stats = BlockStats<1, 0>;
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<1, 0> s;
+    Stats s;
     s.mx[0] = acc;
     s.orv = 0;
     block_combine(s);
-    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finish(t, s.mx[0]);
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
   }
-  __device__ void finish(int t, uint32_t abits) {
+  __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
+    const uint32_t abits = s.mx[0];
     const bool m_nonfinite = abits >= 0x7F800000u;
     adam_choose_scales<WCOPY>(p, tb.scratch[t].pend, t, m_nonfinite ? __builtin_inff() : u2f(abits));
   }
@@ -1438,8 +1498,9 @@ struct AdamUpdateOp {
     }
   }
 
+  using Stats = BlockStats<3, STATS ? 8 : 0>;
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<3, STATS ? 8 : 0> s;
+    Stats s;
     s.mx[0] = f2u(vmax);
     s.mx[1] = f2u(wmax);
     s.mx[2] = f2u(mmax);
@@ -1449,7 +1510,10 @@ struct AdamUpdateOp {
     }
     s.orv = nf;
     block_combine(s);
-    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
+  }
+  __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
+    {
       unsigned long long c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
       if constexpr (STATS) {
 #pragma unroll
@@ -1619,14 +1683,18 @@ struct AdamUpdateVarOp {
     M.n_sat = 0;
     M.n_underflow = 0;
   }
+  using Stats = BlockStats<3, 0>;
   __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
-    BlockStats<3, 0> s;
+    Stats s;
     s.mx[0] = f2u(vmax);
     s.mx[1] = f2u(wmax);
     s.mx[2] = f2u(mmax);
     s.orv = nf;
     block_combine(s);
-    if (collect(tb, t, d, done, s) && threadIdx.x == 0) {
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
+  }
+  __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
+    {
       {
         const float A_v = u2f(s.mx[0]), A_w = u2f(s.mx[1]), A_m = u2f(s.mx[2]);
         const uint32_t nfb = s.orv;
@@ -1809,7 +1877,7 @@ struct fp8lm_ctx {
   std::vector<fp8lm_tensor> tensors;
   int32_t chunk_elems = 16384;
   int32_t blocks_per_cu = kMaxBlocksPerCu;
-  int32_t min_chunks_per_wg = FP8LM_MIN_CHUNKS_PER_WG;
+  int32_t single_pass_min_chunks = FP8LM_SINGLE_PASS_MIN_CHUNKS;
   int32_t n_chunks = 0;
   TensorDesc* d_desc = nullptr;
   int32_t* d_chunk_tensor = nullptr;
@@ -1874,18 +1942,22 @@ fp8lm_status build_tables(fp8lm_ctx* c) {
   return FP8LM_OK;
 }
 
-Tables tables_of(const fp8lm_ctx* c) {
-  return Tables{c->d_desc, c->d_chunk_tensor, c->d_scratch, c->d_partials, c->n_chunks, c->chunk_elems};
-}
-
-// Workgroups per launch.  Every workgroup ends with one ticket atomic per tensor it touched, and atomics on
-// the small scratch array complete one after the other (about 26 ns each on MI355X): a launch with G
-// workgroups cannot finish faster than G x 26 ns.  Large inputs hide that behind their data; smaller ones
-// get fewer workgroups, each with at least min_chunks_per_wg chunks, but no fewer than one per CU.
+// Workgroups per launch: blocks_per_cu per compute unit, but never more than there are chunks.
 int grid_of(const fp8lm_ctx* c) {
   const long long full = (long long)c->num_cus * c->blocks_per_cu;
-  const long long by_work = std::max<long long>(c->num_cus, c->n_chunks / std::max(1, c->min_chunks_per_wg));
-  return (int)std::max<long long>(1, std::min<long long>(std::min(full, by_work), c->n_chunks));
+  return (int)std::max<long long>(1, std::min<long long>(full, c->n_chunks));
+}
+
+// The single-pass form of the cross-workgroup reduction costs every workgroup a ticket (about 20 ns that
+// do not overlap between workgroups); with few chunks per workgroup that is more than the data, and the
+// deferred form (a second, tiny launch) is used instead.
+bool deferred_of(const fp8lm_ctx* c) {
+  return c->single_pass_min_chunks > 0 && c->n_chunks / grid_of(c) < c->single_pass_min_chunks;
+}
+
+Tables tables_of(const fp8lm_ctx* c) {
+  return Tables{c->d_desc, c->d_chunk_tensor, c->d_scratch, c->d_partials, c->n_chunks, c->chunk_elems,
+                deferred_of(c) ? 1 : 0};
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -1918,17 +1990,28 @@ fp8lm_status after_launch() {
   return FP8LM_OK;
 }
 
+// Launches a chunk-walking kernel and, in the deferred form, the launch that finishes its tensors.
+template <class Op, class Params, class Kernel>
+void launch_walk(fp8lm_ctx* c, hipStream_t s, Kernel kernel, const Params& p) {
+  const Tables tb = tables_of(c);
+  const dim3 g(grid_of(c)), b(kThreads);
+  hipLaunchKernelGGL(kernel, g, b, 0, s, tb, p);
+  if (tb.deferred)
+    hipLaunchKernelGGL((epilogue_kernel<Op, Params>), dim3(std::min<int>(c->n_tensors, 4 * c->num_cus)), b, 0, s, tb, p,
+                       (int)g.x, (int)c->n_tensors);
+}
+
 // Selects the adam_update_kernel instantiation.
 template <int GFMT, int WCOPY>
 void launch_update(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, bool fast, bool stats) {
   const dim3 g(grid_of(c)), b(kThreads);
   const Tables tb = tables_of(c);
   if (fast) {
-    if (stats) hipLaunchKernelGGL((adam_update_kernel<GFMT, WCOPY, true, true>), g, b, 0, s, tb, p);
-    else hipLaunchKernelGGL((adam_update_kernel<GFMT, WCOPY, true, false>), g, b, 0, s, tb, p);
+    if (stats) launch_walk<AdamUpdateOp<GFMT, WCOPY, true, true>>(c, s, adam_update_kernel<GFMT, WCOPY, true, true>, p);
+    else launch_walk<AdamUpdateOp<GFMT, WCOPY, true, false>>(c, s, adam_update_kernel<GFMT, WCOPY, true, false>, p);
   } else {
-    if (stats) hipLaunchKernelGGL((adam_update_kernel<GFMT, WCOPY, false, true>), g, b, 0, s, tb, p);
-    else hipLaunchKernelGGL((adam_update_kernel<GFMT, WCOPY, false, false>), g, b, 0, s, tb, p);
+    if (stats) launch_walk<AdamUpdateOp<GFMT, WCOPY, false, true>>(c, s, adam_update_kernel<GFMT, WCOPY, false, true>, p);
+    else launch_walk<AdamUpdateOp<GFMT, WCOPY, false, false>>(c, s, adam_update_kernel<GFMT, WCOPY, false, false>, p);
   }
 }
 
@@ -1937,7 +2020,7 @@ template <int GFMT>
 void launch_update_variant_g(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, int master, int vfmt) {
   const dim3 g(grid_of(c)), b(kThreads);
   const Tables tb = tables_of(c);
-#define FP8LM_VAR(M, V) hipLaunchKernelGGL((adam_update_var_kernel<GFMT, M, V>), g, b, 0, s, tb, p)
+#define FP8LM_VAR(M, V) launch_walk<AdamUpdateVarOp<GFMT, M, V>>(c, s, adam_update_var_kernel<GFMT, M, V>, p)
   if (vfmt == kStF16) {
     if (master == kStBF16) FP8LM_VAR(kStBF16, kStF16);
     else if (master == kStE4M3) FP8LM_VAR(kStE4M3, kStF16);
@@ -2036,15 +2119,15 @@ fp8lm_status fp8lm_destroy(fp8lm_ctx* c) {
   return FP8LM_OK;
 }
 
-fp8lm_status fp8lm_set_tuning(fp8lm_ctx* c, int32_t chunk_elems, int32_t blocks_per_cu, int32_t min_chunks_per_wg) {
+fp8lm_status fp8lm_set_tuning(fp8lm_ctx* c, int32_t chunk_elems, int32_t blocks_per_cu, int32_t single_pass_min_chunks) {
   if (!c || chunk_elems < kTile || chunk_elems > (1 << 20) || chunk_elems % kTile != 0 || blocks_per_cu < 1 ||
-      blocks_per_cu > kMaxBlocksPerCu || min_chunks_per_wg < 1 || min_chunks_per_wg > 65536)
+      blocks_per_cu > kMaxBlocksPerCu || single_pass_min_chunks < 0 || single_pass_min_chunks > (1 << 30))
     return FP8LM_ERR_INVALID_ARGUMENT;
   DeviceGuard guard(c->device);
   HIP_TRY(hipDeviceSynchronize());
   c->chunk_elems = chunk_elems;
   c->blocks_per_cu = blocks_per_cu;
-  c->min_chunks_per_wg = min_chunks_per_wg;
+  c->single_pass_min_chunks = single_pass_min_chunks;
   return build_tables(c);
 }
 
@@ -2071,9 +2154,9 @@ fp8lm_status fp8lm_amax_scale(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
   hipStream_t s = (hipStream_t)stream;
   const Tables tb = tables_of(c);
   Timed tm(c, s, FP8LM_K_AMAX);
-  if (src_type == FP8LM_SRC_F32) hipLaunchKernelGGL((amax_kernel<kAmaxForGradient, kSrcF32>), g, b, 0, s, tb, p);
-  else if (src_type == FP8LM_SRC_F16) hipLaunchKernelGGL((amax_kernel<kAmaxForGradient, kSrcF16>), g, b, 0, s, tb, p);
-  else hipLaunchKernelGGL((amax_kernel<kAmaxForGradient, kSrcBF16>), g, b, 0, s, tb, p);
+  if (src_type == FP8LM_SRC_F32) launch_walk<AmaxOp<kAmaxForGradient, kSrcF32>>(c, s, amax_kernel<kAmaxForGradient, kSrcF32>, p);
+  else if (src_type == FP8LM_SRC_F16) launch_walk<AmaxOp<kAmaxForGradient, kSrcF16>>(c, s, amax_kernel<kAmaxForGradient, kSrcF16>, p);
+  else launch_walk<AmaxOp<kAmaxForGradient, kSrcBF16>>(c, s, amax_kernel<kAmaxForGradient, kSrcBF16>, p);
   return after_launch();
 }
 
@@ -2112,10 +2195,10 @@ static fp8lm_status cast_impl(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
     Timed tm(c, s, FP8LM_K_CAST);
 #define FP8LM_CAST_LAUNCH(F, S)                                                                           \
     do {                                                                                                    \
-      if (delayed && fuse) hipLaunchKernelGGL((cast_kernel<F, true, true, S>), g, b, 0, s, tb, p);          \
-      else if (delayed) hipLaunchKernelGGL((cast_kernel<F, true, false, S>), g, b, 0, s, tb, p);            \
-      else if (fuse) hipLaunchKernelGGL((cast_kernel<F, false, true, S>), g, b, 0, s, tb, p);               \
-      else hipLaunchKernelGGL((cast_kernel<F, false, false, S>), g, b, 0, s, tb, p);                        \
+      if (delayed && fuse) launch_walk<CastOp<F, true, true, S>>(c, s, cast_kernel<F, true, true, S>, p);          \
+      else if (delayed) launch_walk<CastOp<F, true, false, S>>(c, s, cast_kernel<F, true, false, S>, p);            \
+      else if (fuse) launch_walk<CastOp<F, false, true, S>>(c, s, cast_kernel<F, false, true, S>, p);               \
+      else launch_walk<CastOp<F, false, false, S>>(c, s, cast_kernel<F, false, false, S>, p);                        \
     } while (0)
 #define FP8LM_CAST_SRC(S)                                                                                   \
     do {                                                                                                    \
@@ -2177,9 +2260,9 @@ fp8lm_status fp8lm_requantize_fp8(fp8lm_ctx* c, const uint8_t* src, fp8lm_fmt fm
   RequantParams p{src, src_meta, shared, dst, dst_meta};
   Timed tm(c, (hipStream_t)stream, FP8LM_K_REQUANT);
   if (fmt == FP8LM_E4M3)
-    hipLaunchKernelGGL(requantize_kernel<kE4M3>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
+    launch_walk<RequantOp<kE4M3>>(c, (hipStream_t)stream, requantize_kernel<kE4M3>, p);
   else
-    hipLaunchKernelGGL(requantize_kernel<kE5M2>, dim3(grid_of(c)), dim3(kThreads), 0, (hipStream_t)stream, tables_of(c), p);
+    launch_walk<RequantOp<kE5M2>>(c, (hipStream_t)stream, requantize_kernel<kE5M2>, p);
   return after_launch();
 }
 
@@ -2207,8 +2290,8 @@ fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* c, const uint8_t* const* payloads, int32_t
   const Tables tb = tables_of(c);
 #define FP8LM_SUM_N(N)                                                                          \
   case N:                                                                                       \
-    if (fmt == FP8LM_E4M3) hipLaunchKernelGGL((sum_fp8_kernel<kE4M3, N>), g, b, 0, s, tb, p);   \
-    else hipLaunchKernelGGL((sum_fp8_kernel<kE5M2, N>), g, b, 0, s, tb, p);                     \
+    if (fmt == FP8LM_E4M3) launch_walk<SumOp<kE4M3, N>>(c, s, sum_fp8_kernel<kE4M3, N>, p);   \
+    else launch_walk<SumOp<kE5M2, N>>(c, s, sum_fp8_kernel<kE5M2, N>, p);                     \
     break
   static_assert(kMaxRanks == 8, "one case per rank count");
   switch (n_ranks) {
@@ -2231,16 +2314,16 @@ fp8lm_status fp8lm_init_master_as(fp8lm_ctx* c, const void* w_bf16, void* w_out,
   Timed tm(c, s, FP8LM_K_INIT_MASTER);
   const uint32_t fmax_bits = master_fmt == FP8LM_STATE_F16 ? kBitsF16Max : (master_fmt == FP8LM_STATE_E4M3 ? kBitsE4M3Max : 0u);
   AmaxParams pa{static_cast<const uint16_t*>(w_bf16), w_meta, fmax_bits, 1, 0};
-  hipLaunchKernelGGL((amax_kernel<kAmaxForMaster, kSrcBF16>), dim3(grid_of(c)), dim3(kThreads), 0, s, tables_of(c), pa);
+  launch_walk<AmaxOp<kAmaxForMaster, kSrcBF16>>(c, s, amax_kernel<kAmaxForMaster, kSrcBF16>, pa);
   fp8lm_status st = after_launch();
   if (st != FP8LM_OK) return st;
   InitParams pi{static_cast<const uint16_t*>(w_bf16), w_out, w_meta};
   const dim3 g(grid_of(c)), b(kThreads);
   switch (master_fmt) {
-    case FP8LM_STATE_F16: hipLaunchKernelGGL(init_master_cast_kernel<kStF16>, g, b, 0, s, tables_of(c), pi); break;
-    case FP8LM_STATE_BF16: hipLaunchKernelGGL(init_master_cast_kernel<kStBF16>, g, b, 0, s, tables_of(c), pi); break;
-    case FP8LM_STATE_E4M3: hipLaunchKernelGGL(init_master_cast_kernel<kStE4M3>, g, b, 0, s, tables_of(c), pi); break;
-    default: hipLaunchKernelGGL(init_master_cast_kernel<kStF32>, g, b, 0, s, tables_of(c), pi); break;
+    case FP8LM_STATE_F16: launch_walk<InitCastOp<kStF16>>(c, s, init_master_cast_kernel<kStF16>, pi); break;
+    case FP8LM_STATE_BF16: launch_walk<InitCastOp<kStBF16>>(c, s, init_master_cast_kernel<kStBF16>, pi); break;
+    case FP8LM_STATE_E4M3: launch_walk<InitCastOp<kStE4M3>>(c, s, init_master_cast_kernel<kStE4M3>, pi); break;
+    default: launch_walk<InitCastOp<kStF32>>(c, s, init_master_cast_kernel<kStF32>, pi); break;
   }
   return after_launch();
 }
@@ -2308,10 +2391,10 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
     else hipLaunchKernelGGL((adam_predict_scales_kernel<FP8LM_WCOPY_BF16>), gs, bs, 0, s, tb, p, c->n_tensors);
   } else {
     Timed tm(c, s, FP8LM_K_ADAM_AMAX);
-    if (e5 && q8) hipLaunchKernelGGL((adam_amax_kernel<kE5M2, FP8LM_WCOPY_E4M3>), g, b, 0, s, tb, p);
-    else if (e5) hipLaunchKernelGGL((adam_amax_kernel<kE5M2, FP8LM_WCOPY_BF16>), g, b, 0, s, tb, p);
-    else if (q8) hipLaunchKernelGGL((adam_amax_kernel<kE4M3, FP8LM_WCOPY_E4M3>), g, b, 0, s, tb, p);
-    else hipLaunchKernelGGL((adam_amax_kernel<kE4M3, FP8LM_WCOPY_BF16>), g, b, 0, s, tb, p);
+    if (e5 && q8) launch_walk<AdamAmaxOp<kE5M2, FP8LM_WCOPY_E4M3>>(c, s, adam_amax_kernel<kE5M2, FP8LM_WCOPY_E4M3>, p);
+    else if (e5) launch_walk<AdamAmaxOp<kE5M2, FP8LM_WCOPY_BF16>>(c, s, adam_amax_kernel<kE5M2, FP8LM_WCOPY_BF16>, p);
+    else if (q8) launch_walk<AdamAmaxOp<kE4M3, FP8LM_WCOPY_E4M3>>(c, s, adam_amax_kernel<kE4M3, FP8LM_WCOPY_E4M3>, p);
+    else launch_walk<AdamAmaxOp<kE4M3, FP8LM_WCOPY_BF16>>(c, s, adam_amax_kernel<kE4M3, FP8LM_WCOPY_BF16>, p);
   }
   fp8lm_status st = after_launch();
   if (st != FP8LM_OK) return st;

@@ -174,7 +174,10 @@ def test_free_running_oracle_and_gpu_end_in_the_same_state(name, steps):
     fr.assert_equal_to(st, f"{name} after {steps} free-running steps")
 
 
-@pytest.mark.parametrize("tuning", [(4096, 1, 1), (4096, 16, 1), (65536, 4, 2), (1048576, 2, 64), (16384, 16, 1)])
+# chunk size, workgroups per CU, and both forms of the cross-workgroup reduction (third entry 0: tickets in the
+# same launch; large: a second launch finishes the tensors)
+@pytest.mark.parametrize("tuning", [(4096, 1, 0), (4096, 16, 0), (65536, 4, 0), (1048576, 2, 0), (16384, 16, 0),
+                                    (4096, 16, 1 << 20), (16384, 3, 1 << 20), (262144, 16, 1 << 20)])
 def test_launch_shapes_give_identical_results(tuning):
     wl = synth.workload("tiny")
     run_lockstep(wl, seed=5, steps=2, exact=1, stats=1, tuning=tuning)
