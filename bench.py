@@ -166,7 +166,7 @@ def main() -> int:
                         grad_buffer=True)
     if args.chunk or args.blocks_per_cu or args.single_pass_min_chunks >= 0:
         st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 16,
-                          64 if args.single_pass_min_chunks < 0 else args.single_pass_min_chunks)
+                          (1 << 30) if args.single_pass_min_chunks < 0 else args.single_pass_min_chunks)
     grad = st.grad
     placement = {"spread_over_hbm_regions": st.spread, **{k: v for k, v in st.placement.items() if k != "where"}}
     if st.spread:

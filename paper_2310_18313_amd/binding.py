@@ -210,7 +210,7 @@ class Context:
         except Exception:  # interpreter shutdown
             pass
 
-    def set_tuning(self, chunk_elems=16384, blocks_per_cu=16, single_pass_min_chunks=64):
+    def set_tuning(self, chunk_elems=16384, blocks_per_cu=16, single_pass_min_chunks=1 << 30):
         _check(lib().fp8lm_set_tuning(self._h, chunk_elems, blocks_per_cu, single_pass_min_chunks), "fp8lm_set_tuning")
 
     def new_meta(self, cfg: AutoscaleCfg, stream=None) -> torch.Tensor:

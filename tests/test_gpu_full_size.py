@@ -34,11 +34,13 @@ def sample_ids(layout):
     return small, sorted(big)
 
 
-def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False, paths=None):
+def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False, paths=None, tuning=None):
     lay = wl.layout
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
     st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=True, grad_buffer=True)
-    say(f"{wl.name}: {lay.n_tensors} tensors, {lay.n_params} params, spread={st.spread}")
+    if tuning:
+        st.ctx.set_tuning(*tuning)
+    say(f"{wl.name}: {lay.n_tensors} tensors, {lay.n_params} params, spread={st.spread}, tuning={tuning}")
     grad = st.grad
     synth.fill_weights(grad, lay, seed)
     st.init_master(grad)
@@ -93,8 +95,10 @@ def test_gpt175b_layer_heavy_tails_hundred_steps():
     lay = wl.layout
     proj = lay.names.index("l0.proj.w")
     checked = {1, 2, 3, 10, 11, 20, 21, 22, 23, 24, 50, 99, 100}
+    # this one combines the workgroups' statistics through tickets in the same launch (third tuning entry 0);
+    # the other two use the default, a second launch
     st, tot, mus = run(wl, seed=5, steps=100, small_steps=checked, big_steps={1, 24, 100}, big_ids=[proj],
-                       track_mu=True)
+                       track_mu=True, tuning=(16384, 16, 0))
     mus = np.array(mus)                            # [step, tensor]
     # Large matrices: the amax is set by a rare outlier, so even mu = 2 clips far fewer than 0.001 % of
     # the elements and mu climbs to 2 and stays.  Small tensors (< 100 000 elements) overflow whenever
