@@ -1573,16 +1573,8 @@ struct AdamUpdateOp {
   }
 };
 
-#ifndef FP8LM_UPDATE_WAVES
-#define FP8LM_UPDATE_WAVES 0
-#endif
-#if FP8LM_UPDATE_WAVES > 0
-#define FP8LM_UPDATE_ATTR __attribute__((amdgpu_waves_per_eu(FP8LM_UPDATE_WAVES)))
-#else
-#define FP8LM_UPDATE_ATTR
-#endif
 template <int GFMT, int WCOPY, bool FAST, bool STATS>
-__global__ __launch_bounds__(kThreads) FP8LM_UPDATE_ATTR void adam_update_kernel(Tables tb, AdamParams p) {
+__global__ __launch_bounds__(kThreads) void adam_update_kernel(Tables tb, AdamParams p) {
   AdamUpdateOp<GFMT, WCOPY, FAST, STATS> op(p, tb);
   walk_chunks<FP8LM_UN_UPDATE>(tb, op);
 }
