@@ -21,6 +21,9 @@
  *     Data-dependent conditions (non-finite inputs, all-zero tensors, saturation) are reported in the
  *     metadata flags and counters on the device, never in the return value.
  *   - Tensors with numel == 0 are skipped: their metadata is left untouched.
+ *   - Parameter groups (other hyper-parameters for some tensors, e.g. no weight decay on biases): one
+ *     context per group, over disjoint tensor lists of the same flat buffers, each with its own
+ *     metadata arrays (indexed by the position in its own list) and stepped with its own calls.
  */
 #ifndef FP8LM_H
 #define FP8LM_H

@@ -15,7 +15,11 @@ from .placement import SpreadAllocator
 class OptimizerState:
     def __init__(self, tensors, total_elems: int, cfg: B.AutoscaleCfg, device: int = 0,
                  grad_fmt: int = B.E5M2, wcopy: int = B.WCOPY_E4M3, spread: bool = False,
-                 grad_buffer: bool = False, master_fmt: int = B.STATE_F16, v_fmt: int = B.STATE_F16):
+                 grad_buffer: bool = False, master_fmt: int = B.STATE_F16, v_fmt: int = B.STATE_F16,
+                 share_with: "OptimizerState" = None):
+        """`share_with`: another state over the same flat buffers.  Parameter groups (say, no weight decay on
+        biases and LayerNorm weights) are one state each, over disjoint tensor lists of the same buffers; each
+        has its own context and metadata and is stepped with its own hyper-parameters."""
         dev = torch.device(f"cuda:{device}")
         self.tensors = list(tensors)
         self.total = int(total_elems)
@@ -34,7 +38,15 @@ class OptimizerState:
                 [("w", n, state_dtype[master_fmt])],
                 [("m", n, torch.uint8), ("g8", n, torch.uint8), ("wq", n, qdt)]]
         self.placement = {}
-        if spread:
+        if share_with is not None:
+            o = share_with
+            assert (o.grad_fmt, o.wcopy_kind, o.master_fmt, o.v_fmt) == (grad_fmt, wcopy, master_fmt, v_fmt)
+            assert o.g8.numel() >= n
+            bufs = dict(g8=o.g8, m=o.m, v=o.v, w=o.w, wq=o.wq)
+            if o.grad is not None:
+                bufs["grad"] = o.grad
+            self.spread = o.spread
+        elif spread:
             alloc = SpreadAllocator(self.ctx, device)
             bufs = alloc.allocate(plan)
             self.spread = alloc.spread

@@ -671,3 +671,36 @@ def test_a_step_replayed_from_a_hip_graph_equals_the_eager_step():
         torch.cuda.synchronize()
         for k in names:
             assert torch.equal(getattr(st, k), want[k]), f"replay {rep}: {k} differs from the eager step"
+
+
+# ---- parameter groups: one context per group over the same flat buffers ---------------------------------------
+def test_parameter_groups_share_the_flat_buffers():
+    """Weight decay on the matrices, none on biases and LayerNorm weights: two tensor lists, two contexts, the
+    same buffers.  Every tensor must come out as the oracle computes it with its own group's hyper-parameters,
+    and no group may touch the other's elements."""
+    wl = synth.Workload("groups", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-3, sigma=None)
+    lay = wl.layout
+    decay = [i for i, nm in enumerate(lay.names) if nm.endswith(".w") and "ln" not in nm or nm == "emb"]
+    plain = [i for i in range(lay.n_tensors) if i not in decay]
+    assert decay and plain
+    cfg = B.autoscale_cfg()
+    tens = lay.tensors()
+    st_d = OptimizerState([tens[i] for i in decay], lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
+    st_p = OptimizerState([tens[i] for i in plain], lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, share_with=st_d)
+    w0 = torch.zeros(max(lay.total, 16), dtype=torch.bfloat16, device=DEV)
+    synth.fill_weights(w0, lay, 17)
+    st_d.init_master(w0)
+    st_p.init_master(w0)
+    grad = torch.zeros(max(lay.total, 16), dtype=torch.bfloat16, device=DEV)
+    for step in (1, 2, 3):
+        synth.fill_gradients(grad, wl, 17, step)
+        hp_d = B.adam_hparams(wl.lr, step, weight_decay=0.1)
+        hp_p = B.adam_hparams(wl.lr, step, weight_decay=0.0)
+        snaps_d = [P.Snapshot(st_d, grad, t) for t in range(len(decay))]
+        snaps_p = [P.Snapshot(st_p, grad, t) for t in range(len(plain))]
+        say(f"parameter groups step {step}: {len(decay)} + {len(plain)} tensors")
+        st_d.step(grad, hp_d)
+        st_p.step(grad, hp_p)
+        torch.cuda.synchronize()
+        P.check_step(st_d, snaps_d, hp_d, what=f"decay group step {step}")
+        P.check_step(st_p, snaps_p, hp_p, what=f"no-decay group step {step}")
