@@ -125,6 +125,7 @@ def main() -> int:
     ap.add_argument("--workload", default="gpt13b")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle work the cpu_baseline leg aims for")
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--single-pass-min-chunks", type=int, default=-1,
@@ -303,7 +304,7 @@ def main() -> int:
     if extra:
         out["allreduce_steps"] = extra
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, args.seed)
+        out["cpu_baseline"] = cpu_baseline(wl, args.seed, budget_s=args.cpu_budget)
     print(json.dumps(out), flush=True)
     return 0
 
