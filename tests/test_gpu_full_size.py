@@ -109,3 +109,24 @@ def test_gpt175b_layer_heavy_tails_hundred_steps():
     assert (mus[:, small] == -1).any() and (mus[:, small] == 0).any() and (mus[:, small] == 1).any()
     gm = B.meta_to_numpy(st.g_meta, lay.n_tensors)
     assert gm["n_sat"].sum() > 0
+
+
+def test_gpt175b_layer_with_the_papers_ramp_of_a_thousand_steps():
+    """Same layer and gradients with the ramp length the paper states (Sec. 2.1: back up over 1000 steps): within a
+    dozen steps nothing can climb, so a tensor that overflowed sits at mu = 1/2 and the others stay at mu = 1."""
+    wl = synth.workload("gpt175b_layer")
+    wl.ramp_steps = 1000
+    lay = wl.layout
+    st, tot, mus = run(wl, seed=5, steps=12, small_steps=set(range(1, 13)), big_steps={12},
+                       big_ids=[lay.names.index("l0.proj.w")], track_mu=True)
+    mus = np.array(mus)
+    big = [t for t, n in enumerate(lay.numels) if n > SMALL]
+    small = [t for t, n in enumerate(lay.numels) if 0 < n <= SMALL]
+    assert (mus[:, big] == 0).all()                                    # mu = 1 throughout
+    assert set(np.unique(mus[:, small])) <= {-1, 0}                    # mu = 1 until the first overflow, then 1/2
+    gm = B.meta_to_numpy(st.g_meta, lay.n_tensors)
+    overflowed = [t for t in small if (mus[:, t] == -1).any()]
+    assert overflowed, "no small tensor put its largest element on the top code in 12 steps"
+    for t in overflowed:
+        first = int(np.argmax(mus[:, t] == -1))
+        assert (mus[first:, t] == -1).all() and gm["clean_steps"][t] < 500
