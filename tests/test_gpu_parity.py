@@ -704,3 +704,50 @@ def test_parameter_groups_share_the_flat_buffers():
         torch.cuda.synchronize()
         P.check_step(st_d, snaps_d, hp_d, what=f"decay group step {step}")
         P.check_step(st_p, snaps_p, hp_p, what=f"no-decay group step {step}")
+
+
+# ---- randomised differential test -----------------------------------------------------------------------------
+def test_random_layouts_and_hyper_parameters_match_the_oracle():
+    """Sixty seeded random cases: ragged tensor sizes, gradient scales over forty binades, hyper-parameters at and
+    between the ends of their ranges, every format, source type, moment-scale mode and both gradient scalings."""
+    rng = np.random.default_rng(20231018)
+    dtypes = [torch.bfloat16, torch.float16, torch.float32]
+    for case in range(60):
+        n_t = int(rng.integers(1, 7))
+        numels = [int(rng.choice([0, 1, 15, 16, 17, 255, 4095, 4096, 4097, int(rng.integers(1, 70000))])) for _ in range(n_t)]
+        if sum(numels) == 0:
+            numels[0] = 33
+        lay = synth.Layout([f"t{i}" for i in range(n_t)], numels)
+        dtype = dtypes[case % 3]
+        lo = -6 if dtype == torch.float16 else -20
+        sig = float(2.0 ** rng.integers(lo, 6))
+        wl = synth.Workload(f"rnd{case}", lay, lr=1e-3, sigma=sig, grad_kind=["normal", "student_t"][case % 2],
+                            ramp_steps=int(rng.choice([2, 4, 20])), hist_window=int(rng.choice([1, 1, 3, 16])))
+        grad_fmt = [B.E5M2, B.E4M3][int(rng.integers(0, 2))]
+        wcopy = [B.WCOPY_E4M3, B.WCOPY_BF16][int(rng.integers(0, 2))]
+        master_fmt, v_fmt = B.STATE_F16, B.STATE_F16
+        if wcopy == B.WCOPY_E4M3 and rng.random() < 0.4:
+            master_fmt = int(rng.choice([B.STATE_F16, B.STATE_BF16, B.STATE_E4M3, B.STATE_F32]))
+            v_fmt = int(rng.choice([B.STATE_F16, B.STATE_E4M3]))
+        st, _ = P.make_state(wl, case, grad_fmt, wcopy, master_fmt=master_fmt, v_fmt=v_fmt)
+        if rng.random() < 0.5:
+            st.ctx.set_tuning(int(rng.choice([4096, 16384])), int(rng.integers(1, 17)), int(rng.choice([0, 1 << 30])))
+        ids = list(range(n_t))
+        grad = torch.zeros(max(lay.total, 16), dtype=dtype, device=DEV)
+        step0 = int(rng.choice([1, 1, 2, 1000, 10 ** 6]))
+        for k in range(3):
+            synth.fill_gradients(grad, wl, case, k + 1)
+            hp = B.adam_hparams(lr=float(rng.choice([0.0, 1e-5, 1e-3, 0.5, 1024.0])), step=step0 + k,
+                                beta1=float(rng.choice([0.0, 0.5, 0.9, 0.999])), beta2=float(rng.choice([0.0, 0.5, 0.95, 0.9999])),
+                                eps=float(rng.choice([2.0 ** -36, 1e-8, 1e-3, 1.0])), weight_decay=float(rng.choice([0.0, 0.1, 10.0])),
+                                v_scaled=int(rng.integers(0, 2)) if (master_fmt, v_fmt) == (B.STATE_F16, B.STATE_F16) else 1,
+                                wcopy=wcopy, stats=int(rng.integers(0, 2)) if (master_fmt, v_fmt) == (B.STATE_F16, B.STATE_F16) else 0,
+                                m_scale_mode=int(rng.integers(0, 3)), master_fmt=master_fmt, v_fmt=v_fmt)
+            delayed = bool(rng.integers(0, 2)) and k > 0
+            snaps = [P.Snapshot(st, grad, t) for t in ids]
+            say(f"random case {case} step {k}: numels={numels} dtype={dtype} sigma={sig:g} fmt={grad_fmt} wcopy={wcopy} "
+                f"master={master_fmt} v={v_fmt} lr={hp.lr:g} b1={hp.beta1:g} b2={hp.beta2:g} eps={hp.eps:g} wd={hp.weight_decay:g} "
+                f"t={hp.step} v_scaled={hp.v_scaled} stats={hp.stats} mode={hp.m_scale_mode} delayed={delayed}")
+            st.step(grad, hp, delayed=delayed)
+            torch.cuda.synchronize()
+            P.check_step(st, snaps, hp, what=f"random case {case} step {k}", delayed=delayed)
