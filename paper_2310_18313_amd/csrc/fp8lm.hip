@@ -1288,7 +1288,8 @@ struct AdamUpdateOp {
   bool careful;
   float vmax, wmax, mmax;                 // running maxima of v', |w'| (and |m'| on the careful path)
   uint32_t nf;
-  uint32_t cnt[8];                        // sat m,v,w,q ; underflow m,v,w,q
+  uint32_t cnt[8];                        // sat m,v,w,q ; underflow m,v,w,q: per lane (tails, careful path)
+  uint32_t wcnt[8];                       // the same for whole tiles: wave totals, identical in every lane
   __device__ AdamUpdateOp(const AdamParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
   __device__ __forceinline__ void begin(int t, const TensorDesc&) {
     const Scratch::Pending& P = tb.scratch[t].pend;
@@ -1301,25 +1302,37 @@ struct AdamUpdateOp {
     vmax = wmax = mmax = 0.0f;
     nf = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) cnt[i] = 0;
+    for (int i = 0; i < 8; ++i) cnt[i] = wcnt[i] = 0;
   }
 
-  // exact counters, from the scaled values before clamping
+  // Exact counters, from the scaled values before clamping.  WAVE: called by all 64 lanes together (whole
+  // tiles); a condition then costs one compare, the count of lanes that meet it is taken from the lane mask
+  // with scalar instructions and kept once per wavefront instead of once per lane.
+  template <bool WAVE> __device__ __forceinline__ void count(int i, bool cond) {
+    if constexpr (WAVE) wcnt[i] += (uint32_t)__popcll(__ballot(cond));
+    else cnt[i] += cond;
+  }
+  // both conditions hold; WAVE: the two lane masks are combined with one scalar instruction
+  template <bool WAVE> __device__ __forceinline__ void count2(int i, bool a, bool b) {
+    if constexpr (WAVE) wcnt[i] += (uint32_t)__popcll(__ballot(a) & __ballot(b));
+    else cnt[i] += a && b;
+  }
+  template <bool WAVE>
   __device__ __forceinline__ void stats(float m1, float v1, float w1, float tm, float tv, float tw, float tq) {
     if constexpr (STATS) {
-      cnt[0] += fabsf(tm) >= 432.0f;                       // rounds to (or beyond) the top E4M3 code
-      cnt[1] += fabsf(tv) > 65488.0f;                      // rounds to the top FP16 code
-      cnt[2] += fabsf(tw) > 65488.0f;
-      cnt[4] += (fabsf(tm) <= 0x1p-10f) && (m1 != 0.0f);   // rounds to zero
-      cnt[5] += (fabsf(tv) <= 0x1p-25f) && (v1 != 0.0f);
-      cnt[6] += (fabsf(tw) <= 0x1p-25f) && (w1 != 0.0f);
+      count<WAVE>(0, fabsf(tm) >= 432.0f);                       // rounds to (or beyond) the top E4M3 code
+      count<WAVE>(1, fabsf(tv) > 65488.0f);                      // rounds to the top FP16 code
+      count<WAVE>(2, fabsf(tw) > 65488.0f);
+      count2<WAVE>(4, fabsf(tm) <= 0x1p-10f, m1 != 0.0f);        // rounds to zero
+      count2<WAVE>(5, fabsf(tv) <= 0x1p-25f, v1 != 0.0f);
+      count2<WAVE>(6, fabsf(tw) <= 0x1p-25f, w1 != 0.0f);
       if constexpr (WCOPY == FP8LM_WCOPY_E4M3) {
-        cnt[3] += fabsf(tq) >= 432.0f;
-        cnt[7] += (fabsf(tq) <= 0x1p-10f) && (w1 != 0.0f);
+        count<WAVE>(3, fabsf(tq) >= 432.0f);
+        count2<WAVE>(7, fabsf(tq) <= 0x1p-10f, w1 != 0.0f);
       } else {
         const uint32_t ab = f2u(w1) & 0x7FFFFFFFu;
-        cnt[3] += (ab >= 0x7F7F8000u) && (ab <= 0x7F800000u);   // rounds to infinity
-        cnt[7] += (ab <= 0x00008000u) && (ab != 0u);
+        count<WAVE>(3, (ab - 0x7F7F8000u) <= 0x8000u);          // 0x7F7F8000 .. 0x7F800000: rounds to infinity
+        count<WAVE>(7, (ab - 1u) < 0x8000u);                    // 1 .. 0x8000: rounds to zero
       }
     }
   }
@@ -1327,6 +1340,7 @@ struct AdamUpdateOp {
   struct Quad { uint32_t m, v01, v23, w01, w23, q, q2; };
 
   // four elements: one word of gradient codes, one of moment codes, two words each of v and w
+  template <bool WAVE>
   __device__ __forceinline__ Quad quad(uint32_t gw, uint32_t mw, uint32_t v01, uint32_t v23, uint32_t w01, uint32_t w23) {
     const float2_t dg01 = fp8x2_to_f32<GFMT, false>(gw), dg23 = fp8x2_to_f32<GFMT, true>(gw);
     const float2_t dm01 = fp8x2_to_f32<kE4M3, false>(mw), dm23 = fp8x2_to_f32<kE4M3, true>(mw);
@@ -1351,7 +1365,7 @@ struct AdamUpdateOp {
       tw[j] = w1 * sw;
       tq[j] = w1 * sq;
       w1s[j] = w1;
-      stats(m1, v1, w1, tm[j], tv[j], tw[j], tq[j]);
+      stats<WAVE>(m1, v1, w1, tm[j], tv[j], tw[j], tq[j]);
     }
     Quad o;
     o.m = encode4_fp8<kE4M3>(tm[0], tm[1], tm[2], tm[3]);
@@ -1393,7 +1407,7 @@ struct AdamUpdateOp {
     if (am <= kMaxF) mmax = fmaxf(mmax, am); else nf |= (m1 != m1) ? 1u : 2u;
     if (av <= kMaxF) vmax = fmaxf(vmax, av); else nf |= (v1 != v1) ? 4u : 8u;
     if (aw <= kMaxF) wmax = fmaxf(wmax, aw); else nf |= (w1 != w1) ? 16u : 32u;
-    stats(m1, v1, w1, tm, tv, tw, tq);
+    stats<false>(m1, v1, w1, tm, tv, tw, tq);
   }
 
   __device__ __forceinline__ bool fast() const { return !careful; }
@@ -1421,10 +1435,10 @@ struct AdamUpdateOp {
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       const long long a = pos0 + u * kTile, b = a + kTile / 2;
-      const Quad q0 = quad(ga[u].x, ma[u].x, va[u].x, va[u].y, wa[u].x, wa[u].y);
-      const Quad q1 = quad(ga[u].y, ma[u].y, va[u].z, va[u].w, wa[u].z, wa[u].w);
-      const Quad q2 = quad(gb[u].x, mb[u].x, vb[u].x, vb[u].y, wb[u].x, wb[u].y);
-      const Quad q3 = quad(gb[u].y, mb[u].y, vb[u].z, vb[u].w, wb[u].z, wb[u].w);
+      const Quad q0 = quad<true>(ga[u].x, ma[u].x, va[u].x, va[u].y, wa[u].x, wa[u].y);
+      const Quad q1 = quad<true>(ga[u].y, ma[u].y, va[u].z, va[u].w, wa[u].z, wa[u].w);
+      const Quad q2 = quad<true>(gb[u].x, mb[u].x, vb[u].x, vb[u].y, wb[u].x, wb[u].y);
+      const Quad q3 = quad<true>(gb[u].y, mb[u].y, vb[u].z, vb[u].w, wb[u].z, wb[u].w);
       st8<kNtStoreRW>(p.m + a, make_uint2(q0.m, q1.m));
       st8<kNtStoreRW>(p.m + b, make_uint2(q2.m, q3.m));
       st16<kNtStoreRW>(pv + a, make_uint4(q0.v01, q0.v23, q1.v01, q1.v23));
@@ -1464,10 +1478,10 @@ struct AdamUpdateOp {
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       const long long pos = pos0 + u * kTile;
-      const Quad q0 = quad(g[u].x, m[u].x, va[u].x, va[u].y, wa[u].x, wa[u].y);
-      const Quad q1 = quad(g[u].y, m[u].y, va[u].z, va[u].w, wa[u].z, wa[u].w);
-      const Quad q2 = quad(g[u].z, m[u].z, vb[u].x, vb[u].y, wb[u].x, wb[u].y);
-      const Quad q3 = quad(g[u].w, m[u].w, vb[u].z, vb[u].w, wb[u].z, wb[u].w);
+      const Quad q0 = quad<true>(g[u].x, m[u].x, va[u].x, va[u].y, wa[u].x, wa[u].y);
+      const Quad q1 = quad<true>(g[u].y, m[u].y, va[u].z, va[u].w, wa[u].z, wa[u].w);
+      const Quad q2 = quad<true>(g[u].z, m[u].z, vb[u].x, vb[u].y, wb[u].x, wb[u].y);
+      const Quad q3 = quad<true>(g[u].w, m[u].w, vb[u].z, vb[u].w, wb[u].z, wb[u].w);
       st16<kNtStoreRW>(p.m + pos, make_uint4(q0.m, q1.m, q2.m, q3.m));
       st16<kNtStoreRW>(pv + pos, make_uint4(q0.v01, q0.v23, q1.v01, q1.v23));
       st16<kNtStoreRW>(pv + pos + 8, make_uint4(q2.v01, q2.v23, q3.v01, q3.v23));
@@ -1489,7 +1503,7 @@ struct AdamUpdateOp {
       uint16_t* pw = static_cast<uint16_t*>(p.w);
       for (int j = 0; j < valid; ++j) {
         const long long i = pos + j;
-        const Quad o = quad(p.grad[i], p.m[i], pv[i], 0u, pw[i], 0u);
+        const Quad o = quad<false>(p.grad[i], p.m[i], pv[i], 0u, pw[i], 0u);
         p.m[i] = (uint8_t)o.m;
         pv[i] = (uint16_t)o.v01;
         pw[i] = (uint16_t)o.w01;
@@ -1508,8 +1522,9 @@ struct AdamUpdateOp {
     s.mx[1] = f2u(wmax);
     s.mx[2] = f2u(mmax);
     if constexpr (STATS) {
+      const bool first_lane = (threadIdx.x & 63) == 0;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) s.ct[i] = cnt[i];
+      for (int i = 0; i < 8; ++i) s.ct[i] = cnt[i] + (first_lane ? wcnt[i] : 0u);
     }
     s.orv = nf;
     block_combine(s);
