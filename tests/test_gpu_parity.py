@@ -239,6 +239,19 @@ def test_empty_layouts_and_empty_tensors():
     assert torch.equal(before, meta2)
 
 
+def test_tensor_lists_beyond_the_tables_are_refused():
+    """The chunk table is indexed with 32 bits: a list that needs more chunks is refused at creation, before
+    anything is allocated; so are overlapping and misaligned lists."""
+    for tensors, status in (([(0, 1 << 46)], -5), ([(0, 1 << 45), (1 << 45, 1 << 45)], -5),
+                            ([(0, 100), (96, 100)], -3), ([(8, 100)], -2), ([(0, -1)], -1)):
+        with pytest.raises(B.Fp8lmError) as e:
+            B.Context(tensors)
+        assert e.value.status == status, (tensors, e.value.status)
+    big = B.Context([(0, (1 << 31) + 16), ((1 << 33), 4096)])     # sizes and offsets past 32 bits are fine
+    assert big.required_elems == (1 << 33) + 4096
+    big.close()
+
+
 def test_argument_errors_are_reported_not_launched():
     lay = synth.flat_layout(1024)
     cfg = B.autoscale_cfg()
