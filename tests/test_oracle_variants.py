@@ -136,6 +136,24 @@ def test_predicted_scale_equals_just_in_time_when_the_bound_is_attained():
         assert np.array_equal(sts[0].m, sts[1].m)
 
 
+def test_predicted_bound_is_built_from_the_stored_gradient_not_from_its_amax():
+    """beta1 = 0 and m = 0: the new moment is the stored gradient itself, so the bound must be the stored amax.
+    The largest gradient, 1.8125, is stored as 1.75 in E5M2: the two differ across the 1.75 * 2^k edge of
+    E4M3's range, and only the stored value gives the scale that puts it on 448."""
+    n = 64
+    lay = synth.flat_layout(n)
+    wbits = np.zeros(lay.total, dtype=np.uint16)
+    g = np.zeros(lay.total, dtype=np.uint16)
+    g[:n] = bf16_bits(np.linspace(-0.5, 0.5, n))
+    g[7] = bf16_bits(np.array([1.8125]))[0]
+    sts = [State(lay, wbits), State(lay, wbits)]
+    for mode, st in enumerate(sts):
+        st.step(g, O.AdamHparams(1e-3, 0.0, 0.95, 1e-8, 0.0, 1, 1, O.WCOPY_E4M3, mode))
+        assert st.g_meta[0]["amax"] == np.float32(1.8125) and st.g_meta[0]["amax_deq"] == np.float32(1.75)
+        assert st.m_meta[0]["scale"] == 256.0 and st.m[7] == 0x7E            # 1.75 * 256 = 448, the top code
+    assert np.array_equal(sts[0].m, sts[1].m)
+
+
 # ---- shared-scale re-quantisation and the FP8 sum (Sec. 2.1, Eq. 4-6) -------------------------------
 def _ranks(n_ranks, fmt, seed=0, spread=(1.0, 0.3, 5.0, 0.02)):
     """Every rank casts its own gradient of the same layout just in time."""
