@@ -132,7 +132,8 @@ def main() -> int:
                     help="chunks per workgroup below which tensors are finished by a second launch (0: never)")
     ap.add_argument("--exact", type=int, default=1)
     ap.add_argument("--stats", type=int, default=0)
-    ap.add_argument("--copy-ceiling", action="store_true", help="also time a plain 128-bit copy kernel")
+    ap.add_argument("--copy-ceiling", action="store_true", help="(always on: a plain 128-bit copy kernel is timed beside the step)")
+    ap.add_argument("--no-copy-ceiling", action="store_true")
     ap.add_argument("--path", choices=["jit", "fused", "single"], default="jit",
                     help="jit: amax pass + cast + two-pass Adam (19 B/param, the three entry points as they are); "
                          "fused: same results, the cast also does the Adam step's first pass (18 B/param, one GPU "
@@ -269,15 +270,16 @@ def main() -> int:
             graph.replay()
         torch.cuda.synchronize()
         out["graph_replay_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
-    if args.copy_ceiling:
-        nbytes = min(lay.total, 1 << 32)
+    if not args.no_copy_ceiling and lay.total >= (1 << 20):
+        nbytes = min(lay.total // 16 * 16, 1 << 32)
         st.ctx.set_timing(True)
         st.ctx.get_timing()
         for _ in range(5):
             st.ctx.copy_bytes(st.m, st.g8, nbytes)
         n, ms = st.ctx.get_timing()["copy"]
         st.ctx.set_timing(False)
-        out["copy_kernel_GBps"] = round(2 * nbytes / (ms / n * 1e-3) / 1e9, 1)
+        out["copy_kernel_GBps"] = round(2 * nbytes / (ms / n * 1e-3) / 1e9, 1)     # m -> FP8 gradient buffer, same region
+        out["step_frac_of_copy_kernel"] = round(out["step_GBps"] / out["copy_kernel_GBps"], 4)
     if args.allreduce_steps:
         N = args.allreduce_steps
         ranks = [st.g8] + [st.g8.clone() for _ in range(N - 1)]
