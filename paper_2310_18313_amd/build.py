@@ -7,7 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "fp8lm.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "formats.hpp"), os.path.join(ROOT, "include", "fp8lm.h")]
+DEPS = [SRC, os.path.join(ROOT, "include", "fp8lm.h")] + [
+    os.path.join(HERE, "csrc", h) for h in ("formats.hpp", "walk.hpp", "quantize.hpp", "adam.hpp", "stats.hpp")]
 LIB = os.path.join(HERE, "libfp8lm.so")
 
 HIPCC_FLAGS = [

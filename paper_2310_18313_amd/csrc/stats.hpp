@@ -1,0 +1,158 @@
+// Quantisation-error statistics of an FP8 gradient (Sec. 3.3, communication ablation) and the small
+// utility kernels (metadata initialisation, streaming copy).
+#ifndef FP8LM_STATS_HPP
+#define FP8LM_STATS_HPP
+
+#include "walk.hpp"
+
+namespace fp8lm {
+
+// ================================================================================================
+// Quantisation error of an FP8 gradient against a high-precision reference (Sec. 3.3, the figure
+// of the communication ablation: SNR, underflow rate, overflow rate)
+// ================================================================================================
+struct StatsParams {
+  const void* ref;
+  const uint8_t* q;
+  const fp8lm_meta* meta;
+  fp8lm_quant_stats* out;
+};
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+// workgroup-wide sum of two doubles; result valid in thread 0
+__device__ __forceinline__ void block_sum2_f64(double& a, double& b) {
+  __shared__ double l[kWaves][2];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  a = wave_sum_f64(a);
+  b = wave_sum_f64(b);
+  __syncthreads();
+  if (lane == 0) { l[wave][0] = a; l[wave][1] = b; }
+  __syncthreads();
+  if (threadIdx.x == 0)
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) { a += l[w][0]; b += l[w][1]; }
+}
+
+template <int FMT, int SRC>
+struct QuantStatsOp {
+  using elem_t = typename SrcTraits<SRC>::elem_t;
+  static constexpr int kPer = 16 / (int)sizeof(elem_t);
+  static constexpr int kLoads = kGroup / kPer;
+  static constexpr int kW = kSrcWords<SRC>;
+  const StatsParams& p;
+  double rs, signal, noise;
+  uint32_t n_nonzero, n_under, n_over, n_nonfinite;
+  __device__ QuantStatsOp(const StatsParams& p_) : p(p_) {}
+  __device__ __forceinline__ void begin(int t, const TensorDesc&) {
+    rs = 1.0 / (double)p.meta[t].scale;
+    signal = noise = 0.0;
+    n_nonzero = n_under = n_over = n_nonfinite = 0;
+  }
+  __device__ __forceinline__ bool fast() const { return true; }
+  __device__ __forceinline__ void one(uint32_t rbits, uint32_t code) {
+    const float r = SrcTraits<SRC>::dec(rbits);
+    const float pv = fp8_to_f32<FMT>(code);
+    if (!(fabsf(r) <= 3.4028234664e38f) || !(fabsf(pv) <= 3.4028234664e38f)) {
+      ++n_nonfinite;
+      return;
+    }
+    const double rd = (double)r;
+    const double e = rd - (double)pv * rs;
+    signal += rd * rd;
+    noise += e * e;
+    const uint32_t mag = code & 0x7Fu;
+    n_nonzero += (r != 0.0f);
+    n_under += (r != 0.0f) && mag == 0u;
+    n_over += mag == Fp8Traits<FMT>::kTop;
+  }
+  template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
+    const long long pos = pos0 + threadIdx.x * kGroup;
+    const elem_t* rp = static_cast<const elem_t*>(p.ref) + pos;
+    uint4 r[UN][kLoads], qq[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+#pragma unroll
+      for (int k = 0; k < kLoads; ++k) r[u][k] = ld16<kNtLoadRO>(rp + u * kTile + k * kPer);
+      qq[u] = ld16<kNtLoadRO>(p.q + pos + u * kTile);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      uint32_t w[kW];
+#pragma unroll
+      for (int k = 0; k < kLoads; ++k) {
+        w[4 * k] = r[u][k].x; w[4 * k + 1] = r[u][k].y; w[4 * k + 2] = r[u][k].z; w[4 * k + 3] = r[u][k].w;
+      }
+      const uint32_t qw[4] = {qq[u].x, qq[u].y, qq[u].z, qq[u].w};
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const uint32_t bits = kSrc16<SRC> ? (w[(j >> 1) % kW] >> ((j & 1) * 16)) & 0xFFFFu : w[j % kW];
+        one(bits, (qw[j >> 2] >> ((j & 3) * 8)) & 0xFFu);
+      }
+    }
+  }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    const elem_t* rp = static_cast<const elem_t*>(p.ref) + pos;
+    for (int j = 0; j < valid; ++j) one(rp[j], p.q[pos + j]);
+  }
+  __device__ __forceinline__ void flush(int t, const TensorDesc&, int) {
+    BlockStats<0, 4> s;
+    s.ct[0] = n_nonzero; s.ct[1] = n_under; s.ct[2] = n_over; s.ct[3] = n_nonfinite;
+    s.orv = 0;
+    block_combine(s);
+    block_sum2_f64(signal, noise);
+    if (threadIdx.x == 0) {
+      fp8lm_quant_stats* o = p.out + t;
+      if (signal != 0.0) __hip_atomic_fetch_add(&o->signal, signal, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (noise != 0.0) __hip_atomic_fetch_add(&o->noise, noise, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      atomic_add_u64(reinterpret_cast<unsigned long long*>(&o->n_nonzero), s.ct[0]);
+      atomic_add_u64(reinterpret_cast<unsigned long long*>(&o->n_underflow), s.ct[1]);
+      atomic_add_u64(reinterpret_cast<unsigned long long*>(&o->n_overflow), s.ct[2]);
+      atomic_add_u64(reinterpret_cast<unsigned long long*>(&o->n_nonfinite), s.ct[3]);
+    }
+  }
+};
+
+template <int FMT, int SRC>
+__global__ __launch_bounds__(kThreads) void quant_stats_kernel(Tables tb, StatsParams p) {
+  QuantStatsOp<FMT, SRC> op(p);
+  walk_chunks<1>(tb, op);
+}
+
+__global__ void quant_stats_zero_kernel(fp8lm_quant_stats* out, int n) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < n) out[t] = fp8lm_quant_stats{0.0, 0.0, 0, 0, 0, 0};
+}
+
+__global__ void meta_init_kernel(fp8lm_meta* meta, int n, int clean0) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n) return;
+  fp8lm_meta M;
+  M.scale = 1.0f; M.inv_scale = 1.0f; M.amax = 0.0f; M.amax_deq = 0.0f;
+  for (int h = 0; h < FP8LM_HIST; ++h) M.amax_hist[h] = 0.0f;
+  M.hist_pos = 0; M.mu_exp = 0; M.clean_steps = clean0; M.flags = 0; M.n_sat = 0; M.n_underflow = 0;
+  meta[t] = M;
+}
+
+// Plain streaming copy: every workgroup owns one contiguous range, four 128-bit loads in flight per
+// thread, non-temporal on both sides.
+__global__ __launch_bounds__(kThreads) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long long n16) {
+  const long long b0 = n16 * blockIdx.x / gridDim.x, b1 = n16 * (blockIdx.x + 1) / gridDim.x;
+  long long i = b0 + threadIdx.x;
+  for (; i + 3 * kThreads < b1; i += 4 * kThreads) {
+    const uint4 a = ld16<true>(src + i), b = ld16<true>(src + i + kThreads), c = ld16<true>(src + i + 2 * kThreads),
+                d = ld16<true>(src + i + 3 * kThreads);
+    st16<true>(dst + i, a);
+    st16<true>(dst + i + kThreads, b);
+    st16<true>(dst + i + 2 * kThreads, c);
+    st16<true>(dst + i + 3 * kThreads, d);
+  }
+  for (; i < b1; i += kThreads) st16<true>(dst + i, ld16<true>(src + i));
+}
+
+}  // namespace fp8lm
+
+#endif
