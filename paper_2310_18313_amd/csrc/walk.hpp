@@ -215,20 +215,22 @@ __device__ __forceinline__ void atomic_add_u64(unsigned long long* p, unsigned l
 // tiles<UN>(pos): UN complete 4096-element tiles starting at element `pos` of the flat buffers, handled
 // by the whole workgroup (all loads issued before the first use; the op chooses which 16 elements of
 // a tile a thread takes); group(pos, valid) with 1 <= valid <= 16 for everything else, element by
-// element; flush(t, desc, chunks_done) (called by all threads).
+// element; flush(t, desc, chunks_done) (called by all threads when the workgroup leaves tensor t: it fills
+// a Stats = BlockStats<..>, combines it over the workgroup and hands it to `collect`); and for the tensor's
+// scalar epilogue finalize(t, desc, stats), run by one thread once the totals of all workgroups are known.
 template <int UN, class Op>
 __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
   // workgroup b walks the contiguous chunk range [b*C/G, (b+1)*C/G): `collect` relies on this mapping
   const long long G = gridDim.x, b = blockIdx.x;
   long long c = b * tb.n_chunks / G;
-  const long long c_end = (b + 1) * tb.n_chunks / G, step = 1;
+  const long long c_end = (b + 1) * tb.n_chunks / G;
   int cur = -1, done = 0;
   TensorDesc d{};
   // the tensor id of the next chunk is fetched one iteration ahead, so its latency hides behind the body
   int t_next = c < c_end ? tb.chunk_tensor[c] : -1;
-  for (; c < c_end; c += step) {
+  for (; c < c_end; ++c) {
     const int t = t_next;
-    t_next = c + step < c_end ? tb.chunk_tensor[c + step] : -1;
+    t_next = c + 1 < c_end ? tb.chunk_tensor[c + 1] : -1;
     if (t != cur) {
       if (cur >= 0) op.flush(cur, d, done);
       cur = t;
