@@ -297,8 +297,9 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* ctx,
  *   caller), n_nonzero = #{r != 0}, n_underflow = #{r != 0, payload = +-0}, n_overflow = #{|payload|
  *   is the largest finite code}.  Elements whose reference is inf/NaN or whose payload is a NaN/inf
  *   code are counted in n_nonfinite and in nothing else.
- * The sums are accumulated in an unspecified order (agree with a sequential sum to about
- * numel * 2^-52 relative); the counts are exact.
+ * The sums are accumulated in an order that depends only on the launch shape (they agree with a
+ * sequential sum to about numel * 2^-52 relative and are reproducible from call to call); the counts
+ * are exact.
  *   ref  : device, flat buffer of element type ref_type (read only);
  *   q    : device, flat uint8 payloads of format fmt;  q_meta : device [n_tensors], only scale is read;
  *   out  : device [n_tensors], overwritten (entries of empty tensors are zeroed).

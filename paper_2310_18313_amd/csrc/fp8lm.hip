@@ -591,26 +591,24 @@ fp8lm_status fp8lm_quant_error_stats(fp8lm_ctx* c, const void* ref, fp8lm_src re
                                      const fp8lm_meta* q_meta, fp8lm_quant_stats* out, void* stream) {
   if (!c || !src_ok(ref_type) || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2)) return FP8LM_ERR_INVALID_ARGUMENT;
   if (c->n_tensors == 0) return FP8LM_OK;
-  if (!out) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!out || (c->n_chunks > 0 && (!ref || !q || !q_meta))) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_chunks > 0 && (!aligned16(ref) || !aligned16(q))) return FP8LM_ERR_MISALIGNED;
   DeviceGuard guard(c->device);
   hipStream_t s = (hipStream_t)stream;
   {
+    // entries of empty tensors are never written by the reduction: start from zero
     Timed tm(c, s, FP8LM_K_SCALARS);
     hipLaunchKernelGGL(quant_stats_zero_kernel, dim3((c->n_tensors + 255) / 256), dim3(256), 0, s, out, c->n_tensors);
     fp8lm_status st = after_launch();
     if (st != FP8LM_OK) return st;
   }
   if (c->n_chunks == 0) return FP8LM_OK;
-  if (!ref || !q || !q_meta) return FP8LM_ERR_INVALID_ARGUMENT;
-  if (!aligned16(ref) || !aligned16(q)) return FP8LM_ERR_MISALIGNED;
   StatsParams p{ref, q, q_meta, out};
-  const dim3 g(grid_of(c)), b(kThreads);
-  const Tables tb = tables_of(c);
   Timed tm(c, s, FP8LM_K_STATS);
 #define FP8LM_STATS_SRC(S)                                                                                   \
   do {                                                                                                       \
-    if (fmt == FP8LM_E4M3) hipLaunchKernelGGL((quant_stats_kernel<kE4M3, S>), g, b, 0, s, tb, p);            \
-    else hipLaunchKernelGGL((quant_stats_kernel<kE5M2, S>), g, b, 0, s, tb, p);                              \
+    if (fmt == FP8LM_E4M3) launch_walk<QuantStatsOp<kE4M3, S>>(c, s, quant_stats_kernel<kE4M3, S>, p);        \
+    else launch_walk<QuantStatsOp<kE5M2, S>>(c, s, quant_stats_kernel<kE5M2, S>, p);                          \
   } while (0)
   if (ref_type == FP8LM_SRC_F32) FP8LM_STATS_SRC(kSrcF32);
   else if (ref_type == FP8LM_SRC_F16) FP8LM_STATS_SRC(kSrcF16);

@@ -18,25 +18,6 @@ struct StatsParams {
   fp8lm_quant_stats* out;
 };
 
-__device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
-// workgroup-wide sum of two doubles; result valid in thread 0
-__device__ __forceinline__ void block_sum2_f64(double& a, double& b) {
-  __shared__ double l[kWaves][2];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  a = wave_sum_f64(a);
-  b = wave_sum_f64(b);
-  __syncthreads();
-  if (lane == 0) { l[wave][0] = a; l[wave][1] = b; }
-  __syncthreads();
-  if (threadIdx.x == 0)
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) { a += l[w][0]; b += l[w][1]; }
-}
-
 template <int FMT, int SRC>
 struct QuantStatsOp {
   using elem_t = typename SrcTraits<SRC>::elem_t;
@@ -44,9 +25,10 @@ struct QuantStatsOp {
   static constexpr int kLoads = kGroup / kPer;
   static constexpr int kW = kSrcWords<SRC>;
   const StatsParams& p;
+  const Tables& tb;
   double rs, signal, noise;
   uint32_t n_nonzero, n_under, n_over, n_nonfinite;
-  __device__ QuantStatsOp(const StatsParams& p_) : p(p_) {}
+  __device__ QuantStatsOp(const StatsParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
   __device__ __forceinline__ void begin(int t, const TensorDesc&) {
     rs = 1.0 / (double)p.meta[t].scale;
     signal = noise = 0.0;
@@ -98,27 +80,23 @@ struct QuantStatsOp {
     const elem_t* rp = static_cast<const elem_t*>(p.ref) + pos;
     for (int j = 0; j < valid; ++j) one(rp[j], p.q[pos + j]);
   }
-  __device__ __forceinline__ void flush(int t, const TensorDesc&, int) {
-    BlockStats<0, 4> s;
+  using Stats = BlockStats<0, 4, 2>;
+  __device__ __forceinline__ void flush(int t, const TensorDesc& d, int done) {
+    Stats s;
     s.ct[0] = n_nonzero; s.ct[1] = n_under; s.ct[2] = n_over; s.ct[3] = n_nonfinite;
+    s.fs[0] = signal; s.fs[1] = noise;
     s.orv = 0;
     block_combine(s);
-    block_sum2_f64(signal, noise);
-    if (threadIdx.x == 0) {
-      fp8lm_quant_stats* o = p.out + t;
-      if (signal != 0.0) __hip_atomic_fetch_add(&o->signal, signal, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (noise != 0.0) __hip_atomic_fetch_add(&o->noise, noise, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      atomic_add_u64(reinterpret_cast<unsigned long long*>(&o->n_nonzero), s.ct[0]);
-      atomic_add_u64(reinterpret_cast<unsigned long long*>(&o->n_underflow), s.ct[1]);
-      atomic_add_u64(reinterpret_cast<unsigned long long*>(&o->n_overflow), s.ct[2]);
-      atomic_add_u64(reinterpret_cast<unsigned long long*>(&o->n_nonfinite), s.ct[3]);
-    }
+    if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
+  }
+  __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
+    p.out[t] = fp8lm_quant_stats{s.fs[0], s.fs[1], s.ct[0], s.ct[1], s.ct[2], s.ct[3]};
   }
 };
 
 template <int FMT, int SRC>
 __global__ __launch_bounds__(kThreads) void quant_stats_kernel(Tables tb, StatsParams p) {
-  QuantStatsOp<FMT, SRC> op(p);
+  QuantStatsOp<FMT, SRC> op(p, tb);
   walk_chunks<1>(tb, op);
 }
 

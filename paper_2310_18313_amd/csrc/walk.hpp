@@ -40,6 +40,7 @@ struct alignas(128) Partial {
   uint32_t mx[3];
   uint32_t orv;
   unsigned long long ct[8];
+  double fs[2];                   // float64 sums (error statistics)
 };
 
 struct Tables {
@@ -68,25 +69,35 @@ __device__ __forceinline__ uint32_t wave_or_u32(uint32_t v) {
   for (int o = 32; o > 0; o >>= 1) v |= (uint32_t)__shfl_xor((int)v, o, 64);
   return v;
 }
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
 
-// Workgroup-wide combine of up to NV maxima, NC counters and one OR-mask; result valid in thread 0.
-template <int NV, int NC>
+// Workgroup-wide combine of up to NV maxima, NC counters, NF float64 sums and one OR-mask; result valid in
+// thread 0.  Every step is done in a fixed order, so the float64 sums are reproducible from run to run.
+template <int NV, int NC, int NF = 0>
 struct BlockStats {
   uint32_t mx[NV > 0 ? NV : 1];
   unsigned long long ct[NC > 0 ? NC : 1];
+  double fs[NF > 0 ? NF : 1];
   uint32_t orv;
 };
 
-template <int NV, int NC>
-__device__ __forceinline__ void block_combine(BlockStats<NV, NC>& s) {
+template <int NV, int NC, int NF>
+__device__ __forceinline__ void block_combine(BlockStats<NV, NC, NF>& s) {
   __shared__ uint32_t l_mx[kWaves][NV > 0 ? NV : 1];
   __shared__ unsigned long long l_ct[kWaves][NC > 0 ? NC : 1];
+  __shared__ double l_fs[kWaves][NF > 0 ? NF : 1];
   __shared__ uint32_t l_or[kWaves];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
   for (int i = 0; i < NV; ++i) s.mx[i] = wave_max_u32(s.mx[i]);
 #pragma unroll
   for (int i = 0; i < NC; ++i) s.ct[i] = wave_sum_u64(s.ct[i]);
+#pragma unroll
+  for (int i = 0; i < NF; ++i) s.fs[i] = wave_sum_f64(s.fs[i]);
   s.orv = wave_or_u32(s.orv);
   __syncthreads();   // the previous use of the LDS arrays is over
   if (lane == 0) {
@@ -94,6 +105,8 @@ __device__ __forceinline__ void block_combine(BlockStats<NV, NC>& s) {
     for (int i = 0; i < NV; ++i) l_mx[wave][i] = s.mx[i];
 #pragma unroll
     for (int i = 0; i < NC; ++i) l_ct[wave][i] = s.ct[i];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) l_fs[wave][i] = s.fs[i];
     l_or[wave] = s.orv;
   }
   __syncthreads();
@@ -104,6 +117,8 @@ __device__ __forceinline__ void block_combine(BlockStats<NV, NC>& s) {
       for (int i = 0; i < NV; ++i) s.mx[i] = max(s.mx[i], l_mx[w][i]);
 #pragma unroll
       for (int i = 0; i < NC; ++i) s.ct[i] += l_ct[w][i];
+#pragma unroll
+      for (int i = 0; i < NF; ++i) s.fs[i] += l_fs[w][i];
       s.orv |= l_or[w];
     }
   }
@@ -132,20 +147,22 @@ __device__ __forceinline__ void block_combine(BlockStats<NV, NC>& s) {
 // Ordering in the single pass: records are written and read with agent-scope atomic accesses (they bypass
 // the caches that are not coherent across the chip); the ticket is bumped with release/acquire semantics,
 // so the completing workgroup observes every record written before the other workgroups' bumps.
-template <int NV, int NC>
-__device__ __forceinline__ void store_record(const Tables& tb, int t, const BlockStats<NV, NC>& s) {
+template <int NV, int NC, int NF>
+__device__ __forceinline__ void store_record(const Tables& tb, int t, const BlockStats<NV, NC, NF>& s) {
   Partial* rec = tb.partials + ((long long)blockIdx.x + t);
 #pragma unroll
   for (int i = 0; i < NV; ++i) __hip_atomic_store(&rec->mx[i], s.mx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
   for (int i = 0; i < NC; ++i) __hip_atomic_store(&rec->ct[i], s.ct[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+  for (int i = 0; i < NF; ++i) __hip_atomic_store(&rec->fs[i], s.fs[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __hip_atomic_store(&rec->orv, s.orv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Combines the records of all workgroups of a launch with `grid` workgroups that touched tensor t.  Called
 // by all threads; the totals end up in thread 0's `s`.
-template <int NV, int NC>
-__device__ __forceinline__ void gather_records(const Tables& tb, int t, const TensorDesc& d, long long grid, BlockStats<NV, NC>& s) {
+template <int NV, int NC, int NF>
+__device__ __forceinline__ void gather_records(const Tables& tb, int t, const TensorDesc& d, long long grid, BlockStats<NV, NC, NF>& s) {
   // owner(c) = the b with b*C/G <= c < (b+1)*C/G
   const long long C = tb.n_chunks;
   const long long c0 = d.first_chunk, c1 = c0 + d.n_chunks - 1;
@@ -154,6 +171,8 @@ __device__ __forceinline__ void gather_records(const Tables& tb, int t, const Te
   for (int i = 0; i < NV; ++i) s.mx[i] = 0;
 #pragma unroll
   for (int i = 0; i < NC; ++i) s.ct[i] = 0;
+#pragma unroll
+  for (int i = 0; i < NF; ++i) s.fs[i] = 0.0;
   s.orv = 0;
   for (long long b = b_lo + threadIdx.x; b <= b_hi; b += kThreads) {
     const Partial* rec = tb.partials + (b + t);
@@ -161,6 +180,8 @@ __device__ __forceinline__ void gather_records(const Tables& tb, int t, const Te
     for (int i = 0; i < NV; ++i) s.mx[i] = max(s.mx[i], __hip_atomic_load(&rec->mx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 #pragma unroll
     for (int i = 0; i < NC; ++i) s.ct[i] += __hip_atomic_load(&rec->ct[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int i = 0; i < NF; ++i) s.fs[i] += __hip_atomic_load(&rec->fs[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s.orv |= __hip_atomic_load(&rec->orv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   block_combine(s);
@@ -169,8 +190,8 @@ __device__ __forceinline__ void gather_records(const Tables& tb, int t, const Te
 // Called by all threads at the end of a workgroup's part of tensor t, after block_combine(s).  Returns
 // true in every thread of the workgroup that has to run the tensor's epilogue, with the tensor's totals in
 // thread 0's `s`; always false in the deferred form.
-template <int NV, int NC>
-__device__ __forceinline__ bool collect(const Tables& tb, int t, const TensorDesc& d, int done, BlockStats<NV, NC>& s) {
+template <int NV, int NC, int NF>
+__device__ __forceinline__ bool collect(const Tables& tb, int t, const TensorDesc& d, int done, BlockStats<NV, NC, NF>& s) {
   if (tb.deferred) {
     if (threadIdx.x == 0) store_record(tb, t, s);
     return false;
@@ -204,10 +225,6 @@ __global__ __launch_bounds__(kThreads) void epilogue_kernel(Tables tb, Params p,
     gather_records(tb, t, d, main_grid, s);
     if (threadIdx.x == 0) op.finalize(t, d, s);
   }
-}
-
-__device__ __forceinline__ void atomic_add_u64(unsigned long long* p, unsigned long long v) {
-  if (v) __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- the chunk walk shared by all kernels -------------------------------------------------------
