@@ -179,8 +179,6 @@ void launch_walk(fp8lm_ctx* c, hipStream_t s, Kernel kernel, const Params& p) {
 // Selects the adam_update_kernel instantiation.
 template <int GFMT, int WCOPY>
 void launch_update(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, bool fast, bool stats) {
-  const dim3 g(grid_of(c)), b(kThreads);
-  const Tables tb = tables_of(c);
   if (fast) {
     if (stats) launch_walk<AdamUpdateOp<GFMT, WCOPY, true, true>>(c, s, adam_update_kernel<GFMT, WCOPY, true, true>, p);
     else launch_walk<AdamUpdateOp<GFMT, WCOPY, true, false>>(c, s, adam_update_kernel<GFMT, WCOPY, true, false>, p);
@@ -193,8 +191,6 @@ void launch_update(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, bool fast, 
 // Selects the adam_update_var_kernel instantiation (every master / second-moment format pair except the default).
 template <int GFMT>
 void launch_update_variant_g(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, int master, int vfmt) {
-  const dim3 g(grid_of(c)), b(kThreads);
-  const Tables tb = tables_of(c);
 #define FP8LM_VAR(M, V) launch_walk<AdamUpdateVarOp<GFMT, M, V>>(c, s, adam_update_var_kernel<GFMT, M, V>, p)
   if (vfmt == kStF16) {
     if (master == kStBF16) FP8LM_VAR(kStBF16, kStF16);
@@ -325,9 +321,7 @@ fp8lm_status fp8lm_amax_scale(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
   if (!aligned16(src)) return FP8LM_ERR_MISALIGNED;
   DeviceGuard guard(c->device);
   AmaxParams p{src, meta, target == FP8LM_E4M3 ? kBitsE4M3Max : kBitsE5M2Max, cfg->hist_window, cfg->margin};
-  const dim3 g(grid_of(c)), b(kThreads);
   hipStream_t s = (hipStream_t)stream;
-  const Tables tb = tables_of(c);
   Timed tm(c, s, FP8LM_K_AMAX);
   if (src_type == FP8LM_SRC_F32) launch_walk<AmaxOp<kAmaxForGradient, kSrcF32>>(c, s, amax_kernel<kAmaxForGradient, kSrcF32>, p);
   else if (src_type == FP8LM_SRC_F16) launch_walk<AmaxOp<kAmaxForGradient, kSrcF16>>(c, s, amax_kernel<kAmaxForGradient, kSrcF16>, p);
@@ -364,8 +358,6 @@ static fp8lm_status cast_impl(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
   p.m_meta = m_meta;
   p.b1 = beta1;
   p.omb1 = (float)(1.0 - (double)beta1);
-  const dim3 g(grid_of(c)), b(kThreads);
-  const Tables tb = tables_of(c);
   {
     Timed tm(c, s, FP8LM_K_CAST);
 #define FP8LM_CAST_LAUNCH(F, S)                                                                           \
@@ -460,9 +452,7 @@ fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* c, const uint8_t* const* payloads, int32_t
   p.sat_num = cfg->sat_num; p.sat_den = cfg->sat_den; p.ramp_steps = cfg->ramp_steps;
   DeviceGuard guard(c->device);
   Timed tm(c, (hipStream_t)stream, FP8LM_K_SUM);
-  const dim3 g(grid_of(c)), b(kThreads);
   hipStream_t s = (hipStream_t)stream;
-  const Tables tb = tables_of(c);
 #define FP8LM_SUM_N(N)                                                                          \
   case N:                                                                                       \
     if (fmt == FP8LM_E4M3) launch_walk<SumOp<kE4M3, N>>(c, s, sum_fp8_kernel<kE4M3, N>, p);   \
@@ -493,7 +483,6 @@ fp8lm_status fp8lm_init_master_as(fp8lm_ctx* c, const void* w_bf16, void* w_out,
   fp8lm_status st = after_launch();
   if (st != FP8LM_OK) return st;
   InitParams pi{static_cast<const uint16_t*>(w_bf16), w_out, w_meta};
-  const dim3 g(grid_of(c)), b(kThreads);
   switch (master_fmt) {
     case FP8LM_STATE_F16: launch_walk<InitCastOp<kStF16>>(c, s, init_master_cast_kernel<kStF16>, pi); break;
     case FP8LM_STATE_BF16: launch_walk<InitCastOp<kStBF16>>(c, s, init_master_cast_kernel<kStBF16>, pi); break;
@@ -547,7 +536,6 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
 
   const bool stats = hp->stats != 0, fast = hp->exact == 0;
   hipStream_t s = (hipStream_t)stream;
-  const dim3 g(grid_of(c)), b(kThreads);
   const Tables tb = tables_of(c);
   const bool e5 = grad_fmt == FP8LM_E5M2, q8 = hp->wcopy == FP8LM_WCOPY_E4M3;
   if (hp->m_scale_mode == FP8LM_MSCALE_FROM_CAST) {
