@@ -220,7 +220,7 @@ fp8lm_status fp8lm_cast_fp8_for_adam(fp8lm_ctx* ctx, const void* src /*device*/,
 
 /*
  * The three steps around the FP8 gradient all-reduce of Sec. 2.1 (Eq. 4-6), as one GPU can run them;
- * the collectives themselves are not part of this library.  n_ranks <= 8.
+ * the collectives themselves are not part of this library.  n_ranks <= 128.
  *
  * Eq. 4: shared[t] = min over r of metas[r][t].scale.
  *   metas  : host array of n_ranks device pointers, each to a meta array [n_tensors];

@@ -458,11 +458,14 @@ fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* c, const uint8_t* const* payloads, int32_t
     if (fmt == FP8LM_E4M3) launch_walk<SumOp<kE4M3, N>>(c, s, sum_fp8_kernel<kE4M3, N>, p);   \
     else launch_walk<SumOp<kE5M2, N>>(c, s, sum_fp8_kernel<kE5M2, N>, p);                     \
     break
-  static_assert(kMaxRanks == 8, "one case per rank count");
+  static_assert(kUnrolledRanks == 8, "one case per unrolled rank count");
   switch (n_ranks) {
     FP8LM_SUM_N(1); FP8LM_SUM_N(2); FP8LM_SUM_N(3); FP8LM_SUM_N(4);
     FP8LM_SUM_N(5); FP8LM_SUM_N(6); FP8LM_SUM_N(7); FP8LM_SUM_N(8);
-    default: return FP8LM_ERR_INVALID_ARGUMENT;
+    default:          // any larger number of ranks: the kernel that loops over them
+      if (fmt == FP8LM_E4M3) launch_walk<SumOp<kE4M3, 0>>(c, s, sum_fp8_kernel<kE4M3, 0>, p);
+      else launch_walk<SumOp<kE5M2, 0>>(c, s, sum_fp8_kernel<kE5M2, 0>, p);
+      break;
   }
 #undef FP8LM_SUM_N
   return after_launch();

@@ -428,7 +428,8 @@ __global__ void delayed_scale_kernel(const TensorDesc* desc, fp8lm_meta* meta, i
 // ================================================================================================
 // Shared-scale re-quantisation and the FP8 gradient sum (Sec. 2.1, Eq. 4-6)
 // ================================================================================================
-constexpr int kMaxRanks = 8;
+constexpr int kMaxRanks = 128;      // rank pointers travel as kernel arguments (1 KiB)
+constexpr int kUnrolledRanks = 8;   // rank counts up to this have a kernel of their own
 struct RankMetas { const fp8lm_meta* m[kMaxRanks]; int32_t n_ranks; };
 struct RankPayloads { const uint8_t* p[kMaxRanks]; int32_t n_ranks; };
 
@@ -585,51 +586,79 @@ struct SumOp {
     nz_top += nonzero_bytes7(mag ^ Fp8Traits<FMT>::kTopX4);
     return c;
   }
+  // one rank's 16 payloads added to the running sums: rank order, one fp32 addition per rank
+  __device__ __forceinline__ void add_rank(float* acc, const uint4& a) {
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float2_t lo = fp8x2_to_f32<FMT, false>(w[k]), hi = fp8x2_to_f32<FMT, true>(w[k]);
+      acc[4 * k + 0] = acc[4 * k + 0] + lo.x;
+      acc[4 * k + 1] = acc[4 * k + 1] + lo.y;
+      acc[4 * k + 2] = acc[4 * k + 2] + hi.x;
+      acc[4 * k + 3] = acc[4 * k + 3] + hi.y;
+    }
+  }
+  // rounds 16 sums to FP8 and stores them
+  __device__ __forceinline__ void finish_group(const float* acc, long long pos) {
+    bool any_nan = false;
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j) any_nan |= acc[j] != acc[j];
+    uint32_t o[4] = {0, 0, 0, 0};
+    if (!any_nan) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = finish_quad(acc + 4 * k);
+      n_fast += kGroup;
+    } else {
+#pragma unroll
+      for (int j = 0; j < kGroup; ++j) o[j >> 2] |= finish_one(acc[j]) << ((j & 3) * 8);
+    }
+    st16<kNtStoreWO>(p.dst + pos, make_uint4(o[0], o[1], o[2], o[3]));
+  }
+  // NR > 0: that many ranks, all loads of UN tiles issued up front.  NR == 0: any number of ranks
+  // (p.in.n_ranks), loaded eight at a time.
   template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
     const long long pos = pos0 + threadIdx.x * kGroup;
-    uint4 a[UN][NR];
+    if constexpr (NR == 0) {
+      const int n = p.in.n_ranks;
 #pragma unroll
-    for (int u = 0; u < UN; ++u)
+      for (int u = 0; u < UN; ++u) {
+        float acc[kGroup];
 #pragma unroll
-      for (int r = 0; r < NR; ++r) a[u][r] = ld16<kNtLoadRO>(p.in.p[r] + pos + u * kTile);
+        for (int j = 0; j < kGroup; ++j) acc[j] = 0.0f;
+        for (int r0 = 0; r0 < n; r0 += kUnrolledRanks) {
+          uint4 a[kUnrolledRanks];
 #pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      float acc[kGroup];
+          for (int k = 0; k < kUnrolledRanks; ++k)
+            if (r0 + k < n) a[k] = ld16<kNtLoadRO>(p.in.p[r0 + k] + pos + u * kTile);
 #pragma unroll
-      for (int j = 0; j < kGroup; ++j) acc[j] = 0.0f;
-#pragma unroll
-      for (int r = 0; r < NR; ++r) {            // rank order, one fp32 addition per rank
-        const uint32_t w[4] = {a[u][r].x, a[u][r].y, a[u][r].z, a[u][r].w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const float2_t lo = fp8x2_to_f32<FMT, false>(w[k]), hi = fp8x2_to_f32<FMT, true>(w[k]);
-          acc[4 * k + 0] = acc[4 * k + 0] + lo.x;
-          acc[4 * k + 1] = acc[4 * k + 1] + lo.y;
-          acc[4 * k + 2] = acc[4 * k + 2] + hi.x;
-          acc[4 * k + 3] = acc[4 * k + 3] + hi.y;
+          for (int k = 0; k < kUnrolledRanks; ++k)
+            if (r0 + k < n) add_rank(acc, a[k]);
         }
+        finish_group(acc, pos + u * kTile);
       }
-      bool any_nan = false;
+    } else {
+      uint4 a[UN][NR > 0 ? NR : 1];
 #pragma unroll
-      for (int j = 0; j < kGroup; ++j) any_nan |= acc[j] != acc[j];
-      uint32_t o[4] = {0, 0, 0, 0};
-      if (!any_nan) {
+      for (int u = 0; u < UN; ++u)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) o[k] = finish_quad(acc + 4 * k);
-        n_fast += kGroup;
-      } else {
+        for (int r = 0; r < NR; ++r) a[u][r] = ld16<kNtLoadRO>(p.in.p[r] + pos + u * kTile);
 #pragma unroll
-        for (int j = 0; j < kGroup; ++j) o[j >> 2] |= finish_one(acc[j]) << ((j & 3) * 8);
+      for (int u = 0; u < UN; ++u) {
+        float acc[kGroup];
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) acc[j] = 0.0f;
+#pragma unroll
+        for (int r = 0; r < NR; ++r) add_rank(acc, a[u][r]);
+        finish_group(acc, pos + u * kTile);
       }
-      st16<kNtStoreWO>(p.dst + pos + u * kTile, make_uint4(o[0], o[1], o[2], o[3]));
     }
     n_elems += UN * kGroup;
   }
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) {
       float acc = 0.0f;
-#pragma unroll
-      for (int r = 0; r < NR; ++r) acc = acc + fp8_to_f32<FMT>(p.in.p[r][pos + j]);
+      const int n = NR > 0 ? NR : p.in.n_ranks;
+      for (int r = 0; r < n; ++r) acc = acc + fp8_to_f32<FMT>(p.in.p[r][pos + j]);
       p.dst[pos + j] = (uint8_t)finish_one(acc);
     }
     n_elems += valid;
@@ -670,7 +699,7 @@ struct SumOp {
 template <int FMT, int NR>
 __global__ __launch_bounds__(kThreads) void sum_fp8_kernel(Tables tb, SumParams p) {
   SumOp<FMT, NR> op(p, tb);
-  walk_chunks<(NR <= 2 ? 4 : NR <= 4 ? 2 : 1)>(tb, op);   // about eight 128-bit loads in flight per thread
+  walk_chunks<(NR == 0 ? 1 : NR <= 2 ? 4 : NR <= 4 ? 2 : 1)>(tb, op);   // about eight 128-bit loads in flight per thread
 }
 
 }  // namespace fp8lm

@@ -394,6 +394,60 @@ def test_shared_scale_requantize_and_sum(fmt):
             assert gm["flags"][0] & B.FLAG_NONFINITE
 
 
+@pytest.mark.parametrize("fmt", [B.E5M2, B.E4M3])
+@pytest.mark.parametrize("n_ranks", [9, 13, 128])
+def test_sum_of_many_ranks(fmt, n_ranks):
+    """More ranks than have a kernel of their own (the paper's communication study uses 128): shared scale and
+    sum go through the kernels that loop over the ranks."""
+    wl = synth.Workload("manyranks", synth.Layout(["a", "b", "c", "d"], [20001, 4096, 17, 50000]), lr=1e-3, sigma=None)
+    lay = wl.layout
+    cfg = B.autoscale_cfg(ramp_steps=20)
+    ocfg = P.oracle_cfg(cfg)
+    ctx = B.Context(lay.tensors())
+    tens = O.tensors_array(lay.tensors())
+    nt = lay.n_tensors
+    size = max(lay.total, 16)
+    d_q, d_meta = [], []
+    grad = torch.zeros(size, dtype=torch.bfloat16, device=DEV)
+    for r in range(n_ranks):
+        synth.fill_gradients(grad, wl, 300 + r, 1)
+        grad *= float(2.0 ** ((r * 7) % 5 - 2))               # ranks with different scales
+        if r == n_ranks - 2:
+            grad[lay.offsets[3] + 5] = float("nan")
+        meta, q = ctx.new_meta(cfg), torch.zeros(size, dtype=torch.uint8, device=DEV)
+        ctx.amax_scale(grad, fmt, meta, cfg)
+        ctx.cast_fp8(grad, q, fmt, meta, cfg)
+        d_q.append(q); d_meta.append(meta)
+    say(f"sum of {n_ranks} ranks fmt={fmt}")
+    shared = ctx.shared_scale(d_meta)
+    h_meta = [B.meta_to_numpy(m, nt) for m in d_meta]
+    ref_shared = O.shared_scale(h_meta, nt)
+    assert np.array_equal(shared.cpu().numpy()[:nt], ref_shared)
+    d_rq, h_rq = [], []
+    for r in range(n_ranks):
+        dst, out_meta = torch.zeros(size, dtype=torch.uint8, device=DEV), ctx.new_meta(cfg)
+        ctx.requantize_fp8(d_q[r], fmt, d_meta[r], shared, dst, out_meta)
+        ref, ref_meta = np.zeros(size, dtype=np.uint8), O.new_meta(nt, ocfg)
+        O.requantize_fp8(d_q[r].cpu().numpy(), fmt, h_meta[r], ref_shared, tens, ref, ref_meta)
+        d_rq.append(dst); h_rq.append(ref)
+    out, out_meta = torch.zeros(size, dtype=torch.uint8, device=DEV), ctx.new_meta(cfg)
+    ref_meta = B.meta_to_numpy(out_meta, nt)
+    ctx.sum_fp8(d_rq, fmt, shared, out, out_meta, cfg)
+    torch.cuda.synchronize()
+    for r in range(n_ranks):
+        assert np.array_equal(d_rq[r].cpu().numpy(), h_rq[r]), r
+    ref = np.zeros(size, dtype=np.uint8)
+    O.sum_fp8(h_rq, fmt, ref_shared, tens, ref, ref_meta, ocfg)
+    got, gm = out.cpu().numpy(), B.meta_to_numpy(out_meta, nt)
+    for t, (off, n) in enumerate(lay.tensors()):
+        assert np.array_equal(got[off:off + n], ref[off:off + n]), t
+        diff = P.meta_equal(gm[t], ref_meta[t], P.ALL_FIELDS)
+        assert not diff, (t, diff, gm[t], ref_meta[t])
+    assert gm["flags"][3] & B.FLAG_NONFINITE
+    with pytest.raises(B.Fp8lmError):
+        ctx.sum_fp8(d_rq + d_rq[:129 - n_ranks] if n_ranks == 128 else [d_rq[0]] * 129, fmt, shared, out, out_meta, cfg)
+
+
 # ---- storage formats of the precision-decoupling study (Sec. 2.2; Sec. 3.3) ----------------------------
 @pytest.mark.parametrize("master_fmt", [B.STATE_F16, B.STATE_BF16, B.STATE_E4M3, B.STATE_F32])
 @pytest.mark.parametrize("v_fmt", [B.STATE_F16, B.STATE_E4M3])
