@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 import torch
 
+import oracle as O
 import parity as P
 from conftest import say
 from paper_2310_18313_amd import binding as B
@@ -130,3 +131,49 @@ def test_gpt175b_layer_with_the_papers_ramp_of_a_thousand_steps():
     for t in overflowed:
         first = int(np.argmax(mus[:, t] == -1))
         assert (mus[first:, t] == -1).all() and gm["clean_steps"][t] < 500
+
+
+@pytest.mark.parametrize("fmt,scale_exp", [(B.E5M2, 3), (B.E5M2, -100), (B.E4M3, -2), (B.E4M3, 97)])
+def test_cast_of_every_fp32_bit_pattern(fmt, scale_exp):
+    """All 2^32 fp32 inputs through the cast kernel (hardware clamp + convert on the fast path, the explicit NaN
+    handling on the careful path) against the oracle's encoder, 2^28 patterns at a time."""
+    from concurrent.futures import ThreadPoolExecutor
+    piece, parts = 1 << 28, 16
+    sub = piece // parts                                            # 2^24 patterns per tensor: one top byte each
+    tensors = [(i * sub, sub) for i in range(parts)]
+    cfg = B.autoscale_cfg()
+    ctx = B.Context(tensors)
+    tens = O.tensors_array(tensors)
+    src = torch.empty(piece, dtype=torch.int32, device=DEV)
+    dst = torch.zeros(piece, dtype=torch.uint8, device=DEV)
+    base = torch.arange(piece, dtype=torch.int64, device=DEV)
+    pool = ThreadPoolExecutor(parts)
+    # scales other than 1, so that the multiply is exercised too; the large ones push part of the inputs through
+    # fp32 overflow and subnormal products
+    for k in range(16):
+        src.copy_(((base + (k << 28)) & 0xFFFFFFFF).to(torch.int32) if k < 8 else (base + (k << 28) - (1 << 32)).to(torch.int32))
+        meta = B.meta_to_numpy(ctx.new_meta(cfg), parts)
+        meta["scale"], meta["inv_scale"] = 2.0 ** scale_exp, 2.0 ** -scale_exp
+        for i in range(parts):
+            top_byte = (k << 4) | i
+            if top_byte in (0x7F, 0xFF):                           # holds the infinities and NaNs
+                meta["flags"][i] = B.FLAG_NONFINITE
+        ref_meta = meta.copy()
+        d_meta = B.meta_from_numpy(meta, DEV)
+        say(f"fp32 sweep fmt={fmt} scale=2^{scale_exp}: patterns {k << 28:#010x} .. {((k + 1) << 28) - 1:#010x}")
+        ctx.cast_fp8(src.view(torch.float32), dst, fmt, d_meta, cfg)
+        torch.cuda.synchronize()
+        h_src = src.cpu().numpy().view(np.float32)
+        ref = np.zeros(piece, dtype=np.uint8)
+
+        def one(i):
+            O.cast_fp8(h_src, tens[i:i + 1], ref, fmt, ref_meta[i:i + 1], P.oracle_cfg(cfg), src_type=O.SRC_F32)
+
+        list(pool.map(one, range(parts)))
+        got = dst.cpu().numpy()
+        bad = np.flatnonzero(got != ref)
+        assert bad.size == 0, f"{bad.size} codes differ, first {h_src.view(np.uint32)[bad[:4]]} -> gpu {got[bad[:4]]} oracle {ref[bad[:4]]}"
+        gm = B.meta_to_numpy(d_meta, parts)
+        for i in range(parts):
+            diff = P.meta_equal(gm[i], ref_meta[i], ["n_sat", "n_underflow", "amax_deq", "flags", "mu_exp", "clean_steps"])
+            assert not diff, (k, i, diff, gm[i], ref_meta[i])
