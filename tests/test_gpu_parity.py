@@ -103,6 +103,53 @@ def test_fp8_decode_of_every_code_matches_the_oracle_through_adam(gfmt, finite_o
         assert not diff, (k, diff, got, metas[k][0])
 
 
+@pytest.mark.parametrize("finite_only", [True, False])
+def test_fp16_decode_of_every_pattern_matches_the_oracle_through_adam(finite_only):
+    """Every FP16 pattern as a stored master weight, every non-negative one as a stored second moment (subnormals
+    included): the finite ones on the fast path, all of them (inf and NaN too) on the careful path."""
+    pats = np.arange(65536, dtype=np.uint16)
+    w_bits = pats[(pats & 0x7C00) != 0x7C00] if finite_only else pats
+    n = w_bits.size
+    v_bits = (np.arange(n, dtype=np.uint32) * 7 % 0x7C00).astype(np.uint16)        # finite, non-negative, all exponents
+    lay = synth.flat_layout(n)
+    cfg = B.autoscale_cfg()
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
+    rng = np.random.default_rng(8)
+    g_codes = rng.integers(0, 0x7C, n).astype(np.uint8) | (rng.integers(0, 2, n).astype(np.uint8) << 7)
+    m_codes = rng.integers(0, 0x7F, n).astype(np.uint8) | (rng.integers(0, 2, n).astype(np.uint8) << 7)
+    pad = lay.total
+    host = {k: np.zeros(pad, dt) for k, dt in (("g8", np.uint8), ("m", np.uint8), ("v", np.uint16), ("w", np.uint16))}
+    host["g8"][:n], host["m"][:n], host["v"][:n], host["w"][:n] = g_codes, m_codes, v_bits, w_bits
+    st.g8.copy_(torch.from_numpy(host["g8"]).to(DEV))
+    st.m.copy_(torch.from_numpy(host["m"]).to(DEV))
+    st.v.copy_(torch.from_numpy(host["v"].view(np.int16)).to(DEV).view(torch.float16))
+    st.w.copy_(torch.from_numpy(host["w"].view(np.int16)).to(DEV).view(torch.float16))
+    metas = {k: B.meta_to_numpy(getattr(st, k), 1) for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta")}
+    metas["g_meta"]["scale"], metas["g_meta"]["inv_scale"], metas["g_meta"]["amax_deq"] = 2.0 ** 20, 2.0 ** -20, 57344.0 * 2.0 ** -20
+    metas["m_meta"]["scale"], metas["m_meta"]["inv_scale"], metas["m_meta"]["amax_deq"] = 2.0 ** 12, 2.0 ** -12, 448.0 * 2.0 ** -12
+    metas["v_meta"]["scale"], metas["v_meta"]["inv_scale"], metas["v_meta"]["amax_deq"] = 2.0 ** 30, 2.0 ** -30, 65504.0 * 2.0 ** -30
+    metas["w_meta"]["scale"], metas["w_meta"]["inv_scale"], metas["w_meta"]["amax_deq"] = 2.0 ** 14, 2.0 ** -14, 65504.0 * 2.0 ** -14
+    if not finite_only:
+        metas["w_meta"]["flags"] = B.FLAG_NONFINITE             # as the step that stored the inf / NaN left it
+    for k, mt in metas.items():
+        setattr(st, k, B.meta_from_numpy(mt, DEV))
+    hp = B.adam_hparams(1e-2, 5, stats=1)
+    say(f"FP16 decode sweep finite_only={finite_only} n={n}")
+    st.adam(hp)
+    torch.cuda.synchronize()
+    wq = np.zeros(pad, np.uint8)
+    O.adam_step_fp8(O.tensors_array(lay.tensors()), host["g8"], B.E5M2, metas["g_meta"], host["m"], metas["m_meta"],
+                    host["v"], metas["v_meta"], host["w"], metas["w_meta"], wq, metas["q_meta"], P.oracle_hp(hp))
+    assert np.array_equal(st.m[:n].cpu().numpy(), host["m"][:n])
+    assert np.array_equal(synth.bits16(st.v[:n]), host["v"][:n])
+    assert np.array_equal(synth.bits16(st.w[:n]), host["w"][:n])
+    assert np.array_equal(st.wq[:n].cpu().numpy(), wq[:n])
+    for k in ("m_meta", "v_meta", "w_meta", "q_meta"):
+        got = B.meta_to_numpy(getattr(st, k), 1)[0]
+        diff = P.meta_equal(got, metas[k][0], ["scale", "inv_scale", "amax", "amax_deq", "flags", "n_sat", "n_underflow"])
+        assert not diff, (k, diff, got, metas[k][0])
+
+
 # ---- whole-path lock-step parity ------------------------------------------------------------------------
 def run_lockstep(wl, seed, steps, ids=None, grad_fmt=B.E5M2, wcopy=B.WCOPY_E4M3, v_scaled=1, stats=0, exact=1,
                  check_steps=None, tuning=None, lr=None):
