@@ -45,7 +45,7 @@ META_DTYPE = np.dtype([
 
 class AutoscaleCfg(C.Structure):
     _fields_ = [("sat_num", C.c_int32), ("sat_den", C.c_int32), ("ramp_steps", C.c_int32),
-                ("hist_window", C.c_int32), ("margin", C.c_int32)]
+                ("hist_window", C.c_int32), ("margin", C.c_int32), ("mu_rule", C.c_int32), ("mu_min_exp", C.c_int32)]
 
 
 class AdamHparams(C.Structure):
@@ -54,8 +54,11 @@ class AdamHparams(C.Structure):
                 ("wcopy", C.c_int32), ("m_predict", C.c_int32), ("master_fmt", C.c_int32), ("v_fmt", C.c_int32)]
 
 
-def default_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=100000):
-    return AutoscaleCfg(sat_num, sat_den, ramp_steps, hist_window, margin)
+MU_SET_HALF, MU_HALVE = 0, 1
+
+
+def default_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=100000, mu_rule=MU_SET_HALF, mu_min_exp=-1):
+    return AutoscaleCfg(sat_num, sat_den, ramp_steps, hist_window, margin, mu_rule, mu_min_exp)
 
 
 def build(force: bool = False) -> str:

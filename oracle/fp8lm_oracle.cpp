@@ -162,7 +162,11 @@ typedef struct {
   uint64_t n_underflow;
 } oracle_meta;
 
-typedef struct { int32_t sat_num, sat_den, ramp_steps, hist_window, margin; } oracle_autoscale_cfg;
+typedef struct {
+  int32_t sat_num, sat_den, ramp_steps, hist_window, margin;
+  int32_t mu_rule;     // 0: the reading taken (set to 1/2, ramp back to 2); 1: the alternative (halve / double)
+  int32_t mu_min_exp;  // rule 1: lowest log2(mu)
+} oracle_autoscale_cfg;
 
 typedef struct {
   float lr, beta1, beta2, eps, weight_decay;
@@ -226,9 +230,37 @@ void oracle_meta_init(oracle_meta* meta, int32_t n, const oracle_autoscale_cfg* 
     std::memset(&M, 0, sizeof(M));
     M.scale = 1.0f;
     M.inv_scale = 1.0f;
-    M.clean_steps = cfg->ramp_steps / 2;
+    M.clean_steps = cfg->mu_rule == 1 ? 0 : cfg->ramp_steps / 2;
     M.mu_exp = 0;
   }
+}
+
+// ---- the auto-scaling state machine (Sec. 2.1, the paragraph after Eq. 3) ------------------------
+// The statistic is the share of stored payloads on the largest finite code; "overflow" means it is above
+// sat_num / sat_den (0.001 %).  The sentence that says what happens then is garbled; two readings:
+//   rule 0 (taken by default): on overflow mu is SET to 1/2 and the count of clean steps restarts; mu is a
+//     function of that count alone: 1/2 for the first ramp_steps/2 clean steps, 1 for the next
+//     ramp_steps/2, 2 from ramp_steps on ("exponentially increase mu to 2 over the span of 1,000 steps").
+//   rule 1 (alternative): every overflowing step HALVES mu, down to 2^mu_min_exp; every ramp_steps/2
+//     clean steps in a row double it, up to 2.  Unlike rule 0 it can follow a sum that grows by more than 2.
+// Takes effect in the next scale computation.
+static void autoscale_step(oracle_meta& M, uint64_t n_sat, int64_t n, const oracle_autoscale_cfg* cfg) {
+  const int R = cfg->ramp_steps < 2 ? 2 : cfg->ramp_steps;
+  const bool overflow = int64_t(n_sat) * int64_t(cfg->sat_den) > n * int64_t(cfg->sat_num);
+  if (cfg->mu_rule == 1) {
+    if (overflow) {
+      M.mu_exp = M.mu_exp - 1 < cfg->mu_min_exp ? cfg->mu_min_exp : M.mu_exp - 1;
+      M.clean_steps = 0;
+    } else if (++M.clean_steps >= R / 2) {
+      M.mu_exp = M.mu_exp + 1 > 1 ? 1 : M.mu_exp + 1;
+      M.clean_steps = 0;
+    }
+    return;
+  }
+  if (overflow) M.clean_steps = 0;
+  else M.clean_steps = M.clean_steps + 1 > R ? R : M.clean_steps + 1;
+  const int ramp = (2 * M.clean_steps) / R;
+  M.mu_exp = -1 + (ramp > 2 ? 2 : ramp);
 }
 
 // ---- the high-precision source of a cast ------------------------------------------------------
@@ -323,13 +355,7 @@ void oracle_cast_fp8_src(const void* src, int src_type, const oracle_tensor* ten
     M.n_underflow = n_under;
     M.amax_deq = stored_max * M.inv_scale;
     if (n_sat > 0) M.flags |= ORACLE_FLAG_SATURATED; else M.flags &= ~uint32_t(ORACLE_FLAG_SATURATED);
-    // auto-scaling state machine; takes effect in the next amax/scale call
-    const int R = cfg->ramp_steps < 2 ? 2 : cfg->ramp_steps;
-    const bool overflow = int64_t(n_sat) * int64_t(cfg->sat_den) > n * int64_t(cfg->sat_num);
-    if (overflow) M.clean_steps = 0;
-    else M.clean_steps = M.clean_steps + 1 > R ? R : M.clean_steps + 1;
-    const int ramp = (2 * M.clean_steps) / R;
-    M.mu_exp = -1 + (ramp > 2 ? 2 : ramp);
+    autoscale_step(M, n_sat, n, cfg);
   }
 }
 void oracle_cast_fp8(const uint16_t* src_bf16, const oracle_tensor* tensors, int32_t n_tensors,
@@ -471,12 +497,7 @@ void oracle_sum_fp8(const uint8_t* const* payloads, int32_t n_ranks, int fmt, co
     M.n_sat = n_sat;
     M.n_underflow = n_under;
     M.flags = (nonfinite ? uint32_t(ORACLE_FLAG_NONFINITE) : 0u) | (n_sat ? uint32_t(ORACLE_FLAG_SATURATED) : 0u);
-    const int R = cfg->ramp_steps < 2 ? 2 : cfg->ramp_steps;
-    const bool overflow = int64_t(n_sat) * int64_t(cfg->sat_den) > n * int64_t(cfg->sat_num);
-    if (overflow) M.clean_steps = 0;
-    else M.clean_steps = M.clean_steps + 1 > R ? R : M.clean_steps + 1;
-    const int ramp = (2 * M.clean_steps) / R;
-    M.mu_exp = -1 + (ramp > 2 ? 2 : ramp);
+    autoscale_step(M, n_sat, n, cfg);
   }
 }
 

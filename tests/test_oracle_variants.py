@@ -549,3 +549,57 @@ def test_quant_error_stats_uniform_noise_model(fmt, kind):
     assert st["n_underflow"] == 0 and st["n_nonzero"] == n and st["n_nonfinite"] == 0
     d = dec8(fmt, q[:n]).astype(np.float64) / float(meta[0]["scale"])
     assert st["noise"] == pytest.approx(np.sum((ref[:n].astype(np.float64) - d) ** 2), rel=1e-10)
+
+
+# ---- the two readings of the auto-scaling rule (Sec. 2.1, paragraph after Eq. 3) ---------------------------
+def _mu_trajectory(cfg, pattern):
+    """Drives the state machine through the FP8 sum of 8 ranks: 'O' = a step whose sum clips everywhere,
+    '.' = a step whose sum is far inside the range.  Returns log2(mu) after every step."""
+    lay = synth.flat_layout(48)
+    tens = O.tensors_array(lay.tensors())
+    shared = np.ones(1, dtype=np.float32)
+    meta = O.new_meta(1, cfg)
+    out = np.zeros(lay.total, dtype=np.uint8)
+    big = np.full(lay.total, O.encode_fp8(O.E5M2, np.array([16384.0], np.float32))[0], dtype=np.uint8)
+    small = np.full(lay.total, O.encode_fp8(O.E5M2, np.array([1.0], np.float32))[0], dtype=np.uint8)
+    traj = []
+    for ch in pattern:
+        O.sum_fp8([big if ch == "O" else small] * 8, O.E5M2, shared, tens, out, meta, cfg)
+        assert (meta[0]["n_sat"] == 48) == (ch == "O")
+        traj.append(int(meta[0]["mu_exp"]))
+    return traj
+
+
+def test_mu_rule_set_to_half_and_ramp():
+    """The reading taken: an overflow sets mu to 1/2 whatever it was; mu then depends on the clean steps alone."""
+    cfg = O.default_cfg(ramp_steps=4)
+    assert O.new_meta(1, cfg)[0]["mu_exp"] == 0 and O.new_meta(1, cfg)[0]["clean_steps"] == 2
+    #                                  O   O   O   .   .   .   .   .   O   .   .   O
+    assert _mu_trajectory(cfg, "OOO.....O..O") == [-1, -1, -1, -1, 0, 0, 1, 1, -1, -1, 0, -1]
+
+
+def test_mu_rule_halve_and_double():
+    """The alternative reading: every overflowing step halves mu down to the floor, every ramp_steps / 2 clean
+    steps in a row double it up to 2."""
+    cfg = O.default_cfg(ramp_steps=4, mu_rule=O.MU_HALVE, mu_min_exp=-3)
+    assert O.new_meta(1, cfg)[0]["mu_exp"] == 0 and O.new_meta(1, cfg)[0]["clean_steps"] == 0
+    #                                        O   O   O   O   O   .   .   .   .   .   O   .   .   .   .   .   .   .   .   .  .  O
+    assert _mu_trajectory(cfg, "OOOOO.....O..........O") == [-1, -2, -3, -3, -3, -3, -2, -2, -1, -1, -2, -2, -1, -1, 0, 0, 1, 1, 1, 1, 1, 0]
+    # an interrupted run of clean steps starts again
+    cfg = O.default_cfg(ramp_steps=6, mu_rule=O.MU_HALVE, mu_min_exp=-8)
+    assert _mu_trajectory(cfg, "O..O..O...") == [-1, -1, -1, -2, -2, -2, -3, -3, -3, -2]
+
+
+def test_mu_rules_scale_the_next_cast():
+    """Whatever the rule, the recorded factor multiplies the next just-in-time scale (Eq. 3)."""
+    lay = synth.flat_layout(64)
+    tens = O.tensors_array(lay.tensors())
+    g = np.zeros(lay.total, dtype=np.uint16)
+    g[:64] = bf16_bits(np.linspace(-1.0, 1.0, 64))
+    for rule, floor in ((O.MU_SET_HALF, -1), (O.MU_HALVE, -5)):
+        cfg = O.default_cfg(ramp_steps=4, mu_rule=rule, mu_min_exp=floor)
+        meta = O.new_meta(1, cfg)
+        for mu_exp in (0, -1, floor):
+            meta["mu_exp"] = mu_exp
+            O.amax_scale(g, tens, O.E5M2, meta, cfg)
+            assert meta[0]["scale"] == 2.0 ** (15 + mu_exp)              # 2^15 * 1.0 <= 57344 < 2^16
