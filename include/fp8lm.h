@@ -106,7 +106,14 @@ typedef struct {
   int32_t ramp_steps;  /* mu climbs from 1/2 to 2 over this many clean steps  [1000]               */
   int32_t hist_window; /* amax values that bound the scale, 1..FP8LM_HIST; 1 = just-in-time  [1]   */
   int32_t margin;      /* extra binades of headroom subtracted from the scale exponent  [0]        */
+  int32_t mu_rule;     /* fp8lm_mu_rule: which reading of the garbled sentence of Sec. 2.1  [SET_HALF] */
+  int32_t mu_min_exp;  /* FP8LM_MU_HALVE only: lowest log2(mu), -64..-1                             */
 } fp8lm_autoscale_cfg;
+/* FP8LM_MU_SET_HALF: an overflowing step sets mu to 1/2; mu then depends on the number of clean steps
+ * since: 1/2 below ramp_steps/2, 1 below ramp_steps, 2 from there on.  FP8LM_MU_HALVE: every overflowing
+ * step halves mu (down to 2^mu_min_exp), every ramp_steps/2 clean steps in a row double it (up to 2);
+ * needed when a sum over many ranks outgrows the FP8 range by more than a factor of 2.             */
+typedef enum { FP8LM_MU_SET_HALF = 0, FP8LM_MU_HALVE = 1 } fp8lm_mu_rule;
 
 /* Hyper-parameters of one AdamW step (Sec. 3.1.2: beta1 0.9, beta2 0.95, weight decay 0.1).
  * Accepted ranges: 0 <= lr <= 1024, 0 <= beta1, beta2 < 1, 2^-36 <= eps < inf,
@@ -156,7 +163,8 @@ fp8lm_status fp8lm_set_tuning(fp8lm_ctx* ctx, int32_t chunk_elems, int32_t block
                               int32_t single_pass_min_chunks);
 
 /*
- * Initial metadata: scale 1, empty amax history, mu = 1 (clean_steps = ramp_steps / 2), counters 0.
+ * Initial metadata: scale 1, empty amax history, mu = 1 (clean_steps = ramp_steps / 2; 0 with
+ * FP8LM_MU_HALVE), counters 0.
  *   meta : device array of n entries (n = the context's tensor count), overwritten.
  */
 fp8lm_status fp8lm_meta_init(fp8lm_ctx* ctx, fp8lm_meta* meta /*device*/, const fp8lm_autoscale_cfg* cfg /*host*/,

@@ -106,13 +106,19 @@ def main(argv=None) -> None:
     ap.add_argument("--signal", type=float, default=0.25, help="weight of the component all ranks share")
     ap.add_argument("--ramp-steps", type=int, default=8)
     ap.add_argument("--heavy-tails", action="store_true")
+    ap.add_argument("--mu-rule", choices=["set-half", "halve"], default="set-half",
+                    help="reading of the auto-scaling rule: set mu to 1/2 on overflow (default), or halve it on every "
+                         "overflowing step down to 1/ranks")
     a = ap.parse_args(argv)
     wl = synth.workload(a.workload)
     if a.heavy_tails:
         wl.grad_kind = "student_t"
     lay = wl.layout
     fmt = B.E5M2 if a.fmt == "e5m2" else B.E4M3
-    cfg = B.autoscale_cfg(ramp_steps=a.ramp_steps)
+    if a.mu_rule == "halve":
+        cfg = B.autoscale_cfg(ramp_steps=a.ramp_steps, mu_rule=B.MU_HALVE, mu_min_exp=-max(1, int(math.ceil(math.log2(a.ranks)))))
+    else:
+        cfg = B.autoscale_cfg(ramp_steps=a.ramp_steps)
     ctx = B.Context(lay.tensors())
     size = max(lay.total, 16)
     common = torch.zeros(size, dtype=torch.float32, device="cuda:0")
@@ -130,7 +136,7 @@ def main(argv=None) -> None:
             out[s] = report(grp.error_stats(mean), lay.numels)
         del mean
     print(json.dumps({"workload": a.workload, "ranks": a.ranks, "fmt": a.fmt, "steps": a.steps, "signal": a.signal,
-                      "heavy_tails": a.heavy_tails, "ramp_steps": a.ramp_steps, "last_step": out}))
+                      "heavy_tails": a.heavy_tails, "ramp_steps": a.ramp_steps, "mu_rule": a.mu_rule, "last_step": out}))
 
 
 if __name__ == "__main__":

@@ -22,6 +22,7 @@ E4M3, E5M2 = 0, 1
 SRC_BF16, SRC_F16, SRC_F32 = 0, 1, 2
 WCOPY_E4M3, WCOPY_BF16 = 0, 1
 MSCALE_EXACT_PASS, MSCALE_PREDICTED, MSCALE_FROM_CAST = 0, 1, 2
+MU_SET_HALF, MU_HALVE = 0, 1
 STATE_F16, STATE_BF16, STATE_E4M3, STATE_F32 = 0, 1, 2, 3
 STATE_BYTES = {STATE_F16: 2, STATE_BF16: 2, STATE_E4M3: 1, STATE_F32: 4}
 FLAG_NONFINITE, FLAG_AMAX_ZERO, FLAG_SCALE_CLAMPED, FLAG_SATURATED = 1, 2, 4, 8
@@ -69,7 +70,7 @@ META_DTYPE = np.dtype([
 
 class AutoscaleCfg(C.Structure):
     _fields_ = [("sat_num", C.c_int32), ("sat_den", C.c_int32), ("ramp_steps", C.c_int32),
-                ("hist_window", C.c_int32), ("margin", C.c_int32)]
+                ("hist_window", C.c_int32), ("margin", C.c_int32), ("mu_rule", C.c_int32), ("mu_min_exp", C.c_int32)]
 
 
 class AdamHparams(C.Structure):
@@ -79,8 +80,11 @@ class AdamHparams(C.Structure):
                 ("v_fmt", C.c_int32), ("exact", C.c_int32)]
 
 
-def autoscale_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=100000) -> AutoscaleCfg:
-    return AutoscaleCfg(sat_num, sat_den, ramp_steps, hist_window, margin)
+def autoscale_cfg(ramp_steps=1000, hist_window=1, margin=0, sat_num=1, sat_den=100000, mu_rule=0,
+                  mu_min_exp=-1) -> AutoscaleCfg:
+    """mu_rule: MU_SET_HALF (the reading taken by default) or MU_HALVE (halve on every overflowing step down to
+    2^mu_min_exp, double after ramp_steps / 2 clean ones)."""
+    return AutoscaleCfg(sat_num, sat_den, ramp_steps, hist_window, margin, mu_rule, mu_min_exp)
 
 
 def adam_hparams(lr, step, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, v_scaled=1,

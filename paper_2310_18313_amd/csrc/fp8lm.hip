@@ -210,7 +210,13 @@ void launch_update_variant(fp8lm_ctx* c, hipStream_t s, const AdamParams& p, boo
 }
 
 bool src_ok(fp8lm_src t) { return t == FP8LM_SRC_BF16 || t == FP8LM_SRC_F16 || t == FP8LM_SRC_F32; }
+AutoscaleRule rule_of(const fp8lm_autoscale_cfg* cfg) {
+  return AutoscaleRule{cfg->sat_num, cfg->sat_den, cfg->ramp_steps, cfg->mu_rule, cfg->mu_min_exp};
+}
 bool cfg_ok(const fp8lm_autoscale_cfg* cfg) {
+  if (cfg && cfg->mu_rule != FP8LM_MU_SET_HALF &&
+      !(cfg->mu_rule == FP8LM_MU_HALVE && cfg->mu_min_exp >= -64 && cfg->mu_min_exp <= -1))
+    return false;
   return cfg && cfg->sat_num >= 0 && cfg->sat_den > 0 && cfg->ramp_steps >= 2 && cfg->hist_window >= 1 &&
          cfg->hist_window <= FP8LM_HIST && cfg->margin >= -64 && cfg->margin <= 64;
 }
@@ -308,7 +314,7 @@ fp8lm_status fp8lm_meta_init(fp8lm_ctx* c, fp8lm_meta* meta, const fp8lm_autosca
   DeviceGuard guard(c->device);
   const int blocks = (c->n_tensors + 255) / 256;
   hipLaunchKernelGGL(meta_init_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, meta, c->n_tensors,
-                     cfg->ramp_steps / 2);
+                     cfg->mu_rule == FP8LM_MU_HALVE ? 0 : cfg->ramp_steps / 2);
   return after_launch();
 }
 
@@ -353,7 +359,8 @@ static fp8lm_status cast_impl(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
   p.src = src;
   p.dst = dst;
   p.meta = meta;
-  p.sat_num = cfg->sat_num; p.sat_den = cfg->sat_den; p.ramp_steps = cfg->ramp_steps; p.hist_window = cfg->hist_window;
+  p.rule = rule_of(cfg);
+  p.hist_window = cfg->hist_window;
   p.m = m;
   p.m_meta = m_meta;
   p.b1 = beta1;
@@ -449,7 +456,7 @@ fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* c, const uint8_t* const* payloads, int32_t
   }
   if (!aligned16(dst)) return FP8LM_ERR_MISALIGNED;
   p.shared = shared; p.dst = dst; p.dst_meta = dst_meta;
-  p.sat_num = cfg->sat_num; p.sat_den = cfg->sat_den; p.ramp_steps = cfg->ramp_steps;
+  p.rule = rule_of(cfg);
   DeviceGuard guard(c->device);
   Timed tm(c, (hipStream_t)stream, FP8LM_K_SUM);
   hipStream_t s = (hipStream_t)stream;

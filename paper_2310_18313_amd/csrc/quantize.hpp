@@ -170,10 +170,28 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(Tables tb, AmaxParams p)
 // Kernel 2: scaled saturating FP8 cast + auto-scaling state (Sec. 2.1; Appendix A.1)
 // ================================================================================================
 // The auto-scaling state machine of Sec. 2.1 (text after Eq. 3), shared by the cast and the sum.
-__device__ __forceinline__ void autoscale_update(fp8lm_meta& M, unsigned long long n_sat, long long numel, int sat_num,
-                                                 int sat_den, int ramp_steps) {
-  const int R = ramp_steps < 2 ? 2 : ramp_steps;
-  const bool overflow = (long long)n_sat * (long long)sat_den > numel * (long long)sat_num;
+// mu_rule 0: an overflow sets mu to 1/2; mu then follows the count of clean steps (1/2, 1, 2 as it passes
+// 0, ramp_steps/2, ramp_steps).  mu_rule 1, the other reading of the same sentence: every overflowing step
+// halves mu down to 2^mu_min_exp, every ramp_steps/2 clean steps in a row double it up to 2.
+struct AutoscaleRule {
+  int32_t sat_num, sat_den, ramp_steps, mu_rule, mu_min_exp;
+};
+__device__ __forceinline__ void autoscale_update(fp8lm_meta& M, unsigned long long n_sat, long long numel,
+                                                 const AutoscaleRule& a) {
+  const int R = a.ramp_steps < 2 ? 2 : a.ramp_steps;
+  const bool overflow = (long long)n_sat * (long long)a.sat_den > numel * (long long)a.sat_num;
+  if (a.mu_rule == 1) {
+    if (overflow) {
+      M.mu_exp = M.mu_exp - 1 < a.mu_min_exp ? a.mu_min_exp : M.mu_exp - 1;
+      M.clean_steps = 0;
+    } else if (M.clean_steps + 1 >= R / 2) {
+      M.mu_exp = M.mu_exp + 1 > 1 ? 1 : M.mu_exp + 1;
+      M.clean_steps = 0;
+    } else {
+      M.clean_steps = M.clean_steps + 1;
+    }
+    return;
+  }
   const int clean = overflow ? 0 : (M.clean_steps + 1 > R ? R : M.clean_steps + 1);
   M.clean_steps = clean;
   const int ramp = (2 * clean) / R;
@@ -184,7 +202,7 @@ struct CastParams {
   const void* src;
   uint8_t* dst;
   fp8lm_meta* meta;
-  int32_t sat_num, sat_den, ramp_steps;
+  AutoscaleRule rule;
   int32_t hist_window;   // delayed scaling only
   // fused first pass of the Adam step (FUSE): the first moment as it stands and beta1
   const uint8_t* m;
@@ -407,7 +425,7 @@ struct CastOp {
     M.n_underflow = n_und;
     M.amax_deq = fp8_to_f32<FMT>(encode1_fp8<FMT>(vm)) * M.inv_scale;
     M.flags = n_sat ? (M.flags | FP8LM_FLAG_SATURATED) : (M.flags & ~FP8LM_FLAG_SATURATED);
-    autoscale_update(M, n_sat, d.numel, p.sat_num, p.sat_den, p.ramp_steps);
+    autoscale_update(M, n_sat, d.numel, p.rule);
   }
 };
 
@@ -545,7 +563,7 @@ struct SumParams {
   const float* shared;
   uint8_t* dst;
   fp8lm_meta* dst_meta;
-  int32_t sat_num, sat_den, ramp_steps;
+  AutoscaleRule rule;
 };
 
 // Eq. 6 on one GPU: the payloads of all ranks (same shared scale) are added in rank order in fp32 and
@@ -690,7 +708,7 @@ struct SumOp {
         M.n_sat = n_sat;
         M.n_underflow = n_under;
         M.flags = (nf ? FP8LM_FLAG_NONFINITE : 0u) | (n_sat ? FP8LM_FLAG_SATURATED : 0u);
-        autoscale_update(M, n_sat, d.numel, p.sat_num, p.sat_den, p.ramp_steps);
+        autoscale_update(M, n_sat, d.numel, p.rule);
       }
     }
   }

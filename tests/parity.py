@@ -48,7 +48,8 @@ def ordered8(bits: np.ndarray) -> np.ndarray:
 
 
 def oracle_cfg(cfg: B.AutoscaleCfg) -> O.AutoscaleCfg:
-    return O.AutoscaleCfg(cfg.sat_num, cfg.sat_den, cfg.ramp_steps, cfg.hist_window, cfg.margin)
+    return O.AutoscaleCfg(cfg.sat_num, cfg.sat_den, cfg.ramp_steps, cfg.hist_window, cfg.margin, cfg.mu_rule,
+                          cfg.mu_min_exp)
 
 
 def oracle_hp(hp: B.AdamHparams) -> O.AdamHparams:

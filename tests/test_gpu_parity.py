@@ -867,3 +867,64 @@ def test_random_layouts_and_hyper_parameters_match_the_oracle():
             st.step(grad, hp, delayed=delayed)
             torch.cuda.synchronize()
             P.check_step(st, snaps, hp, what=f"random case {case} step {k}", delayed=delayed)
+
+
+# ---- the alternative reading of the auto-scaling rule ------------------------------------------------------------
+@pytest.mark.parametrize("fmt", [B.E5M2, B.E4M3])
+def test_halving_rule_follows_the_oracle_through_cast_and_sum(fmt):
+    """mu_rule = MU_HALVE: eight ranks whose sum outgrows the range by far more than 2.  The summed gradient's
+    statistic drives mu (fed back to the ranks' casts), step after step, on both sides."""
+    from paper_2310_18313_amd.allreduce_study import Fp8AllReduce
+    n_ranks, steps = 8, 14
+    lay = synth.Layout(["a", "b", "c"], [30001, 4096, 200])
+    wl = synth.Workload("halve", lay, lr=1e-3, sigma=1e-2, ramp_steps=6)
+    cfg = B.autoscale_cfg(ramp_steps=6, mu_rule=B.MU_HALVE, mu_min_exp=-6)
+    ocfg = P.oracle_cfg(cfg)
+    assert ocfg.mu_rule == 1 and ocfg.mu_min_exp == -6
+    tens = O.tensors_array(lay.tensors())
+    ctx = B.Context(lay.tensors())
+    size = max(lay.total, 16)
+    common = torch.zeros(size, dtype=torch.float32, device=DEV)
+    grads = [torch.zeros(size, dtype=torch.float32, device=DEV) for _ in range(n_ranks)]
+    ar = Fp8AllReduce(ctx, n_ranks, lay.total, fmt, cfg, "auto")
+    o_meta = [O.new_meta(lay.n_tensors, ocfg) for _ in range(n_ranks)]
+    o_sum_meta = O.new_meta(lay.n_tensors, ocfg)
+    assert np.array_equal(B.meta_to_numpy(ar.summed_meta, lay.n_tensors)["clean_steps"], o_sum_meta["clean_steps"])
+    seen = set()
+    for step in range(1, steps + 1):
+        synth.fill_gradients(common, wl, 77, step)
+        for r in range(n_ranks):
+            synth.fill_gradients(grads[r], wl, 500 + r, step)
+            grads[r].mul_(0.05).add_(common)                   # almost the same gradient on every rank: the sum is 8x
+        say(f"halving rule fmt={fmt} step={step}")
+        ar.step(grads)
+        torch.cuda.synchronize()
+        h = [g.cpu().numpy() for g in grads]
+        pay = []
+        for r in range(n_ranks):
+            o_meta[r]["mu_exp"], o_meta[r]["clean_steps"] = o_sum_meta["mu_exp"], o_sum_meta["clean_steps"]
+            q = np.zeros(size, dtype=np.uint8)
+            O.amax_scale(h[r], tens, fmt, o_meta[r], ocfg, src_type=O.SRC_F32)
+            O.cast_fp8(h[r], tens, q, fmt, o_meta[r], ocfg, src_type=O.SRC_F32)
+            pay.append(q)
+        shared = O.shared_scale(o_meta, lay.n_tensors)
+        rq = []
+        for r in range(n_ranks):
+            q2, m2 = np.zeros(size, dtype=np.uint8), O.new_meta(lay.n_tensors, ocfg)
+            O.requantize_fp8(pay[r], fmt, o_meta[r], shared, tens, q2, m2)
+            rq.append(q2)
+        o_sum = np.zeros(size, dtype=np.uint8)
+        O.sum_fp8(rq, fmt, shared, tens, o_sum, o_sum_meta, ocfg)
+        assert np.array_equal(ar.summed.cpu().numpy(), o_sum), f"step {step}: summed payload differs"
+        gm = B.meta_to_numpy(ar.summed_meta, lay.n_tensors)
+        for t in range(lay.n_tensors):
+            bad = P.meta_equal(gm[t], o_sum_meta[t], ["scale", "inv_scale", "amax_deq", "mu_exp", "clean_steps", "n_sat", "flags"])
+            assert not bad, (step, t, bad, gm[t], o_sum_meta[t])
+            rm = B.meta_to_numpy(ar.meta[0], lay.n_tensors)[t]
+            bad = P.meta_equal(rm, o_meta[0][t], P.ALL_FIELDS)
+            assert not bad, (step, t, bad, rm, o_meta[0][t])
+        seen.update(int(x) for x in gm["mu_exp"])
+    assert min(seen) <= -3, seen                               # mu went well below the 1/2 floor of the default rule
+    bad_cfg = B.autoscale_cfg(mu_rule=B.MU_HALVE, mu_min_exp=0)
+    with pytest.raises(B.Fp8lmError):
+        ctx.new_meta(bad_cfg)
