@@ -90,13 +90,15 @@ struct DeviceGuard {
   ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
 };
 
-fp8lm_status build_tables(fp8lm_ctx* c) {
+// Builds the tensor and chunk tables for chunks of chunk_elems elements and installs them.  On failure the
+// context keeps the tables (and the chunk size) it had.
+fp8lm_status build_tables(fp8lm_ctx* c, int32_t chunk_elems) {
   std::vector<TensorDesc> desc(c->n_tensors);
   std::vector<int32_t> chunk_tensor;
   long long total_chunks = 0;
   for (int t = 0; t < c->n_tensors; ++t) {
     const long long n = c->tensors[t].numel;
-    const long long nc = (n + c->chunk_elems - 1) / c->chunk_elems;
+    const long long nc = (n + chunk_elems - 1) / chunk_elems;
     if (total_chunks + nc > 0x7FFFFFF0LL) return FP8LM_ERR_TOO_LARGE;
     desc[t] = TensorDesc{c->tensors[t].offset, n, (int32_t)total_chunks, (int32_t)nc};
     total_chunks += nc;
@@ -104,16 +106,26 @@ fp8lm_status build_tables(fp8lm_ctx* c) {
   chunk_tensor.resize((size_t)total_chunks);
   for (int t = 0; t < c->n_tensors; ++t)
     std::fill(chunk_tensor.begin() + desc[t].first_chunk, chunk_tensor.begin() + desc[t].first_chunk + desc[t].n_chunks, t);
-  if (c->d_desc) HIP_TRY(hipFree(c->d_desc));
-  if (c->d_chunk_tensor) HIP_TRY(hipFree(c->d_chunk_tensor));
-  c->d_desc = nullptr;
-  c->d_chunk_tensor = nullptr;
+  TensorDesc* d_desc = nullptr;
+  int32_t* d_chunk_tensor = nullptr;
+  hipError_t e = hipMalloc((void**)&d_desc, std::max<size_t>(1, desc.size()) * sizeof(TensorDesc));
+  if (e == hipSuccess) e = hipMalloc((void**)&d_chunk_tensor, std::max<size_t>(1, chunk_tensor.size()) * sizeof(int32_t));
+  if (e == hipSuccess && !desc.empty())
+    e = hipMemcpy(d_desc, desc.data(), desc.size() * sizeof(TensorDesc), hipMemcpyHostToDevice);
+  if (e == hipSuccess && !chunk_tensor.empty())
+    e = hipMemcpy(d_chunk_tensor, chunk_tensor.data(), chunk_tensor.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    g_hip_error = std::string("chunk tables: ") + hipGetErrorString(e);
+    if (d_desc) (void)hipFree(d_desc);
+    if (d_chunk_tensor) (void)hipFree(d_chunk_tensor);
+    return FP8LM_ERR_HIP;
+  }
+  if (c->d_desc) (void)hipFree(c->d_desc);
+  if (c->d_chunk_tensor) (void)hipFree(c->d_chunk_tensor);
+  c->d_desc = d_desc;
+  c->d_chunk_tensor = d_chunk_tensor;
+  c->chunk_elems = chunk_elems;
   c->n_chunks = (int32_t)total_chunks;
-  HIP_TRY(hipMalloc((void**)&c->d_desc, std::max<size_t>(1, desc.size()) * sizeof(TensorDesc)));
-  HIP_TRY(hipMalloc((void**)&c->d_chunk_tensor, std::max<size_t>(1, chunk_tensor.size()) * sizeof(int32_t)));
-  if (!desc.empty()) HIP_TRY(hipMemcpy(c->d_desc, desc.data(), desc.size() * sizeof(TensorDesc), hipMemcpyHostToDevice));
-  if (!chunk_tensor.empty())
-    HIP_TRY(hipMemcpy(c->d_chunk_tensor, chunk_tensor.data(), chunk_tensor.size() * sizeof(int32_t), hipMemcpyHostToDevice));
   return FP8LM_OK;
 }
 
@@ -267,7 +279,7 @@ fp8lm_status fp8lm_create(fp8lm_ctx** out, const fp8lm_tensor* tensors, int32_t 
   c->n_tensors = n;
   c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   c->tensors.assign(tensors, tensors + n);
-  fp8lm_status st = build_tables(c);
+  fp8lm_status st = build_tables(c, c->chunk_elems);
   if (st == FP8LM_OK) {
     const size_t bytes = std::max<size_t>(1, (size_t)n) * sizeof(Scratch);
     hipError_t e = hipMalloc((void**)&c->d_scratch, bytes);
@@ -301,11 +313,12 @@ fp8lm_status fp8lm_set_tuning(fp8lm_ctx* c, int32_t chunk_elems, int32_t blocks_
       blocks_per_cu > kMaxBlocksPerCu || single_pass_min_chunks < 0 || single_pass_min_chunks > (1 << 30))
     return FP8LM_ERR_INVALID_ARGUMENT;
   DeviceGuard guard(c->device);
-  HIP_TRY(hipDeviceSynchronize());
-  c->chunk_elems = chunk_elems;
+  HIP_TRY(hipDeviceSynchronize());   // no launch may still be reading the tables that are about to go
+  const fp8lm_status st = build_tables(c, chunk_elems);
+  if (st != FP8LM_OK) return st;
   c->blocks_per_cu = blocks_per_cu;
   c->single_pass_min_chunks = single_pass_min_chunks;
-  return build_tables(c);
+  return FP8LM_OK;
 }
 
 fp8lm_status fp8lm_meta_init(fp8lm_ctx* c, fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {
@@ -584,7 +597,6 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
   return after_launch();
 }
 
-// Host only.  Whole-tensor greedy distribution of Sec. 2.3, Alg. 1, with a heap over the GPUs.
 fp8lm_status fp8lm_quant_error_stats(fp8lm_ctx* c, const void* ref, fp8lm_src ref_type, const uint8_t* q, fp8lm_fmt fmt,
                                      const fp8lm_meta* q_meta, fp8lm_quant_stats* out, void* stream) {
   if (!c || !src_ok(ref_type) || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2)) return FP8LM_ERR_INVALID_ARGUMENT;
@@ -615,6 +627,7 @@ fp8lm_status fp8lm_quant_error_stats(fp8lm_ctx* c, const void* ref, fp8lm_src re
   return after_launch();
 }
 
+// Host only.  Whole-tensor greedy distribution of Sec. 2.3, Alg. 1, with a heap over the GPUs.
 fp8lm_status fp8lm_greedy_partition(const int64_t* sizes, int32_t n, int32_t n_gpus, int32_t* owner, int64_t* usage) {
   if (n < 0 || n_gpus < 1 || (n > 0 && (!sizes || !owner)) || !usage) return FP8LM_ERR_INVALID_ARGUMENT;
   for (int32_t i = 0; i < n; ++i)
@@ -656,9 +669,13 @@ fp8lm_status fp8lm_set_timing(fp8lm_ctx* c, int32_t enable) {
   DeviceGuard guard(c->device);
   if (enable && c->free_events.empty() && c->stamps.empty()) {
     for (int i = 0; i < 4096; ++i) {
-      hipEvent_t a, b;
+      hipEvent_t a = nullptr, b = nullptr;
       HIP_TRY(hipEventCreate(&a));
-      HIP_TRY(hipEventCreate(&b));
+      if (hipError_t e = hipEventCreate(&b); e != hipSuccess) {
+        (void)hipEventDestroy(a);
+        g_hip_error = std::string("hipEventCreate: ") + hipGetErrorString(e);
+        return FP8LM_ERR_HIP;
+      }
       c->free_events.emplace_back(a, b);
     }
   }
