@@ -1,5 +1,6 @@
 """GPU parity tests: the HIP path behind the C ABI against the CPU oracle, element by element."""
 import ctypes as C
+import os
 
 import numpy as np
 import pytest
@@ -928,3 +929,18 @@ def test_halving_rule_follows_the_oracle_through_cast_and_sum(fmt):
     bad_cfg = B.autoscale_cfg(mu_rule=B.MU_HALVE, mu_min_exp=0)
     with pytest.raises(B.Fp8lmError):
         ctx.new_meta(bad_cfg)
+
+
+def test_c_program_steps_identically_to_the_oracle_through_the_c_abi():
+    """No Python between the caller and the library: a C++ program (built beforehand) drives five free-running steps
+    through include/fp8lm.h on ragged tensors and compares every byte and metadata field with the oracle."""
+    import subprocess
+    import c_abi_build
+    exe = c_abi_build.build()          # a host-only compile of two seconds, and only if the program is missing or stale
+    assert os.path.exists(exe)
+    say("c_abi_parity: 5 steps")
+    r = subprocess.run([exe, O.build(), "5"], capture_output=True, text=True, timeout=120)
+    say(r.stdout.strip().splitlines()[-1] if r.stdout.strip() else r.stderr[-300:])
+    assert r.returncode == 0, (r.returncode, r.stdout[-2000:], r.stderr[-2000:])
+    assert "identical after 5 steps" in r.stdout
+    assert "log2 mu between -1 and 1" in r.stdout          # the auto-scaling state went through all three values

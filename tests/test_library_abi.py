@@ -69,3 +69,18 @@ def test_there_is_no_fallback_when_the_library_is_missing(monkeypatch, tmp_path)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libfp8lm.so"))
     with pytest.raises(ImportError):
         B.lib()
+
+
+def test_c_program_against_the_header_builds_and_fails_loudly_without_a_gpu():
+    """tests/c_abi_parity.cpp includes only include/fp8lm.h and links libfp8lm.so: it compiling and linking shows
+    the header is plain C-callable; without a GPU its first library call must report the HIP error."""
+    import subprocess
+    import torch
+    import c_abi_build
+    import oracle as O
+    exe = c_abi_build.build()
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present: the run itself is a gpu test")
+    r = subprocess.run([exe, O.build()], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 2, (r.returncode, r.stdout, r.stderr)
+    assert "fp8lm_create" in r.stderr and "HIP runtime error" in r.stderr
