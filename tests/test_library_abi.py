@@ -84,3 +84,21 @@ def test_c_program_against_the_header_builds_and_fails_loudly_without_a_gpu():
     r = subprocess.run([exe, O.build()], capture_output=True, text=True, timeout=60)
     assert r.returncode == 2, (r.returncode, r.stdout, r.stderr)
     assert "fp8lm_create" in r.stderr and "HIP runtime error" in r.stderr
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/fp8lm.h compiles as pedantic C99 with every warning on, and its structures have the sizes the
+    Python binding assumes."""
+    import subprocess
+    src = tmp_path / "hdr.c"
+    src.write_text(
+        '#include "fp8lm.h"\n'
+        "#define CHECK(name, cond) typedef char name[(cond) ? 1 : -1]\n"
+        f"CHECK(meta_size, sizeof(fp8lm_meta) == {C.sizeof(B.Meta)});\n"
+        f"CHECK(cfg_size, sizeof(fp8lm_autoscale_cfg) == {C.sizeof(B.AutoscaleCfg)});\n"
+        f"CHECK(hp_size, sizeof(fp8lm_adam_hparams) == {C.sizeof(B.AdamHparams)});\n"
+        f"CHECK(tensor_size, sizeof(fp8lm_tensor) == {C.sizeof(B.Tensor)});\n"
+        "int main(void) { return 0; }\n")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                        "-fsyntax-only", str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
