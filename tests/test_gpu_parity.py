@@ -222,6 +222,34 @@ def test_free_running_oracle_and_gpu_end_in_the_same_state(name, steps):
     fr.assert_equal_to(st, f"{name} after {steps} free-running steps")
 
 
+@pytest.mark.parametrize("mu_rule", [B.MU_SET_HALF, B.MU_HALVE])
+def test_three_hundred_free_running_steps_with_heavy_tails(mu_rule):
+    """A long run without any exchange of state: heavy-tailed gradients and a ramp of 20 steps take mu through many
+    overflow / recovery cycles, the amax history (window 3) and every scale move all the time; the two sides must
+    still hold the same bytes at steps 50, 150 and 300."""
+    wl = synth.Workload("long", synth.gpt_layout(128, 2, 512, 1000), lr=1e-3, grad_kind="student_t", sigma=None,
+                        hist_window=3, ramp_steps=20)
+    cfg = B.autoscale_cfg(ramp_steps=20, hist_window=3, mu_rule=mu_rule, mu_min_exp=-4)
+    st = OptimizerState(wl.layout.tensors(), wl.layout.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
+    w0 = torch.zeros(max(wl.layout.total, 16), dtype=torch.bfloat16, device=DEV)
+    synth.fill_weights(w0, wl.layout, 21)
+    st.init_master(w0)
+    fr = P.FreeRunningOracle(wl.layout, cfg, synth.bits16(w0), threads=16)
+    grad = torch.zeros(max(wl.layout.total, 16), dtype=torch.bfloat16, device=DEV)
+    mus = set()
+    for step in range(1, 301):
+        synth.fill_gradients(grad, wl, 21, step)
+        hp = B.adam_hparams(wl.lr, step)
+        st.step(grad, hp)
+        fr.step(synth.bits16(grad), hp)
+        if step in (50, 150, 300):
+            say(f"long free-running run, mu rule {mu_rule}: comparing at step {step}")
+            torch.cuda.synchronize()
+            fr.assert_equal_to(st, f"step {step} of the long free-running run")
+            mus.update(int(x) for x in B.meta_to_numpy(st.g_meta, wl.layout.n_tensors)["mu_exp"])
+    assert len(mus) >= 2, mus
+
+
 # chunk size, workgroups per CU, and both forms of the cross-workgroup reduction (third entry 0: tickets in the
 # same launch; large: a second launch finishes the tensors)
 @pytest.mark.parametrize("tuning", [(4096, 1, 0), (4096, 16, 0), (65536, 4, 0), (1048576, 2, 0), (16384, 16, 0),
