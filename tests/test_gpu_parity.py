@@ -851,6 +851,50 @@ def test_parameter_groups_share_the_flat_buffers():
         P.check_step(st_p, snaps_p, hp_p, what=f"no-decay group step {step}")
 
 
+def test_shards_of_the_greedy_distribution_step_like_the_whole_model():
+    """Sec. 2.3, Alg. 1 on one GPU: the tensors are dealt to eight owners by the greedy rule; every owner steps only
+    its own tensors (a context over its tensor list, its own metadata) inside the shared flat buffers.  The union of
+    the shards must hold the bytes and the scales of the whole model stepped by one context, which in turn is checked
+    against the free-running oracle."""
+    wl = synth.Workload("shards", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-3, sigma=None)
+    lay, tens = wl.layout, wl.layout.tensors()
+    owner, usage = B.greedy_partition(np.array(lay.numels, dtype=np.int64) * 7, 8)
+    assert usage.max() <= usage.sum() / 8 + max(lay.numels) * 7
+    cfg = B.autoscale_cfg(ramp_steps=4, hist_window=2)
+    whole = OptimizerState(tens, lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
+    ids = [[t for t in range(lay.n_tensors) if owner[t] == r] for r in range(8)]
+    assert all(ids)
+    shards = [OptimizerState([tens[t] for t in ids[0]], lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)]
+    shards += [OptimizerState([tens[t] for t in ids[r]], lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, share_with=shards[0])
+               for r in range(1, 8)]
+    w0 = torch.zeros(max(lay.total, 16), dtype=torch.bfloat16, device=DEV)
+    synth.fill_weights(w0, lay, 23)
+    whole.init_master(w0)
+    for sh in shards:
+        sh.init_master(w0)
+    fr = P.FreeRunningOracle(lay, cfg, synth.bits16(w0), threads=8)
+    grad = torch.zeros(max(lay.total, 16), dtype=torch.bfloat16, device=DEV)
+    for step in range(1, 7):
+        synth.fill_gradients(grad, wl, 23, step)
+        if step == 4:
+            grad.mul_(32.0)                       # a jump the amax history and mu have to follow
+        hp = B.adam_hparams(wl.lr, step)
+        say(f"greedy shards step {step}")
+        whole.step(grad, hp)
+        for sh in shards:
+            sh.step(grad, hp)
+        fr.step(synth.bits16(grad), hp)
+    torch.cuda.synchronize()
+    fr.assert_equal_to(whole, "whole model after 6 steps")
+    for name in ("g8", "m", "v", "w", "wq"):
+        assert torch.equal(getattr(shards[0], name), getattr(whole, name)), f"{name}: union of the shards differs"
+    for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta"):
+        ref = B.meta_to_numpy(getattr(whole, k), lay.n_tensors)
+        for r, sh in enumerate(shards):
+            got = B.meta_to_numpy(getattr(sh, k), len(ids[r]))
+            assert got.tobytes() == ref[ids[r]].tobytes(), f"{k} of owner {r} differs from the whole model's rows"
+
+
 # ---- randomised differential test -----------------------------------------------------------------------------
 def test_random_layouts_and_hyper_parameters_match_the_oracle():
     """Sixty seeded random cases: ragged tensor sizes, gradient scales over forty binades, hyper-parameters at and
