@@ -851,6 +851,35 @@ def test_parameter_groups_share_the_flat_buffers():
         P.check_step(st_p, snaps_p, hp_p, what=f"no-decay group step {step}")
 
 
+def test_two_contexts_on_two_streams_at_once():
+    """One context per stream is the rule; two contexts on two streams may run at the same time (each has its own
+    records and scratch).  Two halves of a layout are stepped concurrently and each must match the oracle."""
+    wl = synth.Workload("streams", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-3, sigma=None)
+    lay, tens = wl.layout, wl.layout.tensors()
+    halves = [list(range(0, lay.n_tensors, 2)), list(range(1, lay.n_tensors, 2))]
+    cfg = B.autoscale_cfg()
+    st = [OptimizerState([tens[t] for t in halves[0]], lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)]
+    st.append(OptimizerState([tens[t] for t in halves[1]], lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, share_with=st[0]))
+    w0 = torch.zeros(max(lay.total, 16), dtype=torch.bfloat16, device=DEV)
+    synth.fill_weights(w0, lay, 29)
+    for x in st:
+        x.init_master(w0)
+    grad = torch.zeros(max(lay.total, 16), dtype=torch.bfloat16, device=DEV)
+    streams = [torch.cuda.Stream(device=DEV), torch.cuda.Stream(device=DEV)]
+    for step in (1, 2, 3):
+        synth.fill_gradients(grad, wl, 29, step)
+        hp = B.adam_hparams(wl.lr, step)
+        snaps = [[P.Snapshot(x, grad, t) for t in range(len(h))] for x, h in zip(st, halves)]
+        torch.cuda.synchronize()
+        say(f"two streams step {step}")
+        for x, s in zip(st, streams):
+            with torch.cuda.stream(s):
+                x.step(grad, hp)
+        torch.cuda.synchronize()
+        for k, x in enumerate(st):
+            P.check_step(x, snaps[k], hp, what=f"stream {k} step {step}")
+
+
 def test_shards_of_the_greedy_distribution_step_like_the_whole_model():
     """Sec. 2.3, Alg. 1 on one GPU: the tensors are dealt to eight owners by the greedy rule; every owner steps only
     its own tensors (a context over its tensor list, its own metadata) inside the shared flat buffers.  The union of
