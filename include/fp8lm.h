@@ -101,8 +101,8 @@ typedef struct {
 
 /* Auto-scaling configuration (Sec. 2.1, paragraph after Eq. 3).  Defaults in brackets.            */
 typedef struct {
-  int32_t sat_num;     /* overflow when n_sat * sat_den > numel * sat_num  [1]                     */
-  int32_t sat_den;     /*   ... i.e. more than 0.001 % of the payloads on the top code  [100000]   */
+  int32_t sat_num;     /* overflow when n_sat * sat_den > numel * sat_num  [1]; 0..2^24            */
+  int32_t sat_den;     /*   ... i.e. more than 0.001 % of the payloads on the top code  [100000]; 1..2^24 */
   int32_t ramp_steps;  /* mu climbs from 1/2 to 2 over this many clean steps  [1000]               */
   int32_t hist_window; /* amax values that bound the scale, 1..FP8LM_HIST; 1 = just-in-time  [1]   */
   int32_t margin;      /* extra binades of headroom subtracted from the scale exponent  [0]        */

@@ -229,7 +229,9 @@ bool cfg_ok(const fp8lm_autoscale_cfg* cfg) {
   if (cfg && cfg->mu_rule != FP8LM_MU_SET_HALF &&
       !(cfg->mu_rule == FP8LM_MU_HALVE && cfg->mu_min_exp >= -64 && cfg->mu_min_exp <= -1))
     return false;
-  return cfg && cfg->sat_num >= 0 && cfg->sat_den > 0 && cfg->ramp_steps >= 2 && cfg->hist_window >= 1 &&
+  // sat_num, sat_den <= 2^24: the overflow test multiplies them with element counts in 64 bits
+  return cfg && cfg->sat_num >= 0 && cfg->sat_num <= (1 << 24) && cfg->sat_den > 0 && cfg->sat_den <= (1 << 24) &&
+         cfg->ramp_steps >= 2 && cfg->hist_window >= 1 &&
          cfg->hist_window <= FP8LM_HIST && cfg->margin >= -64 && cfg->margin <= 64;
 }
 

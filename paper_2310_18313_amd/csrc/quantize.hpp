@@ -210,7 +210,7 @@ struct CastParams {
   float b1, omb1;
 };
 
-// number of zero bytes among the four 7-bit fields of x (each byte of x must be <= 0x7F)
+// number of non-zero bytes among the four 7-bit fields of x (each byte of x must be <= 0x7F)
 __device__ __forceinline__ uint32_t nonzero_bytes7(uint32_t x) { return __popc((x + 0x7F7F7F7Fu) & 0x80808080u); }
 
 // DELAYED: the scale was fixed from the amax history before the launch (Appendix A.2, delayed

@@ -350,9 +350,11 @@ def test_argument_errors_are_reported_not_launched():
         st.adam(B.adam_hparams(1e-3, 1, beta1=0.8, m_scale_mode=B.MSCALE_FROM_CAST))
     with pytest.raises(B.Fp8lmError):
         st.ctx.set_tuning(1000, 8, 8)
-    bad_cfg = B.autoscale_cfg(hist_window=17)
-    with pytest.raises(B.Fp8lmError):
-        st.ctx.amax_scale(grad, B.E5M2, st.g_meta, bad_cfg)
+    for bad_cfg in (B.autoscale_cfg(hist_window=17), B.autoscale_cfg(sat_den=(1 << 24) + 1), B.autoscale_cfg(sat_den=0),
+                    B.autoscale_cfg(ramp_steps=1), B.autoscale_cfg(mu_rule=2), B.autoscale_cfg(mu_rule=B.MU_HALVE, mu_min_exp=-65)):
+        with pytest.raises(B.Fp8lmError) as e:
+            st.ctx.amax_scale(grad, B.E5M2, st.g_meta, bad_cfg)
+        assert e.value.status == -1
 
 
 # ---- auto-scaling over many steps with heavy tails ----------------------------------------------------
