@@ -12,7 +12,10 @@ constexpr int kThreads = 256;
 constexpr int kGroup = 16;                 // elements per thread per iteration
 constexpr int kTile = kThreads * kGroup;   // elements per workgroup per iteration
 constexpr int kWaves = kThreads / 64;
-constexpr int kMaxBlocksPerCu = 16;        // upper limit of the launch tuning; sizes the record array
+#ifndef FP8LM_MAX_BLOCKS_PER_CU
+#define FP8LM_MAX_BLOCKS_PER_CU 16         // the step gains up to 16 workgroups per compute unit and is flat from 16 to 64
+#endif
+constexpr int kMaxBlocksPerCu = FP8LM_MAX_BLOCKS_PER_CU;   // upper limit (and default) of the launch tuning; sizes the record array
 
 struct TensorDesc {
   int64_t offset;
