@@ -177,3 +177,59 @@ def test_cast_of_every_fp32_bit_pattern(fmt, scale_exp):
         for i in range(parts):
             diff = P.meta_equal(gm[i], ref_meta[i], ["n_sat", "n_underflow", "amax_deq", "flags", "mu_exp", "clean_steps"])
             assert not diff, (k, i, diff, gm[i], ref_meta[i])
+
+
+def test_one_tensor_with_more_than_two_to_the_31_elements():
+    """Element indices that do not fit 32 bits.  One tensor of 16 x (2^27 + 12368) elements is stepped twice; the
+    same flat range cut into 16 tensors is stepped beside it.  Every piece carries the same planted extremes (the
+    largest gradient, the largest weight), so all sixteen pieces and the one huge tensor choose the same scales and
+    their payloads must be equal element by element, the huge tensor's counters the sum of the pieces'.  Three of
+    the pieces are recomputed by the oracle."""
+    pieces, piece = 16, (1 << 27) + 3 * 4096 + 5 * 16
+    total = pieces * piece
+    assert total > (1 << 31) and piece % 16 == 0
+    cfg = B.autoscale_cfg()
+    huge = OptimizerState([(0, total)], total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
+    split = OptimizerState([(k * piece, piece) for k in range(pieces)], total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
+    buf = torch.zeros(total, dtype=torch.bfloat16, device=DEV)
+    starts = torch.arange(pieces, device=DEV, dtype=torch.int64) * piece
+
+    def fill(seed, sigma, at0, at1):
+        g = torch.Generator(device=DEV)
+        g.manual_seed(seed)
+        for p0 in range(0, total, 1 << 26):
+            n = min(1 << 26, total - p0)
+            buf[p0:p0 + n] = (torch.randn(n, generator=g, device=DEV, dtype=torch.float32) * sigma).to(torch.bfloat16)
+        buf[starts] = at0           # element 0 of every piece
+        buf[starts + 1] = at1       # element 1 of every piece
+
+    say(f"huge tensor: {total} elements; weights")
+    fill(31, 0.02, 0.01, 0.5)       # the largest weight of every piece: 0.5, on an element whose gradient stays zero
+    huge.init_master(buf)
+    split.init_master(buf)
+    torch.cuda.synchronize()
+    checked = [0, 7, 15]
+    P.check_init_master(split, buf, checked)
+    for step in (1, 2):
+        say(f"huge tensor: gradients of step {step}")
+        fill(40 + step, 1e-4, 1.0 if step == 1 else -0.75, 0.0)   # the largest gradient of every piece, same place
+        hp = B.adam_hparams(3e-4, step, stats=1)
+        snaps = [P.Snapshot(split, buf, t) for t in checked]
+        huge.step(buf, hp)
+        split.step(buf, hp)
+        torch.cuda.synchronize()
+        say(f"huge tensor step {step}: oracle on pieces {checked}")
+        r = P.check_step(split, snaps, hp, what=f"pieces, step {step}")
+        assert r["m_diff"] == 0 and r["w_diff"] == 0 and r["q_diff"] == 0
+        say(f"huge tensor step {step}: comparing {total} elements of five buffers")
+        for name in ("g8", "m", "v", "w", "wq"):
+            assert torch.equal(getattr(huge, name), getattr(split, name)), f"step {step}: {name} differs"
+        for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta"):
+            one = B.meta_to_numpy(getattr(huge, k), 1)[0]
+            many = B.meta_to_numpy(getattr(split, k), pieces)
+            assert (many["scale"] == one["scale"]).all(), (k, one["scale"], many["scale"])
+            assert one["amax"] == many["amax"].max() and one["amax_deq"] == many["amax_deq"].max(), k
+            assert int(one["n_sat"]) == int(many["n_sat"].sum()) and int(one["n_underflow"]) == int(many["n_underflow"].sum()), k
+            assert int(one["flags"]) == int(np.bitwise_or.reduce(many["flags"])), k
+        gm = B.meta_to_numpy(huge.g_meta, 1)[0]
+        assert gm["amax"] == (1.0 if step == 1 else 0.75) and gm["n_underflow"] > 0
