@@ -929,10 +929,12 @@ def test_shards_of_the_greedy_distribution_step_like_the_whole_model():
 # ---- randomised differential test -----------------------------------------------------------------------------
 def test_random_layouts_and_hyper_parameters_match_the_oracle():
     """Sixty seeded random cases: ragged tensor sizes, gradient scales over forty binades, hyper-parameters at and
-    between the ends of their ranges, every format, source type, moment-scale mode and both gradient scalings."""
-    rng = np.random.default_rng(20231018)
+    between the ends of their ranges, every format, source type, moment-scale mode, both gradient scalings and both
+    auto-scaling rules.  FP8LM_RANDOM_CASES / FP8LM_RANDOM_SEED in the environment run more cases or other ones."""
+    n_cases = int(os.environ.get("FP8LM_RANDOM_CASES", "60"))
+    rng = np.random.default_rng(int(os.environ.get("FP8LM_RANDOM_SEED", "20231018")))
     dtypes = [torch.bfloat16, torch.float16, torch.float32]
-    for case in range(60):
+    for case in range(n_cases):
         n_t = int(rng.integers(1, 7))
         numels = [int(rng.choice([0, 1, 15, 16, 17, 255, 4095, 4096, 4097, int(rng.integers(1, 70000))])) for _ in range(n_t)]
         if sum(numels) == 0:
@@ -949,7 +951,9 @@ def test_random_layouts_and_hyper_parameters_match_the_oracle():
         if wcopy == B.WCOPY_E4M3 and rng.random() < 0.4:
             master_fmt = int(rng.choice([B.STATE_F16, B.STATE_BF16, B.STATE_E4M3, B.STATE_F32]))
             v_fmt = int(rng.choice([B.STATE_F16, B.STATE_E4M3]))
-        st, _ = P.make_state(wl, case, grad_fmt, wcopy, master_fmt=master_fmt, v_fmt=v_fmt)
+        mu_rule = int(rng.integers(0, 2))
+        st, _ = P.make_state(wl, case, grad_fmt, wcopy, master_fmt=master_fmt, v_fmt=v_fmt, mu_rule=mu_rule,
+                             mu_min_exp=int(rng.integers(-5, 0)))
         if rng.random() < 0.5:
             st.ctx.set_tuning(int(rng.choice([4096, 16384])), int(rng.integers(1, 17)), int(rng.choice([0, 1 << 30])))
         ids = list(range(n_t))
@@ -967,7 +971,7 @@ def test_random_layouts_and_hyper_parameters_match_the_oracle():
             snaps = [P.Snapshot(st, grad, t) for t in ids]
             say(f"random case {case} step {k}: numels={numels} dtype={dtype} sigma={sig:g} fmt={grad_fmt} wcopy={wcopy} "
                 f"master={master_fmt} v={v_fmt} lr={hp.lr:g} b1={hp.beta1:g} b2={hp.beta2:g} eps={hp.eps:g} wd={hp.weight_decay:g} "
-                f"t={hp.step} v_scaled={hp.v_scaled} stats={hp.stats} mode={hp.m_scale_mode} delayed={delayed}")
+                f"t={hp.step} v_scaled={hp.v_scaled} stats={hp.stats} mode={hp.m_scale_mode} delayed={delayed} mu_rule={mu_rule}")
             st.step(grad, hp, delayed=delayed)
             torch.cuda.synchronize()
             P.check_step(st, snaps, hp, what=f"random case {case} step {k}", delayed=delayed)
