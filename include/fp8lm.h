@@ -157,7 +157,9 @@ fp8lm_status fp8lm_destroy(fp8lm_ctx* ctx);
  * that completes it finishes the tensor); with fewer, in a second tiny launch, because the tickets then
  * cost more than the data.  0 = always in the same launch; the default always takes the second launch
  * (measured faster at every size on MI355X); results are identical either way.
- * Rebuilds the chunk table (synchronises).
+ * Rebuilds the chunk table (synchronises the device; not to be called while a stream is being captured).
+ * A HIP graph captured from this context before the call holds the old tables and must not be replayed
+ * afterwards.  On an error the context keeps its previous tuning and tables.
  */
 fp8lm_status fp8lm_set_tuning(fp8lm_ctx* ctx, int32_t chunk_elems, int32_t blocks_per_cu,
                               int32_t single_pass_min_chunks);
