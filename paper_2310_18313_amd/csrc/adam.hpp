@@ -80,16 +80,12 @@ struct InitCastOp {
     if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
   }
   __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
-    {
-      {
-        const float vm = u2f(s.mx[0]);
-        fp8lm_meta& M = p.meta[t];
-        M.n_sat = s.ct[0];
-        M.n_underflow = s.ct[1];
-        M.amax_deq = vm * M.inv_scale;        // vm is already a stored value
-        if (M.n_sat) M.flags |= FP8LM_FLAG_SATURATED;
-      }
-    }
+    const float vm = u2f(s.mx[0]);
+    fp8lm_meta& M = p.meta[t];
+    M.n_sat = s.ct[0];
+    M.n_underflow = s.ct[1];
+    M.amax_deq = vm * M.inv_scale;        // vm is already a stored value
+    if (M.n_sat) M.flags |= FP8LM_FLAG_SATURATED;
   }
 };
 
@@ -530,14 +526,12 @@ struct AdamUpdateOp {
     if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
   }
   __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
-    {
-      unsigned long long c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-      if constexpr (STATS) {
+    unsigned long long c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (STATS) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) c[i] = s.ct[i];
-      }
-      finish(t, u2f(s.mx[0]), u2f(s.mx[1]), u2f(s.mx[2]), s.orv, c);
+      for (int i = 0; i < 8; ++i) c[i] = s.ct[i];
     }
+    finish(t, u2f(s.mx[0]), u2f(s.mx[1]), u2f(s.mx[2]), s.orv, c);
   }
 
   // Fills one output meta.  amax_deq is the stored value of the largest element: rounding is monotone,
@@ -703,17 +697,13 @@ struct AdamUpdateVarOp {
     if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
   }
   __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
-    {
-      {
-        const float A_v = u2f(s.mx[0]), A_w = u2f(s.mx[1]), A_m = u2f(s.mx[2]);
-        const uint32_t nfb = s.orv;
-        const Scratch::Pending& P = tb.scratch[t].pend;
-        fill<StTraits<kStE4M3>>(p.m_meta[t], P.sm, P.ism, A_m, nfb & 3u, P.fm);
-        fill<VT>(p.v_meta[t], P.sv, P.isv, A_v, (nfb >> 2) & 3u, P.fv);
-        fill<WT>(p.w_meta[t], P.sw, P.isw, A_w, (nfb >> 4) & 3u, P.fw);
-        fill<StTraits<kStE4M3>>(p.wcopy_meta[t], P.sq, P.isq, A_w, (nfb >> 4) & 3u, P.fq);
-      }
-    }
+    const float A_v = u2f(s.mx[0]), A_w = u2f(s.mx[1]), A_m = u2f(s.mx[2]);
+    const uint32_t nfb = s.orv;
+    const Scratch::Pending& P = tb.scratch[t].pend;
+    fill<StTraits<kStE4M3>>(p.m_meta[t], P.sm, P.ism, A_m, nfb & 3u, P.fm);
+    fill<VT>(p.v_meta[t], P.sv, P.isv, A_v, (nfb >> 2) & 3u, P.fv);
+    fill<WT>(p.w_meta[t], P.sw, P.isw, A_w, (nfb >> 4) & 3u, P.fw);
+    fill<StTraits<kStE4M3>>(p.wcopy_meta[t], P.sq, P.isq, A_w, (nfb >> 4) & 3u, P.fq);
   }
 };
 

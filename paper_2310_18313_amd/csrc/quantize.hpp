@@ -399,25 +399,21 @@ struct CastOp {
     if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
   }
   __device__ void finalize(int t, const TensorDesc& d, const Stats& s) {
-    {
-      {
-        const float vm = u2f(s.mx[0]);
-        const uint32_t abits = s.mx[1];
-        if constexpr (FUSE) tb.scratch[t].pend.amax_m_bits = s.mx[2];
-        const unsigned long long n_sat = s.ct[0], n_und = s.ct[1];
-        if constexpr (DELAYED) {
-          fp8lm_meta& M = p.meta[t];
-          if (abits >= SrcTraits<SRC>::kNonfinite) {
-            M.amax = __builtin_inff();
-            M.flags |= FP8LM_FLAG_NONFINITE;
-          } else {
-            M.amax = SrcTraits<SRC>::dec(abits);
-            push_history(M, M.amax, p.hist_window);
-          }
-        }
-        finish(t, d, vm, n_sat, n_und);
+    const float vm = u2f(s.mx[0]);
+    const uint32_t abits = s.mx[1];
+    if constexpr (FUSE) tb.scratch[t].pend.amax_m_bits = s.mx[2];
+    const unsigned long long n_sat = s.ct[0], n_und = s.ct[1];
+    if constexpr (DELAYED) {
+      fp8lm_meta& M = p.meta[t];
+      if (abits >= SrcTraits<SRC>::kNonfinite) {
+        M.amax = __builtin_inff();
+        M.flags |= FP8LM_FLAG_NONFINITE;
+      } else {
+        M.amax = SrcTraits<SRC>::dec(abits);
+        push_history(M, M.amax, p.hist_window);
       }
     }
+    finish(t, d, vm, n_sat, n_und);
   }
   __device__ void finish(int t, const TensorDesc& d, float vm, unsigned long long n_sat, unsigned long long n_und) {
     fp8lm_meta& M = p.meta[t];
@@ -532,23 +528,19 @@ struct RequantOp {
     if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
   }
   __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
-    {
-      {
-        const float vm = u2f(s.mx[0]);
-        const unsigned long long n_sat = s.ct[0], n_und = s.ct[1];
-        const uint32_t nf = s.orv;
-        fp8lm_meta& M = p.dst_meta[t];
-        const float src_amax = p.src_meta[t].amax;
-        const float inv = 1.0f / sg;
-        M.scale = sg;
-        M.inv_scale = inv;
-        M.amax = nf ? __builtin_inff() : src_amax;
-        M.amax_deq = fp8_to_f32<FMT>(encode1_fp8<FMT>(vm)) * inv;
-        M.n_sat = n_sat;
-        M.n_underflow = n_und;
-        M.flags = (nf ? FP8LM_FLAG_NONFINITE : 0u) | (n_sat ? FP8LM_FLAG_SATURATED : 0u);
-      }
-    }
+    const float vm = u2f(s.mx[0]);
+    const unsigned long long n_sat = s.ct[0], n_und = s.ct[1];
+    const uint32_t nf = s.orv;
+    fp8lm_meta& M = p.dst_meta[t];
+    const float src_amax = p.src_meta[t].amax;
+    const float inv = 1.0f / sg;
+    M.scale = sg;
+    M.inv_scale = inv;
+    M.amax = nf ? __builtin_inff() : src_amax;
+    M.amax_deq = fp8_to_f32<FMT>(encode1_fp8<FMT>(vm)) * inv;
+    M.n_sat = n_sat;
+    M.n_underflow = n_und;
+    M.flags = (nf ? FP8LM_FLAG_NONFINITE : 0u) | (n_sat ? FP8LM_FLAG_SATURATED : 0u);
   }
 };
 
@@ -693,24 +685,20 @@ struct SumOp {
     if (collect(tb, t, d, done, s) && threadIdx.x == 0) finalize(t, d, s);
   }
   __device__ void finalize(int t, const TensorDesc& d, const Stats& s) {
-    {
-      {
-        const float vm = u2f(s.mx[0]);
-        const uint32_t ab = s.mx[1];
-        const unsigned long long n_sat = s.ct[0], n_under = s.ct[1];
-        fp8lm_meta& M = p.dst_meta[t];
-        const float sc_out = (float)p.in.n_ranks * p.shared[t];
-        const bool nf = ab >= 0x7F800000u;
-        M.scale = sc_out;
-        M.inv_scale = 1.0f / sc_out;
-        M.amax = nf ? __builtin_inff() : u2f(ab) * M.inv_scale;
-        M.amax_deq = fp8_to_f32<FMT>(encode1_fp8<FMT>(vm)) * M.inv_scale;
-        M.n_sat = n_sat;
-        M.n_underflow = n_under;
-        M.flags = (nf ? FP8LM_FLAG_NONFINITE : 0u) | (n_sat ? FP8LM_FLAG_SATURATED : 0u);
-        autoscale_update(M, n_sat, d.numel, p.rule);
-      }
-    }
+    const float vm = u2f(s.mx[0]);
+    const uint32_t ab = s.mx[1];
+    const unsigned long long n_sat = s.ct[0], n_under = s.ct[1];
+    fp8lm_meta& M = p.dst_meta[t];
+    const float sc_out = (float)p.in.n_ranks * p.shared[t];
+    const bool nf = ab >= 0x7F800000u;
+    M.scale = sc_out;
+    M.inv_scale = 1.0f / sc_out;
+    M.amax = nf ? __builtin_inff() : u2f(ab) * M.inv_scale;
+    M.amax_deq = fp8_to_f32<FMT>(encode1_fp8<FMT>(vm)) * M.inv_scale;
+    M.n_sat = n_sat;
+    M.n_underflow = n_under;
+    M.flags = (nf ? FP8LM_FLAG_NONFINITE : 0u) | (n_sat ? FP8LM_FLAG_SATURATED : 0u);
+    autoscale_update(M, n_sat, d.numel, p.rule);
   }
 };
 
