@@ -3,8 +3,13 @@
 Measured on MI355X (`python -m paper_2310_18313_amd.placement --probe`): the 288 GiB of HBM3E behave
 as three regions of 96 GiB.  Streams that a kernel walks at the same time run faster when they live
 in different regions: a copy between regions reaches about 5 % more bandwidth than a copy inside one
-region.  For the whole cast + Adam step the gain is between 1 % and 5 %, and the slow outliers of plain
-allocation (the first process on a freshly booted GPU) disappear.
+region.  For the whole cast + Adam step at 13e9 parameters the gain is between 1 % and 5 %, and the slow
+outliers of plain allocation (the first process on a freshly booted GPU) disappear.  What the kernels feel
+is distance: with the buffers of a 1e9-parameter state carved out of one allocation, the update kernel runs
+at 5.0 TB/s while they are within 8 GiB of each other, 5.8 TB/s at 16 GiB and 5.9-6.1 TB/s from 32 GiB on
+(small offsets on top, from 4 KiB to hundreds of MiB, change nothing).  Buffers of 12 GiB and more are that
+far apart by themselves; smaller ones, allocated one after the other, are not, and gain 10 % of the step
+from this allocator.
 
 `SpreadAllocator` therefore puts the buffers of an optimizer state into chosen regions without
 assuming anything about the allocator: it takes all free device memory in slabs, finds out which
