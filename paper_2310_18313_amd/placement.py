@@ -15,6 +15,10 @@ from this allocator.
 assuming anything about the allocator: it takes all free device memory in slabs, finds out which
 slabs share a region by timing copies between them, then frees exactly the slabs a buffer should
 occupy and allocates the buffer into that hole.  The remaining slabs are released at the end.
+For buffers smaller than a slab the memory that the slabs left over is taken as well, so that the
+freed slab is the only place where such a buffer fits.  Where a buffer lands is still up to the
+driver: in a process that has allocated and freed much before, small buffers have been seen to end
+up next to each other all the same (then nothing is lost against plain allocation).
 
 Nothing here computes anything of the method: it only decides where `torch.zeros` buffers land.
 """
@@ -114,21 +118,39 @@ class SpreadAllocator:
         self.log["region_slabs"] = [len(r) for r in regions]
         return slabs
 
+    def _fill(self, keep_free: int) -> List[torch.Tensor]:
+        """Takes what the slabs left over, in ever smaller blocks, until less than `keep_free` bytes are free.
+        A buffer smaller than a slab would otherwise land in that remainder instead of in the slab freed
+        for it."""
+        fillers: List[torch.Tensor] = []
+        try:
+            for block in (GiB, 256 << 20, 64 << 20, 16 << 20):
+                while torch.cuda.mem_get_info(self.device)[0] > keep_free + block and len(fillers) < 256:
+                    fillers.append(torch.empty(block, dtype=torch.uint8, device=self.device))
+        except RuntimeError:          # fragmented remainder: what has been taken is enough
+            pass
+        self.log["fillers"] = len(fillers)
+        return fillers
+
     # -- allocation --------------------------------------------------------------------------------
     def allocate(self, plan: Sequence[Sequence[Tuple[str, int, torch.dtype]]]) -> Dict[str, torch.Tensor]:
         sizes = [[_round_up(n * torch.empty((), dtype=dt).element_size()) for _, n, dt in reg] for reg in plan]
         want = sum(sum(s) for s in sizes)
+        smallest = min((b for s in sizes for b in s), default=0)
         free = torch.cuda.mem_get_info(self.device)[0]
         bufs: Dict[str, torch.Tensor] = {}
         slabs: List[torch.Tensor] = []
-        ok = want >= 2 * GiB and free > want + 16 * GiB and free > 64 * GiB
+        fillers: List[torch.Tensor] = []
+        ok = want >= 256 << 20 and smallest >= 32 << 20 and free > want + 16 * GiB and free > 64 * GiB
         if ok:
             slabs = self._discover()
+            if smallest < self.slab_bytes:
+                fillers = self._fill(max(16 << 20, smallest // 2))
             big = sorted((r for r in self.regions if len(r) >= 2), key=len, reverse=True)
             need = [-(-sum(s) // self.slab_bytes) for s in sizes]          # slabs per plan region
             ok = len(big) >= len(plan) and all(len(big[i]) >= need[i] for i in range(len(plan)))
         if not ok:
-            del slabs
+            del slabs, fillers
             torch.cuda.empty_cache()
             for reg in plan:
                 for name, n, dt in reg:
@@ -145,7 +167,7 @@ class SpreadAllocator:
             for name, n, dt in plan[i]:          # ... and let the buffers fall into the hole
                 bufs[name] = torch.zeros(n, dtype=dt, device=self.device)
                 self.where[name] = rank
-        del slabs
+        del slabs, fillers
         torch.cuda.empty_cache()
         self.spread = True
         return bufs
