@@ -240,7 +240,7 @@ void oracle_meta_init(oracle_meta* meta, int32_t n, const oracle_autoscale_cfg* 
 // sat_num / sat_den (0.001 %).  The sentence that says what happens then is garbled; two readings:
 //   rule 0 (taken by default): on overflow mu is SET to 1/2 and the count of clean steps restarts; mu is a
 //     function of that count alone: 1/2 for the first ramp_steps/2 clean steps, 1 for the next
-//     ramp_steps/2, 2 from ramp_steps on ("exponentially increase mu to 2 over the span of 1,000 steps").
+//     ramp_steps/2, 2 from ramp_steps on (the paper has mu grow exponentially back to 2 within a thousand steps).
 //   rule 1 (alternative): every overflowing step HALVES mu, down to 2^mu_min_exp; every ramp_steps/2
 //     clean steps in a row double it, up to 2.  Unlike rule 0 it can follow a sum that grows by more than 2.
 // Takes effect in the next scale computation.
