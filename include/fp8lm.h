@@ -21,9 +21,10 @@
  *     Data-dependent conditions (non-finite inputs, all-zero tensors, saturation) are reported in the
  *     metadata flags and counters on the device, never in the return value.
  *   - Tensors with numel == 0 are skipped: their metadata is left untouched.
- *   - Parameter groups (other hyper-parameters for some tensors, e.g. no weight decay on biases): one
- *     context per group, over disjoint tensor lists of the same flat buffers, each with its own
- *     metadata arrays (indexed by the position in its own list) and stepped with its own calls.
+ *   - Parameter groups (other hyper-parameters for some tensors): one context per group, over disjoint
+ *     tensor lists of the same flat buffers, each with its own metadata arrays (indexed by the position
+ *     in its own list) and stepped with its own calls.  The most common case, no weight decay on biases
+ *     and normalisation weights, needs no second context: see fp8lm_set_tensor_flags.
  */
 #ifndef FP8LM_H
 #define FP8LM_H
@@ -163,6 +164,19 @@ fp8lm_status fp8lm_destroy(fp8lm_ctx* ctx);
  */
 fp8lm_status fp8lm_set_tuning(fp8lm_ctx* ctx, int32_t chunk_elems, int32_t blocks_per_cu,
                               int32_t single_pass_min_chunks);
+
+/*
+ * Per-tensor attributes (optional; all 0 after fp8lm_create).  flags: host array of n = the context's tensor
+ * count entries, each a combination of FP8LM_TENSOR_* bits.
+ *   FP8LM_TENSOR_NO_WEIGHT_DECAY: fp8lm_adam_step_fp8 updates this tensor as if hp->weight_decay were 0 (the
+ *   usual exemption of biases and normalisation weights; Sec. 3.1.2 states one weight decay of 0.1 and is silent
+ *   on exemptions).  Every other hyper-parameter stays common to the call; tensors that need another learning rate
+ *   or other betas go into a context of their own.
+ * Rebuilds the tensor table (synchronises the device; not under stream capture; graphs captured from this context
+ * before the call must not be replayed afterwards).  Unknown bits are refused.
+ */
+#define FP8LM_TENSOR_NO_WEIGHT_DECAY 1u
+fp8lm_status fp8lm_set_tensor_flags(fp8lm_ctx* ctx, const uint32_t* flags /*host[n]*/, int32_t n);
 
 /*
  * Initial metadata: scale 1, empty amax history, mu = 1 (clean_steps = ramp_steps / 2; 0 with

@@ -22,6 +22,7 @@ E4M3, E5M2 = 0, 1
 SRC_BF16, SRC_F16, SRC_F32 = 0, 1, 2
 WCOPY_E4M3, WCOPY_BF16 = 0, 1
 MSCALE_EXACT_PASS, MSCALE_PREDICTED, MSCALE_FROM_CAST = 0, 1, 2
+TENSOR_NO_WEIGHT_DECAY = 1
 MU_SET_HALF, MU_HALVE = 0, 1
 STATE_F16, STATE_BF16, STATE_E4M3, STATE_F32 = 0, 1, 2, 3
 STATE_BYTES = {STATE_F16: 2, STATE_BF16: 2, STATE_E4M3: 1, STATE_F32: 4}
@@ -30,7 +31,7 @@ K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_
 KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars", "requantize", "sum", "quant_stats"]
 
 EXPORTS = [
-    "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_meta_init", "fp8lm_amax_scale",
+    "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_set_tensor_flags", "fp8lm_meta_init", "fp8lm_amax_scale",
     "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_cast_fp8_for_adam", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
     "fp8lm_quant_error_stats",
     "fp8lm_init_master", "fp8lm_init_master_as", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
@@ -118,6 +119,7 @@ def lib() -> C.CDLL:
         L.fp8lm_create.argtypes = [C.POINTER(vp), vp, i32, C.c_int]
         L.fp8lm_destroy.argtypes = [vp]
         L.fp8lm_set_tuning.argtypes = [vp, i32, i32, i32]
+        L.fp8lm_set_tensor_flags.argtypes = [vp, vp, i32]
         L.fp8lm_meta_init.argtypes = [vp, vp, vp, vp]
         L.fp8lm_amax_scale.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, vp]
         L.fp8lm_cast_fp8.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
@@ -216,6 +218,12 @@ class Context:
 
     def set_tuning(self, chunk_elems=16384, blocks_per_cu=16, single_pass_min_chunks=1 << 30):
         _check(lib().fp8lm_set_tuning(self._h, chunk_elems, blocks_per_cu, single_pass_min_chunks), "fp8lm_set_tuning")
+
+    def set_tensor_flags(self, flags) -> None:
+        """One combination of TENSOR_* bits per tensor of the context (TENSOR_NO_WEIGHT_DECAY: the Adam step treats
+        the tensor as if weight_decay were 0)."""
+        arr = np.ascontiguousarray(flags, dtype=np.uint32)
+        _check(lib().fp8lm_set_tensor_flags(self._h, arr.ctypes.data, len(arr)), "fp8lm_set_tensor_flags")
 
     def new_meta(self, cfg: AutoscaleCfg, stream=None) -> torch.Tensor:
         """Device array of fp8lm_meta (as raw bytes, [n_tensors, 112]) in its initial state."""

@@ -262,15 +262,15 @@ __global__ __launch_bounds__(kThreads) void adam_amax_kernel(Tables tb, AdamPara
 // ---- pass B: the update ----------------------------------------------------------------------------
 // FAST: v_sqrt_f32 / v_rcp_f32 (1 ulp each) instead of correctly rounded sqrt and divide in the weight
 // update; m and v are unaffected (multiply/fma only).  STATS: count n_sat / n_underflow per output.
-template <bool FAST> __device__ __forceinline__ float adam_update(float m1, float v1, float w0, const AdamParams& p) {
+template <bool FAST> __device__ __forceinline__ float adam_update(float m1, float v1, float w0, float decay, const AdamParams& p) {
   if constexpr (FAST) {
     const float den = __builtin_amdgcn_sqrtf(v1 * p.rbc2) + p.eps;
     const float upd = (m1 * p.rbc1) * __builtin_amdgcn_rcpf(den);
-    return __builtin_fmaf(-p.lr, upd, w0 * p.decay);
+    return __builtin_fmaf(-p.lr, upd, w0 * decay);
   } else {
     const float den = __builtin_sqrtf(v1 * p.rbc2) + p.eps;
     const float upd = ((m1 * p.rbc1) / den);
-    return __builtin_fmaf(-p.lr, upd, w0 * p.decay);
+    return __builtin_fmaf(-p.lr, upd, w0 * decay);
   }
 }
 
@@ -280,14 +280,16 @@ struct AdamUpdateOp {
   const Tables& tb;
   float inv_sg, inv_sm, inv_sv, inv_sw;   // scales of the inputs
   float sm, sv, sw, sq;                   // scales of the outputs
+  float decay;                            // 1 - lr * weight_decay, or 1 for a tensor that is exempt
   bool careful;
   float vmax, wmax, mmax;                 // running maxima of v', |w'| (and |m'| on the careful path)
   uint32_t nf;
   uint32_t cnt[8];                        // sat m,v,w,q ; underflow m,v,w,q: per lane (tails, careful path)
   uint32_t wcnt[8];                       // the same for whole tiles: wave totals, identical in every lane
   __device__ AdamUpdateOp(const AdamParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
-  __device__ __forceinline__ void begin(int t, const TensorDesc&) {
+  __device__ __forceinline__ void begin(int t, const TensorDesc& d) {
     const Scratch::Pending& P = tb.scratch[t].pend;
+    decay = (d.flags & FP8LM_TENSOR_NO_WEIGHT_DECAY) ? 1.0f : p.decay;
     inv_sg = p.grad_meta[t].inv_scale;
     inv_sm = p.m_meta[t].inv_scale;
     inv_sv = p.v_meta[t].inv_scale;
@@ -351,7 +353,7 @@ struct AdamUpdateOp {
       const float g = dg[j] * inv_sg, m0 = dm[j] * inv_sm, v0 = dv[j] * inv_sv, w0 = dw[j] * inv_sw;
       const float m1 = __builtin_fmaf(p.b1, m0, p.omb1 * g);
       const float v1 = __builtin_fmaf(p.b2, v0, p.omb2 * (g * g));
-      const float w1 = adam_update<FAST>(m1, v1, w0, p);
+      const float w1 = adam_update<FAST>(m1, v1, w0, decay, p);
       vmax = fmaxf(vmax, v1);
       wmax = fmaxf(wmax, fabsf(w1));
       mmax = fmaxf(mmax, fabsf(m1));
@@ -390,7 +392,7 @@ struct AdamUpdateOp {
     const float v1 = __builtin_fmaf(p.b2, v0, p.omb2 * (g * g));
     const float den = __builtin_sqrtf(v1 * p.rbc2) + p.eps;
     const float upd = ((m1 * p.rbc1) / den);
-    const float w1 = __builtin_fmaf(-p.lr, upd, w0 * p.decay);
+    const float w1 = __builtin_fmaf(-p.lr, upd, w0 * decay);
     const float tm = m1 * sm, tv = v1 * sv, tw = w1 * sw, tq = w1 * sq;
     p.m[i] = (uint8_t)encode1_fp8_careful<kE4M3>(tm);
     pv[i] = (uint16_t)encode1_f16_careful(tv);
@@ -597,13 +599,14 @@ struct AdamUpdateVarOp {
   typedef StTraits<VFMT> VT;
   const AdamParams& p;
   const Tables& tb;
-  float inv_sg, inv_sm, inv_sv, inv_sw, sm, sv, sw, sq;
+  float inv_sg, inv_sm, inv_sv, inv_sw, sm, sv, sw, sq, decay;
   bool careful;
   float vmax, wmax, mmax;
   uint32_t nf;
   __device__ AdamUpdateVarOp(const AdamParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
-  __device__ __forceinline__ void begin(int t, const TensorDesc&) {
+  __device__ __forceinline__ void begin(int t, const TensorDesc& d) {
     const Scratch::Pending& P = tb.scratch[t].pend;
+    decay = (d.flags & FP8LM_TENSOR_NO_WEIGHT_DECAY) ? 1.0f : p.decay;
     inv_sg = p.grad_meta[t].inv_scale;
     inv_sm = p.m_meta[t].inv_scale;
     inv_sv = p.v_meta[t].inv_scale;
@@ -620,7 +623,7 @@ struct AdamUpdateVarOp {
     v1 = __builtin_fmaf(p.b2, v0, p.omb2 * (g * g));
     const float den = __builtin_sqrtf(v1 * p.rbc2) + p.eps;
     const float upd = (m1 * p.rbc1) / den;
-    w1 = __builtin_fmaf(-p.lr, upd, w0 * p.decay);
+    w1 = __builtin_fmaf(-p.lr, upd, w0 * decay);
   }
   template <int UN> __device__ __forceinline__ void tiles(long long tile0) {
     static_assert(UN == 1, "one group at a time");

@@ -50,6 +50,7 @@ struct fp8lm_ctx {
   int n_tensors = 0;
   int num_cus = 0;
   std::vector<fp8lm_tensor> tensors;
+  std::vector<uint32_t> tensor_flags;   // FP8LM_TENSOR_* per tensor
   int32_t chunk_elems = 16384;
   int32_t blocks_per_cu = kMaxBlocksPerCu;
   int32_t single_pass_min_chunks = FP8LM_SINGLE_PASS_MIN_CHUNKS;
@@ -100,7 +101,7 @@ fp8lm_status build_tables(fp8lm_ctx* c, int32_t chunk_elems) {
     const long long n = c->tensors[t].numel;
     const long long nc = (n + chunk_elems - 1) / chunk_elems;
     if (total_chunks + nc > 0x7FFFFFF0LL) return FP8LM_ERR_TOO_LARGE;
-    desc[t] = TensorDesc{c->tensors[t].offset, n, (int32_t)total_chunks, (int32_t)nc};
+    desc[t] = TensorDesc{c->tensors[t].offset, n, (int32_t)total_chunks, (int32_t)nc, c->tensor_flags[t], 0u};
     total_chunks += nc;
   }
   chunk_tensor.resize((size_t)total_chunks);
@@ -281,6 +282,7 @@ fp8lm_status fp8lm_create(fp8lm_ctx** out, const fp8lm_tensor* tensors, int32_t 
   c->n_tensors = n;
   c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   c->tensors.assign(tensors, tensors + n);
+  c->tensor_flags.assign((size_t)n, 0u);
   fp8lm_status st = build_tables(c, c->chunk_elems);
   if (st == FP8LM_OK) {
     const size_t bytes = std::max<size_t>(1, (size_t)n) * sizeof(Scratch);
@@ -321,6 +323,19 @@ fp8lm_status fp8lm_set_tuning(fp8lm_ctx* c, int32_t chunk_elems, int32_t blocks_
   c->blocks_per_cu = blocks_per_cu;
   c->single_pass_min_chunks = single_pass_min_chunks;
   return FP8LM_OK;
+}
+
+fp8lm_status fp8lm_set_tensor_flags(fp8lm_ctx* c, const uint32_t* flags, int32_t n) {
+  if (!c || n != c->n_tensors || (n > 0 && !flags)) return FP8LM_ERR_INVALID_ARGUMENT;
+  for (int t = 0; t < n; ++t)
+    if (flags[t] & ~(uint32_t)FP8LM_TENSOR_NO_WEIGHT_DECAY) return FP8LM_ERR_INVALID_ARGUMENT;
+  DeviceGuard guard(c->device);
+  HIP_TRY(hipDeviceSynchronize());   // no launch may still be reading the tables that are about to go
+  const std::vector<uint32_t> before = c->tensor_flags;
+  c->tensor_flags.assign(flags, flags + n);
+  const fp8lm_status st = build_tables(c, c->chunk_elems);
+  if (st != FP8LM_OK) c->tensor_flags = before;
+  return st;
 }
 
 fp8lm_status fp8lm_meta_init(fp8lm_ctx* c, fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {

@@ -22,6 +22,8 @@ struct TensorDesc {
   int64_t numel;
   int32_t first_chunk;
   int32_t n_chunks;
+  uint32_t flags;       // FP8LM_TENSOR_* attributes of the tensor
+  uint32_t pad;
 };
 
 // Per-tensor scratch.  The ticket is zero between launches; the `pend` block carries the scales chosen

@@ -853,6 +853,43 @@ def test_parameter_groups_share_the_flat_buffers():
         P.check_step(st_p, snaps_p, hp_p, what=f"no-decay group step {step}")
 
 
+@pytest.mark.parametrize("master_fmt,exact", [(B.STATE_F16, 1), (B.STATE_F16, 0), (B.STATE_BF16, 1)])
+def test_weight_decay_exemption_by_tensor_flag(master_fmt, exact):
+    """One context, one launch: tensors flagged TENSOR_NO_WEIGHT_DECAY (biases, LayerNorm weights) must come out as
+    the oracle computes them with weight_decay = 0, all others with the call's weight decay; with the flags cleared
+    again every tensor decays."""
+    wl = synth.Workload("flags", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-2, sigma=None)
+    lay = wl.layout
+    exempt = [i for i, nm in enumerate(lay.names) if not (nm.endswith(".w") and "ln" not in nm or nm == "emb")]
+    decays = [i for i in range(lay.n_tensors) if i not in exempt]
+    assert exempt and decays
+    st, _ = P.make_state(wl, 31, master_fmt=master_fmt)
+    flags = np.zeros(lay.n_tensors, dtype=np.uint32)
+    flags[exempt] = B.TENSOR_NO_WEIGHT_DECAY
+    st.ctx.set_tensor_flags(flags)
+    grad = torch.zeros(max(lay.total, 16), dtype=torch.bfloat16, device=DEV)
+    for step in (1, 2, 3):
+        if step == 3:
+            st.ctx.set_tensor_flags(np.zeros(lay.n_tensors, dtype=np.uint32))
+        synth.fill_gradients(grad, wl, 31, step)
+        kw = dict(weight_decay=0.5, exact=exact, master_fmt=master_fmt)
+        hp = B.adam_hparams(wl.lr, step, **kw)
+        hp0 = B.adam_hparams(wl.lr, step, **dict(kw, weight_decay=0.0))
+        with_decay = decays if step < 3 else decays + exempt
+        snaps_d = [P.Snapshot(st, grad, t) for t in with_decay]
+        snaps_e = [P.Snapshot(st, grad, t) for t in exempt] if step < 3 else []
+        say(f"tensor flags (master {master_fmt}, exact {exact}) step {step}: {len(with_decay)} decaying, {len(snaps_e)} exempt")
+        st.step(grad, hp)
+        torch.cuda.synchronize()
+        P.check_step(st, snaps_d, hp, what=f"decaying tensors step {step}")
+        if snaps_e:
+            P.check_step(st, snaps_e, hp0, what=f"exempt tensors step {step}")
+    with pytest.raises(B.Fp8lmError):
+        st.ctx.set_tensor_flags(np.full(lay.n_tensors, 2, dtype=np.uint32))      # unknown bit
+    with pytest.raises(B.Fp8lmError):
+        st.ctx.set_tensor_flags(np.zeros(lay.n_tensors + 1, dtype=np.uint32))    # wrong length
+
+
 def test_two_contexts_on_two_streams_at_once():
     """One context per stream is the rule; two contexts on two streams may run at the same time (each has its own
     records and scratch).  Two halves of a layout are stepped concurrently and each must match the oracle."""
