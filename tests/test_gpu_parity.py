@@ -991,6 +991,8 @@ def test_random_layouts_and_hyper_parameters_match_the_oracle():
         mu_rule = int(rng.integers(0, 2))
         st, _ = P.make_state(wl, case, grad_fmt, wcopy, master_fmt=master_fmt, v_fmt=v_fmt, mu_rule=mu_rule,
                              mu_min_exp=int(rng.integers(-5, 0)))
+        flags = rng.integers(0, 2, n_t).astype(np.uint32) if rng.random() < 0.3 else np.zeros(n_t, dtype=np.uint32)
+        st.ctx.set_tensor_flags(flags)               # before the tuning call: the flags must survive the table rebuild
         if rng.random() < 0.5:
             st.ctx.set_tuning(int(rng.choice([4096, 16384])), int(rng.integers(1, 17)), int(rng.choice([0, 1 << 30])))
         ids = list(range(n_t))
@@ -1008,10 +1010,16 @@ def test_random_layouts_and_hyper_parameters_match_the_oracle():
             snaps = [P.Snapshot(st, grad, t) for t in ids]
             say(f"random case {case} step {k}: numels={numels} dtype={dtype} sigma={sig:g} fmt={grad_fmt} wcopy={wcopy} "
                 f"master={master_fmt} v={v_fmt} lr={hp.lr:g} b1={hp.beta1:g} b2={hp.beta2:g} eps={hp.eps:g} wd={hp.weight_decay:g} "
-                f"t={hp.step} v_scaled={hp.v_scaled} stats={hp.stats} mode={hp.m_scale_mode} delayed={delayed} mu_rule={mu_rule}")
+                f"t={hp.step} v_scaled={hp.v_scaled} stats={hp.stats} mode={hp.m_scale_mode} delayed={delayed} mu_rule={mu_rule} "
+                f"exempt={flags.tolist()}")
             st.step(grad, hp, delayed=delayed)
             torch.cuda.synchronize()
-            P.check_step(st, snaps, hp, what=f"random case {case} step {k}", delayed=delayed)
+            P.check_step(st, [x for x in snaps if not flags[x.t]], hp, what=f"random case {case} step {k}", delayed=delayed)
+            if flags.any():
+                hp0 = B.AdamHparams.from_buffer_copy(hp)
+                hp0.weight_decay = 0.0
+                P.check_step(st, [x for x in snaps if flags[x.t]], hp0, what=f"random case {case} step {k}, exempt tensors",
+                             delayed=delayed)
 
 
 # ---- the alternative reading of the auto-scaling rule ------------------------------------------------------------
