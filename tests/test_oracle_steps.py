@@ -510,6 +510,33 @@ def test_negating_gradients_flips_only_the_sign_of_the_first_moment():
     assert np.array_equal(a.w[used] ^ 0x8000, b.w[used])
 
 
+def test_weight_copy_of_a_zero_initialised_tensor_clips_in_its_first_steps_and_says_so():
+    """The weight copy takes its scale from the master weights as they stood before the step, without headroom.  A
+    tensor that starts at zero and moves by lr per step (constant gradient: |update| = 1) doubles between steps 1
+    and 2: the copy clips at 448 / scale, which lies between 1x and 2x the previous amax, and carries FLAG_SATURATED,
+    while the master weights (one binade of headroom) hold the true value."""
+    lay = synth.flat_layout(64)
+    st = State(lay, np.zeros(lay.total, dtype=np.uint16))
+    g = bf16_bits(np.full(lay.total, 2.0 ** -10, dtype=np.float32))
+    lr = 2.0 ** -10
+    for t in (1, 2, 3, 4):
+        prev = float(st.w_meta[0]["amax_deq"])                                        # what the copy's scale is taken from
+        st.step(g, O.AdamHparams(lr, 0.9, 0.95, 1e-8, 0.0, t, 1, O.WCOPY_E4M3))
+        val = st.values(0)
+        assert np.allclose(val["w"], -t * lr, rtol=0.03), (t, val["w"][:2])           # |update| = 1 up to the FP8 moment's rounding
+        assert not (st.w_meta[0]["flags"] & O.FLAG_SATURATED)
+        if t == 1:
+            # no amax yet: the copy keeps scale 1, and lr = 2^-10 is half of E4M3's smallest subnormal: a tie, to zero
+            assert np.all(val["wq"] == 0.0)
+        elif t == 2:
+            top = 448.0 * float(st.q_meta[0]["inv_scale"])
+            assert prev <= top < 2 * prev
+            assert np.all(val["wq"] == -top) and np.all(np.abs(val["wq"]) < np.abs(val["w"]))     # clipped
+            assert st.q_meta[0]["flags"] & O.FLAG_SATURATED
+        else:
+            assert np.all(np.abs(val["wq"]) <= np.abs(val["w"]) * 1.07)
+
+
 def test_state_is_six_bytes_per_parameter():
     # Sec. 2.2, Eq. 8: master 2 + gradient 1 + first moment 1 + second moment 2
     lay = synth.flat_layout(1 << 16)
