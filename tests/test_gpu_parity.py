@@ -250,6 +250,41 @@ def test_three_hundred_free_running_steps_with_heavy_tails(mu_rule):
     assert len(mus) >= 2, mus
 
 
+@pytest.mark.parametrize("single_pass", [0, 1 << 30])
+def test_twenty_thousand_small_tensors(single_pass):
+    """Many tensors per workgroup: 20 000 tensors of 0 to 6000 elements (a workgroup crosses a dozen of them per launch,
+    leaves a record for each, and every tensor is a chunk of its own), three free-running steps, both forms of the
+    grid-wide reduction."""
+    rng = np.random.default_rng(77)
+    numels = np.minimum(6000, (rng.pareto(1.2, 20000) * 40).astype(np.int64)).tolist()
+    numels[17], numels[18], numels[19999] = 0, 0, 1
+    lay = synth.Layout([f"t{i}" for i in range(len(numels))], numels)
+    wl = synth.Workload("many", lay, lr=1e-3, sigma=None, ramp_steps=4, hist_window=2)
+    cfg = B.autoscale_cfg(ramp_steps=4, hist_window=2)
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
+    st.ctx.set_tuning(16384, 16, single_pass)
+    say(f"{lay.n_tensors} tensors, {lay.n_params} parameters, reduction form {single_pass}")
+    gw = torch.Generator(device=DEV)
+    gw.manual_seed(5)
+    w0 = torch.randn(lay.total, device=DEV, generator=gw).mul_(0.02).to(torch.bfloat16)
+    st.init_master(w0)
+    fr = P.FreeRunningOracle(lay, cfg, synth.bits16(w0), threads=16)
+    sig_host = np.zeros(lay.total, dtype=np.float32)
+    for (off, n), sg in zip(lay.tensors(), 10.0 ** rng.uniform(-5, -2, lay.n_tensors)):
+        sig_host[off:off + n] = sg
+    sig = torch.from_numpy(sig_host).to(DEV)
+    g = torch.Generator(device=DEV)
+    for step in (1, 2, 3):
+        g.manual_seed(1000 + step)
+        grad = (torch.randn(lay.total, device=DEV, generator=g) * sig * (20.0 if step == 3 else 1.0)).to(torch.bfloat16)
+        hp = B.adam_hparams(wl.lr, step)
+        st.step(grad, hp)
+        fr.step(synth.bits16(grad), hp)
+    torch.cuda.synchronize()
+    say("comparing 20 000 tensors")
+    fr.assert_equal_to(st, "20 000 tensors after 3 steps")
+
+
 # chunk size, workgroups per CU, and both forms of the cross-workgroup reduction (third entry 0: tickets in the
 # same launch; large: a second launch finishes the tensors)
 @pytest.mark.parametrize("tuning", [(4096, 1, 0), (4096, 16, 0), (65536, 4, 0), (1048576, 2, 0), (16384, 16, 0),
