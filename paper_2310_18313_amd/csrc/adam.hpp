@@ -57,6 +57,8 @@ struct InitCastOp {
     }
     st_store16<MASTER>(p.dst, pos, y);
   }
+  // 16 consecutive elements at `pos`, by this thread alone: the tile body with the thread's own offset taken out
+  __device__ __forceinline__ void full_group(long long pos) { tiles<1>(pos - (long long)threadIdx.x * kGroup); }
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) {
       const uint32_t bits = p.src[pos + j];
@@ -235,6 +237,8 @@ struct AdamAmaxOp {
       word(g[u].w, m[u].w);
     }
   }
+  // 16 consecutive elements at `pos`, by this thread alone: the tile body with the thread's own offset taken out
+  __device__ __forceinline__ void full_group(long long pos) { tiles<1>(pos - (long long)threadIdx.x * kGroup); }
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) elem(fp8_to_f32<GFMT>(p.grad[pos + j]), fp8_to_f32<kE4M3>(p.m[pos + j]));
   }
@@ -454,10 +458,11 @@ struct AdamUpdateOp {
     }
   }
   template <int UN> __device__ __forceinline__ void tiles(long long tile0) {
-    if constexpr (FP8LM_UPDATE_SPLIT) {
-      tiles_split<UN>(tile0);
-      return;
-    }
+    if constexpr (FP8LM_UPDATE_SPLIT) tiles_split<UN>(tile0);
+    else tiles_plain<UN>(tile0);
+  }
+  // a thread takes 16 consecutive elements of the tile
+  template <int UN> __device__ __forceinline__ void tiles_plain(long long tile0) {
     uint4 g[UN], m[UN], va[UN], vb[UN], wa[UN], wb[UN];
     const long long pos0 = tile0 + threadIdx.x * kGroup;
     uint16_t* pv = static_cast<uint16_t*>(p.v);
@@ -493,6 +498,8 @@ struct AdamUpdateOp {
       }
     }
   }
+  // 16 consecutive elements at `pos`, by this thread alone (the layout without the split)
+  __device__ __forceinline__ void full_group(long long pos) { tiles_plain<1>(pos - (long long)threadIdx.x * kGroup); }
   __device__ __forceinline__ void group(long long pos, int valid) {
     if (!careful) {
       // ragged tail of a tensor: same arithmetic, element by element
@@ -658,6 +665,8 @@ struct AdamUpdateVarOp {
     st_store16<MASTER>(p.w, pos, dw);
     st_store16<kStE4M3>(p.wcopy, pos, tq);
   }
+  // 16 consecutive elements at `pos`, by this thread alone: the tile body with the thread's own offset taken out
+  __device__ __forceinline__ void full_group(long long pos) { tiles<1>(pos - (long long)threadIdx.x * kGroup); }
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) {
       const long long i = pos + j;

@@ -185,7 +185,7 @@ void launch_walk(fp8lm_ctx* c, hipStream_t s, Kernel kernel, const Params& p) {
   const dim3 g(grid_of(c)), b(kThreads);
   hipLaunchKernelGGL(kernel, g, b, 0, s, tb, p);
   if (tb.deferred)
-    hipLaunchKernelGGL((epilogue_kernel<Op, Params>), dim3(std::min<int>(c->n_tensors, 4 * c->num_cus)), b, 0, s, tb, p,
+    hipLaunchKernelGGL((epilogue_kernel<Op, Params>), dim3(std::min<int>(c->n_tensors, 8 * c->num_cus)), b, 0, s, tb, p,
                        (int)g.x, (int)c->n_tensors);
 }
 

@@ -114,6 +114,20 @@ struct AmaxOp {
         src_fold<SRC>(acc, r[u][k].w);
       }
   }
+  // 16 consecutive elements at `pos`, by this thread alone
+  __device__ __forceinline__ void full_group(long long pos) {
+    const elem_t* q = static_cast<const elem_t*>(p.src) + pos;
+    uint4 r[kLoads];
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) r[k] = ld16<kNtLoadRO>(q + k * kPer);
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      src_fold<SRC>(acc, r[k].x);
+      src_fold<SRC>(acc, r[k].y);
+      src_fold<SRC>(acc, r[k].z);
+      src_fold<SRC>(acc, r[k].w);
+    }
+  }
   __device__ __forceinline__ void group(long long pos, int valid) {
     const elem_t* q = static_cast<const elem_t*>(p.src) + pos;
     for (int j = 0; j < valid; ++j) src_fold1<SRC>(acc, q[j]);
@@ -315,10 +329,10 @@ struct CastOp {
     return c;
   }
   __device__ __forceinline__ bool fast() const { return !careful; }
-  template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
-    // kSplit: the thread's 16 elements are [8L, 8L+8) of each half of the tile (every 128-bit load contiguous
-    // over the workgroup, 64-bit stores); otherwise 16 consecutive elements.
-    constexpr bool kSplit = FP8LM_CAST_SPLIT && kSrc16<SRC>;
+  template <int UN> __device__ __forceinline__ void tiles(long long pos0) { tiles_as<UN, FP8LM_CAST_SPLIT && kSrc16<SRC>>(pos0); }
+  // kSplit: the thread's 16 elements are [8L, 8L+8) of each half of the tile (every 128-bit load contiguous
+  // over the workgroup, 64-bit stores); otherwise 16 consecutive elements.
+  template <int UN, bool kSplit> __device__ __forceinline__ void tiles_as(long long pos0) {
     uint4 r[UN][kLoads], mm[UN];
     const long long pos = pos0 + threadIdx.x * (kSplit ? 8 : kGroup);
     const elem_t* q = static_cast<const elem_t*>(p.src) + pos;
@@ -381,6 +395,8 @@ struct CastOp {
     }
     n_elems += UN * kGroup;
   }
+  // 16 consecutive elements at `pos`, by this thread alone (the layout without the split)
+  __device__ __forceinline__ void full_group(long long pos) { tiles_as<1, false>(pos - (long long)threadIdx.x * kGroup); }
   __device__ __forceinline__ void group(long long pos, int valid) {
     const elem_t* q = static_cast<const elem_t*>(p.src) + pos;
     for (int j = 0; j < valid; ++j) p.dst[pos + j] = (uint8_t)one(q[j], FUSE ? p.m[pos + j] : 0u);
@@ -503,6 +519,8 @@ struct RequantOp {
     for (int u = 0; u < UN; ++u) st16<false>(p.dst + pos + u * kTile, make_uint4(word(a[u].x), word(a[u].y), word(a[u].z), word(a[u].w)));
     n_elems += UN * kGroup;
   }
+  // 16 consecutive elements at `pos`, by this thread alone: the tile body with the thread's own offset taken out
+  __device__ __forceinline__ void full_group(long long pos) { tiles<1>(pos - (long long)threadIdx.x * kGroup); }
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) {
       const uint32_t in = p.src[pos + j];
@@ -664,6 +682,8 @@ struct SumOp {
     }
     n_elems += UN * kGroup;
   }
+  // 16 consecutive elements at `pos`, by this thread alone: the tile body with the thread's own offset taken out
+  __device__ __forceinline__ void full_group(long long pos) { tiles<1>(pos - (long long)threadIdx.x * kGroup); }
   __device__ __forceinline__ void group(long long pos, int valid) {
     for (int j = 0; j < valid; ++j) {
       float acc = 0.0f;

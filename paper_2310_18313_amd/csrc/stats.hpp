@@ -76,6 +76,8 @@ struct QuantStatsOp {
       }
     }
   }
+  // 16 consecutive elements at `pos`, by this thread alone: the tile body with the thread's own offset taken out
+  __device__ __forceinline__ void full_group(long long pos) { tiles<1>(pos - (long long)threadIdx.x * kGroup); }
   __device__ __forceinline__ void group(long long pos, int valid) {
     const elem_t* rp = static_cast<const elem_t*>(p.ref) + pos;
     for (int j = 0; j < valid; ++j) one(rp[j], p.q[pos + j]);

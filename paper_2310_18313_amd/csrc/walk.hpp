@@ -236,8 +236,9 @@ __global__ __launch_bounds__(kThreads) void epilogue_kernel(Tables tb, Params p,
 // Op must provide: begin(t, desc); fast() (uniform: may the vector path be used for this tensor);
 // tiles<UN>(pos): UN complete 4096-element tiles starting at element `pos` of the flat buffers, handled
 // by the whole workgroup (all loads issued before the first use; the op chooses which 16 elements of
-// a tile a thread takes); group(pos, valid) with 1 <= valid <= 16 for everything else, element by
-// element; flush(t, desc, chunks_done) (called by all threads when the workgroup leaves tensor t: it fills
+// a tile a thread takes); full_group(pos): the 16 consecutive elements starting at `pos`, handled by the calling
+// thread alone with vector accesses (any subset of the threads may call it); group(pos, valid) with
+// 1 <= valid <= 16 for everything else, element by element; flush(t, desc, chunks_done) (called by all threads when the workgroup leaves tensor t: it fills
 // a Stats = BlockStats<..>, combines it over the workgroup and hands it to `collect`); and for the tensor's
 // scalar epilogue finalize(t, desc, stats), run by one thread once the totals of all workgroups are known.
 template <int UN, class Op>
@@ -271,9 +272,12 @@ __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
         for (; tile + UN <= ntiles; tile += UN) op.template tiles<UN>(base + (long long)tile * kTile);
       for (; tile < ntiles; ++tile) op.template tiles<1>(base + (long long)tile * kTile);
     }
+    // what is left of the chunk (less than a tile; a whole small tensor): complete 16-element groups still take
+    // 128-bit accesses, only the last, incomplete group of a tensor goes element by element
     for (int i = tile * kTile + threadIdx.x * kGroup; i < len; i += kTile) {
       const int valid = len - i < kGroup ? len - i : kGroup;
-      op.group(base + i, valid);
+      if (valid == kGroup && op.fast()) op.full_group(base + i);
+      else op.group(base + i, valid);
     }
     ++done;
   }
