@@ -574,6 +574,10 @@ void oracle_init_master_as(const uint16_t* w_bf16, const oracle_tensor* tensors,
     }
     uint32_t flags = 0;
     M.amax = nonfinite ? std::numeric_limits<float>::infinity() : A;
+    // an initialisation has no earlier scale to keep: a tensor of zeros (biases), a non-finite one and the
+    // formats without tensor scaling all get scale 1, whatever the caller's buffer held
+    M.scale = 1.0f;
+    M.inv_scale = 1.0f;
     if (nonfinite) flags |= ORACLE_FLAG_NONFINITE;
     else if (A == 0.0f) flags |= ORACLE_FLAG_AMAX_ZERO;
     else if (st_scaled(wk)) {
@@ -583,7 +587,6 @@ void oracle_init_master_as(const uint16_t* w_bf16, const oracle_tensor* tensors,
       M.scale = std::ldexp(1.0f, e);
       M.inv_scale = std::ldexp(1.0f, -e);
     }
-    if (!st_scaled(wk)) { M.scale = 1.0f; M.inv_scale = 1.0f; }
     float stored_max = 0.0f;
     uint64_t n_sat = 0, n_under = 0;
     for (int64_t i = 0; i < n; ++i) {

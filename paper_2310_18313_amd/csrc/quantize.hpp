@@ -144,6 +144,11 @@ struct AmaxOp {
   __device__ void finalize(int t, const TensorDesc&, const Stats& s) {
     const uint32_t abits = s.mx[0];
     fp8lm_meta& M = p.meta[t];
+    if constexpr (MODE == kAmaxForMaster) {
+      // an initialisation has no earlier scale to keep: zero tensors, non-finite ones and unscaled formats get 1
+      M.scale = 1.0f;
+      M.inv_scale = 1.0f;
+    }
     if (abits >= SrcTraits<SRC>::kNonfinite) {
       M.amax = __builtin_inff();
       M.flags = FP8LM_FLAG_NONFINITE;
@@ -159,10 +164,7 @@ struct AmaxOp {
       // master weights: one binade of headroom; flags and the rest are completed by the cast pass
       if (A == 0.0f) {
         flags |= FP8LM_FLAG_AMAX_ZERO;
-      } else if (p.fmax_bits == 0u) {      // BF16 / FP32 master weights carry no scale
-        M.scale = 1.0f;
-        M.inv_scale = 1.0f;
-      } else {
+      } else if (p.fmax_bits != 0u) {      // 0: BF16 / FP32 master weights carry no scale
         const int k = pow2_exp(p.fmax_bits, A) - 1;
         const int e = k < -126 ? -126 : (k > 126 ? 126 : k);
         if (e != k) flags |= FP8LM_FLAG_SCALE_CLAMPED;
