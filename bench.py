@@ -7,7 +7,8 @@ A "step" is one pass of the whole hot path over one model's flat tensors, all in
     fp8lm_adam_step_fp8: amax pass (read 2) + update pass (read 6, write 6)
 = 19 algorithmic bytes per parameter.  Prints one JSON line: parameters updated per second, the
 achieved HBM bandwidth of the dominant kernel (the Adam update pass, 12 B/param) against the 8 TB/s
-peak, and the CPU oracle timed on the host cores for a bounded sample of the same workload.
+peak, the bandwidth that memory-only skeletons of the same kernels reach on the same buffers
+("ceilings"), and the CPU oracle timed on the host cores for a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -132,8 +133,8 @@ def main() -> int:
                     help="chunks per workgroup below which tensors are finished by a second launch (0: never)")
     ap.add_argument("--exact", type=int, default=1)
     ap.add_argument("--stats", type=int, default=0)
-    ap.add_argument("--copy-ceiling", action="store_true", help="(always on: a plain 128-bit copy kernel is timed beside the step)")
-    ap.add_argument("--no-copy-ceiling", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the memory-only skeletons of the four kernels that are timed on the same buffers after the step")
     ap.add_argument("--path", choices=["jit", "fused", "single"], default="jit",
                     help="jit: amax pass + cast + two-pass Adam (19 B/param, the three entry points as they are); "
                          "fused: same results, the cast also does the Adam step's first pass (18 B/param, one GPU "
@@ -141,7 +142,10 @@ def main() -> int:
     ap.add_argument("--allreduce-steps", type=int, default=0, metavar="N",
                     help="also time the shared-scale re-quantise kernel and the N-rank FP8 sum (Eq. 4-6) on this layout")
     ap.add_argument("--only-path", action="store_true", help="do not also time the other two paths")
-    ap.add_argument("--no-spread", action="store_true", help="allocate the buffers plainly, one after the other")
+    ap.add_argument("--spread", action="store_true",
+                    help="place the buffers in different HBM regions with placement.SpreadAllocator (it briefly takes all "
+                         "free device memory; measurably faster for states of 0.5e9 to 10e9 parameters).  Default: one "
+                         "allocation with the buffers carved out one after the other, as a caller of the C ABI would")
     ap.add_argument("--graph", action="store_true",
                     help="also record one step into a HIP graph and time its replays (small workloads are bound by "
                          "launch latency; the hyper-parameters, step number included, are baked into the graph)")
@@ -164,13 +168,13 @@ def main() -> int:
     lay = wl.layout
     P = lay.n_params
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
-    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=not args.no_spread,
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=args.spread,
                         grad_buffer=True)
     if args.chunk or args.blocks_per_cu or args.single_pass_min_chunks >= 0:
         st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 16,
                           (1 << 30) if args.single_pass_min_chunks < 0 else args.single_pass_min_chunks)
     grad = st.grad
-    placement = {"spread_over_hbm_regions": st.spread, **{k: v for k, v in st.placement.items() if k != "where"}}
+    placement = {"allocation": "spread over HBM regions" if st.spread else "one arena", **{k: v for k, v in st.placement.items() if k != "where"}}
     if st.spread:
         from paper_2310_18313_amd.placement import verify_spread
         placement["check_v_vs_w"] = verify_spread(st.ctx, st.v, st.w)
@@ -270,16 +274,7 @@ def main() -> int:
             graph.replay()
         torch.cuda.synchronize()
         out["graph_replay_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
-    if not args.no_copy_ceiling and lay.total >= (1 << 20):
-        nbytes = min(lay.total // 16 * 16, 1 << 32)
-        st.ctx.set_timing(True)
-        st.ctx.get_timing()
-        for _ in range(5):
-            st.ctx.copy_bytes(st.m, st.g8, nbytes)
-        n, ms = st.ctx.get_timing()["copy"]
-        st.ctx.set_timing(False)
-        out["copy_kernel_GBps"] = round(2 * nbytes / (ms / n * 1e-3) / 1e9, 1)     # m -> FP8 gradient buffer, same region
-        out["step_frac_of_copy_kernel"] = round(out["step_GBps"] / out["copy_kernel_GBps"], 4)
+    want_ceilings = not args.no_ceilings and lay.total >= (1 << 20)
     if args.allreduce_steps:
         N = args.allreduce_steps
         ranks = [st.g8] + [st.g8.clone() for _ in range(N - 1)]
@@ -301,6 +296,35 @@ def main() -> int:
         del ranks, summed
     else:
         extra = None
+    if want_ceilings:
+        # Memory-only skeletons of the four kernels (same grid, tile walk, access widths and cache policies, XORs for
+        # arithmetic) over the same buffers, whole tiles only: the bandwidth this access pattern reaches on this
+        # machine.  Last, because they overwrite the state.
+        n_el = lay.total // 4096 * 4096
+        shapes = {"amax": (B.SKEL_READ16, [grad]), "cast": (B.SKEL_CAST, [grad, st.g8]),
+                  "adam_amax": (B.SKEL_READ8X2, [st.g8, st.m]),
+                  "adam_update": (B.SKEL_UPDATE, [st.g8, st.m, st.v, st.w, st.wq]),
+                  "write16": (B.SKEL_WRITE16, [grad]), "write8": (B.SKEL_WRITE8, [st.g8])}
+        ceilings = {}
+        for name, (shape, bufs) in shapes.items():
+            views = [t.view(torch.int16) if t.element_size() == 2 else t for t in bufs]
+            st.ctx.memory_skeleton(shape, views, n_el)
+            st.ctx.set_timing(True)
+            st.ctx.get_timing()
+            for _ in range(5):
+                st.ctx.memory_skeleton(shape, views, n_el)
+            n, ms = st.ctx.get_timing()["skeleton"]
+            st.ctx.set_timing(False)
+            bpe = B.SKEL_BYTES_PER_ELEM[shape]
+            ceilings[name] = {"avg_ms": round(ms / n, 4), "bytes_per_elem": bpe,
+                              "GBps": round(bpe * n_el / (ms / n * 1e-3) / 1e9, 1)}
+            if name in kernels:
+                kernels[name]["frac_of_skeleton"] = round(ceilings[name]["avg_ms"] / kernels[name]["avg_ms"], 4)
+        path_ms = sum(ceilings[k]["avg_ms"] for k in ("amax", "cast", "adam_amax", "adam_update"))
+        ceilings["step_of_skeletons_ms"] = round(path_ms, 3)        # the pass structure of the jit path, memory only
+        out["ceilings"] = ceilings
+        if args.path == "jit":
+            out["step_frac_of_skeletons"] = round(path_ms / ms_per_step, 4)
     del st, grad
     torch.cuda.empty_cache()
     if extra:

@@ -13,10 +13,13 @@
  *     overlap.  Elements between tensors are padding: never read into a result, never written.
  *   - Each scaled buffer carries one fp8lm_meta per tensor (device memory, caller-owned).  A stored
  *     payload equals value * scale; the value is payload / scale (Sec. 2.1, text before Eq. 4).
- *     Scales are powers of two, so scaling is exact.
- *   - Calls enqueue work on the given HIP stream and return without synchronising.  They allocate
- *     nothing; only fp8lm_create / fp8lm_destroy touch the allocator.  One context must not be used
- *     from two streams at the same time (its reduction scratch is shared).
+ *     Scales are powers of two, so scaling is exact; the one exception is the metadata fp8lm_sum_fp8
+ *     writes (scale N * s_g, see there).
+ *   - Calls enqueue work on the given HIP stream and return without synchronising.  They allocate no
+ *     device memory; only fp8lm_create / fp8lm_destroy, the two calls that rebuild a context's tables
+ *     (fp8lm_set_tuning, fp8lm_set_tensor_flags) and the timing aid (fp8lm_set_timing creates its events
+ *     up front) touch an allocator.  One context must not be used from two streams at the same time (its
+ *     reduction scratch is shared).
  *   - Return value: FP8LM_OK or a negative fp8lm_status.  On an error nothing has been enqueued.
  *     Data-dependent conditions (non-finite inputs, all-zero tensors, saturation) are reported in the
  *     metadata flags and counters on the device, never in the return value.
@@ -88,7 +91,8 @@ typedef struct {
 /* Per-tensor, per-buffer scaling metadata.  Device resident, plain data, 112 bytes.               */
 typedef struct {
   float scale;       /* power of two; stored payload = value * scale                               */
-  float inv_scale;   /* exact reciprocal                                                           */
+  float inv_scale;   /* 1 / scale: exact for a power-of-two scale; the fp32-rounded reciprocal in the
+                        metadata fp8lm_sum_fp8 writes when the number of ranks is not a power of two  */
   float amax;        /* max |value| before quantisation; +inf if a non-finite value was seen       */
   float amax_deq;    /* max |stored payload| / scale over the stored codes that are not NaN        */
   float amax_hist[FP8LM_HIST]; /* ring of recent amax values (Appendix A.2, delayed scaling)       */
@@ -135,7 +139,9 @@ typedef struct {
                        0: hardware v_sqrt_f32 / v_rcp_f32, 1 ulp each: m and v are unaffected, the
                           update term is off by a few fp32 ulps, so a new weight is within one FP16
                           ulp of max(|w|, lr * |update|) -- more than one ulp of the result itself
-                          where the two nearly cancel                                              */
+                          where the two nearly cancel.  This setting is therefore OUTSIDE the accuracy
+                          bar of this library (master weights within one FP16 ulp of the scalar
+                          definition): a faster, looser variant, never the default                 */
 } fp8lm_adam_hparams;
 
 /*
@@ -202,7 +208,10 @@ fp8lm_status fp8lm_amax_scale(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_
 /*
  * Step 2 of the gradient quantisation (Sec. 2.1: the scaling tensor (g', s'); Appendix A.1).
  * dst[i] = FP8(meta[t].scale * src[i]), round to nearest even, saturating to the largest finite
- * code (inf included); NaN becomes 0x7F.  Also writes meta[t].{n_sat, n_underflow, amax_deq,
+ * code (inf included); NaN becomes 0x7F.  Precondition: meta[t].flags is what fp8lm_amax_scale left for
+ * this very source (FLAG_NONFINITE routes the tensor to the element-by-element path that knows NaN; with
+ * stale flags a NaN in src is stored as an arbitrary finite code).  fp8lm_cast_fp8_delayed has no such
+ * precondition.  Also writes meta[t].{n_sat, n_underflow, amax_deq,
  * FLAG_SATURATED} and advances the auto-scaling state of Sec. 2.1: if more than sat_num/sat_den of
  * the payloads sit on the top code the next scale uses mu = 1/2 (clean_steps = 0); otherwise
  * clean_steps grows and mu = 1/2, 1, 2 as it passes 0, ramp_steps/2, ramp_steps.
@@ -253,9 +262,11 @@ fp8lm_status fp8lm_cast_fp8_for_adam(fp8lm_ctx* ctx, const void* src /*device*/,
 fp8lm_status fp8lm_shared_scale(fp8lm_ctx* ctx, const fp8lm_meta* const* metas /*host -> device*/, int32_t n_ranks,
                                 float* shared /*device*/, void* stream);
 /*
- * Eq. 5: dst[i] = FP8(shared[t] * (src[i] / src_meta[t].scale)), round to nearest even.  Both scales are
- * powers of two and shared <= scale, so this is an exponent shift: nothing saturates, values that
- * fall below the format's range lose bits or become zero (n_underflow).  dst may be src (in place);
+ * Eq. 5: dst[i] = FP8(shared[t] * (src[i] / src_meta[t].scale)), round to nearest even.  For a source as
+ * fp8lm_cast_fp8 leaves it both scales are powers of two and shared <= scale, so this is an exponent shift:
+ * nothing saturates, values that fall below the format's range lose bits or become zero (n_underflow).  A
+ * source with another scale (say the output of fp8lm_sum_fp8) is multiplied by src_meta[t].inv_scale and
+ * by shared[t], two fp32 roundings, and saturates like any cast.  dst may be src (in place);
  * dst_meta must not be src_meta.  Writes dst_meta[t].{scale = shared, inv_scale, amax, amax_deq, n_sat,
  * n_underflow, flags}; the auto-scaling fields are left alone.
  */
@@ -266,8 +277,11 @@ fp8lm_status fp8lm_requantize_fp8(fp8lm_ctx* ctx, const uint8_t* src /*device*/,
  * Eq. 6 as a sum all-reduce would leave it on every rank: dst[i] = FP8(payloads[0][i] + ... +
  * payloads[N-1][i]), added in rank order in fp32 and rounded once (nearest even, saturating).  All
  * payloads carry the shared scale; dst_meta[t].scale = N * shared[t], so dst / scale is the mean
- * gradient.  Also writes amax (of the sum, in value units), amax_deq, n_sat, n_underflow, flags, and
- * advances the auto-scaling state of dst_meta with n_sat as fp8lm_cast_fp8 does.
+ * gradient.  For N that is not a power of two this scale is not one either and dst_meta[t].inv_scale is the
+ * fp32-rounded 1 / (N * shared[t]): fp8lm_adam_step_fp8 dequantises with inv_scale, so it sees the mean
+ * gradient to within one fp32 rounding (2^-24 relative) instead of exactly.  Also writes amax (of the sum, in
+ * value units), amax_deq, n_sat, n_underflow, flags, and advances the auto-scaling state of dst_meta with
+ * n_sat as fp8lm_cast_fp8 does.
  *   payloads : host array of n_ranks device pointers to flat FP8 buffers (read only).
  */
 fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* ctx, const uint8_t* const* payloads /*host -> device*/, int32_t n_ranks,
@@ -275,9 +289,30 @@ fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* ctx, const uint8_t* const* payloads /*host
                            fp8lm_meta* dst_meta /*device*/, const fp8lm_autoscale_cfg* cfg /*host*/, void* stream);
 
 /*
+ * Sec. 2.1 (text after Eq. 3): the auto-scaling factor mu follows the saturation statistic of the summed
+ * gradient, and every rank applies it to its own gradient in the next step.  fp8lm_sum_fp8 leaves the state
+ * (mu_exp, clean_steps) in the sum's metadata; this call copies those two fields of `from[t]` into
+ * metas[r][t] for every rank, where the ranks' next fp8lm_amax_scale reads them.  Nothing else is touched.
+ *   from  : device array [n_tensors] (read only);
+ *   metas : host array of n_ranks device pointers, each to a meta array [n_tensors].  n_ranks <= 128.
+ */
+fp8lm_status fp8lm_autoscale_broadcast(fp8lm_ctx* ctx, const fp8lm_meta* from /*device*/,
+                                       fp8lm_meta* const* metas /*host -> device*/, int32_t n_ranks, void* stream);
+/*
+ * Sec. 2.1, Eq. 1-2: the fixed factors the paper compares auto-scaling with -- pre-scaling (mu = 1/N, Eq. 1)
+ * and post-scaling (mu = 1, Eq. 2).  Sets meta[t].mu_exp = mu_exp (-64..1) for every tensor; the following
+ * fp8lm_amax_scale multiplies the scale with 2^mu_exp.  (A cast afterwards recomputes mu_exp from its own
+ * statistic, so a fixed factor is set again before every step.)
+ */
+fp8lm_status fp8lm_set_mu(fp8lm_ctx* ctx, fp8lm_meta* meta /*device*/, int32_t mu_exp, void* stream);
+
+/*
  * Master-weight initialisation (Sec. 2.2: FP16 master weights with tensor scaling).
  * For every tensor: scale = 2^(k - 1) with k the largest integer such that 2^k * max|w| <= 65504,
- * w_f16[i] = FP16(scale * w_bf16[i]) (round to nearest even, saturating).  Fills w_meta[t].
+ * w_f16[i] = FP16(scale * w_bf16[i]) (round to nearest even, saturating).  A tensor of zeros (biases) or one
+ * that holds inf/NaN gets scale 1 (FLAG_AMAX_ZERO / FLAG_NONFINITE).  Writes w_meta[t].{scale, inv_scale,
+ * amax, amax_deq, flags, n_sat, n_underflow} whatever the buffer held before; the auto-scaling fields and the
+ * amax history are not used by master weights and are left alone.
  */
 fp8lm_status fp8lm_init_master(fp8lm_ctx* ctx, const void* w_bf16 /*device*/, uint16_t* w_f16 /*device*/,
                                fp8lm_meta* w_meta /*device*/, void* stream);
@@ -351,13 +386,32 @@ fp8lm_status fp8lm_greedy_partition(const int64_t* sizes /*host*/, int32_t n, in
 fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* ctx, const void* src /*device*/, void* dst /*device*/, int64_t bytes,
                               void* stream);
 
+/*
+ * Memory-only skeletons of the hot kernels, for measurement: the same grid, tile walk, access widths, access
+ * layout and cache policies as the kernel named, with the arithmetic replaced by XORs, so that what they reach
+ * is the bandwidth ceiling of that access pattern on this machine.  They move exactly the algorithmic bytes of
+ * the kernel they stand for.  Buffers written are overwritten with meaningless data.
+ *   READ16   bufs = {src16}                     reads 2 B/element     (fp8lm_amax_scale on a bf16 gradient)
+ *   READ8X2  bufs = {a8, b8}                    reads 1 + 1           (first pass of fp8lm_adam_step_fp8)
+ *   WRITE16  bufs = {dst16}                     writes 2
+ *   WRITE8   bufs = {dst8}                      writes 1
+ *   CAST     bufs = {src16, dst8}               reads 2, writes 1     (fp8lm_cast_fp8 from a 16-bit source)
+ *   UPDATE   bufs = {g8, m8, v16, w16, q8}      reads g, m, v, w (6), writes m, v, w in place and q (6)
+ *                                               (second pass of fp8lm_adam_step_fp8, default formats)
+ *   bufs : host array of device pointers, each covering n_elems elements; n_elems a multiple of 4096.
+ */
+typedef enum { FP8LM_SKEL_READ16 = 0, FP8LM_SKEL_READ8X2 = 1, FP8LM_SKEL_WRITE16 = 2, FP8LM_SKEL_WRITE8 = 3,
+               FP8LM_SKEL_CAST = 4, FP8LM_SKEL_UPDATE = 5 } fp8lm_skeleton;
+fp8lm_status fp8lm_memory_skeleton(fp8lm_ctx* ctx, int32_t shape, void* const* bufs /*host -> device*/,
+                                   int64_t n_elems, void* stream);
+
 /* Times the most recent launch of each kernel with HIP events recorded on the launch stream.
  * fp8lm_set_timing(ctx, 1) starts recording event pairs around every kernel launch;
  * fp8lm_get_timing synchronises and returns, per kernel id, the number of launches and the summed
  * duration in milliseconds since timing was enabled, then resets the sums.                       */
 enum { FP8LM_K_AMAX = 0, FP8LM_K_CAST = 1, FP8LM_K_ADAM_AMAX = 2, FP8LM_K_ADAM_UPDATE = 3,
        FP8LM_K_INIT_MASTER = 4, FP8LM_K_COPY = 5, FP8LM_K_SCALARS = 6 /* per-tensor scalar kernels */,
-       FP8LM_K_REQUANT = 7, FP8LM_K_SUM = 8, FP8LM_K_STATS = 9, FP8LM_K_COUNT = 10 };
+       FP8LM_K_REQUANT = 7, FP8LM_K_SUM = 8, FP8LM_K_STATS = 9, FP8LM_K_SKELETON = 10, FP8LM_K_COUNT = 11 };
 fp8lm_status fp8lm_set_timing(fp8lm_ctx* ctx, int32_t enable);
 fp8lm_status fp8lm_get_timing(fp8lm_ctx* ctx, int32_t* launches /*host[FP8LM_K_COUNT]*/,
                               double* total_ms /*host[FP8LM_K_COUNT]*/);

@@ -11,9 +11,9 @@ of Eq. 3 that the per-rank scale is multiplied with:
   auto-scaling   mu follows the saturation statistic of the summed gradient (1/2 after an overflow, back
                  up to 2 over `ramp_steps` clean steps).
 
-Everything numerical runs in the library's kernels (amax, cast, shared scale, re-quantise, sum, error
-statistics); this module only sequences the calls and moves the auto-scaling state from the summed
-gradient's metadata into the ranks' metadata, which is where the next step's cast reads it.
+Everything that belongs to the method runs in the library's kernels (amax, cast, shared scale, re-quantise,
+sum, the hand-over of the auto-scaling state from the summed gradient to the ranks, the error sums and counts);
+this module only sequences the calls and turns the error sums into the figures the ablation plots.
 """
 from __future__ import annotations
 
@@ -26,8 +26,6 @@ import torch
 from . import binding as B
 
 STRATEGIES = ("pre", "post", "auto")
-_MU_EXP_WORD = B.META_DTYPE.fields["mu_exp"][1] // 4          # position of mu_exp / clean_steps in a meta seen
-_CLEAN_WORD = B.META_DTYPE.fields["clean_steps"][1] // 4      # as int32 words
 
 
 class Fp8AllReduce:
@@ -51,16 +49,12 @@ class Fp8AllReduce:
         self.shared = None
 
     def _plant_mu(self) -> None:
-        words = [m.view(torch.int32) for m in self.meta]
         if self.strategy == "auto":
-            src = self.summed_meta.view(torch.int32)
-            for w in words:
-                w[:, _MU_EXP_WORD] = src[:, _MU_EXP_WORD]
-                w[:, _CLEAN_WORD] = src[:, _CLEAN_WORD]
+            self.ctx.autoscale_broadcast(self.summed_meta, self.meta)
         else:
             mu_exp = -int(round(math.log2(self.n))) if self.strategy == "pre" else 0
-            for w in words:
-                w[:, _MU_EXP_WORD] = mu_exp
+            for m in self.meta:
+                self.ctx.set_mu(m, mu_exp)
 
     def step(self, grads: Sequence[torch.Tensor]) -> None:
         """grads: one flat high-precision gradient buffer per rank.  Leaves the result in `summed`/`summed_meta`."""
@@ -82,7 +76,8 @@ class Fp8AllReduce:
 
 
 def report(stats: np.ndarray, numels: List[int]) -> dict:
-    """Totals over tensors: SNR in dB, underflow rate (of the non-zero reference entries), overflow rate."""
+    """Presentation of the kernel's per-tensor sums and counts as the ablation plots them: totals over tensors as
+    SNR in dB, underflow rate (of the non-zero reference entries), overflow rate."""
     sig, noi = float(stats["signal"].sum()), float(stats["noise"].sum())
     nz, n = int(stats["n_nonzero"].sum()), int(sum(numels))
     return {"snr_db": float("inf") if noi == 0 else 10 * math.log10(sig / noi) if sig > 0 else float("nan"),

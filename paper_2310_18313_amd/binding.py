@@ -27,13 +27,15 @@ MU_SET_HALF, MU_HALVE = 0, 1
 STATE_F16, STATE_BF16, STATE_E4M3, STATE_F32 = 0, 1, 2, 3
 STATE_BYTES = {STATE_F16: 2, STATE_BF16: 2, STATE_E4M3: 1, STATE_F32: 4}
 FLAG_NONFINITE, FLAG_AMAX_ZERO, FLAG_SCALE_CLAMPED, FLAG_SATURATED = 1, 2, 4, 8
-K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_REQUANT, K_SUM, K_STATS, K_COUNT = range(11)
-KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars", "requantize", "sum", "quant_stats"]
+SKEL_READ16, SKEL_READ8X2, SKEL_WRITE16, SKEL_WRITE8, SKEL_CAST, SKEL_UPDATE = range(6)
+SKEL_BYTES_PER_ELEM = {SKEL_READ16: 2, SKEL_READ8X2: 2, SKEL_WRITE16: 2, SKEL_WRITE8: 1, SKEL_CAST: 3, SKEL_UPDATE: 12}
+K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_REQUANT, K_SUM, K_STATS, K_SKELETON, K_COUNT = range(12)
+KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars", "requantize", "sum", "quant_stats", "skeleton"]
 
 EXPORTS = [
     "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_set_tensor_flags", "fp8lm_meta_init", "fp8lm_amax_scale",
     "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_cast_fp8_for_adam", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
-    "fp8lm_quant_error_stats",
+    "fp8lm_quant_error_stats", "fp8lm_autoscale_broadcast", "fp8lm_set_mu", "fp8lm_memory_skeleton",
     "fp8lm_init_master", "fp8lm_init_master_as", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
@@ -41,12 +43,6 @@ EXPORTS = [
 
 QUANT_STATS_DTYPE = np.dtype([("signal", "<f8"), ("noise", "<f8"), ("n_nonzero", "<u8"), ("n_underflow", "<u8"),
                               ("n_overflow", "<u8"), ("n_nonfinite", "<u8")])
-
-
-def snr_db(stats: np.ndarray) -> np.ndarray:
-    """10 log10(signal / noise) per tensor; +inf where nothing was lost, NaN for an all-zero reference."""
-    with np.errstate(divide="ignore", invalid="ignore"):
-        return 10.0 * np.log10(stats["signal"] / stats["noise"])
 
 
 class Tensor(C.Structure):
@@ -131,6 +127,9 @@ def lib() -> C.CDLL:
         L.fp8lm_requantize_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp]
         L.fp8lm_sum_fp8.argtypes = [vp, vp, i32, C.c_int, vp, vp, vp, vp, vp]
         L.fp8lm_quant_error_stats.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
+        L.fp8lm_autoscale_broadcast.argtypes = [vp, vp, vp, i32, vp]
+        L.fp8lm_set_mu.argtypes = [vp, vp, i32, vp]
+        L.fp8lm_memory_skeleton.argtypes = [vp, i32, vp, i64, vp]
         L.fp8lm_adam_step_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fp8lm_copy_bytes.argtypes = [vp, vp, vp, i64, vp]
         L.fp8lm_greedy_partition.argtypes = [vp, i32, i32, vp, vp]
@@ -285,10 +284,22 @@ class Context:
         _check(lib().fp8lm_sum_fp8(self._h, C.cast(ptrs, C.c_void_p), len(payloads), fmt, _ptr(shared), _ptr(dst),
                                    _ptr(dst_meta), C.addressof(cfg), _stream(stream)), "fp8lm_sum_fp8")
 
+    def autoscale_broadcast(self, from_meta, metas, stream=None):
+        """Copies the auto-scaling state (mu_exp, clean_steps) of `from_meta` into every meta array of `metas`."""
+        self._fits_meta(from_meta, *metas)
+        ptrs = (C.c_void_p * len(metas))(*[_ptr(m) for m in metas])
+        _check(lib().fp8lm_autoscale_broadcast(self._h, _ptr(from_meta), C.cast(ptrs, C.c_void_p), len(metas),
+                                               _stream(stream)), "fp8lm_autoscale_broadcast")
+
+    def set_mu(self, meta, mu_exp: int, stream=None):
+        """Fixed auto-scaling factor 2^mu_exp for the next scale computation of every tensor."""
+        self._fits_meta(meta)
+        _check(lib().fp8lm_set_mu(self._h, _ptr(meta), mu_exp, _stream(stream)), "fp8lm_set_mu")
+
     def quant_error_stats(self, ref, q, fmt, q_meta, stream=None) -> np.ndarray:
         """Per-tensor signal and noise energies and underflow / overflow counts of the FP8 tensor `q` against the
         high-precision reference `ref` (Sec. 3.3, communication ablation).  Synchronises and returns a host array
-        of QUANT_STATS_DTYPE; `snr_db(stats)` turns the energies into decibels."""
+        of QUANT_STATS_DTYPE (the signal-to-noise ratio is signal / noise)."""
         assert q.element_size() == 1
         self._fits(ref, q)
         self._fits_meta(q_meta)
@@ -319,6 +330,18 @@ class Context:
     def copy_bytes(self, src, dst, nbytes, stream=None):
         assert src.numel() * src.element_size() >= nbytes and dst.numel() * dst.element_size() >= nbytes
         _check(lib().fp8lm_copy_bytes(self._h, _ptr(src), _ptr(dst), nbytes, _stream(stream)), "fp8lm_copy_bytes")
+
+    def memory_skeleton(self, shape: int, bufs, n_elems: int, stream=None):
+        """Memory-only stand-in of one hot kernel over the first n_elems elements of `bufs` (see fp8lm.h); buffers
+        that the shape writes are overwritten with meaningless data."""
+        sizes = {SKEL_READ16: (2,), SKEL_READ8X2: (1, 1), SKEL_WRITE16: (2,), SKEL_WRITE8: (1,), SKEL_CAST: (2, 1),
+                 SKEL_UPDATE: (1, 1, 2, 2, 1)}[shape]
+        assert len(bufs) == len(sizes)
+        for t, sz in zip(bufs, sizes):
+            assert t.element_size() == sz and t.numel() >= n_elems
+        ptrs = (C.c_void_p * len(bufs))(*[_ptr(t) for t in bufs])
+        _check(lib().fp8lm_memory_skeleton(self._h, shape, C.cast(ptrs, C.c_void_p), n_elems, _stream(stream)),
+               "fp8lm_memory_skeleton")
 
     def set_timing(self, enable: bool):
         _check(lib().fp8lm_set_timing(self._h, 1 if enable else 0), "fp8lm_set_timing")

@@ -508,6 +508,35 @@ fp8lm_status fp8lm_sum_fp8(fp8lm_ctx* c, const uint8_t* const* payloads, int32_t
   return after_launch();
 }
 
+fp8lm_status fp8lm_autoscale_broadcast(fp8lm_ctx* c, const fp8lm_meta* from, fp8lm_meta* const* metas, int32_t n_ranks,
+                                       void* stream) {
+  if (!c || !metas || n_ranks < 1 || n_ranks > kMaxRanks) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_tensors == 0) return FP8LM_OK;
+  if (!from) return FP8LM_ERR_INVALID_ARGUMENT;
+  RankMetasOut rm{};
+  rm.n_ranks = n_ranks;
+  for (int r = 0; r < n_ranks; ++r) {
+    if (!metas[r] || metas[r] == from) return FP8LM_ERR_INVALID_ARGUMENT;
+    rm.m[r] = metas[r];
+  }
+  DeviceGuard guard(c->device);
+  Timed tm(c, (hipStream_t)stream, FP8LM_K_SCALARS);
+  hipLaunchKernelGGL(autoscale_broadcast_kernel, dim3((c->n_tensors + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                     from, rm, c->n_tensors);
+  return after_launch();
+}
+
+fp8lm_status fp8lm_set_mu(fp8lm_ctx* c, fp8lm_meta* meta, int32_t mu_exp, void* stream) {
+  if (!c || mu_exp < -64 || mu_exp > 1) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_tensors == 0) return FP8LM_OK;
+  if (!meta) return FP8LM_ERR_INVALID_ARGUMENT;
+  DeviceGuard guard(c->device);
+  Timed tm(c, (hipStream_t)stream, FP8LM_K_SCALARS);
+  hipLaunchKernelGGL(set_mu_kernel, dim3((c->n_tensors + 255) / 256), dim3(256), 0, (hipStream_t)stream, meta,
+                     c->n_tensors, mu_exp);
+  return after_launch();
+}
+
 fp8lm_status fp8lm_init_master_as(fp8lm_ctx* c, const void* w_bf16, void* w_out, fp8lm_meta* w_meta,
                                   fp8lm_state_fmt master_fmt, void* stream) {
   if (!c || (int)master_fmt < 0 || (int)master_fmt > 3) return FP8LM_ERR_INVALID_ARGUMENT;
@@ -681,10 +710,61 @@ fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* c, const void* src, void* dst, int64_t 
   return after_launch();
 }
 
+fp8lm_status fp8lm_memory_skeleton(fp8lm_ctx* c, int32_t shape, void* const* bufs, int64_t n_elems, void* stream) {
+  static const int n_bufs[] = {1, 2, 1, 1, 2, 5};
+  if (!c || shape < 0 || shape > FP8LM_SKEL_UPDATE || !bufs || n_elems < 0 || n_elems % kTile != 0)
+    return FP8LM_ERR_INVALID_ARGUMENT;
+  for (int i = 0; i < n_bufs[shape]; ++i) {
+    if (!bufs[i]) return FP8LM_ERR_INVALID_ARGUMENT;
+    if (!aligned16(bufs[i])) return FP8LM_ERR_MISALIGNED;
+  }
+  if (n_elems == 0) return FP8LM_OK;
+  DeviceGuard guard(c->device);
+  SkeletonParams p{};
+  p.n_tiles = n_elems / kTile;
+  p.sink = reinterpret_cast<uint32_t*>(c->d_partials);     // kWaves words per workgroup: far inside the record array
+  const long long want = (long long)c->num_cus * c->blocks_per_cu;
+  const dim3 g((unsigned)std::max<long long>(1, std::min<long long>(want, p.n_tiles))), b(kThreads);
+  hipStream_t s = (hipStream_t)stream;
+  Timed tm(c, s, FP8LM_K_SKELETON);
+  switch (shape) {
+    case FP8LM_SKEL_READ16:
+      p.s2[0] = static_cast<const uint16_t*>(bufs[0]);
+      hipLaunchKernelGGL((skeleton_kernel<0, 1, 0, 0, FP8LM_UN_READ>), g, b, 0, s, p);
+      break;
+    case FP8LM_SKEL_READ8X2:
+      p.s1[0] = static_cast<const uint8_t*>(bufs[0]); p.s1[1] = static_cast<const uint8_t*>(bufs[1]);
+      hipLaunchKernelGGL((skeleton_kernel<2, 0, 0, 0, FP8LM_UN_READ>), g, b, 0, s, p);
+      break;
+    case FP8LM_SKEL_WRITE16:
+      p.d2[0] = static_cast<uint16_t*>(bufs[0]);
+      hipLaunchKernelGGL((skeleton_kernel<0, 0, 0, 1, 1>), g, b, 0, s, p);
+      break;
+    case FP8LM_SKEL_WRITE8:
+      p.d1[0] = static_cast<uint8_t*>(bufs[0]);
+      hipLaunchKernelGGL((skeleton_kernel<0, 0, 1, 0, 1>), g, b, 0, s, p);
+      break;
+    case FP8LM_SKEL_CAST:
+      p.s2[0] = static_cast<const uint16_t*>(bufs[0]); p.d1[0] = static_cast<uint8_t*>(bufs[1]);
+      hipLaunchKernelGGL((skeleton_kernel<0, 1, 1, 0, FP8LM_UN_CAST>), g, b, 0, s, p);
+      break;
+    default:   // FP8LM_SKEL_UPDATE: reads g, m, v, w; writes m, v, w in place and the weight copy
+      p.s1[0] = static_cast<const uint8_t*>(bufs[0]); p.s1[1] = static_cast<const uint8_t*>(bufs[1]);
+      p.s2[0] = static_cast<const uint16_t*>(bufs[2]); p.s2[1] = static_cast<const uint16_t*>(bufs[3]);
+      p.d1[0] = static_cast<uint8_t*>(bufs[1]); p.d1[1] = static_cast<uint8_t*>(bufs[4]);
+      p.d2[0] = static_cast<uint16_t*>(bufs[2]); p.d2[1] = static_cast<uint16_t*>(bufs[3]);
+      hipLaunchKernelGGL((skeleton_kernel<2, 2, 2, 2, FP8LM_UN_UPDATE>), g, b, 0, s, p);
+      break;
+  }
+  return after_launch();
+}
+
 fp8lm_status fp8lm_set_timing(fp8lm_ctx* c, int32_t enable) {
   if (!c) return FP8LM_ERR_INVALID_ARGUMENT;
   DeviceGuard guard(c->device);
   if (enable && c->free_events.empty() && c->stamps.empty()) {
+    c->stamps.reserve(4096);           // launches are stamped without touching the host allocator
+    c->free_events.reserve(4096);
     for (int i = 0; i < 4096; ++i) {
       hipEvent_t a = nullptr, b = nullptr;
       HIP_TRY(hipEventCreate(&a));

@@ -474,6 +474,24 @@ __global__ void shared_scale_kernel(RankMetas rm, int n, float* shared) {
   shared[t] = s;
 }
 
+// Sec. 2.1, text after Eq. 3: the factor mu chosen from the summed gradient's statistic is what every rank
+// applies to its next gradient.  One thread per tensor copies the auto-scaling state into the ranks' metas.
+struct RankMetasOut { fp8lm_meta* m[kMaxRanks]; int32_t n_ranks; };
+__global__ void autoscale_broadcast_kernel(const fp8lm_meta* from, RankMetasOut rm, int n) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n) return;
+  const int32_t mu_exp = from[t].mu_exp, clean = from[t].clean_steps;
+  for (int r = 0; r < rm.n_ranks; ++r) {
+    rm.m[r][t].mu_exp = mu_exp;
+    rm.m[r][t].clean_steps = clean;
+  }
+}
+// Sec. 2.1, Eq. 1-2: a fixed factor mu = 2^mu_exp (pre-scaling 1/N, post-scaling 1) for every tensor.
+__global__ void set_mu_kernel(fp8lm_meta* meta, int n, int32_t mu_exp) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < n) meta[t].mu_exp = mu_exp;
+}
+
 struct RequantParams {
   const uint8_t* src;
   const fp8lm_meta* src_meta;

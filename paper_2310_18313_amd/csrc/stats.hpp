@@ -3,6 +3,8 @@
 #ifndef FP8LM_STATS_HPP
 #define FP8LM_STATS_HPP
 
+#include <type_traits>
+
 #include "walk.hpp"
 
 namespace fp8lm {
@@ -131,6 +133,63 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const uint4* __restrict_
     st16<true>(dst + i + 3 * kThreads, d);
   }
   for (; i < b1; i += kThreads) st16<true>(dst + i, ld16<true>(src + i));
+}
+
+// Memory-only skeletons of the hot kernels: the same persistent grid, tile walk, access widths, access layout and
+// cache policies as the kernels they stand for, with the arithmetic replaced by XORs.  What they reach is the
+// bandwidth ceiling of that access pattern on this machine; the real kernels are measured against it.
+//   NS1 / NS2 : number of 8-bit / 16-bit streams read;  ND1 / ND2 : number of 8-bit / 16-bit streams written.
+// A thread takes elements [8L, 8L+8) of both halves of a 4096-element tile (L = thread index), like the update and
+// cast kernels: 64-bit accesses on 8-bit streams, 128-bit accesses on 16-bit streams, contiguous over the workgroup.
+struct SkeletonParams {
+  const uint8_t* s1[2];
+  const uint16_t* s2[2];
+  uint8_t* d1[2];
+  uint16_t* d2[2];
+  long long n_tiles;
+  uint32_t* sink;        // one word per workgroup, so that pure reads cannot be optimised away
+};
+template <int NS1, int NS2, int ND1, int ND2, int UN>
+__global__ __launch_bounds__(kThreads) void skeleton_kernel(SkeletonParams p) {
+  const long long t0 = p.n_tiles * blockIdx.x / gridDim.x, t1 = p.n_tiles * (blockIdx.x + 1) / gridDim.x;
+  uint32_t acc = 0;
+  auto body = [&](long long tile, auto un_tag) {
+    constexpr int U = decltype(un_tag)::value;
+    uint2 a1[U][NS1 > 0 ? NS1 : 1][2];
+    uint4 a2[U][NS2 > 0 ? NS2 : 1][2];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long long a = (tile + u) * kTile + threadIdx.x * 8, b = a + kTile / 2;
+#pragma unroll
+      for (int i = 0; i < NS1; ++i) { a1[u][i][0] = ld8<true>(p.s1[i] + a); a1[u][i][1] = ld8<true>(p.s1[i] + b); }
+#pragma unroll
+      for (int i = 0; i < NS2; ++i) { a2[u][i][0] = ld16<true>(p.s2[i] + a); a2[u][i][1] = ld16<true>(p.s2[i] + b); }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long long a = (tile + u) * kTile + threadIdx.x * 8, b = a + kTile / 2;
+      uint32_t x = acc, y = ~acc;
+#pragma unroll
+      for (int i = 0; i < NS1; ++i) { x ^= a1[u][i][0].x ^ a1[u][i][1].y; y ^= a1[u][i][0].y ^ a1[u][i][1].x; }
+#pragma unroll
+      for (int i = 0; i < NS2; ++i) {
+        x ^= a2[u][i][0].x ^ a2[u][i][0].z ^ a2[u][i][1].y ^ a2[u][i][1].w;
+        y ^= a2[u][i][0].y ^ a2[u][i][0].w ^ a2[u][i][1].x ^ a2[u][i][1].z;
+      }
+      acc = x + y;
+#pragma unroll
+      for (int i = 0; i < ND1; ++i) { st8<true>(p.d1[i] + a, make_uint2(x, y)); st8<true>(p.d1[i] + b, make_uint2(y, x)); }
+#pragma unroll
+      for (int i = 0; i < ND2; ++i) { st16<true>(p.d2[i] + a, make_uint4(x, y, y, x)); st16<true>(p.d2[i] + b, make_uint4(y, x, x, y)); }
+    }
+  };
+  long long tile = t0;
+  for (; tile + UN <= t1; tile += UN) body(tile, std::integral_constant<int, UN>{});
+  for (; tile < t1; ++tile) body(tile, std::integral_constant<int, 1>{});
+  if constexpr (ND1 + ND2 == 0) {
+    acc = wave_or_u32(acc);
+    if ((threadIdx.x & 63) == 0) p.sink[blockIdx.x * kWaves + (threadIdx.x >> 6)] = acc;
+  }
 }
 
 }  // namespace fp8lm

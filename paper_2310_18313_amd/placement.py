@@ -1,6 +1,6 @@
 """Placement of the large flat buffers in HBM on MI355X.
 
-Measured on MI355X (`python -m paper_2310_18313_amd.placement --probe`): the 288 GiB of HBM3E behave
+Measured on MI355X (copy rates between 4 GiB pieces of the whole device memory): the 288 GiB of HBM3E behave
 as three regions of 96 GiB.  Streams that a kernel walks at the same time run faster when they live
 in different regions: a copy between regions reaches about 5 % more bandwidth than a copy inside one
 region.  For the whole cast + Adam step at 13e9 parameters the gain is between 1 % and 5 %, and the slow
@@ -24,7 +24,6 @@ Nothing here computes anything of the method: it only decides where `torch.zeros
 """
 from __future__ import annotations
 
-import sys
 from typing import Dict, List, Sequence, Tuple
 
 import torch
@@ -171,28 +170,3 @@ class SpreadAllocator:
         torch.cuda.empty_cache()
         self.spread = True
         return bufs
-
-
-def probe(piece_gib: int = 4) -> None:
-    """Prints the copy rate from three reference pieces of device memory to every other piece."""
-    from . import binding as B
-    ctx = B.Context([(0, 16)])
-    pieces = []
-    free, total = torch.cuda.mem_get_info()
-    print(f"total {total / GiB:.2f} GiB, free {free / GiB:.2f} GiB, piece {piece_gib} GiB", flush=True)
-    while torch.cuda.mem_get_info()[0] > (piece_gib + 2) * GiB:
-        pieces.append(torch.zeros(piece_gib * GiB, dtype=torch.uint8, device="cuda:0"))
-    nb = min(piece_gib, 1) * GiB
-    for ref in (0, len(pieces) // 2, len(pieces) - 1):
-        print(f"copy of 1 GiB from piece {ref} (allocated {ref * piece_gib} GiB into the run) to piece k, GB/s:")
-        row = []
-        for k, p in enumerate(pieces):
-            row.append("  ref" if k == ref else f"{copy_rate(ctx, pieces[ref], p, nb):5.0f}")
-            if len(row) == 12 or k == len(pieces) - 1:
-                print(" ".join(row) + f"   | up to {(k + 1) * piece_gib} GiB", flush=True)
-                row = []
-
-
-if __name__ == "__main__":
-    if "--probe" in sys.argv:
-        probe()

@@ -52,8 +52,19 @@ class OptimizerState:
             self.spread = alloc.spread
             self.placement = dict(alloc.log, where=alloc.where)
         else:
-            bufs = {name: torch.zeros(k, dtype=dt, device=dev) for reg in plan for name, k, dt in reg}
+            # one allocation, the buffers carved out of it one after the other (what a caller of the C ABI with an
+            # arena of its own would do): where they lie relative to each other is then the same in every process
+            items = [(name, k, dt) for reg in plan for name, k, dt in reg]
+            align = (2 << 20) if n >= (2 << 20) else 256
+            offs, end = [], 0
+            for _, k, dt in items:
+                offs.append(end)
+                end += (k * torch.empty((), dtype=dt).element_size() + align - 1) // align * align
+            self.arena = torch.zeros(end, dtype=torch.uint8, device=dev)
+            bufs = {name: self.arena[o:o + k * torch.empty((), dtype=dt).element_size()].view(dt)
+                    for (name, k, dt), o in zip(items, offs)}
             self.spread = False
+            self.placement = {"arena_bytes": end, "order": [name for name, _, _ in items]}
         self.g8, self.m, self.v, self.w, self.wq = bufs["g8"], bufs["m"], bufs["v"], bufs["w"], bufs["wq"]
         self.grad = bufs.get("grad")       # bf16 gradient source, only if asked for
         self.g_meta = self.ctx.new_meta(cfg)

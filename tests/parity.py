@@ -4,9 +4,13 @@ Before a step the inputs of the sampled tensors are copied from the GPU to the h
 runs through the C ABI; the oracle runs the same step on the host copies; the outputs are compared
 element by element.  Bars: FP8 gradient codes, amax, scales, counters and auto-scaling state are
 bit-exact; the second moment is bit-exact; the first moment may differ by one E4M3 code on at most
-1e-4 of the elements (it is bit-exact in practice); master weights within one FP16 ulp and the FP8
-weight copy within one code on at most 1e-4 of the elements when the hardware sqrt/reciprocal are
-used, bit-exact with correctly rounded sqrt and divide.
+1e-4 of the elements (it is bit-exact in practice); master weights and the weight copy are bit-exact
+with correctly rounded sqrt and divide (exact = 1, the default and the benchmarked path).
+
+exact = 0 (hardware sqrt / reciprocal) is OUTSIDE the bar of one FP16 ulp on the master weights, by
+design: where w * decay and lr * update nearly cancel no approximation of the update can meet it.  What
+is checked for it is the looser contract the header documents (`fast_math_contract` below), and every
+test that runs it says so in its log line.
 """
 from __future__ import annotations
 
@@ -72,6 +76,21 @@ class Snapshot:
         self.w = _pad(_host_bits(st.w, off, n))
         self.metas = {k: B.meta_to_numpy(getattr(st, k), len(st.tensors))[t:t + 1].copy()
                       for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta")}
+
+
+def fast_math_contract(tag, s, hp, gw, w, wm, nan_w, dw, n):
+    """exact = 0 only.  LOOSER THAN THE 1-ULP BAR BY DESIGN: the update term carries a few fp32 ulps of error
+    (hardware sqrt and reciprocal, 1 ulp each), so a new weight is within one FP16 ulp at the magnitude of the
+    larger of its two operands (payload units: the old payload, or lr * scale when the update dominates), not of
+    the result, and up to 1e-3 of the elements may be off by more than one ulp of the result."""
+    old = np.abs(s.w[:s.n].view(np.float16).astype(np.float64))[~nan_w]
+    new = np.abs(w[:s.n].view(np.float16).astype(np.float64))[~nan_w]
+    big = np.maximum(np.maximum(old, new), float(hp.lr) * float(wm[0]["scale"]) * 16)
+    err = np.abs(gw.view(np.float16).astype(np.float64) - w[:s.n].view(np.float16).astype(np.float64))[~nan_w]
+    assert np.all(err <= np.maximum(big * 2.0 ** -10, 2.0 ** -24)), \
+        f"{tag}: [exact=0, looser contract] master weight off by more than one FP16 ulp of its operands"
+    assert np.count_nonzero(dw > 1) <= 1e-3 * n, \
+        f"{tag}: [exact=0, looser contract] too many master weights off by more than one ulp"
 
 
 def meta_equal(a, b, fields):
@@ -141,15 +160,7 @@ def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool
         if hp.exact:
             assert dw.max(initial=0) == 0, f"{tag}: master weights differ with exact sqrt/divide"
         else:
-            # hardware sqrt/reciprocal: the update term carries a few fp32 ulps of error, so the new
-            # weight is within one FP16 ulp at the magnitude of the larger of old weight and update
-            # (payload units: the old payload, or lr * scale when the update dominates)
-            old = np.abs(s.w[:s.n].view(np.float16).astype(np.float64))[~nan_w]
-            new = np.abs(w[:s.n].view(np.float16).astype(np.float64))[~nan_w]
-            big = np.maximum(np.maximum(old, new), float(hp.lr) * float(wm[0]["scale"]) * 16)
-            err = np.abs(gw.view(np.float16).astype(np.float64) - w[:s.n].view(np.float16).astype(np.float64))[~nan_w]
-            assert np.all(err <= np.maximum(big * 2.0 ** -10, 2.0 ** -24)), f"{tag}: master weight off by more than one FP16 ulp of its operands"
-            assert np.count_nonzero(dw > 1) <= 1e-3 * n, f"{tag}: too many master weights off by more than one ulp"
+            fast_math_contract(tag, s, hp, gw, w, wm, nan_w, dw, n)
         out["w_diff"] += int(np.count_nonzero(dw))
         # weight copy
         if hp.wcopy == B.WCOPY_E4M3:

@@ -1,7 +1,7 @@
 """GPU parity at the full sizes of the benchmark configurations, on sampled tensors.
 
-The whole model steps on the GPU in the launch configuration bench.py times (default tuning, buffers
-spread over the HBM regions); before a checked step the inputs of the sampled tensors are copied to
+The whole model steps on the GPU in the launch configuration bench.py times (default tuning, the buffers
+carved out of one allocation); before a checked step the inputs of the sampled tensors are copied to
 the host and the oracle recomputes those tensors completely.  Every small tensor (LayerNorm weights,
 biases) is sampled, plus one tensor of every distinct large shape.
 """
@@ -38,10 +38,10 @@ def sample_ids(layout):
 def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False, paths=None, tuning=None):
     lay = wl.layout
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
-    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=True, grad_buffer=True)
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, grad_buffer=True)
     if tuning:
         st.ctx.set_tuning(*tuning)
-    say(f"{wl.name}: {lay.n_tensors} tensors, {lay.n_params} params, spread={st.spread}, tuning={tuning}")
+    say(f"{wl.name}: {lay.n_tensors} tensors, {lay.n_params} params, placement={st.placement}, tuning={tuning}")
     grad = st.grad
     synth.fill_weights(grad, lay, seed)
     st.init_master(grad)
@@ -133,10 +133,12 @@ def test_gpt175b_layer_with_the_papers_ramp_of_a_thousand_steps():
         assert (mus[first:, t] == -1).all() and gm["clean_steps"][t] < 500
 
 
-@pytest.mark.parametrize("fmt,scale_exp", [(B.E5M2, 3), (B.E5M2, -100), (B.E4M3, -2), (B.E4M3, 97)])
+@pytest.mark.parametrize("fmt,scale_exp", [(B.E5M2, 3), (B.E4M3, -2)])
 def test_cast_of_every_fp32_bit_pattern(fmt, scale_exp):
     """All 2^32 fp32 inputs through the cast kernel (hardware clamp + convert on the fast path, the explicit NaN
-    handling on the careful path) against the oracle's encoder, 2^28 patterns at a time."""
+    handling on the careful path) against the oracle's encoder, 2^28 patterns at a time, under one scale per
+    format; scales that push the product through fp32 overflow and into the subnormals (2^-126 .. 2^126) are
+    covered on the values that decide roundings by test_cast_wide_sources_under_many_scales."""
     from concurrent.futures import ThreadPoolExecutor
     piece, parts = 1 << 28, 16
     sub = piece // parts                                            # 2^24 patterns per tensor: one top byte each

@@ -167,7 +167,8 @@ def run_lockstep(wl, seed, steps, ids=None, grad_fmt=B.E5M2, wcopy=B.WCOPY_E4M3,
         hp = B.adam_hparams(lr or wl.lr, step, v_scaled=v_scaled, wcopy=wcopy, stats=stats, exact=exact)
         checked = check_steps is None or step in check_steps
         snaps = [P.Snapshot(st, grad, t) for t in ids] if checked else []
-        say(f"{wl.name} seed={seed} step={step} fmt={grad_fmt} wcopy={wcopy} v_scaled={v_scaled} stats={stats} exact={exact} checked={checked}")
+        say(f"{wl.name} seed={seed} step={step} fmt={grad_fmt} wcopy={wcopy} v_scaled={v_scaled} stats={stats} exact={exact} checked={checked}"
+            + ("" if exact else "  [exact=0: checked against the documented looser contract, outside the 1-ulp bar by design]"))
         st.step(grad, hp)
         torch.cuda.synchronize()
         if checked:
@@ -561,12 +562,88 @@ def test_sum_of_many_ranks(fmt, n_ranks):
         ctx.sum_fp8(d_rq + d_rq[:129 - n_ranks] if n_ranks == 128 else [d_rq[0]] * 129, fmt, shared, out, out_meta, cfg)
 
 
+@pytest.mark.parametrize("n_ranks", [3, 4])
+def test_summed_gradient_feeds_the_adam_step(n_ranks):
+    """The data-parallel chain end to end on one GPU (Sec. 2.1 Eq. 4-6, then Sec. 2.2): every rank casts its own
+    gradient, shared scale, re-quantisation, FP8 sum with scale N * s_g (no power of two for N = 3, so the Adam
+    kernels dequantise with a rounded reciprocal), Adam step on the sum with the sum's metadata, and the sum's
+    auto-scaling state handed back to the ranks for the next step.  Three steps, every byte against the same chain
+    on the oracle."""
+    fmt = B.E5M2
+    wl = synth.Workload("join", synth.Layout(["a", "b", "c", "d", "e", "f"], [70001, 1, 4096, 333, 0, 16385]), lr=1e-3,
+                        sigma=None, ramp_steps=4)
+    lay = wl.layout
+    nt, size = lay.n_tensors, max(lay.total, 16)
+    st, w0 = P.make_state(wl, 17, fmt, ramp_steps=4)
+    cfg, ocfg, ctx = st.cfg, P.oracle_cfg(st.cfg), st.ctx
+    tens = O.tensors_array(lay.tensors())
+    # the oracle's own state
+    o = dict(m=np.zeros(size, np.uint8), v=np.zeros(size, np.uint16), w=np.zeros(size, np.uint16), wq=np.zeros(size, np.uint8),
+             g8=np.zeros(size, np.uint8))
+    om = {k: O.new_meta(nt, ocfg) for k in ("sum", "m", "v", "w", "q")}
+    O.init_master(synth.bits16(w0), tens, o["w"], om["w"])
+    o_rank_meta = [O.new_meta(nt, ocfg) for _ in range(n_ranks)]
+    d_rank_meta = [ctx.new_meta(cfg) for _ in range(n_ranks)]
+    d_sum_meta = ctx.new_meta(cfg)
+    d_pay = [torch.zeros(size, dtype=torch.uint8, device=DEV) for _ in range(n_ranks)]
+    scratch_meta = ctx.new_meta(cfg)
+    grad = torch.zeros(size, dtype=torch.bfloat16, device=DEV)
+    for step in range(1, 4):
+        hp = B.adam_hparams(wl.lr, step)
+        o_pay = []
+        ctx.autoscale_broadcast(d_sum_meta, d_rank_meta)
+        for r in range(n_ranks):
+            synth.fill_gradients(grad, wl, 170 + r, step)
+            grad *= [1.0, 0.25, 8.0, 0.5][r]
+            ctx.amax_scale(grad, fmt, d_rank_meta[r], cfg)
+            ctx.cast_fp8(grad, d_pay[r], fmt, d_rank_meta[r], cfg)
+            bits = synth.bits16(grad)
+            o_rank_meta[r]["mu_exp"], o_rank_meta[r]["clean_steps"] = om["sum"]["mu_exp"], om["sum"]["clean_steps"]
+            q = np.zeros(size, np.uint8)
+            O.amax_scale(bits, tens, fmt, o_rank_meta[r], ocfg)
+            O.cast_fp8(bits, tens, q, fmt, o_rank_meta[r], ocfg)
+            o_pay.append(q)
+        say(f"join of Eq. 4-6 and the Adam step: {n_ranks} ranks, step {step}")
+        shared = ctx.shared_scale(d_rank_meta)
+        for r in range(n_ranks):
+            ctx.requantize_fp8(d_pay[r], fmt, d_rank_meta[r], shared, d_pay[r], scratch_meta)
+        ctx.sum_fp8(d_pay, fmt, shared, st.g8, d_sum_meta, cfg)
+        if step == 1:
+            with pytest.raises(B.Fp8lmError):            # no fused cast has seen this gradient
+                ctx.adam_step_fp8(st.g8, fmt, d_sum_meta, st.m, st.m_meta, st.v, st.v_meta, st.w, st.w_meta, st.wq, st.q_meta,
+                                  B.adam_hparams(wl.lr, step, m_scale_mode=B.MSCALE_FROM_CAST))
+        ctx.adam_step_fp8(st.g8, fmt, d_sum_meta, st.m, st.m_meta, st.v, st.v_meta, st.w, st.w_meta, st.wq, st.q_meta, hp)
+        torch.cuda.synchronize()
+        o_shared = O.shared_scale(o_rank_meta, nt)
+        for r in range(n_ranks):
+            O.requantize_fp8(o_pay[r], fmt, o_rank_meta[r], o_shared, tens, o_pay[r], O.new_meta(nt, ocfg))
+        O.sum_fp8(o_pay, fmt, o_shared, tens, o["g8"], om["sum"], ocfg)
+        O.adam_step_fp8(tens, o["g8"], fmt, om["sum"], o["m"], om["m"], o["v"], om["v"], o["w"], om["w"], o["wq"], om["q"],
+                        P.oracle_hp(hp))
+        if n_ranks == 3:
+            assert not np.any(np.log2(om["sum"]["scale"][[0, 2, 3, 5]]) % 1 == 0)       # not powers of two
+        got_meta = {k: B.meta_to_numpy(t, nt) for k, t in (("sum", d_sum_meta), ("m", st.m_meta), ("v", st.v_meta),
+                                                           ("w", st.w_meta), ("q", st.q_meta))}
+        for t, (off, n) in enumerate(lay.tensors()):
+            for name, dev_buf in (("g8", st.g8), ("m", st.m), ("v", st.v), ("w", st.w), ("wq", st.wq)):
+                assert np.array_equal(P._host_bits(dev_buf, off, n), o[name][off:off + n]), (step, t, name)
+            if n:
+                bad = P.meta_equal(got_meta["sum"][t], om["sum"][t], P.ALL_FIELDS)
+                assert not bad, (step, t, bad, got_meta["sum"][t], om["sum"][t])
+                for k in ("m", "v", "w", "q"):
+                    bad = P.meta_equal(got_meta[k][t], om[k][t], ["scale", "inv_scale", "amax", "amax_deq", "flags"])
+                    assert not bad, (step, t, k, bad, got_meta[k][t], om[k][t])
+    # the hand-over moved the state of the sum into every rank, and only that
+    rm = B.meta_to_numpy(d_rank_meta[0], nt)
+    assert np.array_equal(rm["scale"], o_rank_meta[0]["scale"]) and np.array_equal(rm["amax_hist"], o_rank_meta[0]["amax_hist"])
+
+
 # ---- storage formats of the precision-decoupling study (Sec. 2.2; Sec. 3.3) ----------------------------
-@pytest.mark.parametrize("master_fmt", [B.STATE_F16, B.STATE_BF16, B.STATE_E4M3, B.STATE_F32])
-@pytest.mark.parametrize("v_fmt", [B.STATE_F16, B.STATE_E4M3])
+# every pair but the default one (scaled FP16 for both), which all the other tests cover
+@pytest.mark.parametrize("master_fmt,v_fmt", [(mf, vf) for vf in (B.STATE_F16, B.STATE_E4M3)
+                                              for mf in (B.STATE_F16, B.STATE_BF16, B.STATE_E4M3, B.STATE_F32)
+                                              if (mf, vf) != (B.STATE_F16, B.STATE_F16)])
 def test_master_weight_and_second_moment_formats(master_fmt, v_fmt):
-    if master_fmt == B.STATE_F16 and v_fmt == B.STATE_F16:
-        pytest.skip("the default pair is covered everywhere else")
     for wl, grad_fmt in ((synth.workload("tiny"), B.E5M2),
                          (synth.Workload("mid", synth.gpt_layout(256, 2, 1024, 1000), lr=1e-3, sigma=None), B.E4M3)):
         st, w0 = P.make_state(wl, 13, grad_fmt, master_fmt=master_fmt, v_fmt=v_fmt)
