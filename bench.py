@@ -133,6 +133,9 @@ def main() -> int:
                     help="chunks per workgroup below which tensors are finished by a second launch (0: never)")
     ap.add_argument("--exact", type=int, default=1)
     ap.add_argument("--stats", type=int, default=0)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run the library's plain 128-bit copy kernel over 4 GiB (m -> FP8 gradient buffer) three times: "
+                         "a kernel of known size that profiler counters are scaled by")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the memory-only skeletons of the four kernels that are timed on the same buffers after the step")
     ap.add_argument("--path", choices=["jit", "fused", "single"], default="jit",
@@ -275,6 +278,16 @@ def main() -> int:
         torch.cuda.synchronize()
         out["graph_replay_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
     want_ceilings = not args.no_ceilings and lay.total >= (1 << 20)
+    if args.calibration_copy:
+        nbytes = min(lay.total // 16 * 16, 1 << 32)
+        st.ctx.set_timing(True)
+        st.ctx.get_timing()
+        for _ in range(3):
+            st.ctx.copy_bytes(st.m, st.g8, nbytes)
+        n, ms = st.ctx.get_timing()["copy"]
+        st.ctx.set_timing(False)
+        out["calibration_copy"] = {"bytes_read": nbytes, "bytes_written": nbytes, "avg_ms": round(ms / n, 4),
+                                   "GBps": round(2 * nbytes / (ms / n * 1e-3) / 1e9, 1)}
     if args.allreduce_steps:
         N = args.allreduce_steps
         ranks = [st.g8] + [st.g8.clone() for _ in range(N - 1)]

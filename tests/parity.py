@@ -288,12 +288,14 @@ class FreeRunningOracle:
     def assert_equal_to(self, st, what: str) -> None:
         n_tensors = self.layout.n_tensors
         gpu_meta = {k: B.meta_to_numpy(getattr(st, k), n_tensors) for k in ("g_meta", "m_meta", "v_meta", "w_meta", "q_meta")}
+        tensors = self.layout.tensors()
+        host = {name: _host_bits(getattr(st, name), 0, getattr(st, name).numel())      # one copy per buffer
+                for name in ("g8", "m", "v", "w", "wq")}
         for ids, _, M in self.jobs:
             for j, t in enumerate(ids):
-                off, n = self.layout.tensors()[t]
+                off, n = tensors[t]
                 for name, ref in (("g8", self.g8), ("m", self.m), ("v", self.v), ("w", self.w), ("wq", self.wq)):
-                    got = _host_bits(getattr(st, name), off, n)
-                    assert np.array_equal(got, ref[off:off + n]), f"{what}: {name} of tensor {t} differs"
+                    assert np.array_equal(host[name][off:off + n], ref[off:off + n]), f"{what}: {name} of tensor {t} differs"
                 if n:
                     for k in gpu_meta:
                         fields = ALL_FIELDS if k == "g_meta" else ["scale", "inv_scale", "amax", "amax_deq", "flags"]

@@ -88,7 +88,8 @@ def test_gpt7b_five_steps_with_amax_history():
     # steps 1-2 on the two-pass path, then the one-GPU fused cast, then the single-pass path (delayed gradient
     # scale + predicted moment scale): the three paths bench.py times, at full size and default tuning
     paths = {3: (B.MSCALE_FROM_CAST, False), 4: (B.MSCALE_PREDICTED, True), 5: (B.MSCALE_FROM_CAST, True)}
-    run(wl, seed=2, steps=5, small_steps={1, 2, 3, 4, 5}, big_steps={1, 3, 4, 5}, paths=paths)
+    # every small tensor at every step; the five large shapes at the first step of each of the three paths
+    run(wl, seed=2, steps=5, small_steps={1, 2, 3, 4, 5}, big_steps={1, 3, 4}, paths=paths)
 
 
 def test_gpt175b_layer_heavy_tails_hundred_steps():
@@ -98,7 +99,7 @@ def test_gpt175b_layer_heavy_tails_hundred_steps():
     checked = {1, 2, 3, 10, 11, 20, 21, 22, 23, 24, 50, 99, 100}
     # this one combines the workgroups' statistics through tickets in the same launch (third tuning entry 0);
     # the other two use the default, a second launch
-    st, tot, mus = run(wl, seed=5, steps=100, small_steps=checked, big_steps={1, 24, 100}, big_ids=[proj],
+    st, tot, mus = run(wl, seed=5, steps=100, small_steps=checked, big_steps={1, 100}, big_ids=[proj],
                        track_mu=True, tuning=(16384, 16, 0))
     mus = np.array(mus)                            # [step, tensor]
     # Large matrices: the amax is set by a rare outlier, so even mu = 2 clips far fewer than 0.001 % of

@@ -201,7 +201,7 @@ def test_config1_flat_1m():
 
 def test_config2_gpt125m_ten_steps():
     wl = synth.workload("gpt125m")
-    _, tot = run_lockstep(wl, seed=1, steps=10, check_steps={1, 2, 5, 10})
+    _, tot = run_lockstep(wl, seed=1, steps=10, check_steps={1, 10})      # the free-running test below compares every byte after 10
     assert tot["m_diff"] == 0
     assert tot["w_diff"] <= 0.01 * tot["elements"]
 
