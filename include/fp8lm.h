@@ -348,6 +348,39 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* ctx,
                                  const fp8lm_adam_hparams* hp /*host*/, void* stream);
 
 /*
+ * fp8lm_adam_step_fp8 for callers that cannot allocate device memory and therefore cannot hold a context:
+ * code under HIP graph capture that must not call hipMalloc, tight serving or training loops, harnesses that
+ * forbid allocation.  Same arithmetic, same kernels, same results, bit for bit; what a context keeps in
+ * hipMalloc'd memory (tensor and chunk tables, the per-tensor scales that the first pass hands to the second,
+ * the per-workgroup reduction records) lives in a fixed array inside the library's device image instead (about
+ * 5.4 MiB, held by every GPU the library runs on until the process ends).  Every call rebuilds the tables in
+ * that array from `tensors` with small kernels on `stream` (arguments travel as kernel arguments: no copy from
+ * host memory), then runs the two passes.  The call itself calls no allocator of any kind.
+ *   device       : GPU that owns all buffers; tensors, tensor_flags: host arrays of n entries, read during the
+ *                  call (tensor_flags may be NULL: all 0; same meaning as fp8lm_set_tensor_flags).
+ *   Limits       : n <= FP8LM_STATIC_MAX_TENSORS and at most FP8LM_STATIC_MAX_CHUNKS chunks of 16384 elements
+ *                  (a tensor of k elements takes ceil(k / 16384) of them; about 1.7e10 elements in all):
+ *                  FP8LM_ERR_TOO_LARGE beyond either, nothing enqueued.
+ *   Not offered  : hp->m_scale_mode = FP8LM_MSCALE_FROM_CAST (needs the context of the fused cast):
+ *                  INVALID_ARGUMENT.
+ *   Concurrency  : all calls on one GPU share the one array and each leaves its tables and scales in it.  Calls
+ *                  on the same stream are ordered and safe; calls that overlap on one GPU (two streams, two
+ *                  threads) race and give wrong results.  Nothing in the array has to start at zero: a call
+ *                  overwrites every entry before it reads it.
+ * Errors otherwise as fp8lm_create (tensor list) and fp8lm_adam_step_fp8 (everything else).
+ */
+#define FP8LM_STATIC_MAX_TENSORS 4096
+#define FP8LM_STATIC_MAX_CHUNKS (1 << 20)
+fp8lm_status fp8lm_adam_step_fp8_static(int device, const fp8lm_tensor* tensors /*host*/, int32_t n,
+                                        const uint32_t* tensor_flags /*host[n] or NULL*/,
+                                        const uint8_t* grad /*device*/, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta /*device*/,
+                                        uint8_t* m /*device, in place*/, fp8lm_meta* m_meta /*device*/,
+                                        void* v /*device, in place*/, fp8lm_meta* v_meta /*device*/,
+                                        void* w /*device, in place*/, fp8lm_meta* w_meta /*device*/,
+                                        void* wcopy /*device, write only*/, fp8lm_meta* wcopy_meta /*device*/,
+                                        const fp8lm_adam_hparams* hp /*host*/, void* stream);
+
+/*
  * Quantisation error of an FP8 gradient against a high-precision reference: the three quantities of
  * the communication ablation (Sec. 3.3, figure comparing pre-, post- and auto-scaling for the FP8
  * gradient all-reduce).  With r the reference and x = payload / scale the value a scaling tensor

@@ -35,7 +35,7 @@ KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy
 EXPORTS = [
     "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_set_tensor_flags", "fp8lm_meta_init", "fp8lm_amax_scale",
     "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_cast_fp8_for_adam", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
-    "fp8lm_quant_error_stats", "fp8lm_autoscale_broadcast", "fp8lm_set_mu", "fp8lm_memory_skeleton",
+    "fp8lm_quant_error_stats", "fp8lm_autoscale_broadcast", "fp8lm_set_mu", "fp8lm_memory_skeleton", "fp8lm_adam_step_fp8_static",
     "fp8lm_init_master", "fp8lm_init_master_as", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
@@ -131,6 +131,7 @@ def lib() -> C.CDLL:
         L.fp8lm_set_mu.argtypes = [vp, vp, i32, vp]
         L.fp8lm_memory_skeleton.argtypes = [vp, i32, vp, i64, vp]
         L.fp8lm_adam_step_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.fp8lm_adam_step_fp8_static.argtypes = [C.c_int, vp, i32, vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fp8lm_copy_bytes.argtypes = [vp, vp, vp, i64, vp]
         L.fp8lm_greedy_partition.argtypes = [vp, i32, i32, vp, vp]
         L.fp8lm_set_timing.argtypes = [vp, i32]
@@ -352,6 +353,34 @@ class Context:
         ms = (C.c_double * K_COUNT)()
         _check(lib().fp8lm_get_timing(self._h, C.cast(n, C.c_void_p), C.cast(ms, C.c_void_p)), "fp8lm_get_timing")
         return {KERNEL_NAMES[k]: (int(n[k]), float(ms[k])) for k in range(K_COUNT)}
+
+
+STATIC_MAX_TENSORS, STATIC_MAX_CHUNKS, STATIC_CHUNK_ELEMS = 4096, 1 << 20, 16384
+
+
+def adam_step_fp8_static(tensors: Sequence[Tuple[int, int]], grad, grad_fmt, grad_meta, m, m_meta, v, v_meta, w, w_meta,
+                         wcopy, wcopy_meta, hp: AdamHparams, tensor_flags=None, device: int = 0, stream=None) -> None:
+    """fp8lm_adam_step_fp8 without a context, for callers that cannot allocate device memory (see fp8lm.h): the
+    tensor list travels with every call."""
+    n = len(tensors)
+    arr = (Tensor * max(1, n))()
+    for i, (off, k) in enumerate(tensors):
+        arr[i].offset, arr[i].numel = int(off), int(k)
+    need = max([int(o) + int(k) for o, k in tensors if k > 0], default=0)
+    for t in (grad, m, v, w, wcopy):
+        if t.numel() < need:
+            raise ValueError(f"flat buffer of {t.numel()} elements is shorter than the tensor list needs ({need})")
+    for t in (grad_meta, m_meta, v_meta, w_meta, wcopy_meta):
+        if t.numel() * t.element_size() < n * C.sizeof(Meta):
+            raise ValueError("meta array is shorter than the tensor list")
+    flags = None
+    if tensor_flags is not None:
+        flags = np.ascontiguousarray(tensor_flags, dtype=np.uint32)
+        assert len(flags) == n
+    _check(lib().fp8lm_adam_step_fp8_static(device, C.cast(arr, C.c_void_p), n, flags.ctypes.data if flags is not None else None,
+                                            _ptr(grad), grad_fmt, _ptr(grad_meta), _ptr(m), _ptr(m_meta), _ptr(v),
+                                            _ptr(v_meta), _ptr(w), _ptr(w_meta), _ptr(wcopy), _ptr(wcopy_meta),
+                                            C.addressof(hp), _stream(stream)), "fp8lm_adam_step_fp8_static")
 
 
 def greedy_partition(sizes, n_gpus: int):

@@ -24,6 +24,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <numeric>
 #include <queue>
 #include <string>
@@ -37,6 +38,46 @@
 #include "adam.hpp"
 #include "stats.hpp"
 
+
+// ====================================================================================================
+// Fixed device array for fp8lm_adam_step_fp8_static (callers that cannot allocate)
+// ====================================================================================================
+namespace fp8lm {
+
+// Everything a context keeps in hipMalloc'd memory, at fixed maximum sizes.
+constexpr int kStaticMaxGrid = 4096;                      // workgroups of a launch: bounds the reduction records
+constexpr int kStaticChunkElems = 16384;
+struct StaticArena {
+  TensorDesc desc[FP8LM_STATIC_MAX_TENSORS];              // 128 KiB
+  Scratch scratch[FP8LM_STATIC_MAX_TENSORS];              // 288 KiB
+  Partial partials[kStaticMaxGrid + FP8LM_STATIC_MAX_TENSORS + 1];   // 1 MiB
+  int32_t chunk_tensor[FP8LM_STATIC_MAX_CHUNKS];          // 4 MiB
+};
+
+// A batch of tensor descriptors travels as kernel arguments: no copy from host memory is enqueued.
+constexpr int kDescBatch = 96;                            // 3 KiB of arguments per launch
+struct DescBatch {
+  TensorDesc d[kDescBatch];
+  int32_t first, count;
+};
+__global__ void static_desc_kernel(DescBatch b, TensorDesc* desc) {
+  const int i = threadIdx.x;
+  if (i < b.count) desc[b.first + i] = b.d[i];
+}
+// Workgroup t (and t + grid, ...) writes tensor t's id into its chunks; also returns the tickets to zero.
+__global__ void static_chunks_kernel(const TensorDesc* desc, int32_t* chunk_tensor, Scratch* scratch, int n) {
+  for (int t = blockIdx.x; t < n; t += gridDim.x) {
+    const TensorDesc d = desc[t];
+    for (int i = threadIdx.x; i < d.n_chunks; i += blockDim.x) chunk_tensor[d.first_chunk + i] = t;
+    if (threadIdx.x == 0) scratch[t].ticket = 0;
+  }
+}
+
+}  // namespace fp8lm
+
+// The array itself.  In host code this name is only a handle for hipGetSymbolAddress: the device address is
+// looked up once per GPU (static_arena_of) and that pointer is what kernels and launches are given.
+static __device__ __align__(256) unsigned char scratch[sizeof(fp8lm::StaticArena)];
 
 // ====================================================================================================
 // Host side: context, validation, launches
@@ -565,11 +606,11 @@ fp8lm_status fp8lm_init_master(fp8lm_ctx* c, const void* w_bf16, uint16_t* w_f16
   return fp8lm_init_master_as(c, w_bf16, w_f16, w_meta, FP8LM_STATE_F16, stream);
 }
 
-fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta,
-                                 uint8_t* m, fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta, void* w,
-                                 fp8lm_meta* w_meta, void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp,
-                                 void* stream) {
-  if (!c || !hp || (grad_fmt != FP8LM_E4M3 && grad_fmt != FP8LM_E5M2)) return FP8LM_ERR_INVALID_ARGUMENT;
+// Validation of everything but the context (shared by the two Adam entry points).
+static fp8lm_status adam_args_ok(const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta, uint8_t* m,
+                                 fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta, void* w, fp8lm_meta* w_meta, void* wcopy,
+                                 fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp, bool have_chunks) {
+  if (!hp || (grad_fmt != FP8LM_E4M3 && grad_fmt != FP8LM_E5M2)) return FP8LM_ERR_INVALID_ARGUMENT;
   if (hp->wcopy != FP8LM_WCOPY_E4M3 && hp->wcopy != FP8LM_WCOPY_BF16) return FP8LM_ERR_INVALID_ARGUMENT;
   if (hp->m_scale_mode < 0 || hp->m_scale_mode > 2) return FP8LM_ERR_INVALID_ARGUMENT;
   if (hp->master_fmt < 0 || hp->master_fmt > 3 || (hp->v_fmt != FP8LM_STATE_F16 && hp->v_fmt != FP8LM_STATE_E4M3))
@@ -580,11 +621,36 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
       !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f) || !(hp->eps >= 0x1p-36f && hp->eps < INFINITY) ||
       !(hp->weight_decay >= 0.0f && hp->weight_decay <= 1024.0f) || hp->step < 1)
     return FP8LM_ERR_INVALID_ARGUMENT;
-  if (c->n_chunks == 0) return FP8LM_OK;
+  if (!have_chunks) return FP8LM_OK;
   if (!grad || !grad_meta || !m || !m_meta || !v || !v_meta || !w || !w_meta || !wcopy || !wcopy_meta)
     return FP8LM_ERR_INVALID_ARGUMENT;
   if (!aligned16(grad) || !aligned16(m) || !aligned16(v) || !aligned16(w) || !aligned16(wcopy)) return FP8LM_ERR_MISALIGNED;
+  return FP8LM_OK;
+}
+
+static fp8lm_status adam_launch(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta,
+                                uint8_t* m, fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta, void* w, fp8lm_meta* w_meta,
+                                void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp, hipStream_t s);
+
+fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta,
+                                 uint8_t* m, fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta, void* w,
+                                 fp8lm_meta* w_meta, void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp,
+                                 void* stream) {
+  if (!c) return FP8LM_ERR_INVALID_ARGUMENT;
+  const fp8lm_status ok = adam_args_ok(grad, grad_fmt, grad_meta, m, m_meta, v, v_meta, w, w_meta, wcopy, wcopy_meta, hp,
+                                       c->n_chunks > 0);
+  if (ok != FP8LM_OK) return ok;
+  if (c->n_chunks == 0) return FP8LM_OK;
   DeviceGuard guard(c->device);
+  return adam_launch(c, grad, grad_fmt, grad_meta, m, m_meta, v, v_meta, w, w_meta, wcopy, wcopy_meta, hp,
+                     (hipStream_t)stream);
+}
+
+// The launches of one Adam step on the tables `c` points to (a context's own, or the fixed device array).
+static fp8lm_status adam_launch(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta,
+                                uint8_t* m, fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta, void* w, fp8lm_meta* w_meta,
+                                void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp, hipStream_t s) {
+  const bool variant = hp->master_fmt != FP8LM_STATE_F16 || hp->v_fmt != FP8LM_STATE_F16;
 
   AdamParams p{};
   p.grad = grad; p.grad_meta = grad_meta; p.m = m; p.m_meta = m_meta; p.v = v; p.v_meta = v_meta;
@@ -604,7 +670,6 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
   p.w_fmax_bits = hp->master_fmt == FP8LM_STATE_F16 ? kBitsF16Max : (hp->master_fmt == FP8LM_STATE_E4M3 ? kBitsE4M3Max : 0u);
 
   const bool stats = hp->stats != 0, fast = hp->exact == 0;
-  hipStream_t s = (hipStream_t)stream;
   const Tables tb = tables_of(c);
   const bool e5 = grad_fmt == FP8LM_E5M2, q8 = hp->wcopy == FP8LM_WCOPY_E4M3;
   if (hp->m_scale_mode == FP8LM_MSCALE_FROM_CAST) {
@@ -641,6 +706,112 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
     else launch_update<kE4M3, FP8LM_WCOPY_BF16>(c, s, p, fast, stats);
   }
   return after_launch();
+}
+
+// ---- the Adam step without a context: tables, scales and reduction records in the fixed device array ----------
+namespace {
+
+constexpr int kMaxDevices = 64;
+struct StaticDevice {
+  StaticArena* arena = nullptr;      // device address of `scratch` on this GPU
+  int num_cus = 0;
+};
+std::mutex g_static_mutex;
+StaticDevice g_static_dev[kMaxDevices];
+
+// Device address of the fixed array on `device` (which must be current) and that GPU's size; looked up on the
+// first call per GPU.  Each GPU holds its own copy of the array at its own address.
+fp8lm_status static_arena_of(int device, StaticDevice* out) {
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  StaticDevice& d = g_static_dev[device];
+  if (!d.arena) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) { g_hip_error = "hipGetSymbolAddress returned a null address"; return FP8LM_ERR_HIP; }
+    int cus = 0;
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device));
+    d.num_cus = cus > 0 ? cus : 256;
+    d.arena = static_cast<StaticArena*>(ptr);
+  }
+  *out = d;
+  return FP8LM_OK;
+}
+
+}  // namespace
+
+fp8lm_status fp8lm_adam_step_fp8_static(int device, const fp8lm_tensor* tensors, int32_t n, const uint32_t* tensor_flags,
+                                        const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta, uint8_t* m,
+                                        fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta, void* w, fp8lm_meta* w_meta,
+                                        void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp, void* stream) {
+  if (n < 0 || (n > 0 && !tensors) || device < 0 || device >= kMaxDevices) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (n > FP8LM_STATIC_MAX_TENSORS) return FP8LM_ERR_TOO_LARGE;
+  // the tensor list: same rules as fp8lm_create; everything below lives on this thread's stack
+  long long total_chunks = 0;
+  {
+    std::pair<long long, long long> spans[FP8LM_STATIC_MAX_TENSORS];
+    int n_spans = 0;
+    for (int t = 0; t < n; ++t) {
+      if (tensors[t].numel < 0 || tensors[t].offset < 0) return FP8LM_ERR_INVALID_ARGUMENT;
+      if (tensors[t].offset % 16 != 0) return FP8LM_ERR_MISALIGNED;
+      if (tensor_flags && (tensor_flags[t] & ~(uint32_t)FP8LM_TENSOR_NO_WEIGHT_DECAY)) return FP8LM_ERR_INVALID_ARGUMENT;
+      if (tensors[t].numel > 0) spans[n_spans++] = {tensors[t].offset, tensors[t].offset + tensors[t].numel};
+      total_chunks += (tensors[t].numel + kStaticChunkElems - 1) / kStaticChunkElems;
+      if (total_chunks > FP8LM_STATIC_MAX_CHUNKS) return FP8LM_ERR_TOO_LARGE;
+    }
+    std::sort(spans, spans + n_spans);
+    for (int i = 1; i < n_spans; ++i)
+      if (spans[i].first < spans[i - 1].second) return FP8LM_ERR_OVERLAP;
+  }
+  const fp8lm_status ok = adam_args_ok(grad, grad_fmt, grad_meta, m, m_meta, v, v_meta, w, w_meta, wcopy, wcopy_meta, hp,
+                                       total_chunks > 0);
+  if (ok != FP8LM_OK) return ok;
+  if (hp->m_scale_mode == FP8LM_MSCALE_FROM_CAST) return FP8LM_ERR_INVALID_ARGUMENT;   // needs the fused cast's context
+  int count = 0;
+  HIP_TRY(hipGetDeviceCount(&count));
+  if (device >= count) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (total_chunks == 0) return FP8LM_OK;
+  DeviceGuard guard(device);
+  if (!guard.ok) { g_hip_error = "hipSetDevice failed"; return FP8LM_ERR_HIP; }
+  StaticDevice dev;
+  const fp8lm_status got = static_arena_of(device, &dev);
+  if (got != FP8LM_OK) return got;
+  StaticArena* A = dev.arena;
+  hipStream_t s = (hipStream_t)stream;
+
+  // 1. the tensor table, a batch of descriptors per launch, then the chunk table
+  DescBatch batch;
+  int32_t first_chunk = 0;
+  for (int t0 = 0; t0 < n; t0 += kDescBatch) {
+    batch.first = t0;
+    batch.count = std::min(kDescBatch, n - t0);
+    for (int i = 0; i < batch.count; ++i) {
+      const fp8lm_tensor& T = tensors[t0 + i];
+      const int32_t nc = (int32_t)((T.numel + kStaticChunkElems - 1) / kStaticChunkElems);
+      batch.d[i] = TensorDesc{T.offset, T.numel, first_chunk, nc, tensor_flags ? tensor_flags[t0 + i] : 0u, 0u};
+      first_chunk += nc;
+    }
+    for (int i = batch.count; i < kDescBatch; ++i) batch.d[i] = TensorDesc{0, 0, 0, 0, 0u, 0u};
+    hipLaunchKernelGGL(static_desc_kernel, dim3(1), dim3(kDescBatch), 0, s, batch, A->desc);
+  }
+  hipLaunchKernelGGL(static_chunks_kernel, dim3(std::min(n, 1024)), dim3(256), 0, s, A->desc, A->chunk_tensor, A->scratch, n);
+  fp8lm_status st = after_launch();
+  if (st != FP8LM_OK) return st;
+
+  // 2. the two passes, on a context-shaped view of the array (no vectors in it are ever filled: nothing allocates)
+  fp8lm_ctx view;
+  view.device = device;
+  view.n_tensors = n;
+  view.num_cus = dev.num_cus;
+  view.chunk_elems = kStaticChunkElems;
+  view.blocks_per_cu = std::max(1, std::min<int>(kMaxBlocksPerCu, kStaticMaxGrid / dev.num_cus));   // grid <= kStaticMaxGrid records
+  if ((long long)view.num_cus * view.blocks_per_cu > kStaticMaxGrid) return FP8LM_ERR_TOO_LARGE;
+  view.single_pass_min_chunks = 1 << 30;     // per-tensor totals in a second launch: no tickets to keep at zero
+  view.n_chunks = (int32_t)total_chunks;
+  view.d_desc = A->desc;
+  view.d_chunk_tensor = A->chunk_tensor;
+  view.d_scratch = A->scratch;
+  view.d_partials = A->partials;
+  return adam_launch(&view, grad, grad_fmt, grad_meta, m, m_meta, v, v_meta, w, w_meta, wcopy, wcopy_meta, hp, s);
 }
 
 fp8lm_status fp8lm_quant_error_stats(fp8lm_ctx* c, const void* ref, fp8lm_src ref_type, const uint8_t* q, fp8lm_fmt fmt,
