@@ -149,6 +149,8 @@ def main() -> int:
                     help="place the buffers in different HBM regions with placement.SpreadAllocator (it briefly takes all "
                          "free device memory; measurably faster for states of 0.5e9 to 10e9 parameters).  Default: one "
                          "allocation with the buffers carved out one after the other, as a caller of the C ABI would")
+    ap.add_argument("--arena-order", default="", help="comma-separated buffer names (v,grad,w,m,g8,wq) in the order they are "
+                    "carved out of the one allocation")
     ap.add_argument("--graph", action="store_true",
                     help="also record one step into a HIP graph and time its replays (small workloads are bound by "
                          "launch latency; the hyper-parameters, step number included, are baked into the graph)")
@@ -172,7 +174,7 @@ def main() -> int:
     P = lay.n_params
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
     st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=args.spread,
-                        grad_buffer=True)
+                        grad_buffer=True, arena_order=args.arena_order.split(",") if args.arena_order else None)
     if args.chunk or args.blocks_per_cu or args.single_pass_min_chunks >= 0:
         st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 16,
                           (1 << 30) if args.single_pass_min_chunks < 0 else args.single_pass_min_chunks)
@@ -317,6 +319,8 @@ def main() -> int:
         shapes = {"amax": (B.SKEL_READ16, [grad]), "cast": (B.SKEL_CAST, [grad, st.g8]),
                   "adam_amax": (B.SKEL_READ8X2, [st.g8, st.m]),
                   "adam_update": (B.SKEL_UPDATE, [st.g8, st.m, st.v, st.w, st.wq]),
+                  "update_reads_only": (B.SKEL_UPDATE_READS, [st.g8, st.m, st.v, st.w, st.wq]),
+                  "update_writes_only": (B.SKEL_UPDATE_WRITES, [st.g8, st.m, st.v, st.w, st.wq]),
                   "write16": (B.SKEL_WRITE16, [grad]), "write8": (B.SKEL_WRITE8, [st.g8])}
         ceilings = {}
         for name, (shape, bufs) in shapes.items():
@@ -335,6 +339,10 @@ def main() -> int:
                 kernels[name]["frac_of_skeleton"] = round(ceilings[name]["avg_ms"] / kernels[name]["avg_ms"], 4)
         path_ms = sum(ceilings[k]["avg_ms"] for k in ("amax", "cast", "adam_amax", "adam_update"))
         ceilings["step_of_skeletons_ms"] = round(path_ms, 3)        # the pass structure of the jit path, memory only
+        # what sharing the memory between the two directions costs the update shape: its reads alone plus its writes
+        # alone, against both in one kernel
+        ceilings["update_mixing_cost"] = round(ceilings["adam_update"]["avg_ms"] / (
+            ceilings["update_reads_only"]["avg_ms"] + ceilings["update_writes_only"]["avg_ms"]), 4)
         out["ceilings"] = ceilings
         if args.path == "jit":
             out["step_frac_of_skeletons"] = round(path_ms / ms_per_step, 4)

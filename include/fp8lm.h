@@ -431,10 +431,14 @@ fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* ctx, const void* src /*device*/, void* 
  *   CAST     bufs = {src16, dst8}               reads 2, writes 1     (fp8lm_cast_fp8 from a 16-bit source)
  *   UPDATE   bufs = {g8, m8, v16, w16, q8}      reads g, m, v, w (6), writes m, v, w in place and q (6)
  *                                               (second pass of fp8lm_adam_step_fp8, default formats)
+ *   UPDATE_READS / UPDATE_WRITES  same bufs as UPDATE: only its four read streams (6 B/element), only its four
+ *                                               write streams (6): what the two directions reach when they do not
+ *                                               share the memory with each other
  *   bufs : host array of device pointers, each covering n_elems elements; n_elems a multiple of 4096.
  */
 typedef enum { FP8LM_SKEL_READ16 = 0, FP8LM_SKEL_READ8X2 = 1, FP8LM_SKEL_WRITE16 = 2, FP8LM_SKEL_WRITE8 = 3,
-               FP8LM_SKEL_CAST = 4, FP8LM_SKEL_UPDATE = 5 } fp8lm_skeleton;
+               FP8LM_SKEL_CAST = 4, FP8LM_SKEL_UPDATE = 5, FP8LM_SKEL_UPDATE_READS = 6,
+               FP8LM_SKEL_UPDATE_WRITES = 7 } fp8lm_skeleton;
 fp8lm_status fp8lm_memory_skeleton(fp8lm_ctx* ctx, int32_t shape, void* const* bufs /*host -> device*/,
                                    int64_t n_elems, void* stream);
 

@@ -27,8 +27,9 @@ MU_SET_HALF, MU_HALVE = 0, 1
 STATE_F16, STATE_BF16, STATE_E4M3, STATE_F32 = 0, 1, 2, 3
 STATE_BYTES = {STATE_F16: 2, STATE_BF16: 2, STATE_E4M3: 1, STATE_F32: 4}
 FLAG_NONFINITE, FLAG_AMAX_ZERO, FLAG_SCALE_CLAMPED, FLAG_SATURATED = 1, 2, 4, 8
-SKEL_READ16, SKEL_READ8X2, SKEL_WRITE16, SKEL_WRITE8, SKEL_CAST, SKEL_UPDATE = range(6)
-SKEL_BYTES_PER_ELEM = {SKEL_READ16: 2, SKEL_READ8X2: 2, SKEL_WRITE16: 2, SKEL_WRITE8: 1, SKEL_CAST: 3, SKEL_UPDATE: 12}
+SKEL_READ16, SKEL_READ8X2, SKEL_WRITE16, SKEL_WRITE8, SKEL_CAST, SKEL_UPDATE, SKEL_UPDATE_READS, SKEL_UPDATE_WRITES = range(8)
+SKEL_BYTES_PER_ELEM = {SKEL_READ16: 2, SKEL_READ8X2: 2, SKEL_WRITE16: 2, SKEL_WRITE8: 1, SKEL_CAST: 3, SKEL_UPDATE: 12,
+                       SKEL_UPDATE_READS: 6, SKEL_UPDATE_WRITES: 6}
 K_AMAX, K_CAST, K_ADAM_AMAX, K_ADAM_UPDATE, K_INIT_MASTER, K_COPY, K_SCALARS, K_REQUANT, K_SUM, K_STATS, K_SKELETON, K_COUNT = range(12)
 KERNEL_NAMES = ["amax", "cast", "adam_amax", "adam_update", "init_master", "copy", "scalars", "requantize", "sum", "quant_stats", "skeleton"]
 
@@ -336,7 +337,7 @@ class Context:
         """Memory-only stand-in of one hot kernel over the first n_elems elements of `bufs` (see fp8lm.h); buffers
         that the shape writes are overwritten with meaningless data."""
         sizes = {SKEL_READ16: (2,), SKEL_READ8X2: (1, 1), SKEL_WRITE16: (2,), SKEL_WRITE8: (1,), SKEL_CAST: (2, 1),
-                 SKEL_UPDATE: (1, 1, 2, 2, 1)}[shape]
+                 SKEL_UPDATE: (1, 1, 2, 2, 1), SKEL_UPDATE_READS: (1, 1, 2, 2, 1), SKEL_UPDATE_WRITES: (1, 1, 2, 2, 1)}[shape]
         assert len(bufs) == len(sizes)
         for t, sz in zip(bufs, sizes):
             assert t.element_size() == sz and t.numel() >= n_elems

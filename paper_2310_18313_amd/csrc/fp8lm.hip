@@ -882,8 +882,8 @@ fp8lm_status fp8lm_copy_bytes(fp8lm_ctx* c, const void* src, void* dst, int64_t 
 }
 
 fp8lm_status fp8lm_memory_skeleton(fp8lm_ctx* c, int32_t shape, void* const* bufs, int64_t n_elems, void* stream) {
-  static const int n_bufs[] = {1, 2, 1, 1, 2, 5};
-  if (!c || shape < 0 || shape > FP8LM_SKEL_UPDATE || !bufs || n_elems < 0 || n_elems % kTile != 0)
+  static const int n_bufs[] = {1, 2, 1, 1, 2, 5, 5, 5};
+  if (!c || shape < 0 || shape > FP8LM_SKEL_UPDATE_WRITES || !bufs || n_elems < 0 || n_elems % kTile != 0)
     return FP8LM_ERR_INVALID_ARGUMENT;
   for (int i = 0; i < n_bufs[shape]; ++i) {
     if (!bufs[i]) return FP8LM_ERR_INVALID_ARGUMENT;
@@ -919,12 +919,14 @@ fp8lm_status fp8lm_memory_skeleton(fp8lm_ctx* c, int32_t shape, void* const* buf
       p.s2[0] = static_cast<const uint16_t*>(bufs[0]); p.d1[0] = static_cast<uint8_t*>(bufs[1]);
       hipLaunchKernelGGL((skeleton_kernel<0, 1, 1, 0, FP8LM_UN_CAST>), g, b, 0, s, p);
       break;
-    default:   // FP8LM_SKEL_UPDATE: reads g, m, v, w; writes m, v, w in place and the weight copy
+    default:   // the update shapes: reads g, m, v, w; writes m, v, w in place and the weight copy; or one half of that
       p.s1[0] = static_cast<const uint8_t*>(bufs[0]); p.s1[1] = static_cast<const uint8_t*>(bufs[1]);
       p.s2[0] = static_cast<const uint16_t*>(bufs[2]); p.s2[1] = static_cast<const uint16_t*>(bufs[3]);
       p.d1[0] = static_cast<uint8_t*>(bufs[1]); p.d1[1] = static_cast<uint8_t*>(bufs[4]);
       p.d2[0] = static_cast<uint16_t*>(bufs[2]); p.d2[1] = static_cast<uint16_t*>(bufs[3]);
-      hipLaunchKernelGGL((skeleton_kernel<2, 2, 2, 2, FP8LM_UN_UPDATE>), g, b, 0, s, p);
+      if (shape == FP8LM_SKEL_UPDATE) hipLaunchKernelGGL((skeleton_kernel<2, 2, 2, 2, FP8LM_UN_UPDATE>), g, b, 0, s, p);
+      else if (shape == FP8LM_SKEL_UPDATE_READS) hipLaunchKernelGGL((skeleton_kernel<2, 2, 0, 0, FP8LM_UN_UPDATE>), g, b, 0, s, p);
+      else hipLaunchKernelGGL((skeleton_kernel<0, 0, 2, 2, FP8LM_UN_UPDATE>), g, b, 0, s, p);
       break;
   }
   return after_launch();

@@ -351,8 +351,17 @@ struct CastOp {
         }
       }
     }
+    // called by all lanes of a wavefront together (the 128-bit form exchanges halves between neighbouring lanes)
     auto store = [&](int u, const uint4& o) {
-      if constexpr (kSplit) {
+      if constexpr (kSplit && FP8LM_CAST_STORE16) {
+        // lanes 2k and 2k+1 hold 8 codes each of both halves of the tile: the even lane takes the pair's 16 codes
+        // of the first half, the odd lane those of the second half, and each stores once with 128 bits
+        const bool odd = (threadIdx.x & 1) != 0;
+        const uint32_t g0 = (uint32_t)__shfl_xor((int)(odd ? o.x : o.z), 1, 64);
+        const uint32_t g1 = (uint32_t)__shfl_xor((int)(odd ? o.y : o.w), 1, 64);
+        const long long at = pos0 + u * kTile + (threadIdx.x & ~1) * 8 + (odd ? kTile / 2 : 0);
+        st16<kNtStoreWO>(p.dst + at, odd ? make_uint4(g0, g1, o.z, o.w) : make_uint4(o.x, o.y, g0, g1));
+      } else if constexpr (kSplit) {
         st8<kNtStoreWO>(p.dst + pos + u * kTile, make_uint2(o.x, o.y));
         st8<kNtStoreWO>(p.dst + pos + u * kTile + kTile / 2, make_uint2(o.z, o.w));
       } else {
@@ -366,34 +375,32 @@ struct CastOp {
       for (int k = 0; k < kLoads; ++k) {
         w[4 * k] = r[u][k].x; w[4 * k + 1] = r[u][k].y; w[4 * k + 2] = r[u][k].z; w[4 * k + 3] = r[u][k].w;
       }
-      if constexpr (DELAYED) {
-        if (note_source(w)) {   // rare: this group holds inf/NaN, encode it element by element
-          const uint32_t mw[4] = {mm[u].x, mm[u].y, mm[u].z, mm[u].w};
-          const uint32_t keep = amax16;
-          uint4 o = make_uint4(0, 0, 0, 0);
-          uint32_t* ow = &o.x;
+      uint4 o = make_uint4(0, 0, 0, 0);
+      bool slow = false;
+      if constexpr (DELAYED) slow = note_source(w);
+      if (slow) {             // rare: this group holds inf/NaN, encode it element by element
+        const uint32_t mw[4] = {mm[u].x, mm[u].y, mm[u].z, mm[u].w};
+        const uint32_t keep = amax16;
+        uint32_t* ow = &o.x;
 #pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const uint32_t bits = kSrc16<SRC> ? (w[(j >> 1) % kW] >> ((j & 1) * 16)) & 0xFFFFu : w[j % kW];
-            ow[j >> 2] |= one(bits, FUSE ? (mw[j >> 2] >> ((j & 3) * 8)) & 0xFFu : 0u) << ((j & 3) * 8);
-          }
-          amax16 = keep;
-          store(u, o);
-          continue;
+        for (int j = 0; j < 16; ++j) {
+          const uint32_t bits = kSrc16<SRC> ? (w[(j >> 1) % kW] >> ((j & 1) * 16)) & 0xFFFFu : w[j % kW];
+          ow[j >> 2] |= one(bits, FUSE ? (mw[j >> 2] >> ((j & 3) * 8)) & 0xFFu : 0u) << ((j & 3) * 8);
+        }
+        amax16 = keep;
+      } else {
+        o.x = quad(w, 0);
+        o.y = quad(w, 1);
+        o.z = quad(w, 2);
+        o.w = quad(w, 3);
+        if constexpr (FUSE) {
+          moment_word(o.x, mm[u].x);
+          moment_word(o.y, mm[u].y);
+          moment_word(o.z, mm[u].z);
+          moment_word(o.w, mm[u].w);
         }
       }
-      uint4 o;
-      o.x = quad(w, 0);
-      o.y = quad(w, 1);
-      o.z = quad(w, 2);
-      o.w = quad(w, 3);
-      if constexpr (FUSE) {
-        moment_word(o.x, mm[u].x);
-        moment_word(o.y, mm[u].y);
-        moment_word(o.z, mm[u].z);
-        moment_word(o.w, mm[u].w);
-      }
-      store(u, o);
+      store(u, o);            // all lanes again: the store may exchange data between lanes
     }
     n_elems += UN * kGroup;
   }

@@ -309,6 +309,9 @@ __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
 #ifndef FP8LM_CAST_SPLIT
 #define FP8LM_CAST_SPLIT 1     // cast kernel, 16-bit sources: the same split layout as the update kernel
 #endif
+#ifndef FP8LM_CAST_STORE16
+#define FP8LM_CAST_STORE16 0   // cast kernel, split layout: neighbouring lanes swap halves so that each stores 128 bits once
+#endif
 #ifndef FP8LM_UPDATE_SPLIT
 #define FP8LM_UPDATE_SPLIT 1   // update kernel: a thread takes elements [8L, 8L+8) of both halves of a tile, so
                                // that every access of the workgroup is contiguous (0: 16 consecutive elements)

@@ -16,7 +16,7 @@ class OptimizerState:
     def __init__(self, tensors, total_elems: int, cfg: B.AutoscaleCfg, device: int = 0,
                  grad_fmt: int = B.E5M2, wcopy: int = B.WCOPY_E4M3, spread: bool = False,
                  grad_buffer: bool = False, master_fmt: int = B.STATE_F16, v_fmt: int = B.STATE_F16,
-                 share_with: "OptimizerState" = None):
+                 share_with: "OptimizerState" = None, arena_order=None):
         """`share_with`: another state over the same flat buffers.  Parameter groups (say, no weight decay on
         biases and LayerNorm weights) are one state each, over disjoint tensor lists of the same buffers; each
         has its own context and metadata and is stepped with its own hyper-parameters."""
@@ -55,6 +55,9 @@ class OptimizerState:
             # one allocation, the buffers carved out of it one after the other (what a caller of the C ABI with an
             # arena of its own would do): where they lie relative to each other is then the same in every process
             items = [(name, k, dt) for reg in plan for name, k, dt in reg]
+            if arena_order:            # names in the order they are to follow each other inside the allocation
+                assert sorted(arena_order) == sorted(name for name, _, _ in items), arena_order
+                items.sort(key=lambda it: list(arena_order).index(it[0]))
             align = (2 << 20) if n >= (2 << 20) else 256
             offs, end = [], 0
             for _, k, dt in items:
