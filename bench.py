@@ -2,10 +2,14 @@
 """Benchmark of the FP8 gradient cast + FP8 Adam step on one MI355X.
 
 A "step" is one pass of the whole hot path over one model's flat tensors, all inputs resident in HBM:
-    fp8lm_amax_scale  (read 2 B/param)
-    fp8lm_cast_fp8    (read 2, write 1)
+    amax + scale      (read 2 B/param)
+    FP8 cast          (read 2, write 1)
     fp8lm_adam_step_fp8: amax pass (read 2) + update pass (read 6, write 6)
-= 19 algorithmic bytes per parameter.  Prints one JSON line: parameters updated per second, the
+= 19 algorithmic bytes per parameter.  The default path (`spec`) produces exactly these results but goes through
+fp8lm_quantize_fp8, which reads a tensor once for amax and cast together when its power-of-two scale does not
+change from the step before (17 bytes per parameter plus 3 for every element of a tensor that has to be cast
+again); `--path jit` is the three entry points one after the other.  Successive steps take different gradient
+buffers (independent draws), so that amax values move from step to step as they do in training.  Prints one JSON line: parameters updated per second, the
 achieved HBM bandwidth of the dominant kernel (the Adam update pass, 12 B/param) against the 8 TB/s
 peak, the bandwidth that memory-only skeletons of the same kernels reach on the same buffers
 ("ceilings"), and the CPU oracle timed on the host cores for a bounded sample of the same workload.
@@ -138,10 +142,15 @@ def main() -> int:
                          "a kernel of known size that profiler counters are scaled by")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the memory-only skeletons of the four kernels that are timed on the same buffers after the step")
-    ap.add_argument("--path", choices=["jit", "fused", "single"], default="jit",
+    ap.add_argument("--path", choices=["spec", "jit", "fused", "spec-fused", "single"], default="spec",
                     help="jit: amax pass + cast + two-pass Adam (19 B/param, the three entry points as they are); "
-                         "fused: same results, the cast also does the Adam step's first pass (18 B/param, one GPU "
-                         "only); single: delayed gradient scaling + predicted first-moment scale (15 B/param)")
+                         "spec: the same results through fp8lm_quantize_fp8, which casts with the predicted scale while "
+                         "measuring the amax and casts again only the tensors whose scale changed (17 B/param + redone "
+                         "tensors); fused: same results, the cast also does the Adam step's first pass (18 B/param, one "
+                         "GPU only); spec-fused: both (16 B/param + redone tensors); single: delayed gradient scaling + "
+                         "predicted first-moment scale (15 B/param, results differ: looser scales)")
+    ap.add_argument("--grad-buffers", type=int, default=3,
+                    help="number of gradient source buffers with independent draws that successive steps rotate through")
     ap.add_argument("--allreduce-steps", type=int, default=0, metavar="N",
                     help="also time the shared-scale re-quantise kernel and the N-rank FP8 sum (Eq. 4-6) on this layout")
     ap.add_argument("--only-path", action="store_true", help="do not also time the other two paths")
@@ -186,12 +195,16 @@ def main() -> int:
     synth.fill_weights(grad, lay, args.seed)          # reuse the buffer for the initial weights
     st.init_master(grad)
     torch.cuda.synchronize()
+    # gradient sources: independent draws that successive steps rotate through (the first lives in the state's arena)
     grad.zero_()
-    synth.fill_gradients(grad, wl, args.seed, 1)
+    grads = [grad] + [torch.zeros_like(grad) for _ in range(max(1, args.grad_buffers) - 1)]
+    for k, gbuf in enumerate(grads):
+        synth.fill_gradients(gbuf, wl, args.seed, 1 + k)
     torch.cuda.synchronize()
 
-    bytes_of = {"jit": 19, "fused": 18, "single": 15}
-    mode_of = {"jit": B.MSCALE_EXACT_PASS, "fused": B.MSCALE_FROM_CAST, "single": B.MSCALE_PREDICTED}
+    base_bytes = {"jit": 19, "fused": 18, "single": 15, "spec": 17, "spec-fused": 16}     # before any tensor is cast twice
+    mode_of = {"jit": B.MSCALE_EXACT_PASS, "fused": B.MSCALE_FROM_CAST, "single": B.MSCALE_PREDICTED,
+               "spec": B.MSCALE_EXACT_PASS, "spec-fused": B.MSCALE_FROM_CAST}
     step_no = [0]
 
     def run_steps(path, n):
@@ -199,10 +212,13 @@ def main() -> int:
         for _ in range(n):
             step_no[0] += 1
             hp = B.adam_hparams(wl.lr, step_no[0], exact=args.exact, stats=args.stats, m_scale_mode=mode_of[path])
-            st.step(grad, hp, delayed=(path == "single" and step_no[0] > 1))
+            st.step(grads[step_no[0] % len(grads)], hp, delayed=(path == "single" and step_no[0] > 1),
+                    speculative=path.startswith("spec"))
 
     def timed(path, n):
+        """(seconds, per-kernel timing, bytes per parameter and step actually moved, speculation totals of the region)."""
         torch.cuda.synchronize()
+        before = st.ctx.speculation_stats()
         st.ctx.set_timing(True)
         st.ctx.get_timing()
         torch.cuda.synchronize()
@@ -212,31 +228,40 @@ def main() -> int:
         dt = time.perf_counter() - t0
         tm = st.ctx.get_timing()
         st.ctx.set_timing(False)
-        return dt, tm
+        after = st.ctx.speculation_stats()
+        spec = {k: after[k] - before[k] for k in after}
+        # a tensor cast twice costs its 2 B/element read and 1 B/element write (3 + 1 with the moment read) once more
+        redo_bytes = (4 if path == "spec-fused" else 3) * spec["elems_redone"] / n
+        return dt, tm, base_bytes[path] + redo_bytes / P, spec
 
-    bytes_per_param = bytes_of[args.path]
     run_steps(args.path, args.warmup)
-    dt, timing = timed(args.path, args.steps)
+    dt, timing, bytes_per_param, spec_totals = timed(args.path, args.steps)
     other_paths = {}
     if not args.only_path:
-        for path in ("jit", "fused", "single"):
+        for path in ("jit", "spec", "fused", "spec-fused", "single"):
             if path != args.path:
                 run_steps(path, 2)
-                odt, _ = timed(path, min(args.steps, 10))
                 n = min(args.steps, 10)
+                odt, _, obytes, _ = timed(path, n)
                 other_paths[path] = {"ms_per_step": round(odt / n * 1e3, 3), "params_per_s": P / (odt / n),
-                                     "bytes_per_param_step": bytes_of[path]}
+                                     "bytes_per_param_step": round(obytes, 3)}
 
     ms_per_step = dt / args.steps * 1e3
     kernels = {}
     for name, bpp in BYTES_PER_PARAM.items():
-        if name == "cast" and args.path == "fused":
-            bpp = 4
         n, ms = timing[name]
-        if n:
-            avg = ms / n
-            kernels[name] = {"avg_ms": round(avg, 4), "launches": n, "bytes_per_param": bpp,
-                             "GBps": round(bpp * P / (avg * 1e-3) / 1e9, 1)}
+        if not n:
+            continue
+        if name == "cast":
+            # the cast is timed per step: a speculative step launches it twice (all tensors, then the ones to redo)
+            per_step = ms / args.steps
+            moved = bytes_per_param - {"jit": 16, "fused": 14, "single": 12, "spec": 14, "spec-fused": 12}[args.path]
+            kernels[name] = {"avg_ms": round(per_step, 4), "launches": n, "bytes_per_param": round(moved, 3),
+                             "GBps": round(moved * P / (per_step * 1e-3) / 1e9, 1)}
+            continue
+        avg = ms / n
+        kernels[name] = {"avg_ms": round(avg, 4), "launches": n, "bytes_per_param": bpp,
+                         "GBps": round(bpp * P / (avg * 1e-3) / 1e9, 1)}
     dom = "adam_update"
     achieved = kernels[dom]["GBps"]
     out = {
@@ -254,11 +279,15 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": wl.name, "tensors": lay.n_tensors, "params": P, "grad_fmt": "e5m2",
                    "m_fmt": "e4m3", "v": "fp16 scaled", "master": "fp16 scaled", "wcopy": "e4m3",
-                   "exact_div_sqrt": bool(args.exact), "path": args.path, "bytes_per_param_step": bytes_per_param,
-                   "placement": placement},
+                   "exact_div_sqrt": bool(args.exact), "path": args.path,
+                   "bytes_per_param_step": round(bytes_per_param, 3), "algorithmic_bytes_per_param_step": 19,
+                   "gradient_buffers": len(grads), "placement": placement},
         "step_GBps": round(bytes_per_param * P / (dt / args.steps) / 1e9, 1),
         "step_frac_of_peak": round(bytes_per_param * P / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
         "kernels": kernels,
+        "speculation": ({"steps": spec_totals["calls"], "tensors_cast_twice_per_step": round(spec_totals["tensors_redone"] / max(1, spec_totals["calls"]), 2),
+                         "share_of_elements_cast_twice": round(spec_totals["elems_redone"] / max(1, spec_totals["calls"]) / P, 4)}
+                        if args.path.startswith("spec") else None),
         "other_paths": other_paths,
         "roofline": {"kernel": "adam_update_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(wl.name)},
@@ -270,7 +299,7 @@ def main() -> int:
         side.wait_stream(torch.cuda.current_stream())
         torch.cuda.synchronize()
         with torch.cuda.graph(graph, stream=side):
-            st.step(grad, hp, delayed=delayed)
+            st.step(grad, hp, delayed=delayed, speculative=args.path.startswith("spec"))
         for _ in range(args.warmup):
             graph.replay()
         torch.cuda.synchronize()
@@ -346,7 +375,9 @@ def main() -> int:
         out["ceilings"] = ceilings
         if args.path == "jit":
             out["step_frac_of_skeletons"] = round(path_ms / ms_per_step, 4)
-    del st, grad
+        elif args.path == "spec":       # no separate amax pass; tensors cast twice are not in the skeleton sum
+            out["step_frac_of_skeletons"] = round((path_ms - ceilings["amax"]["avg_ms"]) / ms_per_step, 4)
+    del st, grad, grads
     torch.cuda.empty_cache()
     if extra:
         out["allreduce_steps"] = extra

@@ -252,6 +252,30 @@ fp8lm_status fp8lm_cast_fp8_for_adam(fp8lm_ctx* ctx, const void* src /*device*/,
                                      void* stream);
 
 /*
+ * Just-in-time quantisation (Appendix A.2; Sec. 2.1) in one call: the results -- dst and every field of meta -- are
+ * those of fp8lm_amax_scale followed by fp8lm_cast_fp8, bit for bit, but a tensor whose scale does not change from
+ * one step to the next is read once instead of twice.  The scale is first set as the tensor's amax history predicts
+ * it (the rule of fp8lm_cast_fp8_delayed) and one pass casts with it while measuring the true amax; then the scale
+ * the true amax demands is computed exactly as fp8lm_amax_scale does, and only the tensors for which it differs
+ * from the prediction (the amax crossed a power-of-two boundary, the first step, an inf/NaN in the source) are
+ * cast a second time with the right scale.  Per step this moves 3 bytes per element of the tensors whose
+ * prediction held and 6 of the others, instead of 5 of all.
+ * fp8lm_quantize_fp8_for_adam also measures the amax of the first moment the following Adam step will produce, like
+ * fp8lm_cast_fp8_for_adam: call fp8lm_adam_step_fp8 next with m_scale_mode = FP8LM_MSCALE_FROM_CAST.
+ * fp8lm_get_speculation_stats synchronises `stream` and returns the context's running totals since fp8lm_create:
+ * calls of the two entry points above, tensors cast twice, elements cast twice.
+ */
+fp8lm_status fp8lm_quantize_fp8(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_src src_type, uint8_t* dst /*device*/,
+                                fp8lm_fmt fmt, fp8lm_meta* meta /*device*/, const fp8lm_autoscale_cfg* cfg /*host*/,
+                                void* stream);
+fp8lm_status fp8lm_quantize_fp8_for_adam(fp8lm_ctx* ctx, const void* src /*device*/, fp8lm_src src_type,
+                                         uint8_t* dst /*device*/, fp8lm_fmt fmt, fp8lm_meta* meta /*device*/,
+                                         const fp8lm_autoscale_cfg* cfg /*host*/, const uint8_t* m /*device*/,
+                                         const fp8lm_meta* m_meta /*device*/, float beta1, void* stream);
+fp8lm_status fp8lm_get_speculation_stats(fp8lm_ctx* ctx, uint64_t* calls /*host*/, uint64_t* tensors_redone /*host*/,
+                                         uint64_t* elems_redone /*host*/, void* stream);
+
+/*
  * The three steps around the FP8 gradient all-reduce of Sec. 2.1 (Eq. 4-6), as one GPU can run them;
  * the collectives themselves are not part of this library.  n_ranks <= 128.
  *

@@ -37,6 +37,7 @@ EXPORTS = [
     "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_set_tensor_flags", "fp8lm_meta_init", "fp8lm_amax_scale",
     "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_cast_fp8_for_adam", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
     "fp8lm_quant_error_stats", "fp8lm_autoscale_broadcast", "fp8lm_set_mu", "fp8lm_memory_skeleton", "fp8lm_adam_step_fp8_static",
+    "fp8lm_quantize_fp8", "fp8lm_quantize_fp8_for_adam", "fp8lm_get_speculation_stats",
     "fp8lm_init_master", "fp8lm_init_master_as", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
@@ -122,6 +123,9 @@ def lib() -> C.CDLL:
         L.fp8lm_cast_fp8.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
         L.fp8lm_cast_fp8_delayed.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
         L.fp8lm_cast_fp8_for_adam.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, i32, vp, vp, C.c_float, vp]
+        L.fp8lm_quantize_fp8.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
+        L.fp8lm_quantize_fp8_for_adam.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_float, vp]
+        L.fp8lm_get_speculation_stats.argtypes = [vp, vp, vp, vp, vp]
         L.fp8lm_init_master.argtypes = [vp, vp, vp, vp, vp]
         L.fp8lm_init_master_as.argtypes = [vp, vp, vp, vp, C.c_int, vp]
         L.fp8lm_shared_scale.argtypes = [vp, vp, i32, vp, vp]
@@ -259,6 +263,29 @@ class Context:
         _check(lib().fp8lm_cast_fp8_for_adam(self._h, _ptr(src), src_type_of(src), _ptr(dst), fmt, _ptr(meta), C.addressof(cfg),
                                              1 if delayed else 0, _ptr(m), _ptr(m_meta), beta1, _stream(stream)),
                "fp8lm_cast_fp8_for_adam")
+
+    def quantize_fp8(self, src, dst, fmt, meta, cfg, stream=None):
+        """amax + scale + cast with the results of amax_scale followed by cast_fp8, reading unchanged-scale tensors once."""
+        assert dst.element_size() == 1
+        self._fits(src, dst)
+        self._fits_meta(meta)
+        _check(lib().fp8lm_quantize_fp8(self._h, _ptr(src), src_type_of(src), _ptr(dst), fmt, _ptr(meta), C.addressof(cfg),
+                                        _stream(stream)), "fp8lm_quantize_fp8")
+
+    def quantize_fp8_for_adam(self, src, dst, fmt, meta, cfg, m, m_meta, beta1, stream=None):
+        assert dst.element_size() == 1 and m.element_size() == 1
+        self._fits(src, dst, m)
+        self._fits_meta(meta, m_meta)
+        _check(lib().fp8lm_quantize_fp8_for_adam(self._h, _ptr(src), src_type_of(src), _ptr(dst), fmt, _ptr(meta),
+                                                 C.addressof(cfg), _ptr(m), _ptr(m_meta), beta1, _stream(stream)),
+               "fp8lm_quantize_fp8_for_adam")
+
+    def speculation_stats(self, stream=None) -> dict:
+        """Running totals of quantize_fp8 / quantize_fp8_for_adam on this context (synchronises the stream)."""
+        vals = (C.c_uint64 * 3)()
+        _check(lib().fp8lm_get_speculation_stats(self._h, C.addressof(vals), C.addressof(vals) + 8, C.addressof(vals) + 16,
+                                                 _stream(stream)), "fp8lm_get_speculation_stats")
+        return {"calls": int(vals[0]), "tensors_redone": int(vals[1]), "elems_redone": int(vals[2])}
 
     def shared_scale(self, metas, stream=None) -> torch.Tensor:
         """Eq. 4: per-tensor minimum of the ranks' scales; returns a device fp32 array [n_tensors]."""

@@ -100,6 +100,12 @@ struct fp8lm_ctx {
   int32_t* d_chunk_tensor = nullptr;
   Scratch* d_scratch = nullptr;
   Partial* d_partials = nullptr;    // [num_cus * kMaxBlocksPerCu + n_tensors]
+  // speculative quantisation: tensor and chunk tables of the tensors that have to be cast again, their chunk
+  // count, and running totals (calls, tensors cast twice, elements cast twice)
+  TensorDesc* d_redo_desc = nullptr;
+  int32_t* d_redo_chunk_tensor = nullptr;
+  int32_t* d_redo_count = nullptr;
+  unsigned long long* d_spec_totals = nullptr;
   // what the last fused cast measured for (checked by the Adam step that wants to use it)
   struct Fused { bool valid; const uint8_t* grad; const uint8_t* m; const fp8lm_meta* m_meta; float b1; int fmt; };
   Fused fused{false, nullptr, nullptr, nullptr, 0.0f, 0};
@@ -149,9 +155,13 @@ fp8lm_status build_tables(fp8lm_ctx* c, int32_t chunk_elems) {
   for (int t = 0; t < c->n_tensors; ++t)
     std::fill(chunk_tensor.begin() + desc[t].first_chunk, chunk_tensor.begin() + desc[t].first_chunk + desc[t].n_chunks, t);
   TensorDesc* d_desc = nullptr;
+  TensorDesc* d_redo_desc = nullptr;
   int32_t* d_chunk_tensor = nullptr;
+  int32_t* d_redo_chunk_tensor = nullptr;
   hipError_t e = hipMalloc((void**)&d_desc, std::max<size_t>(1, desc.size()) * sizeof(TensorDesc));
   if (e == hipSuccess) e = hipMalloc((void**)&d_chunk_tensor, std::max<size_t>(1, chunk_tensor.size()) * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMalloc((void**)&d_redo_desc, std::max<size_t>(1, desc.size()) * sizeof(TensorDesc));
+  if (e == hipSuccess) e = hipMalloc((void**)&d_redo_chunk_tensor, std::max<size_t>(1, chunk_tensor.size()) * sizeof(int32_t));
   if (e == hipSuccess && !desc.empty())
     e = hipMemcpy(d_desc, desc.data(), desc.size() * sizeof(TensorDesc), hipMemcpyHostToDevice);
   if (e == hipSuccess && !chunk_tensor.empty())
@@ -160,12 +170,18 @@ fp8lm_status build_tables(fp8lm_ctx* c, int32_t chunk_elems) {
     g_hip_error = std::string("chunk tables: ") + hipGetErrorString(e);
     if (d_desc) (void)hipFree(d_desc);
     if (d_chunk_tensor) (void)hipFree(d_chunk_tensor);
+    if (d_redo_desc) (void)hipFree(d_redo_desc);
+    if (d_redo_chunk_tensor) (void)hipFree(d_redo_chunk_tensor);
     return FP8LM_ERR_HIP;
   }
   if (c->d_desc) (void)hipFree(c->d_desc);
   if (c->d_chunk_tensor) (void)hipFree(c->d_chunk_tensor);
+  if (c->d_redo_desc) (void)hipFree(c->d_redo_desc);
+  if (c->d_redo_chunk_tensor) (void)hipFree(c->d_redo_chunk_tensor);
   c->d_desc = d_desc;
   c->d_chunk_tensor = d_chunk_tensor;
+  c->d_redo_desc = d_redo_desc;
+  c->d_redo_chunk_tensor = d_redo_chunk_tensor;
   c->chunk_elems = chunk_elems;
   c->n_chunks = (int32_t)total_chunks;
   return FP8LM_OK;
@@ -186,7 +202,13 @@ bool deferred_of(const fp8lm_ctx* c) {
 
 Tables tables_of(const fp8lm_ctx* c) {
   return Tables{c->d_desc, c->d_chunk_tensor, c->d_scratch, c->d_partials, c->n_chunks, c->chunk_elems,
-                deferred_of(c) ? 1 : 0};
+                deferred_of(c) ? 1 : 0, nullptr};
+}
+// The tables of the tensors a speculative quantisation has to cast again: built on the device, so the number of
+// chunks is only known there; tensors always finished by the second launch.
+Tables redo_tables_of(const fp8lm_ctx* c) {
+  return Tables{c->d_redo_desc, c->d_redo_chunk_tensor, c->d_scratch, c->d_partials, c->n_chunks, c->chunk_elems, 1,
+                c->d_redo_count};
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -220,6 +242,14 @@ fp8lm_status after_launch() {
 }
 
 // Launches a chunk-walking kernel and, in the deferred form, the launch that finishes its tensors.
+template <class Op, class Params, class Kernel>
+void launch_walk_on(fp8lm_ctx* c, hipStream_t s, Kernel kernel, const Params& p, const Tables& tb) {
+  const dim3 g(grid_of(c)), b(kThreads);
+  hipLaunchKernelGGL(kernel, g, b, 0, s, tb, p);
+  if (tb.deferred)
+    hipLaunchKernelGGL((epilogue_kernel<Op, Params>), dim3(std::min<int>(c->n_tensors, 8 * c->num_cus)), b, 0, s, tb, p,
+                       (int)g.x, (int)c->n_tensors);
+}
 template <class Op, class Params, class Kernel>
 void launch_walk(fp8lm_ctx* c, hipStream_t s, Kernel kernel, const Params& p) {
   const Tables tb = tables_of(c);
@@ -332,6 +362,10 @@ fp8lm_status fp8lm_create(fp8lm_ctx** out, const fp8lm_tensor* tensors, int32_t 
     const size_t records = (size_t)c->num_cus * kMaxBlocksPerCu + (size_t)n + 1;
     if (e == hipSuccess) e = hipMalloc((void**)&c->d_partials, records * sizeof(Partial));
     if (e == hipSuccess) e = hipMemset(c->d_partials, 0, records * sizeof(Partial));
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_redo_count, sizeof(int32_t));
+    if (e == hipSuccess) e = hipMemset(c->d_redo_count, 0, sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_spec_totals, 3 * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMemset(c->d_spec_totals, 0, 3 * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) { g_hip_error = hipGetErrorString(e); st = FP8LM_ERR_HIP; }
   }
@@ -347,6 +381,10 @@ fp8lm_status fp8lm_destroy(fp8lm_ctx* c) {
   if (c->d_chunk_tensor) (void)hipFree(c->d_chunk_tensor);
   if (c->d_scratch) (void)hipFree(c->d_scratch);
   if (c->d_partials) (void)hipFree(c->d_partials);
+  if (c->d_redo_desc) (void)hipFree(c->d_redo_desc);
+  if (c->d_redo_chunk_tensor) (void)hipFree(c->d_redo_chunk_tensor);
+  if (c->d_redo_count) (void)hipFree(c->d_redo_count);
+  if (c->d_spec_totals) (void)hipFree(c->d_spec_totals);
   for (auto& s : c->stamps) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
   for (auto& e : c->free_events) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
   delete c;
@@ -407,9 +445,11 @@ fp8lm_status fp8lm_amax_scale(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
 }
 
 // Common body of the three cast entry points.
+enum CastMode { kCastPlain = 0, kCastDelayed = 1, kCastSpeculative = 2 };
 static fp8lm_status cast_impl(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
-                              fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, bool delayed, bool fuse,
+                              fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, int mode, bool fuse,
                               const uint8_t* m, const fp8lm_meta* m_meta, float beta1, void* stream) {
+  const bool delayed = mode != kCastPlain;        // the first pass of a speculation is a delayed-scaling cast
   if (!c || !cfg_ok(cfg) || !src_ok(src_type) || (fmt != FP8LM_E4M3 && fmt != FP8LM_E5M2))
     return FP8LM_ERR_INVALID_ARGUMENT;
   c->fused.valid = false;
@@ -419,14 +459,23 @@ static fp8lm_status cast_impl(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
   if (!aligned16(src) || !aligned16(dst) || (fuse && !aligned16(m))) return FP8LM_ERR_MISALIGNED;
   DeviceGuard guard(c->device);
   hipStream_t s = (hipStream_t)stream;
+  const uint32_t fmax_bits = fmt == FP8LM_E4M3 ? kBitsE4M3Max : kBitsE5M2Max;
   if (delayed) {
     Timed tm(c, s, FP8LM_K_SCALARS);
-    hipLaunchKernelGGL(delayed_scale_kernel, dim3((c->n_tensors + 255) / 256), dim3(256), 0, s, c->d_desc, meta,
-                       c->n_tensors, fmt == FP8LM_E4M3 ? kBitsE4M3Max : kBitsE5M2Max, cfg->hist_window, cfg->margin);
+    const dim3 gs((c->n_tensors + 255) / 256), bs(256);
+    if (mode == kCastSpeculative)
+      hipLaunchKernelGGL(speculate_scale_kernel, gs, bs, 0, s, c->d_desc, meta, c->d_scratch, c->n_tensors, fmax_bits,
+                         cfg->hist_window, cfg->margin);
+    else
+      hipLaunchKernelGGL(delayed_scale_kernel, gs, bs, 0, s, c->d_desc, meta, c->n_tensors, fmax_bits, cfg->hist_window,
+                         cfg->margin);
     fp8lm_status st = after_launch();
     if (st != FP8LM_OK) return st;
   }
   CastParams p{};
+  p.speculative = mode == kCastSpeculative ? 1 : 0;
+  p.fmax_bits = fmax_bits;
+  p.margin = cfg->margin;
   p.src = src;
   p.dst = dst;
   p.meta = meta;
@@ -457,24 +506,79 @@ static fp8lm_status cast_impl(fp8lm_ctx* c, const void* src, fp8lm_src src_type,
 #undef FP8LM_CAST_LAUNCH
   }
   fp8lm_status st = after_launch();
+  if (st == FP8LM_OK && mode == kCastSpeculative) {
+    // the tensors whose scale turned out different: their chunk list, then the plain cast over that list
+    {
+      Timed tm(c, s, FP8LM_K_SCALARS);
+      hipLaunchKernelGGL(redo_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, c->d_desc, c->d_scratch, c->d_redo_desc,
+                         c->n_tensors, c->d_redo_count, c->d_spec_totals);
+      hipLaunchKernelGGL(redo_fill_kernel, dim3(std::min<int>(c->n_tensors, 1024)), dim3(256), 0, s, c->d_redo_desc,
+                         c->d_redo_chunk_tensor, c->n_tensors);
+      st = after_launch();
+    }
+    if (st == FP8LM_OK) {
+      const Tables rt = redo_tables_of(c);
+      p.speculative = 0;
+      Timed tm(c, s, FP8LM_K_CAST);
+#define FP8LM_REDO_LAUNCH(F, S)                                                                            \
+      do {                                                                                                  \
+        if (fuse) launch_walk_on<CastOp<F, false, true, S>>(c, s, cast_kernel<F, false, true, S>, p, rt);   \
+        else launch_walk_on<CastOp<F, false, false, S>>(c, s, cast_kernel<F, false, false, S>, p, rt);      \
+      } while (0)
+#define FP8LM_REDO_SRC(S)                                                                                  \
+      do {                                                                                                  \
+        if (fmt == FP8LM_E4M3) FP8LM_REDO_LAUNCH(kE4M3, S);                                                 \
+        else FP8LM_REDO_LAUNCH(kE5M2, S);                                                                   \
+      } while (0)
+      if (src_type == FP8LM_SRC_F32) FP8LM_REDO_SRC(kSrcF32);
+      else if (src_type == FP8LM_SRC_F16) FP8LM_REDO_SRC(kSrcF16);
+      else FP8LM_REDO_SRC(kSrcBF16);
+#undef FP8LM_REDO_SRC
+#undef FP8LM_REDO_LAUNCH
+      st = after_launch();
+    }
+  }
   if (st == FP8LM_OK && fuse) c->fused = {true, dst, m, m_meta, p.b1, fmt};
   return st;
 }
 
 fp8lm_status fp8lm_cast_fp8(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
                             fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {
-  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, false, false, nullptr, nullptr, 0.0f, stream);
+  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, kCastPlain, false, nullptr, nullptr, 0.0f, stream);
 }
 
 fp8lm_status fp8lm_cast_fp8_delayed(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
                                     fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {
-  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, true, false, nullptr, nullptr, 0.0f, stream);
+  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, kCastDelayed, false, nullptr, nullptr, 0.0f, stream);
 }
 
 fp8lm_status fp8lm_cast_fp8_for_adam(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
                                      fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, int32_t delayed,
                                      const uint8_t* m, const fp8lm_meta* m_meta, float beta1, void* stream) {
-  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, delayed != 0, true, m, m_meta, beta1, stream);
+  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, delayed != 0 ? kCastDelayed : kCastPlain, true, m, m_meta, beta1,
+                   stream);
+}
+
+fp8lm_status fp8lm_quantize_fp8(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
+                                fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, void* stream) {
+  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, kCastSpeculative, false, nullptr, nullptr, 0.0f, stream);
+}
+
+fp8lm_status fp8lm_quantize_fp8_for_adam(fp8lm_ctx* c, const void* src, fp8lm_src src_type, uint8_t* dst, fp8lm_fmt fmt,
+                                         fp8lm_meta* meta, const fp8lm_autoscale_cfg* cfg, const uint8_t* m,
+                                         const fp8lm_meta* m_meta, float beta1, void* stream) {
+  return cast_impl(c, src, src_type, dst, fmt, meta, cfg, kCastSpeculative, true, m, m_meta, beta1, stream);
+}
+
+fp8lm_status fp8lm_get_speculation_stats(fp8lm_ctx* c, uint64_t* calls, uint64_t* tensors_redone, uint64_t* elems_redone,
+                                         void* stream) {
+  if (!c || !calls || !tensors_redone || !elems_redone) return FP8LM_ERR_INVALID_ARGUMENT;
+  DeviceGuard guard(c->device);
+  unsigned long long h[3] = {0, 0, 0};
+  HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+  HIP_TRY(hipMemcpy(h, c->d_spec_totals, sizeof(h), hipMemcpyDeviceToHost));
+  *calls = h[0]; *tensors_redone = h[1]; *elems_redone = h[2];
+  return FP8LM_OK;
 }
 
 fp8lm_status fp8lm_shared_scale(fp8lm_ctx* c, const fp8lm_meta* const* metas, int32_t n_ranks, float* shared,

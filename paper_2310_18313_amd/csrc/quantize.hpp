@@ -219,7 +219,10 @@ struct CastParams {
   uint8_t* dst;
   fp8lm_meta* meta;
   AutoscaleRule rule;
-  int32_t hist_window;   // delayed scaling only
+  int32_t hist_window;   // delayed scaling and speculation
+  int32_t speculative;   // DELAYED pass of the speculative just-in-time quantisation (see CastOp::speculation_verdict)
+  uint32_t fmax_bits;    // speculation: largest finite value of the target format
+  int32_t margin;
   // fused first pass of the Adam step (FUSE): the first moment as it stands and beta1
   const uint8_t* m;
   const fp8lm_meta* m_meta;
@@ -429,6 +432,10 @@ struct CastOp {
     if constexpr (FUSE) tb.scratch[t].pend.amax_m_bits = s.mx[2];
     const unsigned long long n_sat = s.ct[0], n_und = s.ct[1];
     if constexpr (DELAYED) {
+      if (p.speculative) {
+        if (speculation_verdict(t, abits)) finish(t, d, vm, n_sat, n_und);
+        return;
+      }
       fp8lm_meta& M = p.meta[t];
       if (abits >= SrcTraits<SRC>::kNonfinite) {
         M.amax = __builtin_inff();
@@ -439,6 +446,32 @@ struct CastOp {
       }
     }
     finish(t, d, vm, n_sat, n_und);
+  }
+  // Speculative just-in-time quantisation (Appendix A.2): this pass has cast the tensor with the scale its amax
+  // history predicted and measured the true amax on the way.  Now the metadata is brought to exactly what the amax
+  // pass of the two-pass form would have left (scale from the true amax, history pushed, flags); if that scale is
+  // the one the cast used, the codes already written are the just-in-time result and the caller finishes the cast's
+  // bookkeeping; otherwise the tensor is marked to be cast again.  Returns true if the speculation held.
+  __device__ bool speculation_verdict(int t, uint32_t abits) {
+    fp8lm_meta& M = p.meta[t];
+    Scratch& S = tb.scratch[t];
+    const float used = M.scale;
+    M.scale = S.old_scale;
+    M.inv_scale = S.old_inv;
+    bool held;
+    if (abits >= SrcTraits<SRC>::kNonfinite) {
+      M.amax = __builtin_inff();
+      M.flags = FP8LM_FLAG_NONFINITE;       // the second cast takes the path that knows NaN
+      held = false;
+    } else {
+      const float A = SrcTraits<SRC>::dec(abits);
+      M.amax = A;
+      push_history(M, A, p.hist_window);
+      M.flags = scale_from_history(M, p.fmax_bits, p.hist_window, p.margin);
+      held = M.scale == used;
+    }
+    S.redo = held ? 0u : 1u;
+    return held;
   }
   __device__ void finish(int t, const TensorDesc& d, float vm, unsigned long long n_sat, unsigned long long n_und) {
     fp8lm_meta& M = p.meta[t];
@@ -454,6 +487,78 @@ template <int FMT, bool DELAYED, bool FUSE, int SRC>
 __global__ __launch_bounds__(kThreads) void cast_kernel(Tables tb, CastParams p) {
   CastOp<FMT, DELAYED, FUSE, SRC> op(p, tb);
   walk_chunks<FP8LM_UN_CAST>(tb, op);
+}
+
+// Speculative just-in-time quantisation, step 1: one thread per tensor keeps the scale the meta holds and sets the
+// scale its amax history predicts (the rule of delayed scaling; with an all-zero history the scale stays).
+__global__ void speculate_scale_kernel(const TensorDesc* desc, fp8lm_meta* meta, Scratch* scratch, int n, uint32_t fmax_bits,
+                                       int hist_window, int margin) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n || desc[t].numel == 0) return;
+  scratch[t].old_scale = meta[t].scale;
+  scratch[t].old_inv = meta[t].inv_scale;
+  scratch[t].redo = 0;
+  meta[t].flags = scale_from_history(meta[t], fmax_bits, hist_window, margin);
+}
+
+// Step 3: the chunk list of the tensors whose speculation failed.  One workgroup scans the tensors in order and
+// gives each marked tensor its run of chunks (first_chunk = chunks of the marked tensors before it); the others
+// get none.  Also adds to the running totals that fp8lm_get_speculation_stats reports.
+constexpr int kScanThreads = 1024;
+__global__ __launch_bounds__(kScanThreads) void redo_scan_kernel(const TensorDesc* desc, const Scratch* scratch, TensorDesc* redo_desc,
+                                                                 int n, int32_t* n_chunks_out, unsigned long long* totals) {
+  __shared__ int l_scan[kScanThreads];
+  __shared__ int l_base;
+  if (threadIdx.x == 0) l_base = 0;
+  __syncthreads();
+  unsigned long long redone_elems = 0, redone_tensors = 0;
+  for (int t0 = 0; t0 < n; t0 += kScanThreads) {
+    const int t = t0 + threadIdx.x;
+    TensorDesc d{};
+    int c = 0;
+    if (t < n) {
+      d = desc[t];
+      if (d.numel > 0 && scratch[t].redo) { c = d.n_chunks; redone_elems += (unsigned long long)d.numel; redone_tensors += 1; }
+    }
+    l_scan[threadIdx.x] = c;
+    __syncthreads();
+    for (int o = 1; o < kScanThreads; o <<= 1) {             // inclusive scan over the block
+      const int add = threadIdx.x >= o ? l_scan[threadIdx.x - o] : 0;
+      __syncthreads();
+      l_scan[threadIdx.x] += add;
+      __syncthreads();
+    }
+    const int base = l_base;
+    if (t < n) {
+      d.first_chunk = base + l_scan[threadIdx.x] - c;
+      d.n_chunks = c;
+      redo_desc[t] = d;
+    }
+    __syncthreads();
+    if (threadIdx.x == kScanThreads - 1) l_base = base + l_scan[threadIdx.x];
+    __syncthreads();
+  }
+  // totals: calls, tensors cast twice, elements cast twice (exact sums, one workgroup)
+  __shared__ unsigned long long l_e[kScanThreads / 64], l_t[kScanThreads / 64];
+  redone_elems = wave_sum_u64(redone_elems);
+  redone_tensors = wave_sum_u64(redone_tensors);
+  if ((threadIdx.x & 63) == 0) { l_e[threadIdx.x >> 6] = redone_elems; l_t[threadIdx.x >> 6] = redone_tensors; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long e = 0, k = 0;
+    for (int w = 0; w < kScanThreads / 64; ++w) { e += l_e[w]; k += l_t[w]; }
+    *n_chunks_out = l_base;
+    totals[0] += 1;
+    totals[1] += k;
+    totals[2] += e;
+  }
+}
+// ... and its chunk table: workgroup t (and t + grid, ...) writes tensor t's id into its run of chunks.
+__global__ void redo_fill_kernel(const TensorDesc* redo_desc, int32_t* chunk_tensor, int n) {
+  for (int t = blockIdx.x; t < n; t += gridDim.x) {
+    const TensorDesc d = redo_desc[t];
+    for (int i = threadIdx.x; i < d.n_chunks; i += blockDim.x) chunk_tensor[d.first_chunk + i] = t;
+  }
 }
 
 // Delayed scaling, step 1: one thread per tensor fixes the scale from the history before the cast.

@@ -30,7 +30,8 @@ struct TensorDesc {
 // by the first Adam pass to the second.
 struct Scratch {
   uint32_t ticket;                // chunks finished
-  uint32_t pad[3];
+  uint32_t redo;                  // speculative quantisation: 1 if the tensor has to be cast again with the scale now in its meta
+  float old_scale, old_inv;       // ... and the scale the meta held before the speculation
   struct Pending {
     float sm, ism, sv, isv, sw, isw, sq, isq;
     uint32_t fm, fv, fw, fq;      // flags gathered while choosing the scales
@@ -56,7 +57,10 @@ struct Tables {
   int32_t n_chunks;
   int32_t chunk_elems;
   int32_t deferred;               // 1: workgroups only leave their records; an epilogue launch finishes the tensors
+  const int32_t* n_chunks_dev;    // if set: the number of chunks is read from here (a chunk list built on the device);
+                                  // n_chunks is then only the host's upper bound
 };
+__device__ __forceinline__ long long chunk_count(const Tables& tb) { return tb.n_chunks_dev ? *tb.n_chunks_dev : tb.n_chunks; }
 
 // ---- reductions ----------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
@@ -169,7 +173,8 @@ __device__ __forceinline__ void store_record(const Tables& tb, int t, const Bloc
 template <int NV, int NC, int NF>
 __device__ __forceinline__ void gather_records(const Tables& tb, int t, const TensorDesc& d, long long grid, BlockStats<NV, NC, NF>& s) {
   // owner(c) = the b with b*C/G <= c < (b+1)*C/G
-  const long long C = tb.n_chunks;
+  const long long C = chunk_count(tb);
+  if (grid > C) grid = C;         // a launch with more workgroups than chunks uses only the first C (see walk_chunks)
   const long long c0 = d.first_chunk, c1 = c0 + d.n_chunks - 1;
   const long long b_lo = ((c0 + 1) * grid - 1) / C, b_hi = ((c1 + 1) * grid - 1) / C;
 #pragma unroll
@@ -244,9 +249,13 @@ __global__ __launch_bounds__(kThreads) void epilogue_kernel(Tables tb, Params p,
 template <int UN, class Op>
 __device__ __forceinline__ void walk_chunks(const Tables& tb, Op& op) {
   // workgroup b walks the contiguous chunk range [b*C/G, (b+1)*C/G): `collect` relies on this mapping
-  const long long G = gridDim.x, b = blockIdx.x;
-  long long c = b * tb.n_chunks / G;
-  const long long c_end = (b + 1) * tb.n_chunks / G;
+  // With fewer chunks than workgroups (a chunk list built on the device) only the first C workgroups take part, so
+  // that every one of them owns a chunk and leaves a record wherever `gather_records` expects one.
+  const long long C = chunk_count(tb), b = blockIdx.x;
+  const long long G = C < (long long)gridDim.x ? C : (long long)gridDim.x;
+  if (b >= G) return;
+  long long c = b * C / G;
+  const long long c_end = (b + 1) * C / G;
   int cur = -1, done = 0;
   TensorDesc d{};
   // the tensor id of the next chunk is fetched one iteration ahead, so its latency hides behind the body

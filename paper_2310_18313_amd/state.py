@@ -95,12 +95,23 @@ class OptimizerState:
         self.ctx.adam_step_fp8(self.g8, self.grad_fmt, self.g_meta, self.m, self.m_meta, self.v, self.v_meta,
                                self.w, self.w_meta, self.wq, self.q_meta, hp)
 
-    def step(self, grad: torch.Tensor, hp: B.AdamHparams, delayed: bool = False) -> None:
+    def step(self, grad: torch.Tensor, hp: B.AdamHparams, delayed: bool = False, speculative: bool = False) -> None:
         """One pass of the whole hot path: amax + scale, FP8 cast, FP8 Adam, from a bf16, fp16 or fp32
         gradient buffer.  With `delayed` the
         gradient is quantised in a single pass with the scale of the preceding steps.  With
-        hp.m_scale_mode == MSCALE_FROM_CAST the cast also does the Adam step's first pass."""
+        hp.m_scale_mode == MSCALE_FROM_CAST the cast also does the Adam step's first pass.  With `speculative` the
+        just-in-time quantisation goes through quantize_fp8 (same results; tensors whose scale does not change are
+        read once)."""
         fused = hp.m_scale_mode == B.MSCALE_FROM_CAST
+        if speculative:
+            assert not delayed
+            if fused:
+                self.ctx.quantize_fp8_for_adam(grad, self.g8, self.grad_fmt, self.g_meta, self.cfg, self.m, self.m_meta,
+                                               hp.beta1)
+            else:
+                self.ctx.quantize_fp8(grad, self.g8, self.grad_fmt, self.g_meta, self.cfg)
+            self.adam(hp)
+            return
         if not delayed:
             self.ctx.amax_scale(grad, self.grad_fmt, self.g_meta, self.cfg)
         if fused:

@@ -34,6 +34,14 @@ def test_bench_line_has_the_agreed_fields():
     r = d["roofline"]
     assert r["bound"] == "hbm" and r["unit"] == "GB/s" and r["peak"] == 8000.0
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-3 and 0 < r["frac"] < 1
+    # the default path is the speculative just-in-time one; bytes are what was moved, the algorithmic figure beside it
+    assert d["config"]["path"] == "spec" and d["config"]["algorithmic_bytes_per_param_step"] == 19
+    assert 17.0 <= d["config"]["bytes_per_param_step"] <= 20.0 and d["speculation"]["steps"] == 3
+    assert "jit" in d["other_paths"] and d["other_paths"]["jit"]["bytes_per_param_step"] == 19
+    # memory-only skeletons of the four kernels, timed on the same buffers
+    for name in ("amax", "cast", "adam_amax", "adam_update", "update_reads_only", "update_writes_only"):
+        assert d["ceilings"][name]["GBps"] > 0
+    assert 0 < d["kernels"]["adam_update"]["frac_of_skeleton"] <= 1.1
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == "params/s" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
     assert d["value"] > 100 * c["value"]                     # the GPU path, not the oracle, was timed as `value`
