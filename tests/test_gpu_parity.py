@@ -1078,10 +1078,11 @@ def test_shards_of_the_greedy_distribution_step_like_the_whole_model():
 # ---- randomised differential test -----------------------------------------------------------------------------
 def test_random_layouts_and_hyper_parameters_match_the_oracle():
     """Sixty seeded random cases: ragged tensor sizes, gradient scales over forty binades, hyper-parameters at and
-    between the ends of their ranges, every format, source type, moment-scale mode, both gradient scalings and both
-    auto-scaling rules.  FP8LM_RANDOM_CASES / FP8LM_RANDOM_SEED in the environment run more cases or other ones."""
+    between the ends of their ranges, every format, source type, moment-scale mode, both gradient scalings (the
+    just-in-time one also through the speculative call) and both auto-scaling rules.  FP8LM_RANDOM_CASES / FP8LM_RANDOM_SEED in the environment run more cases or other ones."""
     n_cases = int(os.environ.get("FP8LM_RANDOM_CASES", "60"))
     rng = np.random.default_rng(int(os.environ.get("FP8LM_RANDOM_SEED", "20231018")))
+    rng2 = np.random.default_rng(int(os.environ.get("FP8LM_RANDOM_SEED", "20231018")) + 1)    # draws added later: the cases above stay what they were
     dtypes = [torch.bfloat16, torch.float16, torch.float32]
     for case in range(n_cases):
         n_t = int(rng.integers(1, 7))
@@ -1119,12 +1120,13 @@ def test_random_layouts_and_hyper_parameters_match_the_oracle():
                                 wcopy=wcopy, stats=int(rng.integers(0, 2)) if (master_fmt, v_fmt) == (B.STATE_F16, B.STATE_F16) else 0,
                                 m_scale_mode=int(rng.integers(0, 3)), master_fmt=master_fmt, v_fmt=v_fmt)
             delayed = bool(rng.integers(0, 2)) and k > 0
+            speculative = bool(rng2.integers(0, 2)) and not delayed      # same results as just in time, by another route
             snaps = [P.Snapshot(st, grad, t) for t in ids]
             say(f"random case {case} step {k}: numels={numels} dtype={dtype} sigma={sig:g} fmt={grad_fmt} wcopy={wcopy} "
                 f"master={master_fmt} v={v_fmt} lr={hp.lr:g} b1={hp.beta1:g} b2={hp.beta2:g} eps={hp.eps:g} wd={hp.weight_decay:g} "
-                f"t={hp.step} v_scaled={hp.v_scaled} stats={hp.stats} mode={hp.m_scale_mode} delayed={delayed} mu_rule={mu_rule} "
+                f"t={hp.step} v_scaled={hp.v_scaled} stats={hp.stats} mode={hp.m_scale_mode} delayed={delayed} speculative={speculative} mu_rule={mu_rule} "
                 f"exempt={flags.tolist()}")
-            st.step(grad, hp, delayed=delayed)
+            st.step(grad, hp, delayed=delayed, speculative=speculative)
             torch.cuda.synchronize()
             P.check_step(st, [x for x in snaps if not flags[x.t]], hp, what=f"random case {case} step {k}", delayed=delayed)
             if flags.any():
