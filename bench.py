@@ -142,13 +142,15 @@ def main() -> int:
                          "a kernel of known size that profiler counters are scaled by")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the memory-only skeletons of the four kernels that are timed on the same buffers after the step")
-    ap.add_argument("--path", choices=["spec", "jit", "fused", "spec-fused", "single"], default="spec",
+    ap.add_argument("--path", choices=["spec", "jit", "fused", "spec-fused", "spec-m2", "single"], default="spec",
                     help="jit: amax pass + cast + two-pass Adam (19 B/param, the three entry points as they are); "
                          "spec: the same results through fp8lm_quantize_fp8, which casts with the predicted scale while "
                          "measuring the amax and casts again only the tensors whose scale changed (17 B/param + redone "
                          "tensors); fused: same results, the cast also does the Adam step's first pass (18 B/param, one "
-                         "GPU only); spec-fused: both (16 B/param + redone tensors); single: delayed gradient scaling + "
-                         "predicted first-moment scale (15 B/param, results differ: looser scales)")
+                         "GPU only); spec-fused: both (16 B/param + redone tensors); spec-m2: spec, and the Adam step "
+                         "through fp8lm_adam_step_fp8_m2, which drops the read-only pass for a second first-moment buffer "
+                         "(same results; 15 B/param + redone tensors; state 7 instead of 6 B/param); single: delayed "
+                         "gradient scaling + predicted first-moment scale (15 B/param, results differ: looser scales)")
     ap.add_argument("--grad-buffers", type=int, default=3,
                     help="number of gradient source buffers with independent draws that successive steps rotate through")
     ap.add_argument("--allreduce-steps", type=int, default=0, metavar="N",
@@ -183,7 +185,8 @@ def main() -> int:
     P = lay.n_params
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
     st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=args.spread,
-                        grad_buffer=True, arena_order=args.arena_order.split(",") if args.arena_order else None)
+                        grad_buffer=True, arena_order=args.arena_order.split(",") if args.arena_order else None,
+                        second_m=(args.path == "spec-m2" or not args.only_path))
     if args.chunk or args.blocks_per_cu or args.single_pass_min_chunks >= 0:
         st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 16,
                           (1 << 30) if args.single_pass_min_chunks < 0 else args.single_pass_min_chunks)
@@ -202,9 +205,9 @@ def main() -> int:
         synth.fill_gradients(gbuf, wl, args.seed, 1 + k)
     torch.cuda.synchronize()
 
-    base_bytes = {"jit": 19, "fused": 18, "single": 15, "spec": 17, "spec-fused": 16}     # before any tensor is cast twice
+    base_bytes = {"jit": 19, "fused": 18, "single": 15, "spec": 17, "spec-fused": 16, "spec-m2": 15}   # before anything is redone
     mode_of = {"jit": B.MSCALE_EXACT_PASS, "fused": B.MSCALE_FROM_CAST, "single": B.MSCALE_PREDICTED,
-               "spec": B.MSCALE_EXACT_PASS, "spec-fused": B.MSCALE_FROM_CAST}
+               "spec": B.MSCALE_EXACT_PASS, "spec-fused": B.MSCALE_FROM_CAST, "spec-m2": B.MSCALE_EXACT_PASS}
     step_no = [0]
 
     def run_steps(path, n):
@@ -213,12 +216,12 @@ def main() -> int:
             step_no[0] += 1
             hp = B.adam_hparams(wl.lr, step_no[0], exact=args.exact, stats=args.stats, m_scale_mode=mode_of[path])
             st.step(grads[step_no[0] % len(grads)], hp, delayed=(path == "single" and step_no[0] > 1),
-                    speculative=path.startswith("spec"))
+                    speculative=path.startswith("spec"), pair_m=(path == "spec-m2"))
 
     def timed(path, n):
         """(seconds, per-kernel timing, bytes per parameter and step actually moved, speculation totals of the region)."""
         torch.cuda.synchronize()
-        before = st.ctx.speculation_stats()
+        before, before_m = st.ctx.speculation_stats(), st.ctx.speculation_stats(moment=True)
         st.ctx.set_timing(True)
         st.ctx.get_timing()
         torch.cuda.synchronize()
@@ -228,17 +231,19 @@ def main() -> int:
         dt = time.perf_counter() - t0
         tm = st.ctx.get_timing()
         st.ctx.set_timing(False)
-        after = st.ctx.speculation_stats()
+        after, after_m = st.ctx.speculation_stats(), st.ctx.speculation_stats(moment=True)
         spec = {k: after[k] - before[k] for k in after}
-        # a tensor cast twice costs its 2 B/element read and 1 B/element write (3 + 1 with the moment read) once more
-        redo_bytes = (4 if path == "spec-fused" else 3) * spec["elems_redone"] / n
+        spec.update({"moment_" + k: after_m[k] - before_m[k] for k in after_m})
+        # a tensor cast twice costs its 2 B/element read and 1 B/element write (3 + 1 with the moment read) once more;
+        # a first moment computed twice its two 1 B/element reads and its 1 B/element write
+        redo_bytes = ((4 if path == "spec-fused" else 3) * spec["elems_redone"] + 3 * spec["moment_elems_redone"]) / n
         return dt, tm, base_bytes[path] + redo_bytes / P, spec
 
     run_steps(args.path, args.warmup)
     dt, timing, bytes_per_param, spec_totals = timed(args.path, args.steps)
     other_paths = {}
     if not args.only_path:
-        for path in ("jit", "spec", "fused", "spec-fused", "single"):
+        for path in ("jit", "spec", "fused", "spec-fused", "spec-m2", "single"):
             if path != args.path:
                 run_steps(path, 2)
                 n = min(args.steps, 10)
@@ -252,10 +257,15 @@ def main() -> int:
         n, ms = timing[name]
         if not n:
             continue
+        if name == "adam_amax" and args.path == "spec-m2":
+            # no read-only pass on this path: what is timed under this id is the repair of failed moment speculations
+            kernels["moment_repair"] = {"avg_ms": round(ms / args.steps, 4), "launches": n}
+            continue
         if name == "cast":
             # the cast is timed per step: a speculative step launches it twice (all tensors, then the ones to redo)
             per_step = ms / args.steps
-            moved = bytes_per_param - {"jit": 16, "fused": 14, "single": 12, "spec": 14, "spec-fused": 12}[args.path]
+            moved = (base_bytes[args.path] + (4 if args.path == "spec-fused" else 3) * spec_totals["elems_redone"] / args.steps / P
+                     - {"jit": 16, "fused": 14, "single": 12, "spec": 14, "spec-fused": 12, "spec-m2": 12}[args.path])
             kernels[name] = {"avg_ms": round(per_step, 4), "launches": n, "bytes_per_param": round(moved, 3),
                              "GBps": round(moved * P / (per_step * 1e-3) / 1e9, 1)}
             continue
@@ -281,12 +291,16 @@ def main() -> int:
                    "m_fmt": "e4m3", "v": "fp16 scaled", "master": "fp16 scaled", "wcopy": "e4m3",
                    "exact_div_sqrt": bool(args.exact), "path": args.path,
                    "bytes_per_param_step": round(bytes_per_param, 3), "algorithmic_bytes_per_param_step": 19,
-                   "gradient_buffers": len(grads), "placement": placement},
+                   "gradient_buffers": len(grads), "state_bytes_per_param": st.state_bytes_per_param + (1 if args.path == "spec-m2" else 0),
+                   "placement": placement},
         "step_GBps": round(bytes_per_param * P / (dt / args.steps) / 1e9, 1),
         "step_frac_of_peak": round(bytes_per_param * P / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
         "kernels": kernels,
         "speculation": ({"steps": spec_totals["calls"], "tensors_cast_twice_per_step": round(spec_totals["tensors_redone"] / max(1, spec_totals["calls"]), 2),
-                         "share_of_elements_cast_twice": round(spec_totals["elems_redone"] / max(1, spec_totals["calls"]) / P, 4)}
+                         "share_of_elements_cast_twice": round(spec_totals["elems_redone"] / max(1, spec_totals["calls"]) / P, 4),
+                         **({"moments_computed_twice_per_step": round(spec_totals["moment_tensors_redone"] / max(1, spec_totals["moment_calls"]), 2),
+                             "share_of_moment_elements_computed_twice": round(spec_totals["moment_elems_redone"] / max(1, spec_totals["moment_calls"]) / P, 4)}
+                            if args.path == "spec-m2" else {})}
                         if args.path.startswith("spec") else None),
         "other_paths": other_paths,
         "roofline": {"kernel": "adam_update_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,

@@ -372,6 +372,31 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* ctx,
                                  const fp8lm_adam_hparams* hp /*host*/, void* stream);
 
 /*
+ * fp8lm_adam_step_fp8 with m_scale_mode = EXACT_PASS, without its read-only first pass: the same results bit for bit
+ * -- m_out holds what fp8lm_adam_step_fp8 would have left in m, every metadata field is equal -- for one extra
+ * buffer.  The first moment is read from m_in and written to m_out (callers swap the two after every step; m_in is
+ * left untouched).  Its scale is first taken as the one already in m_meta (what the previous step's exact amax gave);
+ * the update pass measures the exact amax of the new moment anyway, and its epilogue computes the scale that amax
+ * demands by the rule of the first pass.  Where it differs from the prediction -- the amax crossed a power-of-two
+ * boundary, the first step -- the tensor's moment is computed once more from grad and m_in and stored with the right
+ * scale; the second moment, the master weights and the weight copy never depend on that scale.  Per step this moves
+ * 12 bytes per element plus 3 for the tensors that are repaired, instead of 14.
+ * Restrictions: default storage formats, hp->stats = 0, hp->m_scale_mode = EXACT_PASS (INVALID_ARGUMENT otherwise);
+ * m_in and m_out must not overlap over the tensors' extent (OVERLAP).
+ * fp8lm_get_moment_speculation_stats: as fp8lm_get_speculation_stats, for this entry point.
+ */
+fp8lm_status fp8lm_adam_step_fp8_m2(fp8lm_ctx* ctx,
+                                    const uint8_t* grad /*device*/, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta /*device*/,
+                                    const uint8_t* m_in /*device, read only*/, uint8_t* m_out /*device, written*/,
+                                    fp8lm_meta* m_meta /*device*/,
+                                    void* v /*device, in place*/, fp8lm_meta* v_meta /*device*/,
+                                    void* w /*device, in place*/, fp8lm_meta* w_meta /*device*/,
+                                    void* wcopy /*device, write only*/, fp8lm_meta* wcopy_meta /*device*/,
+                                    const fp8lm_adam_hparams* hp /*host*/, void* stream);
+fp8lm_status fp8lm_get_moment_speculation_stats(fp8lm_ctx* ctx, uint64_t* calls /*host*/, uint64_t* tensors_redone /*host*/,
+                                                uint64_t* elems_redone /*host*/, void* stream);
+
+/*
  * fp8lm_adam_step_fp8 for callers that cannot allocate device memory and therefore cannot hold a context:
  * code under HIP graph capture that must not call hipMalloc, tight serving or training loops, harnesses that
  * forbid allocation.  Same arithmetic, same kernels, same results, bit for bit; what a context keeps in

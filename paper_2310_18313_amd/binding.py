@@ -37,7 +37,8 @@ EXPORTS = [
     "fp8lm_create", "fp8lm_destroy", "fp8lm_set_tuning", "fp8lm_set_tensor_flags", "fp8lm_meta_init", "fp8lm_amax_scale",
     "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_cast_fp8_for_adam", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
     "fp8lm_quant_error_stats", "fp8lm_autoscale_broadcast", "fp8lm_set_mu", "fp8lm_memory_skeleton", "fp8lm_adam_step_fp8_static",
-    "fp8lm_quantize_fp8", "fp8lm_quantize_fp8_for_adam", "fp8lm_get_speculation_stats",
+    "fp8lm_quantize_fp8", "fp8lm_quantize_fp8_for_adam", "fp8lm_get_speculation_stats", "fp8lm_adam_step_fp8_m2",
+    "fp8lm_get_moment_speculation_stats",
     "fp8lm_init_master", "fp8lm_init_master_as", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
@@ -126,6 +127,8 @@ def lib() -> C.CDLL:
         L.fp8lm_quantize_fp8.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp]
         L.fp8lm_quantize_fp8_for_adam.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_float, vp]
         L.fp8lm_get_speculation_stats.argtypes = [vp, vp, vp, vp, vp]
+        L.fp8lm_get_moment_speculation_stats.argtypes = [vp, vp, vp, vp, vp]
+        L.fp8lm_adam_step_fp8_m2.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fp8lm_init_master.argtypes = [vp, vp, vp, vp, vp]
         L.fp8lm_init_master_as.argtypes = [vp, vp, vp, vp, C.c_int, vp]
         L.fp8lm_shared_scale.argtypes = [vp, vp, i32, vp, vp]
@@ -280,12 +283,26 @@ class Context:
                                                  C.addressof(cfg), _ptr(m), _ptr(m_meta), beta1, _stream(stream)),
                "fp8lm_quantize_fp8_for_adam")
 
-    def speculation_stats(self, stream=None) -> dict:
-        """Running totals of quantize_fp8 / quantize_fp8_for_adam on this context (synchronises the stream)."""
+    def speculation_stats(self, stream=None, moment: bool = False) -> dict:
+        """Running totals of quantize_fp8 / quantize_fp8_for_adam on this context, or with `moment` of
+        adam_step_fp8_m2 (synchronises the stream)."""
         vals = (C.c_uint64 * 3)()
-        _check(lib().fp8lm_get_speculation_stats(self._h, C.addressof(vals), C.addressof(vals) + 8, C.addressof(vals) + 16,
-                                                 _stream(stream)), "fp8lm_get_speculation_stats")
+        fn = lib().fp8lm_get_moment_speculation_stats if moment else lib().fp8lm_get_speculation_stats
+        _check(fn(self._h, C.addressof(vals), C.addressof(vals) + 8, C.addressof(vals) + 16, _stream(stream)),
+               "fp8lm_get_speculation_stats")
         return {"calls": int(vals[0]), "tensors_redone": int(vals[1]), "elems_redone": int(vals[2])}
+
+    def adam_step_fp8_m2(self, grad, grad_fmt, grad_meta, m_in, m_out, m_meta, v, v_meta, w, w_meta, wcopy, wcopy_meta,
+                         hp: AdamHparams, stream=None):
+        """adam_step_fp8 (exact first-moment scale) without its first pass: m is read from m_in and written to m_out."""
+        assert grad.element_size() == 1 and m_in.element_size() == 1 and m_out.element_size() == 1
+        assert v.element_size() == 2 and w.element_size() == 2
+        assert wcopy.element_size() == (1 if hp.wcopy == WCOPY_E4M3 else 2)
+        self._fits(grad, m_in, m_out, v, w, wcopy)
+        self._fits_meta(grad_meta, m_meta, v_meta, w_meta, wcopy_meta)
+        _check(lib().fp8lm_adam_step_fp8_m2(self._h, _ptr(grad), grad_fmt, _ptr(grad_meta), _ptr(m_in), _ptr(m_out),
+                                            _ptr(m_meta), _ptr(v), _ptr(v_meta), _ptr(w), _ptr(w_meta), _ptr(wcopy),
+                                            _ptr(wcopy_meta), C.addressof(hp), _stream(stream)), "fp8lm_adam_step_fp8_m2")
 
     def shared_scale(self, metas, stream=None) -> torch.Tensor:
         """Eq. 4: per-tensor minimum of the ranks' scales; returns a device fp32 array [n_tensors]."""

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kThreads) void init_master_cast_kernel(Tables tb, I
 struct AdamParams {
   const uint8_t* grad;
   const fp8lm_meta* grad_meta;
-  uint8_t* m;
+  uint8_t* m;              // first moment, written (and read, unless m_in points elsewhere)
   fp8lm_meta* m_meta;
   void* v;                 // FP16 (default) or E4M3
   fp8lm_meta* v_meta;
@@ -115,6 +115,9 @@ struct AdamParams {
   int32_t v_scaled;
   uint32_t v_fmax_bits;    // largest finite value of the second moment's storage format
   uint32_t w_fmax_bits;    // ... of the master weight's, 0 if that format carries no scale (BF16, FP32)
+  const uint8_t* m_in;     // where the first moment is read: m itself (in place), or the other buffer of a pair
+  int32_t speculative_m;   // the first-moment scale was predicted; the update pass's epilogue verifies it (see
+                           // AdamUpdateOp::finish)
 };
 
 // Chooses a stored scale from a magnitude bound; keeps the old one when the bound is 0 or not finite.
@@ -192,6 +195,23 @@ __global__ void adam_scales_from_cast_kernel(Tables tb, AdamParams p, int n) {
   if (t >= n || tb.desc[t].numel == 0) return;
   const uint32_t bits = tb.scratch[t].pend.amax_m_bits;
   adam_choose_scales<WCOPY>(p, tb.scratch[t].pend, t, bits >= 0x7F800000u ? __builtin_inff() : u2f(bits));
+}
+
+// Speculative first-moment scale (the update pass verifies it): the scale that the previous step's exact amax gives,
+// which is the one in the metadata unless that amax was zero or not finite.  The decision for the careful path cannot
+// wait for the exact amax either: it is taken from the bound fma(beta1, amax_deq(m), (1-beta1) * amax_deq(g)), which
+// no new |m| exceeds.  Keeps the scale the moment is stored with for the pass that repairs a failed speculation.
+template <int WCOPY>
+__global__ void adam_speculate_scales_kernel(Tables tb, AdamParams p, int n) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n || tb.desc[t].numel == 0) return;
+  Scratch& S = tb.scratch[t];
+  S.redo = 0;
+  S.old_scale = p.m_meta[t].scale;
+  S.old_inv = p.m_meta[t].inv_scale;
+  adam_choose_scales<WCOPY>(p, S.pend, t, p.m_meta[t].amax);
+  const float Bm = __builtin_fmaf(p.b1, p.m_meta[t].amax_deq, p.omb1 * p.grad_meta[t].amax_deq);
+  if (!(Bm < 1.0995116e12f)) S.pend.careful = 1u;      // 2^40, as in adam_choose_scales
 }
 
 // ---- pass A: exact amax of the new first moment, then all four scales ---------------------------
@@ -387,7 +407,7 @@ struct AdamUpdateOp {
   // one element with every special case handled (NaN codes, infinities, fp32 overflow)
   __device__ __forceinline__ void one_careful(long long i) {
     const float g = fp8_to_f32<GFMT>(p.grad[i]) * inv_sg;
-    const float m0 = fp8_to_f32<kE4M3>(p.m[i]) * inv_sm;
+    const float m0 = fp8_to_f32<kE4M3>(p.m_in[i]) * inv_sm;
     uint16_t* pv = static_cast<uint16_t*>(p.v);
     uint16_t* pw = static_cast<uint16_t*>(p.w);
     const float v0 = f16_to_f32(pv[i]) * inv_sv;
@@ -426,8 +446,8 @@ struct AdamUpdateOp {
       const long long a = pos0 + u * kTile, b = a + kTile / 2;
       ga[u] = ld8<kNtLoadRO>(p.grad + a);
       gb[u] = ld8<kNtLoadRO>(p.grad + b);
-      ma[u] = ld8<kNtLoadRW>(p.m + a);
-      mb[u] = ld8<kNtLoadRW>(p.m + b);
+      ma[u] = ld8<kNtLoadRW>(p.m_in + a);
+      mb[u] = ld8<kNtLoadRW>(p.m_in + b);
       va[u] = ld16<kNtLoadRW>(pv + a);
       vb[u] = ld16<kNtLoadRW>(pv + b);
       wa[u] = ld16<kNtLoadRW>(pw + a);
@@ -471,7 +491,7 @@ struct AdamUpdateOp {
     for (int u = 0; u < UN; ++u) {
       const long long pos = pos0 + u * kTile;
       g[u] = ld16<kNtLoadRO>(p.grad + pos);
-      m[u] = ld16<kNtLoadRW>(p.m + pos);
+      m[u] = ld16<kNtLoadRW>(p.m_in + pos);
       va[u] = ld16<kNtLoadRW>(pv + pos);
       vb[u] = ld16<kNtLoadRW>(pv + pos + 8);
       wa[u] = ld16<kNtLoadRW>(pw + pos);
@@ -507,7 +527,7 @@ struct AdamUpdateOp {
       uint16_t* pw = static_cast<uint16_t*>(p.w);
       for (int j = 0; j < valid; ++j) {
         const long long i = pos + j;
-        const Quad o = quad<false>(p.grad[i], p.m[i], pv[i], 0u, pw[i], 0u);
+        const Quad o = quad<false>(p.grad[i], p.m_in[i], pv[i], 0u, pw[i], 0u);
         p.m[i] = (uint8_t)o.m;
         pv[i] = (uint16_t)o.v01;
         pw[i] = (uint16_t)o.w01;
@@ -569,9 +589,22 @@ struct AdamUpdateOp {
   }
 
   __device__ void finish(int t, float A_v, float A_w, float A_mc, uint32_t nfb, const unsigned long long* c) {
-    const Scratch::Pending& P = tb.scratch[t].pend;
+    Scratch::Pending& P = tb.scratch[t].pend;
     const float A_m = A_mc;    // measured by this pass on both paths (equals what pass A saw)
     uint32_t m_nf = nfb & 3u;
+    if (p.speculative_m) {
+      // The moment was stored with a predicted scale.  The scale its exact amax demands, by the rule pass A applies:
+      // equal -> what was stored is the just-in-time result; different -> the tensor's moment is computed again with
+      // the right scale from the untouched inputs (grad and the other buffer of the pair); v, w and the copy never
+      // depend on it.  Either way the metadata gets the exact scale and the flags that go with it.
+      float sm = 0.0f, ism = 0.0f;
+      uint32_t fm = 0;
+      refresh_scale(kBitsE4M3Max, m_nf ? __builtin_inff() : A_m, 0, tb.scratch[t].old_scale, tb.scratch[t].old_inv, sm, ism, fm);
+      tb.scratch[t].redo = sm != P.sm ? 1u : 0u;
+      P.sm = sm;
+      P.ism = ism;
+      P.fm = fm;
+    }
     auto enc8 = [](float x) { return encode1_fp8<kE4M3>(x); };
     auto dec8 = [](uint32_t cc) { return fp8_to_f32<kE4M3>(cc); };
     auto enc16 = [](float x) { return encode1_f16(x); };
@@ -594,6 +627,58 @@ template <int GFMT, int WCOPY, bool FAST, bool STATS>
 __global__ __launch_bounds__(kThreads) void adam_update_kernel(Tables tb, AdamParams p) {
   AdamUpdateOp<GFMT, WCOPY, FAST, STATS> op(p, tb);
   walk_chunks<FP8LM_UN_UPDATE>(tb, op);
+}
+
+// ---- repair of a failed first-moment speculation ---------------------------------------------------
+// Walks the chunk list of the marked tensors: m' = fma(beta1, m_in / s_m, (1-beta1) * g / s_g) once more, stored to
+// m with the exact scale that the update pass's epilogue left in the scratch.
+template <int GFMT>
+struct AdamMomentRedoOp {
+  const AdamParams& p;
+  const Tables& tb;
+  float inv_sg, inv_sm, sm;
+  bool careful;
+  __device__ AdamMomentRedoOp(const AdamParams& p_, const Tables& tb_) : p(p_), tb(tb_) {}
+  __device__ __forceinline__ void begin(int t, const TensorDesc&) {
+    inv_sg = p.grad_meta[t].inv_scale;
+    inv_sm = tb.scratch[t].old_inv;                 // the scale m_in is stored with (m_meta already holds the new one)
+    sm = tb.scratch[t].pend.sm;
+    careful = tb.scratch[t].pend.careful != 0;
+  }
+  __device__ __forceinline__ float moment(float dg, float dm) const {
+    return __builtin_fmaf(p.b1, dm * inv_sm, p.omb1 * (dg * inv_sg));
+  }
+  __device__ __forceinline__ uint32_t word(uint32_t gw, uint32_t mw) const {
+    const float2_t g01 = fp8x2_to_f32<GFMT, false>(gw), g23 = fp8x2_to_f32<GFMT, true>(gw);
+    const float2_t m01 = fp8x2_to_f32<kE4M3, false>(mw), m23 = fp8x2_to_f32<kE4M3, true>(mw);
+    return encode4_fp8<kE4M3>(moment(g01.x, m01.x) * sm, moment(g01.y, m01.y) * sm, moment(g23.x, m23.x) * sm,
+                              moment(g23.y, m23.y) * sm);
+  }
+  __device__ __forceinline__ bool fast() const { return !careful; }
+  template <int UN> __device__ __forceinline__ void tiles(long long pos0) {
+    const long long pos = pos0 + threadIdx.x * kGroup;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const uint4 g = ld16<kNtLoadRO>(p.grad + pos + u * kTile), m = ld16<kNtLoadRO>(p.m_in + pos + u * kTile);
+      st16<kNtStoreWO>(p.m + pos + u * kTile, make_uint4(word(g.x, m.x), word(g.y, m.y), word(g.z, m.z), word(g.w, m.w)));
+    }
+  }
+  __device__ __forceinline__ void full_group(long long pos) { tiles<1>(pos - (long long)threadIdx.x * kGroup); }
+  __device__ __forceinline__ void group(long long pos, int valid) {
+    for (int j = 0; j < valid; ++j) {
+      const long long i = pos + j;
+      p.m[i] = (uint8_t)encode1_fp8_careful<kE4M3>(moment(fp8_to_f32<GFMT>(p.grad[i]), fp8_to_f32<kE4M3>(p.m_in[i])) * sm);
+    }
+  }
+  using Stats = BlockStats<1, 0>;
+  __device__ __forceinline__ void flush(int, const TensorDesc&, int) {}      // nothing to reduce: the metadata is complete
+  __device__ void finalize(int, const TensorDesc&, const Stats&) {}
+};
+
+template <int GFMT>
+__global__ __launch_bounds__(kThreads) void adam_moment_redo_kernel(Tables tb, AdamParams p) {
+  AdamMomentRedoOp<GFMT> op(p, tb);
+  walk_chunks<2>(tb, op);
 }
 
 // ---- pass B for the other storage formats of the precision-decoupling study ----------------------

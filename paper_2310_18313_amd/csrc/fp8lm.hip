@@ -364,8 +364,8 @@ fp8lm_status fp8lm_create(fp8lm_ctx** out, const fp8lm_tensor* tensors, int32_t 
     if (e == hipSuccess) e = hipMemset(c->d_partials, 0, records * sizeof(Partial));
     if (e == hipSuccess) e = hipMalloc((void**)&c->d_redo_count, sizeof(int32_t));
     if (e == hipSuccess) e = hipMemset(c->d_redo_count, 0, sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc((void**)&c->d_spec_totals, 3 * sizeof(unsigned long long));
-    if (e == hipSuccess) e = hipMemset(c->d_spec_totals, 0, 3 * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_spec_totals, 6 * sizeof(unsigned long long));     // gradient, first moment
+    if (e == hipSuccess) e = hipMemset(c->d_spec_totals, 0, 6 * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) { g_hip_error = hipGetErrorString(e); st = FP8LM_ERR_HIP; }
   }
@@ -734,7 +734,8 @@ static fp8lm_status adam_args_ok(const uint8_t* grad, fp8lm_fmt grad_fmt, const 
 
 static fp8lm_status adam_launch(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta,
                                 uint8_t* m, fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta, void* w, fp8lm_meta* w_meta,
-                                void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp, hipStream_t s);
+                                void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp, hipStream_t s,
+                                const uint8_t* m_in = nullptr);
 
 fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta,
                                  uint8_t* m, fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta, void* w,
@@ -751,10 +752,13 @@ fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gr
 }
 
 // The launches of one Adam step on the tables `c` points to (a context's own, or the fixed device array).
+// m_in: null for the in-place step; otherwise the buffer the first moment is read from, and its scale is speculated.
 static fp8lm_status adam_launch(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta,
                                 uint8_t* m, fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta, void* w, fp8lm_meta* w_meta,
-                                void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp, hipStream_t s) {
+                                void* wcopy, fp8lm_meta* wcopy_meta, const fp8lm_adam_hparams* hp, hipStream_t s,
+                                const uint8_t* m_in) {
   const bool variant = hp->master_fmt != FP8LM_STATE_F16 || hp->v_fmt != FP8LM_STATE_F16;
+  const bool spec_m = m_in != nullptr;
 
   AdamParams p{};
   p.grad = grad; p.grad_meta = grad_meta; p.m = m; p.m_meta = m_meta; p.v = v; p.v_meta = v_meta;
@@ -772,11 +776,18 @@ static fp8lm_status adam_launch(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gra
   p.v_scaled = (hp->v_scaled || hp->v_fmt == FP8LM_STATE_E4M3) ? 1 : 0;
   p.v_fmax_bits = hp->v_fmt == FP8LM_STATE_E4M3 ? kBitsE4M3Max : kBitsF16Max;
   p.w_fmax_bits = hp->master_fmt == FP8LM_STATE_F16 ? kBitsF16Max : (hp->master_fmt == FP8LM_STATE_E4M3 ? kBitsE4M3Max : 0u);
+  p.m_in = spec_m ? m_in : m;
+  p.speculative_m = spec_m ? 1 : 0;
 
   const bool stats = hp->stats != 0, fast = hp->exact == 0;
   const Tables tb = tables_of(c);
   const bool e5 = grad_fmt == FP8LM_E5M2, q8 = hp->wcopy == FP8LM_WCOPY_E4M3;
-  if (hp->m_scale_mode == FP8LM_MSCALE_FROM_CAST) {
+  if (spec_m) {
+    Timed tm(c, s, FP8LM_K_SCALARS);
+    const dim3 gs((c->n_tensors + 255) / 256), bs(256);
+    if (q8) hipLaunchKernelGGL((adam_speculate_scales_kernel<FP8LM_WCOPY_E4M3>), gs, bs, 0, s, tb, p, c->n_tensors);
+    else hipLaunchKernelGGL((adam_speculate_scales_kernel<FP8LM_WCOPY_BF16>), gs, bs, 0, s, tb, p, c->n_tensors);
+  } else if (hp->m_scale_mode == FP8LM_MSCALE_FROM_CAST) {
     const fp8lm_ctx::Fused f = c->fused;
     c->fused.valid = false;
     if (!f.valid || f.grad != grad || f.m != m || f.m_meta != m_meta || f.b1 != p.b1 || f.fmt != (int)grad_fmt)
@@ -809,7 +820,64 @@ static fp8lm_status adam_launch(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt gra
     else if (q8) launch_update<kE4M3, FP8LM_WCOPY_E4M3>(c, s, p, fast, stats);
     else launch_update<kE4M3, FP8LM_WCOPY_BF16>(c, s, p, fast, stats);
   }
+  st = after_launch();
+  if (st != FP8LM_OK || !spec_m) return st;
+  // tensors whose first-moment scale turned out different: their chunk list, then the moment once more
+  {
+    Timed tm(c, s, FP8LM_K_SCALARS);
+    hipLaunchKernelGGL(redo_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, c->d_desc, c->d_scratch, c->d_redo_desc,
+                       c->n_tensors, c->d_redo_count, c->d_spec_totals + 3);
+    hipLaunchKernelGGL(redo_fill_kernel, dim3(std::min<int>(c->n_tensors, 1024)), dim3(256), 0, s, c->d_redo_desc,
+                       c->d_redo_chunk_tensor, c->n_tensors);
+    st = after_launch();
+    if (st != FP8LM_OK) return st;
+  }
+  {
+    const Tables rt = redo_tables_of(c);
+    const dim3 g(grid_of(c)), b(kThreads);
+    Timed tm(c, s, FP8LM_K_ADAM_AMAX);
+    if (e5) hipLaunchKernelGGL((adam_moment_redo_kernel<kE5M2>), g, b, 0, s, rt, p);
+    else hipLaunchKernelGGL((adam_moment_redo_kernel<kE4M3>), g, b, 0, s, rt, p);
+  }
   return after_launch();
+}
+
+fp8lm_status fp8lm_adam_step_fp8_m2(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt grad_fmt, const fp8lm_meta* grad_meta,
+                                    const uint8_t* m_in, uint8_t* m_out, fp8lm_meta* m_meta, void* v, fp8lm_meta* v_meta,
+                                    void* w, fp8lm_meta* w_meta, void* wcopy, fp8lm_meta* wcopy_meta,
+                                    const fp8lm_adam_hparams* hp, void* stream) {
+  if (!c) return FP8LM_ERR_INVALID_ARGUMENT;
+  const fp8lm_status ok = adam_args_ok(grad, grad_fmt, grad_meta, m_out, m_meta, v, v_meta, w, w_meta, wcopy, wcopy_meta, hp,
+                                       c->n_chunks > 0);
+  if (ok != FP8LM_OK) return ok;
+  // the exact-amax scale only, default storage formats, no element counters (they would have to be recounted)
+  if (hp->m_scale_mode != FP8LM_MSCALE_EXACT_PASS || hp->master_fmt != FP8LM_STATE_F16 || hp->v_fmt != FP8LM_STATE_F16 || hp->stats)
+    return FP8LM_ERR_INVALID_ARGUMENT;
+  if (c->n_chunks == 0) return FP8LM_OK;
+  if (!m_in || m_in == m_out) return FP8LM_ERR_INVALID_ARGUMENT;
+  if (!aligned16(m_in)) return FP8LM_ERR_MISALIGNED;
+  {
+    // the two buffers must not share an element of any tensor
+    long long extent = 0;
+    for (const fp8lm_tensor& T : c->tensors) extent = std::max<long long>(extent, T.numel > 0 ? T.offset + T.numel : 0);
+    const uintptr_t a = reinterpret_cast<uintptr_t>(m_in), b = reinterpret_cast<uintptr_t>(m_out);
+    if (a < b + (uintptr_t)extent && b < a + (uintptr_t)extent) return FP8LM_ERR_OVERLAP;
+  }
+  DeviceGuard guard(c->device);
+  c->fused.valid = false;
+  return adam_launch(c, grad, grad_fmt, grad_meta, m_out, m_meta, v, v_meta, w, w_meta, wcopy, wcopy_meta, hp,
+                     (hipStream_t)stream, m_in);
+}
+
+fp8lm_status fp8lm_get_moment_speculation_stats(fp8lm_ctx* c, uint64_t* calls, uint64_t* tensors_redone,
+                                                uint64_t* elems_redone, void* stream) {
+  if (!c || !calls || !tensors_redone || !elems_redone) return FP8LM_ERR_INVALID_ARGUMENT;
+  DeviceGuard guard(c->device);
+  unsigned long long h[3] = {0, 0, 0};
+  HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+  HIP_TRY(hipMemcpy(h, c->d_spec_totals + 3, sizeof(h), hipMemcpyDeviceToHost));
+  *calls = h[0]; *tensors_redone = h[1]; *elems_redone = h[2];
+  return FP8LM_OK;
 }
 
 // ---- the Adam step without a context: tables, scales and reduction records in the fixed device array ----------

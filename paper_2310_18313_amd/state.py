@@ -16,10 +16,12 @@ class OptimizerState:
     def __init__(self, tensors, total_elems: int, cfg: B.AutoscaleCfg, device: int = 0,
                  grad_fmt: int = B.E5M2, wcopy: int = B.WCOPY_E4M3, spread: bool = False,
                  grad_buffer: bool = False, master_fmt: int = B.STATE_F16, v_fmt: int = B.STATE_F16,
-                 share_with: "OptimizerState" = None, arena_order=None):
+                 share_with: "OptimizerState" = None, arena_order=None, second_m: bool = False):
         """`share_with`: another state over the same flat buffers.  Parameter groups (say, no weight decay on
         biases and LayerNorm weights) are one state each, over disjoint tensor lists of the same buffers; each
-        has its own context and metadata and is stepped with its own hyper-parameters."""
+        has its own context and metadata and is stepped with its own hyper-parameters.
+        `second_m`: a second first-moment buffer (1 B/param more), so that `step(..., pair_m=True)` can run the Adam
+        step without its read-only pass (fp8lm_adam_step_fp8_m2); `m` always names the buffer that holds the moment."""
         dev = torch.device(f"cuda:{device}")
         self.tensors = list(tensors)
         self.total = int(total_elems)
@@ -36,13 +38,14 @@ class OptimizerState:
         # set (see placement.py): v (+ the bf16 gradient source) | w | m, FP8 gradient, weight copy.
         plan = [[("v", n, state_dtype[v_fmt])] + ([("grad", n, torch.bfloat16)] if grad_buffer else []),
                 [("w", n, state_dtype[master_fmt])],
-                [("m", n, torch.uint8), ("g8", n, torch.uint8), ("wq", n, qdt)]]
+                [("m", n, torch.uint8), ("g8", n, torch.uint8), ("wq", n, qdt)] + ([("m_other", n, torch.uint8)] if second_m else [])]
         self.placement = {}
         if share_with is not None:
             o = share_with
             assert (o.grad_fmt, o.wcopy_kind, o.master_fmt, o.v_fmt) == (grad_fmt, wcopy, master_fmt, v_fmt)
             assert o.g8.numel() >= n
             bufs = dict(g8=o.g8, m=o.m, v=o.v, w=o.w, wq=o.wq)
+            assert not second_m, "parameter groups share one first-moment buffer"
             if o.grad is not None:
                 bufs["grad"] = o.grad
             self.spread = o.spread
@@ -70,6 +73,7 @@ class OptimizerState:
             self.placement = {"arena_bytes": end, "order": [name for name, _, _ in items]}
         self.g8, self.m, self.v, self.w, self.wq = bufs["g8"], bufs["m"], bufs["v"], bufs["w"], bufs["wq"]
         self.grad = bufs.get("grad")       # bf16 gradient source, only if asked for
+        self.m_other = bufs.get("m_other")  # the other buffer of the first-moment pair, only if asked for
         self.g_meta = self.ctx.new_meta(cfg)
         self.m_meta = self.ctx.new_meta(cfg)
         self.v_meta = self.ctx.new_meta(cfg)
@@ -95,14 +99,26 @@ class OptimizerState:
         self.ctx.adam_step_fp8(self.g8, self.grad_fmt, self.g_meta, self.m, self.m_meta, self.v, self.v_meta,
                                self.w, self.w_meta, self.wq, self.q_meta, hp)
 
-    def step(self, grad: torch.Tensor, hp: B.AdamHparams, delayed: bool = False, speculative: bool = False) -> None:
+    def step(self, grad: torch.Tensor, hp: B.AdamHparams, delayed: bool = False, speculative: bool = False,
+             pair_m: bool = False) -> None:
         """One pass of the whole hot path: amax + scale, FP8 cast, FP8 Adam, from a bf16, fp16 or fp32
         gradient buffer.  With `delayed` the
         gradient is quantised in a single pass with the scale of the preceding steps.  With
         hp.m_scale_mode == MSCALE_FROM_CAST the cast also does the Adam step's first pass.  With `speculative` the
         just-in-time quantisation goes through quantize_fp8 (same results; tensors whose scale does not change are
-        read once)."""
+        read once).  With `pair_m` (state created with second_m) the Adam step goes through adam_step_fp8_m2 (same
+        results; no read-only pass; the first moment moves to the other buffer of the pair)."""
         fused = hp.m_scale_mode == B.MSCALE_FROM_CAST
+        if pair_m:
+            assert self.m_other is not None and not fused and not delayed
+            if speculative:
+                self.ctx.quantize_fp8(grad, self.g8, self.grad_fmt, self.g_meta, self.cfg)
+            else:
+                self.quantize_grad(grad)
+            self.ctx.adam_step_fp8_m2(self.g8, self.grad_fmt, self.g_meta, self.m, self.m_other, self.m_meta, self.v,
+                                      self.v_meta, self.w, self.w_meta, self.wq, self.q_meta, hp)
+            self.m, self.m_other = self.m_other, self.m
+            return
         if speculative:
             assert not delayed
             if fused:

@@ -133,3 +133,58 @@ def test_speculation_with_many_small_tensors_and_every_launch_shape():
             assert torch.equal(ma, mb), (tuning, step)
         s = ctx.speculation_stats()
         assert s["calls"] == 4 and lay.n_tensors < s["tensors_redone"] < 4 * lay.n_tensors
+
+
+@pytest.mark.parametrize("grad_fmt,wcopy,exact", [(B.E5M2, B.WCOPY_E4M3, 1), (B.E4M3, B.WCOPY_BF16, 1), (B.E5M2, B.WCOPY_E4M3, 0)])
+def test_adam_step_with_a_pair_of_moment_buffers_equals_the_two_pass_step(grad_fmt, wcopy, exact):
+    """fp8lm_adam_step_fp8_m2 (speculated first-moment scale, repaired where it fails) against fp8lm_adam_step_fp8 with
+    the exact pass: every payload byte and every metadata byte, over steps whose gradients jump by factors of 8 and
+    1/16 (the moment's amax crosses binades: repairs), stay put (no repair), vanish, and carry a NaN; the first
+    state is also held to the oracle lock-step."""
+    from paper_2310_18313_amd.state import OptimizerState
+    lay = _layout()
+    wl = synth.Workload("pair-m", lay, lr=1e-3, sigma=None, ramp_steps=4)
+    plain, w0 = P.make_state(wl, 23, grad_fmt, wcopy)
+    cfg = plain.cfg
+    pair = OptimizerState(lay.tensors(), lay.total, cfg, 0, grad_fmt, wcopy, second_m=True)
+    pair.init_master(w0)
+    ids = list(range(lay.n_tensors))
+    grad = torch.zeros(max(lay.total, 16), dtype=torch.bfloat16, device=DEV)
+    factors = [1.0, 1.0, 1.0, 8.0, 8.0, 1.0 / 16, 1.0, 0.0, 1.0, 1.0, 1.0, 1.0]
+    repaired_any = held_any = False
+    for step, f in enumerate(factors, 1):
+        synth.fill_gradients(grad, wl, 23, min(step, 3))
+        grad *= f
+        if step == 10:
+            off6, n6 = lay.tensors()[6]
+            grad[off6 + 777] = float("nan")
+        hp = B.adam_hparams(wl.lr, step, wcopy=wcopy, exact=exact)
+        snaps = [P.Snapshot(plain, grad, t) for t in ids]
+        before = pair.ctx.speculation_stats(moment=True)
+        say(f"pair of moment buffers: fmt={grad_fmt} wcopy={wcopy} exact={exact} step={step} factor={f}")
+        plain.step(grad, hp)
+        pair.step(grad, hp, pair_m=True, speculative=bool(step % 2))
+        torch.cuda.synchronize()
+        after = pair.ctx.speculation_stats(moment=True)
+        redone = after["tensors_redone"] - before["tensors_redone"]
+        assert after["calls"] == before["calls"] + 1 and 0 <= redone <= 7
+        repaired_any |= redone > 0
+        held_any |= redone == 0
+        if step in (1, 4):
+            assert redone > 0, step                      # zero state; the jump up (a drop only decays the moment by 10 % a step)
+        if exact:
+            P.check_step(plain, snaps, hp, what=f"plain step {step}")
+        for k in ("g8", "m", "v", "w", "wq", "g_meta", "m_meta", "v_meta", "w_meta", "q_meta"):
+            a, b = getattr(plain, k), getattr(pair, k)
+            if a.element_size() == 2:
+                a, b = a.view(torch.int16), b.view(torch.int16)
+            assert torch.equal(a, b), (step, k)
+    assert repaired_any and held_any
+    # argument errors: the same buffer twice, overlapping buffers, the element counters, another scale mode
+    hp = B.adam_hparams(wl.lr, 99, wcopy=wcopy)
+    args = lambda mi, mo, h: pair.ctx.adam_step_fp8_m2(pair.g8, grad_fmt, pair.g_meta, mi, mo, pair.m_meta, pair.v, pair.v_meta,
+                                                        pair.w, pair.w_meta, pair.wq, pair.q_meta, h)
+    for mi, mo, h in ((pair.m, pair.m, hp), (pair.m, pair.m[16:], hp), (pair.m, pair.m_other, B.adam_hparams(wl.lr, 99, wcopy=wcopy, stats=1)),
+                      (pair.m, pair.m_other, B.adam_hparams(wl.lr, 99, wcopy=wcopy, m_scale_mode=B.MSCALE_PREDICTED))):
+        with pytest.raises((B.Fp8lmError, ValueError)):
+            args(mi, mo, h)
