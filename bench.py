@@ -17,6 +17,7 @@ peak, the bandwidth that memory-only skeletons of the same kernels reach on the 
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -160,6 +161,8 @@ def main() -> int:
                     help="place the buffers in different HBM regions with placement.SpreadAllocator (it briefly takes all "
                          "free device memory; measurably faster for states of 0.5e9 to 10e9 parameters).  Default: one "
                          "allocation with the buffers carved out one after the other, as a caller of the C ABI would")
+    ap.add_argument("--no-spread-compare", action="store_true",
+                    help="do not repeat the measurement with --spread placement after the headline run")
     ap.add_argument("--arena-order", default="", help="comma-separated buffer names (v,grad,w,m,g8,wq) in the order they are "
                     "carved out of the one allocation")
     ap.add_argument("--graph", action="store_true",
@@ -391,8 +394,46 @@ def main() -> int:
             out["step_frac_of_skeletons"] = round(path_ms / ms_per_step, 4)
         elif args.path == "spec":       # no separate amax pass; tensors cast twice are not in the skeleton sum
             out["step_frac_of_skeletons"] = round((path_ms - ceilings["amax"]["avg_ms"]) / ms_per_step, 4)
-    del st, grad, grads
+    shapes = bufs = views = gbuf = None       # every view of the arena has to go before its memory does
+    del st, grad, grads, shapes, bufs, views, gbuf
+    gc.collect()
     torch.cuda.empty_cache()
+    if not args.spread and not args.no_spread_compare and lay.total >= (1 << 28):
+        # The same path once more with the buffers placed in different HBM regions (what --spread does): printed
+        # beside the headline, never as the headline, because that allocator briefly takes all free device memory.
+        st2 = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=True, grad_buffer=True,
+                             second_m=(args.path == "spec-m2"))
+        synth.fill_weights(st2.grad, lay, args.seed)
+        st2.init_master(st2.grad)
+        torch.cuda.synchronize()
+        st2.grad.zero_()
+        grads2 = [st2.grad] + [torch.zeros_like(st2.grad) for _ in range(max(1, args.grad_buffers) - 1)]
+        for k, gbuf in enumerate(grads2):
+            synth.fill_gradients(gbuf, wl, args.seed, 1 + k)
+
+        def steps2(first, n):
+            for i in range(first, first + n):
+                hp = B.adam_hparams(wl.lr, i, exact=args.exact, stats=args.stats, m_scale_mode=mode_of[args.path])
+                st2.step(grads2[i % len(grads2)], hp, delayed=(args.path == "single" and i > 1),
+                         speculative=args.path.startswith("spec"), pair_m=(args.path == "spec-m2"))
+
+        steps2(1, args.warmup)
+        torch.cuda.synchronize()
+        st2.ctx.set_timing(True)
+        st2.ctx.get_timing()
+        n2 = min(args.steps, 10)
+        t0 = time.perf_counter()
+        steps2(1 + args.warmup, n2)
+        torch.cuda.synchronize()
+        dt2 = (time.perf_counter() - t0) / n2
+        tm2 = st2.ctx.get_timing()
+        st2.ctx.set_timing(False)
+        upd = tm2["adam_update"][1] / max(1, tm2["adam_update"][0])
+        out["spread_allocation"] = {"spread": st2.spread, "ms_per_step": round(dt2 * 1e3, 3), "params_per_s": P / dt2,
+                                    "adam_update_avg_ms": round(upd, 4),
+                                    "adam_update_frac_of_peak": round(12 * P / (upd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del st2, grads2
+        torch.cuda.empty_cache()
     if extra:
         out["allreduce_steps"] = extra
     if not args.no_cpu_baseline:

@@ -217,13 +217,13 @@ def check_step(st, snaps, hp: B.AdamHparams, what: str = "", quantize_only: bool
 
 def make_state(wl: synth.Workload, seed: int, grad_fmt=B.E5M2, wcopy=B.WCOPY_E4M3, hist_window=None,
                ramp_steps=None, device=0, master_fmt=B.STATE_F16, v_fmt=B.STATE_F16, mu_rule=B.MU_SET_HALF,
-               mu_min_exp=-1):
+               mu_min_exp=-1, second_m=False):
     """State on the GPU with master weights initialised from the seeded bf16 weights."""
     from paper_2310_18313_amd.state import OptimizerState
     cfg = B.autoscale_cfg(ramp_steps=ramp_steps or wl.ramp_steps, hist_window=hist_window or wl.hist_window,
                           mu_rule=mu_rule, mu_min_exp=mu_min_exp)
     st = OptimizerState(wl.layout.tensors(), wl.layout.total, cfg, device, grad_fmt, wcopy, master_fmt=master_fmt,
-                        v_fmt=v_fmt)
+                        v_fmt=v_fmt, second_m=second_m)
     w0 = torch.zeros(max(wl.layout.total, 16), dtype=torch.bfloat16, device=f"cuda:{device}")
     synth.fill_weights(w0, wl.layout, seed)
     st.init_master(w0)

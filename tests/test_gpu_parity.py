@@ -1103,7 +1103,7 @@ def test_random_layouts_and_hyper_parameters_match_the_oracle():
             v_fmt = int(rng.choice([B.STATE_F16, B.STATE_E4M3]))
         mu_rule = int(rng.integers(0, 2))
         st, _ = P.make_state(wl, case, grad_fmt, wcopy, master_fmt=master_fmt, v_fmt=v_fmt, mu_rule=mu_rule,
-                             mu_min_exp=int(rng.integers(-5, 0)))
+                             mu_min_exp=int(rng.integers(-5, 0)), second_m=True)
         flags = rng.integers(0, 2, n_t).astype(np.uint32) if rng.random() < 0.3 else np.zeros(n_t, dtype=np.uint32)
         st.ctx.set_tensor_flags(flags)               # before the tuning call: the flags must survive the table rebuild
         if rng.random() < 0.5:
@@ -1121,12 +1121,15 @@ def test_random_layouts_and_hyper_parameters_match_the_oracle():
                                 m_scale_mode=int(rng.integers(0, 3)), master_fmt=master_fmt, v_fmt=v_fmt)
             delayed = bool(rng.integers(0, 2)) and k > 0
             speculative = bool(rng2.integers(0, 2)) and not delayed      # same results as just in time, by another route
+            # ... and so has the Adam step with the exact moment scale: through the pair of first-moment buffers
+            pair_m = (bool(rng2.integers(0, 2)) and not delayed and (master_fmt, v_fmt) == (B.STATE_F16, B.STATE_F16)
+                      and hp.stats == 0 and hp.m_scale_mode == B.MSCALE_EXACT_PASS)
             snaps = [P.Snapshot(st, grad, t) for t in ids]
             say(f"random case {case} step {k}: numels={numels} dtype={dtype} sigma={sig:g} fmt={grad_fmt} wcopy={wcopy} "
                 f"master={master_fmt} v={v_fmt} lr={hp.lr:g} b1={hp.beta1:g} b2={hp.beta2:g} eps={hp.eps:g} wd={hp.weight_decay:g} "
-                f"t={hp.step} v_scaled={hp.v_scaled} stats={hp.stats} mode={hp.m_scale_mode} delayed={delayed} speculative={speculative} mu_rule={mu_rule} "
+                f"t={hp.step} v_scaled={hp.v_scaled} stats={hp.stats} mode={hp.m_scale_mode} delayed={delayed} speculative={speculative} pair_m={pair_m} mu_rule={mu_rule} "
                 f"exempt={flags.tolist()}")
-            st.step(grad, hp, delayed=delayed, speculative=speculative)
+            st.step(grad, hp, delayed=delayed, speculative=speculative, pair_m=pair_m)
             torch.cuda.synchronize()
             P.check_step(st, [x for x in snaps if not flags[x.t]], hp, what=f"random case {case} step {k}", delayed=delayed)
             if flags.any():
