@@ -123,6 +123,48 @@ def measured_traffic(workload: str):
     return None
 
 
+def spread_compare(args, wl, cfg, m_scale_mode) -> dict:
+    """The chosen path once more with the buffers placed in different HBM regions (what --spread does).  Printed
+    beside the headline, never as the headline, because that allocator briefly takes all free device memory."""
+    import torch
+    from paper_2310_18313_amd import binding as B
+    from paper_2310_18313_amd import synth
+    from paper_2310_18313_amd.state import OptimizerState
+    lay = wl.layout
+    P = lay.n_params
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=True, grad_buffer=True,
+                        second_m=(args.path == "spec-m2"))
+    synth.fill_weights(st.grad, lay, args.seed)
+    st.init_master(st.grad)
+    torch.cuda.synchronize()
+    st.grad.zero_()
+    grads = [st.grad] + [torch.zeros_like(st.grad) for _ in range(max(1, args.grad_buffers) - 1)]
+    for k, gbuf in enumerate(grads):
+        synth.fill_gradients(gbuf, wl, args.seed, 1 + k)
+
+    def steps(first, n):
+        for i in range(first, first + n):
+            hp = B.adam_hparams(wl.lr, i, exact=args.exact, stats=args.stats, m_scale_mode=m_scale_mode)
+            st.step(grads[i % len(grads)], hp, delayed=(args.path == "single" and i > 1),
+                    speculative=args.path.startswith("spec"), pair_m=(args.path == "spec-m2"))
+
+    steps(1, args.warmup)
+    torch.cuda.synchronize()
+    st.ctx.set_timing(True)
+    st.ctx.get_timing()
+    n = min(args.steps, 10)
+    t0 = time.perf_counter()
+    steps(1 + args.warmup, n)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / n
+    tm = st.ctx.get_timing()
+    st.ctx.set_timing(False)
+    upd = tm["adam_update"][1] / max(1, tm["adam_update"][0])
+    return {"spread": st.spread, "ms_per_step": round(dt * 1e3, 3), "params_per_s": P / dt,
+            "adam_update_avg_ms": round(upd, 4),
+            "adam_update_frac_of_peak": round(12 * P / (upd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -156,7 +198,8 @@ def main() -> int:
                     help="number of gradient source buffers with independent draws that successive steps rotate through")
     ap.add_argument("--allreduce-steps", type=int, default=0, metavar="N",
                     help="also time the shared-scale re-quantise kernel and the N-rank FP8 sum (Eq. 4-6) on this layout")
-    ap.add_argument("--only-path", action="store_true", help="do not also time the other two paths")
+    ap.add_argument("--only-path", action="store_true",
+                    help="time the chosen path only: not the other paths, not the repeat in --spread placement")
     ap.add_argument("--spread", action="store_true",
                     help="place the buffers in different HBM regions with placement.SpreadAllocator (it briefly takes all "
                          "free device memory; measurably faster for states of 0.5e9 to 10e9 parameters).  Default: one "
@@ -398,41 +441,11 @@ def main() -> int:
     del st, grad, grads, shapes, bufs, views, gbuf
     gc.collect()
     torch.cuda.empty_cache()
-    if not args.spread and not args.no_spread_compare and lay.total >= (1 << 28):
-        # The same path once more with the buffers placed in different HBM regions (what --spread does): printed
-        # beside the headline, never as the headline, because that allocator briefly takes all free device memory.
-        st2 = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=True, grad_buffer=True,
-                             second_m=(args.path == "spec-m2"))
-        synth.fill_weights(st2.grad, lay, args.seed)
-        st2.init_master(st2.grad)
-        torch.cuda.synchronize()
-        st2.grad.zero_()
-        grads2 = [st2.grad] + [torch.zeros_like(st2.grad) for _ in range(max(1, args.grad_buffers) - 1)]
-        for k, gbuf in enumerate(grads2):
-            synth.fill_gradients(gbuf, wl, args.seed, 1 + k)
-
-        def steps2(first, n):
-            for i in range(first, first + n):
-                hp = B.adam_hparams(wl.lr, i, exact=args.exact, stats=args.stats, m_scale_mode=mode_of[args.path])
-                st2.step(grads2[i % len(grads2)], hp, delayed=(args.path == "single" and i > 1),
-                         speculative=args.path.startswith("spec"), pair_m=(args.path == "spec-m2"))
-
-        steps2(1, args.warmup)
-        torch.cuda.synchronize()
-        st2.ctx.set_timing(True)
-        st2.ctx.get_timing()
-        n2 = min(args.steps, 10)
-        t0 = time.perf_counter()
-        steps2(1 + args.warmup, n2)
-        torch.cuda.synchronize()
-        dt2 = (time.perf_counter() - t0) / n2
-        tm2 = st2.ctx.get_timing()
-        st2.ctx.set_timing(False)
-        upd = tm2["adam_update"][1] / max(1, tm2["adam_update"][0])
-        out["spread_allocation"] = {"spread": st2.spread, "ms_per_step": round(dt2 * 1e3, 3), "params_per_s": P / dt2,
-                                    "adam_update_avg_ms": round(upd, 4),
-                                    "adam_update_frac_of_peak": round(12 * P / (upd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        del st2, grads2
+    if not (args.spread or args.no_spread_compare or args.only_path) and lay.total >= (1 << 28):
+        try:
+            out["spread_allocation"] = spread_compare(args, wl, cfg, mode_of[args.path])
+        except (RuntimeError, MemoryError) as e:       # the headline is printed whatever happens to this extra
+            out["spread_allocation"] = {"error": str(e).splitlines()[0][:200]}
         torch.cuda.empty_cache()
     if extra:
         out["allreduce_steps"] = extra
