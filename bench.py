@@ -20,6 +20,7 @@ import argparse
 import gc
 import json
 import os
+import subprocess
 import sys
 import time
 from concurrent.futures import ThreadPoolExecutor
@@ -123,46 +124,80 @@ def measured_traffic(workload: str):
     return None
 
 
-def spread_compare(args, wl, cfg, m_scale_mode) -> dict:
-    """The chosen path once more with the buffers placed in different HBM regions (what --spread does).  Printed
-    beside the headline, never as the headline, because that allocator briefly takes all free device memory."""
+def placement_compare(args, spread: bool) -> dict:
+    """The chosen path once more in the other placement: one plain arena (v | gradient source | w | m | FP8 gradient |
+    copy, one allocation) when the headline ran region-aware, and the other way round.  In a process of its own, begun
+    after this one has given its device memory back: where a plain allocation lands depends on what the process
+    allocated and freed before, and the figure wanted is that of a fresh process.  Printed beside the headline."""
+    cmd = [sys.executable, os.path.abspath(__file__), "--only-path", "--no-cpu-baseline", "--no-ceilings",
+           "--workload", args.workload, "--seed", str(args.seed), "--path", args.path, "--steps", str(min(args.steps, 10)),
+           "--warmup", str(args.warmup), "--grad-buffers", str(args.grad_buffers), "--exact", str(args.exact),
+           "--stats", str(args.stats)] + ([] if spread else ["--arena"]) + (["--wcopy-over-grad"] if args.wcopy_over_grad else [])
+    res = subprocess.run(cmd, capture_output=True, text=True, timeout=400)
+    lines = [ln for ln in res.stdout.splitlines() if ln.startswith("{")]
+    if res.returncode != 0 or len(lines) != 1:
+        raise RuntimeError(f"the run in the other placement failed (exit {res.returncode}): {res.stderr.strip().splitlines()[-1:]}")
+    d = json.loads(lines[0])
+    upd = d["kernels"]["adam_update"]
+    return {"command": " ".join(["bench.py"] + cmd[2:]), "placement": d["config"]["placement"], "steps": d["steps"],
+            "ms_per_step": round(d["ms_per_step"], 3), "params_per_s": d["value"], "adam_update_avg_ms": upd["avg_ms"],
+            "adam_update_frac_of_peak": d["roofline"]["frac"]}
+
+
+def region_map(lay) -> dict:
+    """Where in device memory do the streams of the update pass have to lie?  One allocation over nearly all of the
+    device; the update-shaped memory skeleton (fp8lm_memory_skeleton: 12 bytes per element, reads and writes mixed,
+    no arithmetic) is timed (a) with 2^29 elements, its 16-bit streams at the start and its 8-bit streams d GiB
+    further on, (b) at the workload's full size with the five streams at chosen offsets, (c) reads alone."""
     import torch
     from paper_2310_18313_amd import binding as B
-    from paper_2310_18313_amd import synth
-    from paper_2310_18313_amd.state import OptimizerState
-    lay = wl.layout
-    P = lay.n_params
-    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=True, grad_buffer=True,
-                        second_m=(args.path == "spec-m2"))
-    synth.fill_weights(st.grad, lay, args.seed)
-    st.init_master(st.grad)
-    torch.cuda.synchronize()
-    st.grad.zero_()
-    grads = [st.grad] + [torch.zeros_like(st.grad) for _ in range(max(1, args.grad_buffers) - 1)]
-    for k, gbuf in enumerate(grads):
-        synth.fill_gradients(gbuf, wl, args.seed, 1 + k)
+    G = 1 << 30
+    ctx = B.Context(lay.tensors())
+    gib = (torch.cuda.mem_get_info(0)[0] >> 30) - 8
+    arena = torch.zeros(gib * G, dtype=torch.uint8, device="cuda:0")
 
-    def steps(first, n):
-        for i in range(first, first + n):
-            hp = B.adam_hparams(wl.lr, i, exact=args.exact, stats=args.stats, m_scale_mode=m_scale_mode)
-            st.step(grads[i % len(grads)], hp, delayed=(args.path == "single" and i > 1),
-                    speculative=args.path.startswith("spec"), pair_m=(args.path == "spec-m2"))
+    def timed(shape, bufs, n, reps=3):
+        ctx.memory_skeleton(shape, bufs, n)
+        torch.cuda.synchronize()
+        ctx.set_timing(True)
+        ctx.get_timing()
+        for _ in range(reps):
+            ctx.memory_skeleton(shape, bufs, n)
+        k, ms = ctx.get_timing()["skeleton"]
+        ctx.set_timing(False)
+        return round(ms / k, 3)
 
-    steps(1, args.warmup)
-    torch.cuda.synchronize()
-    st.ctx.set_timing(True)
-    st.ctx.get_timing()
-    n = min(args.steps, 10)
-    t0 = time.perf_counter()
-    steps(1 + args.warmup, n)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / n
-    tm = st.ctx.get_timing()
-    st.ctx.set_timing(False)
-    upd = tm["adam_update"][1] / max(1, tm["adam_update"][0])
-    return {"spread": st.spread, "ms_per_step": round(dt * 1e3, 3), "params_per_s": P / dt,
-            "adam_update_avg_ms": round(upd, 4),
-            "adam_update_frac_of_peak": round(12 * P / (upd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    def win(off_gib, nbytes):
+        return arena[int(off_gib * G): int(off_gib * G) + nbytes]
+
+    def i16(t):
+        return t.view(torch.int16)
+
+    n = 1 << 29
+    pair = {}
+    for d in range(4, gib - 2, 4):
+        b = win(d, 3 * n)
+        pair[d] = timed(B.SKEL_UPDATE, [b[:n], b[n:2 * n], i16(win(0, 2 * n)), i16(win(1, 2 * n)), b[2 * n:]], n)
+    P = lay.total // 4096 * 4096
+    s16, s8 = 2 * P / G, P / G
+    full = {}
+    if 3 * s16 + 3 * s8 < gib - 100:
+
+        def upd(v, w, m, g, q):
+            return timed(B.SKEL_UPDATE, [win(g, P), win(m, P), i16(win(v, 2 * P)), i16(win(w, 2 * P)), win(q, P)], P)
+
+        for base in range(0, int(gib - 2 * s16 - 3 * s8), 24):
+            full[f"packed v w m g8 wq from +{base} GiB"] = upd(base, base + s16, base + 2 * s16, base + 2 * s16 + s8,
+                                                             base + 2 * s16 + 2 * s8)
+        full["one arena from +0 in the order v, gradient source, w, m, g8, wq"] = upd(0, 2 * s16, 3 * s16, 3 * s16 + s8, 3 * s16 + 2 * s8)
+        full["one arena from +0 in the order v, wq, gradient source, w, g8, m (what --arena allocates)"] = upd(0, 2 * s16 + s8, 3 * s16 + 2 * s8, 3 * s16 + s8, s16)
+        full["v wq / w m g8: second group from +100 GiB"] = upd(0, 100, 100 + s16, 100 + s16 + s8, s16)
+        full["v m / w g8 wq: second group from +100 GiB"] = upd(0, 100, s16, 100 + s16, 100 + s16 + s8)
+        full["v / w / m g8 wq at +0, +100, +200 GiB"] = upd(0, 100, 200, 200 + s8, 200 + 2 * s8)
+    reads = {o: timed(B.SKEL_READ16, [i16(win(o, 8 * G))], 4 * G) for o in range(0, gib - 8, 40)}
+    return {"device_GiB_used": gib, "params": P,
+            "update_skeleton_ms_2^29_elements_16bit_streams_at_0_8bit_streams_at_GiB": pair,
+            "update_skeleton_ms_full_size": full, "read16_ms_8GiB_at_GiB": reads}
 
 
 def main() -> int:
@@ -199,13 +234,20 @@ def main() -> int:
     ap.add_argument("--allreduce-steps", type=int, default=0, metavar="N",
                     help="also time the shared-scale re-quantise kernel and the N-rank FP8 sum (Eq. 4-6) on this layout")
     ap.add_argument("--only-path", action="store_true",
-                    help="time the chosen path only: not the other paths, not the repeat in --spread placement")
-    ap.add_argument("--spread", action="store_true",
-                    help="place the buffers in different HBM regions with placement.SpreadAllocator (it briefly takes all "
-                         "free device memory; measurably faster for states of 0.5e9 to 10e9 parameters).  Default: one "
-                         "allocation with the buffers carved out one after the other, as a caller of the C ABI would")
-    ap.add_argument("--no-spread-compare", action="store_true",
-                    help="do not repeat the measurement with --spread placement after the headline run")
+                    help="time the chosen path only: not the other paths, not the repeat in the other placement")
+    ap.add_argument("--arena", action="store_true",
+                    help="carve all buffers out of one plain allocation, one after the other.  Default: the two halves "
+                         "of the update pass's traffic are placed in different HBM regions by placement.RegionAllocator "
+                         "(plain allocations, checked by timing; spacers up to the next region are held briefly)")
+    ap.add_argument("--spread", action="store_true", help="what the default does (kept for older command lines)")
+    ap.add_argument("--region-map", action="store_true",
+                    help="instead of the benchmark: time the update-shaped memory skeleton with its streams at chosen "
+                         "places of one allocation over nearly all device memory, and print the table as JSON")
+    ap.add_argument("--wcopy-over-grad", action="store_true",
+                    help="write the E4M3 weight copy over the FP8 gradient (wcopy == grad): one buffer and one stream fewer")
+    ap.add_argument("--no-placement-compare", "--no-spread-compare", dest="no_placement_compare", action="store_true",
+                    help="do not repeat the measurement in the other placement (one plain arena, or with --arena the "
+                         "region-aware one) after the headline run")
     ap.add_argument("--arena-order", default="", help="comma-separated buffer names (v,grad,w,m,g8,wq) in the order they are "
                     "carved out of the one allocation")
     ap.add_argument("--graph", action="store_true",
@@ -230,17 +272,25 @@ def main() -> int:
     lay = wl.layout
     P = lay.n_params
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
-    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=args.spread,
+    if args.region_map:
+        print(json.dumps(region_map(lay)), flush=True)
+        return 0
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=not args.arena,
                         grad_buffer=True, arena_order=args.arena_order.split(",") if args.arena_order else None,
-                        second_m=(args.path == "spec-m2" or not args.only_path))
+                        second_m=(args.path == "spec-m2" or (not args.only_path and not args.wcopy_over_grad)),
+                        wcopy_over_grad=args.wcopy_over_grad)
     if args.chunk or args.blocks_per_cu or args.single_pass_min_chunks >= 0:
         st.ctx.set_tuning(args.chunk or 16384, args.blocks_per_cu or 16,
                           (1 << 30) if args.single_pass_min_chunks < 0 else args.single_pass_min_chunks)
     grad = st.grad
-    placement = {"allocation": "spread over HBM regions" if st.spread else "one arena", **{k: v for k, v in st.placement.items() if k != "where"}}
+    placement = {"allocation": "two groups in different HBM regions" if st.spread else
+                 ("one arena" if args.arena else "plain, one allocation per buffer (regions not told apart)"),
+                 **st.placement}
     if st.spread:
         from paper_2310_18313_amd.placement import verify_spread
-        placement["check_v_vs_w"] = verify_spread(st.ctx, st.v, st.w)
+        placement["check_v_vs_w"] = verify_spread(st.ctx, st.v, st.w)      # overwrites both
+        st.v.zero_()
+        st.w.zero_()
     synth.fill_weights(grad, lay, args.seed)          # reuse the buffer for the initial weights
     st.init_master(grad)
     torch.cuda.synchronize()
@@ -290,6 +340,8 @@ def main() -> int:
     other_paths = {}
     if not args.only_path:
         for path in ("jit", "spec", "fused", "spec-fused", "spec-m2", "single"):
+            if path == "spec-m2" and st.m_other is None:
+                continue
             if path != args.path:
                 run_steps(path, 2)
                 n = min(args.steps, 10)
@@ -337,7 +389,7 @@ def main() -> int:
                    "m_fmt": "e4m3", "v": "fp16 scaled", "master": "fp16 scaled", "wcopy": "e4m3",
                    "exact_div_sqrt": bool(args.exact), "path": args.path,
                    "bytes_per_param_step": round(bytes_per_param, 3), "algorithmic_bytes_per_param_step": 19,
-                   "gradient_buffers": len(grads), "state_bytes_per_param": st.state_bytes_per_param + (1 if args.path == "spec-m2" else 0),
+                   "gradient_buffers": len(grads), "wcopy_over_grad": bool(args.wcopy_over_grad), "state_bytes_per_param": st.state_bytes_per_param + (1 if args.path == "spec-m2" else 0),
                    "placement": placement},
         "step_GBps": round(bytes_per_param * P / (dt / args.steps) / 1e9, 1),
         "step_frac_of_peak": round(bytes_per_param * P / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
@@ -441,11 +493,12 @@ def main() -> int:
     del st, grad, grads, shapes, bufs, views, gbuf
     gc.collect()
     torch.cuda.empty_cache()
-    if not (args.spread or args.no_spread_compare or args.only_path) and lay.total >= (1 << 28):
+    if not (args.no_placement_compare or args.only_path) and lay.total >= (1 << 28):
+        key = "region_aware_allocation" if args.arena else "plain_arena_allocation"
         try:
-            out["spread_allocation"] = spread_compare(args, wl, cfg, mode_of[args.path])
-        except (RuntimeError, MemoryError) as e:       # the headline is printed whatever happens to this extra
-            out["spread_allocation"] = {"error": str(e).splitlines()[0][:200]}
+            out[key] = placement_compare(args, spread=args.arena)
+        except (RuntimeError, MemoryError, subprocess.SubprocessError, ValueError, KeyError) as e:       # the headline is printed whatever happens to this extra
+            out[key] = {"error": str(e).splitlines()[0][:200]}
         torch.cuda.empty_cache()
     if extra:
         out["allreduce_steps"] = extra

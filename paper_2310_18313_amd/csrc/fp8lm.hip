@@ -729,6 +729,8 @@ static fp8lm_status adam_args_ok(const uint8_t* grad, fp8lm_fmt grad_fmt, const 
   if (!grad || !grad_meta || !m || !m_meta || !v || !v_meta || !w || !w_meta || !wcopy || !wcopy_meta)
     return FP8LM_ERR_INVALID_ARGUMENT;
   if (!aligned16(grad) || !aligned16(m) || !aligned16(v) || !aligned16(w) || !aligned16(wcopy)) return FP8LM_ERR_MISALIGNED;
+  // the one pair of buffers that may be the same: an E4M3 weight copy written over the gradient it was computed from
+  if (static_cast<const void*>(grad) == wcopy && hp->wcopy != FP8LM_WCOPY_E4M3) return FP8LM_ERR_INVALID_ARGUMENT;
   return FP8LM_OK;
 }
 
@@ -856,6 +858,7 @@ fp8lm_status fp8lm_adam_step_fp8_m2(fp8lm_ctx* c, const uint8_t* grad, fp8lm_fmt
   if (c->n_chunks == 0) return FP8LM_OK;
   if (!m_in || m_in == m_out) return FP8LM_ERR_INVALID_ARGUMENT;
   if (!aligned16(m_in)) return FP8LM_ERR_MISALIGNED;
+  if (static_cast<const void*>(grad) == wcopy) return FP8LM_ERR_OVERLAP;     // the repair reads the gradient again
   {
     // the two buffers must not share an element of any tensor
     long long extent = 0;

@@ -9,19 +9,22 @@ from __future__ import annotations
 import torch
 
 from . import binding as B
-from .placement import SpreadAllocator
+from .placement import RegionAllocator
 
 
 class OptimizerState:
     def __init__(self, tensors, total_elems: int, cfg: B.AutoscaleCfg, device: int = 0,
                  grad_fmt: int = B.E5M2, wcopy: int = B.WCOPY_E4M3, spread: bool = False,
                  grad_buffer: bool = False, master_fmt: int = B.STATE_F16, v_fmt: int = B.STATE_F16,
-                 share_with: "OptimizerState" = None, arena_order=None, second_m: bool = False):
+                 share_with: "OptimizerState" = None, arena_order=None, second_m: bool = False,
+                 wcopy_over_grad: bool = False):
         """`share_with`: another state over the same flat buffers.  Parameter groups (say, no weight decay on
         biases and LayerNorm weights) are one state each, over disjoint tensor lists of the same buffers; each
         has its own context and metadata and is stepped with its own hyper-parameters.
         `second_m`: a second first-moment buffer (1 B/param more), so that `step(..., pair_m=True)` can run the Adam
-        step without its read-only pass (fp8lm_adam_step_fp8_m2); `m` always names the buffer that holds the moment."""
+        step without its read-only pass (fp8lm_adam_step_fp8_m2); `m` always names the buffer that holds the moment.
+        `wcopy_over_grad`: the E4M3 weight copy is written over the FP8 gradient (`wq` is `g8`): after a step the buffer
+        holds the weights, after a quantisation the gradient; 1 B/param less and one stream fewer in the update pass."""
         dev = torch.device(f"cuda:{device}")
         self.tensors = list(tensors)
         self.total = int(total_elems)
@@ -34,11 +37,18 @@ class OptimizerState:
         self.ctx = B.Context(self.tensors, device)
         n = max(self.total, 16)
         qdt = torch.uint8 if wcopy == B.WCOPY_E4M3 else torch.bfloat16
-        # Streams that the update kernel walks together go to different thirds of HBM when `spread` is
-        # set (see placement.py): v (+ the bf16 gradient source) | w | m, FP8 gradient, weight copy.
-        plan = [[("v", n, state_dtype[v_fmt])] + ([("grad", n, torch.bfloat16)] if grad_buffer else []),
-                [("w", n, state_dtype[master_fmt])],
-                [("m", n, torch.uint8), ("g8", n, torch.uint8), ("wq", n, qdt)] + ([("m_other", n, torch.uint8)] if second_m else [])]
+        # Two groups of buffers; with `spread` they are put into different HBM regions (see placement.py).  Of the
+        # 12 bytes per element the update pass moves, the first group carries 5 (v in place, the weight copy) and the
+        # second 7 (w and m in place, the FP8 gradient): no region then carries more than the four fifths beyond which
+        # it becomes the bottleneck.  The cast reads the gradient source in one group and writes the FP8 gradient in
+        # the other; the read-only pass finds its two streams (FP8 gradient, m) in one.
+        plan = [[("v", n, state_dtype[v_fmt])] + ([] if wcopy_over_grad else [("wq", n, qdt)])
+                + ([("grad", n, torch.bfloat16)] if grad_buffer else []),
+                [("w", n, state_dtype[master_fmt]), ("m", n, torch.uint8), ("g8", n, torch.uint8)]
+                + ([("m_other", n, torch.uint8)] if second_m else [])]
+        if wcopy_over_grad:
+            assert wcopy == B.WCOPY_E4M3 and not second_m and share_with is None, \
+                "only an E4M3 copy fits the gradient's buffer; the step with a pair of moments reads the gradient twice"
         self.placement = {}
         if share_with is not None:
             o = share_with
@@ -50,17 +60,21 @@ class OptimizerState:
                 bufs["grad"] = o.grad
             self.spread = o.spread
         elif spread:
-            alloc = SpreadAllocator(self.ctx, device)
+            alloc = RegionAllocator(self.ctx, device)
             bufs = alloc.allocate(plan)
             self.spread = alloc.spread
             self.placement = dict(alloc.log, where=alloc.where)
         else:
             # one allocation, the buffers carved out of it one after the other (what a caller of the C ABI with an
             # arena of its own would do): where they lie relative to each other is then the same in every process
+            # Default order: the first moment last.  Of a 13e9-parameter state in a fresh process (device memory is
+            # handed out upwards from a region boundary) only the last 12 GiB of the 108 lie in the second region;
+            # m carries more of the update pass's traffic (2 of 12 bytes per element) than the other 8-bit buffers.
             items = [(name, k, dt) for reg in plan for name, k, dt in reg]
-            if arena_order:            # names in the order they are to follow each other inside the allocation
-                assert sorted(arena_order) == sorted(name for name, _, _ in items), arena_order
-                items.sort(key=lambda it: list(arena_order).index(it[0]))
+            order = list(arena_order) if arena_order else [nm for nm in ("v", "wq", "grad", "w", "g8", "m", "m_other")
+                                                            if any(nm == it[0] for it in items)]
+            assert sorted(order) == sorted(name for name, _, _ in items), order
+            items.sort(key=lambda it: order.index(it[0]))
             align = (2 << 20) if n >= (2 << 20) else 256
             offs, end = [], 0
             for _, k, dt in items:
@@ -71,7 +85,8 @@ class OptimizerState:
                     for (name, k, dt), o in zip(items, offs)}
             self.spread = False
             self.placement = {"arena_bytes": end, "order": [name for name, _, _ in items]}
-        self.g8, self.m, self.v, self.w, self.wq = bufs["g8"], bufs["m"], bufs["v"], bufs["w"], bufs["wq"]
+        self.g8, self.m, self.v, self.w = bufs["g8"], bufs["m"], bufs["v"], bufs["w"]
+        self.wq = self.g8 if wcopy_over_grad else bufs["wq"]
         self.grad = bufs.get("grad")       # bf16 gradient source, only if asked for
         self.m_other = bufs.get("m_other")  # the other buffer of the first-moment pair, only if asked for
         self.g_meta = self.ctx.new_meta(cfg)
@@ -82,6 +97,7 @@ class OptimizerState:
 
     @property
     def state_bytes_per_param(self) -> int:
+        """Eq. 8's four buffers: FP8 gradient, first moment, second moment, master weight."""
         return self.g8.element_size() + self.m.element_size() + self.v.element_size() + self.w.element_size()
 
     def init_master(self, w_bf16: torch.Tensor) -> None:

@@ -35,10 +35,11 @@ def sample_ids(layout):
     return small, sorted(big)
 
 
-def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False, paths=None, tuning=None):
+def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False, paths=None, tuning=None, spread=False,
+        speculative=False):
     lay = wl.layout
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
-    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, grad_buffer=True)
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, grad_buffer=True, spread=spread)
     if tuning:
         st.ctx.set_tuning(*tuning)
     say(f"{wl.name}: {lay.n_tensors} tensors, {lay.n_params} params, placement={st.placement}, tuning={tuning}")
@@ -59,7 +60,7 @@ def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False, p
         hp = B.adam_hparams(wl.lr, step, m_scale_mode=mode)
         ids = (small if step in small_steps else []) + (big if step in big_steps else [])
         snaps = [P.Snapshot(st, grad, t) for t in ids]
-        st.step(grad, hp, delayed=delayed)
+        st.step(grad, hp, delayed=delayed, speculative=speculative and not delayed)
         torch.cuda.synchronize()
         if ids:
             say(f"{wl.name} step {step} (moment-scale mode {mode}, delayed {delayed}): checking {len(ids)} tensors, "
@@ -75,9 +76,17 @@ def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False, p
     return st, tot, mus
 
 
+def lay_tensors_with_elements(wl) -> int:
+    return sum(1 for n in wl.layout.numels if n > 0)
+
+
 def test_gpt13b_in_the_benchmark_configuration():
     wl = synth.workload("gpt13b")
-    st, tot, _ = run(wl, seed=0, steps=2, small_steps={1, 2}, big_steps={1})
+    # as bench.py runs it by default: region-aware placement, just-in-time quantisation through fp8lm_quantize_fp8
+    st, tot, _ = run(wl, seed=0, steps=2, small_steps={1, 2}, big_steps={1}, spread=True, speculative=True)
+    spec = st.ctx.speculation_stats()
+    say(f"placement {st.placement}; speculation {spec}")
+    assert spec["calls"] == 2 and lay_tensors_with_elements(wl) <= spec["tensors_redone"] < 2 * lay_tensors_with_elements(wl)
     assert st.state_bytes_per_param == 6          # Sec. 2.2, Eq. 8
     assert tot["elements"] > 5e8
 

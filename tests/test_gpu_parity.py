@@ -892,6 +892,90 @@ def test_allreduce_strategies_match_the_oracle_and_order_as_the_ablation_says(fm
 
 
 # ---- the entry points can be recorded into a HIP graph ---------------------------------------------------------
+@pytest.mark.parametrize("grad_fmt,route", [(B.E5M2, "jit"), (B.E4M3, "spec"), (B.E5M2, "static"), (B.E5M2, "predicted")])
+def test_weight_copy_written_over_the_fp8_gradient(grad_fmt, route):
+    """wcopy == grad (the E4M3 weight copy takes the place of the gradient it was computed from): the buffer must hold
+    the bytes that a separate copy buffer holds, everything else must be untouched by the sharing; the state with
+    two buffers is held to the oracle lock-step.  Ragged sizes (tails, one-element and empty tensors), a careful
+    tensor (NaN planted), every route into the update pass."""
+    from paper_2310_18313_amd.state import OptimizerState
+    lay = synth.Layout(["a", "b", "c", "d", "e", "f", "g"], [70001, 1, 4096, 333, 0, 16385, 300017])
+    wl = synth.Workload("alias", lay, lr=1e-3, sigma=None, ramp_steps=4)
+    two, w0 = P.make_state(wl, 31, grad_fmt, B.WCOPY_E4M3)
+    one = OptimizerState(lay.tensors(), lay.total, two.cfg, 0, grad_fmt, B.WCOPY_E4M3, wcopy_over_grad=True)
+    assert one.wq.data_ptr() == one.g8.data_ptr()
+    one.init_master(w0)
+    ids = list(range(lay.n_tensors))
+    grad = torch.zeros(max(lay.total, 16), dtype=torch.bfloat16, device=DEV)
+    mode = B.MSCALE_PREDICTED if route == "predicted" else B.MSCALE_EXACT_PASS
+    for step in range(1, 6):
+        synth.fill_gradients(grad, wl, 31, step)
+        if step == 3:
+            grad[lay.tensors()[5][0] + 99] = float("nan")
+        hp = B.adam_hparams(wl.lr, step, stats=step % 2, m_scale_mode=mode)
+        snaps = [P.Snapshot(two, grad, t) for t in ids]
+        say(f"weight copy over the gradient: fmt={grad_fmt} route={route} step={step}")
+        two.step(grad, hp, speculative=(route == "spec"))
+        if route == "static":
+            one.quantize_grad(grad)
+            B.adam_step_fp8_static(lay.tensors(), one.g8, grad_fmt, one.g_meta, one.m, one.m_meta, one.v, one.v_meta,
+                                   one.w, one.w_meta, one.g8, one.q_meta, hp)
+        else:
+            one.step(grad, hp, speculative=(route == "spec"))
+        torch.cuda.synchronize()
+        P.check_step(two, snaps, hp, what=f"two buffers, step {step}")
+        for k in ("m", "v", "w", "wq", "g_meta", "m_meta", "v_meta", "w_meta", "q_meta"):
+            a, b = getattr(two, k), getattr(one, k)
+            if a.element_size() == 2:
+                a, b = a.view(torch.int16), b.view(torch.int16)
+            assert torch.equal(a, b), (step, k)
+    # a bf16 copy does not fit the gradient's buffer; the step with a pair of moment buffers reads the gradient twice
+    big = torch.zeros(2 * one.g8.numel(), dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.Fp8lmError):
+        one.ctx.adam_step_fp8(big[:one.g8.numel()], grad_fmt, one.g_meta, one.m, one.m_meta, one.v, one.v_meta, one.w,
+                              one.w_meta, big.view(torch.bfloat16), one.q_meta, B.adam_hparams(wl.lr, 9, wcopy=B.WCOPY_BF16))
+    with pytest.raises(B.Fp8lmError):
+        one.ctx.adam_step_fp8_m2(one.g8, grad_fmt, one.g_meta, one.m, two.m, one.m_meta, one.v, one.v_meta, one.w,
+                                 one.w_meta, one.g8, one.q_meta, B.adam_hparams(wl.lr, 9))
+
+
+def test_region_aware_placement_changes_no_result():
+    """OptimizerState(spread=True): where the buffers lie is decided by timing (placement.RegionAllocator); what the
+    kernels compute must not depend on it.  A state of 0.5e9 parameters placed that way and one carved out of a plain
+    arena step side by side and must hold the same bytes; if the allocator reports the two groups apart, the check
+    that bench.py prints must agree."""
+    from paper_2310_18313_amd.placement import verify_spread
+    from paper_2310_18313_amd.state import OptimizerState
+    lay = synth.Layout(["a", "b", "c"], [250_000_017, 4097, 250_000_000])
+    wl = synth.Workload("placed", lay, lr=1e-3, sigma=None, ramp_steps=4)
+    cfg = B.autoscale_cfg(ramp_steps=4)
+    placed = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=True, grad_buffer=True)
+    say(f"region-aware placement: {placed.placement}")
+    for t in (placed.v, placed.w, placed.m, placed.g8, placed.wq, placed.grad):
+        assert int(t.view(torch.uint8).max()) == 0              # handed over as zeros, whatever the probes wrote
+    if placed.spread:
+        assert placed.placement["where"]["v"] == 0 and placed.placement["where"]["w"] == 1
+        chk = verify_spread(placed.ctx, placed.v, placed.w)
+        assert chk["distinct"], chk
+        placed.v.zero_()
+        placed.w.zero_()
+    plain = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
+    synth.fill_weights(placed.grad, lay, 3)
+    placed.init_master(placed.grad)
+    plain.init_master(placed.grad)
+    for step in (1, 2):
+        synth.fill_gradients(placed.grad, wl, 3, step)
+        hp = B.adam_hparams(wl.lr, step)
+        placed.step(placed.grad, hp, speculative=True)
+        plain.step(placed.grad, hp, speculative=True)
+        torch.cuda.synchronize()
+        for k in ("g8", "m", "v", "w", "wq", "g_meta", "m_meta", "v_meta", "w_meta", "q_meta"):
+            a, b = getattr(placed, k), getattr(plain, k)
+            if a.element_size() == 2:
+                a, b = a.view(torch.int16), b.view(torch.int16)
+            assert torch.equal(a, b), (step, k)
+
+
 def test_a_step_replayed_from_a_hip_graph_equals_the_eager_step():
     """None of the hot-path calls synchronises, allocates or clears memory with a memset, so a whole step can be
     captured once and replayed; the hyper-parameters are baked in at capture, so every replay is the same step."""
