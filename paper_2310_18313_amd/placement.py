@@ -1,22 +1,27 @@
 """Placement of the large flat buffers in HBM on MI355X.
 
 Measured on MI355X (bench.py --region-map): the 288 GiB of HBM3E behave as three regions of 96 GiB of the physical
-address space.  Streams that are only read do not care where they lie (6.7-7.0 TB/s anywhere).  Traffic that mixes
+address space.  Streams that are only read do not care where they lie (6.7-7.1 TB/s anywhere).  Traffic that mixes
 reads and writes -- the update pass reads and rewrites m, v and w in place -- reaches 5.2 TB/s while all of it falls
-into one region and 6.3 TB/s once it is split over two or three of them, whatever the distance otherwise: the update
-pass of a 13e9-parameter state takes 30 ms with its five streams in one region, 26.5 ms with all but the weight copy
-in one region (what one plain allocation in the order v, gradient source, w, m, FP8 gradient, copy gives in a fresh
-process, where device memory is handed out from the bottom of the address space upwards), and 24.5 ms when each
-region carries about half of the bytes.
+into one region and 6.2-6.3 TB/s once it is split over two or three of them, whatever the distance otherwise: the
+update pass of a 13e9-parameter state takes 30 ms with its five streams in one region, 27 ms with all but an 8-bit
+stream in one region and 24.5 ms when no region carries more than about four fifths of the bytes.  Where an allocation
+lands is up to the driver: a large one is built from big physical blocks that need not be neighbours (a 120 GiB
+allocation was seen as 64 GiB in one region, 32 GiB in another and 24 GiB in the first again), and what earlier
+processes left behind changes the picture from one process to the next.  Only measurement tells.
 
-`RegionAllocator` therefore puts the buffers of an optimizer state into two groups that carry the same traffic in the
-update pass -- (v, m, gradient source) and (w, FP8 gradient, weight copy) -- and makes sure the two groups lie in
-different regions, by measurement and with bounded memory: it allocates the first group plainly, then steps through
-device memory with 4 GiB spacers until a spacer lies in another region than the first group (told apart with the
-library's update-shaped memory skeleton: 20 % faster across regions than inside one), allocates the second group
-there, verifies head and tail of every buffer, and frees the spacers.  At most `max_spacer_gib` of spacers are held,
-briefly; nothing else of the device is touched.  If the regions cannot be told apart, or the memory runs out, the
-buffers stay where plain allocation put them and `spread` is False.
+`RegionAllocator` therefore keeps a tally of the update pass's traffic per region while it allocates, by measurement
+and with bounded memory.  All kernels walk their buffers in step, so the tally is kept per place: seven places spread
+evenly from head to tail of every buffer.  The anchor (v) is allocated first (again, up to three times, if it does not
+lie in one region as a whole) and a window of it that lies inside one region becomes the reference.  Every further
+buffer that the update pass touches is allocated plainly and looked up at its seven places against the reference
+with the library's update-shaped memory skeleton (16 % faster across regions than inside one); at each place the
+bytes per element that the update pass moves through the buffer are added to the reference's region or to the rest.
+A buffer that would push the reference's region above two thirds of the traffic at any place (four fifths once
+110 GiB of spacers are held), or the rest above four fifths, is kept aside as a spacer and allocated again, further
+on; the spacers are freed at the end.  At most
+`max_spacer_gib` of them are held, briefly; nothing else of the device is touched.  If no reference can be found or
+memory runs short the buffers stay where plain allocation put them and `spread` is False.
 
 Nothing here computes anything of the method: it only decides where `torch.zeros` buffers land.
 """
@@ -30,6 +35,10 @@ from . import binding as B
 
 GiB = 1 << 30
 REGION_GIB = 96           # what was measured; the allocator does not rely on it
+# The probe moves 12 bytes per element: 5.2e12 B/s inside one region, 6.2e12 B/s across two.  A buffer whose own first
+# bytes already run faster than this is made of pieces from several regions (small allocations in a process that has
+# allocated and freed much) and cannot serve as the anchor.
+MIXED_ABOVE_BPS = 5.5e12
 
 
 def _bytes(t: torch.Tensor) -> torch.Tensor:
@@ -76,121 +85,135 @@ def verify_spread(ctx, a: torch.Tensor, b: torch.Tensor) -> dict:
 
 
 class RegionAllocator:
-    """Allocates two groups of named buffers into different HBM regions (see the module docstring).
+    """Allocates named buffers so that neither the reference's region nor the rest of the device carries more than
+    `limit` of a kernel's mixed traffic (`soft_limit` once `patience_gib` of spacers are held; beyond four fifths a
+    region becomes the bottleneck).  See the module docstring.
 
-    `plan` lists the two groups, each a list of (name, numel, dtype).  The first buffer of the first group is the
-    anchor; every buffer of the second group is verified, head and tail, to lie in another region than the anchor;
-    the remaining buffers of the first group are allocated last, plainly, into what the spacers leave behind.
-    `where[name]`: 0 in the anchor's region, 1 in another one, 2 across a boundary, -1 not looked at.
+    `plan`: (name, numel, dtype, weight) per buffer, weight = bytes per element that the update pass moves through
+    it (0: the buffer's place does not matter; it is allocated last).  The first entry is the anchor.
+    `where[name]`: per place looked at, from head to tail, 0 in the reference's region, 1 outside (None: not looked at).
     """
 
-    def __init__(self, ctx, device: int = 0, spacer_gib: int = 4, max_spacer_gib: int = 200, ratio: float = 0.91):
+    def __init__(self, ctx, device: int = 0, max_spacer_gib: int = 200, limit: float = 0.67, soft_limit: float = 0.8,
+                 patience_gib: int = 110, ratio: float = 0.91):
         self.ctx = ctx
         self.device = torch.device(f"cuda:{device}")
-        self.spacer_bytes = spacer_gib * GiB
         self.max_spacer_bytes = max_spacer_gib * GiB
+        self.limit = limit                  # share of the traffic one side may carry ...
+        self.soft_limit = soft_limit        # ... and once more than patience_gib of spacers are held
+        self.patience_bytes = patience_gib * GiB
+        self.positions = 7                  # places per buffer at which its region is looked up
         self.ratio = ratio
         self.spread = False
-        self.where: Dict[str, int] = {}
+        self.where: Dict[str, Optional[str]] = {}
         self.log: Dict[str, object] = {}
 
     def _zeros(self, n: int, dt: torch.dtype) -> torch.Tensor:
         return torch.zeros(n, dtype=dt, device=self.device)
 
-    def allocate(self, plan: Sequence[Sequence[Tuple[str, int, torch.dtype]]]) -> Dict[str, torch.Tensor]:
+    def allocate(self, plan: Sequence[Tuple[str, int, torch.dtype, float]]) -> Dict[str, torch.Tensor]:
         bufs: Dict[str, torch.Tensor] = {}
-        first, second = list(plan[0]), list(plan[1])
-        for name, _, _ in first + second:
-            self.where[name] = -1
+        for name, _, _, _ in plan:
+            self.where[name] = None
         spacers: List[torch.Tensor] = []
         torch.cuda.empty_cache()
         try:
-            self.spread = self._place(bufs, first, second, spacers)
+            self.spread = self._place(bufs, [p for p in plan if p[3] > 0], spacers)
         except (RuntimeError, MemoryError) as e:          # out of memory on the way: what exists stays, the rest is plain
             self.log["gave_up"] = str(e).splitlines()[0][:120]
             self.spread = False
-        self.log.setdefault("spacers_GiB", round(sum(t.numel() * t.element_size() for t in spacers) / GiB, 1))
+        self.log["spacers_GiB"] = round(sum(t.numel() * t.element_size() for t in spacers) / GiB, 1)
         spacers.clear()
         torch.cuda.empty_cache()
-        for name, _, _ in first:
-            if name in bufs:
-                bufs[name].zero_()                       # the probes wrote into them
-        for name, n, dt in first + second:
+        for t in bufs.values():
+            t.zero_()                                    # the probes wrote into them
+        for name, n, dt, _ in plan:
             if name not in bufs:
                 bufs[name] = self._zeros(n, dt)
         return bufs
 
-    def _place(self, bufs, first, second, spacers) -> bool:
+    def _place(self, bufs, plan, spacers) -> bool:
         size = lambda k, dt: k * torch.empty((), dtype=dt).element_size()
-        a_name, a_k, a_dt = first[0]
-        smallest = min(size(k, dt) for _, k, dt in [first[0]] + second)
-        n = min(1 << 29, size(a_k, a_dt) // 7, smallest // 3) // 4096 * 4096   # the probe fits the anchor and every buffer
-        if n < (1 << 27) or self.spacer_bytes < 3 * n:
+        a_name, a_k, a_dt, a_w = plan[0]
+        n = min(1 << 29, size(a_k, a_dt) // 7, min(size(k, dt) for _, k, dt, _ in plan) // 3) // 4096 * 4096
+        if n < (1 << 27):
             self.log["gave_up"] = "buffers too small for their place to matter"
             return False
+        total_w = float(sum(w for _, _, _, w in plan))
+        K = self.positions
         held = lambda: sum(t.numel() * t.element_size() for t in spacers)
 
         def room(nbytes: int) -> bool:
             return torch.cuda.mem_get_info(self.device)[0] > nbytes + 2 * GiB and held() <= self.max_spacer_bytes
 
-        # 1. the anchor: a buffer whose head and tail lie in one region
-        anchor = inside = None
-        for _ in range(4):
+        def reference_in(anchor: torch.Tensor):
+            """A window of the anchor that lies in one region (the probe inside it runs slowly): (window, ms, offset)."""
+            for o in range(0, anchor.numel() - 7 * n + 1, 7 * n)[:8]:
+                t_in = probe_ms(self.ctx, anchor[o:o + 4 * n], anchor[o + 4 * n:o + 7 * n], n)
+                if 12 * n / (t_in * 1e-3) < MIXED_ABOVE_BPS:
+                    return anchor[o:o + 4 * n], t_in, o
+            return None, None, None
+
+        def profile(t: torch.Tensor, ref, inside, skip=None) -> List[bool]:
+            """At K places spread evenly over the buffer, head and tail included: does it lie outside the
+            reference's region?  All kernels walk their buffers in step, so what has to be balanced is the traffic
+            at each place, not its sum over the buffer."""
+            t = _bytes(t)
+            last = t.numel() - 3 * n
+            out = []
+            for i in range(K):
+                o = (last * i // (K - 1)) // 4096 * 4096
+                if skip is not None and o < skip + 7 * n and o + 3 * n > skip:
+                    out.append(False)                    # overlaps the reference: its region by construction
+                else:
+                    out.append(probe_ms(self.ctx, ref, t[o:o + 3 * n], n, reps=2) < self.ratio * inside)
+            return out
+
+        # 1. the anchor, preferably a buffer that lies in one region as a whole
+        anchor = ref = inside = prof = None
+        for attempt in range(3):
             if not room(size(a_k, a_dt)):
                 break
             t = _bytes(self._zeros(a_k, a_dt))
-            t_in = probe_ms(self.ctx, t[:4 * n], t[4 * n:7 * n], n)
-            t_tail = probe_ms(self.ctx, t[:4 * n], t[t.numel() - 3 * n:], n)
-            if self.ratio * t_in <= t_tail <= t_in / self.ratio:
-                anchor, inside = t, max(t_in, t_tail)
+            r, t_in, at = reference_in(t)
+            p = profile(t, r, t_in, skip=at) if r is not None else None
+            if anchor is None or (p is not None and (prof is None or sum(p) < sum(prof))):
+                if anchor is not None:
+                    spacers.append(anchor)
+                anchor, ref, inside, prof = t, r, t_in, p
+            else:
+                spacers.append(t)
+            if prof is not None and not any(prof):
                 break
-            spacers.append(t)                            # head and tail in different regions: step over it
-        if anchor is None:
-            self.log["gave_up"] = "no anchor buffer inside one region"
+        if anchor is None or ref is None:
+            if anchor is not None:
+                bufs[a_name] = anchor.view(a_dt)
+            self.log["gave_up"] = "no window of the anchor lies inside one region (allocations come in small pieces from several)"
             return False
         bufs[a_name] = anchor.view(a_dt)
-        self.where[a_name] = 0
-        head = anchor[:4 * n]
+        self.where[a_name] = "".join("01"[x] for x in prof)
         self.log.update(probe_elements=n, inside_ms=round(inside, 4))
-
-        def region_of(t: torch.Tensor) -> int:
-            t = _bytes(t)
-            h = probe_ms(self.ctx, head, t[:3 * n], n) < self.ratio * inside
-            tl = probe_ms(self.ctx, head, t[t.numel() - 3 * n:], n) < self.ratio * inside
-            return 1 if (h and tl) else 0 if not (h or tl) else 2
-
-        # 2. step through memory until a spacer lies elsewhere, then allocate the second group and keep what verifies
-        pending = list(second)
-        across = []
-        while pending:
-            need = sum(size(k, dt) for _, k, dt in pending)
-            if not room(need + self.spacer_bytes):
-                self.log["gave_up"] = "another region not reached within the memory allowed"
-                return False
-            s = torch.empty(self.spacer_bytes, dtype=torch.uint8, device=self.device)
-            spacers.append(s)
-            t_ms = probe_ms(self.ctx, head, s, n)
-            if t_ms >= self.ratio * inside:
-                continue
-            across.append(round(t_ms, 4))
-            still = []
-            for name, k, dt in pending:
+        here = [a_w * (not x) for x in prof]                 # traffic in the reference's region, at each place
+        away = [a_w * x for x in prof]
+        # 2. every other buffer: keep it if neither side exceeds the limit at any place, else step over it
+        for name, k, dt, w in plan[1:]:
+            while True:
+                if not room(size(k, dt)):
+                    self.log["gave_up"] = f"no place for {name} within the memory allowed"
+                    self.log["traffic_share_busiest"] = round(max(here + away) / total_w, 3)
+                    return False
                 t = self._zeros(k, dt)
-                r = region_of(t)
-                if r == 1:
-                    t.zero_()
-                    bufs[name] = t
-                    self.where[name] = 1
-                else:
-                    spacers.append(_bytes(t))            # a buffer in the wrong place is one more spacer
-                    still.append((name, k, dt))
-            pending = still
-        self.log["across_ms"] = across[:4]
-        # 3. the rest of the first group goes where the spacers were
-        self.log["spacers_GiB"] = round(held() / GiB, 1)
-        spacers.clear()
-        torch.cuda.empty_cache()
-        for name, k, dt in first[1:]:
-            bufs[name] = self._zeros(k, dt)
-            self.where[name] = region_of(bufs[name]) if size(k, dt) >= 3 * n else -1
+                p = profile(t, ref, inside)
+                # Too much in the reference's region: stepping on leads out of it.  Too much outside it: stepping on
+                # rarely leads back, so there the soft limit applies at once.
+                lim_here = (self.limit if held() < self.patience_bytes else self.soft_limit) * total_w + 1e-9
+                lim_away = self.soft_limit * total_w + 1e-9
+                if all(here[i] + w * (not p[i]) <= lim_here and away[i] + w * p[i] <= lim_away for i in range(K)):
+                    break
+                spacers.append(_bytes(t))                # in the wrong place: one more spacer
+            bufs[name] = t
+            self.where[name] = "".join("01"[x] for x in p)
+            here = [here[i] + w * (not p[i]) for i in range(K)]
+            away = [away[i] + w * p[i] for i in range(K)]
+        self.log["traffic_share_busiest"] = round(max(here + away) / total_w, 3)
         return True

@@ -37,15 +37,17 @@ class OptimizerState:
         self.ctx = B.Context(self.tensors, device)
         n = max(self.total, 16)
         qdt = torch.uint8 if wcopy == B.WCOPY_E4M3 else torch.bfloat16
-        # Two groups of buffers; with `spread` they are put into different HBM regions (see placement.py).  Of the
-        # 12 bytes per element the update pass moves, the first group carries 5 (v in place, the weight copy) and the
-        # second 7 (w and m in place, the FP8 gradient): no region then carries more than the four fifths beyond which
-        # it becomes the bottleneck.  The cast reads the gradient source in one group and writes the FP8 gradient in
-        # the other; the read-only pass finds its two streams (FP8 gradient, m) in one.
-        plan = [[("v", n, state_dtype[v_fmt])] + ([] if wcopy_over_grad else [("wq", n, qdt)])
-                + ([("grad", n, torch.bfloat16)] if grad_buffer else []),
-                [("w", n, state_dtype[master_fmt]), ("m", n, torch.uint8), ("g8", n, torch.uint8)]
-                + ([("m_other", n, torch.uint8)] if second_m else [])]
+        # (name, elements, type, bytes per element that the update pass moves through the buffer), in the order of
+        # allocation.  With `spread` the buffers are placed so that no HBM region carries more than about three fifths
+        # of that traffic (see placement.py: typically v and the copy in one region, w, m and the FP8 gradient in
+        # another); otherwise they are carved out of one allocation.
+        esz = lambda dt: torch.empty((), dtype=dt).element_size()
+        plan = [("v", n, state_dtype[v_fmt], 2.0 * esz(state_dtype[v_fmt]))] \
+            + ([] if wcopy_over_grad else [("wq", n, qdt, 1.0 * esz(qdt))]) \
+            + [("w", n, state_dtype[master_fmt], 2.0 * esz(state_dtype[master_fmt])),
+               ("m", n, torch.uint8, 1.0 if second_m else 2.0)] + ([("m_other", n, torch.uint8, 1.0)] if second_m else []) \
+            + [("g8", n, torch.uint8, 2.0 if wcopy_over_grad else 1.0)] \
+            + ([("grad", n, torch.bfloat16, 0.0)] if grad_buffer else [])
         if wcopy_over_grad:
             assert wcopy == B.WCOPY_E4M3 and not second_m and share_with is None, \
                 "only an E4M3 copy fits the gradient's buffer; the step with a pair of moments reads the gradient twice"
@@ -67,10 +69,11 @@ class OptimizerState:
         else:
             # one allocation, the buffers carved out of it one after the other (what a caller of the C ABI with an
             # arena of its own would do): where they lie relative to each other is then the same in every process
-            # Default order: the first moment last.  Of a 13e9-parameter state in a fresh process (device memory is
-            # handed out upwards from a region boundary) only the last 12 GiB of the 108 lie in the second region;
-            # m carries more of the update pass's traffic (2 of 12 bytes per element) than the other 8-bit buffers.
-            items = [(name, k, dt) for reg in plan for name, k, dt in reg]
+            # Default order: the first moment last.  When an allocation of this size is laid out along the address
+            # space from a region boundary, only the last 12 of the 108 GiB of a 13e9-parameter state lie in the
+            # second region; m carries more of the update pass's traffic (2 of 12 bytes per element) than the
+            # other 8-bit buffers.  (Where the pieces of an allocation really lie is up to the driver.)
+            items = [(name, k, dt) for name, k, dt, _ in plan]
             order = list(arena_order) if arena_order else [nm for nm in ("v", "wq", "grad", "w", "g8", "m", "m_other")
                                                             if any(nm == it[0] for it in items)]
             assert sorted(order) == sorted(name for name, _, _ in items), order

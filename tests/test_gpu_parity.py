@@ -954,11 +954,13 @@ def test_region_aware_placement_changes_no_result():
     for t in (placed.v, placed.w, placed.m, placed.g8, placed.wq, placed.grad):
         assert int(t.view(torch.uint8).max()) == 0              # handed over as zeros, whatever the probes wrote
     if placed.spread:
-        assert placed.placement["where"]["v"] == 0 and placed.placement["where"]["w"] == 1
-        chk = verify_spread(placed.ctx, placed.v, placed.w)
-        assert chk["distinct"], chk
-        placed.v.zero_()
-        placed.w.zero_()
+        where = placed.placement["where"]
+        assert placed.placement["traffic_share_busiest"] <= 0.8 + 1e-6
+        if set(where["v"]) == {"0"} and set(where["w"]) == {"1"}:      # v and w as wholes in different regions
+            chk = verify_spread(placed.ctx, placed.v, placed.w)
+            assert chk["distinct"], chk
+            placed.v.zero_()
+            placed.w.zero_()
     plain = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3)
     synth.fill_weights(placed.grad, lay, 3)
     placed.init_master(placed.grad)
