@@ -244,7 +244,7 @@ def main() -> int:
                     help="instead of the benchmark: time the update-shaped memory skeleton with its streams at chosen "
                          "places of one allocation over nearly all device memory, and print the table as JSON")
     ap.add_argument("--wcopy-over-grad", action="store_true",
-                    help="write the E4M3 weight copy over the FP8 gradient (wcopy == grad): one buffer and one stream fewer")
+                    help="write the E4M3 weight copy over the FP8 gradient (wcopy == grad): one buffer fewer, same bytes moved")
     ap.add_argument("--no-placement-compare", "--no-spread-compare", dest="no_placement_compare", action="store_true",
                     help="do not repeat the measurement in the other placement (one plain arena, or with --arena the "
                          "region-aware one) after the headline run")

@@ -365,9 +365,8 @@ fp8lm_status fp8lm_init_master_as(fp8lm_ctx* ctx, const void* w_bf16 /*device*/,
  * (wcopy == grad, the same address).  The gradient is dead once the step has read it and the copy is only needed
  * after the step, so one buffer can serve both; every thread reads an element's gradient code before it stores that
  * element's copy.  The results are the same bytes as with two buffers, the step moves the same 12 bytes per element
- * through one stream fewer (measured 3 % faster on MI355X), and the state is 1 byte per element smaller.  A bf16
- * copy cannot share the gradient's buffer (INVALID_ARGUMENT); buffers that overlap in any other way give undefined
- * results.
+ * in the same time, and the state is 1 byte per element smaller.  A bf16 copy cannot share the gradient's buffer
+ * (INVALID_ARGUMENT); buffers that overlap in any other way give undefined results.
  * Errors: INVALID_ARGUMENT for hyper-parameters outside the ranges given at fp8lm_adam_hparams.
  */
 fp8lm_status fp8lm_adam_step_fp8(fp8lm_ctx* ctx,

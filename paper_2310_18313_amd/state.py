@@ -24,7 +24,7 @@ class OptimizerState:
         `second_m`: a second first-moment buffer (1 B/param more), so that `step(..., pair_m=True)` can run the Adam
         step without its read-only pass (fp8lm_adam_step_fp8_m2); `m` always names the buffer that holds the moment.
         `wcopy_over_grad`: the E4M3 weight copy is written over the FP8 gradient (`wq` is `g8`): after a step the buffer
-        holds the weights, after a quantisation the gradient; 1 B/param less and one stream fewer in the update pass."""
+        holds the weights, after a quantisation the gradient; 1 B/param less, the same bytes, the same speed."""
         dev = torch.device(f"cuda:{device}")
         self.tensors = list(tensors)
         self.total = int(total_elems)
