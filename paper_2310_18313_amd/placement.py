@@ -84,6 +84,15 @@ def verify_spread(ctx, a: torch.Tensor, b: torch.Tensor) -> dict:
     return {"elements": n, "inside_ms": round(inside, 4), "across_ms": round(across, 4), "distinct": across < 0.91 * inside}
 
 
+def fits(here: Sequence[float], away: Sequence[float], weight: float, outside: Sequence[bool], lim_here: float,
+         lim_away: float) -> bool:
+    """The acceptance rule: `here[i]` / `away[i]` is the traffic already placed in / outside the reference's region at
+    place i; a buffer of `weight` bytes per element that lies outside the region where `outside[i]` is accepted if
+    no place ends up above its limit on either side."""
+    return all((here[i] + weight <= lim_here) if not outside[i] else (away[i] + weight <= lim_away)
+               for i in range(len(outside)))
+
+
 class RegionAllocator:
     """Allocates named buffers so that neither the reference's region nor the rest of the device carries more than
     `limit` of a kernel's mixed traffic (`soft_limit` once `patience_gib` of spacers are held; beyond four fifths a
@@ -208,7 +217,7 @@ class RegionAllocator:
                 # rarely leads back, so there the soft limit applies at once.
                 lim_here = (self.limit if held() < self.patience_bytes else self.soft_limit) * total_w + 1e-9
                 lim_away = self.soft_limit * total_w + 1e-9
-                if all(here[i] + w * (not p[i]) <= lim_here and away[i] + w * p[i] <= lim_away for i in range(K)):
+                if fits(here, away, w, p, lim_here, lim_away):
                     break
                 spacers.append(_bytes(t))                # in the wrong place: one more spacer
             bufs[name] = t
