@@ -18,8 +18,8 @@ buffer that the update pass touches is allocated plainly and looked up at its se
 with the library's update-shaped memory skeleton (16 % faster across regions than inside one); at each place the
 bytes per element that the update pass moves through the buffer are added to the reference's region or to the rest.
 A buffer that would push the reference's region above two thirds of the traffic at any place (four fifths once
-110 GiB of spacers are held), or the rest above four fifths, is kept aside as a spacer and allocated again, further
-on; the spacers are freed at the end.  At most
+110 GiB of spacers are held) is kept aside as a spacer and allocated again, further on; one that only pushes the rest
+above four fifths is kept, because stepping on rarely leads back into the region.  The spacers are freed at the end.  At most
 `max_spacer_gib` of them are held, briefly; nothing else of the device is touched.  If no reference can be found or
 memory runs short the buffers stay where plain allocation put them and `spread` is False.
 
@@ -204,25 +204,31 @@ class RegionAllocator:
         self.log.update(probe_elements=n, inside_ms=round(inside, 4))
         here = [a_w * (not x) for x in prof]                 # traffic in the reference's region, at each place
         away = [a_w * x for x in prof]
-        # 2. every other buffer: keep it if neither side exceeds the limit at any place, else step over it
+        # 2. every other buffer: keep it if neither side exceeds its limit at any place.  Too much in the reference's
+        # region: step over the buffer, which leads out of the region sooner or later.  Too much outside it only:
+        # stepping on rarely leads back, so the buffer is kept as it is.
+        over = []
         for name, k, dt, w in plan[1:]:
             while True:
-                if not room(size(k, dt)):
-                    self.log["gave_up"] = f"no place for {name} within the memory allowed"
-                    self.log["traffic_share_busiest"] = round(max(here + away) / total_w, 3)
-                    return False
+                if torch.cuda.mem_get_info(self.device)[0] < size(k, dt) + 2 * GiB:
+                    raise MemoryError(f"no memory left for {name}")      # the caller frees the spacers and goes on plainly
                 t = self._zeros(k, dt)
                 p = profile(t, ref, inside)
-                # Too much in the reference's region: stepping on leads out of it.  Too much outside it: stepping on
-                # rarely leads back, so there the soft limit applies at once.
                 lim_here = (self.limit if held() < self.patience_bytes else self.soft_limit) * total_w + 1e-9
                 lim_away = self.soft_limit * total_w + 1e-9
                 if fits(here, away, w, p, lim_here, lim_away):
+                    break
+                if fits(here, away, w, p, lim_here, float("inf")) or not room(size(k, dt)):
+                    over.append(name)                    # nothing to gain, or nothing left to try with
                     break
                 spacers.append(_bytes(t))                # in the wrong place: one more spacer
             bufs[name] = t
             self.where[name] = "".join("01"[x] for x in p)
             here = [here[i] + w * (not p[i]) for i in range(K)]
             away = [away[i] + w * p[i] for i in range(K)]
+        if over:
+            self.log["kept_over_the_limit"] = over
+        # what counts in the end: the busiest side at the worst place, and on average over the places
         self.log["traffic_share_busiest"] = round(max(here + away) / total_w, 3)
-        return True
+        self.log["traffic_share_busiest_mean"] = round(sum(max(h, a) for h, a in zip(here, away)) / (K * total_w), 3)
+        return self.log["traffic_share_busiest_mean"] <= self.soft_limit
