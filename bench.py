@@ -276,7 +276,8 @@ def main() -> int:
         print(json.dumps(region_map(lay)), flush=True)
         return 0
     st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, spread=not args.arena,
-                        grad_buffer=True, arena_order=args.arena_order.split(",") if args.arena_order else None,
+                        grad_buffer=True, n_grad_buffers=max(1, args.grad_buffers),
+                        arena_order=args.arena_order.split(",") if args.arena_order else None,
                         second_m=(args.path == "spec-m2" or (not args.only_path and not args.wcopy_over_grad)),
                         wcopy_over_grad=args.wcopy_over_grad)
     if args.chunk or args.blocks_per_cu or args.single_pass_min_chunks >= 0:
@@ -294,9 +295,9 @@ def main() -> int:
     synth.fill_weights(grad, lay, args.seed)          # reuse the buffer for the initial weights
     st.init_master(grad)
     torch.cuda.synchronize()
-    # gradient sources: independent draws that successive steps rotate through (the first lives in the state's arena)
+    # gradient sources: independent draws that successive steps rotate through (allocated with the state)
     grad.zero_()
-    grads = [grad] + [torch.zeros_like(grad) for _ in range(max(1, args.grad_buffers) - 1)]
+    grads = st.grads
     for k, gbuf in enumerate(grads):
         synth.fill_gradients(gbuf, wl, args.seed, 1 + k)
     torch.cuda.synchronize()

@@ -98,8 +98,8 @@ class RegionAllocator:
     `limit` of a kernel's mixed traffic (`soft_limit` once `patience_gib` of spacers are held; beyond four fifths a
     region becomes the bottleneck).  See the module docstring.
 
-    `plan`: (name, numel, dtype, weight) per buffer, weight = bytes per element that the update pass moves through
-    it (0: the buffer's place does not matter; it is allocated last).  The first entry is the anchor.
+    `plan`: (name, numel, dtype, weight) per buffer in the order of allocation, weight = bytes per element that the
+    update pass moves through it (0: the buffer lies where it falls).  The first entry is the anchor.
     `where[name]`: per place looked at, from head to tail, 0 in the reference's region, 1 outside (None: not looked at).
     """
 
@@ -127,7 +127,7 @@ class RegionAllocator:
         spacers: List[torch.Tensor] = []
         torch.cuda.empty_cache()
         try:
-            self.spread = self._place(bufs, [p for p in plan if p[3] > 0], spacers)
+            self.spread = self._place(bufs, list(plan), spacers)
         except (RuntimeError, MemoryError) as e:          # out of memory on the way: what exists stays, the rest is plain
             self.log["gave_up"] = str(e).splitlines()[0][:120]
             self.spread = False
@@ -144,7 +144,7 @@ class RegionAllocator:
     def _place(self, bufs, plan, spacers) -> bool:
         size = lambda k, dt: k * torch.empty((), dtype=dt).element_size()
         a_name, a_k, a_dt, a_w = plan[0]
-        n = min(1 << 29, size(a_k, a_dt) // 7, min(size(k, dt) for _, k, dt, _ in plan) // 3) // 4096 * 4096
+        n = min(1 << 29, size(a_k, a_dt) // 7, min(size(k, dt) for _, k, dt, w in plan if w > 0) // 3) // 4096 * 4096
         if n < (1 << 27):
             self.log["gave_up"] = "buffers too small for their place to matter"
             return False
@@ -213,6 +213,9 @@ class RegionAllocator:
                 if torch.cuda.mem_get_info(self.device)[0] < size(k, dt) + 2 * GiB:
                     raise MemoryError(f"no memory left for {name}")      # the caller frees the spacers and goes on plainly
                 t = self._zeros(k, dt)
+                if w <= 0:                               # not touched by the update pass: it lies where it falls
+                    p = profile(t, ref, inside) if size(k, dt) >= 3 * n else []
+                    break
                 p = profile(t, ref, inside)
                 lim_here = (self.limit if held() < self.patience_bytes else self.soft_limit) * total_w + 1e-9
                 lim_away = self.soft_limit * total_w + 1e-9
@@ -223,9 +226,10 @@ class RegionAllocator:
                     break
                 spacers.append(_bytes(t))                # in the wrong place: one more spacer
             bufs[name] = t
-            self.where[name] = "".join("01"[x] for x in p)
-            here = [here[i] + w * (not p[i]) for i in range(K)]
-            away = [away[i] + w * p[i] for i in range(K)]
+            self.where[name] = "".join("01"[x] for x in p) if p else None
+            if w > 0:
+                here = [here[i] + w * (not p[i]) for i in range(K)]
+                away = [away[i] + w * p[i] for i in range(K)]
         if over:
             self.log["kept_over_the_limit"] = over
         # what counts in the end: the busiest side at the worst place, and on average over the places

@@ -17,12 +17,13 @@ class OptimizerState:
                  grad_fmt: int = B.E5M2, wcopy: int = B.WCOPY_E4M3, spread: bool = False,
                  grad_buffer: bool = False, master_fmt: int = B.STATE_F16, v_fmt: int = B.STATE_F16,
                  share_with: "OptimizerState" = None, arena_order=None, second_m: bool = False,
-                 wcopy_over_grad: bool = False):
+                 wcopy_over_grad: bool = False, n_grad_buffers: int = 1):
         """`share_with`: another state over the same flat buffers.  Parameter groups (say, no weight decay on
         biases and LayerNorm weights) are one state each, over disjoint tensor lists of the same buffers; each
         has its own context and metadata and is stepped with its own hyper-parameters.
         `second_m`: a second first-moment buffer (1 B/param more), so that `step(..., pair_m=True)` can run the Adam
         step without its read-only pass (fp8lm_adam_step_fp8_m2); `m` always names the buffer that holds the moment.
+        `n_grad_buffers`: with grad_buffer, how many bf16 gradient sources to allocate (`grads`; `grad` is the first).
         `wcopy_over_grad`: the E4M3 weight copy is written over the FP8 gradient (`wq` is `g8`): after a step the buffer
         holds the weights, after a quantisation the gradient; 1 B/param less, the same bytes, the same speed."""
         dev = torch.device(f"cuda:{device}")
@@ -40,14 +41,16 @@ class OptimizerState:
         # (name, elements, type, bytes per element that the update pass moves through the buffer), in the order of
         # allocation.  With `spread` the buffers are placed so that no HBM region carries more than about three fifths
         # of that traffic (see placement.py: typically v and the copy in one region, w, m and the FP8 gradient in
-        # another); otherwise they are carved out of one allocation.
+        # another; the gradient sources, which the cast reads while it writes the FP8 gradient, beside v); otherwise
+        # they are carved out of one allocation.
         esz = lambda dt: torch.empty((), dtype=dt).element_size()
+        grad_names = (["grad"] + [f"grad_{i}" for i in range(1, n_grad_buffers)]) if grad_buffer else []
         plan = [("v", n, state_dtype[v_fmt], 2.0 * esz(state_dtype[v_fmt]))] \
             + ([] if wcopy_over_grad else [("wq", n, qdt, 1.0 * esz(qdt))]) \
+            + [(g, n, torch.bfloat16, 0.0) for g in grad_names] \
             + [("w", n, state_dtype[master_fmt], 2.0 * esz(state_dtype[master_fmt])),
                ("m", n, torch.uint8, 1.0 if second_m else 2.0)] + ([("m_other", n, torch.uint8, 1.0)] if second_m else []) \
-            + [("g8", n, torch.uint8, 2.0 if wcopy_over_grad else 1.0)] \
-            + ([("grad", n, torch.bfloat16, 0.0)] if grad_buffer else [])
+            + [("g8", n, torch.uint8, 2.0 if wcopy_over_grad else 1.0)]
         if wcopy_over_grad:
             assert wcopy == B.WCOPY_E4M3 and not second_m and share_with is None, \
                 "only an E4M3 copy fits the gradient's buffer; the step with a pair of moments reads the gradient twice"
@@ -74,8 +77,8 @@ class OptimizerState:
             # second region; m carries more of the update pass's traffic (2 of 12 bytes per element) than the
             # other 8-bit buffers.  (Where the pieces of an allocation really lie is up to the driver.)
             items = [(name, k, dt) for name, k, dt, _ in plan]
-            order = list(arena_order) if arena_order else [nm for nm in ("v", "wq", "grad", "w", "g8", "m", "m_other")
-                                                            if any(nm == it[0] for it in items)]
+            order = (list(arena_order) + grad_names[1:]) if arena_order else \
+                [nm for nm in ["v", "wq"] + grad_names + ["w", "g8", "m", "m_other"] if any(nm == it[0] for it in items)]
             assert sorted(order) == sorted(name for name, _, _ in items), order
             items.sort(key=lambda it: order.index(it[0]))
             align = (2 << 20) if n >= (2 << 20) else 256
@@ -91,6 +94,7 @@ class OptimizerState:
         self.g8, self.m, self.v, self.w = bufs["g8"], bufs["m"], bufs["v"], bufs["w"]
         self.wq = self.g8 if wcopy_over_grad else bufs["wq"]
         self.grad = bufs.get("grad")       # bf16 gradient source, only if asked for
+        self.grads = [bufs[g] for g in grad_names]
         self.m_other = bufs.get("m_other")  # the other buffer of the first-moment pair, only if asked for
         self.g_meta = self.ctx.new_meta(cfg)
         self.m_meta = self.ctx.new_meta(cfg)
