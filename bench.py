@@ -194,6 +194,12 @@ def region_map(lay) -> dict:
         full["v wq / w m g8: second group from +100 GiB"] = upd(0, 100, 100 + s16, 100 + s16 + s8, s16)
         full["v m / w g8 wq: second group from +100 GiB"] = upd(0, 100, s16, 100 + s16, 100 + s16 + s8)
         full["v / w / m g8 wq at +0, +100, +200 GiB"] = upd(0, 100, 200, 200 + s8, 200 + 2 * s8)
+        # the pass's reads alone and its writes alone (6 bytes per element each), in one region and over two
+        for tag, shape in (("reads alone", B.SKEL_UPDATE_READS), ("writes alone", B.SKEL_UPDATE_WRITES)):
+            full[f"{tag}, all streams from +0 GiB"] = timed(shape, [win(2 * s16, P), win(2 * s16 + s8, P), i16(win(0, 2 * P)),
+                                                                    i16(win(s16, 2 * P)), win(2 * s16 + 2 * s8, P)], P)
+            full[f"{tag}, v wq / w m g8: second group from +100 GiB"] = timed(
+                shape, [win(100 + s16 + s8, P), win(100 + s16, P), i16(win(0, 2 * P)), i16(win(100, 2 * P)), win(s16, P)], P)
     reads = {o: timed(B.SKEL_READ16, [i16(win(o, 8 * G))], 4 * G) for o in range(0, gib - 8, 40)}
     return {"device_GiB_used": gib, "params": P,
             "update_skeleton_ms_2^29_elements_16bit_streams_at_0_8bit_streams_at_GiB": pair,
