@@ -9,7 +9,10 @@ A "step" is one pass of the whole hot path over one model's flat tensors, all in
 fp8lm_quantize_fp8, which reads a tensor once for amax and cast together when its power-of-two scale does not
 change from the step before (17 bytes per parameter plus 3 for every element of a tensor that has to be cast
 again); `--path jit` is the three entry points one after the other.  Successive steps take different gradient
-buffers (independent draws), so that amax values move from step to step as they do in training.  Prints one JSON line: parameters updated per second, the
+buffers (independent draws), so that amax values move from step to step as they do in training.  The buffers are
+placed so that two of the device's three HBM regions share the update pass's traffic (placement.RegionAllocator;
+`--arena`: one plain allocation; the other of the two is run in a child process and printed beside the headline).
+Prints one JSON line: parameters updated per second, the
 achieved HBM bandwidth of the dominant kernel (the Adam update pass, 12 B/param) against the 8 TB/s
 peak, the bandwidth that memory-only skeletons of the same kernels reach on the same buffers
 ("ceilings"), and the CPU oracle timed on the host cores for a bounded sample of the same workload.
