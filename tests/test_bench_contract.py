@@ -42,6 +42,7 @@ def test_bench_line_has_the_agreed_fields():
     for name in ("amax", "cast", "adam_amax", "adam_update", "update_reads_only", "update_writes_only"):
         assert d["ceilings"][name]["GBps"] > 0
     assert 0 < d["kernels"]["adam_update"]["frac_of_skeleton"] <= 1.1
+    assert d["config"]["placement"]["allocation"]            # where the buffers were put, and how that was decided
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == "params/s" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
     assert d["value"] > 100 * c["value"]                     # the GPU path, not the oracle, was timed as `value`
