@@ -36,10 +36,11 @@ def sample_ids(layout):
 
 
 def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False, paths=None, tuning=None, spread=False,
-        speculative=False):
+        speculative=False, pair_steps=()):
     lay = wl.layout
     cfg = B.autoscale_cfg(ramp_steps=wl.ramp_steps, hist_window=wl.hist_window)
-    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, grad_buffer=True, spread=spread)
+    st = OptimizerState(lay.tensors(), lay.total, cfg, 0, B.E5M2, B.WCOPY_E4M3, grad_buffer=True, spread=spread,
+                        second_m=bool(pair_steps))
     if tuning:
         st.ctx.set_tuning(*tuning)
     say(f"{wl.name}: {lay.n_tensors} tensors, {lay.n_params} params, placement={st.placement}, tuning={tuning}")
@@ -60,7 +61,7 @@ def run(wl, seed, steps, small_steps, big_steps, big_ids=None, track_mu=False, p
         hp = B.adam_hparams(wl.lr, step, m_scale_mode=mode)
         ids = (small if step in small_steps else []) + (big if step in big_steps else [])
         snaps = [P.Snapshot(st, grad, t) for t in ids]
-        st.step(grad, hp, delayed=delayed, speculative=speculative and not delayed)
+        st.step(grad, hp, delayed=delayed, speculative=speculative and not delayed, pair_m=step in pair_steps)
         torch.cuda.synchronize()
         if ids:
             say(f"{wl.name} step {step} (moment-scale mode {mode}, delayed {delayed}): checking {len(ids)} tensors, "
@@ -97,8 +98,10 @@ def test_gpt7b_five_steps_with_amax_history():
     # steps 1-2 on the two-pass path, then the one-GPU fused cast, then the single-pass path (delayed gradient
     # scale + predicted moment scale): the three paths bench.py times, at full size and default tuning
     paths = {3: (B.MSCALE_FROM_CAST, False), 4: (B.MSCALE_PREDICTED, True), 5: (B.MSCALE_FROM_CAST, True)}
-    # every small tensor at every step; the five large shapes at the first step of each of the three paths
-    run(wl, seed=2, steps=5, small_steps={1, 2, 3, 4, 5}, big_steps={1, 3, 4}, paths=paths)
+    # every small tensor at every step; the five large shapes at steps 2, 3 and 4, one per path.  Step 2
+    # goes through fp8lm_adam_step_fp8_m2 (first moment read from one buffer of a pair, written to the other).
+    st, _, _ = run(wl, seed=2, steps=5, small_steps={1, 2, 3, 4, 5}, big_steps={2, 3, 4}, paths=paths, pair_steps={2})
+    assert st.ctx.speculation_stats(moment=True)["calls"] == 1
 
 
 def test_gpt175b_layer_heavy_tails_hundred_steps():
