@@ -498,6 +498,33 @@ typedef enum { FP8LM_SKEL_READ16 = 0, FP8LM_SKEL_READ8X2 = 1, FP8LM_SKEL_WRITE16
 fp8lm_status fp8lm_memory_skeleton(fp8lm_ctx* ctx, int32_t shape, void* const* bufs /*host -> device*/,
                                    int64_t n_elems, void* stream);
 
+/*
+ * Device memory whose pieces are chosen one by one: thin wrappers of the HIP virtual-memory calls, for callers that
+ * lay their flat buffers out over the regions of HBM.  On MI355X a kernel that writes (the update pass, the cast)
+ * runs up to 20 % slower while everything it writes lies in one 96 GiB region of the physical address space; a buffer
+ * whose address range alternates between pieces from two regions does not have that problem wherever a kernel is in
+ * it.  Where a piece lies can only be measured (fp8lm_memory_skeleton across two pieces is faster than inside one
+ * region), so the steps are separate: create pieces, map each somewhere, time it against a reference piece, then map
+ * the pieces wanted into one reserved range in alternating order and destroy the others.  None of these calls is on
+ * the path of a training step; they allocate, and fp8lm_vmm_unmap waits for the device.
+ *   fp8lm_vmm_granularity : *bytes = what piece sizes and offsets must be multiples of
+ *   fp8lm_vmm_reserve     : reserves an address range of `bytes`; nothing is behind it yet
+ *   fp8lm_vmm_create      : physical memory of `bytes` on `device`; *piece is an opaque handle
+ *   fp8lm_vmm_map         : puts `piece` behind [va, va + bytes) of a reserved range, readable and writable by `device`
+ *   fp8lm_vmm_unmap       : waits for the device, then takes the mapping away (the piece stays)
+ *   fp8lm_vmm_destroy     : gives the piece's memory back once it is mapped nowhere
+ *   fp8lm_vmm_free        : gives a reserved range back (nothing may be mapped in it)
+ * Errors: INVALID_ARGUMENT for null pointers, zero sizes or sizes that are not multiples of the granularity; HIP
+ * for whatever the runtime refuses (fp8lm_last_hip_error has the text).
+ */
+fp8lm_status fp8lm_vmm_granularity(int device, uint64_t* bytes /*host*/);
+fp8lm_status fp8lm_vmm_reserve(uint64_t bytes, void** va /*host; receives a device address*/);
+fp8lm_status fp8lm_vmm_free(void* va, uint64_t bytes);
+fp8lm_status fp8lm_vmm_create(int device, uint64_t bytes, uint64_t* piece /*host*/);
+fp8lm_status fp8lm_vmm_destroy(uint64_t piece);
+fp8lm_status fp8lm_vmm_map(void* va, uint64_t bytes, uint64_t piece, int device);
+fp8lm_status fp8lm_vmm_unmap(void* va, uint64_t bytes);
+
 /* Times the most recent launch of each kernel with HIP events recorded on the launch stream.
  * fp8lm_set_timing(ctx, 1) starts recording event pairs around every kernel launch;
  * fp8lm_get_timing synchronises and returns, per kernel id, the number of launches and the summed

@@ -38,7 +38,8 @@ EXPORTS = [
     "fp8lm_cast_fp8", "fp8lm_cast_fp8_delayed", "fp8lm_cast_fp8_for_adam", "fp8lm_shared_scale", "fp8lm_requantize_fp8", "fp8lm_sum_fp8",
     "fp8lm_quant_error_stats", "fp8lm_autoscale_broadcast", "fp8lm_set_mu", "fp8lm_memory_skeleton", "fp8lm_adam_step_fp8_static",
     "fp8lm_quantize_fp8", "fp8lm_quantize_fp8_for_adam", "fp8lm_get_speculation_stats", "fp8lm_adam_step_fp8_m2",
-    "fp8lm_get_moment_speculation_stats",
+    "fp8lm_get_moment_speculation_stats", "fp8lm_vmm_granularity", "fp8lm_vmm_reserve", "fp8lm_vmm_free", "fp8lm_vmm_create",
+    "fp8lm_vmm_destroy", "fp8lm_vmm_map", "fp8lm_vmm_unmap",
     "fp8lm_init_master", "fp8lm_init_master_as", "fp8lm_greedy_partition", "fp8lm_adam_step_fp8", "fp8lm_copy_bytes", "fp8lm_set_timing",
     "fp8lm_get_timing", "fp8lm_status_string", "fp8lm_last_hip_error", "fp8lm_sizeof_meta",
 ]
@@ -141,6 +142,14 @@ def lib() -> C.CDLL:
         L.fp8lm_adam_step_fp8.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fp8lm_adam_step_fp8_static.argtypes = [C.c_int, vp, i32, vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fp8lm_copy_bytes.argtypes = [vp, vp, vp, i64, vp]
+        u64 = C.c_uint64
+        L.fp8lm_vmm_granularity.argtypes = [C.c_int, vp]
+        L.fp8lm_vmm_reserve.argtypes = [u64, vp]
+        L.fp8lm_vmm_free.argtypes = [vp, u64]
+        L.fp8lm_vmm_create.argtypes = [C.c_int, u64, vp]
+        L.fp8lm_vmm_destroy.argtypes = [u64]
+        L.fp8lm_vmm_map.argtypes = [vp, u64, u64, C.c_int]
+        L.fp8lm_vmm_unmap.argtypes = [vp, u64]
         L.fp8lm_greedy_partition.argtypes = [vp, i32, i32, vp, vp]
         L.fp8lm_set_timing.argtypes = [vp, i32]
         L.fp8lm_get_timing.argtypes = [vp, vp, vp]
@@ -426,6 +435,41 @@ def adam_step_fp8_static(tensors: Sequence[Tuple[int, int]], grad, grad_fmt, gra
                                             _ptr(grad), grad_fmt, _ptr(grad_meta), _ptr(m), _ptr(m_meta), _ptr(v),
                                             _ptr(v_meta), _ptr(w), _ptr(w_meta), _ptr(wcopy), _ptr(wcopy_meta),
                                             C.addressof(hp), _stream(stream)), "fp8lm_adam_step_fp8_static")
+
+
+# ---- device memory piece by piece (see fp8lm.h): argument marshalling only ------------------------------------------
+def vmm_granularity(device: int = 0) -> int:
+    out = C.c_uint64(0)
+    _check(lib().fp8lm_vmm_granularity(device, C.addressof(out)), "fp8lm_vmm_granularity")
+    return int(out.value)
+
+
+def vmm_reserve(nbytes: int) -> int:
+    out = C.c_void_p(0)
+    _check(lib().fp8lm_vmm_reserve(nbytes, C.addressof(out)), "fp8lm_vmm_reserve")
+    return int(out.value)
+
+
+def vmm_free(va: int, nbytes: int) -> None:
+    _check(lib().fp8lm_vmm_free(va, nbytes), "fp8lm_vmm_free")
+
+
+def vmm_create(nbytes: int, device: int = 0) -> int:
+    out = C.c_uint64(0)
+    _check(lib().fp8lm_vmm_create(device, nbytes, C.addressof(out)), "fp8lm_vmm_create")
+    return int(out.value)
+
+
+def vmm_destroy(piece: int) -> None:
+    _check(lib().fp8lm_vmm_destroy(piece), "fp8lm_vmm_destroy")
+
+
+def vmm_map(va: int, nbytes: int, piece: int, device: int = 0) -> None:
+    _check(lib().fp8lm_vmm_map(va, nbytes, piece, device), "fp8lm_vmm_map")
+
+
+def vmm_unmap(va: int, nbytes: int) -> None:
+    _check(lib().fp8lm_vmm_unmap(va, nbytes), "fp8lm_vmm_unmap")
 
 
 def greedy_partition(sizes, n_gpus: int):

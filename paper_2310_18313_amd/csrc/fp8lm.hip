@@ -1107,6 +1107,95 @@ fp8lm_status fp8lm_memory_skeleton(fp8lm_ctx* c, int32_t shape, void* const* buf
   return after_launch();
 }
 
+// ---- device memory piece by piece (HIP virtual memory management); see fp8lm.h ---------------------------------
+namespace {
+hipMemAllocationProp vmm_prop(int device) {
+  hipMemAllocationProp prop = {};
+  prop.type = hipMemAllocationTypePinned;
+  prop.location.type = hipMemLocationTypeDevice;
+  prop.location.id = device;
+  return prop;
+}
+fp8lm_status vmm_granularity_of(int device, size_t* g) {
+  const hipMemAllocationProp prop = vmm_prop(device);
+  HIP_TRY(hipMemGetAllocationGranularity(g, &prop, hipMemAllocationGranularityRecommended));
+  if (*g == 0) *g = 4096;
+  return FP8LM_OK;
+}
+}  // namespace
+
+fp8lm_status fp8lm_vmm_granularity(int device, uint64_t* bytes) {
+  if (!bytes || device < 0) return FP8LM_ERR_INVALID_ARGUMENT;
+  int ok = 0;
+  HIP_TRY(hipDeviceGetAttribute(&ok, hipDeviceAttributeVirtualMemoryManagementSupported, device));
+  if (!ok) { g_hip_error = "virtual memory management is not supported on this device"; return FP8LM_ERR_HIP; }
+  size_t g = 0;
+  const fp8lm_status st = vmm_granularity_of(device, &g);
+  if (st == FP8LM_OK) *bytes = g;
+  return st;
+}
+
+fp8lm_status fp8lm_vmm_reserve(uint64_t bytes, void** va) {
+  if (!va || bytes == 0) return FP8LM_ERR_INVALID_ARGUMENT;
+  *va = nullptr;
+  HIP_TRY(hipMemAddressReserve(va, bytes, 0, nullptr, 0));
+  return FP8LM_OK;
+}
+
+fp8lm_status fp8lm_vmm_free(void* va, uint64_t bytes) {
+  if (!va || bytes == 0) return FP8LM_ERR_INVALID_ARGUMENT;
+  HIP_TRY(hipMemAddressFree(va, bytes));
+  return FP8LM_OK;
+}
+
+fp8lm_status fp8lm_vmm_create(int device, uint64_t bytes, uint64_t* piece) {
+  if (!piece || bytes == 0 || device < 0) return FP8LM_ERR_INVALID_ARGUMENT;
+  size_t g = 0;
+  const fp8lm_status st = vmm_granularity_of(device, &g);
+  if (st != FP8LM_OK) return st;
+  if (bytes % g != 0) return FP8LM_ERR_INVALID_ARGUMENT;
+  const hipMemAllocationProp prop = vmm_prop(device);
+  hipMemGenericAllocationHandle_t h{};
+  HIP_TRY(hipMemCreate(&h, bytes, &prop, 0));
+  static_assert(sizeof(h) <= sizeof(uint64_t), "the handle travels as 64 bits");
+  *piece = 0;
+  std::memcpy(piece, &h, sizeof(h));
+  return FP8LM_OK;
+}
+
+fp8lm_status fp8lm_vmm_destroy(uint64_t piece) {
+  if (piece == 0) return FP8LM_ERR_INVALID_ARGUMENT;
+  hipMemGenericAllocationHandle_t h{};
+  std::memcpy(&h, &piece, sizeof(h));
+  HIP_TRY(hipMemRelease(h));
+  return FP8LM_OK;
+}
+
+fp8lm_status fp8lm_vmm_map(void* va, uint64_t bytes, uint64_t piece, int device) {
+  if (!va || bytes == 0 || piece == 0 || device < 0) return FP8LM_ERR_INVALID_ARGUMENT;
+  hipMemGenericAllocationHandle_t h{};
+  std::memcpy(&h, &piece, sizeof(h));
+  HIP_TRY(hipMemMap(va, bytes, 0, h, 0));
+  hipMemAccessDesc acc = {};
+  acc.location.type = hipMemLocationTypeDevice;
+  acc.location.id = device;
+  acc.flags = hipMemAccessFlagsProtReadWrite;
+  const hipError_t e = hipMemSetAccess(va, bytes, &acc, 1);
+  if (e != hipSuccess) {
+    g_hip_error = std::string("hipMemSetAccess: ") + hipGetErrorString(e);
+    (void)hipMemUnmap(va, bytes);
+    return FP8LM_ERR_HIP;
+  }
+  return FP8LM_OK;
+}
+
+fp8lm_status fp8lm_vmm_unmap(void* va, uint64_t bytes) {
+  if (!va || bytes == 0) return FP8LM_ERR_INVALID_ARGUMENT;
+  HIP_TRY(hipDeviceSynchronize());     // no kernel may still be using the mapping
+  HIP_TRY(hipMemUnmap(va, bytes));
+  return FP8LM_OK;
+}
+
 fp8lm_status fp8lm_set_timing(fp8lm_ctx* c, int32_t enable) {
   if (!c) return FP8LM_ERR_INVALID_ARGUMENT;
   DeviceGuard guard(c->device);

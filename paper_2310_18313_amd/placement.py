@@ -23,7 +23,13 @@ above four fifths is kept, because stepping on rarely leads back into the region
 `max_spacer_gib` of them are held, briefly; nothing else of the device is touched.  If no reference can be found or
 memory runs short the buffers stay where plain allocation put them and `spread` is False.
 
-Nothing here computes anything of the method: it only decides where `torch.zeros` buffers land.
+A kernel that writes a single buffer (the cast writes the FP8 gradient) is limited by the region that buffer lies in,
+whatever its reads do: 5.4 TB/s for the cast's two-to-one mix, against 6.0 TB/s when the written buffer itself alternates
+between regions.  `StripedArena` builds such a buffer from 1 GiB pieces of device memory (HIP virtual memory
+management through the library's fp8lm_vmm_* calls): pieces are created one by one and timed against the first, and
+those kept are mapped into one address range in alternating order.
+
+Nothing here computes anything of the method: it only decides where buffers land.
 """
 from __future__ import annotations
 
@@ -120,7 +126,10 @@ class RegionAllocator:
     def _zeros(self, n: int, dt: torch.dtype) -> torch.Tensor:
         return torch.zeros(n, dtype=dt, device=self.device)
 
-    def allocate(self, plan: Sequence[Tuple[str, int, torch.dtype, float]]) -> Dict[str, torch.Tensor]:
+    def allocate(self, plan: Sequence[Tuple[str, int, torch.dtype, float]], even_weight: float = 0.0) -> Dict[str, torch.Tensor]:
+        """`even_weight`: bytes per element the update pass moves through buffers that are not in the plan because
+        they lie evenly over the regions anyway (a StripedArena); counted half and half."""
+        self.even_weight = float(even_weight)
         bufs: Dict[str, torch.Tensor] = {}
         for name, _, _, _ in plan:
             self.where[name] = None
@@ -148,7 +157,7 @@ class RegionAllocator:
         if n < (1 << 27):
             self.log["gave_up"] = "buffers too small for their place to matter"
             return False
-        total_w = float(sum(w for _, _, _, w in plan))
+        total_w = float(sum(w for _, _, _, w in plan)) + self.even_weight
         K = self.positions
         held = lambda: sum(t.numel() * t.element_size() for t in spacers)
 
@@ -202,8 +211,8 @@ class RegionAllocator:
         bufs[a_name] = anchor.view(a_dt)
         self.where[a_name] = "".join("01"[x] for x in prof)
         self.log.update(probe_elements=n, inside_ms=round(inside, 4))
-        here = [a_w * (not x) for x in prof]                 # traffic in the reference's region, at each place
-        away = [a_w * x for x in prof]
+        here = [a_w * (not x) + self.even_weight / 2 for x in prof]      # traffic in the reference's region, at each place
+        away = [a_w * x + self.even_weight / 2 for x in prof]
         # 2. every other buffer: keep it if neither side exceeds its limit at any place.  Too much in the reference's
         # region: step over the buffer, which leads out of the region sooner or later.  Too much outside it only:
         # stepping on rarely leads back, so the buffer is kept as it is.
@@ -236,3 +245,126 @@ class RegionAllocator:
         self.log["traffic_share_busiest"] = round(max(here + away) / total_w, 3)
         self.log["traffic_share_busiest_mean"] = round(sum(max(h, a) for h, a in zip(here, away)) / (K * total_w), 3)
         return self.log["traffic_share_busiest_mean"] <= self.soft_limit
+
+
+class _Mappings:
+    """Owns pieces of device memory mapped one after the other into a reserved address range; gives everything back
+    when the last reference goes (after waiting for the device)."""
+
+    def __init__(self, device: int, piece: int, nbytes: int):
+        self.device, self.piece, self.nbytes = device, piece, nbytes
+        self.va = B.vmm_reserve(nbytes)
+        self.pieces: List[int] = []
+
+    def append(self, handle: int) -> int:
+        """Maps one more piece behind the pieces already there; returns its index."""
+        k = len(self.pieces)
+        B.vmm_map(self.va + k * self.piece, self.piece, handle, self.device)
+        self.pieces.append(handle)
+        return k
+
+    def release(self, keep=()) -> None:
+        """Unmaps everything; destroys the pieces not listed in `keep`; gives the range back."""
+        if self.pieces:
+            B.vmm_unmap(self.va, len(self.pieces) * self.piece)
+        for h in self.pieces:
+            if h not in keep:
+                B.vmm_destroy(h)
+        self.pieces = []
+        if self.va:
+            B.vmm_free(self.va, self.nbytes)
+            self.va = 0
+
+    def __del__(self):
+        try:
+            self.release()
+        except Exception:           # interpreter shutdown, or the runtime is already gone
+            pass
+
+
+class _DeviceRange:
+    """A range of device addresses as something torch can wrap without copying (and keep alive)."""
+
+    def __init__(self, owner: _Mappings):
+        self.owner = owner
+        self.__cuda_array_interface__ = {"shape": (owner.nbytes,), "typestr": "|u1", "data": (owner.va, False),
+                                         "version": 2, "strides": None}
+
+
+class StripedArena:
+    """One range of device addresses whose pieces alternate between two HBM regions (see the module docstring).
+
+    Pieces of `piece_gib` are created one after the other, each mapped into a staging range and timed against the
+    first piece with the update-shaped probe, until half of the bytes asked for can come from the first piece's
+    region and half from elsewhere (in a fresh process that means creating pieces up to the next region; the ones
+    not needed are destroyed at once).  The pieces kept are then mapped into one range in alternating order;
+    `bytes` is that range as a tensor (zeroed) and `tensor(offset, nbytes, dtype)` hands out views of it, which keep
+    the memory alive.  Raises RuntimeError (Fp8lmError is one) if the device has no virtual memory management, memory
+    runs short, or fewer than `min_share` of the bytes can come from a second region.
+    """
+
+    def __init__(self, ctx, nbytes: int, device: int = 0, piece_gib: float = 1.0, min_share: float = 0.25,
+                 max_extra_gib: int = 160, alternate: bool = True):
+        gran = B.vmm_granularity(device)
+        piece = max(gran, int(piece_gib * GiB) // gran * gran)
+        n = (nbytes + piece - 1) // piece
+        n_probe = min(1 << 28, piece // 4) // 4096 * 4096
+        if n < 4 or n_probe < (1 << 26):
+            raise RuntimeError("too small for its place to matter")
+        self.log: Dict[str, object] = {}
+        want_away = n // 2
+        limit = n + int(max_extra_gib * GiB) // piece
+        staging = _Mappings(device, piece, limit * piece)
+        is_away: List[bool] = []
+        try:
+            view = torch.as_tensor(_DeviceRange(staging), device=f"cuda:{device}")
+            inside = None
+            while (is_away.count(False) < n - want_away or is_away.count(True) < want_away) and len(is_away) < limit:
+                if torch.cuda.mem_get_info(device)[0] < piece + 2 * GiB:
+                    break
+                k = staging.append(B.vmm_create(piece, device))
+                if k == 0:
+                    is_away.append(False)
+                    continue
+                t = probe_ms(ctx, view[:piece], view[k * piece:(k + 1) * piece], n_probe, reps=2)
+                if inside is None and 12 * n_probe / (t * 1e-3) < MIXED_ABOVE_BPS:
+                    inside = t                       # the first piece against a neighbour in its own region: slow
+                is_away.append(inside is None or t < 0.91 * inside)
+            del view
+            handles = list(staging.pieces)
+            away = [h for h, a in zip(handles, is_away) if a][:want_away]
+            here = [h for h, a in zip(handles, is_away) if not a][:n - len(away)]
+            self.log.update(piece_MiB=piece >> 20, pieces_created=len(handles), pieces_used=n,
+                            created_outside_first_region=sum(is_away),
+                            inside_ms=None if inside is None else round(inside, 4))
+            if len(here) + len(away) < n or len(away) < min_share * n:
+                raise RuntimeError(f"{len(away)} of the {n} pieces needed lie outside the first piece's region")
+            staging.release(keep=here + away)
+        except BaseException:
+            staging.release()
+            raise
+        # the smaller group spread evenly through the larger one
+        final = _Mappings(device, piece, n * piece)
+        try:
+            a = b = 0
+            for _ in range(n):
+                if b < len(away) and (a >= len(here) or (alternate and b * len(here) <= a * len(away))):
+                    final.append(away[b])
+                    b += 1
+                else:
+                    final.append(here[a])
+                    a += 1
+        except BaseException:
+            mapped = set(final.pieces)
+            final.release()
+            for h in here + away:
+                if h not in mapped:
+                    B.vmm_destroy(h)
+            raise
+        self.log["share_outside_first_region"] = round(len(away) / n, 3)
+        self.nbytes = n * piece
+        self.bytes = torch.as_tensor(_DeviceRange(final), device=f"cuda:{device}")
+        self.bytes.zero_()
+
+    def tensor(self, offset: int, nbytes: int, dtype: torch.dtype = torch.uint8) -> torch.Tensor:
+        return self.bytes[offset:offset + nbytes].view(dtype)

@@ -9,7 +9,7 @@ from __future__ import annotations
 import torch
 
 from . import binding as B
-from .placement import RegionAllocator
+from .placement import RegionAllocator, StripedArena
 
 
 class OptimizerState:
@@ -65,10 +65,23 @@ class OptimizerState:
                 bufs["grad"] = o.grad
             self.spread = o.spread
         elif spread:
+            # everything but the FP8 gradient region by region, by measurement; the FP8 gradient, the one buffer the
+            # cast writes, in pieces that alternate between regions (if that fails it is placed like the others)
+            g8_weight = next(w for name, _, _, w in plan if name == "g8")
             alloc = RegionAllocator(self.ctx, device)
-            bufs = alloc.allocate(plan)
+            bufs = alloc.allocate([entry for entry in plan if entry[0] != "g8"], even_weight=g8_weight)
             self.spread = alloc.spread
             self.placement = dict(alloc.log, where=alloc.where)
+            striped = None
+            if self.spread:
+                try:
+                    striped = StripedArena(self.ctx, n, device)
+                    bufs["g8"] = striped.tensor(0, n)
+                    self.placement["g8_striped"] = striped.log
+                except RuntimeError as e:
+                    self.placement["g8_striped"] = {"gave_up": str(e).splitlines()[0][:120]}
+            if "g8" not in bufs:
+                bufs["g8"] = torch.zeros(n, dtype=torch.uint8, device=dev)
         else:
             # one allocation, the buffers carved out of it one after the other (what a caller of the C ABI with an
             # arena of its own would do): where they lie relative to each other is then the same in every process
