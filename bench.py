@@ -147,7 +147,7 @@ def placement_compare(args, spread: bool) -> dict:
             "adam_update_frac_of_peak": d["roofline"]["frac"]}
 
 
-def region_map(lay) -> dict:
+def _region_map_arena(ctx, lay) -> dict:
     """Where in device memory do the streams of the update pass have to lie?  One allocation over nearly all of the
     device; the update-shaped memory skeleton (fp8lm_memory_skeleton: 12 bytes per element, reads and writes mixed,
     no arithmetic) is timed (a) with 2^29 elements, its 16-bit streams at the start and its 8-bit streams d GiB
@@ -155,7 +155,6 @@ def region_map(lay) -> dict:
     import torch
     from paper_2310_18313_amd import binding as B
     G = 1 << 30
-    ctx = B.Context(lay.tensors())
     gib = (torch.cuda.mem_get_info(0)[0] >> 30) - 8
     arena = torch.zeros(gib * G, dtype=torch.uint8, device="cuda:0")
 
@@ -207,6 +206,54 @@ def region_map(lay) -> dict:
     return {"device_GiB_used": gib, "params": P,
             "update_skeleton_ms_2^29_elements_16bit_streams_at_0_8bit_streams_at_GiB": pair,
             "update_skeleton_ms_full_size": full, "read16_ms_8GiB_at_GiB": reads}
+
+
+def region_map(lay) -> dict:
+    """bench.py --region-map: the table over one allocation of nearly all device memory, then one written buffer in
+    three placements."""
+    import torch
+    from paper_2310_18313_amd import binding as B
+    from paper_2310_18313_amd.placement import StripedArena, probe_ms
+    G = 1 << 30
+    ctx = B.Context(lay.tensors())
+    out = _region_map_arena(ctx, lay)           # its allocation is gone when it returns
+    gc.collect()
+    torch.cuda.empty_cache()
+    P = out["params"]
+
+    def timed(shape, bufs, n, reps=3):
+        ctx.memory_skeleton(shape, bufs, n)
+        torch.cuda.synchronize()
+        ctx.set_timing(True)
+        ctx.get_timing()
+        for _ in range(reps):
+            ctx.memory_skeleton(shape, bufs, n)
+        k, ms = ctx.get_timing()["skeleton"]
+        ctx.set_timing(False)
+        return round(ms / k, 3)
+
+    # One written buffer: beside the buffer that is read, 100 GiB further on, and in 1 GiB pieces that alternate between
+    # two regions (placement.StripedArena).  Where the plain allocations lie is looked up with the probe.
+    striped = {}
+    if 7 * P < (torch.cuda.mem_get_info(0)[0] - 110 * G):
+        src = torch.zeros(2 * P, dtype=torch.uint8, device="cuda:0")
+        same = torch.zeros(P, dtype=torch.uint8, device="cuda:0")
+        spacer = torch.empty(100 * G, dtype=torch.uint8, device="cuda:0")
+        other = torch.zeros(P, dtype=torch.uint8, device="cuda:0")
+        del spacer
+        torch.cuda.empty_cache()
+        n_pr = 1 << 28
+        t_same, t_other = probe_ms(ctx, src, same, n_pr), probe_ms(ctx, src, other, n_pr)
+        st8 = StripedArena(ctx, P).tensor(0, P)
+        where = lambda t: "in the source's region" if 12 * n_pr / (t * 1e-3) < 5.5e12 else "in another region"
+        for tag, dst in ((f"plain allocation made right after the source: {where(t_same)} (probe {t_same:.3f} ms)", same),
+                         (f"plain allocation made 100 GiB later: {where(t_other)} (probe {t_other:.3f} ms)", other),
+                         ("pieces of 1 GiB alternating between two regions", st8)):
+            striped[tag] = {"cast_shape_ms": timed(B.SKEL_CAST, [src.view(torch.int16), dst], P),
+                            "write8_ms": timed(B.SKEL_WRITE8, [dst], P),
+                            "read8x2_with_half_the_source_ms": timed(B.SKEL_READ8X2, [dst, src[:P]], P)}
+    out["one_written_buffer_13B_layout"] = striped
+    return out
 
 
 def main() -> int:

@@ -978,6 +978,54 @@ def test_region_aware_placement_changes_no_result():
             assert torch.equal(a, b), (step, k)
 
 
+def test_striped_arena_is_ordinary_memory_and_gives_it_back():
+    """placement.StripedArena (pieces of device memory mapped into one address range in alternating order): what it
+    hands out must behave like any allocation -- zeroed, writable through views, usable by the kernels -- and the
+    device must have its memory back once the last view is gone.  Whether two regions could be found depends on what
+    the process holds already; if not, the constructor must say so with a RuntimeError and leave nothing behind."""
+    import gc
+    from paper_2310_18313_amd.placement import StripedArena
+    gc.collect()
+    torch.cuda.empty_cache()
+    lay = synth.Layout(["a"], [1 << 20])
+    ctx = B.Context(lay.tensors())
+    free0 = torch.cuda.mem_get_info(0)[0]
+    nbytes = 6 << 30
+    try:
+        arena = StripedArena(ctx, nbytes)
+    except RuntimeError as e:
+        say(f"striped arena not built: {e}")
+        assert str(e)
+        gc.collect()
+        assert torch.cuda.mem_get_info(0)[0] >= free0 - (64 << 20)
+        return
+    say(f"striped arena: {arena.log}")
+    assert arena.nbytes >= nbytes and 0.25 <= arena.log["share_outside_first_region"] <= 0.75
+    a, b = arena.tensor(0, 1 << 30), arena.tensor((3 << 30) - 4096, 8192, torch.int16)       # b lies across two pieces
+    assert int(arena.bytes.max()) == 0
+    b.fill_(-2)
+    a[:16] = 7
+    assert int(arena.bytes[(3 << 30) - 4096:(3 << 30) + 4096].view(torch.int16).min()) == -2
+    assert int(arena.bytes[:16].sum()) == 112 and int(arena.bytes[16:(3 << 30) - 4096].max()) == 0
+    # the kernels take it like any buffer: a cast into it equals a cast into a plain buffer
+    wl = synth.Workload("striped", lay, lr=1e-3, sigma=None, ramp_steps=4)
+    cfg = B.autoscale_cfg()
+    grad = torch.zeros(lay.total, dtype=torch.bfloat16, device=DEV)
+    synth.fill_gradients(grad, wl, 5, 1)
+    q_plain, m_plain = torch.zeros(lay.total, dtype=torch.uint8, device=DEV), ctx.new_meta(cfg)
+    q_striped, m_striped = arena.tensor((1 << 30) - (1 << 19), lay.total), ctx.new_meta(cfg)
+    for q, m in ((q_plain, m_plain), (q_striped, m_striped)):
+        ctx.amax_scale(grad, B.E5M2, m, cfg)
+        ctx.cast_fp8(grad, q, B.E5M2, m, cfg)
+    torch.cuda.synchronize()
+    assert torch.equal(q_plain, q_striped) and torch.equal(m_plain, m_striped)
+    held = free0 - torch.cuda.mem_get_info(0)[0]
+    assert held >= nbytes
+    del a, b, q, q_striped, arena                      # every view keeps the mappings alive
+    gc.collect()
+    assert torch.cuda.mem_get_info(0)[0] >= free0 - (64 << 20) - 2 * lay.total - (1 << 20)
+
+
 def test_a_step_replayed_from_a_hip_graph_equals_the_eager_step():
     """None of the hot-path calls synchronises, allocates or clears memory with a memset, so a whole step can be
     captured once and replayed; the hyper-parameters are baked in at capture, so every replay is the same step."""
