@@ -300,7 +300,8 @@ class StripedArena:
     not needed are destroyed at once).  The pieces kept are then mapped into one range in alternating order;
     `bytes` is that range as a tensor (zeroed) and `tensor(offset, nbytes, dtype)` hands out views of it, which keep
     the memory alive.  Raises RuntimeError (Fp8lmError is one) if the device has no virtual memory management, memory
-    runs short, or fewer than `min_share` of the bytes can come from a second region.
+    runs short, or fewer than `min_share` of the bytes can come from a second region.  `alternate=False` maps the first
+    region's pieces first and the others after them (for measurements: same pieces, no alternation).
     """
 
     def __init__(self, ctx, nbytes: int, device: int = 0, piece_gib: float = 1.0, min_share: float = 0.25,
