@@ -130,7 +130,25 @@ int main(int argc, char** argv) {
   LIB_OK(fp8lm_create(&ctx, tensors.data(), n, 0));
   uint16_t* d_g = dev_alloc<uint16_t>(T);
   uint16_t* d_w0 = dev_alloc<uint16_t>(T);
-  uint8_t* d_q = dev_alloc<uint8_t>(T);
+  // The FP8 gradient lives in device memory put together piece by piece (fp8lm_vmm_*): two pieces mapped one after
+  // the other into one reserved range, as a caller would do to make the buffer alternate between HBM regions.
+  uint8_t* d_q = nullptr;
+  uint64_t gran = 0, piece_bytes = 0, pieces[2] = {0, 0};
+  if (fp8lm_vmm_granularity(0, &gran) == FP8LM_OK) {
+    piece_bytes = ((T + 1) / 2 + gran - 1) / gran * gran;
+    void* va = nullptr;
+    LIB_OK(fp8lm_vmm_reserve(2 * piece_bytes, &va));
+    for (int k = 0; k < 2; ++k) {
+      LIB_OK(fp8lm_vmm_create(0, piece_bytes, &pieces[k]));
+      LIB_OK(fp8lm_vmm_map(static_cast<char*>(va) + k * piece_bytes, piece_bytes, pieces[k], 0));
+    }
+    d_q = static_cast<uint8_t*>(va);
+    HIP_OK(hipMemset(d_q, 0, 2 * piece_bytes));
+    std::printf("c_abi_parity: FP8 gradient in two mapped pieces of %llu bytes\n", (unsigned long long)piece_bytes);
+  } else {
+    std::printf("c_abi_parity: no virtual memory management here (%s): plain allocation\n", fp8lm_last_hip_error());
+    d_q = dev_alloc<uint8_t>(T);
+  }
   uint8_t* d_m = dev_alloc<uint8_t>(T);
   uint16_t* d_v = dev_alloc<uint16_t>(T);
   uint16_t* d_w = dev_alloc<uint16_t>(T);
@@ -203,6 +221,11 @@ int main(int argc, char** argv) {
     }
   }
   LIB_OK(fp8lm_destroy(ctx));
+  if (piece_bytes) {
+    LIB_OK(fp8lm_vmm_unmap(d_q, 2 * piece_bytes));
+    for (uint64_t h : pieces) LIB_OK(fp8lm_vmm_destroy(h));
+    LIB_OK(fp8lm_vmm_free(d_q, 2 * piece_bytes));
+  }
   std::printf("c_abi_parity: %s after %d steps, %lld elements in %d tensors (%llu saturated gradient codes in all, log2 mu between %d and %d)\n",
               bad ? "MISMATCH" : "identical", steps, (long long)total, n, (unsigned long long)sat, mu_min, mu_max);
   return bad ? 1 : 0;
