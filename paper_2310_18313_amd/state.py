@@ -85,10 +85,8 @@ class OptimizerState:
         else:
             # one allocation, the buffers carved out of it one after the other (what a caller of the C ABI with an
             # arena of its own would do): where they lie relative to each other is then the same in every process
-            # Default order: the first moment last.  When an allocation of this size is laid out along the address
-            # space from a region boundary, only the last 12 of the 108 GiB of a 13e9-parameter state lie in the
-            # second region; m carries more of the update pass's traffic (2 of 12 bytes per element) than the
-            # other 8-bit buffers.  (Where the pieces of an allocation really lie is up to the driver.)
+            # Default order: v, copy, gradient sources, w, FP8 gradient, m.  Where the pieces of such an allocation
+            # lie among the HBM regions is up to the driver (see placement.py); `spread` is the way to decide it.
             items = [(name, k, dt) for name, k, dt, _ in plan]
             order = (list(arena_order) + grad_names[1:]) if arena_order else \
                 [nm for nm in ["v", "wq"] + grad_names + ["w", "g8", "m", "m_other"] if any(nm == it[0] for it in items)]
